@@ -1,0 +1,197 @@
+"""ctypes/numpy front for the fp64 CPU oracle (oracle/reattn_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by the smoke check and by the
+benchmark's CPU-baseline leg.  The product package never imports this module and
+this module never imports the product package.
+
+Arrays are numpy; q / K / V are passed as their exact stored bytes: float32
+arrays, or bfloat16 as uint16 bit patterns (dtype="bf16").
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from dataclasses import dataclass
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "reattn_oracle.c")
+_LIB = os.path.join(_HERE, "libreattn_oracle.so")
+
+F32, BF16 = 0, 1
+AGG_SUM, AGG_MAX = 0, 1
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (-O2, OpenMP, no fast-math)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-std=c11", "-O2", "-fopenmp", "-fno-fast-math", "-ffp-contract=off",
+               "-shared", "-fPIC", "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+class _Shape(C.Structure):
+    _fields_ = [
+        ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
+        ("dtype", C.c_int32), ("n_ctx", C.c_int64), ("n_sink", C.c_int32),
+        ("n_local", C.c_int32), ("top_k", C.c_int32), ("agg", C.c_int32),
+        ("rope_theta", C.c_double), ("softmax_scale", C.c_double),
+        ("k_stride_head", C.c_int64), ("k_stride_tok", C.c_int64),
+        ("v_stride_head", C.c_int64), ("v_stride_tok", C.c_int64),
+    ]
+
+
+@dataclass
+class Shape:
+    """Problem description in the paper's terms (Eq. 1-3)."""
+    n_q_heads: int
+    n_kv_heads: int
+    head_dim: int
+    dtype: str            # "f32" | "bf16"
+    n_ctx: int
+    n_sink: int
+    n_local: int
+    top_k: int
+    rope_theta: float
+    agg: int = AGG_SUM
+    softmax_scale: float = 0.0
+
+    def c(self) -> _Shape:
+        D, N = self.head_dim, self.n_ctx
+        return _Shape(self.n_q_heads, self.n_kv_heads, D, BF16 if self.dtype == "bf16" else F32,
+                      N, self.n_sink, self.n_local, self.top_k, self.agg,
+                      float(self.rope_theta), float(self.softmax_scale),
+                      N * D, D, N * D, D)
+
+    def partition(self):
+        """(s_eff, l_eff, n_mid, k_eff) of Eq. 1 with the clamping rules."""
+        lib = _lib()
+        s, l, m, k = (C.c_int64() for _ in range(4))
+        lib.ro_partition(self.n_ctx, self.n_sink, self.n_local, self.top_k,
+                         C.byref(s), C.byref(l), C.byref(m), C.byref(k))
+        return s.value, l.value, m.value, k.value
+
+
+_cached = None
+
+
+def _lib():
+    global _cached
+    if _cached is None:
+        lib = C.CDLL(build())
+        P = C.c_void_p
+        lib.ro_partition.argtypes = [C.c_int64, C.c_int32, C.c_int32, C.c_int32, P, P, P, P]
+        lib.ro_partition.restype = None
+        lib.ro_widen_bf16.argtypes = [C.c_uint16]
+        lib.ro_widen_bf16.restype = C.c_double
+        lib.ro_score.argtypes = [P, C.c_int32, P, P, P]
+        lib.ro_topk_row.argtypes = [P, C.c_int64, C.c_int64, C.c_int64, P, P]
+        lib.ro_topk.argtypes = [P, C.c_int64, C.c_int64, C.c_int64, C.c_int64, P, P]
+        lib.ro_gather_rope.argtypes = [P, P, P, P, C.c_int64, C.c_double, P, P]
+        lib.ro_gather_rope.restype = C.c_int64
+        lib.ro_attend.argtypes = [P, C.c_int32, P, P, P, P, P, C.c_double, P]
+        lib.ro_forward.argtypes = [P, C.c_int32, P, P, P, P, P, P, P, P]
+        _cached = lib
+    return _cached
+
+
+def _ptr(a):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def _check_store(a: np.ndarray, sh: Shape, name: str) -> np.ndarray:
+    want = np.uint16 if sh.dtype == "bf16" else np.float32
+    if a.dtype != want:
+        raise TypeError(f"{name}: expected {want} storage for dtype {sh.dtype}, got {a.dtype}")
+    if not a.flags.c_contiguous:
+        raise ValueError(f"{name}: must be C-contiguous")
+    return a
+
+
+def _check_rc(rc: int, what: str):
+    if rc != 0:
+        raise RuntimeError(f"oracle {what} failed with code {rc}")
+
+
+def widen_bf16(bits: int) -> float:
+    return _lib().ro_widen_bf16(int(bits) & 0xFFFF)
+
+
+def score(sh: Shape, q: np.ndarray, k_cache: np.ndarray) -> np.ndarray:
+    """Eq. 2 scores: q [M,Hq,D], K [Hkv,N,D] -> float64 [M,Hkv,N_mid]."""
+    _check_store(q, sh, "q"); _check_store(k_cache, sh, "k_cache")
+    M = q.shape[0]
+    _, _, n_mid, _ = sh.partition()
+    out = np.empty((M, sh.n_kv_heads, n_mid), dtype=np.float64)
+    cs = sh.c()
+    _check_rc(_lib().ro_score(C.byref(cs), M, _ptr(q), _ptr(k_cache), _ptr(out)), "score")
+    return out
+
+
+def topk_rows(scores: np.ndarray, k: int, index_base: int = 0):
+    """scores float64 [R, n] -> (idx int32 [R, min(k,n)] ascending absolute, kth float64 [R])."""
+    scores = np.ascontiguousarray(scores, dtype=np.float64)
+    R, n = scores.shape
+    k_eff = max(0, min(k, n))
+    idx = np.empty((R, k_eff), dtype=np.int32)
+    kth = np.zeros((R,), dtype=np.float64)
+    _check_rc(_lib().ro_topk(_ptr(scores), R, n, k_eff, index_base, _ptr(idx), _ptr(kth)), "topk")
+    return idx, kth
+
+
+def gather_rope(sh: Shape, k_cache, v_cache, idx: np.ndarray, q_tok: int | None = None,
+                pos_offset: float = 0.0):
+    """Concatenation of Eq. 3 for one query: (K rotated [Hkv,S,D], V [Hkv,S,D], kept length)."""
+    _check_store(k_cache, sh, "k_cache"); _check_store(v_cache, sh, "v_cache")
+    s, l, _, k = sh.partition()
+    S = s + k + l
+    idx = np.ascontiguousarray(idx, dtype=np.int32).reshape(sh.n_kv_heads, k)
+    ks = np.zeros((sh.n_kv_heads, S, sh.head_dim), dtype=np.float64)
+    vs = np.zeros_like(ks)
+    cs = sh.c()
+    n = _lib().ro_gather_rope(C.byref(cs), _ptr(k_cache), _ptr(v_cache), _ptr(idx),
+                              sh.n_ctx - 1 if q_tok is None else q_tok, float(pos_offset),
+                              _ptr(ks), _ptr(vs))
+    return ks, vs, int(n)
+
+
+def attend(sh: Shape, q, k_cache, v_cache, idx: np.ndarray, q_tok=None,
+           pos_offset: float = 0.0) -> np.ndarray:
+    """Eq. 3 attention on given index sets: idx [M,Hkv,k_eff] -> float64 [M,Hq,D]."""
+    _check_store(q, sh, "q"); _check_store(k_cache, sh, "k_cache"); _check_store(v_cache, sh, "v_cache")
+    M = q.shape[0]
+    _, _, _, k = sh.partition()
+    idx = np.ascontiguousarray(idx, dtype=np.int32).reshape(M, sh.n_kv_heads, k)
+    qt = _q_tok(sh, M, q_tok)
+    out = np.empty((M, sh.n_q_heads, sh.head_dim), dtype=np.float64)
+    cs = sh.c()
+    _check_rc(_lib().ro_attend(C.byref(cs), M, _ptr(q), _ptr(qt), _ptr(k_cache), _ptr(v_cache),
+                               _ptr(idx), float(pos_offset), _ptr(out)), "attend")
+    return out
+
+
+def _q_tok(sh: Shape, M: int, q_tok) -> np.ndarray:
+    if q_tok is None:  # queries are the last M cached tokens (appendix: append, then select)
+        q_tok = np.arange(sh.n_ctx - M, sh.n_ctx)
+    qt = np.ascontiguousarray(q_tok, dtype=np.int64)
+    assert qt.shape == (M,)
+    return qt
+
+
+def forward(sh: Shape, q, k_cache, v_cache, q_tok=None, want_scores: bool = False):
+    """Whole step.  Returns dict(idx [M,Hkv,k_eff], kth [M,Hkv], out [M,Hq,D], scores?)."""
+    _check_store(q, sh, "q"); _check_store(k_cache, sh, "k_cache"); _check_store(v_cache, sh, "v_cache")
+    M = q.shape[0]
+    _, _, n_mid, k = sh.partition()
+    qt = _q_tok(sh, M, q_tok)
+    idx = np.empty((M, sh.n_kv_heads, k), dtype=np.int32)
+    kth = np.zeros((M, sh.n_kv_heads), dtype=np.float64)
+    sc = np.empty((M, sh.n_kv_heads, n_mid), dtype=np.float64) if want_scores else None
+    out = np.empty((M, sh.n_q_heads, sh.head_dim), dtype=np.float64)
+    cs = sh.c()
+    _check_rc(_lib().ro_forward(C.byref(cs), M, _ptr(q), _ptr(qt), _ptr(k_cache), _ptr(v_cache),
+                                _ptr(idx), _ptr(kth), _ptr(sc), _ptr(out)), "forward")
+    return {"idx": idx, "kth": kth, "out": out, "scores": sc}

@@ -1,0 +1,361 @@
+"""Pins for the fp64 CPU oracle: each test ties one part of oracle/ to something
+fixed by the paper or by mathematics, not to the oracle itself.
+
+  * whole pipeline  -> brute-force causal softmax attention with ordinary RoPE
+                       (complex-number form, written here) when k covers the middle
+                       (Eq. 1-3 collapse to plain attention: positions r == token index);
+  * rotary step     -> closed forms (D=2, D=4), norm preservation, identity at 0,
+                       shift invariance of all outputs (relative-position property);
+  * top-k           -> hand-written toys from tests/golden/, argsort brute force, k edge cases;
+  * selection       -> planted needles are always selected; sets ascending, in range;
+  * softmax / PV    -> q = 0 gives the mean of the kept V rows; convexity bounds;
+  * aggregation     -> G = 1 equals single-head Eq. 2; duplicating a head doubles scores;
+  * storage         -> bf16 bit patterns widen exactly.
+"""
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import reattn_oracle as ro
+from paper_2407_15176_amd import workloads as wl
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+# ----------------------------------------------------------------- helpers
+def rng_inputs(seed, M, Hq, Hkv, D, N, dtype="f32"):
+    g = torch.Generator().manual_seed(seed)
+    q = torch.randn(M, Hq, D, generator=g)
+    k = torch.randn(Hkv, N, D, generator=g)
+    v = torch.randn(Hkv, N, D, generator=g)
+    if dtype == "bf16":
+        q, k, v = q.bfloat16(), k.bfloat16(), v.bfloat16()
+    return q, k, v
+
+
+def store(t):
+    return wl.to_numpy_store(t)
+
+
+def f64(t):
+    return t.detach().double().numpy()
+
+
+def brute_rope_complex(x, pos, theta):
+    """Textbook RoPE: pair (x_i, x_{i+D/2}) as a complex number times exp(i*pos*theta^(-2i/D))."""
+    D = x.shape[-1]
+    h = D // 2
+    z = x[..., :h] + 1j * x[..., h:]
+    w = theta ** (-2.0 * np.arange(h) / D)
+    z = z * np.exp(1j * np.asarray(pos, dtype=np.float64)[..., None] * w)
+    return np.concatenate([z.real, z.imag], axis=-1)
+
+
+def brute_full_attention(q, k, v, q_tok, theta):
+    """Causal softmax attention over the whole cache with RoPE at the true token positions.
+    q [M,Hq,D], k,v [Hkv,N,D] float64; query i is token q_tok[i]."""
+    M, Hq, D = q.shape
+    Hkv, N, _ = k.shape
+    G = Hq // Hkv
+    kr = brute_rope_complex(k, np.broadcast_to(np.arange(N), (Hkv, N)), theta)
+    out = np.zeros((M, Hq, D))
+    for i in range(M):
+        t = int(q_tok[i])
+        for hq in range(Hq):
+            h = hq // G
+            qr = brute_rope_complex(q[i, hq][None, :], np.array([t]), theta)[0]
+            logits = kr[h, : t + 1] @ qr / math.sqrt(D)
+            p = np.exp(logits - logits.max())
+            p /= p.sum()
+            out[i, hq] = p @ v[h, : t + 1]
+    return out
+
+
+# ------------------------------------------------- storage widening is exact
+def test_bf16_widening_exact():
+    assert ro.widen_bf16(0x3F80) == 1.0
+    assert ro.widen_bf16(0xC000) == -2.0
+    assert ro.widen_bf16(0x3FC0) == 1.5
+    assert ro.widen_bf16(0x0001) == 2.0 ** -133          # smallest bf16 subnormal
+    assert ro.widen_bf16(0x4049) == 3.140625             # bf16(pi)
+    x = torch.randn(4096, generator=torch.Generator().manual_seed(5)).bfloat16()
+    got = np.array([ro.widen_bf16(int(b)) for b in store(x)])
+    assert np.array_equal(got, f64(x))
+
+
+# ------------------------------------------------------ Eq. 1: the partition
+def test_partition_rules():
+    sh = ro.Shape(4, 2, 8, "f32", 100, 4, 16, 10, 1e4)
+    assert sh.partition() == (4, 16, 80, 10)
+    assert ro.Shape(4, 2, 8, "f32", 100, 4, 16, 500, 1e4).partition() == (4, 16, 80, 80)
+    assert ro.Shape(4, 2, 8, "f32", 20, 4, 16, 10, 1e4).partition() == (4, 16, 0, 0)
+    assert ro.Shape(4, 2, 8, "f32", 10, 4, 16, 10, 1e4).partition() == (4, 6, 0, 0)
+    assert ro.Shape(4, 2, 8, "f32", 3, 4, 16, 10, 1e4).partition() == (3, 0, 0, 0)
+    # the paper's own scope arithmetic (Setup): 32 global + 4096 local + 127 spans of 32
+    assert 32 + 4096 + 127 * 32 == 8192
+
+
+# ------------------------------ whole pipeline collapses to plain attention
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("M", [1, 5])
+def test_full_cover_equals_brute_force_attention(dtype, M):
+    Hq, Hkv, D, N, s, l = 4, 2, 8, 96, 4, 16
+    q, k, v = rng_inputs(11 + M, M, Hq, Hkv, D, N, dtype)
+    sh = ro.Shape(Hq, Hkv, D, dtype, N, s, l, top_k=10_000, rope_theta=10000.0)
+    res = ro.forward(sh, store(q), store(k), store(v))
+    # k >= N_mid: every middle token is selected, in order
+    assert np.array_equal(res["idx"], np.broadcast_to(np.arange(s, N - l), (M, Hkv, N - s - l)))
+    want = brute_full_attention(f64(q), f64(k), f64(v), np.arange(N - M, N), 10000.0)
+    assert np.abs(res["out"] - want).max() < 1e-12
+
+
+def test_empty_middle_is_plain_attention():
+    Hq, Hkv, D, N = 4, 2, 8, 15   # N < sink + local
+    q, k, v = rng_inputs(3, 2, Hq, Hkv, D, N)
+    sh = ro.Shape(Hq, Hkv, D, "f32", N, 4, 16, 7, 10000.0)
+    res = ro.forward(sh, store(q), store(k), store(v))
+    assert res["idx"].shape == (2, Hkv, 0)
+    want = brute_full_attention(f64(q), f64(k), f64(v), np.arange(N - 2, N), 10000.0)
+    assert np.abs(res["out"] - want).max() < 1e-12
+
+
+def test_sparse_selection_matches_brute_force_on_compacted_cache():
+    """With a real selection (k < N_mid) the output must equal plain attention run on the
+    compacted cache [sink, selected, local], whose token positions are 0..S-1 by construction."""
+    Hq, Hkv, D, N, s, l, kk = 2, 2, 16, 200, 3, 20, 17   # G = 1: same set for q head and kv head
+    q, k, v = rng_inputs(21, 1, Hq, Hkv, D, N)
+    sh = ro.Shape(Hq, Hkv, D, "f32", N, s, l, kk, 500000.0)
+    res = ro.forward(sh, store(q), store(k), store(v), want_scores=True)
+    S = s + kk + l
+    for h in range(Hkv):
+        sc = f64(k)[h, s:N - l] @ f64(q)[0, h]
+        assert np.allclose(res["scores"][0, h], sc, rtol=0, atol=1e-12)
+        keep = np.concatenate([np.arange(s), res["idx"][0, h], np.arange(N - l, N)])
+        assert keep.shape == (S,)
+        want = brute_full_attention(f64(q)[:, h:h + 1], f64(k)[h:h + 1, keep], f64(v)[h:h + 1, keep],
+                                    np.array([S - 1]), 500000.0)
+        assert np.abs(res["out"][0, h] - want[0, 0]).max() < 1e-12
+
+
+# --------------------------------------------------------------- rotary step
+def _rope_via_oracle(x, pos, theta):
+    """Rotate one vector through the oracle's gather_rope (row 0 of a 1-token cache)."""
+    D = x.shape[0]
+    sh = ro.Shape(1, 1, D, "f32", 1, 1, 0, 0, theta)
+    kc = np.ascontiguousarray(x.reshape(1, 1, D), dtype=np.float32)
+    ks, vs, n = ro.gather_rope(sh, kc, kc.copy(), np.empty((1, 0), np.int32), pos_offset=pos)
+    assert n == 1 and np.array_equal(vs[0, 0], kc[0, 0].astype(np.float64))
+    return ks[0, 0]
+
+
+def test_rope_closed_forms():
+    p = 2.5
+    assert np.allclose(_rope_via_oracle(np.array([1.0, 0.0]), p, 10000.0),
+                       [math.cos(p), math.sin(p)], atol=1e-15)
+    assert np.allclose(_rope_via_oracle(np.array([0.0, 1.0]), p, 10000.0),
+                       [-math.sin(p), math.cos(p)], atol=1e-15)
+    # D = 4, theta = 1e4: frequencies 1 and 1e4^(-1/2) = 0.01; pairs are (0,2) and (1,3)
+    y = _rope_via_oracle(np.array([0.0, 1.0, 0.0, 0.0]), 100.0, 10000.0)
+    assert np.allclose(y, [0.0, math.cos(1.0), 0.0, math.sin(1.0)], atol=1e-13)
+    y = _rope_via_oracle(np.array([2.0, 0.0, 0.0, 0.0]), 100.0, 10000.0)
+    assert np.allclose(y, [2 * math.cos(100.0), 0.0, 2 * math.sin(100.0), 0.0], atol=1e-13)
+
+
+def test_rope_identity_at_zero_and_norm():
+    x = np.random.default_rng(0).standard_normal(64).astype(np.float32)
+    assert np.array_equal(_rope_via_oracle(x, 0.0, 500000.0), x.astype(np.float64))
+    for p in (1.0, 771.0, 131071.0):
+        y = _rope_via_oracle(x, p, 500000.0)
+        assert abs(np.linalg.norm(y) - np.linalg.norm(x.astype(np.float64))) < 1e-12
+        assert np.allclose(y, brute_rope_complex(x.astype(np.float64)[None], np.array([p]), 500000.0)[0],
+                           atol=1e-12)
+
+
+def test_shift_invariance_of_assigned_positions():
+    """Adding a constant to every re-assigned position (keys and query) changes nothing."""
+    Hq, Hkv, D, N, s, l, kk = 4, 2, 16, 300, 4, 32, 24
+    q, k, v = rng_inputs(7, 3, Hq, Hkv, D, N)
+    sh = ro.Shape(Hq, Hkv, D, "f32", N, s, l, kk, 10000.0)
+    res = ro.forward(sh, store(q), store(k), store(v))
+    for off in (1.0, 1000.0, 65536.0):
+        shifted = ro.attend(sh, store(q), store(k), store(v), res["idx"], pos_offset=off)
+        assert np.abs(shifted - res["out"]).max() < 1e-10
+
+
+def test_gather_rope_matches_concat_definition():
+    Hq, Hkv, D, N, s, l, kk = 2, 2, 8, 64, 2, 8, 5
+    q, k, v = rng_inputs(9, 1, Hq, Hkv, D, N)
+    sh = ro.Shape(Hq, Hkv, D, "f32", N, s, l, kk, 10000.0)
+    idx = np.array([[5, 9, 20, 33, 50], [2, 3, 4, 40, 55]], np.int32)
+    ks, vs, n = ro.gather_rope(sh, store(k), store(v), idx)
+    assert n == s + kk + l
+    for h in range(Hkv):
+        keep = np.concatenate([np.arange(s), idx[h], np.arange(N - l, N)])
+        assert np.array_equal(vs[h], f64(v)[h, keep])
+        want = brute_rope_complex(f64(k)[h, keep], np.arange(n), 10000.0)
+        assert np.abs(ks[h] - want).max() < 1e-13
+
+
+# ---------------------------------------------------------------------- top-k
+def _read_golden_topk(path):
+    cases, cur = [], {}
+    for line in open(path):
+        line = line.split("#")[0].strip()
+        if not line:
+            continue
+        key, val = line.split(":")
+        if key == "scores":
+            cur = {"scores": [float(x) for x in val.split()]}
+        elif key == "k":
+            cur["k"] = int(val)
+        elif key == "base":
+            cur["base"] = int(val)
+        elif key == "expect":
+            cur["expect"] = [int(x) for x in val.split()]
+            cases.append(cur)
+    return cases
+
+
+def test_topk_hand_written_toys():
+    cases = _read_golden_topk(os.path.join(GOLDEN, "topk_toys.txt"))
+    assert len(cases) >= 5
+    for c in cases:
+        idx, kth = ro.topk_rows(np.array([c["scores"]]), c["k"], c["base"])
+        assert idx[0].tolist() == c["expect"], c
+        if c["expect"]:
+            assert kth[0] == sorted(c["scores"], reverse=True)[len(c["expect"]) - 1]
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_topk_brute_force_argsort(seed):
+    r = np.random.default_rng(seed)
+    sc = r.standard_normal((3, 257))
+    sc[:, ::7] = np.round(sc[:, ::7], 1)          # force exact ties
+    for k in (0, 1, 16, 256, 257, 400):
+        idx, kth = ro.topk_rows(sc, k, index_base=4)
+        kk = min(k, 257)
+        for row in range(3):
+            order = np.lexsort((np.arange(257), -sc[row]))[:kk]   # score desc, then index asc
+            assert idx[row].tolist() == sorted((order + 4).tolist())
+            if kk:
+                assert kth[row] == sc[row, order[-1]]
+
+
+def test_selection_is_position_agnostic():
+    """Eq. 2 uses no positional information: permuting the middle of the cache permutes the
+    selected set the same way."""
+    Hq, Hkv, D, N, s, l, kk = 4, 2, 8, 120, 4, 16, 9
+    q, k, v = rng_inputs(13, 1, Hq, Hkv, D, N)
+    sh = ro.Shape(Hq, Hkv, D, "f32", N, s, l, kk, 10000.0)
+    a = ro.forward(sh, store(q), store(k), store(v))["idx"]
+    perm = np.random.default_rng(1).permutation(N - s - l) + s
+    k2 = k.clone()
+    k2[:, s:N - l] = k[:, perm]
+    b = ro.forward(sh, store(q), store(k2), store(v))["idx"]
+    for h in range(Hkv):
+        assert sorted(perm[b[0, h] - s].tolist()) == a[0, h].tolist()
+
+
+# --------------------------------------------------- selection on the recipe
+def test_needles_are_selected_small_config1_recipe():
+    w = wl.CONFIGS[1].scaled(n_ctx=4096, n_local=128, top_k=64)
+    t = wl.generate(w)
+    sh = ro.Shape(w.n_q_heads, w.n_kv_heads, w.head_dim, w.dtype, w.n_ctx, w.n_sink, w.n_local,
+                  w.top_k, w.rope_theta)
+    res = ro.forward(sh, store(t["q"]), store(t["k"]), store(t["v"]))
+    idx = res["idx"][0]
+    assert idx.shape == (w.n_kv_heads, 64)
+    for h in range(w.n_kv_heads):
+        assert np.all(np.diff(idx[h]) > 0)
+        assert idx[h].min() >= w.n_sink and idx[h].max() < w.n_ctx - w.n_local
+        assert set(t["needles"].tolist()) <= set(idx[h].tolist())
+
+
+def test_needles_are_selected_bf16_scaled_recipe():
+    w = wl.CONFIGS[2].scaled(n_ctx=8192, n_local=256, top_k=128, n_q_heads=8, n_kv_heads=2)
+    t = wl.generate(w)
+    sh = ro.Shape(w.n_q_heads, w.n_kv_heads, w.head_dim, w.dtype, w.n_ctx, w.n_sink, w.n_local,
+                  w.top_k, w.rope_theta)
+    res = ro.forward(sh, store(t["q"]), store(t["k"]), store(t["v"]))
+    for h in range(w.n_kv_heads):
+        assert set(t["needles"].tolist()) <= set(res["idx"][0, h].tolist())
+
+
+# --------------------------------------------------------------- softmax / PV
+def test_zero_query_gives_mean_of_kept_values():
+    Hq, Hkv, D, N, s, l, kk = 4, 2, 8, 80, 4, 8, 6
+    _, k, v = rng_inputs(17, 1, Hq, Hkv, D, N)
+    q = torch.zeros(1, Hq, D)
+    sh = ro.Shape(Hq, Hkv, D, "f32", N, s, l, kk, 10000.0)
+    res = ro.forward(sh, store(q), store(k), store(v))
+    # all scores tie at 0: the lowest k indices of the middle win
+    assert np.array_equal(res["idx"][0], np.broadcast_to(np.arange(s, s + kk), (Hkv, kk)))
+    for hq in range(Hq):
+        h = hq // 2
+        keep = np.concatenate([np.arange(s), np.arange(s, s + kk), np.arange(N - l, N)])
+        assert np.abs(res["out"][0, hq] - f64(v)[h, keep].mean(axis=0)).max() < 1e-14
+
+
+def test_output_is_convex_combination():
+    Hq, Hkv, D, N, s, l, kk = 4, 2, 8, 150, 4, 16, 12
+    q, k, v = rng_inputs(19, 2, Hq, Hkv, D, N)
+    sh = ro.Shape(Hq, Hkv, D, "f32", N, s, l, kk, 10000.0)
+    res = ro.forward(sh, store(q), store(k), store(v))
+    for i in range(2):
+        for hq in range(Hq):
+            h = hq // 2
+            last = N - 2 + i
+            keep = np.concatenate([np.arange(s), res["idx"][i, h], np.arange(N - l, last + 1)])
+            vv = f64(v)[h, keep]
+            assert np.all(res["out"][i, hq] <= vv.max(axis=0) + 1e-12)
+            assert np.all(res["out"][i, hq] >= vv.min(axis=0) - 1e-12)
+
+
+def test_softmax_scale_default_and_override():
+    Hq, Hkv, D, N = 2, 1, 16, 40
+    q, k, v = rng_inputs(23, 1, Hq, Hkv, D, N)
+    a = ro.forward(ro.Shape(Hq, Hkv, D, "f32", N, 4, 8, 100, 1e4), store(q), store(k), store(v))["out"]
+    b = ro.forward(ro.Shape(Hq, Hkv, D, "f32", N, 4, 8, 100, 1e4, softmax_scale=0.25),
+                   store(q), store(k), store(v))["out"]
+    assert np.abs(a - b).max() < 1e-15                       # 1/sqrt(16) == 0.25
+    c = ro.forward(ro.Shape(Hq, Hkv, D, "f32", N, 4, 8, 100, 1e4, softmax_scale=0.5),
+                   store(q), store(k), store(v))["out"]
+    assert np.abs(a - c).max() > 1e-3
+
+
+# ---------------------------------------------------------------- aggregation
+def test_group_of_one_is_single_head_and_duplicate_head_doubles():
+    D, N, s, l, kk = 8, 90, 4, 10, 7
+    q, k, v = rng_inputs(29, 1, 2, 2, D, N)
+    sh1 = ro.Shape(2, 2, D, "f32", N, s, l, kk, 1e4)
+    sc1 = ro.score(sh1, store(q), store(k))
+    for h in range(2):
+        assert np.abs(sc1[0, h] - f64(k)[h, s:N - l] @ f64(q)[0, h]).max() < 1e-13
+    # duplicate every query head inside its group: G = 2, scores double, sets unchanged
+    q2 = q.repeat_interleave(2, dim=1)
+    sh2 = ro.Shape(4, 2, D, "f32", N, s, l, kk, 1e4)
+    sc2 = ro.score(sh2, store(q2), store(k))
+    assert np.array_equal(sc2, 2.0 * sc1)
+    i1 = ro.forward(sh1, store(q), store(k), store(v))["idx"]
+    i2 = ro.forward(sh2, store(q2), store(k), store(v))["idx"]
+    assert np.array_equal(i1, i2)
+
+
+def test_group_sum_mixes_heads():
+    """Sum aggregation: the group score is the sum of its heads' scores (not one head's)."""
+    D, N, s, l = 8, 60, 2, 6
+    q, k, v = rng_inputs(31, 1, 4, 2, D, N)
+    sh = ro.Shape(4, 2, D, "f32", N, s, l, 5, 1e4)
+    sc = ro.score(sh, store(q), store(k))
+    for h in range(2):
+        want = f64(k)[h, s:N - l] @ (f64(q)[0, 2 * h] + f64(q)[0, 2 * h + 1])
+        assert np.abs(sc[0, h] - want).max() < 1e-13
+    shm = ro.Shape(4, 2, D, "f32", N, s, l, 5, 1e4, agg=ro.AGG_MAX)
+    scm = ro.score(shm, store(q), store(k))
+    for h in range(2):
+        a = f64(k)[h, s:N - l] @ f64(q)[0, 2 * h]
+        b = f64(k)[h, s:N - l] @ f64(q)[0, 2 * h + 1]
+        assert np.abs(scm[0, h] - np.maximum(a, b)).max() < 1e-13
