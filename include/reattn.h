@@ -1,0 +1,151 @@
+/*
+ * libreattn -- ReAttention's per-layer attention hot path on AMD MI355X (gfx950).
+ *
+ * C ABI.  Every call takes a host pointer to a plain `reattn_params` and raw
+ * DEVICE pointers for tensors; nothing is allocated, freed or retained by the
+ * library, and no call synchronises: work is enqueued on `stream` (a
+ * hipStream_t passed as void*; NULL is the default stream) and the call returns.
+ * Return value: REATTN_OK or a negative reattn_status.  All argument errors are
+ * detected on the host before anything is launched; REATTN_ERR_HIP reports a
+ * failed launch.  q, k_cache and v_cache are never written: the cache stays
+ * free of positional encoding (paper, Method, "Training-Free Integration").
+ *
+ * Notation (paper Eq. 1-3): Hq query heads, Hkv KV heads, G = Hq/Hkv, D head
+ * dimension, N cached tokens INCLUDING the M current ones as the last M rows
+ * (the appendix pseudocode appends before it selects), s = n_sink = l_global,
+ * l = n_local = l_local.  Clamped partition (Eq. 1):
+ *     s_eff = min(s, N), l_eff = min(l, N - s_eff), N_mid = N - s_eff - l_eff,
+ *     k_eff = min(top_k, N_mid), S = s_eff + k_eff + l_eff   ("scope").
+ * sink = [0, s_eff), middle = [s_eff, N - l_eff), local = [N - l_eff, N).
+ *
+ * Layouts (row-major, contiguous innermost D):
+ *     q        [M][Hq][D]        storage dtype (fp32 or bf16), WITHOUT rotary encoding
+ *     k_cache  [Hkv][N][D]       storage dtype, WITHOUT rotary encoding; strides in params
+ *     v_cache  [Hkv][N][D]       storage dtype; strides in params
+ *     scores   [M][Hkv][N_mid]   fp32
+ *     idx      [M][Hkv][k_eff]   int32, ABSOLUTE cache positions, strictly ascending
+ *     k_sel    [M][Hkv][S][D]    fp32, rotary-encoded at re-assigned position r = 0..S-1
+ *     v_sel    [M][Hkv][S][D]    storage dtype (copied rows)
+ *     out      [M][Hq][D]        fp32
+ * Query i is cache token N - M + i; for M > 1 it sees the local part only up to
+ * its own token (causal), and M <= l is required (a chunk lies inside the local
+ * window: paper, hyper-parameter discussion of the chunk size).
+ */
+#ifndef REATTN_H_
+#define REATTN_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  REATTN_OK = 0,
+  REATTN_ERR_NULL = -1,      /* a required pointer is NULL */
+  REATTN_ERR_SHAPE = -2,     /* heads / head_dim / strides not supported */
+  REATTN_ERR_DTYPE = -3,     /* unknown storage dtype or aggregation */
+  REATTN_ERR_RANGE = -4,     /* n_ctx, n_query, n_sink, n_local or top_k out of range */
+  REATTN_ERR_WINDOW = -5,    /* scope S exceeds max_position */
+  REATTN_ERR_WORKSPACE = -6, /* ws is NULL or smaller than reattn_workspace_bytes() */
+  REATTN_ERR_ALIGN = -7,     /* a pointer or stride breaks the 16-byte row alignment */
+  REATTN_ERR_HIP = -8        /* the HIP runtime refused a launch */
+} reattn_status;
+
+typedef enum { REATTN_F32 = 0, REATTN_BF16 = 1 } reattn_dtype;
+
+/* How the G heads of one GQA group are combined into one score per KV head.
+ * The paper votes over per-head lists; this library aggregates scores instead. */
+typedef enum { REATTN_AGG_SUM = 0 } reattn_agg;
+
+typedef struct reattn_params {
+  int32_t n_q_heads;    /* Hq, multiple of n_kv_heads, G <= 16 */
+  int32_t n_kv_heads;   /* Hkv */
+  int32_t head_dim;     /* D: 64 or 128 */
+  int32_t dtype;        /* reattn_dtype of q, k_cache, v_cache, v_sel */
+  int64_t n_ctx;        /* N >= 1 (and N - 1 must fit int32 indices) */
+  int32_t n_query;      /* M >= 1; M == 1 is a decode step; M <= n_local, M <= N */
+  int32_t n_sink;       /* s >= 0 */
+  int32_t n_local;      /* l >= 1 */
+  int32_t top_k;        /* k >= 0; clamped to N_mid */
+  float   rope_theta;   /* rotary base (> 1), e.g. 10000 or 500000 */
+  int32_t max_position; /* S must not exceed it; 0 disables the check */
+  int32_t agg;          /* reattn_agg */
+  float   softmax_scale;/* 0 selects 1/sqrt(D) */
+  int64_t k_stride_head, k_stride_tok; /* in elements; 0,0 means contiguous [Hkv][N][D] */
+  int64_t v_stride_head, v_stride_tok;
+} reattn_params;
+
+/* Library version (major*10000 + minor*100 + patch) and a static message for a status. */
+int reattn_version(void);
+const char* reattn_status_string(int status);
+
+/* Host-only checks of `p` (no GPU needed).  REATTN_OK or the first error found. */
+int reattn_validate(const reattn_params* p);
+
+/* Eq. 1 with the clamping rules above.  Any output pointer may be NULL.  Host only. */
+int reattn_scope(const reattn_params* p, int64_t* n_sink_eff, int64_t* n_local_eff,
+                 int64_t* n_mid, int64_t* k_eff, int64_t* scope);
+
+/* Bytes of device scratch every call below accepts for these params (0 if `p` is
+ * invalid).  The buffer must be 256-byte aligned; its contents are garbage in and
+ * garbage out, and two calls that share it must be ordered on one stream. */
+size_t reattn_workspace_bytes(const reattn_params* p);
+
+/* Eq. 2, first line: scores[i][h][j] = sum over the G heads of group h of
+ * q[i][hG+g] . k_cache[h][s_eff + j], j in [0, N_mid); no rotary encoding, no
+ * scaling; fp32 accumulation.  M == 1 streams the cache once (HBM-bound);
+ * M > 1 runs a bf16 MFMA contraction.  N_mid == 0 is a no-op. */
+int reattn_score(const reattn_params* p, const void* q, const void* k_cache,
+                 float* scores, void* stream);
+
+/* Eq. 2: per (query, KV head) row of `scores`, the k_eff largest entries as
+ * absolute ascending cache indices.  Ties: higher score first, then lower index.
+ * Deterministic.  k_eff == 0 is a no-op.  `scores` is read only. */
+int reattn_topk(const reattn_params* p, const float* scores, int32_t* idx,
+                void* ws, size_t ws_bytes, void* stream);
+
+/* Eq. 3, first line + PE on the keys: gathers [sink, idx, local] rows of K and V
+ * per (query, KV head); K rows are rotary-encoded in fp32 at slot r (pair
+ * (c, c + D/2), angle r * theta^(-2c/D)); V rows are copied.  Rows of a query
+ * beyond its causal cut are zero-filled.  Needs M*Hkv*S*D*(4 + elem) bytes. */
+int reattn_gather_rope(const reattn_params* p, const void* k_cache, const void* v_cache,
+                       const int32_t* idx, float* k_sel, void* v_sel, void* stream);
+
+/* Eq. 3, second line: out[i][hq] = softmax(q~ . k_sel[i][hq/G]^T * scale) v_sel[i][hq/G]
+ * over the first S - (M - 1 - i) slots, with q~ the query rotary-encoded at the
+ * slot of its own key (the last one it sees).  fp32 throughout. */
+int reattn_attend(const reattn_params* p, const void* q, const float* k_sel, const void* v_sel,
+                  float* out, void* ws, size_t ws_bytes, void* stream);
+
+/* One decode step of one layer (appendix, decoding phase, the lines from the
+ * score to rope_attention): score -> top-k -> concat -> PE -> attention, with the
+ * gather and the rotary encoding done on the fly (nothing of size S*D is
+ * materialised).  Requires M == 1.  idx_out may be NULL. */
+int reattn_decode_step(const reattn_params* p, const void* q, const void* k_cache,
+                       const void* v_cache, int32_t* idx_out, float* out,
+                       void* ws, size_t ws_bytes, void* stream);
+
+/* One prefill chunk of one layer (appendix, prefilling phase, same lines) for
+ * M >= 1 queries: per-query scores, per-query top-k, causal attention over
+ * [sink, selected_i, local up to token i].  idx_out may be NULL. */
+int reattn_prefill_chunk(const reattn_params* p, const void* q, const void* k_cache,
+                         const void* v_cache, int32_t* idx_out, float* out,
+                         void* ws, size_t ws_bytes, void* stream);
+
+/* Measurement aid: reattn_decode_step with HIP events recorded on `stream` at the
+ * stage boundaries; it WAITS for the step to finish and fills the HOST array
+ * stage_ms[REATTN_N_STAGES] with the elapsed milliseconds of
+ *   [0] prep (histogram clear + rotary table), [1] the key scan of Eq. 2,
+ *   [2] top-k (pivot, select, refine, emit),   [3] attention of Eq. 3 (+ combine).
+ * Creates and destroys its events, so it is not for the serving loop. */
+#define REATTN_N_STAGES 4
+int reattn_decode_step_timed(const reattn_params* p, const void* q, const void* k_cache,
+                             const void* v_cache, int32_t* idx_out, float* out,
+                             void* ws, size_t ws_bytes, void* stream, float* stage_ms);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* REATTN_H_ */

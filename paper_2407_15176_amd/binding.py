@@ -1,0 +1,263 @@
+"""Thin ctypes front of libreattn.so: the same names as include/reattn.h.
+
+Argument marshalling only: tensors are torch device tensors whose data pointers
+are handed to the C ABI; every step of the path runs in the library's HIP
+kernels on the current torch stream.  There is no CPU fallback: if the library
+has not been built, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+
+import torch  # loads the HIP runtime the library binds to; used for memory and streams only
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libreattn.so")
+
+F32, BF16 = 0, 1
+AGG_SUM = 0
+
+OK = 0
+ERR_NULL, ERR_SHAPE, ERR_DTYPE, ERR_RANGE, ERR_WINDOW, ERR_WORKSPACE, ERR_ALIGN, ERR_HIP = (
+    -1, -2, -3, -4, -5, -6, -7, -8)
+
+EXPORTS = [
+    "reattn_version", "reattn_status_string", "reattn_validate", "reattn_scope",
+    "reattn_workspace_bytes", "reattn_score", "reattn_topk", "reattn_gather_rope",
+    "reattn_attend", "reattn_decode_step", "reattn_prefill_chunk", "reattn_decode_step_timed",
+]
+STAGES = ("prep", "scan", "topk", "attend")
+
+
+class CParams(C.Structure):
+    _fields_ = [
+        ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
+        ("dtype", C.c_int32), ("n_ctx", C.c_int64), ("n_query", C.c_int32),
+        ("n_sink", C.c_int32), ("n_local", C.c_int32), ("top_k", C.c_int32),
+        ("rope_theta", C.c_float), ("max_position", C.c_int32), ("agg", C.c_int32),
+        ("softmax_scale", C.c_float),
+        ("k_stride_head", C.c_int64), ("k_stride_tok", C.c_int64),
+        ("v_stride_head", C.c_int64), ("v_stride_tok", C.c_int64),
+    ]
+
+
+class ReattnError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (status {status})")
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Loads libreattn.so (built by paper_2407_15176_amd/build.py).  Raises if it is missing."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} is not built; run `python -m paper_2407_15176_amd.build` "
+                "(there is no fallback path)")
+        L = C.CDLL(LIB_PATH)
+        P, PP = C.c_void_p, C.POINTER(CParams)
+        L.reattn_version.restype = C.c_int
+        L.reattn_status_string.argtypes = [C.c_int]
+        L.reattn_status_string.restype = C.c_char_p
+        L.reattn_validate.argtypes = [PP]
+        L.reattn_scope.argtypes = [PP] + [C.POINTER(C.c_int64)] * 5
+        L.reattn_workspace_bytes.argtypes = [PP]
+        L.reattn_workspace_bytes.restype = C.c_size_t
+        L.reattn_score.argtypes = [PP, P, P, P, P]
+        L.reattn_topk.argtypes = [PP, P, P, P, C.c_size_t, P]
+        L.reattn_gather_rope.argtypes = [PP, P, P, P, P, P, P]
+        L.reattn_attend.argtypes = [PP, P, P, P, P, P, C.c_size_t, P]
+        L.reattn_decode_step.argtypes = [PP, P, P, P, P, P, P, C.c_size_t, P]
+        L.reattn_prefill_chunk.argtypes = [PP, P, P, P, P, P, P, C.c_size_t, P]
+        L.reattn_decode_step_timed.argtypes = [PP, P, P, P, P, P, P, C.c_size_t, P,
+                                               C.POINTER(C.c_float)]
+        _lib = L
+    return _lib
+
+
+@dataclass
+class Params:
+    """reattn_params in Python clothing (paper Eq. 1-3 notation; see include/reattn.h)."""
+    n_q_heads: int
+    n_kv_heads: int
+    head_dim: int
+    dtype: int
+    n_ctx: int
+    n_query: int = 1
+    n_sink: int = 4
+    n_local: int = 4096
+    top_k: int = 4096
+    rope_theta: float = 500000.0
+    max_position: int = 0
+    agg: int = AGG_SUM
+    softmax_scale: float = 0.0
+    k_stride_head: int = 0
+    k_stride_tok: int = 0
+    v_stride_head: int = 0
+    v_stride_tok: int = 0
+
+    def c(self) -> CParams:
+        return CParams(self.n_q_heads, self.n_kv_heads, self.head_dim, self.dtype, self.n_ctx,
+                       self.n_query, self.n_sink, self.n_local, self.top_k, self.rope_theta,
+                       self.max_position, self.agg, self.softmax_scale,
+                       self.k_stride_head, self.k_stride_tok, self.v_stride_head, self.v_stride_tok)
+
+    @classmethod
+    def from_workload(cls, w) -> "Params":
+        return cls(w.n_q_heads, w.n_kv_heads, w.head_dim, BF16 if w.dtype == "bf16" else F32,
+                   w.n_ctx, w.n_query, w.n_sink, w.n_local, w.top_k, w.rope_theta, w.max_position)
+
+    def torch_dtype(self):
+        return torch.bfloat16 if self.dtype == BF16 else torch.float32
+
+
+def version() -> int:
+    return lib().reattn_version()
+
+
+def status_string(status: int) -> str:
+    return lib().reattn_status_string(status).decode()
+
+
+def validate(p: Params) -> int:
+    cp = p.c()
+    return lib().reattn_validate(C.byref(cp))
+
+
+def scope(p: Params):
+    """(s_eff, l_eff, n_mid, k_eff, S) of Eq. 1 with the clamping rules."""
+    cp = p.c()
+    v = [C.c_int64() for _ in range(5)]
+    rc = lib().reattn_scope(C.byref(cp), *[C.byref(x) for x in v])
+    if rc:
+        raise ReattnError(rc, "reattn_scope")
+    return tuple(x.value for x in v)
+
+
+def workspace_bytes(p: Params) -> int:
+    cp = p.c()
+    return lib().reattn_workspace_bytes(C.byref(cp))
+
+
+def alloc_workspace(p: Params, device="cuda") -> torch.Tensor:
+    n = workspace_bytes(p)
+    if n == 0:
+        raise ReattnError(validate(p), "reattn_workspace_bytes")
+    return torch.empty(n, dtype=torch.uint8, device=device)
+
+
+def _dev(t: torch.Tensor | None, name: str, dtype=None):
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError(f"{name} must be a device tensor")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError(f"{name}: expected {dtype}, got {t.dtype}")
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _check(rc: int, where: str):
+    if rc != OK:
+        raise ReattnError(rc, where)
+
+
+def score(p: Params, q, k_cache, scores=None):
+    s_eff, l_eff, n_mid, k_eff, S = scope(p)
+    if scores is None:
+        scores = torch.empty(p.n_query, p.n_kv_heads, n_mid, dtype=torch.float32, device=q.device)
+    cp = p.c()
+    _check(lib().reattn_score(C.byref(cp), _dev(q, "q", p.torch_dtype()),
+                              _dev(k_cache, "k_cache", p.torch_dtype()),
+                              _dev(scores, "scores", torch.float32), _stream()), "reattn_score")
+    return scores
+
+
+def topk(p: Params, scores, ws, idx=None):
+    s_eff, l_eff, n_mid, k_eff, S = scope(p)
+    if idx is None:
+        idx = torch.empty(p.n_query, p.n_kv_heads, k_eff, dtype=torch.int32, device=scores.device)
+    cp = p.c()
+    _check(lib().reattn_topk(C.byref(cp), _dev(scores, "scores", torch.float32),
+                             _dev(idx, "idx", torch.int32), _dev(ws, "ws"), ws.numel(), _stream()),
+           "reattn_topk")
+    return idx
+
+
+def gather_rope(p: Params, k_cache, v_cache, idx, k_sel=None, v_sel=None):
+    s_eff, l_eff, n_mid, k_eff, S = scope(p)
+    shape = (p.n_query, p.n_kv_heads, S, p.head_dim)
+    if k_sel is None:
+        k_sel = torch.empty(shape, dtype=torch.float32, device=k_cache.device)
+    if v_sel is None:
+        v_sel = torch.empty(shape, dtype=p.torch_dtype(), device=k_cache.device)
+    cp = p.c()
+    _check(lib().reattn_gather_rope(C.byref(cp), _dev(k_cache, "k_cache", p.torch_dtype()),
+                                    _dev(v_cache, "v_cache", p.torch_dtype()),
+                                    _dev(idx, "idx", torch.int32),
+                                    _dev(k_sel, "k_sel", torch.float32),
+                                    _dev(v_sel, "v_sel", p.torch_dtype()), _stream()),
+           "reattn_gather_rope")
+    return k_sel, v_sel
+
+
+def attend(p: Params, q, k_sel, v_sel, ws, out=None):
+    if out is None:
+        out = torch.empty(p.n_query, p.n_q_heads, p.head_dim, dtype=torch.float32, device=q.device)
+    cp = p.c()
+    _check(lib().reattn_attend(C.byref(cp), _dev(q, "q", p.torch_dtype()),
+                               _dev(k_sel, "k_sel", torch.float32),
+                               _dev(v_sel, "v_sel", p.torch_dtype()),
+                               _dev(out, "out", torch.float32), _dev(ws, "ws"), ws.numel(), _stream()),
+           "reattn_attend")
+    return out
+
+
+def _layer(fn_name: str, p: Params, q, k_cache, v_cache, ws, idx_out, out, want_idx: bool):
+    s_eff, l_eff, n_mid, k_eff, S = scope(p)
+    if out is None:
+        out = torch.empty(p.n_query, p.n_q_heads, p.head_dim, dtype=torch.float32, device=q.device)
+    if idx_out is None and want_idx:
+        idx_out = torch.empty(p.n_query, p.n_kv_heads, k_eff, dtype=torch.int32, device=q.device)
+    cp = p.c()
+    fn = getattr(lib(), fn_name)
+    _check(fn(C.byref(cp), _dev(q, "q", p.torch_dtype()), _dev(k_cache, "k_cache", p.torch_dtype()),
+              _dev(v_cache, "v_cache", p.torch_dtype()), _dev(idx_out, "idx_out", torch.int32),
+              _dev(out, "out", torch.float32), _dev(ws, "ws"), ws.numel(), _stream()), fn_name)
+    return out, idx_out
+
+
+def decode_step(p: Params, q, k_cache, v_cache, ws, idx_out=None, out=None, want_idx=True):
+    return _layer("reattn_decode_step", p, q, k_cache, v_cache, ws, idx_out, out, want_idx)
+
+
+def prefill_chunk(p: Params, q, k_cache, v_cache, ws, idx_out=None, out=None, want_idx=True):
+    return _layer("reattn_prefill_chunk", p, q, k_cache, v_cache, ws, idx_out, out, want_idx)
+
+
+def decode_step_timed(p: Params, q, k_cache, v_cache, ws, idx_out=None, out=None):
+    """decode_step with per-stage HIP-event timing; synchronises.  Returns (out, idx, {stage: ms})."""
+    s_eff, l_eff, n_mid, k_eff, S = scope(p)
+    if out is None:
+        out = torch.empty(p.n_query, p.n_q_heads, p.head_dim, dtype=torch.float32, device=q.device)
+    if idx_out is None:
+        idx_out = torch.empty(p.n_query, p.n_kv_heads, k_eff, dtype=torch.int32, device=q.device)
+    ms = (C.c_float * len(STAGES))()
+    cp = p.c()
+    _check(lib().reattn_decode_step_timed(
+        C.byref(cp), _dev(q, "q", p.torch_dtype()), _dev(k_cache, "k_cache", p.torch_dtype()),
+        _dev(v_cache, "v_cache", p.torch_dtype()), _dev(idx_out, "idx_out", torch.int32),
+        _dev(out, "out", torch.float32), _dev(ws, "ws"), ws.numel(), _stream(), ms),
+        "reattn_decode_step_timed")
+    return out, idx_out, dict(zip(STAGES, [float(x) for x in ms]))

@@ -1,0 +1,312 @@
+// C ABI of libreattn: argument validation, launch planning, workspace layout.
+// Everything here runs on the host and returns before the enqueued kernels finish.
+#include "../../include/reattn.h"
+#include "common.hpp"
+
+#include <cmath>
+#include <cstring>
+
+using namespace reattn;
+
+namespace {
+
+constexpr size_t kAlign = 256;
+inline size_t up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+inline bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
+
+int make_plan(const reattn_params* p, Plan* out) {
+  if (!p) return REATTN_ERR_NULL;
+  Plan pl;
+  std::memset(&pl, 0, sizeof pl);
+  if (p->n_q_heads < 1 || p->n_kv_heads < 1 || p->n_q_heads % p->n_kv_heads) return REATTN_ERR_SHAPE;
+  if (p->n_q_heads / p->n_kv_heads > 16) return REATTN_ERR_SHAPE;
+  if (p->head_dim != 64 && p->head_dim != 128) return REATTN_ERR_SHAPE;
+  if (p->dtype != REATTN_F32 && p->dtype != REATTN_BF16) return REATTN_ERR_DTYPE;
+  if (p->agg != REATTN_AGG_SUM) return REATTN_ERR_DTYPE;
+  if (p->n_ctx < 1 || p->n_ctx > 0x7fffffffLL) return REATTN_ERR_RANGE;
+  if (p->n_query < 1 || p->n_query > p->n_ctx || p->n_query > 65535) return REATTN_ERR_RANGE;
+  if (p->n_sink < 0 || p->n_local < 1 || p->top_k < 0) return REATTN_ERR_RANGE;
+  if (!(p->rope_theta > 1.0f) || !std::isfinite(p->rope_theta)) return REATTN_ERR_RANGE;
+  if (!(p->softmax_scale >= 0.0f) || !std::isfinite(p->softmax_scale)) return REATTN_ERR_RANGE;
+  if (p->max_position < 0) return REATTN_ERR_RANGE;
+
+  pl.Hq = p->n_q_heads; pl.Hkv = p->n_kv_heads; pl.D = p->head_dim; pl.G = pl.Hq / pl.Hkv;
+  pl.dtype = p->dtype; pl.M = p->n_query; pl.N = p->n_ctx;
+  pl.s_eff = p->n_sink < pl.N ? p->n_sink : pl.N;
+  pl.l_eff = p->n_local < pl.N - pl.s_eff ? p->n_local : pl.N - pl.s_eff;
+  pl.n_mid = pl.N - pl.s_eff - pl.l_eff;
+  pl.k_eff = (int)(p->top_k < pl.n_mid ? p->top_k : pl.n_mid);
+  const int64_t S = pl.s_eff + pl.k_eff + pl.l_eff;
+  if (pl.M > pl.l_eff) return REATTN_ERR_RANGE;          // a chunk lies inside the local window
+  if (p->max_position > 0 && S > p->max_position) return REATTN_ERR_WINDOW;
+  pl.S = (int)S;
+
+  const int64_t eb = pl.dtype == REATTN_BF16 ? 2 : 4;
+  const bool kdef = p->k_stride_head == 0 && p->k_stride_tok == 0;
+  const bool vdef = p->v_stride_head == 0 && p->v_stride_tok == 0;
+  pl.kst = kdef ? pl.D : p->k_stride_tok;  pl.ksh = kdef ? pl.N * pl.D : p->k_stride_head;
+  pl.vst = vdef ? pl.D : p->v_stride_tok;  pl.vsh = vdef ? pl.N * pl.D : p->v_stride_head;
+  if (pl.kst < pl.D || pl.vst < pl.D || pl.ksh < 0 || pl.vsh < 0) return REATTN_ERR_SHAPE;
+  if ((pl.kst * eb) % 16 || (pl.ksh * eb) % 16 || (pl.vst * eb) % 16 || (pl.vsh * eb) % 16)
+    return REATTN_ERR_ALIGN;
+
+  pl.theta = p->rope_theta;
+  pl.scale = p->softmax_scale > 0.f ? p->softmax_scale : 1.0f / std::sqrt((float)pl.D);
+
+  pl.nchunks = (int)((pl.n_mid + kChunk - 1) / kChunk);
+  pl.nwords = (int64_t)pl.nchunks * kChunkWords;
+
+  pl.nsub = (pl.G + 3) / 4;
+  pl.gt = (pl.G + pl.nsub - 1) / pl.nsub;
+  {
+    // slots per workgroup: 256 (16 per 16-lane group) unless that leaves CUs idle
+    const int64_t units = (int64_t)pl.Hkv * pl.nsub * pl.M;
+    int64_t want = (256 + units - 1) / units;             // workgroups along S to fill the chip
+    if (want < 1) want = 1;
+    int64_t len = (S + want - 1) / want;
+    len = (len + 63) / 64 * 64;
+    if (len < 64) len = 64;
+    if (units >= 256 && len < S) len = (S + 63) / 64 * 64; // plenty of (query, head) units: no split
+    pl.split_len = (int)len;
+    pl.nsplit = (int)((S + len - 1) / len);
+  }
+
+  // query tile of the prefill path: per-tile scratch stays near 4 GiB
+  const size_t per_query = (size_t)pl.Hkv * ((size_t)pl.n_mid * 8 + (size_t)kHistBins * 4 +
+                                             (size_t)pl.nwords * 4 + (size_t)pl.nchunks * 4 + 64);
+  int64_t mt = (int64_t)(((size_t)4 << 30) / (per_query ? per_query : 1));
+  if (mt < 1) mt = 1;
+  if (mt > pl.M) mt = pl.M;
+  if (mt * pl.Hkv > 65535) mt = 65535 / pl.Hkv;
+  if (mt < 1) return REATTN_ERR_SHAPE;
+  pl.m_tile = (int)mt;
+
+  const size_t rows = (size_t)pl.m_tile * pl.Hkv;
+  size_t off = 0;
+  pl.off_scores = off; off += up(rows * (size_t)pl.n_mid * 4);
+  pl.off_hist = off;   off += up(rows * kHistBins * 4);
+  pl.off_pivot = off;  off += up(rows * sizeof(Pivot));
+  pl.off_ncand = off;  off += up(rows * 4);
+  pl.off_cand = off;   off += up(rows * (size_t)pl.n_mid * 4);
+  pl.off_bitmap = off; off += up(rows * (size_t)pl.nwords * 4);
+  pl.off_cnt = off;    off += up(rows * (size_t)pl.nchunks * 4);
+  pl.off_idx = off;    off += up((size_t)pl.M * pl.Hkv * (size_t)pl.k_eff * 4);
+  pl.off_rope = off;   off += up((size_t)pl.S * (pl.D / 2) * sizeof(float2));
+  pl.off_part = off;   off += up((size_t)pl.M * pl.Hq * (size_t)pl.nsplit * (pl.D + 2) * 4);
+  pl.total = off ? off : kAlign;
+  *out = pl;
+  return REATTN_OK;
+}
+
+struct Ws {
+  float* scores; uint32_t* hist; Pivot* pivot; uint32_t* ncand; int32_t* cand;
+  uint32_t* bitmap; uint32_t* cnt; int32_t* idx; float2* rope; float* part;
+};
+
+int bind_ws(const Plan& pl, void* ws, size_t ws_bytes, Ws* w) {
+  if (!ws || ws_bytes < pl.total) return REATTN_ERR_WORKSPACE;
+  if ((uintptr_t)ws % kAlign) return REATTN_ERR_ALIGN;
+  char* b = (char*)ws;
+  w->scores = (float*)(b + pl.off_scores);   w->hist = (uint32_t*)(b + pl.off_hist);
+  w->pivot = (Pivot*)(b + pl.off_pivot);     w->ncand = (uint32_t*)(b + pl.off_ncand);
+  w->cand = (int32_t*)(b + pl.off_cand);     w->bitmap = (uint32_t*)(b + pl.off_bitmap);
+  w->cnt = (uint32_t*)(b + pl.off_cnt);      w->idx = (int32_t*)(b + pl.off_idx);
+  w->rope = (float2*)(b + pl.off_rope);      w->part = (float*)(b + pl.off_part);
+  return REATTN_OK;
+}
+
+inline int hip_rc(hipError_t e) { return e == hipSuccess ? REATTN_OK : REATTN_ERR_HIP; }
+
+// score -> top-k for the queries [q0, q0 + nq), then the caller attends.
+// `ev`, when given, holds REATTN_N_STAGES + 1 events recorded at the stage boundaries.
+inline void mark(hipEvent_t* ev, int i, hipStream_t st) { if (ev) (void)hipEventRecord(ev[i], st); }
+
+int select_tile(const Plan& pl, const Ws& w, const void* q, int q0, int nq, const void* k_cache,
+                int32_t* idx_all, bool rope_too, hipEvent_t* ev, hipStream_t st) {
+  const int rows = nq * pl.Hkv;
+  const size_t eb = pl.dtype == REATTN_BF16 ? 2 : 4;
+  const char* qt = (const char*)q + (size_t)q0 * pl.Hq * pl.D * eb;
+  int rc = hip_rc(launch_prep(pl, pl.k_eff > 0 ? rows : 0, w.hist, rope_too ? w.rope : nullptr, st));
+  mark(ev, 1, st);
+  if (rc || pl.k_eff == 0) { mark(ev, 2, st); mark(ev, 3, st); return rc; }
+  rc = hip_rc(launch_score_scan(pl, qt, nq, k_cache, w.scores, w.hist, st));
+  mark(ev, 2, st);
+  if (rc) return rc;
+  rc = hip_rc(launch_topk(pl, rows, w.scores, true, w.hist, w.pivot, w.ncand, w.cand, w.bitmap,
+                          w.cnt, idx_all + (size_t)q0 * pl.Hkv * pl.k_eff, st));
+  mark(ev, 3, st);
+  return rc;
+}
+
+int run_layer(const reattn_params* p, bool decode_only, const void* q, const void* k_cache,
+              const void* v_cache, int32_t* idx_out, float* out, void* ws, size_t ws_bytes,
+              void* stream, hipEvent_t* ev = nullptr) {
+  Plan pl;
+  int rc = make_plan(p, &pl);
+  if (rc) return rc;
+  if (decode_only && pl.M != 1) return REATTN_ERR_RANGE;
+  if (!q || !k_cache || !v_cache || !out) return REATTN_ERR_NULL;
+  if (!aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(out))
+    return REATTN_ERR_ALIGN;
+  Ws w;
+  rc = bind_ws(pl, ws, ws_bytes, &w);
+  if (rc) return rc;
+  hipStream_t st = (hipStream_t)stream;
+  int32_t* idx = idx_out ? idx_out : w.idx;
+  mark(ev, 0, st);
+  for (int q0 = 0; q0 < pl.M; q0 += pl.m_tile) {
+    const int nq = pl.M - q0 < pl.m_tile ? pl.M - q0 : pl.m_tile;
+    rc = select_tile(pl, w, q, q0, nq, k_cache, idx, q0 == 0, ev, st);
+    if (rc) return rc;
+  }
+  rc = hip_rc(launch_attend(pl, true, q, 0, pl.M, k_cache, v_cache, idx, w.rope, w.part, out, st));
+  mark(ev, 4, st);
+  return rc;
+}
+
+}  // namespace
+
+extern "C" {
+
+int reattn_version(void) { return 100; }
+
+const char* reattn_status_string(int s) {
+  switch (s) {
+    case REATTN_OK: return "ok";
+    case REATTN_ERR_NULL: return "a required pointer is NULL";
+    case REATTN_ERR_SHAPE: return "unsupported head counts, head_dim or strides";
+    case REATTN_ERR_DTYPE: return "unknown storage dtype or aggregation";
+    case REATTN_ERR_RANGE: return "n_ctx, n_query, n_sink, n_local, top_k or rope parameters out of range";
+    case REATTN_ERR_WINDOW: return "attention scope exceeds max_position";
+    case REATTN_ERR_WORKSPACE: return "workspace missing or too small";
+    case REATTN_ERR_ALIGN: return "pointer or stride not 16-byte aligned (workspace: 256)";
+    case REATTN_ERR_HIP: return "HIP launch failed";
+    default: return "unknown status";
+  }
+}
+
+int reattn_validate(const reattn_params* p) {
+  Plan pl;
+  return make_plan(p, &pl);
+}
+
+int reattn_scope(const reattn_params* p, int64_t* n_sink_eff, int64_t* n_local_eff,
+                 int64_t* n_mid, int64_t* k_eff, int64_t* scope) {
+  Plan pl;
+  const int rc = make_plan(p, &pl);
+  if (rc) return rc;
+  if (n_sink_eff) *n_sink_eff = pl.s_eff;
+  if (n_local_eff) *n_local_eff = pl.l_eff;
+  if (n_mid) *n_mid = pl.n_mid;
+  if (k_eff) *k_eff = pl.k_eff;
+  if (scope) *scope = pl.S;
+  return REATTN_OK;
+}
+
+size_t reattn_workspace_bytes(const reattn_params* p) {
+  Plan pl;
+  return make_plan(p, &pl) == REATTN_OK ? pl.total : 0;
+}
+
+int reattn_score(const reattn_params* p, const void* q, const void* k_cache, float* scores,
+                 void* stream) {
+  Plan pl;
+  int rc = make_plan(p, &pl);
+  if (rc) return rc;
+  if (!q || !k_cache || (!scores && pl.n_mid > 0)) return REATTN_ERR_NULL;
+  if (!aligned16(q) || !aligned16(k_cache)) return REATTN_ERR_ALIGN;
+  const int per = 65535 / pl.Hkv;
+  const size_t eb = pl.dtype == REATTN_BF16 ? 2 : 4;
+  for (int q0 = 0; q0 < pl.M && !rc; q0 += per) {
+    const int nq = pl.M - q0 < per ? pl.M - q0 : per;
+    rc = hip_rc(launch_score_scan(pl, (const char*)q + (size_t)q0 * pl.Hq * pl.D * eb, nq, k_cache,
+                                  scores + (size_t)q0 * pl.Hkv * pl.n_mid, nullptr,
+                                  (hipStream_t)stream));
+  }
+  return rc;
+}
+
+int reattn_topk(const reattn_params* p, const float* scores, int32_t* idx, void* ws,
+                size_t ws_bytes, void* stream) {
+  Plan pl;
+  int rc = make_plan(p, &pl);
+  if (rc) return rc;
+  if (pl.k_eff == 0) return REATTN_OK;
+  if (!scores || !idx) return REATTN_ERR_NULL;
+  Ws w;
+  rc = bind_ws(pl, ws, ws_bytes, &w);
+  if (rc) return rc;
+  hipStream_t st = (hipStream_t)stream;
+  for (int q0 = 0; q0 < pl.M; q0 += pl.m_tile) {
+    const int nq = pl.M - q0 < pl.m_tile ? pl.M - q0 : pl.m_tile;
+    const int rows = nq * pl.Hkv;
+    rc = hip_rc(launch_prep(pl, rows, w.hist, nullptr, st));
+    if (rc) return rc;
+    rc = hip_rc(launch_topk(pl, rows, scores + (size_t)q0 * pl.Hkv * pl.n_mid, false, w.hist,
+                            w.pivot, w.ncand, w.cand, w.bitmap, w.cnt,
+                            idx + (size_t)q0 * pl.Hkv * pl.k_eff, st));
+    if (rc) return rc;
+  }
+  return REATTN_OK;
+}
+
+int reattn_gather_rope(const reattn_params* p, const void* k_cache, const void* v_cache,
+                       const int32_t* idx, float* k_sel, void* v_sel, void* stream) {
+  Plan pl;
+  int rc = make_plan(p, &pl);
+  if (rc) return rc;
+  if (!k_cache || !v_cache || !k_sel || !v_sel || (!idx && pl.k_eff > 0)) return REATTN_ERR_NULL;
+  if (!aligned16(k_cache) || !aligned16(v_cache) || !aligned16(k_sel) || !aligned16(v_sel))
+    return REATTN_ERR_ALIGN;
+  return hip_rc(launch_gather_rope(pl, k_cache, v_cache, idx, k_sel, v_sel, (hipStream_t)stream));
+}
+
+int reattn_attend(const reattn_params* p, const void* q, const float* k_sel, const void* v_sel,
+                  float* out, void* ws, size_t ws_bytes, void* stream) {
+  Plan pl;
+  int rc = make_plan(p, &pl);
+  if (rc) return rc;
+  if (!q || !k_sel || !v_sel || !out) return REATTN_ERR_NULL;
+  if (!aligned16(q) || !aligned16(k_sel) || !aligned16(v_sel) || !aligned16(out))
+    return REATTN_ERR_ALIGN;
+  Ws w;
+  rc = bind_ws(pl, ws, ws_bytes, &w);
+  if (rc) return rc;
+  hipStream_t st = (hipStream_t)stream;
+  rc = hip_rc(launch_prep(pl, 0, nullptr, w.rope, st));
+  if (rc) return rc;
+  return hip_rc(launch_attend(pl, false, q, 0, pl.M, k_sel, v_sel, nullptr, w.rope, w.part, out, st));
+}
+
+int reattn_decode_step(const reattn_params* p, const void* q, const void* k_cache,
+                       const void* v_cache, int32_t* idx_out, float* out, void* ws,
+                       size_t ws_bytes, void* stream) {
+  return run_layer(p, true, q, k_cache, v_cache, idx_out, out, ws, ws_bytes, stream);
+}
+
+int reattn_prefill_chunk(const reattn_params* p, const void* q, const void* k_cache,
+                         const void* v_cache, int32_t* idx_out, float* out, void* ws,
+                         size_t ws_bytes, void* stream) {
+  return run_layer(p, false, q, k_cache, v_cache, idx_out, out, ws, ws_bytes, stream);
+}
+
+int reattn_decode_step_timed(const reattn_params* p, const void* q, const void* k_cache,
+                             const void* v_cache, int32_t* idx_out, float* out, void* ws,
+                             size_t ws_bytes, void* stream, float* stage_ms) {
+  if (!stage_ms) return REATTN_ERR_NULL;
+  hipEvent_t ev[REATTN_N_STAGES + 1];
+  int made = 0;
+  for (; made <= REATTN_N_STAGES; ++made)
+    if (hipEventCreate(&ev[made]) != hipSuccess) break;
+  int rc = made == REATTN_N_STAGES + 1 ? REATTN_OK : REATTN_ERR_HIP;
+  if (!rc) rc = run_layer(p, true, q, k_cache, v_cache, idx_out, out, ws, ws_bytes, stream, ev);
+  if (!rc) {
+    if (hipEventSynchronize(ev[REATTN_N_STAGES]) != hipSuccess) rc = REATTN_ERR_HIP;
+    for (int i = 0; i < REATTN_N_STAGES && !rc; ++i)
+      if (hipEventElapsedTime(&stage_ms[i], ev[i], ev[i + 1]) != hipSuccess) rc = REATTN_ERR_HIP;
+  }
+  for (int i = 0; i < made; ++i) (void)hipEventDestroy(ev[i]);
+  return rc;
+}
+
+}  // extern "C"

@@ -1,0 +1,323 @@
+// Stage 2: ordinary softmax attention over [global, select, local] (paper Eq. 3,
+// second line; appendix `rope_attention`).  The scope S is a few thousand slots
+// and a decode step has one query per head, so this is a flash-decoding kernel:
+// S is split across workgroups, every workgroup keeps an online softmax per query
+// head of one GQA group, partial (max, sum, weighted V) triples are merged with a
+// log-sum-exp combine.  All arithmetic is fp32 on the vector ALUs (0.2 GFLOP per
+// step: the cost is the 2*S*Hkv*D*bytes of gathered rows, not the math).
+//
+// Fused form (used by decode_step / prefill_chunk): the concatenation is never
+// materialised.  Slot r is resolved to a cache row on the fly (sink: r, selected:
+// idx[r - s], local: N - l + ...), the K row is rotary-encoded in registers at
+// position r from a (cos, sin) table, the V row is consumed directly.
+// Materialised form (reattn_attend): reads the fp32 rotated k_sel / v_sel buffers.
+//
+// Sixteen lanes own one slot at a time: lane `sub` holds channels [sub*E, sub*E+E)
+// and the partner channels D/2 higher, so the rotary pairing (c, c + D/2) stays
+// inside a lane and dot products finish with DPP row reductions.
+#include "common.hpp"
+
+namespace reattn {
+namespace {
+
+constexpr int kGroupsPerBlock = 16;   // 256 threads / 16 lanes
+constexpr float kNegBig = -1.0e30f;
+
+struct AttendArgs {
+  const void* q; const void* k; const void* v;
+  const int32_t* idx; const float2* rope;
+  float* part; float* out;
+  int64_t ksh, kst, vsh, vst, N;
+  int Hq, Hkv, G, M, S, s_eff, k_eff, l_eff;
+  int q_first, split_len, nsplit, nsub;
+  float scale_log2e;
+};
+
+template <typename T, int E> struct Half;          // E consecutive channels of one row -> fp32
+template <> struct Half<float, 4> {
+  static __device__ __forceinline__ void load(const void* p, float* x) {
+    const u32x4 d = *(const u32x4*)p;
+    x[0] = __uint_as_float(d.x); x[1] = __uint_as_float(d.y);
+    x[2] = __uint_as_float(d.z); x[3] = __uint_as_float(d.w);
+  }
+};
+template <> struct Half<float, 2> {
+  static __device__ __forceinline__ void load(const void* p, float* x) {
+    const u32x2 d = *(const u32x2*)p;
+    x[0] = __uint_as_float(d.x); x[1] = __uint_as_float(d.y);
+  }
+};
+template <> struct Half<uint16_t, 4> {
+  static __device__ __forceinline__ void load(const void* p, float* x) {
+    const u32x2 d = *(const u32x2*)p;
+    x[0] = bf16_lo(d.x); x[1] = bf16_hi(d.x); x[2] = bf16_lo(d.y); x[3] = bf16_hi(d.y);
+  }
+};
+template <> struct Half<uint16_t, 2> {
+  static __device__ __forceinline__ void load(const void* p, float* x) {
+    const uint32_t d = *(const uint32_t*)p;
+    x[0] = bf16_lo(d); x[1] = bf16_hi(d);
+  }
+};
+
+// T: storage type of q / V (and of K when FUSED).  GT: query heads per workgroup.
+template <typename T, int D, int GT, bool FUSED>
+__global__ __launch_bounds__(256) void attend_kernel(AttendArgs a) {
+  constexpr int E = D / 32;
+  constexpr int UNR = 4;
+  typedef typename std::conditional<FUSED, T, float>::type KT;
+
+  __shared__ float s_m[kGroupsPerBlock][GT];
+  __shared__ float s_l[kGroupsPerBlock][GT];
+  __shared__ float s_acc[kGroupsPerBlock][GT][D];
+
+  const int sub = threadIdx.x & 15, gi = threadIdx.x >> 4;
+  const int split = blockIdx.x;
+  const int h = blockIdx.y / a.nsub, g0 = (blockIdx.y % a.nsub) * GT;
+  const int qn = blockIdx.z, qi = a.q_first + qn;
+  const int visible = a.S - (a.M - 1 - qi);         // slots this query may see; its own key is the last
+  const int c0 = sub * E;
+
+  // query rows of this group, rotary-encoded at the slot of the query's own key
+  float qlo[GT][E], qhi[GT][E];
+  {
+    const float2* rp = a.rope + (int64_t)(visible - 1) * (D / 2) + c0;
+#pragma unroll
+    for (int g = 0; g < GT; ++g) {
+      const int gg = (g0 + g < a.G) ? g0 + g : a.G - 1;
+      const T* qr = (const T*)a.q + ((int64_t)qi * a.Hq + (int64_t)h * a.G + gg) * D;
+      float lo[E], hi[E];
+      Half<T, E>::load(qr + c0, lo);
+      Half<T, E>::load(qr + D / 2 + c0, hi);
+#pragma unroll
+      for (int e = 0; e < E; ++e) {
+        const float2 cs = rp[e];
+        qlo[g][e] = (lo[e] * cs.x - hi[e] * cs.y) * a.scale_log2e;
+        qhi[g][e] = (hi[e] * cs.x + lo[e] * cs.y) * a.scale_log2e;
+      }
+    }
+  }
+
+  int tok_cache = 0;
+  float m[GT], l[GT], alo[GT][E], ahi[GT][E];
+#pragma unroll
+  for (int g = 0; g < GT; ++g) {
+    m[g] = kNegBig; l[g] = 0.f;
+#pragma unroll
+    for (int e = 0; e < E; ++e) { alo[g][e] = 0.f; ahi[g][e] = 0.f; }
+  }
+
+  const int r0 = split * a.split_len;
+  const int r_end = (r0 + a.split_len < visible) ? r0 + a.split_len : visible;
+  const int64_t row_kv = (int64_t)qi * a.Hkv + h;
+  const int32_t* my_idx = FUSED ? a.idx + row_kv * a.k_eff : nullptr;
+
+  // slot -> cache row: lane `sub` resolves the group's slot number `sub` of every batch of
+  // 16 slots up front, so the index load is off the critical path of the row loads
+  auto resolve = [&](int r) -> int {
+    const int r2 = r < r_end ? r : r_end - 1;
+    if (r2 < a.s_eff) return r2;
+    if (r2 < a.s_eff + a.k_eff) return my_idx[r2 - a.s_eff];
+    return (int)(a.N - a.l_eff) + (r2 - a.s_eff - a.k_eff);
+  };
+
+  for (int base = r0; base < r_end; base += kGroupsPerBlock * UNR) {
+    float klo[UNR][E], khi[UNR][E], vlo[UNR][E], vhi[UNR][E];
+    bool valid[UNR];
+    int rr[UNR];
+    int64_t tok[UNR];
+    int tok_lane = 0;
+    if (FUSED) {
+      // 16 slots of this group per pass of 16 lanes: pass index = (base - r0) / (16 * 16)
+      if (((base - r0) / (kGroupsPerBlock * UNR)) % (16 / UNR) == 0) {
+        tok_cache = resolve(base + sub * kGroupsPerBlock + gi);
+      }
+      tok_lane = tok_cache;
+    }
+#pragma unroll
+    for (int u = 0; u < UNR; ++u) {
+      const int r = base + u * kGroupsPerBlock + gi;
+      valid[u] = r < r_end;
+      rr[u] = valid[u] ? r : r_end - 1;
+      if (FUSED) {
+        const int which = (((base - r0) / (kGroupsPerBlock * UNR)) % (16 / UNR)) * UNR + u;
+        tok[u] = __shfl(tok_lane, which, 16);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < UNR; ++u) {
+      const KT* kr; const T* vr;
+      if (FUSED) {
+        kr = (const KT*)a.k + (int64_t)h * a.ksh + tok[u] * a.kst;
+        vr = (const T*)a.v + (int64_t)h * a.vsh + tok[u] * a.vst;
+      } else {
+        kr = (const KT*)a.k + (row_kv * a.S + rr[u]) * D;
+        vr = (const T*)a.v + (row_kv * a.S + rr[u]) * D;
+      }
+      Half<KT, E>::load(kr + c0, klo[u]);
+      Half<KT, E>::load(kr + D / 2 + c0, khi[u]);
+      Half<T, E>::load(vr + c0, vlo[u]);
+      Half<T, E>::load(vr + D / 2 + c0, vhi[u]);
+    }
+    if (FUSED) {
+#pragma unroll
+      for (int u = 0; u < UNR; ++u) {
+        const float2* rp = a.rope + (int64_t)rr[u] * (D / 2) + c0;
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+          const float2 cs = rp[e];
+          const float lo = klo[u][e], hi = khi[u][e];
+          klo[u][e] = lo * cs.x - hi * cs.y;
+          khi[u][e] = hi * cs.x + lo * cs.y;
+        }
+      }
+    }
+#pragma unroll
+    for (int g = 0; g < GT; ++g) {
+      float s[UNR];
+      float mx = m[g];
+#pragma unroll
+      for (int u = 0; u < UNR; ++u) {
+        float d = 0.f;
+#pragma unroll
+        for (int e = 0; e < E; ++e) d = fmaf(klo[u][e], qlo[g][e], fmaf(khi[u][e], qhi[g][e], d));
+        d = group_sum<16>(d);
+        s[u] = valid[u] ? d : kNegBig;
+        mx = fmaxf(mx, s[u]);
+      }
+      const float corr = exp2f(m[g] - mx);
+      m[g] = mx;
+      float lsum = l[g] * corr;
+#pragma unroll
+      for (int e = 0; e < E; ++e) { alo[g][e] *= corr; ahi[g][e] *= corr; }
+#pragma unroll
+      for (int u = 0; u < UNR; ++u) {
+        const float p = valid[u] ? exp2f(s[u] - mx) : 0.f;
+        lsum += p;
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+          alo[g][e] = fmaf(p, vlo[u][e], alo[g][e]);
+          ahi[g][e] = fmaf(p, vhi[u][e], ahi[g][e]);
+        }
+      }
+      l[g] = lsum;
+    }
+  }
+
+  // merge the 16 slot-groups of this workgroup
+#pragma unroll
+  for (int g = 0; g < GT; ++g) {
+    if (sub == 0) { s_m[gi][g] = m[g]; s_l[gi][g] = l[g]; }
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+      s_acc[gi][g][c0 + e] = alo[g][e];
+      s_acc[gi][g][D / 2 + c0 + e] = ahi[g][e];
+    }
+  }
+  __syncthreads();
+  for (int o = threadIdx.x; o < GT * D; o += 256) {
+    const int g = o / D, c = o % D;
+    if (g0 + g >= a.G) continue;
+    float mx = kNegBig;
+#pragma unroll
+    for (int j = 0; j < kGroupsPerBlock; ++j) mx = fmaxf(mx, s_m[j][g]);
+    float lsum = 0.f, acc = 0.f;
+#pragma unroll
+    for (int j = 0; j < kGroupsPerBlock; ++j) {
+      const float w = exp2f(s_m[j][g] - mx);
+      lsum = fmaf(s_l[j][g], w, lsum);
+      acc = fmaf(s_acc[j][g][c], w, acc);
+    }
+    float* pp = a.part + (((int64_t)qn * a.Hq + (int64_t)h * a.G + g0 + g) * a.nsplit + split) * (D + 2);
+    if (c == 0) { pp[0] = mx; pp[1] = lsum; }
+    pp[2 + c] = acc;
+  }
+}
+
+// out[q][hq][c] = sum_s A_s[c] 2^(m_s - m) / sum_s l_s 2^(m_s - m)
+// One workgroup per (query, head); NG thread groups of D lanes each take every NG-th split.
+template <int D, int NG>
+__global__ __launch_bounds__(D * NG) void attend_combine_kernel(const float* __restrict__ part,
+                                                                int nsplit, float* out) {
+  __shared__ float s_m[NG], s_l[NG][D], s_a[NG][D];
+  const int c = threadIdx.x % D, grp = threadIdx.x / D;
+  const int64_t qh = blockIdx.x;
+  const float* pp = part + qh * nsplit * (D + 2);
+  float mx = kNegBig;
+  for (int s = grp; s < nsplit; s += NG) mx = fmaxf(mx, pp[(int64_t)s * (D + 2)]);
+  float lsum = 0.f, acc = 0.f;
+  for (int s = grp; s < nsplit; s += NG) {
+    const float* ps = pp + (int64_t)s * (D + 2);
+    const float w = exp2f(ps[0] - mx);
+    lsum = fmaf(ps[1], w, lsum);
+    acc = fmaf(ps[2 + c], w, acc);
+  }
+  if (c == 0) s_m[grp] = mx;
+  s_l[grp][c] = lsum; s_a[grp][c] = acc;
+  __syncthreads();
+  if (grp == 0) {
+    float gm = kNegBig;
+#pragma unroll
+    for (int g = 0; g < NG; ++g) gm = fmaxf(gm, s_m[g]);
+    float L = 0.f, A = 0.f;
+#pragma unroll
+    for (int g = 0; g < NG; ++g) {
+      const float w = exp2f(s_m[g] - gm);
+      L = fmaf(s_l[g][c], w, L);
+      A = fmaf(s_a[g][c], w, A);
+    }
+    out[qh * D + c] = A / L;
+  }
+}
+
+template <typename T, int D, bool FUSED>
+void launch_gt(const AttendArgs& a, int gt, dim3 grid, hipStream_t st) {
+  switch (gt) {
+    case 1: hipLaunchKernelGGL((attend_kernel<T, D, 1, FUSED>), grid, dim3(256), 0, st, a); break;
+    case 2: hipLaunchKernelGGL((attend_kernel<T, D, 2, FUSED>), grid, dim3(256), 0, st, a); break;
+    case 3: hipLaunchKernelGGL((attend_kernel<T, D, 3, FUSED>), grid, dim3(256), 0, st, a); break;
+    default: hipLaunchKernelGGL((attend_kernel<T, D, 4, FUSED>), grid, dim3(256), 0, st, a); break;
+  }
+}
+
+template <bool FUSED>
+void launch_td(const Plan& pl, const AttendArgs& a, dim3 grid, hipStream_t st) {
+  if (pl.dtype == 0) {
+    if (pl.D == 64) launch_gt<float, 64, FUSED>(a, pl.gt, grid, st);
+    else            launch_gt<float, 128, FUSED>(a, pl.gt, grid, st);
+  } else {
+    if (pl.D == 64) launch_gt<uint16_t, 64, FUSED>(a, pl.gt, grid, st);
+    else            launch_gt<uint16_t, 128, FUSED>(a, pl.gt, grid, st);
+  }
+}
+
+}  // namespace
+
+hipError_t launch_attend(const Plan& pl, bool fused, const void* q, int q_first, int n_query,
+                         const void* k_src, const void* v_src, const int32_t* idx,
+                         const float2* rope, float* part, float* out, hipStream_t st) {
+  if (n_query <= 0) return hipSuccess;
+  AttendArgs a;
+  a.q = q; a.k = k_src; a.v = v_src; a.idx = idx; a.rope = rope; a.part = part; a.out = out;
+  a.ksh = pl.ksh; a.kst = pl.kst; a.vsh = pl.vsh; a.vst = pl.vst; a.N = pl.N;
+  a.Hq = pl.Hq; a.Hkv = pl.Hkv; a.G = pl.G; a.M = pl.M; a.S = pl.S;
+  a.s_eff = (int)pl.s_eff; a.k_eff = pl.k_eff; a.l_eff = (int)pl.l_eff;
+  a.q_first = q_first; a.split_len = pl.split_len; a.nsplit = pl.nsplit; a.nsub = pl.nsub;
+  a.scale_log2e = pl.scale * 1.4426950408889634f;
+  const dim3 grid((unsigned)pl.nsplit, (unsigned)(pl.Hkv * pl.nsub), (unsigned)n_query);
+  if (fused) launch_td<true>(pl, a, grid, st); else launch_td<false>(pl, a, grid, st);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  float* o = out + (int64_t)q_first * pl.Hq * pl.D;
+  const dim3 cgrid((unsigned)(n_query * pl.Hq));
+  if (pl.nsplit > 4) {
+    if (pl.D == 64) hipLaunchKernelGGL((attend_combine_kernel<64, 16>), cgrid, dim3(1024), 0, st, part, pl.nsplit, o);
+    else            hipLaunchKernelGGL((attend_combine_kernel<128, 8>), cgrid, dim3(1024), 0, st, part, pl.nsplit, o);
+  } else {
+    if (pl.D == 64) hipLaunchKernelGGL((attend_combine_kernel<64, 1>), cgrid, dim3(64), 0, st, part, pl.nsplit, o);
+    else            hipLaunchKernelGGL((attend_combine_kernel<128, 1>), cgrid, dim3(128), 0, st, part, pl.nsplit, o);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace reattn

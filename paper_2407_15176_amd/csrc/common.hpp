@@ -1,0 +1,92 @@
+// Internal definitions shared by the HIP sources of libreattn (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+namespace reattn {
+
+// ---- launch plan: clamped partition (Eq. 1) + workspace layout --------------
+constexpr int kHistBits = 12;                 // first radix digit: top 12 bits of the ordered key
+constexpr int kHistBins = 1 << kHistBits;     // 4096 bins, 16 KiB of LDS per workgroup
+constexpr int kKeyShift = 32 - kHistBits;     // remaining 20 key bits are resolved among candidates
+constexpr int kChunk = 8192;                  // middle positions per select/emit workgroup (256 x 32 bits)
+constexpr int kChunkWords = kChunk / 32;
+
+struct Pivot {          // per (query, KV head) row, written by topk_pivot
+  uint32_t bin;         // bin holding the k-th largest score
+  uint32_t need;        // how many entries of that bin are selected (1..count)
+  uint32_t above;       // entries in higher bins (all selected)
+  uint32_t pad;
+};
+
+struct Plan {
+  int Hq, Hkv, D, G, dtype, M;
+  int64_t N, s_eff, l_eff, n_mid;
+  int k_eff, S;
+  int64_t ksh, kst, vsh, vst;     // strides in elements
+  float theta, scale;
+  // top-k geometry for one row of n_mid scores
+  int nchunks;                    // ceil(n_mid / kChunk)
+  int64_t nwords;                 // bitmap words per row (nchunks * kChunkWords)
+  // attention geometry
+  int gt, nsub;                   // heads per attention workgroup, workgroups per KV head
+  int split_len, nsplit;          // slots per attention workgroup, workgroups along S
+  // query tile of the prefill path and workspace offsets (bytes)
+  int m_tile;
+  size_t off_scores, off_hist, off_pivot, off_ncand, off_cand, off_bitmap, off_cnt,
+         off_idx, off_rope, off_part, total;
+};
+
+// ---- host-side launchers (one per .hip file) -------------------------------
+hipError_t launch_prep(const Plan& pl, int rows, uint32_t* hist, float2* rope, hipStream_t st);
+hipError_t launch_score_scan(const Plan& pl, const void* q, int n_query, const void* k_cache,
+                             float* scores, uint32_t* hist, hipStream_t st);
+hipError_t launch_score_gemm(const Plan& pl, const void* q, int q_first, int n_query,
+                             const void* k_cache, float* scores, void* q_split, hipStream_t st);
+hipError_t launch_topk(const Plan& pl, int rows, const float* scores, bool hist_ready,
+                       uint32_t* hist, Pivot* pivot, uint32_t* ncand, int32_t* cand,
+                       uint32_t* bitmap, uint32_t* cnt, int32_t* idx, hipStream_t st);
+hipError_t launch_gather_rope(const Plan& pl, const void* k_cache, const void* v_cache,
+                              const int32_t* idx, float* k_sel, void* v_sel, hipStream_t st);
+hipError_t launch_attend(const Plan& pl, bool fused, const void* q, int q_first, int n_query,
+                         const void* k_src, const void* v_src, const int32_t* idx,
+                         const float2* rope, float* part, float* out, hipStream_t st);
+
+// ---- device helpers ---------------------------------------------------------
+#ifdef __HIPCC__
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+// Order-preserving image of an fp32 score: larger float <=> larger key.  -0 maps to +0's key.
+__device__ __forceinline__ uint32_t score_key(float x) {
+  uint32_t u = __float_as_uint(x);
+  if (u == 0x80000000u) u = 0u;
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+// Sum over a group of 2^k adjacent lanes with DPP row operations (no LDS traffic).
+template <int CTRL>
+__device__ __forceinline__ float dpp_add(float v) {
+  int moved = __builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true);
+  return v + __int_as_float(moved);
+}
+// quad_perm [1,0,3,2] = 0xB1, quad_perm [2,3,0,1] = 0x4E, row_half_mirror = 0x141, row_mirror = 0x140
+template <int LANES>
+__device__ __forceinline__ float group_sum(float v) {
+  static_assert(LANES == 4 || LANES == 8 || LANES == 16 || LANES == 32, "group size");
+  v = dpp_add<0xB1>(v);
+  v = dpp_add<0x4E>(v);
+  if (LANES >= 8) v = dpp_add<0x141>(v);
+  if (LANES >= 16) v = dpp_add<0x140>(v);
+  if (LANES >= 32) v += __shfl_xor(v, 16, 64);
+  return v;
+}
+
+#endif  // __HIPCC__
+}  // namespace reattn

@@ -1,0 +1,123 @@
+// Sequential positional embedding after selection (paper Eq. 3, "PE", and the
+// remark that the cached keys carry no positional information): slot r of the
+// concatenation [global, select, local] is rotary-encoded at position r.
+// Pairing (c, c + D/2), angle r * theta^(-2c/D), as in the LLaMA family.
+//
+//   prep         clears the top-k histograms and fills the (cos, sin) table
+//                [S][D/2] used by the fused attention kernel.  Angles are formed in
+//                fp64 so that the fp32 table entries are correctly rounded even at
+//                position 131071, where an fp32 product r*w is off by ~1e-2 rad.
+//   gather_rope  materialised form of the concatenation: K rows rotated into an
+//                fp32 buffer, V rows copied.
+#include "common.hpp"
+
+namespace reattn {
+namespace {
+
+__global__ __launch_bounds__(256) void prep_kernel(uint32_t* hist, int64_t n_hist,
+                                                   float2* rope, int S, int half, int D,
+                                                   double log2_theta) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n_hist) { hist[i] = 0u; return; }
+  const int64_t j = i - n_hist;
+  if (rope && j < (int64_t)S * half) {
+    const int r = (int)(j / half), c = (int)(j % half);
+    const double w = exp2(-2.0 * (double)c / (double)D * log2_theta);
+    double sn, cs;
+    sincos((double)r * w, &sn, &cs);
+    rope[j] = make_float2((float)cs, (float)sn);
+  }
+}
+
+struct GatherArgs {
+  const void* k; const void* v; const int32_t* idx; float* k_sel; void* v_sel;
+  int64_t ksh, kst, vsh, vst, N;
+  int Hkv, M, S, s_eff, k_eff, l_eff;
+  double log2_theta;
+};
+
+// One 16-lane group per (query, KV head, slot).  Lane `sub` owns channels
+// [sub*E, sub*E+E) and their partners D/2 higher, so a rotation never leaves the lane.
+template <typename T, int D>
+__global__ __launch_bounds__(256) void gather_rope_kernel(GatherArgs a) {
+  constexpr int E = D / 32;                       // channels per lane per half
+  const int sub = threadIdx.x & 15;
+  const int64_t slot_id = (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);
+  const int64_t total = (int64_t)a.M * a.Hkv * a.S;
+  if (slot_id >= total) return;
+  const int r = (int)(slot_id % a.S);
+  const int h = (int)((slot_id / a.S) % a.Hkv);
+  const int qi = (int)(slot_id / ((int64_t)a.S * a.Hkv));
+  const int visible = a.S - (a.M - 1 - qi);       // causal cut inside the local part
+  float* ko = a.k_sel + slot_id * D;
+  T* vo = (T*)a.v_sel + slot_id * D;
+  const int c0 = sub * E;
+  if (r >= visible) {
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+      ko[c0 + e] = 0.f; ko[D / 2 + c0 + e] = 0.f;
+      vo[c0 + e] = T(0); vo[D / 2 + c0 + e] = T(0);
+    }
+    return;
+  }
+  int64_t tok;
+  if (r < a.s_eff) tok = r;
+  else if (r < a.s_eff + a.k_eff) tok = a.idx[((int64_t)qi * a.Hkv + h) * a.k_eff + (r - a.s_eff)];
+  else tok = a.N - a.l_eff + (r - a.s_eff - a.k_eff);
+  const T* kr = (const T*)a.k + (int64_t)h * a.ksh + tok * a.kst;
+  const T* vr = (const T*)a.v + (int64_t)h * a.vsh + tok * a.vst;
+#pragma unroll
+  for (int e = 0; e < E; ++e) {
+    const int c = c0 + e;
+    float lo, hi;
+    if (sizeof(T) == 2) {
+      lo = __uint_as_float(((uint32_t)((const uint16_t*)kr)[c]) << 16);
+      hi = __uint_as_float(((uint32_t)((const uint16_t*)kr)[c + D / 2]) << 16);
+    } else {
+      lo = ((const float*)kr)[c];
+      hi = ((const float*)kr)[c + D / 2];
+    }
+    const double w = exp2(-2.0 * (double)c / (double)D * a.log2_theta);
+    double sn, cs;
+    sincos((double)r * w, &sn, &cs);
+    ko[c] = (float)((double)lo * cs - (double)hi * sn);
+    ko[c + D / 2] = (float)((double)hi * cs + (double)lo * sn);
+    vo[c] = vr[c];
+    vo[c + D / 2] = vr[c + D / 2];
+  }
+}
+
+}  // namespace
+
+hipError_t launch_prep(const Plan& pl, int rows, uint32_t* hist, float2* rope, hipStream_t st) {
+  const int64_t n_hist = hist ? (int64_t)rows * kHistBins : 0;
+  const int64_t n_rope = rope ? (int64_t)pl.S * (pl.D / 2) : 0;
+  const int64_t n = n_hist + n_rope;
+  if (n == 0) return hipSuccess;
+  hipLaunchKernelGGL(prep_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st,
+                     hist, n_hist, rope, pl.S, pl.D / 2, pl.D, log2((double)pl.theta));
+  return hipGetLastError();
+}
+
+hipError_t launch_gather_rope(const Plan& pl, const void* k_cache, const void* v_cache,
+                              const int32_t* idx, float* k_sel, void* v_sel, hipStream_t st) {
+  GatherArgs a;
+  a.k = k_cache; a.v = v_cache; a.idx = idx; a.k_sel = k_sel; a.v_sel = v_sel;
+  a.ksh = pl.ksh; a.kst = pl.kst; a.vsh = pl.vsh; a.vst = pl.vst; a.N = pl.N;
+  a.Hkv = pl.Hkv; a.M = pl.M; a.S = pl.S;
+  a.s_eff = (int)pl.s_eff; a.k_eff = pl.k_eff; a.l_eff = (int)pl.l_eff;
+  a.log2_theta = log2((double)pl.theta);
+  const int64_t total = (int64_t)pl.M * pl.Hkv * pl.S;
+  if (total == 0) return hipSuccess;
+  const dim3 grid((unsigned)((total + 15) / 16));
+  if (pl.dtype == 0) {
+    if (pl.D == 64) hipLaunchKernelGGL((gather_rope_kernel<float, 64>), grid, dim3(256), 0, st, a);
+    else            hipLaunchKernelGGL((gather_rope_kernel<float, 128>), grid, dim3(256), 0, st, a);
+  } else {
+    if (pl.D == 64) hipLaunchKernelGGL((gather_rope_kernel<uint16_t, 64>), grid, dim3(256), 0, st, a);
+    else            hipLaunchKernelGGL((gather_rope_kernel<uint16_t, 128>), grid, dim3(256), 0, st, a);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace reattn

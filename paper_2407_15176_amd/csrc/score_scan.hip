@@ -1,0 +1,195 @@
+// Stage 1 for a decode step: position-agnostic scores of one query against the
+// whole middle of the key cache (paper Eq. 2, first line; appendix decoding
+// phase, the `score = query @ key[l_global:-l_local]^T` line), summed over the
+// heads of each GQA group.
+//
+// The kernel is a pure HBM stream: every key row (D elements, 128..512 bytes) is
+// read exactly once with 16-byte non-temporal loads, LANES_PER_ROW adjacent lanes
+// cover one row so each wave-wide load instruction fetches 1 KiB of consecutive
+// memory, and the partial dot products are reduced with DPP row operations (no
+// LDS round trip).  Because sum_g (q_g . k) = (sum_g q_g) . k, the group's query
+// rows are summed once in fp32 registers and each key costs one dot product.
+//
+// Launch shape: one 1024-thread workgroup per CU, each owning one contiguous
+// slice of one KV head.  Its scores (4 bytes per 256-byte row) are parked in LDS
+// (up to 128 KiB) while it streams and are written out in one burst at the end:
+// on MI355X any store issued in the middle of the stream costs ~15 % of the read
+// bandwidth (dirty-line write-backs interleave with the reads), whereas a burst
+// after the stream is nearly free.  The first radix digit of the top-k (a
+// 4096-bin histogram of the ordered score keys) is accumulated in LDS on the way
+// and flushed with one atomic per non-empty bin.
+#include "common.hpp"
+
+namespace reattn {
+namespace {
+
+struct ScanArgs {
+  const void* k;
+  const void* q;
+  float* scores;
+  uint32_t* hist;       // [rows][kHistBins] or nullptr
+  int64_t ksh, kst;     // key strides in elements
+  int64_t n_mid, first_tok;
+  int Hq, Hkv, G;
+  int rows_per_block;
+};
+
+template <typename T> struct Store;
+template <> struct Store<float> {
+  static constexpr int kPerLoad = 4;
+  static __device__ __forceinline__ void widen(const u32x4& d, float* x) {
+    x[0] = __uint_as_float(d.x); x[1] = __uint_as_float(d.y);
+    x[2] = __uint_as_float(d.z); x[3] = __uint_as_float(d.w);
+  }
+  static __device__ __forceinline__ float one(const void* p, int64_t i) { return ((const float*)p)[i]; }
+};
+template <> struct Store<uint16_t> {   // bf16 bit patterns
+  static constexpr int kPerLoad = 8;
+  static __device__ __forceinline__ void widen(const u32x4& d, float* x) {
+    x[0] = bf16_lo(d.x); x[1] = bf16_hi(d.x); x[2] = bf16_lo(d.y); x[3] = bf16_hi(d.y);
+    x[4] = bf16_lo(d.z); x[5] = bf16_hi(d.z); x[6] = bf16_lo(d.w); x[7] = bf16_hi(d.w);
+  }
+  static __device__ __forceinline__ float one(const void* p, int64_t i) {
+    return __uint_as_float(((uint32_t)((const uint16_t*)p)[i]) << 16);
+  }
+};
+
+constexpr int kScanThreads = 1024;
+constexpr int kScanMaxRows = 32768;            // rows of scores one workgroup parks in LDS (128 KiB)
+
+template <typename T, int D, int U, bool HIST>
+__global__ __launch_bounds__(kScanThreads) void score_scan_kernel(ScanArgs a) {
+  constexpr int EPL = Store<T>::kPerLoad;      // elements per 16-byte load
+  constexpr int LPR = D / EPL;                 // lanes per key row
+  constexpr int RPL = 64 / LPR;                // rows per wave-wide load
+  constexpr int RW = U * RPL;                  // rows per wave iteration
+  static_assert(U <= LPR, "one result slot per lane");
+
+  extern __shared__ float stage[];             // [rows_per_block] scores, then the histogram
+  uint32_t* lhist = (uint32_t*)(stage + a.rows_per_block);
+  if (HIST) {
+    for (int b = threadIdx.x; b < kHistBins; b += kScanThreads) lhist[b] = 0;
+    __syncthreads();
+  }
+
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  constexpr int nwaves = kScanThreads / 64;
+  const int sub = lane % LPR, grp = lane / LPR;
+  const int row_id = blockIdx.y;               // query * Hkv + kv head
+  const int h = row_id % a.Hkv, qi = row_id / a.Hkv;
+
+  // The group's query rows, summed in fp32: this lane's EPL channels.
+  float qv[EPL];
+#pragma unroll
+  for (int e = 0; e < EPL; ++e) qv[e] = 0.f;
+  for (int g = 0; g < a.G; ++g) {
+    const int64_t qoff = ((int64_t)qi * a.Hq + (int64_t)h * a.G + g) * D + sub * EPL;
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) qv[e] += Store<T>::one(a.q, qoff + e);
+  }
+
+  const int64_t blk_row0 = (int64_t)blockIdx.x * a.rows_per_block;
+  const int64_t left = a.n_mid - blk_row0;
+  const int nrows = left < a.rows_per_block ? (int)left : a.rows_per_block;
+  const int64_t row_bytes = a.kst * (int64_t)sizeof(T);
+  const char* kbase = (const char*)a.k +
+      ((int64_t)h * a.ksh + (a.first_tok + blk_row0) * a.kst) * (int64_t)sizeof(T) + sub * 16;
+
+  for (int t = wave * RW; t < nrows; t += nwaves * RW) {
+    u32x4 d[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      int r = t + u * RPL + grp;
+      r = r < nrows ? r : nrows - 1;           // tail rows re-read the last row; result dropped
+      d[u] = __builtin_nontemporal_load((const u32x4*)(kbase + (int64_t)r * row_bytes));
+    }
+    float mine = 0.f;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      float x[EPL];
+      Store<T>::widen(d[u], x);
+      float s = 0.f;
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) s = fmaf(x[e], qv[e], s);
+      s = group_sum<LPR>(s);
+      mine = (sub == u) ? s : mine;            // lane (grp, sub) keeps the result of load `sub`
+    }
+    const int r = t + sub * RPL + grp;
+    if (sub < U && r < nrows) {
+      stage[r] = mine;
+      if (HIST) atomicAdd(&lhist[score_key(mine) >> kKeyShift], 1u);
+    }
+  }
+
+  __syncthreads();
+  float* out = a.scores + (int64_t)row_id * a.n_mid + blk_row0;
+  for (int r = threadIdx.x; r < nrows; r += kScanThreads) out[r] = stage[r];
+  if (HIST) {
+    uint32_t* gh = a.hist + (int64_t)row_id * kHistBins;
+    for (int b = threadIdx.x; b < kHistBins; b += kScanThreads) {
+      const uint32_t c = lhist[b];
+      if (c) atomicAdd(&gh[b], c);
+    }
+  }
+}
+
+template <typename T, int D>
+hipError_t launch_t(const ScanArgs& a, dim3 grid, bool hist, hipStream_t st) {
+  constexpr int U = 8;
+  const size_t lds = (size_t)a.rows_per_block * 4 + (hist ? kHistBins * 4 : 0);
+  if (hist) {
+    auto kern = score_scan_kernel<T, D, U, true>;
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(kern, grid, dim3(kScanThreads), lds, st, a);
+  } else {
+    auto kern = score_scan_kernel<T, D, U, false>;
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(kern, grid, dim3(kScanThreads), lds, st, a);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace
+
+// Rows per workgroup: the whole job is cut into a multiple of the CU count of equal
+// slices (each within one KV head) so that every CU streams the same amount and the
+// bursts of score writes fall together at the end of each round.
+int scan_rows_per_block(int64_t n_mid, int64_t score_rows) {
+  static int n_cu = 0;
+  if (n_cu == 0) {
+    int dev = 0; hipDeviceProp_t pr;
+    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&pr, dev) == hipSuccess)
+      n_cu = pr.multiProcessorCount;
+    if (n_cu <= 0) n_cu = 256;
+  }
+  const int64_t total = n_mid * score_rows;
+  const int64_t rounds = (total + (int64_t)n_cu * kScanMaxRows - 1) / ((int64_t)n_cu * kScanMaxRows);
+  const int64_t wgs = rounds * n_cu;
+  const int64_t per_row = (wgs + score_rows - 1) / score_rows;      // workgroups per score row
+  int64_t rpb = (n_mid + per_row - 1) / per_row;
+  rpb = (rpb + 31) / 32 * 32;
+  if (rpb > kScanMaxRows) rpb = kScanMaxRows;
+  if (rpb < 32) rpb = 32;
+  return (int)rpb;
+}
+
+hipError_t launch_score_scan(const Plan& pl, const void* q, int n_query, const void* k_cache,
+                             float* scores, uint32_t* hist, hipStream_t st) {
+  if (pl.n_mid <= 0 || n_query <= 0) return hipSuccess;
+  ScanArgs a;
+  a.k = k_cache; a.q = q; a.scores = scores; a.hist = hist;
+  a.ksh = pl.ksh; a.kst = pl.kst; a.n_mid = pl.n_mid; a.first_tok = pl.s_eff;
+  a.Hq = pl.Hq; a.Hkv = pl.Hkv; a.G = pl.G;
+  a.rows_per_block = scan_rows_per_block(pl.n_mid, (int64_t)pl.Hkv * n_query);
+  dim3 grid((unsigned)((pl.n_mid + a.rows_per_block - 1) / a.rows_per_block),
+            (unsigned)(pl.Hkv * n_query));
+  const bool h = hist != nullptr;
+  if (pl.dtype == 0) return pl.D == 64 ? launch_t<float, 64>(a, grid, h, st)
+                                       : launch_t<float, 128>(a, grid, h, st);
+  return pl.D == 64 ? launch_t<uint16_t, 64>(a, grid, h, st)
+                    : launch_t<uint16_t, 128>(a, grid, h, st);
+}
+
+}  // namespace reattn

@@ -1,0 +1,130 @@
+"""C-ABI checks that need no GPU: the library loads, exports every symbol the
+header declares, and rejects bad arguments on the host before any launch."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2407_15176_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "reattn.h")
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(reattn_[a-z_]+)\s*\(", text)))
+
+
+def good(**kw):
+    base = dict(n_q_heads=32, n_kv_heads=8, head_dim=128, dtype=B.BF16, n_ctx=131072, n_query=1,
+                n_sink=4, n_local=4096, top_k=4096, rope_theta=500000.0, max_position=131072)
+    base.update(kw)
+    return B.Params(**base)
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_functions()
+    assert set(names) == set(B.EXPORTS)
+    lib = B.lib()
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_version_and_status_strings():
+    assert B.version() >= 100
+    seen = set()
+    for s in range(0, -9, -1):
+        msg = B.status_string(s)
+        assert msg and msg != "unknown status"
+        seen.add(msg)
+    assert len(seen) == 9
+    assert B.status_string(-99) == "unknown status"
+
+
+def test_scope_matches_eq1_on_the_five_configs():
+    from paper_2407_15176_amd import workloads as wl
+    want = {1: (15868, 256, 772), 2: (126972, 4096, 8196), 3: (1044476, 8192, 12292),
+            4: (258044, 4096, 8196), 5: (4190204, 8192, 12292)}
+    for cfg, w in wl.CONFIGS.items():
+        p = B.Params.from_workload(w)
+        assert B.validate(p) == B.OK
+        s, l, mid, k, S = B.scope(p)
+        assert (mid, k, S) == want[cfg]
+        assert (s, l) == (4, w.n_local)
+        assert (mid, k, S) == (w.n_mid, w.k_eff, w.scope)
+        assert B.workspace_bytes(p) > 0
+
+
+def test_scope_clamping():
+    assert B.scope(good(n_ctx=100, n_local=16, top_k=10, max_position=0)) == (4, 16, 80, 10, 30)
+    assert B.scope(good(n_ctx=100, n_local=16, top_k=500, max_position=0)) == (4, 16, 80, 80, 100)
+    assert B.scope(good(n_ctx=10, n_local=16, top_k=10, max_position=0)) == (4, 6, 0, 0, 10)
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(n_q_heads=30), B.ERR_SHAPE),
+    (dict(n_kv_heads=0), B.ERR_SHAPE),
+    (dict(head_dim=96), B.ERR_SHAPE),
+    (dict(n_q_heads=34, n_kv_heads=2), B.ERR_SHAPE),          # G = 17
+    (dict(dtype=7), B.ERR_DTYPE),
+    (dict(agg=3), B.ERR_DTYPE),
+    (dict(n_ctx=0), B.ERR_RANGE),
+    (dict(n_ctx=2 ** 31), B.ERR_RANGE),
+    (dict(n_query=0), B.ERR_RANGE),
+    (dict(n_query=5000), B.ERR_RANGE),                        # M > n_local
+    (dict(n_sink=-1), B.ERR_RANGE),
+    (dict(n_local=0), B.ERR_RANGE),
+    (dict(top_k=-1), B.ERR_RANGE),
+    (dict(rope_theta=1.0), B.ERR_RANGE),
+    (dict(rope_theta=float("nan")), B.ERR_RANGE),
+    (dict(softmax_scale=-0.5), B.ERR_RANGE),
+    (dict(max_position=8192), B.ERR_WINDOW),                  # S = 8196
+    (dict(k_stride_tok=64, k_stride_head=64 * 131072), B.ERR_SHAPE),   # row shorter than D
+    (dict(k_stride_tok=132, k_stride_head=132 * 131072), B.ERR_ALIGN), # 264-byte rows
+    (dict(v_stride_tok=128, v_stride_head=0), B.ERR_SHAPE),
+])
+def test_validate_rejects(kw, status):
+    p = good(**kw)
+    assert B.validate(p) == status
+    assert B.workspace_bytes(p) == 0
+
+
+def test_n_ctx_3_is_valid_only_with_a_local_part():
+    # N = 3 < sink: the sink takes everything, no local token remains for the query
+    assert B.validate(good(n_ctx=3, n_local=16, top_k=10, max_position=0)) == B.ERR_RANGE
+    assert B.validate(good(n_ctx=3, n_sink=2, n_local=16, top_k=10, max_position=0)) == B.OK
+
+
+def test_null_and_workspace_errors_before_any_launch():
+    lib = B.lib()
+    p = good(n_ctx=8192, n_local=256, top_k=64)
+    cp = p.c()
+    fake = C.c_void_p(0x1000)       # never dereferenced: the checks below fire first
+    need = B.workspace_bytes(p)
+    assert lib.reattn_validate(None) == B.ERR_NULL
+    assert lib.reattn_score(C.byref(cp), None, fake, fake, None) == B.ERR_NULL
+    assert lib.reattn_topk(C.byref(cp), None, fake, fake, need, None) == B.ERR_NULL
+    assert lib.reattn_topk(C.byref(cp), fake, fake, None, need, None) == B.ERR_WORKSPACE
+    assert lib.reattn_topk(C.byref(cp), fake, fake, fake, need - 1, None) == B.ERR_WORKSPACE
+    assert lib.reattn_topk(C.byref(cp), fake, fake, C.c_void_p(0x1010), need, None) == B.ERR_ALIGN
+    assert lib.reattn_gather_rope(C.byref(cp), fake, fake, None, fake, fake, None) == B.ERR_NULL
+    assert lib.reattn_attend(C.byref(cp), fake, None, fake, fake, fake, need, None) == B.ERR_NULL
+    assert lib.reattn_decode_step(C.byref(cp), fake, fake, None, None, fake, fake, need, None) == B.ERR_NULL
+    assert lib.reattn_decode_step(C.byref(cp), fake, fake, fake, None, fake, fake, 16, None) == B.ERR_WORKSPACE
+    assert lib.reattn_decode_step(C.byref(cp), C.c_void_p(0x1004), fake, fake, None, fake, fake, need,
+                                  None) == B.ERR_ALIGN
+    pm = good(n_ctx=8192, n_local=256, top_k=64, n_query=4).c()
+    assert lib.reattn_decode_step(C.byref(pm), fake, fake, fake, None, fake, fake, 1 << 40, None) == B.ERR_RANGE
+    assert lib.reattn_prefill_chunk(C.byref(pm), fake, fake, fake, None, None, fake, 1 << 40, None) == B.ERR_NULL
+
+
+def test_workspace_is_modest_for_decode():
+    from paper_2407_15176_amd import workloads as wl
+    for cfg in (1, 2, 3, 5):
+        w = wl.CONFIGS[cfg]
+        need = B.workspace_bytes(B.Params.from_workload(w))
+        # scores + candidate list + bitmap: about 8.2 bytes per middle token per KV head
+        assert need < 10 * w.n_mid * w.n_kv_heads + (8 << 20)
