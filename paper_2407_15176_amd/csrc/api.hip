@@ -47,6 +47,7 @@ int make_plan(const reattn_params* p, Plan* out) {
   pl.kst = kdef ? pl.D : p->k_stride_tok;  pl.ksh = kdef ? pl.N * pl.D : p->k_stride_head;
   pl.vst = vdef ? pl.D : p->v_stride_tok;  pl.vsh = vdef ? pl.N * pl.D : p->v_stride_head;
   if (pl.kst < pl.D || pl.vst < pl.D || pl.ksh < 0 || pl.vsh < 0) return REATTN_ERR_SHAPE;
+  if (pl.Hkv > 1 && (pl.ksh < pl.D || pl.vsh < pl.D)) return REATTN_ERR_SHAPE;   // heads must not alias
   if ((pl.kst * eb) % 16 || (pl.ksh * eb) % 16 || (pl.vst * eb) % 16 || (pl.vsh * eb) % 16)
     return REATTN_ERR_ALIGN;
 
@@ -72,8 +73,9 @@ int make_plan(const reattn_params* p, Plan* out) {
   }
 
   // query tile of the prefill path: per-tile scratch stays near 4 GiB
-  const size_t per_query = (size_t)pl.Hkv * ((size_t)pl.n_mid * 8 + (size_t)kHistBins * 4 +
-                                             (size_t)pl.nwords * 4 + (size_t)pl.nchunks * 4 + 64);
+  const size_t per_query = (size_t)pl.Hkv * ((size_t)pl.n_mid * 4 + (size_t)pl.nchunks * kChunk * 4 +
+                                             (size_t)kHistBins * 4 + (size_t)pl.nwords * 4 +
+                                             (size_t)pl.nchunks * 12 + 64);
   int64_t mt = (int64_t)(((size_t)4 << 30) / (per_query ? per_query : 1));
   if (mt < 1) mt = 1;
   if (mt > pl.M) mt = pl.M;
@@ -85,13 +87,13 @@ int make_plan(const reattn_params* p, Plan* out) {
   size_t off = 0;
   pl.off_scores = off; off += up(rows * (size_t)pl.n_mid * 4);
   pl.off_hist = off;   off += up(rows * kHistBins * 4);
-  pl.off_pivot = off;  off += up(rows * sizeof(Pivot));
-  pl.off_ncand = off;  off += up(rows * 4);
-  pl.off_cand = off;   off += up(rows * (size_t)pl.n_mid * 4);
+  pl.off_pfx = off;    off += up(rows * (size_t)pl.nchunks * 4);
+  pl.off_ncand = off;  off += up(rows * (size_t)pl.nchunks * 4);
+  pl.off_cand = off;   off += up(rows * (size_t)pl.nchunks * kChunk * 4);
   pl.off_bitmap = off; off += up(rows * (size_t)pl.nwords * 4);
   pl.off_cnt = off;    off += up(rows * (size_t)pl.nchunks * 4);
   pl.off_idx = off;    off += up((size_t)pl.M * pl.Hkv * (size_t)pl.k_eff * 4);
-  pl.off_rope = off;   off += up((size_t)pl.S * (pl.D / 2) * sizeof(float2));
+  pl.off_rope = off;   off += up((size_t)(rope_rows_hi(pl.S) + kRopeLo) * (pl.D / 2) * sizeof(float2));
   pl.off_part = off;   off += up((size_t)pl.M * pl.Hq * (size_t)pl.nsplit * (pl.D + 2) * 4);
   pl.total = off ? off : kAlign;
   *out = pl;
@@ -99,7 +101,7 @@ int make_plan(const reattn_params* p, Plan* out) {
 }
 
 struct Ws {
-  float* scores; uint32_t* hist; Pivot* pivot; uint32_t* ncand; int32_t* cand;
+  float* scores; uint32_t* hist; uint32_t* pfx; uint32_t* ncand; int32_t* cand;
   uint32_t* bitmap; uint32_t* cnt; int32_t* idx; float2* rope; float* part;
 };
 
@@ -108,7 +110,7 @@ int bind_ws(const Plan& pl, void* ws, size_t ws_bytes, Ws* w) {
   if ((uintptr_t)ws % kAlign) return REATTN_ERR_ALIGN;
   char* b = (char*)ws;
   w->scores = (float*)(b + pl.off_scores);   w->hist = (uint32_t*)(b + pl.off_hist);
-  w->pivot = (Pivot*)(b + pl.off_pivot);     w->ncand = (uint32_t*)(b + pl.off_ncand);
+  w->pfx = (uint32_t*)(b + pl.off_pfx);     w->ncand = (uint32_t*)(b + pl.off_ncand);
   w->cand = (int32_t*)(b + pl.off_cand);     w->bitmap = (uint32_t*)(b + pl.off_bitmap);
   w->cnt = (uint32_t*)(b + pl.off_cnt);      w->idx = (int32_t*)(b + pl.off_idx);
   w->rope = (float2*)(b + pl.off_rope);      w->part = (float*)(b + pl.off_part);
@@ -132,7 +134,7 @@ int select_tile(const Plan& pl, const Ws& w, const void* q, int q0, int nq, cons
   rc = hip_rc(launch_score_scan(pl, qt, nq, k_cache, w.scores, w.hist, st));
   mark(ev, 2, st);
   if (rc) return rc;
-  rc = hip_rc(launch_topk(pl, rows, w.scores, true, w.hist, w.pivot, w.ncand, w.cand, w.bitmap,
+  rc = hip_rc(launch_topk(pl, rows, w.scores, true, w.hist, w.pfx, w.ncand, w.cand, w.bitmap,
                           w.cnt, idx_all + (size_t)q0 * pl.Hkv * pl.k_eff, st));
   mark(ev, 3, st);
   return rc;
@@ -243,7 +245,7 @@ int reattn_topk(const reattn_params* p, const float* scores, int32_t* idx, void*
     rc = hip_rc(launch_prep(pl, rows, w.hist, nullptr, st));
     if (rc) return rc;
     rc = hip_rc(launch_topk(pl, rows, scores + (size_t)q0 * pl.Hkv * pl.n_mid, false, w.hist,
-                            w.pivot, w.ncand, w.cand, w.bitmap, w.cnt,
+                            w.pfx, w.ncand, w.cand, w.bitmap, w.cnt,
                             idx + (size_t)q0 * pl.Hkv * pl.k_eff, st));
     if (rc) return rc;
   }

@@ -78,10 +78,23 @@ __global__ __launch_bounds__(256) void attend_kernel(AttendArgs a) {
   const int visible = a.S - (a.M - 1 - qi);         // slots this query may see; its own key is the last
   const int c0 = sub * E;
 
+  // (cos, sin) of position r for this lane's E channel pairs: product of the two table levels
+  const int n_hi = rope_rows_hi(a.S);
+  auto rope_at = [&](int r, float2* cs) {
+    const float2* hi = a.rope + (int64_t)(r / kRopeLo) * (D / 2) + c0;
+    const float2* lo = a.rope + (int64_t)(n_hi + r % kRopeLo) * (D / 2) + c0;
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+      const float2 x = hi[e], y = lo[e];
+      cs[e] = make_float2(x.x * y.x - x.y * y.y, x.y * y.x + x.x * y.y);
+    }
+  };
+
   // query rows of this group, rotary-encoded at the slot of the query's own key
   float qlo[GT][E], qhi[GT][E];
   {
-    const float2* rp = a.rope + (int64_t)(visible - 1) * (D / 2) + c0;
+    float2 rp[E];
+    rope_at(visible - 1, rp);
 #pragma unroll
     for (int g = 0; g < GT; ++g) {
       const int gg = (g0 + g < a.G) ? g0 + g : a.G - 1;
@@ -162,7 +175,8 @@ __global__ __launch_bounds__(256) void attend_kernel(AttendArgs a) {
     if (FUSED) {
 #pragma unroll
       for (int u = 0; u < UNR; ++u) {
-        const float2* rp = a.rope + (int64_t)rr[u] * (D / 2) + c0;
+        float2 rp[E];
+        rope_at(rr[u], rp);
 #pragma unroll
         for (int e = 0; e < E; ++e) {
           const float2 cs = rp[e];

@@ -13,13 +13,8 @@ constexpr int kHistBins = 1 << kHistBits;     // 4096 bins, 16 KiB of LDS per wo
 constexpr int kKeyShift = 32 - kHistBits;     // remaining 20 key bits are resolved among candidates
 constexpr int kChunk = 8192;                  // middle positions per select/emit workgroup (256 x 32 bits)
 constexpr int kChunkWords = kChunk / 32;
-
-struct Pivot {          // per (query, KV head) row, written by topk_pivot
-  uint32_t bin;         // bin holding the k-th largest score
-  uint32_t need;        // how many entries of that bin are selected (1..count)
-  uint32_t above;       // entries in higher bins (all selected)
-  uint32_t pad;
-};
+constexpr int kRopeLo = 128;                  // positions covered by the low rotary table
+__host__ __device__ inline int rope_rows_hi(int S) { return (S + kRopeLo - 1) / kRopeLo; }
 
 struct Plan {
   int Hq, Hkv, D, G, dtype, M;
@@ -35,7 +30,7 @@ struct Plan {
   int split_len, nsplit;          // slots per attention workgroup, workgroups along S
   // query tile of the prefill path and workspace offsets (bytes)
   int m_tile;
-  size_t off_scores, off_hist, off_pivot, off_ncand, off_cand, off_bitmap, off_cnt,
+  size_t off_scores, off_hist, off_pfx, off_ncand, off_cand, off_bitmap, off_cnt,
          off_idx, off_rope, off_part, total;
 };
 
@@ -46,7 +41,7 @@ hipError_t launch_score_scan(const Plan& pl, const void* q, int n_query, const v
 hipError_t launch_score_gemm(const Plan& pl, const void* q, int q_first, int n_query,
                              const void* k_cache, float* scores, void* q_split, hipStream_t st);
 hipError_t launch_topk(const Plan& pl, int rows, const float* scores, bool hist_ready,
-                       uint32_t* hist, Pivot* pivot, uint32_t* ncand, int32_t* cand,
+                       uint32_t* hist, uint32_t* pfx, uint32_t* ncand, int32_t* cand,
                        uint32_t* bitmap, uint32_t* cnt, int32_t* idx, hipStream_t st);
 hipError_t launch_gather_rope(const Plan& pl, const void* k_cache, const void* v_cache,
                               const int32_t* idx, float* k_sel, void* v_sel, hipStream_t st);

@@ -3,10 +3,13 @@
 // concatenation [global, select, local] is rotary-encoded at position r.
 // Pairing (c, c + D/2), angle r * theta^(-2c/D), as in the LLaMA family.
 //
-//   prep         clears the top-k histograms and fills the (cos, sin) table
-//                [S][D/2] used by the fused attention kernel.  Angles are formed in
-//                fp64 so that the fp32 table entries are correctly rounded even at
-//                position 131071, where an fp32 product r*w is off by ~1e-2 rad.
+//   prep         clears the top-k histograms and fills the two-level
+//                (cos, sin) table used by the attention kernel: rows [0, n_hi) hold
+//                the angles of positions 128*a, rows [n_hi, n_hi+128) those of
+//                positions b < 128; position r = 128a + b is their complex product.
+//                Angles are formed in fp64 so that the fp32 entries are correctly
+//                rounded even at position 131071, where an fp32 product r*w is off
+//                by ~1e-2 rad; the table has (S/128 + 128) rows instead of S.
 //   gather_rope  materialised form of the concatenation: K rows rotated into an
 //                fp32 buffer, V rows copied.
 #include "common.hpp"
@@ -20,8 +23,10 @@ __global__ __launch_bounds__(256) void prep_kernel(uint32_t* hist, int64_t n_his
   const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (i < n_hist) { hist[i] = 0u; return; }
   const int64_t j = i - n_hist;
-  if (rope && j < (int64_t)S * half) {
-    const int r = (int)(j / half), c = (int)(j % half);
+  const int n_hi = rope_rows_hi(S);
+  if (rope && j < (int64_t)(n_hi + kRopeLo) * half) {
+    const int row = (int)(j / half), c = (int)(j % half);
+    const int r = row < n_hi ? row * kRopeLo : row - n_hi;
     const double w = exp2(-2.0 * (double)c / (double)D * log2_theta);
     double sn, cs;
     sincos((double)r * w, &sn, &cs);
@@ -90,8 +95,9 @@ __global__ __launch_bounds__(256) void gather_rope_kernel(GatherArgs a) {
 }  // namespace
 
 hipError_t launch_prep(const Plan& pl, int rows, uint32_t* hist, float2* rope, hipStream_t st) {
-  const int64_t n_hist = hist ? (int64_t)rows * kHistBins : 0;
-  const int64_t n_rope = rope ? (int64_t)pl.S * (pl.D / 2) : 0;
+  if (!hist) rows = 0;
+  const int64_t n_hist = (int64_t)rows * kHistBins;
+  const int64_t n_rope = rope ? (int64_t)(rope_rows_hi(pl.S) + kRopeLo) * (pl.D / 2) : 0;
   const int64_t n = n_hist + n_rope;
   if (n == 0) return hipSuccess;
   hipLaunchKernelGGL(prep_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st,

@@ -8,11 +8,12 @@
 // is a radix select on the order-preserving uint32 image of the scores:
 //   hist    (optional; the decode scan produces it on the fly) 4096-bin histogram
 //           of the top 12 key bits, built in LDS per workgroup;
-//   pivot   one workgroup per row finds the bin that holds the k-th largest key;
+//   pivot   (a device function run by every select/refine workgroup, 16 KiB of L2
+//           reads) finds the bin that holds the k-th largest key;
 //   select  ONE pass over the scores: entries in higher bins are final and go
 //           straight into a per-row bitmap via wave ballots (no atomics); entries
-//           in the pivot bin (typically < 1 % of the row) are appended to a
-//           candidate list;
+//           in the pivot bin (typically < 1 % of the row) go to per-chunk segments
+//           of a candidate array;
 //   refine  one workgroup per row resolves the remaining 20 key bits and the index
 //           tie-break among the candidates with LDS histograms (11-bit digits over
 //           the 52-bit composite (key_low, ~index)) and marks the winners;
@@ -95,53 +96,39 @@ __global__ __launch_bounds__(256) void topk_hist_kernel(const float* __restrict_
   }
 }
 
-// ---- pivot: which bin holds the k-th largest key --------------------------
-__global__ __launch_bounds__(1024) void topk_pivot_kernel(const uint32_t* hist, uint32_t k,
-                                                          Pivot* pivot, uint32_t* ncand) {
-  __shared__ uint32_t sh[40];
-  const int row = blockIdx.x;
-  uint32_t bin, above;
-  find_kth_bin<1024, kHistBins>(hist + (int64_t)row * kHistBins, k, sh, bin, above);
-  if (threadIdx.x == 0) {
-    Pivot pv; pv.bin = bin; pv.need = k - above; pv.above = above; pv.pad = 0;
-    pivot[row] = pv;
-    ncand[row] = 0;
-  }
-}
-
 // ---- select: one pass over the scores --------------------------------------
 // A workgroup owns kChunk consecutive positions; each wave 2048 of them, 64 per
 // iteration.  Lane `it` keeps the two ballots of iteration `it` (final entries,
 // pivot-bin entries), so after the loop the wave holds its slice of the bitmap in
-// registers.  Candidates get their place in the row's list from ONE global atomic
-// per workgroup (an atomic per wave iteration would serialise thousands of
-// returning atomics on a single address).
+// registers.  Candidates go to the chunk's own segment of the candidate array and the
+// chunk's count is a plain store: no global atomics (returning atomics on one address
+// serialise at ~135 ns each on this chip, which made a shared list the bottleneck).
 __global__ __launch_bounds__(256) void topk_select_kernel(
-    const float* __restrict__ scores, int64_t n_mid, const Pivot* __restrict__ pivot,
+    const float* __restrict__ scores, int64_t n_mid, const uint32_t* __restrict__ hist, uint32_t k,
     uint32_t* ncand, int32_t* cand, uint32_t* bitmap, int64_t nwords, uint32_t* cnt, int nchunks) {
-  __shared__ uint32_t w_take[4], w_cand[4], s_base;
+  __shared__ uint32_t w_take[4], w_cand[4], sh[40];
   const int row = blockIdx.y, c = blockIdx.x;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const uint32_t pbin = pivot[row].bin;
   const float* sc = scores + (int64_t)row * n_mid;
   const int64_t wbase = (int64_t)c * kChunk + wave * (kChunk / 4);
+  // all 32 loads of this lane go out before anything waits on them
+  float v[32];
+#pragma unroll
+  for (int j = 0; j < 32; ++j) {
+    const int64_t pos = wbase + j * 64 + lane;
+    v[j] = pos < n_mid ? sc[pos] : 0.f;
+  }
+  uint32_t pbin, above;
+  find_kth_bin<256, kHistBins>(hist + (int64_t)row * kHistBins, k, sh, pbin, above);
   uint64_t take_mask = 0, cand_mask = 0;
-  for (int it0 = 0; it0 < 32; it0 += 8) {
-    float v[8];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      const int64_t pos = wbase + (it0 + j) * 64 + lane;
-      v[j] = pos < n_mid ? sc[pos] : 0.f;
-    }
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      const int64_t pos = wbase + (it0 + j) * 64 + lane;
-      const bool valid = pos < n_mid;
-      const uint32_t bin = score_key(v[j]) >> kKeyShift;
-      const uint64_t mt = __ballot(valid && bin > pbin);
-      const uint64_t mc = __ballot(valid && bin == pbin);
-      if (lane == it0 + j) { take_mask = mt; cand_mask = mc; }
-    }
+  for (int j = 0; j < 32; ++j) {
+    const int64_t pos = wbase + j * 64 + lane;
+    const bool valid = pos < n_mid;
+    const uint32_t bin = score_key(v[j]) >> kKeyShift;
+    const uint64_t mt = __ballot(valid && bin > pbin);
+    const uint64_t mc = __ballot(valid && bin == pbin);
+    if (lane == j) { take_mask = mt; cand_mask = mc; }
   }
   // lanes 0..31 hold the masks of iterations 0..31 (lanes 32..63 hold zeros)
   const uint32_t n_take = (uint32_t)__popcll(take_mask);
@@ -159,14 +146,12 @@ __global__ __launch_bounds__(256) void topk_select_kernel(
   __syncthreads();
   if (threadIdx.x == 0) {
     cnt[(int64_t)row * nchunks + c] = w_take[0] + w_take[1] + w_take[2] + w_take[3];
-    const uint32_t total = w_cand[0] + w_cand[1] + w_cand[2] + w_cand[3];
-    s_base = total ? atomicAdd(&ncand[row], total) : 0u;
+    ncand[(int64_t)row * nchunks + c] = w_cand[0] + w_cand[1] + w_cand[2] + w_cand[3];
   }
-  __syncthreads();
   if (cand_mask) {
-    uint32_t at = s_base + cincl - n_cand;
+    uint32_t at = cincl - n_cand;
     for (int w = 0; w < wave; ++w) at += w_cand[w];
-    int32_t* my_cand = cand + (int64_t)row * n_mid;
+    int32_t* my_cand = cand + ((int64_t)row * nchunks + c) * kChunk;
     const int32_t first = (int32_t)(wbase + lane * 64);
     uint64_t m = cand_mask;
     while (m) {
@@ -183,17 +168,54 @@ __device__ __forceinline__ uint64_t composite(const float* sc, int32_t pos) {
   return (low << 32) | (uint64_t)(0xffffffffu - (uint32_t)pos);   // lower index = larger value
 }
 
+constexpr int kRefineCache = 12288;   // candidates whose composite keys are kept in LDS (96 KiB)
+constexpr int kRefinePfx = 4096;      // chunks whose candidate offsets are kept in LDS
+constexpr size_t kRefineLds = 2048 * 4 + kRefinePfx * 4 + (size_t)kRefineCache * 8;
+
 __global__ __launch_bounds__(1024) void topk_refine_kernel(
-    const float* __restrict__ scores, int64_t n_mid, const Pivot* __restrict__ pivot,
-    const uint32_t* __restrict__ ncand, const int32_t* __restrict__ cand,
+    const float* __restrict__ scores, int64_t n_mid, const uint32_t* __restrict__ hist, uint32_t k,
+    const uint32_t* __restrict__ ncand, const int32_t* __restrict__ cand, uint32_t* gpfx,
     uint32_t* bitmap, int64_t nwords, uint32_t* cnt, int nchunks) {
-  __shared__ uint32_t bins[2048];
+  extern __shared__ uint64_t refine_lds[];
+  uint64_t* cached = refine_lds;                              // [kRefineCache]
+  uint32_t* bins = (uint32_t*)(refine_lds + kRefineCache);    // [2048]
+  uint32_t* lpfx = bins + 2048;                               // [kRefinePfx]
   __shared__ uint32_t sh[40];
   const int row = blockIdx.x;
-  const uint32_t n = ncand[row];
-  const uint32_t need = pivot[row].need;
   const float* sc = scores + (int64_t)row * n_mid;
-  const int32_t* my_cand = cand + (int64_t)row * n_mid;
+  const int32_t* my_cand = cand + (int64_t)row * nchunks * kChunk;
+  const uint32_t* my_n = ncand + (int64_t)row * nchunks;
+  uint32_t pbin, above;
+  find_kth_bin<1024, kHistBins>(hist + (int64_t)row * kHistBins, k, sh, pbin, above);
+  const uint32_t need = k - above;               // entries of the pivot bin that are selected
+
+  // flatten the per-chunk candidate segments: exclusive prefix of their counts
+  uint32_t* pfx = nchunks <= kRefinePfx ? lpfx : gpfx + (int64_t)row * nchunks;
+  uint32_t n = 0;
+  for (int c0 = 0; c0 < nchunks; c0 += 1024) {
+    const int c = c0 + threadIdx.x;
+    const uint32_t x = c < nchunks ? my_n[c] : 0u;
+    uint32_t tot;
+    const uint32_t incl = block_scan_incl<1024>(x, sh, tot);
+    if (c < nchunks) pfx[c] = n + incl - x;
+    n += tot;
+  }
+  __threadfence_block();
+  __syncthreads();
+  auto position = [&](uint32_t f) -> int32_t {   // f-th candidate of the row
+    int lo = 0, hi = nchunks - 1;                // largest chunk with pfx[chunk] <= f
+    while (lo < hi) {
+      const int mid = (lo + hi + 1) >> 1;
+      if (pfx[mid] <= f) lo = mid; else hi = mid - 1;
+    }
+    return my_cand[(int64_t)lo * kChunk + (f - pfx[lo])];
+  };
+  for (uint32_t i = threadIdx.x; i < n && i < kRefineCache; i += 1024)
+    cached[i] = composite(sc, position(i));
+  __syncthreads();
+  auto comp = [&](uint32_t i) -> uint64_t {
+    return i < kRefineCache ? cached[i] : composite(sc, position(i));
+  };
 
   int shift = 0;
   uint64_t prefix = 0;                           // select comp >> shift >= prefix
@@ -206,15 +228,15 @@ __global__ __launch_bounds__(1024) void topk_refine_kernel(
       for (int b = threadIdx.x; b < 2048; b += 1024) bins[b] = 0;
       __syncthreads();
       for (uint32_t i = threadIdx.x; i < n; i += 1024) {
-        const uint64_t cv = composite(sc, my_cand[i]);
+        const uint64_t cv = comp(i);
         if ((cv >> (shift + w)) == prefix)
           atomicAdd(&bins[(uint32_t)(cv >> shift) & ((1u << w) - 1u)], 1u);
       }
       __syncthreads();
-      uint32_t d, above;
-      find_kth_bin<1024, 2048>(bins, remaining, sh, d, above);
+      uint32_t d, ab;
+      find_kth_bin<1024, 2048>(bins, remaining, sh, d, ab);
       const uint32_t in_bin = bins[d];
-      remaining -= above;
+      remaining -= ab;
       prefix = (prefix << w) | d;
       __syncthreads();
       if (in_bin == remaining) break;            // every entry sharing this prefix is selected
@@ -228,9 +250,10 @@ __global__ __launch_bounds__(1024) void topk_refine_kernel(
     for (int b = threadIdx.x; b < nc; b += 1024) bins[b] = 0;
     __syncthreads();
     for (uint32_t i = threadIdx.x; i < n; i += 1024) {
-      const int32_t pos = my_cand[i];
+      const uint64_t cv = comp(i);
+      const int32_t pos = (int32_t)(0xffffffffu - (uint32_t)cv);
       const int ch = pos / kChunk - c0;
-      if (ch >= 0 && ch < nc && (composite(sc, pos) >> shift) >= prefix) {
+      if (ch >= 0 && ch < nc && (cv >> shift) >= prefix) {
         atomicOr(&bm[pos >> 5], 1u << (pos & 31));
         atomicAdd(&bins[ch], 1u);
       }
@@ -269,18 +292,24 @@ __global__ __launch_bounds__(256) void topk_emit_kernel(
 }  // namespace
 
 hipError_t launch_topk(const Plan& pl, int rows, const float* scores, bool hist_ready,
-                       uint32_t* hist, Pivot* pivot, uint32_t* ncand, int32_t* cand,
+                       uint32_t* hist, uint32_t* pfx, uint32_t* ncand, int32_t* cand,
                        uint32_t* bitmap, uint32_t* cnt, int32_t* idx, hipStream_t st) {
   if (pl.k_eff <= 0 || rows <= 0) return hipSuccess;
+  static bool lds_ok = false;
+  if (!lds_ok) {
+    hipError_t e = hipFuncSetAttribute((const void*)topk_refine_kernel,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)kRefineLds);
+    if (e != hipSuccess) return e;
+    lds_ok = true;
+  }
   const dim3 per_chunk((unsigned)pl.nchunks, (unsigned)rows);
+  const uint32_t k = (uint32_t)pl.k_eff;
   if (!hist_ready)
     hipLaunchKernelGGL(topk_hist_kernel, per_chunk, dim3(256), 0, st, scores, pl.n_mid, hist);
-  hipLaunchKernelGGL(topk_pivot_kernel, dim3(rows), dim3(1024), 0, st, hist, (uint32_t)pl.k_eff,
-                     pivot, ncand);
-  hipLaunchKernelGGL(topk_select_kernel, per_chunk, dim3(256), 0, st, scores, pl.n_mid, pivot,
+  hipLaunchKernelGGL(topk_select_kernel, per_chunk, dim3(256), 0, st, scores, pl.n_mid, hist, k,
                      ncand, cand, bitmap, pl.nwords, cnt, pl.nchunks);
-  hipLaunchKernelGGL(topk_refine_kernel, dim3(rows), dim3(1024), 0, st, scores, pl.n_mid, pivot,
-                     ncand, cand, bitmap, pl.nwords, cnt, pl.nchunks);
+  hipLaunchKernelGGL(topk_refine_kernel, dim3(rows), dim3(1024), kRefineLds, st, scores, pl.n_mid,
+                     hist, k, ncand, cand, pfx, bitmap, pl.nwords, cnt, pl.nchunks);
   hipLaunchKernelGGL(topk_emit_kernel, per_chunk, dim3(256), 0, st, bitmap, pl.nwords, cnt,
                      pl.nchunks, (int32_t)pl.s_eff, idx, pl.k_eff);
   return hipGetLastError();
