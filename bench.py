@@ -19,6 +19,8 @@ import sys
 import time
 
 HBM_PEAK_GBPS = 8000.0      # MI355X published HBM3E bandwidth
+# Measured with rocprofv3 --pmc (profiles/score_scan_cfg3_pmc.md): fetched + written bytes per launch.
+SCAN_TRAFFIC_BYTES = {"cfg3_decode_1m_bf16": 2 * 1044544.6 * 1024 + 32913.8 * 1024}
 
 
 def main() -> int:
@@ -29,6 +31,9 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=3, choices=[1, 2, 3, 5],
                     help="decode configuration (3 = the 1M-token one the metric is quoted on)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 1 GiB device copy 3 times (a known-size kernel against "
+                         "which rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings are scaled)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is single-GPU (one layer's hot path on one MI355X); "
@@ -62,6 +67,14 @@ def main() -> int:
     def step(i):
         B.decode_step(p, t["q"], ks[i % n_rot], vs[i % n_rot], ws, idx_out=idx, out=out)
 
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")     # 1 GiB read + 1 GiB written
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
@@ -78,6 +91,7 @@ def main() -> int:
         for s in B.STAGES:
             stage_sum[s] += ms[s]
     stages = {s: stage_sum[s] / args.steps for s in B.STAGES}
+    read_ceiling = B.probe_read_bandwidth(ks[0], iters=10)   # plain read of the same K cache
     scan_ms = stages["scan"]
     scan_gbps = w.scan_bytes / (scan_ms * 1e-3) / 1e9 if scan_ms > 0 else 0.0
 
@@ -106,7 +120,11 @@ def main() -> int:
             "achieved": round(scan_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
             "frac": round(scan_gbps / HBM_PEAK_GBPS, 4),
             "algorithmic_bytes": w.scan_bytes,
-            "traffic": None,
+            # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE (KiB per dispatch,
+            # FETCH_SIZE x2.0 and WRITE_SIZE x1.0 after scaling by a 1 GiB copy): see profiles/
+            "traffic": SCAN_TRAFFIC_BYTES.get(w.name),
+            "measured_read_ceiling_GBps": round(read_ceiling, 1),
+            "frac_of_measured_ceiling": round(scan_gbps / read_ceiling, 4) if read_ceiling > 0 else None,
         },
     }
 

@@ -145,6 +145,13 @@ int reattn_decode_step_timed(const reattn_params* p, const void* q, const void* 
                              const void* v_cache, int32_t* idx_out, float* out,
                              void* ws, size_t ws_bytes, void* stream, float* stage_ms);
 
+/* Measurement aid: streams `bytes` of the device buffer `buf` (16-byte aligned)
+ * `iters` times with the key scan's load shape and nothing else (no arithmetic, no
+ * stores) and reports the rate in GB/s into the HOST float *gb_per_s: the practical
+ * read ceiling reports are normalised against next to the data-sheet peak.  Waits. */
+int reattn_probe_read_bandwidth(const void* buf, size_t bytes, int iters, void* stream,
+                                float* gb_per_s);
+
 #ifdef __cplusplus
 }
 #endif

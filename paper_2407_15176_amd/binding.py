@@ -27,6 +27,7 @@ EXPORTS = [
     "reattn_version", "reattn_status_string", "reattn_validate", "reattn_scope",
     "reattn_workspace_bytes", "reattn_score", "reattn_topk", "reattn_gather_rope",
     "reattn_attend", "reattn_decode_step", "reattn_prefill_chunk", "reattn_decode_step_timed",
+    "reattn_probe_read_bandwidth",
 ]
 STAGES = ("prep", "scan", "topk", "attend")
 
@@ -77,6 +78,7 @@ def lib() -> C.CDLL:
         L.reattn_prefill_chunk.argtypes = [PP, P, P, P, P, P, P, C.c_size_t, P]
         L.reattn_decode_step_timed.argtypes = [PP, P, P, P, P, P, P, C.c_size_t, P,
                                                C.POINTER(C.c_float)]
+        L.reattn_probe_read_bandwidth.argtypes = [P, C.c_size_t, C.c_int, P, C.POINTER(C.c_float)]
         _lib = L
     return _lib
 
@@ -261,3 +263,12 @@ def decode_step_timed(p: Params, q, k_cache, v_cache, ws, idx_out=None, out=None
         _dev(out, "out", torch.float32), _dev(ws, "ws"), ws.numel(), _stream(), ms),
         "reattn_decode_step_timed")
     return out, idx_out, dict(zip(STAGES, [float(x) for x in ms]))
+
+
+def probe_read_bandwidth(buf: torch.Tensor, iters: int = 10) -> float:
+    """GB/s of a plain streaming read of `buf` with the scan's load shape (measurement aid)."""
+    out = C.c_float(0.0)
+    _check(lib().reattn_probe_read_bandwidth(_dev(buf, "buf"), buf.numel() * buf.element_size(),
+                                             iters, _stream(), C.byref(out)),
+           "reattn_probe_read_bandwidth")
+    return float(out.value)

@@ -311,4 +311,25 @@ int reattn_decode_step_timed(const reattn_params* p, const void* q, const void* 
   return rc;
 }
 
+int reattn_probe_read_bandwidth(const void* buf, size_t bytes, int iters, void* stream,
+                                float* gb_per_s) {
+  if (!buf || !gb_per_s) return REATTN_ERR_NULL;
+  if (!aligned16(buf)) return REATTN_ERR_ALIGN;
+  if (bytes < 16 || iters < 1) return REATTN_ERR_RANGE;
+  hipStream_t st = (hipStream_t)stream;
+  hipEvent_t a, b;
+  if (hipEventCreate(&a) != hipSuccess) return REATTN_ERR_HIP;
+  if (hipEventCreate(&b) != hipSuccess) { (void)hipEventDestroy(a); return REATTN_ERR_HIP; }
+  int rc = hip_rc(launch_read_probe(buf, bytes, st));              // warm-up
+  if (!rc) rc = hip_rc(hipEventRecord(a, st));
+  for (int i = 0; i < iters && !rc; ++i) rc = hip_rc(launch_read_probe(buf, bytes, st));
+  if (!rc) rc = hip_rc(hipEventRecord(b, st));
+  if (!rc) rc = hip_rc(hipEventSynchronize(b));
+  float ms = 0.f;
+  if (!rc) rc = hip_rc(hipEventElapsedTime(&ms, a, b));
+  if (!rc) *gb_per_s = ms > 0.f ? (float)((double)(bytes / 16 * 16) * iters / (ms * 1e-3) / 1e9) : 0.f;
+  (void)hipEventDestroy(a); (void)hipEventDestroy(b);
+  return rc;
+}
+
 }  // extern "C"

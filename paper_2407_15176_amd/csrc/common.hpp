@@ -38,6 +38,7 @@ struct Plan {
 hipError_t launch_prep(const Plan& pl, int rows, uint32_t* hist, float2* rope, hipStream_t st);
 hipError_t launch_score_scan(const Plan& pl, const void* q, int n_query, const void* k_cache,
                              float* scores, uint32_t* hist, hipStream_t st);
+hipError_t launch_read_probe(const void* buf, size_t bytes, hipStream_t st);
 hipError_t launch_score_gemm(const Plan& pl, const void* q, int q_first, int n_query,
                              const void* k_cache, float* scores, void* q_split, hipStream_t st);
 hipError_t launch_topk(const Plan& pl, int rows, const float* scores, bool hist_ready,

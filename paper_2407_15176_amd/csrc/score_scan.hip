@@ -133,6 +133,30 @@ __global__ __launch_bounds__(kScanThreads) void score_scan_kernel(ScanArgs a) {
   }
 }
 
+// Plain streaming read with the scan's load shape and nothing else: the ceiling the scan
+// is normalised against in reports (no dot products, no stores).
+__global__ __launch_bounds__(kScanThreads) void read_probe_kernel(const u32x4* __restrict__ p,
+                                                                   size_t n_vec, size_t vec_per_block,
+                                                                   uint32_t* sink) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  constexpr int U = 8, nwaves = kScanThreads / 64;
+  size_t b0 = (size_t)blockIdx.x * vec_per_block, b1 = b0 + vec_per_block;
+  if (b1 > n_vec) b1 = n_vec;
+  uint32_t acc = 0;
+  for (size_t t = b0 + (size_t)wave * U * 64; t < b1; t += (size_t)nwaves * U * 64) {
+    u32x4 d[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      size_t i = t + u * 64 + lane;
+      if (i >= b1) i = b1 - 1;
+      d[u] = __builtin_nontemporal_load(p + i);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) acc += d[u].x ^ d[u].y ^ d[u].z ^ d[u].w;
+  }
+  if (acc == 0x9e3779b9u && sink) sink[0] = acc;   // keeps the loads alive; practically never taken
+}
+
 template <typename T, int D>
 hipError_t launch_t(const ScanArgs& a, dim3 grid, bool hist, hipStream_t st) {
   constexpr int U = 8;
@@ -190,6 +214,15 @@ hipError_t launch_score_scan(const Plan& pl, const void* q, int n_query, const v
                                        : launch_t<float, 128>(a, grid, h, st);
   return pl.D == 64 ? launch_t<uint16_t, 64>(a, grid, h, st)
                     : launch_t<uint16_t, 128>(a, grid, h, st);
+}
+
+hipError_t launch_read_probe(const void* buf, size_t bytes, hipStream_t st) {
+  const size_t n_vec = bytes / 16;
+  if (n_vec == 0) return hipSuccess;
+  const size_t vpb = (size_t)kScanMaxRows * 16;           // 8 MiB per workgroup, as in the scan
+  hipLaunchKernelGGL(read_probe_kernel, dim3((unsigned)((n_vec + vpb - 1) / vpb)), dim3(kScanThreads),
+                     0, st, (const u32x4*)buf, n_vec, vpb, (uint32_t*)nullptr);
+  return hipGetLastError();
 }
 
 }  // namespace reattn
