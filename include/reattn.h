@@ -95,10 +95,12 @@ size_t reattn_workspace_bytes(const reattn_params* p);
 
 /* Eq. 2, first line: scores[i][h][j] = sum over the G heads of group h of
  * q[i][hG+g] . k_cache[h][s_eff + j], j in [0, N_mid); no rotary encoding, no
- * scaling; fp32 accumulation.  M == 1 streams the cache once (HBM-bound);
- * M > 1 runs a bf16 MFMA contraction.  N_mid == 0 is a no-op. */
+ * scaling; fp32 accumulation.  M == 1 streams the cache once (HBM-bound) and
+ * needs no workspace (ws may be NULL); M > 1 with bf16 storage and D == 128 runs
+ * the MFMA contraction and uses ws; other M > 1 shapes stream once per query.
+ * N_mid == 0 is a no-op. */
 int reattn_score(const reattn_params* p, const void* q, const void* k_cache,
-                 float* scores, void* stream);
+                 float* scores, void* ws, size_t ws_bytes, void* stream);
 
 /* Eq. 2: per (query, KV head) row of `scores`, the k_eff largest entries as
  * absolute ascending cache indices.  Ties: higher score first, then lower index.

@@ -70,7 +70,7 @@ def lib() -> C.CDLL:
         L.reattn_scope.argtypes = [PP] + [C.POINTER(C.c_int64)] * 5
         L.reattn_workspace_bytes.argtypes = [PP]
         L.reattn_workspace_bytes.restype = C.c_size_t
-        L.reattn_score.argtypes = [PP, P, P, P, P]
+        L.reattn_score.argtypes = [PP, P, P, P, P, C.c_size_t, P]
         L.reattn_topk.argtypes = [PP, P, P, P, C.c_size_t, P]
         L.reattn_gather_rope.argtypes = [PP, P, P, P, P, P, P]
         L.reattn_attend.argtypes = [PP, P, P, P, P, P, C.c_size_t, P]
@@ -175,14 +175,15 @@ def _check(rc: int, where: str):
         raise ReattnError(rc, where)
 
 
-def score(p: Params, q, k_cache, scores=None):
+def score(p: Params, q, k_cache, scores=None, ws=None):
     s_eff, l_eff, n_mid, k_eff, S = scope(p)
     if scores is None:
         scores = torch.empty(p.n_query, p.n_kv_heads, n_mid, dtype=torch.float32, device=q.device)
     cp = p.c()
     _check(lib().reattn_score(C.byref(cp), _dev(q, "q", p.torch_dtype()),
                               _dev(k_cache, "k_cache", p.torch_dtype()),
-                              _dev(scores, "scores", torch.float32), _stream()), "reattn_score")
+                              _dev(scores, "scores", torch.float32), _dev(ws, "ws"),
+                              ws.numel() if ws is not None else 0, _stream()), "reattn_score")
     return scores
 
 

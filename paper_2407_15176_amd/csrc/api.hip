@@ -76,7 +76,7 @@ int make_plan(const reattn_params* p, Plan* out) {
   const size_t per_query = (size_t)pl.Hkv * ((size_t)pl.n_mid * 4 + (size_t)pl.nchunks * kChunk * 4 +
                                              (size_t)kHistBins * 4 + (size_t)pl.nwords * 4 +
                                              (size_t)pl.nchunks * 12 + 64);
-  int64_t mt = (int64_t)(((size_t)4 << 30) / (per_query ? per_query : 1));
+  int64_t mt = (int64_t)(((size_t)2 << 30) / (per_query ? per_query : 1));
   if (mt < 1) mt = 1;
   if (mt > pl.M) mt = pl.M;
   if (mt * pl.Hkv > 65535) mt = 65535 / pl.Hkv;
@@ -95,6 +95,21 @@ int make_plan(const reattn_params* p, Plan* out) {
   pl.off_idx = off;    off += up((size_t)pl.M * pl.Hkv * (size_t)pl.k_eff * 4);
   pl.off_rope = off;   off += up((size_t)(rope_rows_hi(pl.S) + kRopeLo) * (pl.D / 2) * sizeof(float2));
   pl.off_part = off;   off += up((size_t)pl.M * pl.Hq * (size_t)pl.nsplit * (pl.D + 2) * 4);
+  pl.off_qsplit = off; off += up(pl.M > 1 ? score_gemm_qsplit_bytes(pl) : 0);
+  // fused prefill selection: MFMA scores filtered against sampled thresholds
+  pl.fused_prefill = pl.M > 1 && pl.dtype == REATTN_BF16 && pl.D == 128 && pl.k_eff > 0 &&
+                     cand_topk_lds(pl) <= (size_t)128 * 1024;
+  if (pl.fused_prefill) {
+    int64_t stride, n_s; uint32_t rho, cap;
+    prefill_sampling(pl, &stride, &n_s, &rho, &cap);
+    const size_t prow = (size_t)pl.M * pl.Hkv;
+    pl.off_samp = off;   off += up(prow * (size_t)n_s * 4);
+    pl.off_thr = off;    off += up(prow * 4);
+    pl.off_pcand = off;  off += up(prow * (size_t)cap * 8);
+    pl.off_pcount = off; off += up(prow * 4);
+    pl.off_redo = off;   off += up((prow + 1) * 4);
+    pl.off_exact = off;  off += up((size_t)kExactSlots * (size_t)pl.n_mid * 4);
+  }
   pl.total = off ? off : kAlign;
   *out = pl;
   return REATTN_OK;
@@ -102,7 +117,7 @@ int make_plan(const reattn_params* p, Plan* out) {
 
 struct Ws {
   float* scores; uint32_t* hist; uint32_t* pfx; uint32_t* ncand; int32_t* cand;
-  uint32_t* bitmap; uint32_t* cnt; int32_t* idx; float2* rope; float* part;
+  uint32_t* bitmap; uint32_t* cnt; int32_t* idx; float2* rope; float* part; void* qsplit;
 };
 
 int bind_ws(const Plan& pl, void* ws, size_t ws_bytes, Ws* w) {
@@ -114,8 +129,12 @@ int bind_ws(const Plan& pl, void* ws, size_t ws_bytes, Ws* w) {
   w->cand = (int32_t*)(b + pl.off_cand);     w->bitmap = (uint32_t*)(b + pl.off_bitmap);
   w->cnt = (uint32_t*)(b + pl.off_cnt);      w->idx = (int32_t*)(b + pl.off_idx);
   w->rope = (float2*)(b + pl.off_rope);      w->part = (float*)(b + pl.off_part);
+  w->qsplit = b + pl.off_qsplit;
   return REATTN_OK;
 }
+
+// M > 1 on bf16 / D = 128 takes the MFMA kernel; everything else streams per query.
+inline bool use_mfma(const Plan& pl) { return pl.M > 1 && pl.dtype == REATTN_BF16 && pl.D == 128; }
 
 inline int hip_rc(hipError_t e) { return e == hipSuccess ? REATTN_OK : REATTN_ERR_HIP; }
 
@@ -140,6 +159,30 @@ int select_tile(const Plan& pl, const Ws& w, const void* q, int q0, int nq, cons
   return rc;
 }
 
+// Prefill selection on the matrix cores: sample -> thresholds -> fused filter -> exact per-row
+// top-k over the candidates -> redo of the (rare) rows whose threshold missed.
+int fused_prefill_select(const Plan& pl, const Ws& w, char* ws, const void* q, const void* k_cache,
+                         int32_t* idx, hipStream_t st) {
+  int64_t stride, n_s; uint32_t rho, cap;
+  prefill_sampling(pl, &stride, &n_s, &rho, &cap);
+  float* samp = (float*)(ws + pl.off_samp);
+  float* thr = (float*)(ws + pl.off_thr);
+  uint2* cand = (uint2*)(ws + pl.off_pcand);
+  uint32_t* ccount = (uint32_t*)(ws + pl.off_pcount);
+  uint32_t* redo = (uint32_t*)(ws + pl.off_redo);
+  float* exact = (float*)(ws + pl.off_exact);
+  // the histogram-clear of prep doubles as the clear of the redo counter (one word)
+  int rc = hip_rc(launch_prep(pl, 0, nullptr, w.rope, st));
+  if (!rc) rc = hip_rc(launch_fill_u32(redo, 1, 0u, st));
+  if (!rc) rc = hip_rc(launch_qsplit(pl, q, 0, pl.M, w.qsplit, st));
+  if (!rc) rc = hip_rc(launch_score_gemm_store(pl, pl.M, k_cache, w.qsplit, stride, n_s, samp, n_s, st));
+  if (!rc) rc = hip_rc(launch_sample_threshold(pl, pl.M, samp, n_s, rho, thr, st));
+  if (!rc) rc = hip_rc(launch_score_gemm_filter(pl, pl.M, k_cache, w.qsplit, thr, cand, ccount, cap, st));
+  if (!rc) rc = hip_rc(launch_cand_topk(pl, pl.M, cand, ccount, cap, idx, redo, st));
+  if (!rc) rc = hip_rc(launch_row_exact(pl, pl.M, q, k_cache, redo, exact, kExactSlots, idx, st));
+  return rc;
+}
+
 int run_layer(const reattn_params* p, bool decode_only, const void* q, const void* k_cache,
               const void* v_cache, int32_t* idx_out, float* out, void* ws, size_t ws_bytes,
               void* stream, hipEvent_t* ev = nullptr) {
@@ -156,6 +199,11 @@ int run_layer(const reattn_params* p, bool decode_only, const void* q, const voi
   hipStream_t st = (hipStream_t)stream;
   int32_t* idx = idx_out ? idx_out : w.idx;
   mark(ev, 0, st);
+  if (pl.fused_prefill) {
+    rc = fused_prefill_select(pl, w, (char*)ws, q, k_cache, idx, st);
+    if (rc) return rc;
+    return hip_rc(launch_attend(pl, true, q, 0, pl.M, k_cache, v_cache, idx, w.rope, w.part, out, st));
+  }
   for (int q0 = 0; q0 < pl.M; q0 += pl.m_tile) {
     const int nq = pl.M - q0 < pl.m_tile ? pl.M - q0 : pl.m_tile;
     rc = select_tile(pl, w, q, q0, nq, k_cache, idx, q0 == 0, ev, st);
@@ -211,19 +259,25 @@ size_t reattn_workspace_bytes(const reattn_params* p) {
 }
 
 int reattn_score(const reattn_params* p, const void* q, const void* k_cache, float* scores,
-                 void* stream) {
+                 void* ws, size_t ws_bytes, void* stream) {
   Plan pl;
   int rc = make_plan(p, &pl);
   if (rc) return rc;
   if (!q || !k_cache || (!scores && pl.n_mid > 0)) return REATTN_ERR_NULL;
   if (!aligned16(q) || !aligned16(k_cache)) return REATTN_ERR_ALIGN;
+  hipStream_t st = (hipStream_t)stream;
+  if (use_mfma(pl)) {                       // dense contraction on the matrix cores
+    Ws w;
+    rc = bind_ws(pl, ws, ws_bytes, &w);
+    if (rc) return rc;
+    return hip_rc(launch_score_gemm(pl, q, 0, pl.M, k_cache, scores, w.qsplit, st));
+  }
   const int per = 65535 / pl.Hkv;
   const size_t eb = pl.dtype == REATTN_BF16 ? 2 : 4;
   for (int q0 = 0; q0 < pl.M && !rc; q0 += per) {
     const int nq = pl.M - q0 < per ? pl.M - q0 : per;
     rc = hip_rc(launch_score_scan(pl, (const char*)q + (size_t)q0 * pl.Hq * pl.D * eb, nq, k_cache,
-                                  scores + (size_t)q0 * pl.Hkv * pl.n_mid, nullptr,
-                                  (hipStream_t)stream));
+                                  scores + (size_t)q0 * pl.Hkv * pl.n_mid, nullptr, st));
   }
   return rc;
 }

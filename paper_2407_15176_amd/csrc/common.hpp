@@ -13,6 +13,7 @@ constexpr int kHistBins = 1 << kHistBits;     // 4096 bins, 16 KiB of LDS per wo
 constexpr int kKeyShift = 32 - kHistBits;     // remaining 20 key bits are resolved among candidates
 constexpr int kChunk = 8192;                  // middle positions per select/emit workgroup (256 x 32 bits)
 constexpr int kChunkWords = kChunk / 32;
+constexpr int kExactSlots = 64;               // workgroups (and score scratch rows) of the prefill redo path
 constexpr int kRopeLo = 128;                  // positions covered by the low rotary table
 __host__ __device__ inline int rope_rows_hi(int S) { return (S + kRopeLo - 1) / kRopeLo; }
 
@@ -31,14 +32,37 @@ struct Plan {
   // query tile of the prefill path and workspace offsets (bytes)
   int m_tile;
   size_t off_scores, off_hist, off_pfx, off_ncand, off_cand, off_bitmap, off_cnt,
-         off_idx, off_rope, off_part, total;
+         off_idx, off_rope, off_part, off_qsplit,
+         off_samp, off_thr, off_pcand, off_pcount, off_redo, off_exact, total;
+  bool fused_prefill;             // M > 1 on the MFMA path with sampled thresholds
 };
 
 // ---- host-side launchers (one per .hip file) -------------------------------
+hipError_t launch_fill_u32(uint32_t* p, int64_t n, uint32_t v, hipStream_t st);
 hipError_t launch_prep(const Plan& pl, int rows, uint32_t* hist, float2* rope, hipStream_t st);
 hipError_t launch_score_scan(const Plan& pl, const void* q, int n_query, const void* k_cache,
                              float* scores, uint32_t* hist, hipStream_t st);
+void prefill_sampling(const Plan& pl, int64_t* stride, int64_t* n_s, uint32_t* rho, uint32_t* cap);
+size_t cand_topk_lds(const Plan& pl);
+hipError_t launch_sample_threshold(const Plan& pl, int n_query, const float* samp, int64_t n_s,
+                                   uint32_t rho, float* thr, hipStream_t st);
+hipError_t launch_cand_topk(const Plan& pl, int n_query, const uint2* cand, const uint32_t* ccount,
+                            uint32_t cap, int32_t* idx, uint32_t* redo, hipStream_t st);
+hipError_t launch_row_exact(const Plan& pl, int n_query, const void* q, const void* k_cache,
+                            const uint32_t* redo, float* scratch, int n_slots, int32_t* idx,
+                            hipStream_t st);
 hipError_t launch_read_probe(const void* buf, size_t bytes, hipStream_t st);
+size_t score_gemm_qsplit_bytes(const Plan& pl);
+hipError_t launch_qsplit(const Plan& pl, const void* q, int q_first, int n_query, void* q_split,
+                         hipStream_t st);
+hipError_t launch_score_gemm_store(const Plan& pl, int n_query, const void* k_cache,
+                                   const void* q_split, int64_t key_step, int64_t n_keys,
+                                   float* scores, int64_t score_stride, hipStream_t st);
+hipError_t launch_score_gemm_filter(const Plan& pl, int n_query, const void* k_cache,
+                                    const void* q_split, const float* thr, uint2* cand,
+                                    uint32_t* ccount, uint32_t cap, hipStream_t st);
+hipError_t launch_score_gemm_discard(const Plan& pl, int n_query, const void* k_cache,
+                                     const void* q_split, float* sink, hipStream_t st);
 hipError_t launch_score_gemm(const Plan& pl, const void* q, int q_first, int n_query,
                              const void* k_cache, float* scores, void* q_split, hipStream_t st);
 hipError_t launch_topk(const Plan& pl, int rows, const float* scores, bool hist_ready,

@@ -34,6 +34,11 @@ __global__ __launch_bounds__(256) void prep_kernel(uint32_t* hist, int64_t n_his
   }
 }
 
+__global__ void fill_u32_kernel(uint32_t* p, int64_t n, uint32_t v) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+
 struct GatherArgs {
   const void* k; const void* v; const int32_t* idx; float* k_sel; void* v_sel;
   int64_t ksh, kst, vsh, vst, N;
@@ -102,6 +107,12 @@ hipError_t launch_prep(const Plan& pl, int rows, uint32_t* hist, float2* rope, h
   if (n == 0) return hipSuccess;
   hipLaunchKernelGGL(prep_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st,
                      hist, n_hist, rope, pl.S, pl.D / 2, pl.D, log2((double)pl.theta));
+  return hipGetLastError();
+}
+
+hipError_t launch_fill_u32(uint32_t* p, int64_t n, uint32_t v, hipStream_t st) {
+  if (n <= 0) return hipSuccess;
+  hipLaunchKernelGGL(fill_u32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, p, n, v);
   return hipGetLastError();
 }
 

@@ -105,7 +105,7 @@ def test_null_and_workspace_errors_before_any_launch():
     fake = C.c_void_p(0x1000)       # never dereferenced: the checks below fire first
     need = B.workspace_bytes(p)
     assert lib.reattn_validate(None) == B.ERR_NULL
-    assert lib.reattn_score(C.byref(cp), None, fake, fake, None) == B.ERR_NULL
+    assert lib.reattn_score(C.byref(cp), None, fake, fake, None, 0, None) == B.ERR_NULL
     assert lib.reattn_topk(C.byref(cp), None, fake, fake, need, None) == B.ERR_NULL
     assert lib.reattn_topk(C.byref(cp), fake, fake, None, need, None) == B.ERR_WORKSPACE
     assert lib.reattn_topk(C.byref(cp), fake, fake, fake, need - 1, None) == B.ERR_WORKSPACE

@@ -45,6 +45,23 @@ def test_score_matches_oracle(name):
     assert err <= 2e-6 * np.abs(want).max() + 1e-6, err
 
 
+@pytest.mark.parametrize("M,n_ctx", [(5, 4_321), (64, 20_011), (130, 9_000), (257, 33_000)])
+def test_score_prefill_mfma_matches_oracle(M, n_ctx):
+    """M > 1, bf16, D = 128: the MFMA contraction (hi/lo split of the group-summed query)."""
+    w = wl.CONFIGS[4].scaled(n_ctx=n_ctx, n_query=M, n_local=max(300, M), top_k=64)
+    t = gen(w)
+    p = B.Params.from_workload(w)
+    ws = B.alloc_workspace(p)
+    sc = B.score(p, t["q"], t["k"], ws=ws)
+    torch.cuda.synchronize()
+    q, k, _ = P.host_inputs(t)
+    want = ro.score(P.oracle_shape(w), q, k)
+    got = sc.cpu().numpy().astype(np.float64)
+    assert got.shape == want.shape
+    err = np.abs(got - want).max()
+    assert err <= 4e-6 * np.abs(want).max() + 1e-6, (err, np.abs(want).max())
+
+
 def test_score_respects_strides():
     """K stored as [N][Hkv][D] (token-major): strides head=D, token=Hkv*D."""
     w = SMALL["bf16_d128_g4"]
@@ -225,3 +242,33 @@ def test_prefill_chunk_matches_oracle(name, M):
     t = gen(w)
     out, idx = P.run_layer(w, t)
     P.check_layer(w, t, out, idx)
+
+
+def test_prefill_chunk_sampled_thresholds_larger_cache():
+    """n_mid / 8192 > 1: the thresholds come from a strided sample of the keys."""
+    w = wl.CONFIGS[4].scaled(n_ctx=70_000, n_query=130, n_local=512, top_k=1_000)
+    t = gen(w)
+    out, idx = P.run_layer(w, t)
+    P.check_layer(w, t, out, idx, q_rows=[0, 1, 63, 64, 127, 128, 129])
+
+
+def test_prefill_chunk_redo_path_on_degenerate_scores():
+    """Zero queries: every score ties, every threshold misses (segment overflow), and the exact
+    redo path must return the lowest k indices for every row."""
+    w = wl.CONFIGS[4].scaled(n_ctx=20_000, n_query=9, n_local=300, top_k=200)
+    t = gen(w)
+    t["q"].zero_()
+    out, idx = P.run_layer(w, t)
+    want = torch.arange(w.n_sink, w.n_sink + 200, dtype=torch.int32, device="cuda")
+    assert torch.equal(idx, want.expand(9, w.n_kv_heads, 200))
+    P.check_layer(w, t, out, idx)
+
+
+def test_prefill_chunk_mixed_redo_rows():
+    """Some query rows are zero (redo path), the others take the filtered path."""
+    w = wl.CONFIGS[4].scaled(n_ctx=30_000, n_query=70, n_local=400, top_k=300)
+    t = gen(w)
+    t["q"][3].zero_()
+    t["q"][66].zero_()
+    out, idx = P.run_layer(w, t)
+    P.check_layer(w, t, out, idx, q_rows=[0, 3, 4, 65, 66, 69])
