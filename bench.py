@@ -31,6 +31,8 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=3, choices=[1, 2, 3, 5],
                     help="decode configuration (3 = the 1M-token one the metric is quoted on)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-prefill", action="store_true",
+                    help="skip the config-4 prefill-chunk measurement (MFMA score contraction)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy 3 times (a known-size kernel against "
                          "which rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings are scaled)")
@@ -128,10 +130,65 @@ def main() -> int:
         },
     }
 
+    if not args.no_prefill:
+        del ks, vs, t, ws
+        torch.cuda.empty_cache()
+        result["prefill"] = prefill_leg(min(args.steps, 5))
+        t = None
     if not args.no_cpu_baseline:
+        if t is None:
+            t = wl.generate(w, "cuda")
         result["cpu_baseline"] = cpu_baseline(w, t)
     print(json.dumps(result), flush=True)
     return 0
+
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X published dense bf16 matrix rate
+
+
+def prefill_leg(steps: int) -> dict:
+    """Config 4: one prefill chunk of 4,096 queries against 262,144 cached keys (one layer).
+    Reports the chunk latency and the fused MFMA score contraction's rate from HIP events."""
+    import torch
+    from paper_2407_15176_amd import binding as B
+    from paper_2407_15176_amd import workloads as wl
+    w = wl.CONFIGS[4]
+    p = B.Params.from_workload(w)
+    t = wl.generate(w, "cuda")
+    ws = B.alloc_workspace(p)
+    out = torch.empty(w.n_query, w.n_q_heads, w.head_dim, dtype=torch.float32, device="cuda")
+    idx = torch.empty(w.n_query, w.n_kv_heads, w.k_eff, dtype=torch.int32, device="cuda")
+    B.prefill_chunk(p, t["q"], t["k"], t["v"], ws, idx_out=idx, out=out)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        B.prefill_chunk(p, t["q"], t["k"], t["v"], ws, idx_out=idx, out=out)
+    torch.cuda.synchronize()
+    ms_chunk = (time.perf_counter() - t0) * 1e3 / steps
+    acc = {s: 0.0 for s in B.PREFILL_STAGES}
+    for _ in range(steps):
+        _, _, ms = B.prefill_chunk_timed(p, t["q"], t["k"], t["v"], ws, idx_out=idx, out=out)
+        for s in acc:
+            acc[s] += ms[s] / steps
+    gemm_ms = acc["score_gemm_filter"]
+    alg = w.score_flops                                   # 2*M*Hq*N_mid*D: every head scored (Eq. 2)
+    executed = 2 * w.n_query * w.n_kv_heads * w.n_mid * w.head_dim * 2   # hi + lo of the group sum
+    alg_tf = alg / (gemm_ms * 1e-3) / 1e12
+    return {
+        "workload": w.name, "ms_per_chunk": round(ms_chunk, 3), "steps": steps,
+        "tokens_per_s": round(w.n_query / (ms_chunk * 1e-3), 1),
+        "stages_ms": {s: round(v, 4) for s, v in acc.items()},
+        "roofline": {
+            "kernel": "score_gemm_kernel (fused threshold filter)", "bound": "mfma",
+            "achieved": round(alg_tf, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+            "frac": round(alg_tf / MFMA_BF16_PEAK_TFLOPS, 4),
+            "algorithmic_flops": alg,
+            "executed_mfma_flops": executed,
+            "executed_TFLOPs": round(executed / (gemm_ms * 1e-3) / 1e12, 1),
+            "executed_frac": round(executed / (gemm_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+            "traffic": None,
+        },
+    }
 
 
 def cpu_baseline(w, t) -> dict:

@@ -147,6 +147,16 @@ int reattn_decode_step_timed(const reattn_params* p, const void* q, const void* 
                              const void* v_cache, int32_t* idx_out, float* out,
                              void* ws, size_t ws_bytes, void* stream, float* stage_ms);
 
+/* Measurement aid: reattn_prefill_chunk on the MFMA path (bf16, D == 128, M > 1, k_eff > 0;
+ * other shapes return REATTN_ERR_SHAPE) with HIP events at the stage boundaries; WAITS and
+ * fills the HOST array stage_ms[REATTN_N_STAGES] with
+ *   [0] prep + query split + sampled scores + per-row thresholds,
+ *   [1] the fused MFMA score contraction with threshold filter (Eq. 2 for all M queries),
+ *   [2] exact per-row top-k over the candidates (+ redo rows), [3] attention of Eq. 3. */
+int reattn_prefill_chunk_timed(const reattn_params* p, const void* q, const void* k_cache,
+                               const void* v_cache, int32_t* idx_out, float* out,
+                               void* ws, size_t ws_bytes, void* stream, float* stage_ms);
+
 /* Measurement aid: streams `bytes` of the device buffer `buf` (16-byte aligned)
  * `iters` times with the key scan's load shape and nothing else (no arithmetic, no
  * stores) and reports the rate in GB/s into the HOST float *gb_per_s: the practical

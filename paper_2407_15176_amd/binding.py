@@ -27,8 +27,9 @@ EXPORTS = [
     "reattn_version", "reattn_status_string", "reattn_validate", "reattn_scope",
     "reattn_workspace_bytes", "reattn_score", "reattn_topk", "reattn_gather_rope",
     "reattn_attend", "reattn_decode_step", "reattn_prefill_chunk", "reattn_decode_step_timed",
-    "reattn_probe_read_bandwidth",
+    "reattn_probe_read_bandwidth", "reattn_prefill_chunk_timed",
 ]
+PREFILL_STAGES = ("sample_threshold", "score_gemm_filter", "candidate_topk", "attend")
 STAGES = ("prep", "scan", "topk", "attend")
 
 
@@ -78,6 +79,7 @@ def lib() -> C.CDLL:
         L.reattn_prefill_chunk.argtypes = [PP, P, P, P, P, P, P, C.c_size_t, P]
         L.reattn_decode_step_timed.argtypes = [PP, P, P, P, P, P, P, C.c_size_t, P,
                                                C.POINTER(C.c_float)]
+        L.reattn_prefill_chunk_timed.argtypes = L.reattn_decode_step_timed.argtypes
         L.reattn_probe_read_bandwidth.argtypes = [P, C.c_size_t, C.c_int, P, C.POINTER(C.c_float)]
         _lib = L
     return _lib
@@ -249,21 +251,29 @@ def prefill_chunk(p: Params, q, k_cache, v_cache, ws, idx_out=None, out=None, wa
     return _layer("reattn_prefill_chunk", p, q, k_cache, v_cache, ws, idx_out, out, want_idx)
 
 
+def prefill_chunk_timed(p: Params, q, k_cache, v_cache, ws, idx_out=None, out=None):
+    """prefill_chunk (MFMA path) with per-stage HIP-event timing; synchronises."""
+    return _timed("reattn_prefill_chunk_timed", PREFILL_STAGES, p, q, k_cache, v_cache, ws, idx_out, out)
+
+
 def decode_step_timed(p: Params, q, k_cache, v_cache, ws, idx_out=None, out=None):
     """decode_step with per-stage HIP-event timing; synchronises.  Returns (out, idx, {stage: ms})."""
+    return _timed("reattn_decode_step_timed", STAGES, p, q, k_cache, v_cache, ws, idx_out, out)
+
+
+def _timed(fn_name, names, p: Params, q, k_cache, v_cache, ws, idx_out=None, out=None):
     s_eff, l_eff, n_mid, k_eff, S = scope(p)
     if out is None:
         out = torch.empty(p.n_query, p.n_q_heads, p.head_dim, dtype=torch.float32, device=q.device)
     if idx_out is None:
         idx_out = torch.empty(p.n_query, p.n_kv_heads, k_eff, dtype=torch.int32, device=q.device)
-    ms = (C.c_float * len(STAGES))()
+    ms = (C.c_float * len(names))()
     cp = p.c()
-    _check(lib().reattn_decode_step_timed(
+    _check(getattr(lib(), fn_name)(
         C.byref(cp), _dev(q, "q", p.torch_dtype()), _dev(k_cache, "k_cache", p.torch_dtype()),
         _dev(v_cache, "v_cache", p.torch_dtype()), _dev(idx_out, "idx_out", torch.int32),
-        _dev(out, "out", torch.float32), _dev(ws, "ws"), ws.numel(), _stream(), ms),
-        "reattn_decode_step_timed")
-    return out, idx_out, dict(zip(STAGES, [float(x) for x in ms]))
+        _dev(out, "out", torch.float32), _dev(ws, "ws"), ws.numel(), _stream(), ms), fn_name)
+    return out, idx_out, dict(zip(names, [float(x) for x in ms]))
 
 
 def probe_read_bandwidth(buf: torch.Tensor, iters: int = 10) -> float:

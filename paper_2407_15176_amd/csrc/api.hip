@@ -162,7 +162,7 @@ int select_tile(const Plan& pl, const Ws& w, const void* q, int q0, int nq, cons
 // Prefill selection on the matrix cores: sample -> thresholds -> fused filter -> exact per-row
 // top-k over the candidates -> redo of the (rare) rows whose threshold missed.
 int fused_prefill_select(const Plan& pl, const Ws& w, char* ws, const void* q, const void* k_cache,
-                         int32_t* idx, hipStream_t st) {
+                         int32_t* idx, hipEvent_t* ev, hipStream_t st) {
   int64_t stride, n_s; uint32_t rho, cap;
   prefill_sampling(pl, &stride, &n_s, &rho, &cap);
   float* samp = (float*)(ws + pl.off_samp);
@@ -177,9 +177,12 @@ int fused_prefill_select(const Plan& pl, const Ws& w, char* ws, const void* q, c
   if (!rc) rc = hip_rc(launch_qsplit(pl, q, 0, pl.M, w.qsplit, st));
   if (!rc) rc = hip_rc(launch_score_gemm_store(pl, pl.M, k_cache, w.qsplit, stride, n_s, samp, n_s, st));
   if (!rc) rc = hip_rc(launch_sample_threshold(pl, pl.M, samp, n_s, rho, thr, st));
+  mark(ev, 1, st);
   if (!rc) rc = hip_rc(launch_score_gemm_filter(pl, pl.M, k_cache, w.qsplit, thr, cand, ccount, cap, st));
+  mark(ev, 2, st);
   if (!rc) rc = hip_rc(launch_cand_topk(pl, pl.M, cand, ccount, cap, idx, redo, st));
   if (!rc) rc = hip_rc(launch_row_exact(pl, pl.M, q, k_cache, redo, exact, kExactSlots, idx, st));
+  mark(ev, 3, st);
   return rc;
 }
 
@@ -200,9 +203,11 @@ int run_layer(const reattn_params* p, bool decode_only, const void* q, const voi
   int32_t* idx = idx_out ? idx_out : w.idx;
   mark(ev, 0, st);
   if (pl.fused_prefill) {
-    rc = fused_prefill_select(pl, w, (char*)ws, q, k_cache, idx, st);
+    rc = fused_prefill_select(pl, w, (char*)ws, q, k_cache, idx, ev, st);
     if (rc) return rc;
-    return hip_rc(launch_attend(pl, true, q, 0, pl.M, k_cache, v_cache, idx, w.rope, w.part, out, st));
+    rc = hip_rc(launch_attend(pl, true, q, 0, pl.M, k_cache, v_cache, idx, w.rope, w.part, out, st));
+    mark(ev, 4, st);
+    return rc;
   }
   for (int q0 = 0; q0 < pl.M; q0 += pl.m_tile) {
     const int nq = pl.M - q0 < pl.m_tile ? pl.M - q0 : pl.m_tile;
@@ -346,16 +351,16 @@ int reattn_prefill_chunk(const reattn_params* p, const void* q, const void* k_ca
   return run_layer(p, false, q, k_cache, v_cache, idx_out, out, ws, ws_bytes, stream);
 }
 
-int reattn_decode_step_timed(const reattn_params* p, const void* q, const void* k_cache,
-                             const void* v_cache, int32_t* idx_out, float* out, void* ws,
-                             size_t ws_bytes, void* stream, float* stage_ms) {
+static int layer_timed(const reattn_params* p, bool decode_only, const void* q, const void* k_cache,
+                       const void* v_cache, int32_t* idx_out, float* out, void* ws,
+                       size_t ws_bytes, void* stream, float* stage_ms) {
   if (!stage_ms) return REATTN_ERR_NULL;
   hipEvent_t ev[REATTN_N_STAGES + 1];
   int made = 0;
   for (; made <= REATTN_N_STAGES; ++made)
     if (hipEventCreate(&ev[made]) != hipSuccess) break;
   int rc = made == REATTN_N_STAGES + 1 ? REATTN_OK : REATTN_ERR_HIP;
-  if (!rc) rc = run_layer(p, true, q, k_cache, v_cache, idx_out, out, ws, ws_bytes, stream, ev);
+  if (!rc) rc = run_layer(p, decode_only, q, k_cache, v_cache, idx_out, out, ws, ws_bytes, stream, ev);
   if (!rc) {
     if (hipEventSynchronize(ev[REATTN_N_STAGES]) != hipSuccess) rc = REATTN_ERR_HIP;
     for (int i = 0; i < REATTN_N_STAGES && !rc; ++i)
@@ -363,6 +368,22 @@ int reattn_decode_step_timed(const reattn_params* p, const void* q, const void* 
   }
   for (int i = 0; i < made; ++i) (void)hipEventDestroy(ev[i]);
   return rc;
+}
+
+int reattn_decode_step_timed(const reattn_params* p, const void* q, const void* k_cache,
+                             const void* v_cache, int32_t* idx_out, float* out, void* ws,
+                             size_t ws_bytes, void* stream, float* stage_ms) {
+  return layer_timed(p, true, q, k_cache, v_cache, idx_out, out, ws, ws_bytes, stream, stage_ms);
+}
+
+int reattn_prefill_chunk_timed(const reattn_params* p, const void* q, const void* k_cache,
+                               const void* v_cache, int32_t* idx_out, float* out, void* ws,
+                               size_t ws_bytes, void* stream, float* stage_ms) {
+  Plan pl;
+  const int rc = make_plan(p, &pl);
+  if (rc) return rc;
+  if (!pl.fused_prefill) return REATTN_ERR_SHAPE;   // stage boundaries are defined for the MFMA path
+  return layer_timed(p, false, q, k_cache, v_cache, idx_out, out, ws, ws_bytes, stream, stage_ms);
 }
 
 int reattn_probe_read_bandwidth(const void* buf, size_t bytes, int iters, void* stream,
