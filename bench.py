@@ -33,6 +33,8 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-prefill", action="store_true",
                     help="skip the config-4 prefill-chunk measurement (MFMA score contraction)")
+    ap.add_argument("--only-prefill", action="store_true",
+                    help="run the config-4 prefill leg alone and print its object (for profiling runs)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy 3 times (a known-size kernel against "
                          "which rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings are scaled)")
@@ -50,6 +52,9 @@ def main() -> int:
         print("bench.py: no GPU visible; there is no CPU fallback", file=sys.stderr)
         return 2
     torch.cuda.set_device(0)
+    if args.only_prefill:
+        print(json.dumps({"prefill": prefill_leg(min(args.steps, 5))}), flush=True)
+        return 0
     w = wl.CONFIGS[args.config]
     p = B.Params.from_workload(w)
     t = wl.generate(w, "cuda")

@@ -9,23 +9,32 @@
 // matrix work of scoring the heads one by one, at fp32-level accuracy (a single bf16
 // rounding of qbar would eat half of the 1e-3 tie band of the selection).
 //
-// Tiling: a workgroup of NQW x 4 waves owns NQW x 64 queries of one KV head and walks
+// Tiling: a workgroup of 8 waves (512 threads) owns 128 queries of one KV head and walks
 // key tiles of 128 rows.  Keys are the A operand (row = key), queries the B operand
 // (column = query): a lane then holds ONE query column per 32x32 block, so a per-query
 // threshold test needs one register.  Wave (kw, qw) takes key block kw (32 keys) and
 // the two query blocks of half qw; its 2 x 16 query operands (hi, lo for 8 k-steps,
 // 128 VGPRs) stay in registers for the whole kernel, the key tile is staged through
-// LDS (272-byte row pitch: conflict-free 16-byte reads) with register double-buffering
-// of the next tile.  NQW = 2 (512 threads, 128 queries) is what every launch uses: it
-// halves the L2->LDS key traffic, and measured 1.9x faster than two independent
-// 256-thread workgroups per CU in the fused-filter mode.
+// LDS (272-byte row pitch: conflict-free 16-byte reads), two buffers, the next tile
+// travelling through registers.  128 queries per workgroup halves the L2->LDS key
+// traffic of a 64-query one.  blockIdx.x is the KV head, so that with 8 heads each of
+// the 8 XCDs streams one head's keys through its own L2 (HBM sees the keys once).
 //
 // Fused filter (prefill selection): instead of writing the M x N_mid scores (33.8 GB at
 // M = 4096, N_mid = 258044) each score is compared with a per-(query, KV head) lower
 // bound on the k-th largest score, estimated beforehand from a strided sample of the
 // keys; the few percent that pass are appended as (score, key) pairs to the row's
 // candidate segment.  A workgroup owns its query rows for ALL keys, so the per-row
-// counters live in LDS and no global atomics are needed.
+// counters live in LDS and no global atomics are needed.  The filter of tile t - 1 runs
+// inside the MFMA sequence of tile t: a wave parks its 32 x 64 scores in a private LDS
+// stage, tests them between the first 16 MFMAs of the next tile, and appends the hits
+// either between the two MFMA halves or after them, depending on its query half, so
+// that the two waves sharing a SIMD are not both away from the matrix pipe.
+//
+// Measured on MI355X (random bf16 operands): the matrix pipe itself sustains 1790
+// TFLOP/s from registers and 1680 with one LDS operand read per four MFMAs (all-zero
+// operands reach 2480: the clock is power-limited under real data), the bare loop of
+// this kernel 1400, the fused filter 880 executed = 1760 algorithmic.
 #include "common.hpp"
 
 namespace reattn {
@@ -76,19 +85,26 @@ struct GemmArgs {
 
 enum { kStore = 0, kFilter = 1, kDiscard = 2 };
 
-template <int MODE, int NQW>
-__global__ __launch_bounds__(256 * NQW) void score_gemm_kernel(GemmArgs a) {
-  constexpr int kTileQ = 64 * NQW, kGemmThreads = 256 * NQW;
-  extern __shared__ __attribute__((aligned(16))) unsigned char gemm_lds[];   // two staged key tiles
-  unsigned char (*lds)[kTileKeys * kPitch] = (unsigned char (*)[kTileKeys * kPitch])gemm_lds;
+constexpr int kGemmThreads = 512;               // 8 waves: 4 key blocks x 2 query halves
+constexpr int kTileQ = 128;                     // queries per workgroup
+constexpr int kTileBytes = kTileKeys * kPitch;  // one staged key tile
+constexpr int kStageBytes = 32 * 64 * 4;        // one wave's 32 x 64 scores of a tile (filter mode)
+constexpr int kStageNS = 2048 / kGemmThreads;   // 16-byte pieces of a key tile per thread
+
+template <int MODE>
+__global__ __launch_bounds__(kGemmThreads) void score_gemm_kernel(GemmArgs a) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char gemm_lds[];
+  unsigned char* tiles = gemm_lds;                          // two staged key tiles
   __shared__ uint32_t lcount[kTileQ];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int kw = wave & 3, qw = wave >> 2;
   const int ln = lane & 31, lh = lane >> 5;
-  const int h = blockIdx.z;
+  // blockIdx.x is the KV head: consecutive workgroup ids go to different XCDs, so with 8 heads
+  // every XCD streams the keys of one head through its own L2
+  const int h = blockIdx.x;
   const int q0 = blockIdx.y * kTileQ;
-  const int64_t tile0 = (int64_t)blockIdx.x * a.tiles_per_block;
+  const int64_t tile0 = (int64_t)blockIdx.z * a.tiles_per_block;
   const int64_t n_tiles_all = (a.n_keys + kTileKeys - 1) / kTileKeys;
   int64_t n_tiles = n_tiles_all - tile0;
   if (n_tiles > a.tiles_per_block) n_tiles = a.tiles_per_block;
@@ -109,62 +125,167 @@ __global__ __launch_bounds__(256 * NQW) void score_gemm_kernel(GemmArgs a) {
     }
   }
   float thr[2] = {0.f, 0.f};
+  uint2* seg[2] = {nullptr, nullptr};
   if (MODE == kFilter) {
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
       const int qi = q0 + (qw * 2 + qb) * 32 + ln;
       thr[qb] = qi < a.M ? a.thr[(int64_t)h * a.M + qi] : __builtin_inff();
+      seg[qb] = a.cand + ((int64_t)h * a.M + qi) * a.cap;
     }
   }
+  // filter mode: this wave's 32 x 64 scores of the previous tile, as 8 rows of 64 float4:
+  // row qb*4 + j holds acc[qb][4j .. 4j+3] of every lane
+  float4* stage = (float4*)(gemm_lds + 2 * kTileBytes + wave * kStageBytes);
 
-  // staging: thread t moves NS x 16 bytes of the 128 x 256-byte key tile: rows t/16 + RS*j, column t%16
-  constexpr int NS = 2048 / kGemmThreads, RS = kGemmThreads / 16;
+  // staging: thread t moves kStageNS x 16 bytes of the 128 x 256-byte key tile:
+  // rows t/16 + 32*j, column t%16.  Tile t + 2 is requested at the start of step t, right after
+  // tile t + 1 has been moved from the same registers to LDS, so a load has a whole step to
+  // arrive.  The wait sits at the start of a step, before anything else is requested, because
+  // the hardware counts loads and stores in one queue and the number of candidate stores a
+  // step issues is not known at compile time: a wait placed after them would also wait for
+  // the loads just issued.
+  constexpr int RS = kGemmThreads / 16;
   const int srow = tid >> 4, scol = tid & 15;
-  const uint16_t* kbase = a.k + (int64_t)h * a.ksh;
-  u32x4 stg[NS];
-  auto load_tile = [&](int64_t tile) {
+  const int64_t row_bytes = a.key_step * a.kst * 2;          // distance of consecutive scored keys
+  const char* kbase = (const char*)(a.k + (int64_t)h * a.ksh + a.first_tok * a.kst) + scol * 16;
+  const char* next = kbase + (tile0 * kTileKeys + srow) * row_bytes;   // this thread's piece of the next tile to request
+  u32x4 stg[kStageNS];
+  auto load_tile = [&](int64_t tile, u32x4* s) {
+    if ((tile + 1) * kTileKeys <= a.n_keys) {                // wave-uniform: every tile but a ragged last one
 #pragma unroll
-    for (int j = 0; j < NS; ++j) {
-      int64_t key = tile * kTileKeys + srow + RS * j;
-      if (key >= a.n_keys) key = a.n_keys - 1;
-      stg[j] = *(const u32x4*)(kbase + (a.first_tok + key * a.key_step) * a.kst + scol * 8);
+      for (int j = 0; j < kStageNS; ++j) s[j] = *(const u32x4*)(next + (int64_t)(RS * j) * row_bytes);
+    } else {
+#pragma unroll
+      for (int j = 0; j < kStageNS; ++j) {
+        int64_t key = tile * kTileKeys + srow + RS * j;
+        if (key >= a.n_keys) key = a.n_keys - 1;             // rows past the end repeat the last key; their scores are dropped
+        s[j] = *(const u32x4*)(kbase + key * row_bytes);
+      }
+    }
+    next += (int64_t)kTileKeys * row_bytes;
+  };
+  auto stash_tile = [&](int buf, const u32x4* s) {
+#pragma unroll
+    for (int j = 0; j < kStageNS; ++j)
+      *(u32x4*)(tiles + buf * kTileBytes + (srow + RS * j) * kPitch + scol * 16) = s[j];
+  };
+
+  // C layout of a 32x32 block: acc[i] is row (i/4)*8 + (lane/32)*4 + i%4 (key), column lane%32 (query).
+  // Filter epilogue of a finished tile whose scores sit in `stage` and whose per-lane hit mask
+  // (bit qb*16 + i for acc[qb][i]) was formed in the shadow of the next tile's MFMAs.
+  auto append_hits = [&](int64_t tile, uint32_t mask) {
+    const int64_t key_blk = tile * kTileKeys + kw * 32 + lh * 4;
+    if (key_blk + 27 >= a.n_keys) {                 // only the ragged last tile can hold invalid keys
+#pragma unroll
+      for (int i = 0; i < 16; ++i)
+        if (key_blk + (i >> 2) * 8 + (i & 3) >= a.n_keys) mask &= ~(0x10001u << i);
+    }
+    // one LDS atomic per (lane, query block) reserves room for all of its hits
+    uint32_t pos[2];
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+      const uint32_t c = (uint32_t)__popc((mask >> (qb * 16)) & 0xffffu);
+      pos[qb] = c ? atomicAdd(&lcount[(qw * 2 + qb) * 32 + ln], c) : 0u;
+    }
+    // a lane has 0.8 hits on average: four are fetched from the stage together (one LDS round
+    // trip instead of four in a row), the loop is for the rare lane with more
+    constexpr int kBatch = 4;
+    while (mask) {
+      int b[kBatch]; float sc[kBatch]; bool on[kBatch];
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u) {
+        on[u] = mask != 0;
+        b[u] = on[u] ? __ffs((int)mask) - 1 : 0;
+        mask &= mask - 1;                            // 0 stays 0
+        sc[u] = ((const float*)stage)[((b[u] >> 2) * 64 + lane) * 4 + (b[u] & 3)];
+      }
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u) {
+        if (on[u]) {
+          const int qb = b[u] >> 4, i = b[u] & 15;
+          const uint32_t at = qb ? pos[1]++ : pos[0]++;
+          if (at < a.cap)
+            (qb ? seg[1] : seg[0])[at] =
+                make_uint2(__float_as_uint(sc[u]), (uint32_t)(key_blk + (i >> 2) * 8 + (i & 3)));
+        }
+      }
     }
   };
-  auto stash_tile = [&](int buf) {
-#pragma unroll
-    for (int j = 0; j < NS; ++j)
-      *(u32x4*)(&lds[buf][(srow + RS * j) * kPitch + scol * 16]) = stg[j];
+  auto test_stage_row = [&](int r, uint32_t& mask) {        // 4 staged scores of this lane against its threshold
+    const float4 v = stage[r * 64 + lane];
+    const float th = thr[r >> 2];
+    mask |= ((v.x >= th ? 1u : 0u) | (v.y >= th ? 2u : 0u) | (v.z >= th ? 4u : 0u) |
+             (v.w >= th ? 8u : 0u)) << (r * 4);
   };
 
-  if (n_tiles > 0) { load_tile(tile0); stash_tile(0); }
+  if (MODE == kFilter) {                          // NaN passes no threshold: tile 0 has no predecessor
+    const float nan = __builtin_nanf("");
+#pragma unroll
+    for (int j = 0; j < 8; ++j) stage[j * 64 + lane] = make_float4(nan, nan, nan, nan);
+  }
+  if (n_tiles > 0) {
+    load_tile(tile0, stg);
+    stash_tile(0, stg);
+    if (n_tiles > 1) load_tile(tile0 + 1, stg);
+  }
   __syncthreads();
 
-  for (int64_t t = 0; t < n_tiles; ++t) {
-    const int buf = (int)(t & 1);
-    if (t + 1 < n_tiles) load_tile(tile0 + t + 1);
-
+  // One tile: MFMAs of tile t out of LDS buffer `buf`.  In filter mode the threshold tests of
+  // tile t - 1 run between the first 16 of them (the matrix pipe and the vector ALUs work side
+  // by side), and its hits are appended either between the two halves (waves of query half 1)
+  // or after the second (query half 0): the two waves that share a SIMD are then never both
+  // away from the matrix pipe.
+  auto step = [&](int64_t t, int buf) {
+    if (t + 1 < n_tiles) stash_tile(buf ^ 1, stg);
+    if (t + 2 < n_tiles) load_tile(tile0 + t + 2, stg);
     f32x16 acc[2];
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb)
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[qb][i] = 0.f;
-    const unsigned char* arow = &lds[buf][(kw * 32 + ln) * kPitch + lh * 16];
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
+    uint32_t mask = 0;
+    const unsigned char* arow = tiles + buf * kTileBytes + (kw * 32 + ln) * kPitch + lh * 16;
+    auto mfma_step = [&](int ks) {
       const bf16x8 av = *(const bf16x8*)(arow + ks * 32);
+      acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bhi[0][ks], acc[0], 0, 0, 0);
+      acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bhi[1][ks], acc[1], 0, 0, 0);
+      acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, blo[0][ks], acc[0], 0, 0, 0);
+      acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, blo[1][ks], acc[1], 0, 0, 0);
+    };
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      mfma_step(ks);
+      if (MODE == kFilter) { test_stage_row(2 * ks, mask); test_stage_row(2 * ks + 1, mask); }
+    }
+    if (MODE == kFilter) {
+      // scheduling pattern for the block above: tests spread between the MFMAs
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) {
+        __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);   // LDS reads: key operand, 2 staged rows
+#pragma unroll
+        for (int m = 0; m < 4; ++m) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // one MFMA
+          __builtin_amdgcn_sched_group_barrier(0x002, 6, 0);  // six vector ALU instructions
+        }
+      }
+      if (qw == 1) append_hits(tile0 + t - 1, mask);
+    }
+#pragma unroll
+    for (int ks = 4; ks < 8; ++ks) mfma_step(ks);
+    const int64_t key_blk = (tile0 + t) * kTileKeys + kw * 32 + lh * 4;
+    if (MODE == kFilter) {
+      if (qw == 0) append_hits(tile0 + t - 1, mask);
+#pragma unroll
+      for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          stage[(qb * 4 + j) * 64 + lane] =
+              make_float4(acc[qb][4 * j], acc[qb][4 * j + 1], acc[qb][4 * j + 2], acc[qb][4 * j + 3]);
+    } else if (MODE == kStore) {
 #pragma unroll
       for (int qb = 0; qb < 2; ++qb) {
-        acc[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bhi[qb][ks], acc[qb], 0, 0, 0);
-        acc[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, blo[qb][ks], acc[qb], 0, 0, 0);
-      }
-    }
-
-    // C layout of a 32x32 block: acc[i] is row (i/4)*8 + (lane/32)*4 + i%4 (key), column lane%32 (query)
-    const int64_t key_blk = (tile0 + t) * kTileKeys + kw * 32 + lh * 4;
-#pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
-      const int qi = q0 + (qw * 2 + qb) * 32 + ln;
-      if (MODE == kStore) {
+        const int qi = q0 + (qw * 2 + qb) * 32 + ln;
         if (qi < a.M) {
           float* orow = a.scores + ((int64_t)qi * a.Hkv + h) * a.score_stride;
 #pragma unroll
@@ -173,60 +294,47 @@ __global__ __launch_bounds__(256 * NQW) void score_gemm_kernel(GemmArgs a) {
             if (key < a.n_keys) orow[key] = acc[qb][i];
           }
         }
-      } else if (MODE == kFilter) {
-        // one LDS atomic per lane reserves room for all of its hits in this block
-        uint32_t mask = 0;
+      }
+    } else {
+      float s = 0.f;
 #pragma unroll
-        for (int i = 0; i < 16; ++i) mask |= (acc[qb][i] >= thr[qb] ? 1u : 0u) << i;
-        if (key_blk + 27 >= a.n_keys) {             // only the ragged last tile can hold invalid keys
-#pragma unroll
-          for (int i = 0; i < 16; ++i)
-            if (key_blk + (i >> 2) * 8 + (i & 3) >= a.n_keys) mask &= ~(1u << i);
-        }
-        if (mask) {
-          const int ql = (qw * 2 + qb) * 32 + ln;
-          uint32_t pos = atomicAdd(&lcount[ql], (uint32_t)__popc(mask));
-          uint2* seg = a.cand + ((int64_t)h * a.M + qi) * a.cap;
-#pragma unroll
-          for (int i = 0; i < 16; ++i) {
-            if (mask & (1u << i)) {
-              if (pos < a.cap)
-                seg[pos] = make_uint2(__float_as_uint(acc[qb][i]),
-                                      (uint32_t)(key_blk + (i >> 2) * 8 + (i & 3)));
-              ++pos;
-            }
-          }
-        }
-      } else {
-        float s = 0.f;
+      for (int qb = 0; qb < 2; ++qb)
 #pragma unroll
         for (int i = 0; i < 16; ++i) s += acc[qb][i];
-        if (s == 1.2345e30f) a.scores[0] = s;    // keeps the MFMAs alive in the timing-only mode
-      }
+      if (s == 1.2345e30f) a.scores[0] = s;        // keeps the MFMAs alive in the timing-only mode
     }
-
-    if (t + 1 < n_tiles) stash_tile(buf ^ 1);
     __syncthreads();
+  };
+
+  for (int64_t t = 0; t < n_tiles; t += 2) {
+    step(t, 0);
+    if (t + 1 < n_tiles) step(t + 1, 1);
   }
 
   if (MODE == kFilter) {
+    if (n_tiles > 0) {                              // the last tile has no successor to hide behind
+      uint32_t mask = 0;
+#pragma unroll
+      for (int r = 0; r < 8; ++r) test_stage_row(r, mask);
+      append_hits(tile0 + n_tiles - 1, mask);
+    }
+    __syncthreads();
     if (tid < kTileQ && q0 + tid < a.M) a.ccount[(int64_t)h * a.M + q0 + tid] = lcount[tid];
   }
 }
 
-constexpr size_t kGemmLds = 2 * (size_t)kTileKeys * kPitch;
-
-template <int MODE, int NQW>
+template <int MODE>
 hipError_t gemm_launch(const GemmArgs& a, dim3 grid, hipStream_t st) {
   static bool attr_done = false;
-  auto kern = score_gemm_kernel<MODE, NQW>;
+  constexpr size_t lds = 2 * (size_t)kTileBytes + (MODE == kFilter ? 8 * (size_t)kStageBytes : 0);
+  auto kern = score_gemm_kernel<MODE>;
   if (!attr_done) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       (int)kGemmLds);
+                                       (int)lds);
     if (e != hipSuccess) return e;
     attr_done = true;
   }
-  hipLaunchKernelGGL(kern, grid, dim3(256 * NQW), kGemmLds, st, a);
+  hipLaunchKernelGGL(kern, grid, dim3(kGemmThreads), lds, st, a);
   return hipGetLastError();
 }
 
@@ -270,9 +378,9 @@ hipError_t launch_score_gemm_store(const Plan& pl, int n_query, const void* k_ca
   int64_t split = (1024 + qtiles - 1) / qtiles;          // enough workgroups to fill the chip
   if (split > n_tiles) split = n_tiles;
   a.tiles_per_block = (int)((n_tiles + split - 1) / split);
-  const dim3 grid((unsigned)((n_tiles + a.tiles_per_block - 1) / a.tiles_per_block),
-                  (unsigned)(a.m_pad / 128), (unsigned)pl.Hkv);
-  return gemm_launch<kStore, 2>(a, grid, st);
+  const dim3 grid((unsigned)pl.Hkv, (unsigned)(a.m_pad / 128),
+                  (unsigned)((n_tiles + a.tiles_per_block - 1) / a.tiles_per_block));
+  return gemm_launch<kStore>(a, grid, st);
 }
 
 // Fused filter over all n_mid keys: candidates with score >= thr[h*M + i] go to cand[(h*M + i) * cap ...],
@@ -285,8 +393,8 @@ hipError_t launch_score_gemm_filter(const Plan& pl, int n_query, const void* k_c
   a.thr = thr; a.cand = cand; a.ccount = ccount; a.cap = cap;
   const int64_t n_tiles = (pl.n_mid + kTileKeys - 1) / kTileKeys;
   a.tiles_per_block = (int)n_tiles;
-  const dim3 grid(1u, (unsigned)(a.m_pad / 128), (unsigned)pl.Hkv);
-  return gemm_launch<kFilter, 2>(a, grid, st);
+  const dim3 grid((unsigned)pl.Hkv, (unsigned)(a.m_pad / 128), 1u);
+  return gemm_launch<kFilter>(a, grid, st);
 }
 
 // Timing aid: the contraction alone (scores are neither written nor filtered).
@@ -297,8 +405,8 @@ hipError_t launch_score_gemm_discard(const Plan& pl, int n_query, const void* k_
   a.scores = sink;
   const int64_t n_tiles = (pl.n_mid + kTileKeys - 1) / kTileKeys;
   a.tiles_per_block = (int)((n_tiles + 3) / 4);
-  const dim3 grid(4u, (unsigned)(a.m_pad / 128), (unsigned)pl.Hkv);
-  return gemm_launch<kDiscard, 2>(a, grid, st);
+  const dim3 grid((unsigned)pl.Hkv, (unsigned)(a.m_pad / 128), 4u);
+  return gemm_launch<kDiscard>(a, grid, st);
 }
 
 hipError_t launch_score_gemm(const Plan& pl, const void* q, int q_first, int n_query,
