@@ -94,6 +94,7 @@ int make_plan(const reattn_params* p, Plan* out) {
   pl.off_cnt = off;    off += up(rows * (size_t)pl.nchunks * 4);
   pl.off_idx = off;    off += up((size_t)pl.M * pl.Hkv * (size_t)pl.k_eff * 4);
   pl.off_rope = off;   off += up((size_t)(rope_rows_hi(pl.S) + kRopeLo) * (pl.D / 2) * sizeof(float2));
+  pl.off_rope16 = off; off += up(attend_prefill_applies(pl) ? attend_prefill_table_bytes(pl) : 0);
   pl.off_part = off;   off += up((size_t)pl.M * pl.Hq * (size_t)pl.nsplit * (pl.D + 2) * 4);
   pl.off_qsplit = off; off += up(pl.M > 1 ? score_gemm_qsplit_bytes(pl) : 0);
   // fused prefill selection: MFMA scores filtered against sampled thresholds
@@ -137,6 +138,16 @@ int bind_ws(const Plan& pl, void* ws, size_t ws_bytes, Ws* w) {
 inline bool use_mfma(const Plan& pl) { return pl.M > 1 && pl.dtype == REATTN_BF16 && pl.D == 128; }
 
 inline int hip_rc(hipError_t e) { return e == hipSuccess ? REATTN_OK : REATTN_ERR_HIP; }
+
+// Stage 2 over the cache: chunks on bf16 / D = 128 take the MFMA kernel (one wave per query
+// and KV head), everything else the flash-decoding kernel with its split-S combine.
+int attend_cache(const Plan& pl, const Ws& w, char* ws, const void* q, const void* k_cache,
+                 const void* v_cache, const int32_t* idx, float* out, hipStream_t st) {
+  if (attend_prefill_applies(pl))
+    return hip_rc(launch_attend_prefill(pl, q, k_cache, v_cache, idx, (float2*)(ws + pl.off_rope16),
+                                        out, st));
+  return hip_rc(launch_attend(pl, true, q, 0, pl.M, k_cache, v_cache, idx, w.rope, w.part, out, st));
+}
 
 // score -> top-k for the queries [q0, q0 + nq), then the caller attends.
 // `ev`, when given, holds REATTN_N_STAGES + 1 events recorded at the stage boundaries.
@@ -205,7 +216,7 @@ int run_layer(const reattn_params* p, bool decode_only, const void* q, const voi
   if (pl.fused_prefill) {
     rc = fused_prefill_select(pl, w, (char*)ws, q, k_cache, idx, ev, st);
     if (rc) return rc;
-    rc = hip_rc(launch_attend(pl, true, q, 0, pl.M, k_cache, v_cache, idx, w.rope, w.part, out, st));
+    rc = attend_cache(pl, w, (char*)ws, q, k_cache, v_cache, idx, out, st);
     mark(ev, 4, st);
     return rc;
   }
@@ -214,7 +225,7 @@ int run_layer(const reattn_params* p, bool decode_only, const void* q, const voi
     rc = select_tile(pl, w, q, q0, nq, k_cache, idx, q0 == 0, ev, st);
     if (rc) return rc;
   }
-  rc = hip_rc(launch_attend(pl, true, q, 0, pl.M, k_cache, v_cache, idx, w.rope, w.part, out, st));
+  rc = attend_cache(pl, w, (char*)ws, q, k_cache, v_cache, idx, out, st);
   mark(ev, 4, st);
   return rc;
 }

@@ -1,0 +1,279 @@
+// Stage 2 for a prefill chunk: softmax attention of every chunk query over its own
+// [global, select_i, local up to token i] (paper Eq. 3, second line, applied per query
+// row; appendix prefilling phase, `rope_attention`), bf16 storage, D = 128.
+//
+// One wave owns one (query, KV head) pair and walks its scope in blocks of 16 slots.
+// Per block:
+//   * lane (n, j) = (lane % 16, lane / 16) fetches 64 bytes of the key row of slot n
+//     (channels 32*ks + 8*j + [0, 8) for ks = 0..3, so both members of every rotary pair
+//     (c, c + 64) sit in the same lane) and rotates them at position r = 16*b + n; the
+//     (cos, sin) of r is the product of a row of a per-block table (angle 16*b*w) and
+//     lane-constant values (angle n*w);
+//   * the logits of the (up to four) query heads of the group are one 16x16x32 bf16 MFMA
+//     chain: the A operand holds the rotary-encoded, pre-scaled queries as rows
+//     (2g, 2g+1) = (hi, lo) halves of a two-term bf16 split, the B operand the rotated key
+//     split the same way (two MFMAs per k-step), so the products carry ~16 mantissa bits
+//     and the logit of head g is the sum of two accumulator rows of the same lane;
+//   * online softmax per head in fp32 (row maxima by DPP, running sums kept per lane);
+//   * P.V on the vector ALUs with lane = two channels of the value row: the 256-byte value
+//     row of a slot is one coalesced wave load from a scalar base address, its weight comes
+//     out of the owning lane by v_readlane; the accumulators are 2 floats per head per lane.
+// Nothing is shared between waves: no LDS, no barriers, no split of a row across workgroups.
+#include "common.hpp"
+
+namespace reattn {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kBlk = 16;                     // slots per block
+constexpr float kNegBig = -1.0e30f;
+
+struct PfArgs {
+  const uint16_t* q; const uint16_t* k; const uint16_t* v;
+  const int32_t* idx; const float2* rope; float* out;
+  int64_t ksh, kst, vsh, vst, N;
+  int Hq, Hkv, G, M, S, s_eff, k_eff, l_eff, nsub;
+  int nb;                                    // rows of the per-block table: ceil(S / 16)
+  float scale_log2e;
+};
+
+// rope[row][f], f < 64: rows [0, nb) hold (cos, sin) of 16*row*w_f, rows [nb, nb + 16) those of
+// (row - nb)*w_f, w_f = theta^(-f/64).  Angles in fp64, entries correctly rounded.
+__global__ __launch_bounds__(256) void rope16_kernel(float2* rope, int nb, double log2_theta) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= (nb + kBlk) * 64) return;
+  const int row = i >> 6, f = i & 63;
+  const int r = row < nb ? row * kBlk : row - nb;
+  const double w = exp2(-(double)f / 64.0 * log2_theta);
+  double sn, cs;
+  sincos((double)r * w, &sn, &cs);
+  rope[i] = make_float2((float)cs, (float)sn);
+}
+
+__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {     // round to nearest even
+  const f32x2 v = {a, b};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
+__device__ __forceinline__ float2 cmul(float2 a, float2 b) {
+  return make_float2(a.x * b.x - a.y * b.y, a.x * b.y + a.y * b.x);
+}
+__device__ __forceinline__ float row_max16(float v) {     // max over the 16 lanes of a DPP row, in every lane
+  v = fmaxf(v, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0xB1, 0xf, 0xf, true)));
+  v = fmaxf(v, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x4E, 0xf, 0xf, true)));
+  v = fmaxf(v, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x141, 0xf, 0xf, true)));
+  v = fmaxf(v, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x140, 0xf, 0xf, true)));
+  return v;
+}
+
+// Two fp32 rows x[0..8) (channels c..c+7) and y[0..8) (channels c+64..) rotated by cs[0..8),
+// each result split into bf16 hi + lo; out: {lo-half hi, lo-half lo, hi-half hi, hi-half lo} operands.
+__device__ __forceinline__ void rotate_split(const u32x4& klo, const u32x4& khi, const float2* cs,
+                                             float mul, u32x4& a_hi, u32x4& a_lo, u32x4& b_hi,
+                                             u32x4& b_lo) {
+  const uint32_t wl[4] = {klo.x, klo.y, klo.z, klo.w}, wh[4] = {khi.x, khi.y, khi.z, khi.w};
+  uint32_t ah[4], al[4], bh[4], bl[4];
+#pragma unroll
+  for (int p = 0; p < 4; ++p) {
+    const float x0 = bf16_lo(wl[p]), x1 = bf16_hi(wl[p]), y0 = bf16_lo(wh[p]), y1 = bf16_hi(wh[p]);
+    const float2 c0 = cs[2 * p], c1 = cs[2 * p + 1];
+    const float r0 = (x0 * c0.x - y0 * c0.y) * mul, r1 = (x1 * c1.x - y1 * c1.y) * mul;   // channels c
+    const float s0 = (y0 * c0.x + x0 * c0.y) * mul, s1 = (y1 * c1.x + x1 * c1.y) * mul;   // channels c + 64
+    ah[p] = pack_bf16(r0, r1);
+    al[p] = pack_bf16(r0 - bf16_lo(ah[p]), r1 - bf16_hi(ah[p]));
+    bh[p] = pack_bf16(s0, s1);
+    bl[p] = pack_bf16(s0 - bf16_lo(bh[p]), s1 - bf16_hi(bh[p]));
+  }
+  a_hi = u32x4{ah[0], ah[1], ah[2], ah[3]}; a_lo = u32x4{al[0], al[1], al[2], al[3]};
+  b_hi = u32x4{bh[0], bh[1], bh[2], bh[3]}; b_lo = u32x4{bl[0], bl[1], bl[2], bl[3]};
+}
+
+__device__ __forceinline__ bf16x8 as_bf16x8(const u32x4& v) { return __builtin_bit_cast(bf16x8, v); }
+
+template <int GT>
+__global__ __launch_bounds__(256, 3) void attend_prefill_kernel(PfArgs a) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int n = lane & 15, j = lane >> 4;
+  const int qi = blockIdx.x * 4 + wave;
+  if (qi >= a.M) return;                                   // wave-uniform
+  const int h = blockIdx.y / a.nsub, g0 = (blockIdx.y % a.nsub) * GT;
+  const int visible = a.S - (a.M - 1 - qi);                // slots this query sees; its own key is the last
+  const int nblk = (visible + kBlk - 1) / kBlk;
+  const int32_t* my_idx = a.idx + ((int64_t)qi * a.Hkv + h) * a.k_eff;
+  const float2* t_hi = a.rope;
+  const float2* t_lo = a.rope + (int64_t)a.nb * 64;
+  const int fo = 8 * j;                                    // this lane's frequencies: fo + 32*ks2 + e
+
+  float2 tl[2][8];
+#pragma unroll
+  for (int ks2 = 0; ks2 < 2; ++ks2)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) tl[ks2][e] = t_lo[n * 64 + 32 * ks2 + fo + e];
+
+  // A operand: row m = lane % 16 -> head m / 2, half m % 2 (hi, lo) of the query rotated at the
+  // slot of its own key and scaled by softmax_scale * log2(e); rows past the group are zero.
+  bf16x8 aop[4];
+  {
+    const int g = n >> 1, part = n & 1;
+    const bool row_ok = g < GT && g0 + g < a.G;
+    const int gg = row_ok ? g0 + g : 0;
+    const uint16_t* qr = a.q + ((int64_t)qi * a.Hq + (int64_t)h * a.G + gg) * 128 + fo;
+    const int pq = visible - 1;
+    const float mul = row_ok ? a.scale_log2e : 0.f;
+#pragma unroll
+    for (int ks2 = 0; ks2 < 2; ++ks2) {
+      float2 cs[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e)
+        cs[e] = cmul(t_hi[(int64_t)(pq >> 4) * 64 + 32 * ks2 + fo + e], t_lo[(pq & 15) * 64 + 32 * ks2 + fo + e]);
+      const u32x4 lo = *(const u32x4*)(qr + 32 * ks2), hi = *(const u32x4*)(qr + 64 + 32 * ks2);
+      u32x4 ah, al, bh, bl;
+      rotate_split(lo, hi, cs, mul, ah, al, bh, bl);
+      aop[ks2] = as_bf16x8(part ? al : ah);
+      aop[ks2 + 2] = as_bf16x8(part ? bl : bh);
+    }
+  }
+
+  float m_run[GT], l_run[GT], acc[GT][2];
+#pragma unroll
+  for (int g = 0; g < GT; ++g) { m_run[g] = kNegBig; l_run[g] = 0.f; acc[g][0] = 0.f; acc[g][1] = 0.f; }
+
+  auto slot_token = [&](int r) -> int {                    // cache row of slot r (clamped into the scope)
+    const int rc = r < visible ? r : visible - 1;
+    if (rc < a.s_eff) return rc;
+    if (rc < a.s_eff + a.k_eff) return my_idx[rc - a.s_eff];
+    return (int)(a.N - a.l_eff) + (rc - a.s_eff - a.k_eff);
+  };
+  const uint16_t* kh = a.k + (int64_t)h * a.ksh + fo;
+  const char* vh = (const char*)(a.v + (int64_t)h * a.vsh) + lane * 4;
+  auto load_key = [&](int tok, u32x4* kr) {
+    const uint16_t* row = kh + (int64_t)tok * a.kst;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) kr[ks] = *(const u32x4*)(row + 32 * ks);
+  };
+
+  int tok = slot_token(n);
+  u32x4 kr[4];
+  load_key(tok, kr);
+  int tok_next = slot_token(kBlk + n);
+
+  for (int b = 0; b < nblk; ++b) {
+    // value rows of this block: one coalesced 256-byte wave load per slot, base address from the owning lane
+    uint32_t vw[kBlk];
+#pragma unroll
+    for (int s = 0; s < kBlk; ++s) {
+      const int ts = __builtin_amdgcn_readlane(tok, s);
+      vw[s] = *(const uint32_t*)(vh + (int64_t)ts * a.vst * 2);
+    }
+    // rotary factors of position 16*b + n for this lane's 16 frequencies
+    float2 cs[2][8];
+#pragma unroll
+    for (int ks2 = 0; ks2 < 2; ++ks2)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) cs[ks2][e] = cmul(t_hi[(int64_t)b * 64 + 32 * ks2 + fo + e], tl[ks2][e]);
+    // logits: 8 MFMAs (4 k-steps x (hi, lo) halves of the rotated key)
+    f32x4 c = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int ks2 = 0; ks2 < 2; ++ks2) {
+      u32x4 ah, al, bh, bl;
+      rotate_split(kr[ks2], kr[ks2 + 2], cs[ks2], 1.0f, ah, al, bh, bl);
+      c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aop[ks2], as_bf16x8(ah), c, 0, 0, 0);
+      c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aop[ks2], as_bf16x8(al), c, 0, 0, 0);
+      c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aop[ks2 + 2], as_bf16x8(bh), c, 0, 0, 0);
+      c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aop[ks2 + 2], as_bf16x8(bl), c, 0, 0, 0);
+    }
+    // the key registers are free: request the next block's rows
+    tok = tok_next;
+    if (b + 1 < nblk) load_key(tok, kr);
+    tok_next = slot_token((b + 2) * kBlk + n);
+
+    // lane (n, j) holds rows 4j .. 4j+3 of column n: heads 2j (rows 4j, 4j+1) and 2j+1
+    const float s_even = c[0] + c[1], s_odd = c[2] + c[3];
+    const bool valid = b * kBlk + n < visible;
+    float p[GT];
+    bool grew = false;
+    float m_new[GT];
+#pragma unroll
+    for (int g = 0; g < GT; ++g) {
+      float s = __shfl((g & 1) ? s_odd : s_even, n + 16 * (g >> 1), 64);
+      s = valid ? s : kNegBig;
+      m_new[g] = fmaxf(m_run[g], row_max16(s));
+      grew = grew || (m_new[g] > m_run[g]);
+      p[g] = valid ? exp2f(s - m_new[g]) : 0.f;
+    }
+    if (__any(grew)) {                                     // rare after the first blocks
+#pragma unroll
+      for (int g = 0; g < GT; ++g) {
+        const float corr = exp2f(m_run[g] - m_new[g]);
+        l_run[g] *= corr; acc[g][0] *= corr; acc[g][1] *= corr;
+        m_run[g] = m_new[g];
+      }
+    }
+#pragma unroll
+    for (int g = 0; g < GT; ++g) l_run[g] += p[g];
+    // P.V: lane = channels (2*lane, 2*lane + 1)
+#pragma unroll
+    for (int s = 0; s < kBlk; ++s) {
+      const float v0 = bf16_lo(vw[s]), v1 = bf16_hi(vw[s]);
+#pragma unroll
+      for (int g = 0; g < GT; ++g) {
+        const float ps = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, p[g]), s));
+        acc[g][0] = fmaf(ps, v0, acc[g][0]);
+        acc[g][1] = fmaf(ps, v1, acc[g][1]);
+      }
+    }
+  }
+
+#pragma unroll
+  for (int g = 0; g < GT; ++g) {
+    if (g0 + g < a.G) {
+      // every 16-lane row holds the same partial sums per n: total over the row
+      const float l_tot = group_sum<16>(l_run[g]);
+      const float inv = 1.0f / l_tot;
+      float* o = a.out + ((int64_t)qi * a.Hq + (int64_t)h * a.G + g0 + g) * 128 + 2 * lane;
+      *(float2*)o = make_float2(acc[g][0] * inv, acc[g][1] * inv);
+    }
+  }
+}
+
+}  // namespace
+
+size_t attend_prefill_table_bytes(const Plan& pl) {
+  return (size_t)((pl.S + kBlk - 1) / kBlk + kBlk) * 64 * sizeof(float2);
+}
+
+bool attend_prefill_applies(const Plan& pl) {
+  return pl.M > 1 && pl.dtype == 1 && pl.D == 128;
+}
+
+// out[i][hq] for all M queries; `table` is scratch of attend_prefill_table_bytes().
+hipError_t launch_attend_prefill(const Plan& pl, const void* q, const void* k_cache,
+                                 const void* v_cache, const int32_t* idx, float2* table, float* out,
+                                 hipStream_t st) {
+  PfArgs a;
+  a.q = (const uint16_t*)q; a.k = (const uint16_t*)k_cache; a.v = (const uint16_t*)v_cache;
+  a.idx = idx; a.rope = table; a.out = out;
+  a.ksh = pl.ksh; a.kst = pl.kst; a.vsh = pl.vsh; a.vst = pl.vst; a.N = pl.N;
+  a.Hq = pl.Hq; a.Hkv = pl.Hkv; a.G = pl.G; a.M = pl.M; a.S = pl.S;
+  a.s_eff = (int)pl.s_eff; a.k_eff = pl.k_eff; a.l_eff = (int)pl.l_eff;
+  a.nb = (pl.S + kBlk - 1) / kBlk;
+  a.scale_log2e = pl.scale * 1.4426950408889634f;
+  const int gt = pl.G < 4 ? pl.G : 4;
+  a.nsub = (pl.G + gt - 1) / gt;
+  const int n_tab = (a.nb + kBlk) * 64;
+  hipLaunchKernelGGL(rope16_kernel, dim3((n_tab + 255) / 256), dim3(256), 0, st, table, a.nb,
+                     log2((double)pl.theta));
+  const dim3 grid((unsigned)((pl.M + 3) / 4), (unsigned)(pl.Hkv * a.nsub));
+  switch (gt) {
+    case 1: hipLaunchKernelGGL((attend_prefill_kernel<1>), grid, dim3(256), 0, st, a); break;
+    case 2: hipLaunchKernelGGL((attend_prefill_kernel<2>), grid, dim3(256), 0, st, a); break;
+    case 3: hipLaunchKernelGGL((attend_prefill_kernel<3>), grid, dim3(256), 0, st, a); break;
+    default: hipLaunchKernelGGL((attend_prefill_kernel<4>), grid, dim3(256), 0, st, a); break;
+  }
+  return hipGetLastError();
+}
+
+}  // namespace reattn

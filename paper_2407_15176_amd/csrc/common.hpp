@@ -32,7 +32,7 @@ struct Plan {
   // query tile of the prefill path and workspace offsets (bytes)
   int m_tile;
   size_t off_scores, off_hist, off_pfx, off_ncand, off_cand, off_bitmap, off_cnt,
-         off_idx, off_rope, off_part, off_qsplit,
+         off_idx, off_rope, off_rope16, off_part, off_qsplit,
          off_samp, off_thr, off_pcand, off_pcount, off_redo, off_exact, total;
   bool fused_prefill;             // M > 1 on the MFMA path with sampled thresholds
 };
@@ -73,6 +73,12 @@ hipError_t launch_gather_rope(const Plan& pl, const void* k_cache, const void* v
 hipError_t launch_attend(const Plan& pl, bool fused, const void* q, int q_first, int n_query,
                          const void* k_src, const void* v_src, const int32_t* idx,
                          const float2* rope, float* part, float* out, hipStream_t st);
+
+size_t attend_prefill_table_bytes(const Plan& pl);
+bool attend_prefill_applies(const Plan& pl);
+hipError_t launch_attend_prefill(const Plan& pl, const void* q, const void* k_cache,
+                                 const void* v_cache, const int32_t* idx, float2* table, float* out,
+                                 hipStream_t st);
 
 // ---- device helpers ---------------------------------------------------------
 #ifdef __HIPCC__
