@@ -15,10 +15,13 @@
 //     split the same way (two MFMAs per k-step), so the products carry ~16 mantissa bits
 //     and the logit of head g is the sum of two accumulator rows of the same lane;
 //   * online softmax per head in fp32 (row maxima by DPP, running sums kept per lane);
-//   * P.V on the vector ALUs with lane = two channels of the value row: the 256-byte value
-//     row of a slot is one coalesced wave load from a scalar base address, its weight comes
-//     out of the owning lane by v_readlane; the accumulators are 2 floats per head per lane.
-// Nothing is shared between waves: no LDS, no barriers, no split of a row across workgroups.
+//   * P.V is a second MFMA chain (16x16x16 bf16) whose contraction index is the slot: the A
+//     operand holds the weights as rows (2g, 2g+1) = (hi, lo) bf16 halves, handed from the
+//     slot-per-lane to the row-per-lane layout through 256 bytes of wave-private LDS; the B
+//     operand needs, per lane, four consecutive slots of ONE channel, so lane (n, j) loads
+//     the channel pairs (32u + 2n, 32u + 2n + 1), u < 4, of slots 4j .. 4j+3 as dwords and
+//     regroups the 16-bit halves; the accumulators are 8 tiles x 4 registers.
+// Nothing is shared between waves: no barriers, no split of a row across workgroups.
 #include "common.hpp"
 
 namespace reattn {
@@ -28,6 +31,7 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kBlk = 16;                     // slots per block
 constexpr float kNegBig = -1.0e30f;
@@ -97,8 +101,7 @@ template <int GT>
 __global__ __launch_bounds__(256, 3) void attend_prefill_kernel(PfArgs a) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int n = lane & 15, j = lane >> 4;
-  const int qi = blockIdx.x * 4 + wave;
-  if (qi >= a.M) return;                                   // wave-uniform
+  const int qi = a.M - 1 - (blockIdx.x * 4 + wave);        // longest scopes are dispatched first
   const int h = blockIdx.y / a.nsub, g0 = (blockIdx.y % a.nsub) * GT;
   const int visible = a.S - (a.M - 1 - qi);                // slots this query sees; its own key is the last
   const int nblk = (visible + kBlk - 1) / kBlk;
@@ -107,11 +110,19 @@ __global__ __launch_bounds__(256, 3) void attend_prefill_kernel(PfArgs a) {
   const float2* t_lo = a.rope + (int64_t)a.nb * 64;
   const int fo = 8 * j;                                    // this lane's frequencies: fo + 32*ks2 + e
 
-  float2 tl[2][8];
+  // (cos, sin) of n*w for this lane's 16 frequencies: the same for all four waves, kept in LDS
+  // as 8 rows of 64 float4 (two factors each) so that a lane reads its own 16 bytes per row
+  __shared__ float4 tl_lds[8][64];
+  if (wave == 0) {
 #pragma unroll
-  for (int ks2 = 0; ks2 < 2; ++ks2)
-#pragma unroll
-    for (int e = 0; e < 8; ++e) tl[ks2][e] = t_lo[n * 64 + 32 * ks2 + fo + e];
+    for (int x = 0; x < 8; ++x) {
+      const float2 t0 = t_lo[n * 64 + 32 * (x >> 2) + fo + 2 * (x & 3)];
+      const float2 t1 = t_lo[n * 64 + 32 * (x >> 2) + fo + 2 * (x & 3) + 1];
+      tl_lds[x][lane] = make_float4(t0.x, t0.y, t1.x, t1.y);
+    }
+  }
+  __syncthreads();
+  if (qi < 0) return;                                      // wave-uniform, after the only barrier
 
   // A operand: row m = lane % 16 -> head m / 2, half m % 2 (hi, lo) of the query rotated at the
   // slot of its own key and scaled by softmax_scale * log2(e); rows past the group are zero.
@@ -137,9 +148,16 @@ __global__ __launch_bounds__(256, 3) void attend_prefill_kernel(PfArgs a) {
     }
   }
 
-  float m_run[GT], l_run[GT], acc[GT][2];
+  // weights of the current block, [head][slot], private to this wave
+  __shared__ float p_lds[4][4][kBlk];
+  float (*pw)[kBlk] = p_lds[wave];
+
+  float m_run[GT], l_run[GT];
+  f32x4 acc[8];                                            // tile t = 2u + parity: channels 32u + 2n + parity
 #pragma unroll
-  for (int g = 0; g < GT; ++g) { m_run[g] = kNegBig; l_run[g] = 0.f; acc[g][0] = 0.f; acc[g][1] = 0.f; }
+  for (int g = 0; g < GT; ++g) { m_run[g] = kNegBig; l_run[g] = 0.f; }
+#pragma unroll
+  for (int t = 0; t < 8; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
 
   auto slot_token = [&](int r) -> int {                    // cache row of slot r (clamped into the scope)
     const int rc = r < visible ? r : visible - 1;
@@ -148,7 +166,7 @@ __global__ __launch_bounds__(256, 3) void attend_prefill_kernel(PfArgs a) {
     return (int)(a.N - a.l_eff) + (rc - a.s_eff - a.k_eff);
   };
   const uint16_t* kh = a.k + (int64_t)h * a.ksh + fo;
-  const char* vh = (const char*)(a.v + (int64_t)h * a.vsh) + lane * 4;
+  const uint16_t* vh = a.v + (int64_t)h * a.vsh + 2 * n;
   auto load_key = [&](int tok, u32x4* kr) {
     const uint16_t* row = kh + (int64_t)tok * a.kst;
 #pragma unroll
@@ -159,21 +177,27 @@ __global__ __launch_bounds__(256, 3) void attend_prefill_kernel(PfArgs a) {
   u32x4 kr[4];
   load_key(tok, kr);
   int tok_next = slot_token(kBlk + n);
+  const int pg = n >> 1, ppart = n & 1;                    // A-operand row of this lane in the P.V product
 
   for (int b = 0; b < nblk; ++b) {
-    // value rows of this block: one coalesced 256-byte wave load per slot, base address from the owning lane
-    uint32_t vw[kBlk];
+    // value rows of slots 4j .. 4j+3: channel pairs (32u + 2n, +1) as dwords
+    uint32_t vw[4][4];
 #pragma unroll
-    for (int s = 0; s < kBlk; ++s) {
-      const int ts = __builtin_amdgcn_readlane(tok, s);
-      vw[s] = *(const uint32_t*)(vh + (int64_t)ts * a.vst * 2);
+    for (int i = 0; i < 4; ++i) {
+      const int ts = __shfl(tok, 4 * j + i, 64);
+      const uint16_t* row = vh + (int64_t)ts * a.vst;
+#pragma unroll
+      for (int u = 0; u < 4; ++u) vw[i][u] = *(const uint32_t*)(row + 32 * u);
     }
     // rotary factors of position 16*b + n for this lane's 16 frequencies
     float2 cs[2][8];
 #pragma unroll
-    for (int ks2 = 0; ks2 < 2; ++ks2)
-#pragma unroll
-      for (int e = 0; e < 8; ++e) cs[ks2][e] = cmul(t_hi[(int64_t)b * 64 + 32 * ks2 + fo + e], tl[ks2][e]);
+    for (int x = 0; x < 8; ++x) {
+      const float4 t = tl_lds[x][lane];
+      const int e = 2 * (x & 3), ks2 = x >> 2;
+      cs[ks2][e] = cmul(t_hi[(int64_t)b * 64 + 32 * ks2 + fo + e], make_float2(t.x, t.y));
+      cs[ks2][e + 1] = cmul(t_hi[(int64_t)b * 64 + 32 * ks2 + fo + e + 1], make_float2(t.z, t.w));
+    }
     // logits: 8 MFMAs (4 k-steps x (hi, lo) halves of the rotated key)
     f32x4 c = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -193,9 +217,8 @@ __global__ __launch_bounds__(256, 3) void attend_prefill_kernel(PfArgs a) {
     // lane (n, j) holds rows 4j .. 4j+3 of column n: heads 2j (rows 4j, 4j+1) and 2j+1
     const float s_even = c[0] + c[1], s_odd = c[2] + c[3];
     const bool valid = b * kBlk + n < visible;
-    float p[GT];
+    float p[GT], m_new[GT];
     bool grew = false;
-    float m_new[GT];
 #pragma unroll
     for (int g = 0; g < GT; ++g) {
       float s = __shfl((g & 1) ? s_odd : s_even, n + 16 * (g >> 1), 64);
@@ -205,36 +228,69 @@ __global__ __launch_bounds__(256, 3) void attend_prefill_kernel(PfArgs a) {
       p[g] = valid ? exp2f(s - m_new[g]) : 0.f;
     }
     if (__any(grew)) {                                     // rare after the first blocks
+      float corr[4] = {1.f, 1.f, 1.f, 1.f};
 #pragma unroll
       for (int g = 0; g < GT; ++g) {
-        const float corr = exp2f(m_run[g] - m_new[g]);
-        l_run[g] *= corr; acc[g][0] *= corr; acc[g][1] *= corr;
+        corr[g] = exp2f(m_run[g] - m_new[g]);
+        l_run[g] *= corr[g];
         m_run[g] = m_new[g];
       }
+      // accumulator rows 4j, 4j+1 belong to head 2j, rows 4j+2, 4j+3 to head 2j+1
+      const float ce = j == 0 ? corr[0] : (j == 1 ? corr[2] : 1.f);
+      const float co = j == 0 ? corr[1] : (j == 1 ? corr[3] : 1.f);
+#pragma unroll
+      for (int t = 0; t < 8; ++t) { acc[t][0] *= ce; acc[t][1] *= ce; acc[t][2] *= co; acc[t][3] *= co; }
     }
 #pragma unroll
     for (int g = 0; g < GT; ++g) l_run[g] += p[g];
-    // P.V: lane = channels (2*lane, 2*lane + 1)
+
+    // weights: slot-per-lane -> row-per-lane through LDS, then (hi, lo) bf16 halves by row parity
+    if (j == 0) {
 #pragma unroll
-    for (int s = 0; s < kBlk; ++s) {
-      const float v0 = bf16_lo(vw[s]), v1 = bf16_hi(vw[s]);
+      for (int g = 0; g < GT; ++g) pw[g][n] = p[g];
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    float4 pr = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (pg < GT) pr = *(const float4*)&pw[pg][4 * j];
+    uint32_t pa0 = pack_bf16(pr.x, pr.y), pa1 = pack_bf16(pr.z, pr.w);
+    if (ppart) {
+      const uint32_t l0 = pack_bf16(pr.x - bf16_lo(pa0), pr.y - bf16_hi(pa0));
+      const uint32_t l1 = pack_bf16(pr.z - bf16_lo(pa1), pr.w - bf16_hi(pa1));
+      pa0 = l0; pa1 = l1;
+    }
+    __builtin_amdgcn_wave_barrier();                        // the stage is rewritten by the next block
+    const s16x4 pop = __builtin_bit_cast(s16x4, u32x2{pa0, pa1});
 #pragma unroll
-      for (int g = 0; g < GT; ++g) {
-        const float ps = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, p[g]), s));
-        acc[g][0] = fmaf(ps, v0, acc[g][0]);
-        acc[g][1] = fmaf(ps, v1, acc[g][1]);
-      }
+    for (int u = 0; u < 4; ++u) {
+      // even channel 32u + 2n: low halves of the four slots; odd channel: high halves
+      const uint32_t e0 = (vw[0][u] & 0xffffu) | (vw[1][u] << 16), e1 = (vw[2][u] & 0xffffu) | (vw[3][u] << 16);
+      const uint32_t o0 = (vw[0][u] >> 16) | (vw[1][u] & 0xffff0000u), o1 = (vw[2][u] >> 16) | (vw[3][u] & 0xffff0000u);
+      acc[2 * u] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pop, __builtin_bit_cast(s16x4, u32x2{e0, e1}), acc[2 * u], 0, 0, 0);
+      acc[2 * u + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pop, __builtin_bit_cast(s16x4, u32x2{o0, o1}), acc[2 * u + 1], 0, 0, 0);
     }
   }
 
+  // out[g][c] = (row 2g + row 2g+1) / l: lane (n, j) holds heads 2j, 2j+1 at channels 32u + 2n + parity
+  float l_tot[GT];
 #pragma unroll
-  for (int g = 0; g < GT; ++g) {
-    if (g0 + g < a.G) {
-      // every 16-lane row holds the same partial sums per n: total over the row
-      const float l_tot = group_sum<16>(l_run[g]);
-      const float inv = 1.0f / l_tot;
-      float* o = a.out + ((int64_t)qi * a.Hq + (int64_t)h * a.G + g0 + g) * 128 + 2 * lane;
-      *(float2*)o = make_float2(acc[g][0] * inv, acc[g][1] * inv);
+  for (int g = 0; g < GT; ++g) l_tot[g] = group_sum<16>(l_run[g]);   // every 16-lane row holds the same partials per n
+  if (j < 2) {
+#pragma unroll
+    for (int gg = 0; gg < 2; ++gg) {
+      const int g = 2 * j + gg;
+      if (g < GT && g0 + g < a.G) {
+        float lt = l_tot[0];
+#pragma unroll
+        for (int x = 1; x < GT; ++x) lt = (g == x) ? l_tot[x] : lt;
+        const float inv = 1.0f / lt;
+        float* o = a.out + ((int64_t)qi * a.Hq + (int64_t)h * a.G + g0 + g) * 128 + 2 * n;
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+          *(float2*)(o + 32 * u) = make_float2((acc[2 * u][2 * gg] + acc[2 * u][2 * gg + 1]) * inv,
+                                               (acc[2 * u + 1][2 * gg] + acc[2 * u + 1][2 * gg + 1]) * inv);
+      }
     }
   }
 }
