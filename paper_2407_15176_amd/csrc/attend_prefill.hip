@@ -97,8 +97,66 @@ __device__ __forceinline__ void rotate_split(const u32x4& klo, const u32x4& khi,
 
 __device__ __forceinline__ bf16x8 as_bf16x8(const u32x4& v) { return __builtin_bit_cast(bf16x8, v); }
 
+// (cos, sin) of position 16*b + n for the 16 frequencies of lane (n, j): per-block row times the
+// lane's own factors (tl: 8 x float4 = two factors each, as kept in LDS by the attention kernel).
+template <typename LaneFactors>
+__device__ __forceinline__ void block_factors(const float2* t_hi_row, LaneFactors tl, float2 (*cs)[8]) {
+#pragma unroll
+  for (int x = 0; x < 8; ++x) {
+    const float4 t = tl(x);
+    const int e = 2 * (x & 3), ks2 = x >> 2;
+    cs[ks2][e] = cmul(t_hi_row[32 * ks2 + e], make_float2(t.x, t.y));
+    cs[ks2][e + 1] = cmul(t_hi_row[32 * ks2 + e + 1], make_float2(t.z, t.w));
+  }
+}
+
+// B operands of the logit MFMAs from a raw key row: ops[4*ks2 + {0,1,2,3}] = {hi, lo} halves of the
+// rotated channels 32*ks2 + 8j + e, then of the channels 64 higher.
+__device__ __forceinline__ void key_operands(const u32x4* kr, const float2 (*cs)[8], u32x4* ops) {
+#pragma unroll
+  for (int ks2 = 0; ks2 < 2; ++ks2)
+    rotate_split(kr[ks2], kr[ks2 + 2], cs[ks2], 1.0f, ops[4 * ks2], ops[4 * ks2 + 1], ops[4 * ks2 + 2],
+                 ops[4 * ks2 + 3]);
+}
+
+// The local window's slots s + k + t hold the same key at the same position for every query of
+// the chunk, so their MFMA operands are formed once: pre[h][lb][x][lane], block b = b0 + lb.
+__global__ __launch_bounds__(64) void local_keys_kernel(PfArgs a, int b0, u32x4* pre) {
+  const int lane = threadIdx.x, n = lane & 15, j = lane >> 4;
+  const int lb = blockIdx.x, h = blockIdx.y, b = b0 + lb;
+  const int r = b * kBlk + n;
+  const float2* t_hi = a.rope;
+  const float2* t_lo = a.rope + (int64_t)a.nb * 64;
+  const int fo = 8 * j;
+  u32x4 ops[8];
+  if (r < a.S) {
+    float4 tl[8];
+#pragma unroll
+    for (int x = 0; x < 8; ++x) {
+      const float2 t0 = t_lo[n * 64 + 32 * (x >> 2) + fo + 2 * (x & 3)];
+      const float2 t1 = t_lo[n * 64 + 32 * (x >> 2) + fo + 2 * (x & 3) + 1];
+      tl[x] = make_float4(t0.x, t0.y, t1.x, t1.y);
+    }
+    float2 cs[2][8];
+    block_factors(t_hi + (int64_t)b * 64 + fo, [&](int x) { return tl[x]; }, cs);
+    const int64_t tok = a.N - a.l_eff + (r - a.s_eff - a.k_eff);
+    const uint16_t* row = a.k + (int64_t)h * a.ksh + tok * a.kst + fo;
+    u32x4 kr[4];
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) kr[ks] = *(const u32x4*)(row + 32 * ks);
+    key_operands(kr, cs, ops);
+  } else {
+#pragma unroll
+    for (int x = 0; x < 8; ++x) ops[x] = u32x4{0u, 0u, 0u, 0u};
+  }
+  u32x4* o = pre + (((int64_t)h * gridDim.x + lb) * 8) * 64 + lane;
+#pragma unroll
+  for (int x = 0; x < 8; ++x) o[x * 64] = ops[x];
+}
+
 template <int GT>
-__global__ __launch_bounds__(256, 3) void attend_prefill_kernel(PfArgs a) {
+__global__ __launch_bounds__(256, 2) void attend_prefill_kernel(PfArgs a, int b_local0, int n_lb,
+                                                                const u32x4* __restrict__ pre) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int n = lane & 15, j = lane >> 4;
   const int qi = a.M - 1 - (blockIdx.x * 4 + wave);        // longest scopes are dispatched first
@@ -172,68 +230,49 @@ __global__ __launch_bounds__(256, 3) void attend_prefill_kernel(PfArgs a) {
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) kr[ks] = *(const u32x4*)(row + 32 * ks);
   };
-
-  int tok = slot_token(n);
-  u32x4 kr[4];
-  load_key(tok, kr);
-  int tok_next = slot_token(kBlk + n);
-  const int pg = n >> 1, ppart = n & 1;                    // A-operand row of this lane in the P.V product
-
-  for (int b = 0; b < nblk; ++b) {
-    // value rows of slots 4j .. 4j+3: channel pairs (32u + 2n, +1) as dwords
-    uint32_t vw[4][4];
+  auto load_values = [&](const int* ts, uint32_t (*vw)[4]) {   // slots 4j .. 4j+3: channel pairs (32u + 2n, +1)
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const int ts = __shfl(tok, 4 * j + i, 64);
-      const uint16_t* row = vh + (int64_t)ts * a.vst;
+      const uint16_t* row = vh + (int64_t)ts[i] * a.vst;
 #pragma unroll
       for (int u = 0; u < 4; ++u) vw[i][u] = *(const uint32_t*)(row + 32 * u);
     }
-    // rotary factors of position 16*b + n for this lane's 16 frequencies
-    float2 cs[2][8];
-#pragma unroll
-    for (int x = 0; x < 8; ++x) {
-      const float4 t = tl_lds[x][lane];
-      const int e = 2 * (x & 3), ks2 = x >> 2;
-      cs[ks2][e] = cmul(t_hi[(int64_t)b * 64 + 32 * ks2 + fo + e], make_float2(t.x, t.y));
-      cs[ks2][e + 1] = cmul(t_hi[(int64_t)b * 64 + 32 * ks2 + fo + e + 1], make_float2(t.z, t.w));
-    }
-    // logits: 8 MFMAs (4 k-steps x (hi, lo) halves of the rotated key)
+  };
+  const int pg = n >> 1, ppart = n & 1;                    // A-operand row of this lane in the P.V product
+
+  // logits of one block from its 8 key operands
+  auto logits = [&](const u32x4* ops) -> f32x4 {
     f32x4 c = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int ks2 = 0; ks2 < 2; ++ks2) {
-      u32x4 ah, al, bh, bl;
-      rotate_split(kr[ks2], kr[ks2 + 2], cs[ks2], 1.0f, ah, al, bh, bl);
-      c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aop[ks2], as_bf16x8(ah), c, 0, 0, 0);
-      c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aop[ks2], as_bf16x8(al), c, 0, 0, 0);
-      c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aop[ks2 + 2], as_bf16x8(bh), c, 0, 0, 0);
-      c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aop[ks2 + 2], as_bf16x8(bl), c, 0, 0, 0);
+      c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aop[ks2], as_bf16x8(ops[4 * ks2]), c, 0, 0, 0);
+      c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aop[ks2], as_bf16x8(ops[4 * ks2 + 1]), c, 0, 0, 0);
+      c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aop[ks2 + 2], as_bf16x8(ops[4 * ks2 + 2]), c, 0, 0, 0);
+      c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aop[ks2 + 2], as_bf16x8(ops[4 * ks2 + 3]), c, 0, 0, 0);
     }
-    // the key registers are free: request the next block's rows
-    tok = tok_next;
-    if (b + 1 < nblk) load_key(tok, kr);
-    tok_next = slot_token((b + 2) * kBlk + n);
-
+    return c;
+  };
+  // online softmax of the block's logits and P.V
+  auto finish_block = [&](int b, const f32x4& c, const uint32_t (*vw)[4]) {
     // lane (n, j) holds rows 4j .. 4j+3 of column n: heads 2j (rows 4j, 4j+1) and 2j+1
     const float s_even = c[0] + c[1], s_odd = c[2] + c[3];
     const bool valid = b * kBlk + n < visible;
-    float p[GT], m_new[GT];
+    float sg[GT];
     bool grew = false;
 #pragma unroll
     for (int g = 0; g < GT; ++g) {
-      float s = __shfl((g & 1) ? s_odd : s_even, n + 16 * (g >> 1), 64);
-      s = valid ? s : kNegBig;
-      m_new[g] = fmaxf(m_run[g], row_max16(s));
-      grew = grew || (m_new[g] > m_run[g]);
-      p[g] = valid ? exp2f(s - m_new[g]) : 0.f;
+      const float s = __shfl((g & 1) ? s_odd : s_even, n + 16 * (g >> 1), 64);
+      sg[g] = valid ? s : kNegBig;
+      grew = grew || (sg[g] > m_run[g]);
     }
-    if (__any(grew)) {                                     // rare after the first blocks
+    if (__any(grew)) {                                     // a new maximum: rare after the first blocks
       float corr[4] = {1.f, 1.f, 1.f, 1.f};
 #pragma unroll
       for (int g = 0; g < GT; ++g) {
-        corr[g] = exp2f(m_run[g] - m_new[g]);
+        const float m_new = fmaxf(m_run[g], row_max16(sg[g]));
+        corr[g] = __builtin_amdgcn_exp2f(m_run[g] - m_new);
         l_run[g] *= corr[g];
-        m_run[g] = m_new[g];
+        m_run[g] = m_new;
       }
       // accumulator rows 4j, 4j+1 belong to head 2j, rows 4j+2, 4j+3 to head 2j+1
       const float ce = j == 0 ? corr[0] : (j == 1 ? corr[2] : 1.f);
@@ -241,9 +280,12 @@ __global__ __launch_bounds__(256, 3) void attend_prefill_kernel(PfArgs a) {
 #pragma unroll
       for (int t = 0; t < 8; ++t) { acc[t][0] *= ce; acc[t][1] *= ce; acc[t][2] *= co; acc[t][3] *= co; }
     }
+    float p[GT];
 #pragma unroll
-    for (int g = 0; g < GT; ++g) l_run[g] += p[g];
-
+    for (int g = 0; g < GT; ++g) {
+      p[g] = __builtin_amdgcn_exp2f(sg[g] - m_run[g]);      // invalid slots: 2^(-1e30) = 0
+      l_run[g] += p[g];
+    }
     // weights: slot-per-lane -> row-per-lane through LDS, then (hi, lo) bf16 halves by row parity
     if (j == 0) {
 #pragma unroll
@@ -265,10 +307,63 @@ __global__ __launch_bounds__(256, 3) void attend_prefill_kernel(PfArgs a) {
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       // even channel 32u + 2n: low halves of the four slots; odd channel: high halves
-      const uint32_t e0 = (vw[0][u] & 0xffffu) | (vw[1][u] << 16), e1 = (vw[2][u] & 0xffffu) | (vw[3][u] << 16);
-      const uint32_t o0 = (vw[0][u] >> 16) | (vw[1][u] & 0xffff0000u), o1 = (vw[2][u] >> 16) | (vw[3][u] & 0xffff0000u);
+      const uint32_t e0 = __builtin_amdgcn_perm(vw[1][u], vw[0][u], 0x05040100u);
+      const uint32_t e1 = __builtin_amdgcn_perm(vw[3][u], vw[2][u], 0x05040100u);
+      const uint32_t o0 = __builtin_amdgcn_perm(vw[1][u], vw[0][u], 0x07060302u);
+      const uint32_t o1 = __builtin_amdgcn_perm(vw[3][u], vw[2][u], 0x07060302u);
       acc[2 * u] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pop, __builtin_bit_cast(s16x4, u32x2{e0, e1}), acc[2 * u], 0, 0, 0);
       acc[2 * u + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pop, __builtin_bit_cast(s16x4, u32x2{o0, o1}), acc[2 * u + 1], 0, 0, 0);
+    }
+  };
+
+  // ---- phase 1: blocks with sink or selected slots: gather, rotate, split -----------------
+  const int b_gen = nblk < b_local0 ? nblk : b_local0;
+  if (b_gen > 0) {
+    int tok = slot_token(n);
+    u32x4 kr[4];
+    load_key(tok, kr);
+    int tok_next = slot_token(kBlk + n);
+    for (int b = 0; b < b_gen; ++b) {
+      uint32_t vw[4][4];
+      int ts[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) ts[i] = __shfl(tok, 4 * j + i, 64);
+      load_values(ts, vw);
+      float2 cs[2][8];
+      block_factors(t_hi + (int64_t)b * 64 + fo, [&](int x) { return tl_lds[x][lane]; }, cs);
+      u32x4 ops[8];
+      key_operands(kr, cs, ops);
+      // the key registers are free: request the next block's rows
+      tok = tok_next;
+      if (b + 1 < b_gen) load_key(tok, kr);
+      tok_next = slot_token((b + 2) * kBlk + n);
+      const f32x4 c = logits(ops);
+      finish_block(b, c, vw);
+    }
+  }
+  // ---- phase 2: blocks of the local window: operands formed once for the whole chunk -------
+  if (nblk > b_local0) {
+    const u32x4* pp = pre + ((int64_t)h * n_lb * 8) * 64 + lane;
+    const int tok0 = (int)(a.N - a.l_eff) - a.s_eff - a.k_eff;   // token of slot r is tok0 + r
+    u32x4 ops[8];
+#pragma unroll
+    for (int x = 0; x < 8; ++x) ops[x] = pp[x * 64];
+    for (int b = b_local0; b < nblk; ++b) {
+      uint32_t vw[4][4];
+      int ts[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int r = b * kBlk + 4 * j + i;
+        ts[i] = tok0 + (r < visible ? r : visible - 1);
+      }
+      load_values(ts, vw);
+      const f32x4 c = logits(ops);
+      if (b + 1 < nblk) {                                   // the operand registers are free again
+        const u32x4* nx = pp + (int64_t)(b + 1 - b_local0) * 8 * 64;
+#pragma unroll
+        for (int x = 0; x < 8; ++x) ops[x] = nx[x * 64];
+      }
+      finish_block(b, c, vw);
     }
   }
 
@@ -297,8 +392,17 @@ __global__ __launch_bounds__(256, 3) void attend_prefill_kernel(PfArgs a) {
 
 }  // namespace
 
+namespace {
+inline int pf_blocks(const Plan& pl) { return (pl.S + kBlk - 1) / kBlk; }
+inline int pf_local0(const Plan& pl) { return (int)((pl.s_eff + pl.k_eff + kBlk - 1) / kBlk); }
+}  // namespace
+
+// Scratch of the chunk attention: rotary tables, then the local window's key operands.
 size_t attend_prefill_table_bytes(const Plan& pl) {
-  return (size_t)((pl.S + kBlk - 1) / kBlk + kBlk) * 64 * sizeof(float2);
+  const size_t table = (size_t)(pf_blocks(pl) + kBlk) * 64 * sizeof(float2);
+  const int n_lb = pf_blocks(pl) - pf_local0(pl);
+  const size_t pre = n_lb > 0 ? (size_t)pl.Hkv * n_lb * 8 * 64 * 16 : 0;
+  return (table + 255) / 256 * 256 + pre;
 }
 
 bool attend_prefill_applies(const Plan& pl) {
@@ -315,19 +419,26 @@ hipError_t launch_attend_prefill(const Plan& pl, const void* q, const void* k_ca
   a.ksh = pl.ksh; a.kst = pl.kst; a.vsh = pl.vsh; a.vst = pl.vst; a.N = pl.N;
   a.Hq = pl.Hq; a.Hkv = pl.Hkv; a.G = pl.G; a.M = pl.M; a.S = pl.S;
   a.s_eff = (int)pl.s_eff; a.k_eff = pl.k_eff; a.l_eff = (int)pl.l_eff;
-  a.nb = (pl.S + kBlk - 1) / kBlk;
+  a.nb = pf_blocks(pl);
   a.scale_log2e = pl.scale * 1.4426950408889634f;
   const int gt = pl.G < 4 ? pl.G : 4;
   a.nsub = (pl.G + gt - 1) / gt;
   const int n_tab = (a.nb + kBlk) * 64;
   hipLaunchKernelGGL(rope16_kernel, dim3((n_tab + 255) / 256), dim3(256), 0, st, table, a.nb,
                      log2((double)pl.theta));
+  const int b_local0 = pf_local0(pl);
+  const int n_lb = a.nb - b_local0 > 0 ? a.nb - b_local0 : 0;
+  const size_t table_bytes = ((size_t)n_tab * sizeof(float2) + 255) / 256 * 256;
+  u32x4* pre = (u32x4*)((char*)table + table_bytes);
+  if (n_lb > 0)
+    hipLaunchKernelGGL(local_keys_kernel, dim3((unsigned)n_lb, (unsigned)pl.Hkv), dim3(64), 0, st, a,
+                       b_local0, pre);
   const dim3 grid((unsigned)((pl.M + 3) / 4), (unsigned)(pl.Hkv * a.nsub));
   switch (gt) {
-    case 1: hipLaunchKernelGGL((attend_prefill_kernel<1>), grid, dim3(256), 0, st, a); break;
-    case 2: hipLaunchKernelGGL((attend_prefill_kernel<2>), grid, dim3(256), 0, st, a); break;
-    case 3: hipLaunchKernelGGL((attend_prefill_kernel<3>), grid, dim3(256), 0, st, a); break;
-    default: hipLaunchKernelGGL((attend_prefill_kernel<4>), grid, dim3(256), 0, st, a); break;
+    case 1: hipLaunchKernelGGL((attend_prefill_kernel<1>), grid, dim3(256), 0, st, a, b_local0, n_lb, pre); break;
+    case 2: hipLaunchKernelGGL((attend_prefill_kernel<2>), grid, dim3(256), 0, st, a, b_local0, n_lb, pre); break;
+    case 3: hipLaunchKernelGGL((attend_prefill_kernel<3>), grid, dim3(256), 0, st, a, b_local0, n_lb, pre); break;
+    default: hipLaunchKernelGGL((attend_prefill_kernel<4>), grid, dim3(256), 0, st, a, b_local0, n_lb, pre); break;
   }
   return hipGetLastError();
 }
