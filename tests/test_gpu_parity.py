@@ -272,3 +272,23 @@ def test_prefill_chunk_mixed_redo_rows():
     t["q"][66].zero_()
     out, idx = P.run_layer(w, t)
     P.check_layer(w, t, out, idx, q_rows=[0, 3, 4, 65, 66, 69])
+
+
+@pytest.mark.parametrize("kw", [
+    dict(n_q_heads=8, n_kv_heads=8, n_query=33, n_ctx=6_000, n_local=100, top_k=37),      # G = 1
+    dict(n_q_heads=4, n_kv_heads=2, n_query=20, n_ctx=5_000, n_local=64, top_k=200),      # G = 2
+    dict(n_q_heads=10, n_kv_heads=2, n_query=19, n_ctx=7_000, n_local=90, top_k=150),     # G = 5: two passes (4 + 1)
+    dict(n_q_heads=8, n_kv_heads=1, n_query=40, n_ctx=4_000, n_local=128, top_k=60),      # G = 8: two passes
+    dict(n_query=50, n_ctx=3_000, n_local=50, top_k=0),            # no selected slots; M = l: query 0 sees sink + itself
+    dict(n_query=16, n_ctx=40, n_local=512, top_k=64),             # empty middle: causal attention over all 40 tokens
+    dict(n_query=7, n_ctx=2_000, n_sink=0, n_local=16, top_k=16),  # no sink, s + k a multiple of 16
+    dict(n_query=64, n_ctx=9_000, n_local=1_000, top_k=5),         # the local window dominates the scope
+])
+def test_prefill_chunk_mfma_attention_shapes(kw):
+    """bf16, D = 128, M > 1: the matrix-core attention kernel across group sizes, empty parts of
+    the scope and block boundaries that fall inside / on the edge of the local window."""
+    w = wl.CONFIGS[4].scaled(max_position=0, **kw)
+    t = gen(w)
+    out, idx = P.run_layer(w, t)
+    r = P.check_layer(w, t, out, idx)
+    assert r["max_abs_err"] <= 2e-3          # the hi/lo-split MFMA path stays far inside the 2e-2 bar
