@@ -26,10 +26,22 @@
  *  - ties: higher score first, then lower index;
  *  - k larger than the middle is clamped; an empty middle means plain attention.
  *
+ * Vote selection (paper, "Full-Context Cache Selection", last paragraph; Setup: k = 4,
+ * k' = 127, span 32), readings:
+ *  - every (query row, query HEAD) casts one vote for each of its own top-k middle
+ *    tokens by raw score (no group sum here);
+ *  - votes of all heads and all query rows of the chunk are pooled: one set per layer;
+ *  - the k' centres are the tokens with the most votes (ties: lower index), zero-vote
+ *    tokens are never centres;
+ *  - the span of centre c is the m consecutive tokens [c - m/2, c - m/2 + m) clipped to
+ *    the middle; the selection is the union of the spans, ascending.
+ *
  * Pins (tests/test_oracle_pins.py): brute-force causal RoPE attention when k
  * covers the middle, rotary closed forms / norm / shift invariance, hand-written
  * top-k toys + argsort brute force, softmax mean/convexity, GQA reductions,
- * exact bf16 widening.  Nothing here is "parity unpinned" except the use of the
+ * exact bf16 widening; vote selection: hand-written toys, an independent
+ * dictionary-and-sort restatement, reductions to plain top-k and to full attention,
+ * needle spans.  Nothing here is "parity unpinned" except the use of the
  * sum aggregation itself, which is a reading (see above), not a computed value.
  */
 #include <math.h>
@@ -159,6 +171,73 @@ int ro_topk(const double* scores, int64_t n_rows, int64_t n_mid, int64_t k_eff,
     }
   }
   return rc;
+}
+
+/* ---- vote selection over heads and query rows ----------------------------- */
+/* Per-head scores: scores[i][hq][j - s] = sum_c q[i][hq][c] * K[hq/G][j][c], j in middle. */
+int ro_head_scores(const ro_shape* sh, int32_t n_query, const void* q, const void* k_cache,
+                   double* scores) {
+  int64_t s, l, mid, k;
+  ro_partition(sh->n_ctx, sh->n_sink, sh->n_local, sh->top_k, &s, &l, &mid, &k);
+  const int Hq = sh->n_q_heads, Hkv = sh->n_kv_heads, D = sh->head_dim, G = Hq / Hkv;
+  if (Hq % Hkv) return -1;
+  for (int i = 0; i < n_query; ++i)
+    for (int hq = 0; hq < Hq; ++hq) {
+      double* row = scores + ((int64_t)i * Hq + hq) * mid;
+      const int64_t qoff = ((int64_t)i * Hq + hq) * D;
+#pragma omp parallel for schedule(static)
+      for (int64_t j = 0; j < mid; ++j) {
+        const int64_t koff = (int64_t)(hq / G) * sh->k_stride_head + (s + j) * sh->k_stride_tok;
+        double dot = 0.0;
+        for (int c = 0; c < D; ++c)
+          dot += ro_load(q, qoff + c, sh->dtype) * ro_load(k_cache, koff + c, sh->dtype);
+        row[j] = dot;
+      }
+    }
+  return 0;
+}
+
+typedef struct { int32_t votes; int64_t j; } ro_vote;
+static int ro_cmp_votes_desc(const void* a, const void* b) {
+  const ro_vote* x = a; const ro_vote* y = b;
+  if (x->votes != y->votes) return x->votes > y->votes ? -1 : 1;
+  return (x->j > y->j) - (x->j < y->j);  /* equal votes: lower index first */
+}
+
+/* head_topk: [n_rows][vote_k] absolute indices (the top-k list of every (query row, head));
+ * votes: [n_mid] out (may be NULL); centres: [n_centres] out, ascending, padded with -1;
+ * sel: [n_centres * span] out, ascending absolute indices; *n_sel their number. */
+int ro_vote_merge(const int32_t* head_topk, int64_t n_rows, int64_t vote_k, int64_t n_mid,
+                  int64_t index_base, int64_t n_centres, int64_t span, int32_t* votes,
+                  int32_t* centres, int32_t* sel, int64_t* n_sel) {
+  *n_sel = 0;
+  for (int64_t c = 0; c < n_centres; ++c) centres[c] = -1;
+  if (n_mid <= 0 || n_centres <= 0 || span <= 0) return 0;
+  ro_vote* v = (ro_vote*)malloc((size_t)n_mid * sizeof *v);
+  unsigned char* keep = (unsigned char*)calloc((size_t)n_mid, 1);
+  if (!v || !keep) { free(v); free(keep); return -2; }
+  for (int64_t j = 0; j < n_mid; ++j) { v[j].votes = 0; v[j].j = j; }
+  for (int64_t r = 0; r < n_rows; ++r)                      /* every head and query row votes */
+    for (int64_t t = 0; t < vote_k; ++t) {
+      const int64_t j = (int64_t)head_topk[r * vote_k + t] - index_base;
+      if (j < 0 || j >= n_mid) { free(v); free(keep); return -3; }
+      v[j].votes += 1;
+    }
+  if (votes) for (int64_t j = 0; j < n_mid; ++j) votes[j] = v[j].votes;
+  qsort(v, (size_t)n_mid, sizeof *v, ro_cmp_votes_desc);    /* most votes first */
+  int64_t nc = 0;
+  for (int64_t r = 0; r < n_mid && nc < n_centres && v[r].votes > 0; ++r) {
+    const int64_t c = v[r].j;
+    centres[nc++] = (int32_t)(index_base + c);
+    const int64_t lo = c - span / 2, hi = lo + span;        /* m neighbouring entries as a whole */
+    for (int64_t j = lo < 0 ? 0 : lo; j < hi && j < n_mid; ++j) keep[j] = 1;   /* overlaps deduplicated */
+  }
+  qsort(centres, (size_t)nc, sizeof *centres, ro_cmp_i32);
+  int64_t n = 0;
+  for (int64_t j = 0; j < n_mid; ++j) if (keep[j]) sel[n++] = (int32_t)(index_base + j);
+  *n_sel = n;
+  free(v); free(keep);
+  return 0;
 }
 
 /* ---- Eq. 3: rotary embedding at a re-assigned position ------------------- */

@@ -94,6 +94,9 @@ def _lib():
         lib.ro_gather_rope.restype = C.c_int64
         lib.ro_attend.argtypes = [P, C.c_int32, P, P, P, P, P, C.c_double, P]
         lib.ro_forward.argtypes = [P, C.c_int32, P, P, P, P, P, P, P, P]
+        lib.ro_head_scores.argtypes = [P, C.c_int32, P, P, P]
+        lib.ro_vote_merge.argtypes = [P, C.c_int64, C.c_int64, C.c_int64, C.c_int64, C.c_int64, C.c_int64,
+                                      P, P, P, P]
         _cached = lib
     return _cached
 
@@ -195,3 +198,50 @@ def forward(sh: Shape, q, k_cache, v_cache, q_tok=None, want_scores: bool = Fals
     _check_rc(_lib().ro_forward(C.byref(cs), M, _ptr(q), _ptr(qt), _ptr(k_cache), _ptr(v_cache),
                                 _ptr(idx), _ptr(kth), _ptr(sc), _ptr(out)), "forward")
     return {"idx": idx, "kth": kth, "out": out, "scores": sc}
+
+
+# ---- vote selection (paper: votes over heads and query rows, top-k' centres, spans) ----------
+def head_scores(sh: Shape, q: np.ndarray, k_cache: np.ndarray) -> np.ndarray:
+    """Per-head raw scores: q [M,Hq,D], K [Hkv,N,D] -> float64 [M,Hq,N_mid]."""
+    _check_store(q, sh, "q"); _check_store(k_cache, sh, "k_cache")
+    M = q.shape[0]
+    _, _, n_mid, _ = sh.partition()
+    out = np.empty((M, sh.n_q_heads, n_mid), dtype=np.float64)
+    cs = sh.c()
+    _check_rc(_lib().ro_head_scores(C.byref(cs), M, _ptr(q), _ptr(k_cache), _ptr(out)), "head_scores")
+    return out
+
+
+def vote_merge(head_topk: np.ndarray, n_mid: int, index_base: int, n_centres: int, span: int):
+    """head_topk int32 [R, vote_k] absolute -> dict(votes [n_mid], centres [<=n_centres], sel [n_sel])."""
+    head_topk = np.ascontiguousarray(head_topk, dtype=np.int32)
+    R, vote_k = head_topk.shape
+    votes = np.zeros((max(n_mid, 0),), dtype=np.int32)
+    centres = np.full((max(n_centres, 0),), -1, dtype=np.int32)
+    sel = np.empty((max(n_centres * span, 1),), dtype=np.int32)
+    n_sel = C.c_int64(0)
+    _check_rc(_lib().ro_vote_merge(_ptr(head_topk), R, vote_k, n_mid, index_base, n_centres, span,
+                                   _ptr(votes), _ptr(centres), _ptr(sel), C.byref(n_sel)), "vote_merge")
+    return {"votes": votes, "centres": centres[centres >= 0], "sel": sel[:n_sel.value].copy()}
+
+
+def vote_forward(sh: Shape, q, k_cache, v_cache, vote_k: int, n_centres: int, span: int, q_tok=None,
+                 head_topk=None):
+    """Whole step with the vote selection: per-head top-k -> votes -> centres -> spans ->
+    attention of every query row over [global, shared selection, local].  `head_topk`
+    (int32 [M,Hq,vote_k]) replaces the oracle's own per-head lists when given.
+    Returns dict(head_topk, head_kth [M,Hq], votes, centres, sel, out [M,Hq,D], head_scores)."""
+    M = q.shape[0]
+    s_eff, l_eff, n_mid, _ = sh.partition()
+    hs = head_scores(sh, q, k_cache)
+    kk = max(0, min(vote_k, n_mid))
+    own, kth = topk_rows(hs.reshape(M * sh.n_q_heads, n_mid), kk, index_base=s_eff)
+    lists = own if head_topk is None else np.ascontiguousarray(head_topk, dtype=np.int32).reshape(own.shape)
+    m = vote_merge(lists, n_mid, s_eff, n_centres, span)
+    sel = m["sel"]
+    from dataclasses import replace as _replace
+    sh2 = _replace(sh, top_k=int(sel.size))
+    idx = np.broadcast_to(sel, (M, sh.n_kv_heads, sel.size)).copy()
+    out = attend(sh2, q, k_cache, v_cache, idx, q_tok=q_tok)
+    return {"head_topk": own.reshape(M, sh.n_q_heads, kk), "head_kth": kth.reshape(M, sh.n_q_heads),
+            "votes": m["votes"], "centres": m["centres"], "sel": sel, "out": out, "head_scores": hs}

@@ -10,7 +10,11 @@ fixed by the paper or by mathematics, not to the oracle itself.
   * selection       -> planted needles are always selected; sets ascending, in range;
   * softmax / PV    -> q = 0 gives the mean of the kept V rows; convexity bounds;
   * aggregation     -> G = 1 equals single-head Eq. 2; duplicating a head doubles scores;
-  * storage         -> bf16 bit patterns widen exactly.
+  * storage         -> bf16 bit patterns widen exactly;
+  * vote selection  -> hand-written toys from tests/golden/vote_toys.txt, an independent Counter/sort
+                       restatement on random lists, per-head scores against their einsum definition,
+                       reduction to plain top-k (one head, k' = k, m = 1), reduction to full attention
+                       (one span wider than the middle), needle spans kept whole.
 """
 import math
 import os
@@ -359,3 +363,114 @@ def test_group_sum_mixes_heads():
         a = f64(k)[h, s:N - l] @ f64(q)[0, 2 * h]
         b = f64(k)[h, s:N - l] @ f64(q)[0, 2 * h + 1]
         assert np.abs(scm[0, h] - np.maximum(a, b)).max() < 1e-13
+
+
+# ------------------------------------------------ vote selection (heads and query rows vote)
+def _read_golden_votes(path):
+    cases, cur = [], {}
+    for line in open(path):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        key, val = line.split(":", 1)
+        if key == "lists":
+            if cur:
+                cases.append(cur)
+            cur = {"lists": [[int(x) for x in part.split()] for part in val.split("|")]}
+        elif key.startswith("expect"):
+            cur[key] = [int(x) for x in val.split()]
+        else:
+            cur[key] = int(val)
+    cases.append(cur)
+    return cases
+
+
+def test_vote_merge_hand_written_toys():
+    cases = _read_golden_votes(os.path.join(GOLDEN, "vote_toys.txt"))
+    assert len(cases) == 5
+    for c in cases:
+        r = ro.vote_merge(np.array(c["lists"], dtype=np.int32), c["n_mid"], c["base"], c["centres"], c["span"])
+        assert r["centres"].tolist() == c["expect_centres"], c
+        assert r["sel"].tolist() == c["expect_sel"], c
+
+
+def _brute_vote_merge(lists, n_mid, base, n_centres, span):
+    """Independent restatement with a dictionary of counts and Python sorting."""
+    from collections import Counter
+    cnt = Counter(int(t) for row in lists for t in row)
+    ranked = sorted(cnt.items(), key=lambda kv: (-kv[1], kv[0]))[:n_centres]
+    centres = sorted(t for t, _ in ranked)
+    keep = set()
+    for c in centres:
+        lo = c - span // 2
+        keep.update(t for t in range(lo, lo + span) if base <= t < base + n_mid)
+    return centres, sorted(keep), cnt
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_vote_merge_brute_force(seed):
+    rng = np.random.default_rng(100 + seed)
+    n_mid, base = int(rng.integers(30, 400)), int(rng.integers(0, 9))
+    rows, vote_k = int(rng.integers(1, 40)), int(rng.integers(1, 6))
+    # few distinct tokens so that vote ties and overlapping spans are frequent
+    pool = rng.choice(n_mid, size=min(n_mid, 12), replace=False) + base
+    lists = np.stack([rng.choice(pool, size=vote_k, replace=False) for _ in range(rows)]).astype(np.int32)
+    n_centres, span = int(rng.integers(1, 9)), int(rng.integers(1, 40))
+    r = ro.vote_merge(lists, n_mid, base, n_centres, span)
+    centres, sel, cnt = _brute_vote_merge(lists, n_mid, base, n_centres, span)
+    assert r["centres"].tolist() == centres
+    assert r["sel"].tolist() == sel
+    assert int(r["votes"].sum()) == rows * vote_k
+    for t, c in cnt.items():
+        assert r["votes"][t - base] == c
+    assert len(sel) <= n_centres * span and all(np.diff(r["sel"]) > 0)
+
+
+def test_head_scores_sum_to_group_scores_and_single_head_reduction():
+    Hq, Hkv, D, N, s, l = 6, 2, 8, 120, 3, 20
+    q, k, v = rng_inputs(31, 2, Hq, Hkv, D, N)
+    sh = ro.Shape(Hq, Hkv, D, "f32", N, s, l, top_k=7, rope_theta=1e4)
+    hs = ro.head_scores(sh, store(q), store(k))                    # [M, Hq, n_mid]
+    # definition, written out with numpy: raw dot products against the head's KV head, middle only
+    want = np.einsum("ihc,hjc->ihj", f64(q), np.repeat(f64(k), Hq // Hkv, axis=0)[:, s:N - l])
+    assert np.allclose(hs, want, rtol=0, atol=1e-12)
+    # Eq. 2 with the group-sum reading is the sum of the group's head scores
+    assert np.allclose(hs.reshape(2, Hkv, Hq // Hkv, -1).sum(axis=2), ro.score(sh, store(q), store(k)), atol=1e-12)
+
+
+def test_vote_selection_reduces_to_plain_topk_for_one_head():
+    """One query row, one head, k' = k, m = 1: the vote selection is Eq. 2's top-k itself."""
+    D, N, s, l, k = 8, 300, 4, 30, 9
+    q, kk, v = rng_inputs(77, 1, 1, 1, D, N)
+    sh = ro.Shape(1, 1, D, "f32", N, s, l, top_k=k, rope_theta=1e4)
+    plain = ro.forward(sh, store(q), store(kk), store(v))
+    vote = ro.vote_forward(sh, store(q), store(kk), store(v), vote_k=k, n_centres=k, span=1)
+    assert vote["sel"].tolist() == plain["idx"][0, 0].tolist()
+    assert np.allclose(vote["out"], plain["out"], atol=1e-13)
+
+
+def test_vote_selection_with_one_huge_span_is_full_attention():
+    """A span wider than twice the middle around any centre keeps the whole middle, so the step
+    is plain causal attention with ordinary RoPE (brute force written above)."""
+    M, Hq, Hkv, D, N, s, l = 3, 4, 2, 8, 90, 4, 16
+    q, k, v = rng_inputs(5, M, Hq, Hkv, D, N)
+    sh = ro.Shape(Hq, Hkv, D, "f32", N, s, l, top_k=0, rope_theta=1e4)
+    r = ro.vote_forward(sh, store(q), store(k), store(v), vote_k=2, n_centres=1, span=4 * N)
+    assert r["sel"].tolist() == list(range(s, N - l))
+    want = brute_full_attention(f64(q), f64(k), f64(v), np.arange(N - M, N), 1e4)
+    assert np.allclose(r["out"], want, atol=1e-12)
+
+
+def test_vote_selection_retrieves_needle_spans():
+    """Config-2 recipe at a small size: every head's best key is a planted needle (3x the group
+    query direction), so all needles collect votes and their spans are kept whole."""
+    w = wl.CONFIGS[2].scaled(n_ctx=6_000, n_local=256, top_k=0, n_needles=4)
+    t = wl.generate(w)
+    sh = ro.Shape(w.n_q_heads, w.n_kv_heads, w.head_dim, w.dtype, w.n_ctx, w.n_sink, w.n_local, 0, w.rope_theta)
+    r = ro.vote_forward(sh, store(t["q"]), store(t["k"]), store(t["v"]), vote_k=4, n_centres=16, span=8)
+    sel = set(r["sel"].tolist())
+    for pos in t["needles"].tolist():
+        lo = pos - 4
+        assert all(p in sel for p in range(max(lo, w.n_sink), min(lo + 8, w.n_ctx - w.n_local))), pos
+    assert r["votes"].sum() == w.n_q_heads * 4
+    assert all(np.diff(r["sel"]) > 0) and r["sel"].min() >= w.n_sink and r["sel"].max() < w.n_ctx - w.n_local
