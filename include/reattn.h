@@ -136,6 +136,48 @@ int reattn_prefill_chunk(const reattn_params* p, const void* q, const void* k_ca
                          const void* v_cache, int32_t* idx_out, float* out,
                          void* ws, size_t ws_bytes, void* stream);
 
+/* ---- Vote selection -------------------------------------------------------------------
+ * The paper's way of combining heads and query rows (Method, "Full-Context Cache
+ * Selection", last paragraph; Setup: k = 4, k' = 127, span 32): every (query row, query
+ * head) votes for its own `vote_k` best middle tokens by raw score
+ * q[i][hq] . k_cache[hq/G][j]; votes of all heads and all M query rows are pooled; the
+ * `n_centres` most voted tokens (ties: lower index; tokens without a vote never) are kept
+ * together with their `span` neighbouring entries [c - span/2, c - span/2 + span), clipped
+ * to the middle, overlaps deduplicated.  The result is ONE ascending index list per layer,
+ * shared by all heads and query rows, of data-dependent length n_sel <= cap =
+ * min(n_centres * span, N_mid).  In these calls p->top_k is ignored, the scope is
+ * S = s_eff + n_sel + l_eff (query i sits at slot s_eff + n_sel + l_eff - M + i) and
+ * p->max_position is checked against s_eff + cap + l_eff.
+ * Supported: bf16 with D = 128 or fp32 with D = 64, G <= 8, vote_k <= 8, n_centres <= 1024. */
+typedef struct reattn_vote {
+  int32_t vote_k;     /* k: entries per (query row, head) list, 1..8; clamped to N_mid */
+  int32_t n_centres;  /* k': 1..1024 */
+  int32_t span;       /* m >= 1 */
+} reattn_vote;
+
+/* Bytes of device scratch the vote calls accept for (p, v); 0 if either is invalid. */
+size_t reattn_vote_workspace_bytes(const reattn_params* p, const reattn_vote* v);
+
+/* Fused score + top-k of the selection: head_topk[i][hq][kk], kk = min(vote_k, N_mid),
+ * ascending absolute indices of the kk largest raw scores of query row i, head hq (ties:
+ * lower index).  The key cache is streamed once per query row; no score is written. */
+int reattn_vote_topk(const reattn_params* p, const reattn_vote* v, const void* q,
+                     const void* k_cache, int32_t* head_topk, void* ws, size_t ws_bytes,
+                     void* stream);
+
+/* Votes -> centres -> spans: sel[0 .. *n_sel) ascending absolute indices (sel holds cap
+ * entries), *n_sel a DEVICE int32.  Pure integer work on the given lists. */
+int reattn_vote_merge(const reattn_params* p, const reattn_vote* v, const int32_t* head_topk,
+                      int32_t* sel, int32_t* n_sel, void* ws, size_t ws_bytes, void* stream);
+
+/* One layer step with the vote selection for M >= 1 query rows: reattn_vote_topk ->
+ * reattn_vote_merge -> attention of every query row over [sink, sel, local up to its own
+ * token] with sequential positions (Eq. 3).  sel_out (cap entries) and n_sel_out (device
+ * int32) may be NULL.  out: [M][Hq][D] fp32. */
+int reattn_vote_layer(const reattn_params* p, const reattn_vote* v, const void* q,
+                      const void* k_cache, const void* v_cache, int32_t* sel_out,
+                      int32_t* n_sel_out, float* out, void* ws, size_t ws_bytes, void* stream);
+
 /* Measurement aid: reattn_decode_step with HIP events recorded on `stream` at the
  * stage boundaries; it WAITS for the step to finish and fills the HOST array
  * stage_ms[REATTN_N_STAGES] with the elapsed milliseconds of

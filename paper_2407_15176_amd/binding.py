@@ -28,6 +28,7 @@ EXPORTS = [
     "reattn_workspace_bytes", "reattn_score", "reattn_topk", "reattn_gather_rope",
     "reattn_attend", "reattn_decode_step", "reattn_prefill_chunk", "reattn_decode_step_timed",
     "reattn_probe_read_bandwidth", "reattn_prefill_chunk_timed",
+    "reattn_vote_workspace_bytes", "reattn_vote_topk", "reattn_vote_merge", "reattn_vote_layer",
 ]
 PREFILL_STAGES = ("sample_threshold", "score_gemm_filter", "candidate_topk", "attend")
 STAGES = ("prep", "scan", "topk", "attend")
@@ -43,6 +44,10 @@ class CParams(C.Structure):
         ("k_stride_head", C.c_int64), ("k_stride_tok", C.c_int64),
         ("v_stride_head", C.c_int64), ("v_stride_tok", C.c_int64),
     ]
+
+
+class CVote(C.Structure):
+    _fields_ = [("vote_k", C.c_int32), ("n_centres", C.c_int32), ("span", C.c_int32)]
 
 
 class ReattnError(RuntimeError):
@@ -81,6 +86,12 @@ def lib() -> C.CDLL:
                                                C.POINTER(C.c_float)]
         L.reattn_prefill_chunk_timed.argtypes = L.reattn_decode_step_timed.argtypes
         L.reattn_probe_read_bandwidth.argtypes = [P, C.c_size_t, C.c_int, P, C.POINTER(C.c_float)]
+        PV = C.POINTER(CVote)
+        L.reattn_vote_workspace_bytes.argtypes = [PP, PV]
+        L.reattn_vote_workspace_bytes.restype = C.c_size_t
+        L.reattn_vote_topk.argtypes = [PP, PV, P, P, P, P, C.c_size_t, P]
+        L.reattn_vote_merge.argtypes = [PP, PV, P, P, P, P, C.c_size_t, P]
+        L.reattn_vote_layer.argtypes = [PP, PV, P, P, P, P, P, P, P, C.c_size_t, P]
         _lib = L
     return _lib
 
@@ -283,3 +294,75 @@ def probe_read_bandwidth(buf: torch.Tensor, iters: int = 10) -> float:
                                              iters, _stream(), C.byref(out)),
            "reattn_probe_read_bandwidth")
     return float(out.value)
+
+
+# ---- vote selection (heads and query rows vote; top-k' centres; spans) ------------------------
+@dataclass
+class Vote:
+    """reattn_vote: the paper's k (votes per list), k' (centres) and span m."""
+    vote_k: int = 4
+    n_centres: int = 127
+    span: int = 32
+
+    def c(self) -> CVote:
+        return CVote(self.vote_k, self.n_centres, self.span)
+
+
+def vote_workspace_bytes(p: Params, v: Vote) -> int:
+    cp, cv = p.c(), v.c()
+    return lib().reattn_vote_workspace_bytes(C.byref(cp), C.byref(cv))
+
+
+def alloc_vote_workspace(p: Params, v: Vote, device="cuda") -> torch.Tensor:
+    n = vote_workspace_bytes(p, v)
+    if n == 0:
+        raise ReattnError(validate(p) or ERR_RANGE, "reattn_vote_workspace_bytes")
+    return torch.empty(n, dtype=torch.uint8, device=device)
+
+
+def vote_cap(p: Params, v: Vote) -> int:
+    """Largest selection length min(n_centres * span, N_mid)."""
+    _, _, n_mid, _, _ = scope(p)
+    return min(v.n_centres * v.span, n_mid)
+
+
+def vote_topk(p: Params, v: Vote, q, k_cache, ws, head_topk=None):
+    _, _, n_mid, _, _ = scope(p)
+    kk = min(v.vote_k, n_mid)
+    if head_topk is None:
+        head_topk = torch.empty(p.n_query, p.n_q_heads, kk, dtype=torch.int32, device=q.device)
+    cp, cv = p.c(), v.c()
+    _check(lib().reattn_vote_topk(C.byref(cp), C.byref(cv), _dev(q, "q", p.torch_dtype()),
+                                  _dev(k_cache, "k_cache", p.torch_dtype()),
+                                  _dev(head_topk, "head_topk", torch.int32), _dev(ws, "ws"), ws.numel(),
+                                  _stream()), "reattn_vote_topk")
+    return head_topk
+
+
+def vote_merge(p: Params, v: Vote, head_topk, ws, sel=None, n_sel=None):
+    if sel is None:
+        sel = torch.empty(max(vote_cap(p, v), 1), dtype=torch.int32, device=head_topk.device)
+    if n_sel is None:
+        n_sel = torch.zeros(1, dtype=torch.int32, device=head_topk.device)
+    cp, cv = p.c(), v.c()
+    _check(lib().reattn_vote_merge(C.byref(cp), C.byref(cv), _dev(head_topk, "head_topk", torch.int32),
+                                   _dev(sel, "sel", torch.int32), _dev(n_sel, "n_sel", torch.int32),
+                                   _dev(ws, "ws"), ws.numel(), _stream()), "reattn_vote_merge")
+    return sel, n_sel
+
+
+def vote_layer(p: Params, v: Vote, q, k_cache, v_cache, ws, sel=None, n_sel=None, out=None, want_sel=True):
+    if out is None:
+        out = torch.empty(p.n_query, p.n_q_heads, p.head_dim, dtype=torch.float32, device=q.device)
+    if want_sel and sel is None:
+        sel = torch.empty(max(vote_cap(p, v), 1), dtype=torch.int32, device=q.device)
+    if want_sel and n_sel is None:
+        n_sel = torch.zeros(1, dtype=torch.int32, device=q.device)
+    cp, cv = p.c(), v.c()
+    _check(lib().reattn_vote_layer(C.byref(cp), C.byref(cv), _dev(q, "q", p.torch_dtype()),
+                                   _dev(k_cache, "k_cache", p.torch_dtype()),
+                                   _dev(v_cache, "v_cache", p.torch_dtype()),
+                                   _dev(sel, "sel", torch.int32), _dev(n_sel, "n_sel", torch.int32),
+                                   _dev(out, "out", torch.float32), _dev(ws, "ws"), ws.numel(), _stream()),
+           "reattn_vote_layer")
+    return out, sel, n_sel

@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libreattn.so")
-SOURCES = ["api.hip", "score_scan.hip", "score_gemm.hip", "prefill_select.hip", "topk.hip", "rope.hip", "attend.hip", "attend_prefill.hip"]
+SOURCES = ["api.hip", "score_scan.hip", "score_gemm.hip", "prefill_select.hip", "topk.hip", "rope.hip", "attend.hip", "attend_prefill.hip", "vote.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

@@ -362,6 +362,140 @@ int reattn_prefill_chunk(const reattn_params* p, const void* q, const void* k_ca
   return run_layer(p, false, q, k_cache, v_cache, idx_out, out, ws, ws_bytes, stream);
 }
 
+// ---- vote selection ----------------------------------------------------------------------
+namespace {
+struct VotePlan {
+  Plan pl;                 // base plan with k_eff = cap (largest selection)
+  int kk, kc, span;        // votes per list, centres, span (all clamped)
+  size_t off_part, off_lists, off_votes, off_centres, off_sel, off_nsel, total;
+};
+
+int make_vote_plan(const reattn_params* p, const reattn_vote* v, VotePlan* out) {
+  if (!p || !v) return REATTN_ERR_NULL;
+  if (v->vote_k < 1 || v->vote_k > 8 || v->n_centres < 1 || v->n_centres > 1024 || v->span < 1)
+    return REATTN_ERR_RANGE;
+  reattn_params pp = *p;
+  const int64_t want = (int64_t)v->n_centres * v->span;
+  pp.top_k = want > 0x7fffffffLL ? 0x7fffffff : (int32_t)want;       // make_plan clamps to N_mid: cap
+  VotePlan vp;
+  int rc = make_plan(&pp, &vp.pl);
+  if (rc) return rc;
+  const Plan& pl = vp.pl;
+  vp.kk = (int)(v->vote_k < pl.n_mid ? v->vote_k : pl.n_mid);
+  vp.kc = (int)(v->n_centres < pl.n_mid ? v->n_centres : pl.n_mid);
+  vp.span = v->span;
+  if (pl.n_mid > 0 && !vote_scan_applies(pl)) return REATTN_ERR_SHAPE;
+  const int per = 65535 / pl.Hkv < pl.M ? 65535 / pl.Hkv : pl.M;
+  size_t off = pl.total;
+  vp.off_part = off;    off += up(pl.n_mid > 0 ? vote_part_bytes(pl, per, vp.kk > 0 ? vp.kk : 1) : 0);
+  vp.off_lists = off;   off += up((size_t)pl.M * pl.Hq * (vp.kk > 0 ? vp.kk : 1) * 4);
+  vp.off_votes = off;   off += up((size_t)(pl.n_mid > 0 ? pl.n_mid : 1) * 4);
+  vp.off_centres = off; off += up((size_t)(vp.kc > 0 ? vp.kc : 1) * 4);
+  vp.off_sel = off;     off += up((size_t)(pl.k_eff > 0 ? pl.k_eff : 1) * 4);
+  vp.off_nsel = off;    off += up(4);
+  vp.total = off;
+  *out = vp;
+  return REATTN_OK;
+}
+
+int vote_topk_impl(const VotePlan& vp, const void* q, const void* k_cache, int32_t* head_topk,
+                   char* ws, hipStream_t st) {
+  const Plan& pl = vp.pl;
+  if (vp.kk == 0) return REATTN_OK;
+  const int per = 65535 / pl.Hkv;
+  const size_t eb = pl.dtype == REATTN_BF16 ? 2 : 4;
+  int rc = REATTN_OK;
+  for (int q0 = 0; q0 < pl.M && !rc; q0 += per) {
+    const int nq = pl.M - q0 < per ? pl.M - q0 : per;
+    rc = hip_rc(launch_head_topk_scan(pl, (const char*)q + (size_t)q0 * pl.Hq * pl.D * eb, nq, k_cache,
+                                      vp.kk, (uint64_t*)(ws + vp.off_part),
+                                      head_topk + (size_t)q0 * pl.Hq * vp.kk, st));
+  }
+  return rc;
+}
+
+int vote_merge_impl(const VotePlan& vp, const int32_t* head_topk, int32_t* sel, int32_t* n_sel,
+                    char* ws, hipStream_t st) {
+  const Plan& pl = vp.pl;
+  if (vp.kk == 0 || vp.kc == 0)                        // empty middle: nothing can be selected
+    return hip_rc(launch_fill_u32((uint32_t*)n_sel, 1, 0u, st));
+  Ws w;
+  int rc = bind_ws(pl, ws, pl.total, &w);
+  if (rc) return rc;
+  float* votes = (float*)(ws + vp.off_votes);
+  int32_t* centres = (int32_t*)(ws + vp.off_centres);
+  rc = hip_rc(launch_fill_u32((uint32_t*)votes, pl.n_mid, 0u, st));
+  if (!rc) rc = hip_rc(launch_vote_scatter(pl, head_topk, (int64_t)pl.M * pl.Hq * vp.kk, votes, st));
+  // the k' most voted tokens are the top-k' of the vote array (ties: lower index)
+  Plan pc = pl;
+  pc.k_eff = vp.kc;
+  if (!rc) rc = hip_rc(launch_prep(pc, 1, w.hist, nullptr, st));
+  if (!rc) rc = hip_rc(launch_topk(pc, 1, votes, false, w.hist, w.pfx, w.ncand, w.cand, w.bitmap, w.cnt,
+                                   centres, st));
+  if (!rc) rc = hip_rc(launch_span_union(pl, centres, vp.kc, votes, vp.span, sel, n_sel, st));
+  return rc;
+}
+}  // namespace
+
+extern "C" size_t reattn_vote_workspace_bytes(const reattn_params* p, const reattn_vote* v) {
+  VotePlan vp;
+  return make_vote_plan(p, v, &vp) == REATTN_OK ? vp.total : 0;
+}
+
+extern "C" int reattn_vote_topk(const reattn_params* p, const reattn_vote* v, const void* q,
+                                const void* k_cache, int32_t* head_topk, void* ws, size_t ws_bytes,
+                                void* stream) {
+  VotePlan vp;
+  int rc = make_vote_plan(p, v, &vp);
+  if (rc) return rc;
+  if (vp.kk == 0) return REATTN_OK;
+  if (!q || !k_cache || !head_topk) return REATTN_ERR_NULL;
+  if (!aligned16(q) || !aligned16(k_cache)) return REATTN_ERR_ALIGN;
+  if (!ws || ws_bytes < vp.total) return REATTN_ERR_WORKSPACE;
+  if ((uintptr_t)ws % kAlign) return REATTN_ERR_ALIGN;
+  return vote_topk_impl(vp, q, k_cache, head_topk, (char*)ws, (hipStream_t)stream);
+}
+
+extern "C" int reattn_vote_merge(const reattn_params* p, const reattn_vote* v, const int32_t* head_topk,
+                                 int32_t* sel, int32_t* n_sel, void* ws, size_t ws_bytes, void* stream) {
+  VotePlan vp;
+  int rc = make_vote_plan(p, v, &vp);
+  if (rc) return rc;
+  if (!n_sel || (vp.kk > 0 && (!head_topk || !sel))) return REATTN_ERR_NULL;
+  if (!ws || ws_bytes < vp.total) return REATTN_ERR_WORKSPACE;
+  if ((uintptr_t)ws % kAlign) return REATTN_ERR_ALIGN;
+  return vote_merge_impl(vp, head_topk, sel, n_sel, (char*)ws, (hipStream_t)stream);
+}
+
+extern "C" int reattn_vote_layer(const reattn_params* p, const reattn_vote* v, const void* q,
+                                 const void* k_cache, const void* v_cache, int32_t* sel_out,
+                                 int32_t* n_sel_out, float* out, void* ws, size_t ws_bytes, void* stream) {
+  VotePlan vp;
+  int rc = make_vote_plan(p, v, &vp);
+  if (rc) return rc;
+  if (!q || !k_cache || !v_cache || !out) return REATTN_ERR_NULL;
+  if (!aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(out)) return REATTN_ERR_ALIGN;
+  if (!ws || ws_bytes < vp.total) return REATTN_ERR_WORKSPACE;
+  if ((uintptr_t)ws % kAlign) return REATTN_ERR_ALIGN;
+  const Plan& pl = vp.pl;
+  char* b = (char*)ws;
+  hipStream_t st = (hipStream_t)stream;
+  int32_t* lists = (int32_t*)(b + vp.off_lists);
+  int32_t* sel = sel_out ? sel_out : (int32_t*)(b + vp.off_sel);
+  int32_t* n_sel = n_sel_out ? n_sel_out : (int32_t*)(b + vp.off_nsel);
+  rc = vote_topk_impl(vp, q, k_cache, lists, b, st);
+  if (!rc) rc = vote_merge_impl(vp, lists, sel, n_sel, b, st);
+  if (rc) return rc;
+  Ws w;
+  rc = bind_ws(pl, ws, pl.total, &w);
+  if (rc) return rc;
+  rc = hip_rc(launch_prep(pl, 0, nullptr, w.rope, st));
+  if (rc) return rc;
+  // one shared index row for every (query, KV head); its length is read on the device
+  return hip_rc(launch_attend(pl, true, q, 0, pl.M, k_cache, v_cache, sel, w.rope, w.part, out, st,
+                              n_sel, 0));
+}
+
 static int layer_timed(const reattn_params* p, bool decode_only, const void* q, const void* k_cache,
                        const void* v_cache, int32_t* idx_out, float* out, void* ws,
                        size_t ws_bytes, void* stream, float* stage_ms) {

@@ -72,7 +72,18 @@ hipError_t launch_gather_rope(const Plan& pl, const void* k_cache, const void* v
                               const int32_t* idx, float* k_sel, void* v_sel, hipStream_t st);
 hipError_t launch_attend(const Plan& pl, bool fused, const void* q, int q_first, int n_query,
                          const void* k_src, const void* v_src, const int32_t* idx,
-                         const float2* rope, float* part, float* out, hipStream_t st);
+                         const float2* rope, float* part, float* out, hipStream_t st,
+                         const int32_t* k_dyn = nullptr, int64_t idx_stride = -1);
+// vote selection (vote.hip)
+int vote_list_len(int vote_k);
+bool vote_scan_applies(const Plan& pl);
+size_t vote_part_bytes(const Plan& pl, int n_query, int vote_k);
+hipError_t launch_head_topk_scan(const Plan& pl, const void* q, int n_query, const void* k_cache,
+                                 int vote_k, uint64_t* part, int32_t* head_topk, hipStream_t st);
+hipError_t launch_vote_scatter(const Plan& pl, const int32_t* head_topk, int64_t n_votes, float* votes,
+                               hipStream_t st);
+hipError_t launch_span_union(const Plan& pl, const int32_t* centres, int kc, const float* votes, int span,
+                             int32_t* sel, int32_t* n_sel, hipStream_t st);
 
 size_t attend_prefill_table_bytes(const Plan& pl);
 bool attend_prefill_applies(const Plan& pl);

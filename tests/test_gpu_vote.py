@@ -1,0 +1,111 @@
+"""GPU parity of the vote selection (heads and query rows vote with their top-k lists, top-k'
+centres, span expansion) against the fp64 CPU oracle, through the C ABI.
+
+Floating point enters only the per-head lists: a GPU list may differ from the oracle's inside
+the 1e-3 tie band of the list's k-th score.  Everything after the lists is integer work and is
+compared bit-exactly with the oracle's merge fed with the GPU's own lists."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import reattn_oracle as ro
+from paper_2407_15176_amd import binding as B
+from paper_2407_15176_amd import workloads as wl
+from tests import parity as P
+
+pytestmark = pytest.mark.gpu
+
+
+def _check_lists(w, t, v, lists):
+    """lists: GPU head_topk [M,Hq,kk].  Returns the oracle result evaluated on the GPU's lists."""
+    sh = P.oracle_shape(w)
+    q, k, vv = P.host_inputs(t)
+    res = ro.vote_forward(sh, q, k, vv, v.vote_k, v.n_centres, v.span, head_topk=lists)
+    s_eff, l_eff, n_mid, _ = sh.partition()
+    M, Hq, kk = res["head_topk"].shape
+    assert lists.shape == (M, Hq, kk)
+    differ = P.check_index_sets(lists.reshape(M * Hq, kk), res["head_topk"].reshape(M * Hq, kk),
+                                res["head_scores"].reshape(M * Hq, n_mid), res["head_kth"].reshape(M * Hq),
+                                s_eff, n_mid)
+    return res, differ
+
+
+CASES = {
+    "bf16_g4_decode": (wl.CONFIGS[2].scaled(n_ctx=30_011, n_local=300, top_k=0), B.Vote(4, 20, 16)),
+    "bf16_g3_decode": (wl.CONFIGS[5].scaled(n_ctx=21_000, n_local=257, top_k=0, max_position=0), B.Vote(8, 127, 32)),
+    "f32_g4_decode": (wl.CONFIGS[1].scaled(n_ctx=9_973, n_local=200, top_k=0, max_position=0), B.Vote(1, 5, 7)),
+    "bf16_g1_chunk": (wl.CONFIGS[4].scaled(n_ctx=12_000, n_q_heads=8, n_query=9, n_local=128, top_k=0), B.Vote(2, 33, 5)),
+    "bf16_g8_chunk": (wl.CONFIGS[4].scaled(n_ctx=8_000, n_kv_heads=4, n_query=17, n_local=64, top_k=0), B.Vote(4, 40, 9)),
+    "f32_g5_chunk": (wl.CONFIGS[1].scaled(n_ctx=5_000, n_q_heads=10, n_kv_heads=2, n_query=6, n_local=100, top_k=0,
+                                          max_position=0), B.Vote(3, 11, 64)),
+}
+
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_vote_topk_lists_match_oracle(name):
+    w, v = CASES[name]
+    t = wl.generate(w, "cuda")
+    p = B.Params.from_workload(w)
+    ws = B.alloc_vote_workspace(p, v)
+    lists = B.vote_topk(p, v, t["q"], t["k"], ws)
+    torch.cuda.synchronize()
+    _check_lists(w, t, v, lists.cpu().numpy())
+
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_vote_layer_matches_oracle(name):
+    w, v = CASES[name]
+    t = wl.generate(w, "cuda")
+    p = B.Params.from_workload(w)
+    ws = B.alloc_vote_workspace(p, v)
+    lists = B.vote_topk(p, v, t["q"], t["k"], ws)
+    out, sel, n_sel = B.vote_layer(p, v, t["q"], t["k"], t["v"], ws)
+    torch.cuda.synchronize()
+    res, differ = _check_lists(w, t, v, lists.cpu().numpy())
+    n = int(n_sel.item())
+    assert sel.cpu().numpy()[:n].tolist() == res["sel"].tolist()      # integer pipeline: bit-exact
+    err = np.abs(out.cpu().numpy().astype(np.float64) - res["out"]).max()
+    assert err <= P.OUT_TOL[w.dtype], err
+    if w.n_needles and w.n_query == 1:
+        # all needles of a KV head carry the same key, so every head's list is the vote_k
+        # lowest needle positions (tie rule) and those collect all the votes
+        got = set(sel.cpu().numpy()[:n].tolist())
+        assert set(t["needles"].tolist()[: v.vote_k]) <= got
+
+
+def test_vote_merge_on_given_lists_heavy_ties():
+    """Integer pipeline alone: few distinct tokens, so vote ties and overlapping spans abound."""
+    w = wl.CONFIGS[2].scaled(n_ctx=5_000, n_local=100, top_k=0, n_query=7)
+    p = B.Params.from_workload(w)
+    rng = np.random.default_rng(3)
+    s_eff, l_eff, n_mid, _, _ = B.scope(p)
+    for v in (B.Vote(4, 6, 10), B.Vote(4, 50, 3), B.Vote(4, 3, 400)):
+        pool = rng.choice(n_mid, size=40, replace=False) + s_eff
+        lists = np.stack([np.sort(rng.choice(pool, size=4, replace=False))
+                          for _ in range(7 * w.n_q_heads)]).astype(np.int32).reshape(7, w.n_q_heads, 4)
+        ws = B.alloc_vote_workspace(p, v)
+        sel, n_sel = B.vote_merge(p, v, torch.from_numpy(lists).cuda(), ws)
+        torch.cuda.synchronize()
+        want = ro.vote_merge(lists.reshape(-1, 4), n_mid, s_eff, v.n_centres, v.span)
+        assert sel.cpu().numpy()[: int(n_sel.item())].tolist() == want["sel"].tolist()
+
+
+@pytest.mark.parametrize("kw", [
+    dict(n_ctx=300, n_local=512),                    # empty middle: plain attention, nothing selected
+    dict(n_ctx=520, n_local=512),                    # middle of 4 tokens: lists clamped to it
+    dict(n_ctx=4_000, n_local=64, n_query=5),        # a chunk: causal cut inside the local window
+])
+def test_vote_layer_degenerate_partitions(kw):
+    w = wl.CONFIGS[2].scaled(top_k=0, max_position=0, n_needles=0, **kw)
+    v = B.Vote(8, 127, 32)
+    t = wl.generate(w, "cuda")
+    p = B.Params.from_workload(w)
+    ws = B.alloc_vote_workspace(p, v)
+    out, sel, n_sel = B.vote_layer(p, v, t["q"], t["k"], t["v"], ws)
+    torch.cuda.synchronize()
+    sh = P.oracle_shape(w)
+    q, k, vv = P.host_inputs(t)
+    res = ro.vote_forward(sh, q, k, vv, v.vote_k, v.n_centres, v.span)
+    n = int(n_sel.item())
+    assert sel.cpu().numpy()[:n].tolist() == res["sel"].tolist()
+    assert np.abs(out.cpu().numpy().astype(np.float64) - res["out"]).max() <= P.OUT_TOL[w.dtype]
