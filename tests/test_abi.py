@@ -128,3 +128,22 @@ def test_workspace_is_modest_for_decode():
         need = B.workspace_bytes(B.Params.from_workload(w))
         # scores + candidate list + bitmap: about 8.2 bytes per middle token per KV head
         assert need < 10 * w.n_mid * w.n_kv_heads + (8 << 20)
+
+
+def test_vote_parameters_are_checked_on_the_host():
+    p = good(top_k=0)
+    assert B.vote_workspace_bytes(p, B.Vote(4, 127, 32)) > B.workspace_bytes(good(top_k=127 * 32)) - 1
+    for bad in (B.Vote(0, 127, 32), B.Vote(9, 127, 32), B.Vote(4, 0, 32), B.Vote(4, 1025, 32), B.Vote(4, 127, 0)):
+        assert B.vote_workspace_bytes(p, bad) == 0
+    # the paper's own setting fills an 8K window exactly: 32 + 4096 + 127 * 32 = 8192
+    p8k = good(n_sink=32, top_k=0, max_position=8192)
+    assert B.vote_workspace_bytes(p8k, B.Vote(4, 127, 32)) > 0
+    assert B.vote_workspace_bytes(p8k, B.Vote(4, 128, 32)) == 0          # one more span overflows the window
+    # shapes the streaming vote scan does not cover are refused, not computed some other way
+    assert B.vote_workspace_bytes(good(head_dim=64, top_k=0), B.Vote()) == 0          # bf16 with D = 64
+    assert B.vote_workspace_bytes(good(n_q_heads=72, top_k=0), B.Vote()) == 0         # G = 9
+    # NULL pointers are reported before anything is launched
+    L = B.lib()
+    cp, cv = p.c(), B.Vote().c()
+    assert L.reattn_vote_layer(C.byref(cp), C.byref(cv), None, None, None, None, None, None, None, 0, None) == B.ERR_NULL
+    assert L.reattn_vote_merge(C.byref(cp), C.byref(cv), None, None, None, None, 0, None) == B.ERR_NULL
