@@ -367,7 +367,7 @@ namespace {
 struct VotePlan {
   Plan pl;                 // base plan with k_eff = cap (largest selection)
   int kk, kc, span;        // votes per list, centres, span (all clamped)
-  size_t off_part, off_lists, off_votes, off_centres, off_sel, off_nsel, total;
+  size_t off_part, off_lists, off_counts, off_seg, off_comp, off_sel, off_nsel, total;
 };
 
 int make_vote_plan(const reattn_params* p, const reattn_vote* v, VotePlan* out) {
@@ -383,14 +383,27 @@ int make_vote_plan(const reattn_params* p, const reattn_vote* v, VotePlan* out) 
   const Plan& pl = vp.pl;
   vp.kk = (int)(v->vote_k < pl.n_mid ? v->vote_k : pl.n_mid);
   vp.kc = (int)(v->n_centres < pl.n_mid ? v->n_centres : pl.n_mid);
-  vp.span = v->span;
+  {
+    // a span longer than twice the middle covers it wherever its centre lies
+    const int64_t widest = 2 * pl.n_mid + 2;
+    vp.span = (int)(v->span < widest ? v->span : (widest < 0x7fffffffLL ? widest : 0x7fffffffLL));
+  }
   if (pl.n_mid > 0 && !vote_scan_applies(pl)) return REATTN_ERR_SHAPE;
-  const int per = 65535 / pl.Hkv < pl.M ? 65535 / pl.Hkv : pl.M;
+  const int per = pl.n_mid > 0 ? vote_queries_per_launch(pl) : 1;
   size_t off = pl.total;
-  vp.off_part = off;    off += up(pl.n_mid > 0 ? vote_part_bytes(pl, per, vp.kk > 0 ? vp.kk : 1) : 0);
+  size_t part_bytes = 0;                               // the last launch may take fewer query rows
+  if (pl.n_mid > 0) {
+    part_bytes = vote_part_bytes(pl, per, vp.kk > 0 ? vp.kk : 1);
+    const size_t tail = pl.M % per ? vote_part_bytes(pl, pl.M % per, vp.kk > 0 ? vp.kk : 1) : 0;
+    if (tail > part_bytes) part_bytes = tail;
+  }
+  vp.off_part = off;    off += up(part_bytes);
   vp.off_lists = off;   off += up((size_t)pl.M * pl.Hq * (vp.kk > 0 ? vp.kk : 1) * 4);
-  vp.off_votes = off;   off += up((size_t)(pl.n_mid > 0 ? pl.n_mid : 1) * 4);
-  vp.off_centres = off; off += up((size_t)(vp.kc > 0 ? vp.kc : 1) * 4);
+  size_t cb, sb, mb;
+  vote_merge_layout(pl, (int64_t)pl.M * pl.Hq * vp.kk, &cb, &sb, &mb);
+  vp.off_counts = off;  off += up(cb);
+  vp.off_seg = off;     off += up(sb);
+  vp.off_comp = off;    off += up(mb);
   vp.off_sel = off;     off += up((size_t)(pl.k_eff > 0 ? pl.k_eff : 1) * 4);
   vp.off_nsel = off;    off += up(4);
   vp.total = off;
@@ -402,7 +415,7 @@ int vote_topk_impl(const VotePlan& vp, const void* q, const void* k_cache, int32
                    char* ws, hipStream_t st) {
   const Plan& pl = vp.pl;
   if (vp.kk == 0) return REATTN_OK;
-  const int per = 65535 / pl.Hkv;
+  const int per = vote_queries_per_launch(pl);
   const size_t eb = pl.dtype == REATTN_BF16 ? 2 : 4;
   int rc = REATTN_OK;
   for (int q0 = 0; q0 < pl.M && !rc; q0 += per) {
@@ -419,21 +432,9 @@ int vote_merge_impl(const VotePlan& vp, const int32_t* head_topk, int32_t* sel, 
   const Plan& pl = vp.pl;
   if (vp.kk == 0 || vp.kc == 0)                        // empty middle: nothing can be selected
     return hip_rc(launch_fill_u32((uint32_t*)n_sel, 1, 0u, st));
-  Ws w;
-  int rc = bind_ws(pl, ws, pl.total, &w);
-  if (rc) return rc;
-  float* votes = (float*)(ws + vp.off_votes);
-  int32_t* centres = (int32_t*)(ws + vp.off_centres);
-  rc = hip_rc(launch_fill_u32((uint32_t*)votes, pl.n_mid, 0u, st));
-  if (!rc) rc = hip_rc(launch_vote_scatter(pl, head_topk, (int64_t)pl.M * pl.Hq * vp.kk, votes, st));
-  // the k' most voted tokens are the top-k' of the vote array (ties: lower index)
-  Plan pc = pl;
-  pc.k_eff = vp.kc;
-  if (!rc) rc = hip_rc(launch_prep(pc, 1, w.hist, nullptr, st));
-  if (!rc) rc = hip_rc(launch_topk(pc, 1, votes, false, w.hist, w.pfx, w.ncand, w.cand, w.bitmap, w.cnt,
-                                   centres, st));
-  if (!rc) rc = hip_rc(launch_span_union(pl, centres, vp.kc, votes, vp.span, sel, n_sel, st));
-  return rc;
+  return hip_rc(launch_vote_merge(pl, head_topk, (int64_t)pl.M * pl.Hq, vp.kk, vp.kc, vp.span,
+                                  (uint32_t*)(ws + vp.off_counts), (int32_t*)(ws + vp.off_seg),
+                                  (uint64_t*)(ws + vp.off_comp), sel, n_sel, st));
 }
 }  // namespace
 

@@ -77,13 +77,15 @@ hipError_t launch_attend(const Plan& pl, bool fused, const void* q, int q_first,
 // vote selection (vote.hip)
 int vote_list_len(int vote_k);
 bool vote_scan_applies(const Plan& pl);
+int vote_queries_per_launch(const Plan& pl);
 size_t vote_part_bytes(const Plan& pl, int n_query, int vote_k);
 hipError_t launch_head_topk_scan(const Plan& pl, const void* q, int n_query, const void* k_cache,
                                  int vote_k, uint64_t* part, int32_t* head_topk, hipStream_t st);
-hipError_t launch_vote_scatter(const Plan& pl, const int32_t* head_topk, int64_t n_votes, float* votes,
-                               hipStream_t st);
-hipError_t launch_span_union(const Plan& pl, const int32_t* centres, int kc, const float* votes, int span,
-                             int32_t* sel, int32_t* n_sel, hipStream_t st);
+void vote_merge_layout(const Plan& pl, int64_t n_votes, size_t* counts_bytes, size_t* seg_bytes,
+                       size_t* comp_bytes);
+hipError_t launch_vote_merge(const Plan& pl, const int32_t* lists, int64_t n_rows, int kk, int kc, int span,
+                             uint32_t* counts, int32_t* seg, uint64_t* comp, int32_t* sel, int32_t* n_sel,
+                             hipStream_t st);
 
 size_t attend_prefill_table_bytes(const Plan& pl);
 bool attend_prefill_applies(const Plan& pl);
@@ -123,6 +125,56 @@ __device__ __forceinline__ float group_sum(float v) {
   if (LANES >= 16) v = dpp_add<0x140>(v);
   if (LANES >= 32) v += __shfl_xor(v, 16, 64);
   return v;
+}
+
+// Inclusive prefix sum over the NT threads of a workgroup; `total` gets the grand sum.
+template <int NT>
+__device__ __forceinline__ uint32_t block_scan_incl(uint32_t v, uint32_t* wsum, uint32_t& total) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  uint32_t x = v;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const uint32_t y = __shfl_up(x, o, 64);
+    if (lane >= o) x += y;
+  }
+  if (lane == 63) wsum[wave] = x;
+  __syncthreads();
+  uint32_t base = 0, tot = 0;
+#pragma unroll
+  for (int w = 0; w < NT / 64; ++w) {
+    const uint32_t s = wsum[w];
+    base += (w < wave) ? s : 0u;
+    tot += s;
+  }
+  __syncthreads();
+  total = tot;
+  return x + base;
+}
+
+// bins[0..NB) counts, higher bin = larger key.  Finds the bin d with
+// count(bins > d) < k <= count(bins >= d) and `above` = count(bins > d).  1 <= k <= total.
+template <int NT, int NB, typename BinPtr>
+__device__ __forceinline__ void find_kth_bin(BinPtr bins, uint32_t k, uint32_t* sh,
+                                             uint32_t& bin, uint32_t& above) {
+  constexpr int BPT = NB / NT;
+  static_assert(BPT >= 1 && BPT * NT == NB, "bins per thread");
+  uint32_t loc[BPT], sum = 0;
+#pragma unroll
+  for (int i = 0; i < BPT; ++i) { loc[i] = bins[threadIdx.x * BPT + i]; sum += loc[i]; }
+  uint32_t total;
+  const uint32_t incl = block_scan_incl<NT>(sum, sh, total);
+  const uint32_t higher = total - incl;          // entries owned by threads above this one
+  if (higher < k && k <= higher + sum) {
+    uint32_t acc = higher;
+#pragma unroll
+    for (int i = BPT - 1; i >= 0; --i) {
+      if (acc < k && k <= acc + loc[i]) { sh[32] = threadIdx.x * BPT + i; sh[33] = acc; }
+      acc += loc[i];
+    }
+  }
+  __syncthreads();
+  bin = sh[32]; above = sh[33];
+  __syncthreads();
 }
 
 #endif  // __HIPCC__

@@ -24,56 +24,6 @@
 namespace reattn {
 namespace {
 
-// Inclusive prefix sum over the NT threads of a workgroup; `total` gets the grand sum.
-template <int NT>
-__device__ __forceinline__ uint32_t block_scan_incl(uint32_t v, uint32_t* wsum, uint32_t& total) {
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  uint32_t x = v;
-#pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
-    const uint32_t y = __shfl_up(x, o, 64);
-    if (lane >= o) x += y;
-  }
-  if (lane == 63) wsum[wave] = x;
-  __syncthreads();
-  uint32_t base = 0, tot = 0;
-#pragma unroll
-  for (int w = 0; w < NT / 64; ++w) {
-    const uint32_t s = wsum[w];
-    base += (w < wave) ? s : 0u;
-    tot += s;
-  }
-  __syncthreads();
-  total = tot;
-  return x + base;
-}
-
-// bins[0..NB) counts, higher bin = larger key.  Finds the bin d with
-// count(bins > d) < k <= count(bins >= d) and `above` = count(bins > d).  1 <= k <= total.
-template <int NT, int NB, typename BinPtr>
-__device__ __forceinline__ void find_kth_bin(BinPtr bins, uint32_t k, uint32_t* sh,
-                                             uint32_t& bin, uint32_t& above) {
-  constexpr int BPT = NB / NT;
-  static_assert(BPT >= 1 && BPT * NT == NB, "bins per thread");
-  uint32_t loc[BPT], sum = 0;
-#pragma unroll
-  for (int i = 0; i < BPT; ++i) { loc[i] = bins[threadIdx.x * BPT + i]; sum += loc[i]; }
-  uint32_t total;
-  const uint32_t incl = block_scan_incl<NT>(sum, sh, total);
-  const uint32_t higher = total - incl;          // entries owned by threads above this one
-  if (higher < k && k <= higher + sum) {
-    uint32_t acc = higher;
-#pragma unroll
-    for (int i = BPT - 1; i >= 0; --i) {
-      if (acc < k && k <= acc + loc[i]) { sh[32] = threadIdx.x * BPT + i; sh[33] = acc; }
-      acc += loc[i];
-    }
-  }
-  __syncthreads();
-  bin = sh[32]; above = sh[33];
-  __syncthreads();
-}
-
 // ---- hist: first radix digit of every score of a row ----------------------
 __global__ __launch_bounds__(256) void topk_hist_kernel(const float* __restrict__ scores,
                                                         int64_t n_mid, uint32_t* hist) {

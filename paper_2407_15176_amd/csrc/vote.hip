@@ -3,20 +3,25 @@
 // tokens by raw position-agnostic score, the k' most voted tokens are kept together with
 // their m neighbouring entries, overlaps deduplicated; one shared set per layer.
 //
-//   head_topk_scan   the fused score + top-k of the paper: the key cache is streamed once
-//                    (same load shape as the group-sum scan: 16-byte non-temporal loads,
-//                    DPP row reductions) and every lane keeps a running top-k per head in
-//                    registers, so no score ever leaves the chip; lists are merged by wave
-//                    arg-max rounds and each workgroup writes k (score, index) composites
-//                    per head;
+//   head_topk_scan   the fused score + top-k of the paper: the key cache is streamed once with
+//                    16-byte non-temporal loads and every lane keeps a running top-k in
+//                    registers, so no score ever leaves the chip.  bf16 / D = 128 scores on the
+//                    matrix cores (head_topk_mfma_kernel: up to 32 (query row, head) columns
+//                    per pass over the keys); fp32 / D = 64 on the vector ALU with DPP row
+//                    reductions (head_topk_scan_kernel, one pass per query row).  Lists are
+//                    merged inside the wave, then over the waves, and each workgroup writes k
+//                    (score, index) composites per (query row, head);
 //   head_topk_merge  one wave per (query, head): the best k of the workgroups' partial lists,
 //                    ascending absolute indices;
-//   vote_scatter     one fp32 atomic add of 1.0 per vote into a dense array over the middle
-//                    (exact up to 2^24 votes per token);
-//   (topk.hip)       the k' most voted tokens = top-k of that array, ties by lower index;
-//   span_union       sorted centres -> clipped spans -> union by prefix maximum / prefix sum
-//                    -> ascending index list and its length (a device scalar: the scope of
-//                    the following attention is data dependent).
+//   vote_merge_small up to 1024 votes (a decode step): one workgroup counts the votes of every
+//                    distinct token and ranks (votes desc, index asc) by comparison in LDS;
+//   vote_count / vote_composite / vote_pick
+//                    more votes (a chunk of query rows): atomic counts in a dense array over
+//                    the middle, the thread that finds a zero lists the token, then one
+//                    workgroup radix-selects the k' largest (votes, ~index) composites;
+//   centres_to_spans (tail of both) sorted centres -> clipped spans -> union by prefix maximum
+//                    / prefix sum -> ascending index list and its length (a device scalar: the
+//                    scope of the following attention is data dependent).
 #include "common.hpp"
 
 namespace reattn {
@@ -31,17 +36,6 @@ template <> struct Elem<float> {
   }
   static __device__ __forceinline__ float one(const void* p, int64_t i) { return ((const float*)p)[i]; }
 };
-template <> struct Elem<uint16_t> {   // bf16 bit patterns
-  static constexpr int kPerLoad = 8;
-  static __device__ __forceinline__ void widen(const u32x4& d, float* x) {
-    x[0] = bf16_lo(d.x); x[1] = bf16_hi(d.x); x[2] = bf16_lo(d.y); x[3] = bf16_hi(d.y);
-    x[4] = bf16_lo(d.z); x[5] = bf16_hi(d.z); x[6] = bf16_lo(d.w); x[7] = bf16_hi(d.w);
-  }
-  static __device__ __forceinline__ float one(const void* p, int64_t i) {
-    return __uint_as_float(((uint32_t)((const uint16_t*)p)[i]) << 16);
-  }
-};
-
 // (score desc, index asc) as one unsigned 64-bit maximum; 0 is "nothing".
 __device__ __forceinline__ uint64_t composite(float score, uint32_t pos) {
   return ((uint64_t)score_key(score) << 32) | (uint64_t)(0xffffffffu - pos);
@@ -182,6 +176,140 @@ __global__ __launch_bounds__(kVoteThreads) void head_topk_scan_kernel(HeadScanAr
   }
 }
 
+// ---- the same scan on the matrix cores (bf16, D = 128) ----------------------------------
+// A key tile of 16 rows is the A operand of v_mfma_f32_16x16x32_bf16 and up to 16 (query row,
+// head) pairs of one KV head are the columns of B, so one MFMA chain of 4 gives 16 x 16 raw
+// scores and the vector ALU only compares: the stream stays HBM-bound however many heads vote.
+// Lane l loads the 16-byte piece 4j + l/16 of key row l%16 for step j (the contraction does
+// not care which 8 channels sit in which k slot as long as B uses the same assignment), so
+// the four loads of a tile cover its 4 KiB exactly once.  The product leaves lane l with the
+// scores of column l%16 against key rows 4(l/16)..+3: one running list per lane and column
+// block, merged over the four lanes of a column, then over the waves.
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+struct MfmaScanArgs {
+  const void* k; const void* q;
+  uint64_t* part;          // [n_query * Hq][n_wg][KT] composites, best first
+  int64_t ksh, kst, n_mid, first_tok;
+  int Hq, Hkv, G, n_query, q_per_pass, rows_per_block, n_wg;
+};
+
+template <int KT, int NB>
+__global__ __launch_bounds__(kVoteThreads) void head_topk_mfma_kernel(MfmaScanArgs a) {
+  constexpr int D = 128, T = 2, NC = 16 * NB;
+  extern __shared__ uint64_t mfma_best[];              // [kVoteWaves][NC][KT]
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int col = lane & 15, kq = lane >> 4;
+  const int h = blockIdx.y % a.Hkv, q0 = (blockIdx.y / a.Hkv) * a.q_per_pass;
+  const int q_here = a.n_query - q0 < a.q_per_pass ? a.n_query - q0 : a.q_per_pass;
+  const int n_cols = q_here * a.G;
+
+  bf16x8 bq[NB][4];
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb) {
+    const int c = nb * 16 + col;
+    const bool live = c < n_cols;
+    const int64_t row = live ? ((int64_t)(q0 + c / a.G) * a.Hq + (int64_t)h * a.G + c % a.G) : 0;
+    const u32x4* src = (const u32x4*)((const uint16_t*)a.q + row * D);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      u32x4 w = src[4 * j + kq];
+      if (!live) w = u32x4{0u, 0u, 0u, 0u};
+      bq[nb][j] = __builtin_bit_cast(bf16x8, w);
+    }
+  }
+  float bv[NB][KT]; uint32_t bi[NB][KT];
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+    for (int t = 0; t < KT; ++t) { bv[nb][t] = -__builtin_inff(); bi[nb][t] = 0xffffffffu; }
+
+  const int64_t blk_row0 = (int64_t)blockIdx.x * a.rows_per_block;
+  const int64_t left = a.n_mid - blk_row0;
+  const int nrows = left < a.rows_per_block ? (int)left : a.rows_per_block;
+  const int64_t row_bytes = a.kst * 2;
+  const char* kbase = (const char*)a.k + ((int64_t)h * a.ksh + (a.first_tok + blk_row0) * a.kst) * 2 + kq * 16;
+
+  for (int t = wave * (T * 16); t < nrows; t += kVoteWaves * (T * 16)) {
+    u32x4 d[T][4];
+#pragma unroll
+    for (int tt = 0; tt < T; ++tt) {
+      int r = t + tt * 16 + col;
+      r = r < nrows ? r : nrows - 1;                   // tail rows re-read the last row; result dropped
+      const char* src = kbase + (int64_t)r * row_bytes;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) d[tt][j] = __builtin_nontemporal_load((const u32x4*)(src + j * 64));
+    }
+#pragma unroll
+    for (int tt = 0; tt < T; ++tt) {
+      const int r0 = t + tt * 16 + kq * 4;             // this lane's four key rows of the tile
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) {
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, d[tt][j]), bq[nb][j], acc, 0, 0, 0);
+        const float m01 = acc[0] > acc[1] ? acc[0] : acc[1], m23 = acc[2] > acc[3] ? acc[2] : acc[3];
+        if ((m01 > m23 ? m01 : m23) > bv[nb][KT - 1]) {
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            // rows arrive in ascending position per lane: a later equal score never displaces
+            if (r0 + i < nrows && acc[i] > bv[nb][KT - 1]) {
+              bv[nb][KT - 1] = acc[i]; bi[nb][KT - 1] = (uint32_t)(blk_row0 + r0 + i);
+#pragma unroll
+              for (int x = KT - 1; x > 0; --x) {
+                if (bv[nb][x] > bv[nb][x - 1]) {
+                  const float fv = bv[nb][x]; bv[nb][x] = bv[nb][x - 1]; bv[nb][x - 1] = fv;
+                  const uint32_t iv = bi[nb][x]; bi[nb][x] = bi[nb][x - 1]; bi[nb][x - 1] = iv;
+                }
+              }
+            }
+          }
+        }
+      }
+    }
+  }
+
+  // the four lanes of a column merge their lists: KT rounds of arg-max over lanes l, l^16, l^32, l^48
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb) {
+#pragma unroll
+    for (int round = 0; round < KT; ++round) {
+      const uint64_t c = bi[nb][0] != 0xffffffffu ? composite(bv[nb][0], bi[nb][0]) : 0ull;
+      uint64_t best = c;
+#pragma unroll
+      for (int o = 16; o <= 32; o <<= 1) {
+        const uint32_t lo = __shfl_xor((uint32_t)best, o, 64), hi = __shfl_xor((uint32_t)(best >> 32), o, 64);
+        const uint64_t w = ((uint64_t)hi << 32) | lo;
+        best = w > best ? w : best;
+      }
+      if (c == best && best != 0ull) {                 // pop: composites are unique (distinct positions)
+#pragma unroll
+        for (int x = 0; x + 1 < KT; ++x) { bv[nb][x] = bv[nb][x + 1]; bi[nb][x] = bi[nb][x + 1]; }
+        bv[nb][KT - 1] = -__builtin_inff(); bi[nb][KT - 1] = 0xffffffffu;
+      }
+      if (kq == 0) mfma_best[((size_t)wave * NC + nb * 16 + col) * KT + round] = best;
+    }
+  }
+  __syncthreads();
+  // workgroup merge: a wave takes every 16th column; its lanes hold the 16 waves' KT entries
+  for (int c = wave; c < n_cols; c += kVoteWaves) {
+    uint64_t c0 = 0ull, c1 = 0ull;
+    if (lane < kVoteWaves * KT) c0 = mfma_best[((size_t)(lane / KT) * NC + c) * KT + lane % KT];
+    if (lane + 64 < kVoteWaves * KT) c1 = mfma_best[((size_t)((lane + 64) / KT) * NC + c) * KT + (lane + 64) % KT];
+    uint64_t* out = a.part +
+        (((int64_t)(q0 + c / a.G) * a.Hq + (int64_t)h * a.G + c % a.G) * a.n_wg + blockIdx.x) * KT;
+#pragma unroll
+    for (int round = 0; round < KT; ++round) {
+      const uint64_t best = wave_max_u64(c0 > c1 ? c0 : c1);
+      if (c0 == best) c0 = 0ull;
+      if (c1 == best) c1 = 0ull;
+      if (lane == 0) out[round] = best;
+    }
+  }
+}
+
 // One wave per (query, head): best vote_k of n_wg * KT composites -> ascending absolute indices.
 __global__ __launch_bounds__(64) void head_topk_merge_kernel(const uint64_t* __restrict__ part, int n_cand,
                                                              int vote_k, int32_t index_base,
@@ -209,51 +337,193 @@ __global__ __launch_bounds__(64) void head_topk_merge_kernel(const uint64_t* __r
   if (lane < vote_k) head_topk[(int64_t)blockIdx.x * vote_k + rank] = index_base + (int32_t)mine;
 }
 
-__global__ __launch_bounds__(256) void vote_scatter_kernel(const int32_t* __restrict__ head_topk, int64_t n_votes,
-                                                           int32_t index_base, float* votes) {
-  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (i < n_votes) atomicAdd(&votes[head_topk[i] - index_base], 1.0f);
+// ---- votes -> centres -> spans ---------------------------------------------------------
+// Composite of a voted token: (votes desc, index asc) as one unsigned maximum; 0 = nothing.
+__device__ __forceinline__ uint64_t vote_composite(uint32_t votes, uint32_t tok) {
+  return ((uint64_t)votes << 32) | (uint64_t)(0xffffffffu - tok);
 }
 
-// centres: kc ascending absolute indices (the top-kc of the vote array; some may have no vote).
-__global__ __launch_bounds__(1024) void span_union_kernel(const int32_t* __restrict__ centres, int kc,
-                                                          const float* __restrict__ votes, int32_t s_eff,
-                                                          int64_t n_mid, int span, int32_t* sel,
-                                                          int32_t* n_sel) {
-  __shared__ int32_t sh_a[1024], sh_b[1024];
-  const int i = threadIdx.x;
-  int32_t lo = 0, hi = 0;                              // relative to the middle; empty when no vote
-  if (i < kc) {
-    const int32_t c = centres[i] - s_eff;
-    if (votes[c] > 0.f) {
-      lo = c - span / 2; hi = lo + span;
-      lo = lo < 0 ? 0 : lo;
-      hi = hi > (int32_t)n_mid ? (int32_t)n_mid : hi;
-    }
+constexpr int kMergeThreads = 1024;     // also the largest number of centres
+constexpr int kPickCache = 12288;       // composites the dense pick keeps in LDS (96 KiB)
+constexpr size_t kPickLds = (size_t)kPickCache * 8 + 2048 * 4;
+
+struct SpanArgs {
+  int32_t s_eff; int64_t n_mid; int kc, span;
+  int32_t* sel; int32_t* n_sel;
+};
+
+template <bool MAX>
+__device__ __forceinline__ int32_t block_scan_i32(int32_t v, int32_t* wsum) {   // inclusive, 1024 threads
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  int32_t x = v;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const int32_t y = __shfl_up(x, o, 64);
+    if (lane >= o) x = MAX ? (x > y ? x : y) : x + y;
   }
-  // exclusive prefix maximum of hi (centres ascend, so spans overlap only with predecessors)
-  sh_a[i] = hi;
+  if (lane == 63) wsum[wave] = x;
   __syncthreads();
-  for (int o = 1; o < 1024; o <<= 1) {
-    const int32_t v = i >= o ? sh_a[i - o] : 0;
-    __syncthreads();
-    sh_a[i] = sh_a[i] > v ? sh_a[i] : v;
-    __syncthreads();
+  int32_t base = 0;
+#pragma unroll
+  for (int w = 0; w < kMergeThreads / 64; ++w) {
+    const int32_t s = wsum[w];
+    if (w < wave) base = MAX ? (base > s ? base : s) : base + s;
   }
-  const int32_t before = i > 0 ? sh_a[i - 1] : 0;
+  __syncthreads();
+  return MAX ? (x > base ? x : base) : x + base;
+}
+
+// win[0 .. nc): the centres (distinct tokens relative to the middle, any order), nc <= 1024.
+// Sorts them, clips each span to the middle, unions overlapping spans (a span can only
+// overlap spans of earlier centres once they ascend) and writes the ascending index list.
+__device__ __forceinline__ void centres_to_spans(int32_t* win, int nc, int32_t* sa, int32_t* sb,
+                                                 int32_t* wsum, const SpanArgs& a) {
+  const int i = threadIdx.x;
+  const int32_t mine = i < nc ? win[i] : 0;
+  int rank = 0;
+  for (int j = 0; j < nc; ++j) rank += win[j] < mine ? 1 : 0;
+  __syncthreads();
+  if (i < nc) sa[rank] = mine;                         // ascending centres
+  __syncthreads();
+  int32_t lo = 0, hi = 0;
+  if (i < nc) {
+    const int64_t l64 = (int64_t)sa[i] - a.span / 2, h64 = l64 + a.span;
+    lo = (int32_t)(l64 < 0 ? 0 : l64);
+    hi = (int32_t)(h64 > a.n_mid ? a.n_mid : h64);
+  }
+  __syncthreads();
+  const int32_t hmax = block_scan_i32<true>(hi, wsum);           // inclusive prefix maximum of hi
+  sb[i] = hmax;
+  __syncthreads();
+  const int32_t before = i > 0 ? sb[i - 1] : 0;
   const int32_t start = lo > before ? lo : before;
   const int32_t len = hi > start ? hi - start : 0;
-  sh_b[i] = len;
   __syncthreads();
-  for (int o = 1; o < 1024; o <<= 1) {
-    const int32_t v = i >= o ? sh_b[i - o] : 0;
-    __syncthreads();
-    sh_b[i] += v;
-    __syncthreads();
+  const int32_t end_at = block_scan_i32<false>(len, wsum);       // inclusive prefix sum of lengths
+  sa[i] = end_at; sb[i] = start - (end_at - len);                // output slot o of centre i holds sb[i] + o
+  __syncthreads();
+  const int32_t total = sa[kMergeThreads - 1];
+  for (int32_t o = i; o < total; o += kMergeThreads) {
+    int l = 0, h = kMergeThreads - 1;                  // first centre whose inclusive end exceeds o
+    while (l < h) {
+      const int mid = (l + h) >> 1;
+      if (sa[mid] > o) h = mid; else l = mid + 1;
+    }
+    a.sel[o] = a.s_eff + sb[l] + o;
   }
-  const int32_t at = sh_b[i] - len;
-  for (int32_t t = 0; t < len; ++t) sel[at + t] = s_eff + start + t;
-  if (i == 1023) *n_sel = sh_b[1023];
+  if (i == 0) *a.n_sel = total;
+}
+
+// Up to 1024 votes (a decode step: Hq * vote_k): everything in one workgroup, no vote array.
+__global__ __launch_bounds__(kMergeThreads) void vote_merge_small_kernel(const int32_t* __restrict__ lists,
+                                                                         int n_votes, SpanArgs a) {
+  __shared__ int32_t tok[kMergeThreads], win[kMergeThreads], sa[kMergeThreads], sb[kMergeThreads];
+  __shared__ uint64_t comp[kMergeThreads];
+  __shared__ int32_t wsum[kMergeThreads / 64];
+  const int t = threadIdx.x;
+  const int32_t v = t < n_votes ? lists[t] - a.s_eff : -1;
+  tok[t] = v;
+  __syncthreads();
+  uint32_t votes = 0;
+  bool first = true;                                   // the earliest vote for a token stands for it
+  for (int j = 0; j < n_votes; ++j) {
+    const int32_t x = tok[j];
+    votes += x == v ? 1u : 0u;
+    first = first && !(x == v && j < t);
+  }
+  const bool owner = t < n_votes && first;
+  const uint64_t c = owner ? vote_composite(votes, (uint32_t)v) : 0ull;
+  comp[t] = c;
+  __syncthreads();
+  int rank = 0;                                        // distinct tokens ahead of this one
+  for (int j = 0; j < n_votes; ++j) rank += comp[j] > c ? 1 : 0;
+  const int n_owner = __syncthreads_count(owner);
+  if (owner && rank < a.kc) win[rank] = v;             // composites are distinct: ranks are a permutation
+  __syncthreads();
+  centres_to_spans(win, n_owner < a.kc ? n_owner : a.kc, sa, sb, wsum, a);
+}
+
+// More votes than one workgroup ranks by comparison: a dense vote array over the middle.
+// The thread whose atomic finds a zero stands for the token and lists it in its workgroup's
+// segment; unused slots of the segment are marked.
+__global__ __launch_bounds__(kMergeThreads) void vote_count_kernel(const int32_t* __restrict__ lists,
+                                                                   int64_t n_votes, int32_t s_eff,
+                                                                   uint32_t* counts, int32_t* seg) {
+  __shared__ uint32_t n_own;
+  if (threadIdx.x == 0) n_own = 0;
+  __syncthreads();
+  const int64_t i = (int64_t)blockIdx.x * kMergeThreads + threadIdx.x;
+  int32_t* my_seg = seg + (int64_t)blockIdx.x * kMergeThreads;
+  if (i < n_votes) {
+    const int32_t v = lists[i] - s_eff;
+    if (atomicAdd(&counts[v], 1u) == 0u) my_seg[atomicAdd(&n_own, 1u)] = v;
+  }
+  __syncthreads();
+  if (threadIdx.x >= n_own) my_seg[threadIdx.x] = -1;
+}
+
+// Once every vote is counted: the composite of every listed token (0 in unused slots).
+__global__ __launch_bounds__(kMergeThreads) void vote_composite_kernel(const int32_t* __restrict__ seg,
+                                                                       const uint32_t* __restrict__ counts,
+                                                                       uint64_t* comp) {
+  const int64_t i = (int64_t)blockIdx.x * kMergeThreads + threadIdx.x;
+  const int32_t v = seg[i];
+  comp[i] = v >= 0 ? vote_composite(counts[v], (uint32_t)v) : 0ull;
+}
+
+// One workgroup: radix select of the kc largest composites (11-bit digits from `top_bit`
+// down), then sort + spans.  n_slots is a multiple of 1024.
+__global__ __launch_bounds__(kMergeThreads) void vote_pick_kernel(const uint64_t* __restrict__ comp,
+                                                                  int64_t n_slots, int top_bit, SpanArgs a) {
+  extern __shared__ uint64_t pick_lds[];
+  uint64_t* cached = pick_lds;                                  // [kPickCache]
+  uint32_t* bins = (uint32_t*)(pick_lds + kPickCache);          // [2048]
+  __shared__ int32_t win[kMergeThreads], sa[kMergeThreads], sb[kMergeThreads];
+  __shared__ int32_t wsum[kMergeThreads / 64];
+  __shared__ uint32_t sh[40];
+  __shared__ uint32_t n_win;
+  uint32_t mine = 0;
+  for (int64_t i = threadIdx.x; i < n_slots; i += kMergeThreads) {
+    const uint64_t c = comp[i];
+    if (i < kPickCache) cached[i] = c;
+    mine += c ? 1u : 0u;
+  }
+  if (threadIdx.x == 0) n_win = 0;
+  uint32_t n;                                                   // distinct voted tokens
+  block_scan_incl<kMergeThreads>(mine, sh, n);
+  auto at = [&](int64_t i) -> uint64_t { return i < kPickCache ? cached[i] : comp[i]; };
+
+  int shift = 0;
+  uint64_t prefix = 0;                                          // winners: c != 0 and (c >> shift) >= prefix
+  if ((uint32_t)a.kc < n) {
+    shift = top_bit;
+    uint32_t remaining = (uint32_t)a.kc;
+    while (shift > 0) {
+      const int w = shift < 11 ? shift : 11;
+      shift -= w;
+      for (int b = threadIdx.x; b < 2048; b += kMergeThreads) bins[b] = 0;
+      __syncthreads();
+      for (int64_t i = threadIdx.x; i < n_slots; i += kMergeThreads) {
+        const uint64_t c = at(i);
+        if (c && (c >> (shift + w)) == prefix)
+          atomicAdd(&bins[(uint32_t)(c >> shift) & ((1u << w) - 1u)], 1u);
+      }
+      __syncthreads();
+      uint32_t d, ab;
+      find_kth_bin<kMergeThreads, 2048>(bins, remaining, sh, d, ab);
+      const uint32_t in_bin = bins[d];
+      remaining -= ab;
+      prefix = (prefix << w) | d;
+      __syncthreads();
+      if (in_bin == remaining) break;                           // everything sharing this prefix wins
+    }
+  }
+  for (int64_t i = threadIdx.x; i < n_slots; i += kMergeThreads) {
+    const uint64_t c = at(i);
+    if (c && (c >> shift) >= prefix) win[atomicAdd(&n_win, 1u)] = (int32_t)(0xffffffffu - (uint32_t)c);
+  }
+  __syncthreads();
+  centres_to_spans(win, (int)n_win, sa, sb, wsum, a);
 }
 
 template <typename T, int D, int KT>
@@ -288,47 +558,111 @@ bool vote_scan_applies(const Plan& pl) {
   return pl.G <= 8 && ((pl.dtype == 1 && pl.D == 128) || (pl.dtype == 0 && pl.D == 64));
 }
 
-int vote_scan_workgroups(const Plan& pl, int n_query) {
-  const int rpb = scan_rows_per_block(pl.n_mid, (int64_t)pl.Hkv * n_query);
-  return (int)((pl.n_mid + rpb - 1) / rpb);
+// Geometry of one scan launch over n_query query rows.
+struct ScanGeom { bool mfma; int nb, q_per_pass, n_pass, rpb, n_wg; };
+
+ScanGeom scan_geom(const Plan& pl, int n_query) {
+  ScanGeom g;
+  g.mfma = pl.dtype == 1 && pl.D == 128;
+  if (g.mfma) {
+    g.nb = n_query * pl.G <= 16 ? 1 : 2;               // column blocks of 16 (query row, head) pairs
+    g.q_per_pass = 16 * g.nb / pl.G;
+    g.n_pass = (n_query + g.q_per_pass - 1) / g.q_per_pass;
+  } else {
+    g.nb = 0; g.q_per_pass = 1; g.n_pass = n_query;    // the vector-ALU scan streams once per query row
+  }
+  g.rpb = scan_rows_per_block(pl.n_mid, (int64_t)pl.Hkv * g.n_pass);
+  g.n_wg = (int)((pl.n_mid + g.rpb - 1) / g.rpb);
+  return g;
+}
+
+// Query rows one launch may take: grid.y = passes * Hkv stays below 65536.
+int vote_queries_per_launch(const Plan& pl) {
+  const ScanGeom one = scan_geom(pl, pl.M);
+  const int64_t per = (int64_t)(65535 / pl.Hkv) * one.q_per_pass;
+  return (int)(per < pl.M ? per : pl.M);
 }
 
 size_t vote_part_bytes(const Plan& pl, int n_query, int vote_k) {
-  return (size_t)n_query * pl.Hq * vote_scan_workgroups(pl, n_query) * vote_list_len(vote_k) * sizeof(uint64_t);
+  return (size_t)n_query * pl.Hq * scan_geom(pl, n_query).n_wg * vote_list_len(vote_k) * sizeof(uint64_t);
+}
+
+template <int KT>
+hipError_t mfma_launch_nb(const MfmaScanArgs& a, int nb, dim3 grid, hipStream_t st) {
+  const size_t lds = (size_t)kVoteWaves * 16 * nb * KT * sizeof(uint64_t);
+  if (nb == 1) hipLaunchKernelGGL((head_topk_mfma_kernel<KT, 1>), grid, dim3(kVoteThreads), lds, st, a);
+  else         hipLaunchKernelGGL((head_topk_mfma_kernel<KT, 2>), grid, dim3(kVoteThreads), lds, st, a);
+  return hipGetLastError();
 }
 
 // head_topk[i][hq][vote_k] for queries [0, n_query): ascending absolute indices.
 hipError_t launch_head_topk_scan(const Plan& pl, const void* q, int n_query, const void* k_cache,
                                  int vote_k, uint64_t* part, int32_t* head_topk, hipStream_t st) {
   if (pl.n_mid <= 0 || n_query <= 0 || vote_k <= 0) return hipSuccess;
-  HeadScanArgs a;
-  a.k = k_cache; a.q = q; a.part = part;
-  a.ksh = pl.ksh; a.kst = pl.kst; a.n_mid = pl.n_mid; a.first_tok = pl.s_eff;
-  a.Hq = pl.Hq; a.Hkv = pl.Hkv; a.G = pl.G;
-  a.rows_per_block = scan_rows_per_block(pl.n_mid, (int64_t)pl.Hkv * n_query);
-  a.n_wg = (int)((pl.n_mid + a.rows_per_block - 1) / a.rows_per_block);
+  const ScanGeom g = scan_geom(pl, n_query);
   const int kt = vote_list_len(vote_k);
-  const dim3 grid((unsigned)a.n_wg, (unsigned)(pl.Hkv * n_query));
-  hipError_t e = pl.dtype == 0 ? scan_launch_kt<float, 64>(a, kt, grid, st)
-                               : scan_launch_kt<uint16_t, 128>(a, kt, grid, st);
+  const dim3 grid((unsigned)g.n_wg, (unsigned)(pl.Hkv * g.n_pass));
+  hipError_t e;
+  if (g.mfma) {
+    MfmaScanArgs a;
+    a.k = k_cache; a.q = q; a.part = part;
+    a.ksh = pl.ksh; a.kst = pl.kst; a.n_mid = pl.n_mid; a.first_tok = pl.s_eff;
+    a.Hq = pl.Hq; a.Hkv = pl.Hkv; a.G = pl.G; a.n_query = n_query; a.q_per_pass = g.q_per_pass;
+    a.rows_per_block = g.rpb; a.n_wg = g.n_wg;
+    e = kt == 1 ? mfma_launch_nb<1>(a, g.nb, grid, st) : kt == 2 ? mfma_launch_nb<2>(a, g.nb, grid, st)
+      : kt == 4 ? mfma_launch_nb<4>(a, g.nb, grid, st) : mfma_launch_nb<8>(a, g.nb, grid, st);
+  } else {
+    HeadScanArgs a;
+    a.k = k_cache; a.q = q; a.part = part;
+    a.ksh = pl.ksh; a.kst = pl.kst; a.n_mid = pl.n_mid; a.first_tok = pl.s_eff;
+    a.Hq = pl.Hq; a.Hkv = pl.Hkv; a.G = pl.G;
+    a.rows_per_block = g.rpb; a.n_wg = g.n_wg;
+    e = scan_launch_kt<float, 64>(a, kt, grid, st);
+  }
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(head_topk_merge_kernel, dim3((unsigned)(n_query * pl.Hq)), dim3(64), 0, st, part,
-                     a.n_wg * kt, vote_k, (int32_t)pl.s_eff, head_topk);
+                     g.n_wg * kt, vote_k, (int32_t)pl.s_eff, head_topk);
   return hipGetLastError();
 }
 
-hipError_t launch_vote_scatter(const Plan& pl, const int32_t* head_topk, int64_t n_votes, float* votes,
-                               hipStream_t st) {
-  if (n_votes <= 0) return hipSuccess;
-  hipLaunchKernelGGL(vote_scatter_kernel, dim3((unsigned)((n_votes + 255) / 256)), dim3(256), 0, st,
-                     head_topk, n_votes, (int32_t)pl.s_eff, votes);
-  return hipGetLastError();
+// Bytes of the dense vote array, the owner segments and their composites (0 for the small path).
+void vote_merge_layout(const Plan& pl, int64_t n_votes, size_t* counts_bytes, size_t* seg_bytes,
+                       size_t* comp_bytes) {
+  const bool dense = n_votes > kMergeThreads && pl.n_mid > 0;
+  const size_t slots = dense ? (size_t)((n_votes + kMergeThreads - 1) / kMergeThreads) * kMergeThreads : 0;
+  *counts_bytes = dense ? (size_t)pl.n_mid * 4 : 0;
+  *seg_bytes = slots * 4;
+  *comp_bytes = slots * 8;
 }
 
-hipError_t launch_span_union(const Plan& pl, const int32_t* centres, int kc, const float* votes, int span,
-                             int32_t* sel, int32_t* n_sel, hipStream_t st) {
-  hipLaunchKernelGGL(span_union_kernel, dim3(1), dim3(1024), 0, st, centres, kc, votes, (int32_t)pl.s_eff,
-                     pl.n_mid, span, sel, n_sel);
+// lists: n_rows lists of kk absolute indices.  kc centres (<= 1024), span m.
+hipError_t launch_vote_merge(const Plan& pl, const int32_t* lists, int64_t n_rows, int kk, int kc, int span,
+                             uint32_t* counts, int32_t* seg, uint64_t* comp, int32_t* sel, int32_t* n_sel,
+                             hipStream_t st) {
+  const int64_t n_votes = n_rows * kk;
+  SpanArgs a;
+  a.s_eff = (int32_t)pl.s_eff; a.n_mid = pl.n_mid; a.kc = kc; a.span = span; a.sel = sel; a.n_sel = n_sel;
+  if (n_votes <= kMergeThreads) {
+    hipLaunchKernelGGL(vote_merge_small_kernel, dim3(1), dim3(kMergeThreads), 0, st, lists, (int)n_votes, a);
+    return hipGetLastError();
+  }
+  static bool lds_ok = false;
+  if (!lds_ok) {
+    hipError_t e = hipFuncSetAttribute((const void*)vote_pick_kernel,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)kPickLds);
+    if (e != hipSuccess) return e;
+    lds_ok = true;
+  }
+  const unsigned n_blocks = (unsigned)((n_votes + kMergeThreads - 1) / kMergeThreads);
+  hipError_t e = launch_fill_u32(counts, pl.n_mid, 0u, st);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(vote_count_kernel, dim3(n_blocks), dim3(kMergeThreads), 0, st, lists, n_votes,
+                     (int32_t)pl.s_eff, counts, seg);
+  hipLaunchKernelGGL(vote_composite_kernel, dim3(n_blocks), dim3(kMergeThreads), 0, st, seg, counts, comp);
+  int top_bit = 33;                                    // 32 index bits + the bits of the largest vote count
+  while (top_bit < 63 && (n_rows >> (top_bit - 32)) != 0) ++top_bit;
+  hipLaunchKernelGGL(vote_pick_kernel, dim3(1), dim3(kMergeThreads), kPickLds, st, comp,
+                     (int64_t)n_blocks * kMergeThreads, top_bit, a);
   return hipGetLastError();
 }
 

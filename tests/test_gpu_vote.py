@@ -36,6 +36,8 @@ CASES = {
     "f32_g4_decode": (wl.CONFIGS[1].scaled(n_ctx=9_973, n_local=200, top_k=0, max_position=0), B.Vote(1, 5, 7)),
     "bf16_g1_chunk": (wl.CONFIGS[4].scaled(n_ctx=12_000, n_q_heads=8, n_query=9, n_local=128, top_k=0), B.Vote(2, 33, 5)),
     "bf16_g8_chunk": (wl.CONFIGS[4].scaled(n_ctx=8_000, n_kv_heads=4, n_query=17, n_local=64, top_k=0), B.Vote(4, 40, 9)),
+    "bf16_g4_two_blocks": (wl.CONFIGS[2].scaled(n_ctx=40_000, n_query=7, n_local=300, top_k=0), B.Vote(4, 64, 8)),
+    "bf16_g3_passes": (wl.CONFIGS[5].scaled(n_ctx=9_000, n_query=23, n_local=100, top_k=0, max_position=0), B.Vote(2, 30, 4)),
     "f32_g5_chunk": (wl.CONFIGS[1].scaled(n_ctx=5_000, n_q_heads=10, n_kv_heads=2, n_query=6, n_local=100, top_k=0,
                                           max_position=0), B.Vote(3, 11, 64)),
 }
@@ -87,6 +89,32 @@ def test_vote_merge_on_given_lists_heavy_ties():
         sel, n_sel = B.vote_merge(p, v, torch.from_numpy(lists).cuda(), ws)
         torch.cuda.synchronize()
         want = ro.vote_merge(lists.reshape(-1, 4), n_mid, s_eff, v.n_centres, v.span)
+        assert sel.cpu().numpy()[: int(n_sel.item())].tolist() == want["sel"].tolist()
+
+
+@pytest.mark.parametrize("n_query,pool_size,vote", [
+    (40, 60, B.Vote(4, 6, 10)),          # 5,120 votes on 60 tokens: every count ties with others
+    (40, 3_000, B.Vote(4, 127, 32)),     # most tokens voted once or twice
+    (512, 30_000, B.Vote(4, 127, 32)),   # 65,536 votes, more distinct tokens than the pick caches in LDS
+    (512, 100, B.Vote(8, 1024, 1)),      # fewer voted tokens than centres: all of them are kept
+])
+def test_vote_merge_dense_path(n_query, pool_size, vote):
+    """More than 1024 votes: atomic counts in a dense array + radix select of the centres."""
+    w = wl.CONFIGS[2].scaled(n_ctx=50_000, n_local=600, top_k=0, n_query=n_query, max_position=0)
+    p = B.Params.from_workload(w)
+    rng = np.random.default_rng(pool_size)
+    s_eff, l_eff, n_mid, _, _ = B.scope(p)
+    kk = vote.vote_k
+    pool = rng.choice(n_mid, size=pool_size, replace=False) + s_eff
+    weights = rng.dirichlet(np.full(pool_size, 0.3))       # a few favourites, a long tail
+    lists = np.stack([np.sort(rng.choice(pool, size=kk, replace=False, p=weights))
+                      for _ in range(n_query * w.n_q_heads)]).astype(np.int32)
+    lists = lists.reshape(n_query, w.n_q_heads, kk)
+    ws = B.alloc_vote_workspace(p, vote)
+    for _ in range(2):                                       # the workspace comes back dirty
+        sel, n_sel = B.vote_merge(p, vote, torch.from_numpy(lists).cuda(), ws)
+        torch.cuda.synchronize()
+        want = ro.vote_merge(lists.reshape(-1, kk), n_mid, s_eff, vote.n_centres, vote.span)
         assert sel.cpu().numpy()[: int(n_sel.item())].tolist() == want["sel"].tolist()
 
 
