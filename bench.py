@@ -35,6 +35,10 @@ def main() -> int:
                     help="skip the config-4 prefill-chunk measurement (MFMA score contraction)")
     ap.add_argument("--only-prefill", action="store_true",
                     help="run the config-4 prefill leg alone and print its object (for profiling runs)")
+    ap.add_argument("--no-vote", action="store_true",
+                    help="skip the vote-selection decode step (the paper's own way of combining heads)")
+    ap.add_argument("--only-vote", action="store_true",
+                    help="run the vote-selection leg alone and print its object (for profiling runs)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy 3 times (a known-size kernel against "
                          "which rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings are scaled)")
@@ -54,6 +58,10 @@ def main() -> int:
     torch.cuda.set_device(0)
     if args.only_prefill:
         print(json.dumps({"prefill": prefill_leg(min(args.steps, 5))}), flush=True)
+        return 0
+    if args.only_vote:
+        print(json.dumps({"vote": vote_leg(wl.generate(wl.CONFIGS[args.config], "cuda"), args.config,
+                                           args.steps, args.warmup)}), flush=True)
         return 0
     w = wl.CONFIGS[args.config]
     p = B.Params.from_workload(w)
@@ -135,6 +143,8 @@ def main() -> int:
         },
     }
 
+    if not args.no_vote:
+        result["vote"] = vote_leg(t, args.config, args.steps, args.warmup)
     if not args.no_prefill:
         del ks, vs, t, ws
         torch.cuda.empty_cache()
@@ -191,6 +201,51 @@ def prefill_leg(steps: int) -> dict:
             "executed_mfma_flops": executed,
             "executed_TFLOPs": round(executed / (gemm_ms * 1e-3) / 1e12, 1),
             "executed_frac": round(executed / (gemm_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+            "traffic": None,
+        },
+    }
+
+
+def vote_leg(t: dict, cfg: int, steps: int, warmup: int) -> dict:
+    """The same decode step with the paper's own selection (Method, last paragraph of the cache
+    selection; Setup: every head votes for its top 4, the 127 most voted tokens with spans of
+    32): fused score + per-head top-k scan on the matrix cores, vote merge, shared-set attention."""
+    import torch
+    from paper_2407_15176_amd import binding as B
+    from paper_2407_15176_amd import workloads as wl
+    w = wl.CONFIGS[cfg].scaled(top_k=0)
+    v = B.Vote(4, 127, 32)
+    p = B.Params.from_workload(w)
+    ws = B.alloc_vote_workspace(p, v)
+    out = torch.empty(1, w.n_q_heads, w.head_dim, dtype=torch.float32, device="cuda")
+    sel = torch.empty(B.vote_cap(p, v), dtype=torch.int32, device="cuda")
+    n_sel = torch.zeros(1, dtype=torch.int32, device="cuda")
+
+    def step():
+        B.vote_layer(p, v, t["q"], t["k"], t["v"], ws, sel=sel, n_sel=n_sel, out=out)
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    ms_step = (time.perf_counter() - t0) * 1e3 / steps
+    acc = {s: 0.0 for s in B.VOTE_STAGES}
+    for _ in range(steps):
+        *_, ms = B.vote_layer_timed(p, v, t["q"], t["k"], t["v"], ws, sel=sel, n_sel=n_sel, out=out)
+        for s in acc:
+            acc[s] += ms[s] / steps
+    scan_gbps = w.scan_bytes / (acc["head_topk_scan"] * 1e-3) / 1e9
+    return {
+        "workload": w.name, "vote_k": v.vote_k, "n_centres": v.n_centres, "span": v.span,
+        "n_selected": int(n_sel.item()), "ms_per_step": round(ms_step, 5), "steps": steps,
+        "stages_ms": {s: round(x, 5) for s, x in acc.items()},
+        "roofline": {
+            "kernel": "head_topk_mfma_kernel (+ list merge)", "bound": "hbm",
+            "achieved": round(scan_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+            "frac": round(scan_gbps / HBM_PEAK_GBPS, 4), "algorithmic_bytes": w.scan_bytes,
             "traffic": None,
         },
     }

@@ -199,6 +199,16 @@ int reattn_prefill_chunk_timed(const reattn_params* p, const void* q, const void
                                const void* v_cache, int32_t* idx_out, float* out,
                                void* ws, size_t ws_bytes, void* stream, float* stage_ms);
 
+/* Measurement aid: reattn_vote_layer with HIP events at the stage boundaries; WAITS and fills
+ * the HOST array stage_ms[REATTN_N_VOTE_STAGES] with
+ *   [0] the fused score + per-head top-k scan of the key cache (+ the merge of the workgroups'
+ *       lists),  [1] votes -> centres -> spans,  [2] rotary table + attention of Eq. 3. */
+#define REATTN_N_VOTE_STAGES 3
+int reattn_vote_layer_timed(const reattn_params* p, const reattn_vote* v, const void* q,
+                            const void* k_cache, const void* v_cache, int32_t* sel_out,
+                            int32_t* n_sel_out, float* out, void* ws, size_t ws_bytes, void* stream,
+                            float* stage_ms);
+
 /* Measurement aid: streams `bytes` of the device buffer `buf` (16-byte aligned)
  * `iters` times with the key scan's load shape and nothing else (no arithmetic, no
  * stores) and reports the rate in GB/s into the HOST float *gb_per_s: the practical

@@ -29,9 +29,11 @@ EXPORTS = [
     "reattn_attend", "reattn_decode_step", "reattn_prefill_chunk", "reattn_decode_step_timed",
     "reattn_probe_read_bandwidth", "reattn_prefill_chunk_timed",
     "reattn_vote_workspace_bytes", "reattn_vote_topk", "reattn_vote_merge", "reattn_vote_layer",
+    "reattn_vote_layer_timed",
 ]
 PREFILL_STAGES = ("sample_threshold", "score_gemm_filter", "candidate_topk", "attend")
 STAGES = ("prep", "scan", "topk", "attend")
+VOTE_STAGES = ("head_topk_scan", "vote_merge", "attend")
 
 
 class CParams(C.Structure):
@@ -92,6 +94,7 @@ def lib() -> C.CDLL:
         L.reattn_vote_topk.argtypes = [PP, PV, P, P, P, P, C.c_size_t, P]
         L.reattn_vote_merge.argtypes = [PP, PV, P, P, P, P, C.c_size_t, P]
         L.reattn_vote_layer.argtypes = [PP, PV, P, P, P, P, P, P, P, C.c_size_t, P]
+        L.reattn_vote_layer_timed.argtypes = L.reattn_vote_layer.argtypes + [C.POINTER(C.c_float)]
         _lib = L
     return _lib
 
@@ -366,3 +369,22 @@ def vote_layer(p: Params, v: Vote, q, k_cache, v_cache, ws, sel=None, n_sel=None
                                    _dev(out, "out", torch.float32), _dev(ws, "ws"), ws.numel(), _stream()),
            "reattn_vote_layer")
     return out, sel, n_sel
+
+
+def vote_layer_timed(p: Params, v: Vote, q, k_cache, v_cache, ws, sel=None, n_sel=None, out=None):
+    """vote_layer with per-stage HIP-event timing; synchronises.  Returns (out, sel, n_sel, {stage: ms})."""
+    if out is None:
+        out = torch.empty(p.n_query, p.n_q_heads, p.head_dim, dtype=torch.float32, device=q.device)
+    if sel is None:
+        sel = torch.empty(max(vote_cap(p, v), 1), dtype=torch.int32, device=q.device)
+    if n_sel is None:
+        n_sel = torch.zeros(1, dtype=torch.int32, device=q.device)
+    ms = (C.c_float * len(VOTE_STAGES))()
+    cp, cv = p.c(), v.c()
+    _check(lib().reattn_vote_layer_timed(C.byref(cp), C.byref(cv), _dev(q, "q", p.torch_dtype()),
+                                         _dev(k_cache, "k_cache", p.torch_dtype()),
+                                         _dev(v_cache, "v_cache", p.torch_dtype()),
+                                         _dev(sel, "sel", torch.int32), _dev(n_sel, "n_sel", torch.int32),
+                                         _dev(out, "out", torch.float32), _dev(ws, "ws"), ws.numel(),
+                                         _stream(), ms), "reattn_vote_layer_timed")
+    return out, sel, n_sel, dict(zip(VOTE_STAGES, [float(x) for x in ms]))

@@ -468,9 +468,9 @@ extern "C" int reattn_vote_merge(const reattn_params* p, const reattn_vote* v, c
   return vote_merge_impl(vp, head_topk, sel, n_sel, (char*)ws, (hipStream_t)stream);
 }
 
-extern "C" int reattn_vote_layer(const reattn_params* p, const reattn_vote* v, const void* q,
-                                 const void* k_cache, const void* v_cache, int32_t* sel_out,
-                                 int32_t* n_sel_out, float* out, void* ws, size_t ws_bytes, void* stream) {
+static int vote_layer_impl(const reattn_params* p, const reattn_vote* v, const void* q, const void* k_cache,
+                           const void* v_cache, int32_t* sel_out, int32_t* n_sel_out, float* out, void* ws,
+                           size_t ws_bytes, void* stream, hipEvent_t* ev) {
   VotePlan vp;
   int rc = make_vote_plan(p, v, &vp);
   if (rc) return rc;
@@ -484,8 +484,11 @@ extern "C" int reattn_vote_layer(const reattn_params* p, const reattn_vote* v, c
   int32_t* lists = (int32_t*)(b + vp.off_lists);
   int32_t* sel = sel_out ? sel_out : (int32_t*)(b + vp.off_sel);
   int32_t* n_sel = n_sel_out ? n_sel_out : (int32_t*)(b + vp.off_nsel);
+  mark(ev, 0, st);
   rc = vote_topk_impl(vp, q, k_cache, lists, b, st);
+  mark(ev, 1, st);
   if (!rc) rc = vote_merge_impl(vp, lists, sel, n_sel, b, st);
+  mark(ev, 2, st);
   if (rc) return rc;
   Ws w;
   rc = bind_ws(pl, ws, pl.total, &w);
@@ -493,8 +496,37 @@ extern "C" int reattn_vote_layer(const reattn_params* p, const reattn_vote* v, c
   rc = hip_rc(launch_prep(pl, 0, nullptr, w.rope, st));
   if (rc) return rc;
   // one shared index row for every (query, KV head); its length is read on the device
-  return hip_rc(launch_attend(pl, true, q, 0, pl.M, k_cache, v_cache, sel, w.rope, w.part, out, st,
-                              n_sel, 0));
+  rc = hip_rc(launch_attend(pl, true, q, 0, pl.M, k_cache, v_cache, sel, w.rope, w.part, out, st,
+                            n_sel, 0));
+  mark(ev, 3, st);
+  return rc;
+}
+
+extern "C" int reattn_vote_layer(const reattn_params* p, const reattn_vote* v, const void* q,
+                                 const void* k_cache, const void* v_cache, int32_t* sel_out,
+                                 int32_t* n_sel_out, float* out, void* ws, size_t ws_bytes, void* stream) {
+  return vote_layer_impl(p, v, q, k_cache, v_cache, sel_out, n_sel_out, out, ws, ws_bytes, stream, nullptr);
+}
+
+extern "C" int reattn_vote_layer_timed(const reattn_params* p, const reattn_vote* v, const void* q,
+                                       const void* k_cache, const void* v_cache, int32_t* sel_out,
+                                       int32_t* n_sel_out, float* out, void* ws, size_t ws_bytes,
+                                       void* stream, float* stage_ms) {
+  if (!stage_ms) return REATTN_ERR_NULL;
+  constexpr int kStages = REATTN_N_VOTE_STAGES;
+  hipEvent_t ev[kStages + 1];
+  int made = 0;
+  for (; made <= kStages; ++made)
+    if (hipEventCreate(&ev[made]) != hipSuccess) break;
+  int rc = made == kStages + 1 ? REATTN_OK : REATTN_ERR_HIP;
+  if (!rc) rc = vote_layer_impl(p, v, q, k_cache, v_cache, sel_out, n_sel_out, out, ws, ws_bytes, stream, ev);
+  if (!rc) {
+    if (hipEventSynchronize(ev[kStages]) != hipSuccess) rc = REATTN_ERR_HIP;
+    for (int i = 0; i < kStages && !rc; ++i)
+      if (hipEventElapsedTime(&stage_ms[i], ev[i], ev[i + 1]) != hipSuccess) rc = REATTN_ERR_HIP;
+  }
+  for (int i = 0; i < made; ++i) (void)hipEventDestroy(ev[i]);
+  return rc;
 }
 
 static int layer_timed(const reattn_params* p, bool decode_only, const void* q, const void* k_cache,

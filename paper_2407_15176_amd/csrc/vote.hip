@@ -180,13 +180,18 @@ __global__ __launch_bounds__(kVoteThreads) void head_topk_scan_kernel(HeadScanAr
 // A key tile of 16 rows is the A operand of v_mfma_f32_16x16x32_bf16 and up to 16 (query row,
 // head) pairs of one KV head are the columns of B, so one MFMA chain of 4 gives 16 x 16 raw
 // scores and the vector ALU only compares: the stream stays HBM-bound however many heads vote.
-// Lane l loads the 16-byte piece 4j + l/16 of key row l%16 for step j (the contraction does
-// not care which 8 channels sit in which k slot as long as B uses the same assignment), so
-// the four loads of a tile cover its 4 KiB exactly once.  The product leaves lane l with the
-// scores of column l%16 against key rows 4(l/16)..+3: one running list per lane and column
-// block, merged over the four lanes of a column, then over the waves.
+// For step j of the chain lane l supplies the 16-byte piece 4j + l/16 of key row l%16 (the
+// contraction does not care which 8 channels sit in which k slot as long as B uses the same
+// assignment).  Loading the keys from memory in that shape (16 rows x 64 bytes per
+// instruction) tops out at 6.0 TB/s; 1 KiB of consecutive memory per instruction reaches
+// 6.9, so tiles are loaded that way and turned into the operand shape through a wave-private,
+// XOR-swizzled LDS stage (no barrier: a wave reads only what it wrote).  The product leaves
+// lane l with the scores of column l%16 against key rows 4(l/16)..+3: one running list per
+// lane and column block, merged over the four lanes of a column, then over the waves.
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kMfmaTiles = 2;                          // key tiles (16 rows) per wave iteration
 
 struct MfmaScanArgs {
   const void* k; const void* q;
@@ -197,8 +202,11 @@ struct MfmaScanArgs {
 
 template <int KT, int NB>
 __global__ __launch_bounds__(kVoteThreads) void head_topk_mfma_kernel(MfmaScanArgs a) {
-  constexpr int D = 128, T = 2, NC = 16 * NB;
-  extern __shared__ uint64_t mfma_best[];              // [kVoteWaves][NC][KT]
+  constexpr int D = 128, T = kMfmaTiles, NC = 16 * NB;
+  // staging of the key tiles [kVoteWaves][T][16 rows][16 pieces] of 16 bytes while streaming,
+  // then the waves' merged lists [kVoteWaves][NC][KT]
+  extern __shared__ uint64_t mfma_lds[];
+  uint64_t* mfma_best = mfma_lds;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int col = lane & 15, kq = lane >> 4;
   const int h = blockIdx.y % a.Hkv, q0 = (blockIdx.y / a.Hkv) * a.q_per_pass;
@@ -229,27 +237,36 @@ __global__ __launch_bounds__(kVoteThreads) void head_topk_mfma_kernel(MfmaScanAr
   const int64_t left = a.n_mid - blk_row0;
   const int nrows = left < a.rows_per_block ? (int)left : a.rows_per_block;
   const int64_t row_bytes = a.kst * 2;
-  const char* kbase = (const char*)a.k + ((int64_t)h * a.ksh + (a.first_tok + blk_row0) * a.kst) * 2 + kq * 16;
+  const char* kbase = (const char*)a.k + ((int64_t)h * a.ksh + (a.first_tok + blk_row0) * a.kst) * 2 + col * 16;
+  u32x4* my = (u32x4*)mfma_lds + wave * (T * 256);     // this wave's T tiles of 16 rows x 16 pieces
 
   for (int t = wave * (T * 16); t < nrows; t += kVoteWaves * (T * 16)) {
-    u32x4 d[T][4];
+    // global -> registers: 1 KiB of consecutive memory per load (lane l: row l/16, piece l%16)
+    u32x4 d[4 * T];
 #pragma unroll
-    for (int tt = 0; tt < T; ++tt) {
-      int r = t + tt * 16 + col;
+    for (int u = 0; u < 4 * T; ++u) {
+      int r = t + u * 4 + kq;
       r = r < nrows ? r : nrows - 1;                   // tail rows re-read the last row; result dropped
-      const char* src = kbase + (int64_t)r * row_bytes;
+      d[u] = __builtin_nontemporal_load((const u32x4*)(kbase + (int64_t)r * row_bytes));
+    }
+    // registers -> wave-private LDS, piece index XOR row so that both sides are conflict free
 #pragma unroll
-      for (int j = 0; j < 4; ++j) d[tt][j] = __builtin_nontemporal_load((const u32x4*)(src + j * 64));
+    for (int u = 0; u < 4 * T; ++u) {
+      const int row = u * 4 + kq;
+      my[row * 16 + (col ^ (row & 15))] = d[u];
     }
 #pragma unroll
     for (int tt = 0; tt < T; ++tt) {
       const int r0 = t + tt * 16 + kq * 4;             // this lane's four key rows of the tile
+      u32x4 ka[4];                                     // LDS -> A operand: row l%16, piece 4j + l/16
+#pragma unroll
+      for (int j = 0; j < 4; ++j) ka[j] = my[(tt * 16 + col) * 16 + ((4 * j + kq) ^ col)];
 #pragma unroll
       for (int nb = 0; nb < NB; ++nb) {
         f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int j = 0; j < 4; ++j)
-          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, d[tt][j]), bq[nb][j], acc, 0, 0, 0);
+          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ka[j]), bq[nb][j], acc, 0, 0, 0);
         const float m01 = acc[0] > acc[1] ? acc[0] : acc[1], m23 = acc[2] > acc[3] ? acc[2] : acc[3];
         if ((m01 > m23 ? m01 : m23) > bv[nb][KT - 1]) {
 #pragma unroll
@@ -272,6 +289,7 @@ __global__ __launch_bounds__(kVoteThreads) void head_topk_mfma_kernel(MfmaScanAr
   }
 
   // the four lanes of a column merge their lists: KT rounds of arg-max over lanes l, l^16, l^32, l^48
+  uint64_t keep[NB][KT];
 #pragma unroll
   for (int nb = 0; nb < NB; ++nb) {
 #pragma unroll
@@ -289,8 +307,16 @@ __global__ __launch_bounds__(kVoteThreads) void head_topk_mfma_kernel(MfmaScanAr
         for (int x = 0; x + 1 < KT; ++x) { bv[nb][x] = bv[nb][x + 1]; bi[nb][x] = bi[nb][x + 1]; }
         bv[nb][KT - 1] = -__builtin_inff(); bi[nb][KT - 1] = 0xffffffffu;
       }
-      if (kq == 0) mfma_best[((size_t)wave * NC + nb * 16 + col) * KT + round] = best;
+      keep[nb][round] = best;
     }
+  }
+  __syncthreads();                                     // every wave is done with its staging area
+  if (kq == 0) {
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+      for (int round = 0; round < KT; ++round)
+        mfma_best[((size_t)wave * NC + nb * 16 + col) * KT + round] = keep[nb][round];
   }
   __syncthreads();
   // workgroup merge: a wave takes every 16th column; its lanes hold the 16 waves' KT entries
@@ -381,7 +407,8 @@ __device__ __forceinline__ void centres_to_spans(int32_t* win, int nc, int32_t* 
   const int i = threadIdx.x;
   const int32_t mine = i < nc ? win[i] : 0;
   int rank = 0;
-  for (int j = 0; j < nc; ++j) rank += win[j] < mine ? 1 : 0;
+  if (i < nc)                                          // the other waves skip the loop altogether
+    for (int j = 0; j < nc; ++j) rank += win[j] < mine ? 1 : 0;
   __syncthreads();
   if (i < nc) sa[rank] = mine;                         // ascending centres
   __syncthreads();
@@ -426,17 +453,19 @@ __global__ __launch_bounds__(kMergeThreads) void vote_merge_small_kernel(const i
   __syncthreads();
   uint32_t votes = 0;
   bool first = true;                                   // the earliest vote for a token stands for it
-  for (int j = 0; j < n_votes; ++j) {
-    const int32_t x = tok[j];
-    votes += x == v ? 1u : 0u;
-    first = first && !(x == v && j < t);
-  }
+  if (t < n_votes)                                     // waves without a vote skip the loops
+    for (int j = 0; j < n_votes; ++j) {
+      const int32_t x = tok[j];
+      votes += x == v ? 1u : 0u;
+      first = first && !(x == v && j < t);
+    }
   const bool owner = t < n_votes && first;
   const uint64_t c = owner ? vote_composite(votes, (uint32_t)v) : 0ull;
   comp[t] = c;
   __syncthreads();
   int rank = 0;                                        // distinct tokens ahead of this one
-  for (int j = 0; j < n_votes; ++j) rank += comp[j] > c ? 1 : 0;
+  if (owner)
+    for (int j = 0; j < n_votes; ++j) rank += comp[j] > c ? 1 : 0;
   const int n_owner = __syncthreads_count(owner);
   if (owner && rank < a.kc) win[rank] = v;             // composites are distinct: ranks are a permutation
   __syncthreads();
@@ -589,9 +618,15 @@ size_t vote_part_bytes(const Plan& pl, int n_query, int vote_k) {
 
 template <int KT>
 hipError_t mfma_launch_nb(const MfmaScanArgs& a, int nb, dim3 grid, hipStream_t st) {
-  const size_t lds = (size_t)kVoteWaves * 16 * nb * KT * sizeof(uint64_t);
-  if (nb == 1) hipLaunchKernelGGL((head_topk_mfma_kernel<KT, 1>), grid, dim3(kVoteThreads), lds, st, a);
-  else         hipLaunchKernelGGL((head_topk_mfma_kernel<KT, 2>), grid, dim3(kVoteThreads), lds, st, a);
+  const size_t lds = (size_t)kVoteWaves * kMfmaTiles * 256 * 16;      // staging; the merged lists fit inside
+  static_assert((size_t)kVoteWaves * 32 * 8 * sizeof(uint64_t) <= (size_t)kVoteWaves * kMfmaTiles * 256 * 16, "lists alias the staging");
+  auto k1 = head_topk_mfma_kernel<KT, 1>;
+  auto k2 = head_topk_mfma_kernel<KT, 2>;
+  hipError_t e = hipFuncSetAttribute(nb == 1 ? (const void*)k1 : (const void*)k2,
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  if (e != hipSuccess) return e;
+  if (nb == 1) hipLaunchKernelGGL(k1, grid, dim3(kVoteThreads), lds, st, a);
+  else         hipLaunchKernelGGL(k2, grid, dim3(kVoteThreads), lds, st, a);
   return hipGetLastError();
 }
 
