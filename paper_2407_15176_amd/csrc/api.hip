@@ -389,7 +389,7 @@ int make_vote_plan(const reattn_params* p, const reattn_vote* v, VotePlan* out) 
     vp.span = (int)(v->span < widest ? v->span : (widest < 0x7fffffffLL ? widest : 0x7fffffffLL));
   }
   if (pl.n_mid > 0 && !vote_scan_applies(pl)) return REATTN_ERR_SHAPE;
-  const int per = pl.n_mid > 0 ? vote_queries_per_launch(pl) : 1;
+  const int per = pl.n_mid > 0 ? vote_queries_per_launch(pl, vp.kk > 0 ? vp.kk : 1) : 1;
   size_t off = pl.total;
   size_t part_bytes = 0;                               // the last launch may take fewer query rows
   if (pl.n_mid > 0) {
@@ -415,7 +415,7 @@ int vote_topk_impl(const VotePlan& vp, const void* q, const void* k_cache, int32
                    char* ws, hipStream_t st) {
   const Plan& pl = vp.pl;
   if (vp.kk == 0) return REATTN_OK;
-  const int per = vote_queries_per_launch(pl);
+  const int per = vote_queries_per_launch(pl, vp.kk);
   const size_t eb = pl.dtype == REATTN_BF16 ? 2 : 4;
   int rc = REATTN_OK;
   for (int q0 = 0; q0 < pl.M && !rc; q0 += per) {

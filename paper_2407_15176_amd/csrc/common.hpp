@@ -77,7 +77,10 @@ hipError_t launch_attend(const Plan& pl, bool fused, const void* q, int q_first,
 // vote selection (vote.hip)
 int vote_list_len(int vote_k);
 bool vote_scan_applies(const Plan& pl);
-int vote_queries_per_launch(const Plan& pl);
+int vote_queries_per_launch(const Plan& pl, int vote_k);
+int vote_gemm_splits(const Plan& pl, int n_query);
+hipError_t launch_vote_gemm(const Plan& pl, const void* q, int n_query, const void* k_cache, int list_len,
+                            uint64_t* part, hipStream_t st);
 size_t vote_part_bytes(const Plan& pl, int n_query, int vote_k);
 hipError_t launch_head_topk_scan(const Plan& pl, const void* q, int n_query, const void* k_cache,
                                  int vote_k, uint64_t* part, int32_t* head_topk, hipStream_t st);

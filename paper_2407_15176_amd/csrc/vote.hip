@@ -588,11 +588,17 @@ bool vote_scan_applies(const Plan& pl) {
 }
 
 // Geometry of one scan launch over n_query query rows.
-struct ScanGeom { bool mfma; int nb, q_per_pass, n_pass, rpb, n_wg; };
+struct ScanGeom { bool mfma, gemm; int nb, q_per_pass, n_pass, rpb, n_wg; };
 
-ScanGeom scan_geom(const Plan& pl, int n_query) {
+ScanGeom scan_geom(const Plan& pl, int n_query, int kt) {
   ScanGeom g;
   g.mfma = pl.dtype == 1 && pl.D == 128;
+  g.gemm = g.mfma && n_query * pl.G > 32;              // more columns than one streaming pass holds
+  if (g.gemm) {                                        // tiled contraction: every key is read once per 256 columns
+    g.nb = 0; g.q_per_pass = n_query; g.n_pass = 1; g.rpb = 0;
+    g.n_wg = vote_gemm_splits(pl, n_query);
+    return g;
+  }
   if (g.mfma) {
     g.nb = n_query * pl.G <= 16 ? 1 : 2;               // column blocks of 16 (query row, head) pairs
     g.q_per_pass = 16 * g.nb / pl.G;
@@ -606,14 +612,15 @@ ScanGeom scan_geom(const Plan& pl, int n_query) {
 }
 
 // Query rows one launch may take: grid.y = passes * Hkv stays below 65536.
-int vote_queries_per_launch(const Plan& pl) {
-  const ScanGeom one = scan_geom(pl, pl.M);
+int vote_queries_per_launch(const Plan& pl, int vote_k) {
+  const ScanGeom one = scan_geom(pl, pl.M, vote_list_len(vote_k));
+  if (one.gemm) return pl.M;
   const int64_t per = (int64_t)(65535 / pl.Hkv) * one.q_per_pass;
   return (int)(per < pl.M ? per : pl.M);
 }
 
 size_t vote_part_bytes(const Plan& pl, int n_query, int vote_k) {
-  return (size_t)n_query * pl.Hq * scan_geom(pl, n_query).n_wg * vote_list_len(vote_k) * sizeof(uint64_t);
+  return (size_t)n_query * pl.Hq * scan_geom(pl, n_query, vote_list_len(vote_k)).n_wg * vote_list_len(vote_k) * sizeof(uint64_t);
 }
 
 template <int KT>
@@ -634,11 +641,13 @@ hipError_t mfma_launch_nb(const MfmaScanArgs& a, int nb, dim3 grid, hipStream_t 
 hipError_t launch_head_topk_scan(const Plan& pl, const void* q, int n_query, const void* k_cache,
                                  int vote_k, uint64_t* part, int32_t* head_topk, hipStream_t st) {
   if (pl.n_mid <= 0 || n_query <= 0 || vote_k <= 0) return hipSuccess;
-  const ScanGeom g = scan_geom(pl, n_query);
   const int kt = vote_list_len(vote_k);
-  const dim3 grid((unsigned)g.n_wg, (unsigned)(pl.Hkv * g.n_pass));
+  const ScanGeom g = scan_geom(pl, n_query, kt);
+  const dim3 grid((unsigned)(g.n_wg > 0 ? g.n_wg : 1), (unsigned)(pl.Hkv * g.n_pass));
   hipError_t e;
-  if (g.mfma) {
+  if (g.gemm) {
+    e = launch_vote_gemm(pl, q, n_query, k_cache, kt, part, st);
+  } else if (g.mfma) {
     MfmaScanArgs a;
     a.k = k_cache; a.q = q; a.part = part;
     a.ksh = pl.ksh; a.kst = pl.kst; a.n_mid = pl.n_mid; a.first_tok = pl.s_eff;

@@ -38,6 +38,10 @@ CASES = {
     "bf16_g8_chunk": (wl.CONFIGS[4].scaled(n_ctx=8_000, n_kv_heads=4, n_query=17, n_local=64, top_k=0), B.Vote(4, 40, 9)),
     "bf16_g4_two_blocks": (wl.CONFIGS[2].scaled(n_ctx=40_000, n_query=7, n_local=300, top_k=0), B.Vote(4, 64, 8)),
     "bf16_g3_passes": (wl.CONFIGS[5].scaled(n_ctx=9_000, n_query=23, n_local=100, top_k=0, max_position=0), B.Vote(2, 30, 4)),
+    "bf16_g4_gemm_ragged": (wl.CONFIGS[4].scaled(n_ctx=20_011, n_q_heads=8, n_kv_heads=2, n_query=150, n_local=160,
+                                                 top_k=0), B.Vote(4, 127, 32)),
+    "bf16_g3_gemm_k8": (wl.CONFIGS[5].scaled(n_ctx=6_000, n_q_heads=6, n_kv_heads=2, n_query=90, n_local=100, top_k=0,
+                                             max_position=0), B.Vote(8, 50, 6)),
     "f32_g5_chunk": (wl.CONFIGS[1].scaled(n_ctx=5_000, n_q_heads=10, n_kv_heads=2, n_query=6, n_local=100, top_k=0,
                                           max_position=0), B.Vote(3, 11, 64)),
 }
