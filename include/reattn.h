@@ -166,7 +166,8 @@ int reattn_vote_topk(const reattn_params* p, const reattn_vote* v, const void* q
                      void* stream);
 
 /* Votes -> centres -> spans: sel[0 .. *n_sel) ascending absolute indices (sel holds cap
- * entries), *n_sel a DEVICE int32.  Pure integer work on the given lists. */
+ * entries), *n_sel a DEVICE int32.  Pure integer work on the given lists; a list entry that
+ * lies outside the middle [s_eff, N - l_eff) is ignored (it casts no vote). */
 int reattn_vote_merge(const reattn_params* p, const reattn_vote* v, const int32_t* head_topk,
                       int32_t* sel, int32_t* n_sel, void* ws, size_t ws_bytes, void* stream);
 

@@ -448,18 +448,19 @@ __global__ __launch_bounds__(kMergeThreads) void vote_merge_small_kernel(const i
   __shared__ uint64_t comp[kMergeThreads];
   __shared__ int32_t wsum[kMergeThreads / 64];
   const int t = threadIdx.x;
-  const int32_t v = t < n_votes ? lists[t] - a.s_eff : -1;
+  int32_t v = t < n_votes ? lists[t] - a.s_eff : -1;
+  if (v < 0 || v >= a.n_mid) v = -1;                   // an entry outside the middle is no vote
   tok[t] = v;
   __syncthreads();
   uint32_t votes = 0;
   bool first = true;                                   // the earliest vote for a token stands for it
-  if (t < n_votes)                                     // waves without a vote skip the loops
+  if (v >= 0)                                          // waves without a vote skip the loops
     for (int j = 0; j < n_votes; ++j) {
       const int32_t x = tok[j];
       votes += x == v ? 1u : 0u;
       first = first && !(x == v && j < t);
     }
-  const bool owner = t < n_votes && first;
+  const bool owner = v >= 0 && first;
   const uint64_t c = owner ? vote_composite(votes, (uint32_t)v) : 0ull;
   comp[t] = c;
   __syncthreads();
@@ -476,7 +477,7 @@ __global__ __launch_bounds__(kMergeThreads) void vote_merge_small_kernel(const i
 // The thread whose atomic finds a zero stands for the token and lists it in its workgroup's
 // segment; unused slots of the segment are marked.
 __global__ __launch_bounds__(kMergeThreads) void vote_count_kernel(const int32_t* __restrict__ lists,
-                                                                   int64_t n_votes, int32_t s_eff,
+                                                                   int64_t n_votes, int32_t s_eff, int32_t n_mid,
                                                                    uint32_t* counts, int32_t* seg) {
   __shared__ uint32_t n_own;
   if (threadIdx.x == 0) n_own = 0;
@@ -485,7 +486,8 @@ __global__ __launch_bounds__(kMergeThreads) void vote_count_kernel(const int32_t
   int32_t* my_seg = seg + (int64_t)blockIdx.x * kMergeThreads;
   if (i < n_votes) {
     const int32_t v = lists[i] - s_eff;
-    if (atomicAdd(&counts[v], 1u) == 0u) my_seg[atomicAdd(&n_own, 1u)] = v;
+    if (v >= 0 && v < n_mid)                           // an entry outside the middle is no vote
+      if (atomicAdd(&counts[v], 1u) == 0u) my_seg[atomicAdd(&n_own, 1u)] = v;
   }
   __syncthreads();
   if (threadIdx.x >= n_own) my_seg[threadIdx.x] = -1;
@@ -701,7 +703,7 @@ hipError_t launch_vote_merge(const Plan& pl, const int32_t* lists, int64_t n_row
   hipError_t e = launch_fill_u32(counts, pl.n_mid, 0u, st);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(vote_count_kernel, dim3(n_blocks), dim3(kMergeThreads), 0, st, lists, n_votes,
-                     (int32_t)pl.s_eff, counts, seg);
+                     (int32_t)pl.s_eff, (int32_t)pl.n_mid, counts, seg);
   hipLaunchKernelGGL(vote_composite_kernel, dim3(n_blocks), dim3(kMergeThreads), 0, st, seg, counts, comp);
   int top_bit = 33;                                    // 32 index bits + the bits of the largest vote count
   while (top_bit < 63 && (n_rows >> (top_bit - 32)) != 0) ++top_bit;

@@ -122,6 +122,27 @@ def test_vote_merge_dense_path(n_query, pool_size, vote):
         assert sel.cpu().numpy()[: int(n_sel.item())].tolist() == want["sel"].tolist()
 
 
+@pytest.mark.parametrize("n_query", [3, 64])           # one-workgroup ranking / dense vote array
+def test_vote_merge_ignores_entries_outside_the_middle(n_query):
+    """Lists are caller data: an entry in the sink, in the local window or past the cache casts no vote."""
+    w = wl.CONFIGS[2].scaled(n_ctx=9_000, n_local=500, top_k=0, n_query=n_query, max_position=0)
+    p = B.Params.from_workload(w)
+    v = B.Vote(4, 20, 8)
+    rng = np.random.default_rng(n_query)
+    s_eff, l_eff, n_mid, _, _ = B.scope(p)
+    lists = (rng.choice(n_mid, size=(n_query, w.n_q_heads, 4)) + s_eff).astype(np.int32)
+    bad = rng.random(lists.shape) < 0.2
+    lists[bad] = rng.choice(np.array([0, s_eff - 1, s_eff + n_mid, w.n_ctx - 1, w.n_ctx + 5, -7], dtype=np.int32),
+                            size=int(bad.sum()))
+    ws = B.alloc_vote_workspace(p, v)
+    sel, n_sel = B.vote_merge(p, v, torch.from_numpy(lists).cuda(), ws)
+    torch.cuda.synchronize()
+    flat = lists.reshape(-1)
+    valid = flat[(flat >= s_eff) & (flat < s_eff + n_mid)]
+    want = ro.vote_merge(valid.reshape(-1, 1), n_mid, s_eff, v.n_centres, v.span)   # pooling ignores the list structure
+    assert sel.cpu().numpy()[: int(n_sel.item())].tolist() == want["sel"].tolist()
+
+
 @pytest.mark.parametrize("kw", [
     dict(n_ctx=300, n_local=512),                    # empty middle: plain attention, nothing selected
     dict(n_ctx=520, n_local=512),                    # middle of 4 tokens: lists clamped to it
