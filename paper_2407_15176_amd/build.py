@@ -16,7 +16,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libreattn.so")
 SOURCES = ["api.hip", "score_scan.hip", "score_gemm.hip", "prefill_select.hip", "topk.hip", "rope.hip",
-           "attend.hip", "attend_prefill.hip", "vote.hip", "vote_gemm.hip"]
+           "attend.hip", "attend_prefill.hip", "vote.hip", "vote_gemm.hip", "attend_shared.hip"]
 HEADERS = [os.path.join(CSRC, "common.hpp"), os.path.join(HERE, "..", "include", "reattn.h")]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

@@ -367,7 +367,7 @@ namespace {
 struct VotePlan {
   Plan pl;                 // base plan with k_eff = cap (largest selection)
   int kk, kc, span;        // votes per list, centres, span (all clamped)
-  size_t off_part, off_lists, off_counts, off_seg, off_comp, off_sel, off_nsel, total;
+  size_t off_part, off_lists, off_counts, off_seg, off_comp, off_sel, off_nsel, off_kp, off_vp, off_qp, total;
 };
 
 int make_vote_plan(const reattn_params* p, const reattn_vote* v, VotePlan* out) {
@@ -406,6 +406,11 @@ int make_vote_plan(const reattn_params* p, const reattn_vote* v, VotePlan* out) 
   vp.off_comp = off;    off += up(mb);
   vp.off_sel = off;     off += up((size_t)(pl.k_eff > 0 ? pl.k_eff : 1) * 4);
   vp.off_nsel = off;    off += up(4);
+  size_t kpb = 0, vpb = 0, qpb = 0;
+  if (attend_shared_applies(pl)) attend_shared_layout(pl, &kpb, &vpb, &qpb);
+  vp.off_kp = off;      off += up(kpb);
+  vp.off_vp = off;      off += up(vpb);
+  vp.off_qp = off;      off += up(qpb);
   vp.total = off;
   *out = vp;
   return REATTN_OK;
@@ -496,8 +501,12 @@ static int vote_layer_impl(const reattn_params* p, const reattn_vote* v, const v
   rc = hip_rc(launch_prep(pl, 0, nullptr, w.rope, st));
   if (rc) return rc;
   // one shared index row for every (query, KV head); its length is read on the device
-  rc = hip_rc(launch_attend(pl, true, q, 0, pl.M, k_cache, v_cache, sel, w.rope, w.part, out, st,
-                            n_sel, 0));
+  if (attend_shared_applies(pl))       // a chunk on bf16 / D = 128: packed once, flash attention on the matrix cores
+    rc = hip_rc(launch_attend_shared(pl, q, k_cache, v_cache, sel, n_sel, w.rope, b + vp.off_kp, b + vp.off_vp,
+                                     b + vp.off_qp, out, st));
+  else
+    rc = hip_rc(launch_attend(pl, true, q, 0, pl.M, k_cache, v_cache, sel, w.rope, w.part, out, st,
+                              n_sel, 0));
   mark(ev, 3, st);
   return rc;
 }
