@@ -39,6 +39,9 @@ def main() -> int:
                     help="skip the vote-selection decode step (the paper's own way of combining heads)")
     ap.add_argument("--only-vote", action="store_true",
                     help="run the vote-selection leg alone and print its object (for profiling runs)")
+    ap.add_argument("--only-vote-prefill", action="store_true",
+                    help="run the vote-selection prefill chunk alone (config 4's cache) and print its object")
+    ap.add_argument("--chunk", type=int, default=4096, help="query rows of --only-vote-prefill")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy 3 times (a known-size kernel against "
                          "which rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings are scaled)")
@@ -58,6 +61,9 @@ def main() -> int:
     torch.cuda.set_device(0)
     if args.only_prefill:
         print(json.dumps({"prefill": prefill_leg(min(args.steps, 5))}), flush=True)
+        return 0
+    if args.only_vote_prefill:
+        print(json.dumps({"vote_prefill": vote_prefill_leg(min(args.steps, 5), args.chunk)}), flush=True)
         return 0
     if args.only_vote:
         print(json.dumps({"vote": vote_leg(wl.generate(wl.CONFIGS[args.config], "cuda"), args.config,
@@ -149,6 +155,9 @@ def main() -> int:
         del ks, vs, t, ws
         torch.cuda.empty_cache()
         result["prefill"] = prefill_leg(min(args.steps, 5))
+        if not args.no_vote:
+            torch.cuda.empty_cache()
+            result["vote_prefill"] = vote_prefill_leg(min(args.steps, 5))
         t = None
     if not args.no_cpu_baseline:
         if t is None:
@@ -202,6 +211,48 @@ def prefill_leg(steps: int) -> dict:
             "executed_TFLOPs": round(executed / (gemm_ms * 1e-3) / 1e12, 1),
             "executed_frac": round(executed / (gemm_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
             "traffic": None,
+        },
+    }
+
+
+def vote_prefill_leg(steps: int, n_query: int = 4096) -> dict:
+    """Config 4's cache with the paper's own selection for a chunk of query rows: per-head top-4 lists
+    of all rows on the matrix cores (no score written), pooled votes -> 127 centres -> spans of 32,
+    then ONE shared set attended by every row (causal inside the local window)."""
+    import torch
+    from paper_2407_15176_amd import binding as B
+    from paper_2407_15176_amd import workloads as wl
+    w = wl.CONFIGS[4].scaled(top_k=0, n_query=n_query)
+    v = B.Vote(4, 127, 32)
+    p = B.Params.from_workload(w)
+    t = wl.generate(w, "cuda")
+    ws = B.alloc_vote_workspace(p, v)
+    out = torch.empty(w.n_query, w.n_q_heads, w.head_dim, dtype=torch.float32, device="cuda")
+    sel = torch.empty(B.vote_cap(p, v), dtype=torch.int32, device="cuda")
+    n_sel = torch.zeros(1, dtype=torch.int32, device="cuda")
+    B.vote_layer(p, v, t["q"], t["k"], t["v"], ws, sel=sel, n_sel=n_sel, out=out)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        B.vote_layer(p, v, t["q"], t["k"], t["v"], ws, sel=sel, n_sel=n_sel, out=out)
+    torch.cuda.synchronize()
+    ms_chunk = (time.perf_counter() - t0) * 1e3 / steps
+    acc = {s: 0.0 for s in B.VOTE_STAGES}
+    for _ in range(steps):
+        *_, ms = B.vote_layer_timed(p, v, t["q"], t["k"], t["v"], ws, sel=sel, n_sel=n_sel, out=out)
+        for s in acc:
+            acc[s] += ms[s] / steps
+    flops = w.score_flops                               # 2*M*Hq*N_mid*D, all of it executed (no group-sum shortcut)
+    tf = flops / (acc["head_topk_scan"] * 1e-3) / 1e12
+    return {
+        "workload": w.name, "n_query": n_query, "vote_k": v.vote_k, "n_centres": v.n_centres, "span": v.span,
+        "n_selected": int(n_sel.item()), "ms_per_chunk": round(ms_chunk, 3), "steps": steps,
+        "tokens_per_s": round(n_query / (ms_chunk * 1e-3), 1),
+        "stages_ms": {s: round(x, 4) for s, x in acc.items()},
+        "roofline": {
+            "kernel": "vote_gemm_kernel (fused per-head running top-k) + list merge", "bound": "mfma",
+            "achieved": round(tf, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+            "frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 4), "algorithmic_flops": flops, "traffic": None,
         },
     }
 

@@ -367,7 +367,8 @@ namespace {
 struct VotePlan {
   Plan pl;                 // base plan with k_eff = cap (largest selection)
   int kk, kc, span;        // votes per list, centres, span (all clamped)
-  size_t off_part, off_lists, off_counts, off_seg, off_comp, off_sel, off_nsel, off_kp, off_vp, off_qp, total;
+  size_t off_rope, off_apart, off_part, off_lists, off_counts, off_seg, off_comp, off_sel, off_nsel, off_kp, off_vp,
+         off_qp, total;
 };
 
 int make_vote_plan(const reattn_params* p, const reattn_vote* v, VotePlan* out) {
@@ -390,7 +391,11 @@ int make_vote_plan(const reattn_params* p, const reattn_vote* v, VotePlan* out) 
   }
   if (pl.n_mid > 0 && !vote_scan_applies(pl)) return REATTN_ERR_SHAPE;
   const int per = pl.n_mid > 0 ? vote_queries_per_launch(pl, vp.kk > 0 ? vp.kk : 1) : 1;
-  size_t off = pl.total;
+  // own layout: of the group-sum path's scratch only the rotary table and (for the flash-decoding
+  // kernel) the split-S partials are needed here
+  size_t off = 0;
+  vp.off_rope = off;    off += up((size_t)(rope_rows_hi(pl.S) + kRopeLo) * (pl.D / 2) * sizeof(float2));
+  vp.off_apart = off;   off += up(attend_shared_applies(pl) ? 0 : (size_t)pl.M * pl.Hq * (size_t)pl.nsplit * (pl.D + 2) * 4);
   size_t part_bytes = 0;                               // the last launch may take fewer query rows
   if (pl.n_mid > 0) {
     part_bytes = vote_part_bytes(pl, per, vp.kk > 0 ? vp.kk : 1);
@@ -495,18 +500,16 @@ static int vote_layer_impl(const reattn_params* p, const reattn_vote* v, const v
   if (!rc) rc = vote_merge_impl(vp, lists, sel, n_sel, b, st);
   mark(ev, 2, st);
   if (rc) return rc;
-  Ws w;
-  rc = bind_ws(pl, ws, pl.total, &w);
-  if (rc) return rc;
-  rc = hip_rc(launch_prep(pl, 0, nullptr, w.rope, st));
+  float2* rope = (float2*)(b + vp.off_rope);
+  rc = hip_rc(launch_prep(pl, 0, nullptr, rope, st));
   if (rc) return rc;
   // one shared index row for every (query, KV head); its length is read on the device
   if (attend_shared_applies(pl))       // a chunk on bf16 / D = 128: packed once, flash attention on the matrix cores
-    rc = hip_rc(launch_attend_shared(pl, q, k_cache, v_cache, sel, n_sel, w.rope, b + vp.off_kp, b + vp.off_vp,
+    rc = hip_rc(launch_attend_shared(pl, q, k_cache, v_cache, sel, n_sel, rope, b + vp.off_kp, b + vp.off_vp,
                                      b + vp.off_qp, out, st));
   else
-    rc = hip_rc(launch_attend(pl, true, q, 0, pl.M, k_cache, v_cache, sel, w.rope, w.part, out, st,
-                              n_sel, 0));
+    rc = hip_rc(launch_attend(pl, true, q, 0, pl.M, k_cache, v_cache, sel, rope, (float*)(b + vp.off_apart), out,
+                              st, n_sel, 0));
   mark(ev, 3, st);
   return rc;
 }

@@ -132,7 +132,8 @@ def test_workspace_is_modest_for_decode():
 
 def test_vote_parameters_are_checked_on_the_host():
     p = good(top_k=0)
-    assert B.vote_workspace_bytes(p, B.Vote(4, 127, 32)) > B.workspace_bytes(good(top_k=127 * 32)) - 1
+    need = B.vote_workspace_bytes(p, B.Vote(4, 127, 32))
+    assert 0 < need < (4 << 20)            # a decode step: partial lists, rotary table, split-S partials
     for bad in (B.Vote(0, 127, 32), B.Vote(9, 127, 32), B.Vote(4, 0, 32), B.Vote(4, 1025, 32), B.Vote(4, 127, 0)):
         assert B.vote_workspace_bytes(p, bad) == 0
     # the paper's own setting fills an 8K window exactly: 32 + 4096 + 127 * 32 = 8192
