@@ -253,11 +253,13 @@ static void ro_rope(const double* x, int D, double pos, double theta, double* y)
 }
 
 /* Number of kept entries seen by a query whose own token is q_tok (causal cut
- * inside the local part), and the list itself.  list must hold s+k+l entries. */
+ * inside the local part, or inside the global part when the query is one of the
+ * first l_global tokens), and the list itself.  list must hold s+k+l entries. */
 static int64_t ro_concat(const ro_shape* sh, int64_t s, int64_t l, int64_t k,
                          const int32_t* idx_row, int64_t q_tok, int64_t* list) {
   int64_t n = 0;
-  for (int64_t j = 0; j < s; ++j) list[n++] = j;                       /* K_global */
+  for (int64_t j = 0; j < s && j <= q_tok; ++j) list[n++] = j;         /* K_global (up to itself for a query inside it:
+                                                                          the first prefill chunk holds l_global + l_local tokens) */
   for (int64_t r = 0; r < k; ++r) list[n++] = idx_row[r];              /* K_select, ascending */
   for (int64_t j = sh->n_ctx - l; j <= q_tok && j < sh->n_ctx; ++j)    /* K_local up to itself */
     list[n++] = j;

@@ -245,3 +245,34 @@ def vote_forward(sh: Shape, q, k_cache, v_cache, vote_k: int, n_centres: int, sp
     out = attend(sh2, q, k_cache, v_cache, idx, q_tok=q_tok)
     return {"head_topk": own.reshape(M, sh.n_q_heads, kk), "head_kth": kth.reshape(M, sh.n_q_heads),
             "votes": m["votes"], "centres": m["centres"], "sel": sel, "out": out, "head_scores": hs}
+
+
+# ---- streaming prefill of one layer (appendix, prefilling phase) -------------------------------
+def prefill_sequence(sh: Shape, q, k_new, v_new, chunk: int, vote=None):
+    """The chunk loop of the prefilling phase for ONE layer: the first chunk holds
+    n_sink + n_local tokens, every later one `chunk` tokens; a chunk's keys and values are
+    appended to the cache, then its query rows select from the middle and attend (Eq. 1-3).
+    sh.n_ctx = L is the sequence length.  q [L,Hq,D]; k_new, v_new [L,Hkv,D] token-major, as
+    the projections deliver them.  vote = (vote_k, n_centres, span) switches to the vote
+    selection.  Returns dict(out [L,Hq,D], chunks = [(start, end, per-chunk result dict)])."""
+    from dataclasses import replace as _replace
+    L = sh.n_ctx
+    assert q.shape[0] == L and k_new.shape[0] == L and v_new.shape[0] == L
+    k_cache = np.ascontiguousarray(np.transpose(k_new, (1, 0, 2)))      # [Hkv, L, D]: row t is token t
+    v_cache = np.ascontiguousarray(np.transpose(v_new, (1, 0, 2)))
+    out = np.empty((L, sh.n_q_heads, sh.head_dim), dtype=np.float64)
+    chunks = []
+    s, e = 0, min(L, sh.n_sink + sh.n_local)
+    while s < L:
+        she = _replace(sh, n_ctx=e)
+        kc = np.ascontiguousarray(k_cache[:, :e])                        # the cache as it stands after the append
+        vc = np.ascontiguousarray(v_cache[:, :e])
+        qc = np.ascontiguousarray(q[s:e])
+        if vote is None:
+            r = forward(she, qc, kc, vc, want_scores=True)
+        else:
+            r = vote_forward(she, qc, kc, vc, *vote)
+        out[s:e] = r["out"]
+        chunks.append((s, e, r))
+        s, e = e, min(L, e + chunk)
+    return {"out": out, "chunks": chunks}

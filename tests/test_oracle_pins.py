@@ -474,3 +474,50 @@ def test_vote_selection_retrieves_needle_spans():
         assert all(p in sel for p in range(max(lo, w.n_sink), min(lo + 8, w.n_ctx - w.n_local))), pos
     assert r["votes"].sum() == w.n_q_heads * 4
     assert all(np.diff(r["sel"]) > 0) and r["sel"].min() >= w.n_sink and r["sel"].max() < w.n_ctx - w.n_local
+
+
+# ------------------------------------------- the chunk loop of the prefilling phase
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("mode", ["topk", "vote"])
+def test_prefill_sequence_with_full_cover_is_causal_attention(dtype, mode):
+    """When every chunk selects its whole middle, chunking is invisible: each token's output is
+    plain causal attention over all tokens before it, RoPE at the true positions (the first chunk
+    of n_sink + n_local tokens included: a query inside the global part sees only what precedes it)."""
+    Hq, Hkv, D, L, s, l, chunk = 4, 2, 8, 75, 3, 12, 7
+    q, k, v = rng_inputs(21, L, Hq, Hkv, D, L, dtype)
+    k_new = torch.randn(L, Hkv, D, generator=torch.Generator().manual_seed(77))
+    v_new = torch.randn(L, Hkv, D, generator=torch.Generator().manual_seed(78))
+    if dtype == "bf16":
+        k_new, v_new = k_new.bfloat16(), v_new.bfloat16()
+    sh = ro.Shape(Hq, Hkv, D, dtype, L, s, l, top_k=10_000, rope_theta=10000.0)
+    vote = (2, 5, 1000) if mode == "vote" else None       # one span of 1000 entries covers any middle here
+    res = ro.prefill_sequence(sh, store(q), store(k_new), store(v_new), chunk, vote=vote)
+    bounds = [(a, b) for a, b, _ in res["chunks"]]
+    assert bounds[0] == (0, s + l) and bounds[1] == (s + l, s + l + chunk) and bounds[-1][1] == L
+    assert all(b - a <= chunk for a, b in bounds[1:])
+    kc = np.transpose(f64(k_new), (1, 0, 2)); vc = np.transpose(f64(v_new), (1, 0, 2))
+    want = brute_full_attention(f64(q), kc, vc, np.arange(L), 10000.0)
+    assert np.abs(res["out"] - want).max() < 1e-12
+
+
+def test_prefill_sequence_chunks_select_from_the_growing_middle():
+    """A later chunk's selection is the per-row top-k over [n_sink, e - n_local) of the cache as it
+    stands at that chunk; nothing of a later chunk leaks into an earlier one."""
+    Hq, Hkv, D, L, s, l, chunk, k = 4, 2, 8, 90, 2, 10, 10, 6
+    q, _, _ = rng_inputs(31, L, Hq, Hkv, D, L)
+    k_new = torch.randn(L, Hkv, D, generator=torch.Generator().manual_seed(5))
+    v_new = torch.randn(L, Hkv, D, generator=torch.Generator().manual_seed(6))
+    sh = ro.Shape(Hq, Hkv, D, "f32", L, s, l, top_k=k, rope_theta=10000.0)
+    res = ro.prefill_sequence(sh, store(q), store(k_new), store(v_new), chunk)
+    res_short = ro.prefill_sequence(ro.Shape(Hq, Hkv, D, "f32", 52, s, l, k, 10000.0), store(q[:52]), store(k_new[:52]),
+                                    store(v_new[:52]), chunk)
+    assert np.array_equal(res["out"][:52], res_short["out"])          # causality of the loop
+    kc = np.transpose(f64(k_new), (1, 0, 2))
+    for a, b, r in res["chunks"][1:]:
+        n_mid = b - s - l
+        for i in range(b - a):
+            for h in range(Hkv):
+                qbar = f64(q)[a + i, h * 2:(h + 1) * 2].sum(0)
+                sc = kc[h, s:s + n_mid] @ qbar
+                top = np.sort(np.argsort(-sc, kind="stable")[:min(k, n_mid)]) + s
+                assert np.array_equal(r["idx"][i, h], top)
