@@ -29,7 +29,9 @@
  *     out      [M][Hq][D]        fp32
  * Query i is cache token N - M + i; for M > 1 it sees the local part only up to
  * its own token (causal), and M <= l is required (a chunk lies inside the local
- * window: paper, hyper-parameter discussion of the chunk size).
+ * window: paper, hyper-parameter discussion of the chunk size) unless the middle is
+ * empty: then the kept entries are all N tokens in order and any M <= N is plain
+ * causal attention (the first prefill chunk of l_global + l_local tokens).
  */
 #ifndef REATTN_H_
 #define REATTN_H_
@@ -178,6 +180,36 @@ int reattn_vote_merge(const reattn_params* p, const reattn_vote* v, const int32_
 int reattn_vote_layer(const reattn_params* p, const reattn_vote* v, const void* q,
                       const void* k_cache, const void* v_cache, int32_t* sel_out,
                       int32_t* n_sel_out, float* out, void* ws, size_t ws_bytes, void* stream);
+
+/* ---- Streaming prefill of one layer ------------------------------------------------------
+ * The chunk loop of the appendix's prefilling phase for ONE layer: chunk 0 holds the first
+ * min(L, l_global + l_local) tokens, every later chunk `chunk` tokens (the last one what is
+ * left); each chunk's keys and values are appended to the cache, then its query rows select
+ * from the middle as it stands and attend (Eq. 1-3).  In these calls p->n_ctx = L is the
+ * whole sequence, p->n_query is ignored, and the strides describe the cache
+ * ([Hkv][>= L][D]; 0,0 = contiguous [Hkv][L][D]).  1 <= chunk <= n_local (a chunk lies inside
+ * the local window: paper, hyper-parameter discussion of the chunk size). */
+
+/* cache[h][first_tok + t][:] = new[t][h][:] for t < n_tok: k_new, v_new are token-major
+ * [n_tok][Hkv][D] device buffers (as the projections deliver them); first_tok + n_tok <= n_ctx. */
+int reattn_cache_append(const reattn_params* p, int64_t first_tok, int32_t n_tok, const void* k_new,
+                        const void* v_new, void* k_cache, void* v_cache, void* stream);
+
+/* Number of chunks of the loop (0 if p or chunk is invalid) and the scratch bytes the whole loop
+ * accepts (the largest any chunk needs; v == NULL: per-query top-k, else the vote selection). */
+int64_t reattn_prefill_sequence_chunks(const reattn_params* p, int32_t chunk);
+size_t reattn_prefill_sequence_workspace_bytes(const reattn_params* p, const reattn_vote* v, int32_t chunk);
+
+/* The loop.  q [L][Hq][D], k_new, v_new [L][Hkv][D], out [L][Hq][D] fp32; k_cache, v_cache are WRITTEN
+ * (rows [0, L)).  v == NULL selects per query row and KV head as reattn_prefill_chunk does; then idx_out
+ * (nullable) receives the chunks' index sets back to back, chunk c as [M_c][Hkv][k_eff_c].  v != NULL
+ * uses the vote selection; then sel_out (nullable, [n_chunks][cap_L], cap_L = min(n_centres * span,
+ * middle of the whole sequence)) and n_sel_out (nullable, [n_chunks] device int32) receive every
+ * chunk's shared selection.  Everything is enqueued on `stream`; nothing synchronises. */
+int reattn_prefill_sequence(const reattn_params* p, const reattn_vote* v, int32_t chunk, const void* q,
+                            const void* k_new, const void* v_new, void* k_cache, void* v_cache,
+                            float* out, int32_t* idx_out, int32_t* sel_out, int32_t* n_sel_out,
+                            void* ws, size_t ws_bytes, void* stream);
 
 /* Measurement aid: reattn_decode_step with HIP events recorded on `stream` at the
  * stage boundaries; it WAITS for the step to finish and fills the HOST array

@@ -29,7 +29,8 @@ EXPORTS = [
     "reattn_attend", "reattn_decode_step", "reattn_prefill_chunk", "reattn_decode_step_timed",
     "reattn_probe_read_bandwidth", "reattn_prefill_chunk_timed",
     "reattn_vote_workspace_bytes", "reattn_vote_topk", "reattn_vote_merge", "reattn_vote_layer",
-    "reattn_vote_layer_timed",
+    "reattn_vote_layer_timed", "reattn_cache_append", "reattn_prefill_sequence_chunks",
+    "reattn_prefill_sequence_workspace_bytes", "reattn_prefill_sequence",
 ]
 PREFILL_STAGES = ("sample_threshold", "score_gemm_filter", "candidate_topk", "attend")
 STAGES = ("prep", "scan", "topk", "attend")
@@ -95,6 +96,12 @@ def lib() -> C.CDLL:
         L.reattn_vote_merge.argtypes = [PP, PV, P, P, P, P, C.c_size_t, P]
         L.reattn_vote_layer.argtypes = [PP, PV, P, P, P, P, P, P, P, C.c_size_t, P]
         L.reattn_vote_layer_timed.argtypes = L.reattn_vote_layer.argtypes + [C.POINTER(C.c_float)]
+        L.reattn_cache_append.argtypes = [PP, C.c_int64, C.c_int32, P, P, P, P, P]
+        L.reattn_prefill_sequence_chunks.argtypes = [PP, C.c_int32]
+        L.reattn_prefill_sequence_chunks.restype = C.c_int64
+        L.reattn_prefill_sequence_workspace_bytes.argtypes = [PP, PV, C.c_int32]
+        L.reattn_prefill_sequence_workspace_bytes.restype = C.c_size_t
+        L.reattn_prefill_sequence.argtypes = [PP, PV, C.c_int32, P, P, P, P, P, P, P, P, P, P, C.c_size_t, P]
         _lib = L
     return _lib
 
@@ -388,3 +395,69 @@ def vote_layer_timed(p: Params, v: Vote, q, k_cache, v_cache, ws, sel=None, n_se
                                          _dev(out, "out", torch.float32), _dev(ws, "ws"), ws.numel(),
                                          _stream(), ms), "reattn_vote_layer_timed")
     return out, sel, n_sel, dict(zip(VOTE_STAGES, [float(x) for x in ms]))
+
+
+# ---- streaming prefill of one layer (chunk loop with cache append) ---------------------------
+def cache_append(p: Params, first_tok: int, k_new, v_new, k_cache, v_cache):
+    """cache[h][first_tok + t] = new[t][h]; k_new, v_new token-major [n_tok, Hkv, D]."""
+    cp = p.c()
+    _check(lib().reattn_cache_append(C.byref(cp), first_tok, k_new.shape[0], _dev(k_new, "k_new", p.torch_dtype()),
+                                     _dev(v_new, "v_new", p.torch_dtype()), _dev(k_cache, "k_cache", p.torch_dtype()),
+                                     _dev(v_cache, "v_cache", p.torch_dtype()), _stream()), "reattn_cache_append")
+
+
+def sequence_chunks(p: Params, chunk: int):
+    """[(start, end)] of the chunk loop: first min(L, n_sink + n_local) tokens, then `chunk` at a time."""
+    L = p.n_ctx
+    out, s, e = [], 0, min(L, p.n_sink + p.n_local)
+    while s < L:
+        out.append((s, e))
+        s, e = e, min(L, e + chunk)
+    assert len(out) == lib().reattn_prefill_sequence_chunks(C.byref(p.c()), chunk)
+    return out
+
+
+def prefill_sequence(p: Params, chunk: int, q, k_new, v_new, k_cache=None, v_cache=None, vote: Vote | None = None,
+                     ws=None, want_sets: bool = True):
+    """Chunk loop of one layer.  Returns dict(out [L,Hq,D], k_cache, v_cache, and per mode
+    idx = [per chunk [M,Hkv,k_eff]] or sel = [per chunk 1-D tensor])."""
+    L, dev = p.n_ctx, q.device
+    cp = p.c()
+    cv = vote.c() if vote is not None else None
+    pv = C.byref(cv) if cv is not None else None
+    if k_cache is None:
+        k_cache = torch.empty(p.n_kv_heads, L, p.head_dim, dtype=p.torch_dtype(), device=dev)
+        v_cache = torch.empty_like(k_cache)
+    need = lib().reattn_prefill_sequence_workspace_bytes(C.byref(cp), pv, chunk)
+    if ws is None:
+        if need == 0:
+            raise ReattnError(validate(p) or ERR_RANGE, "reattn_prefill_sequence_workspace_bytes")
+        ws = torch.empty(need, dtype=torch.uint8, device=dev)
+    out = torch.empty(L, p.n_q_heads, p.head_dim, dtype=torch.float32, device=dev)
+    chunks = sequence_chunks(p, chunk)
+    idx_flat = sel_all = n_sel_all = None
+    shapes = []
+    if want_sets and vote is None:
+        for s, e in chunks:
+            n_mid = max(0, e - min(p.n_sink, e) - min(p.n_local, e - min(p.n_sink, e)))
+            shapes.append((e - s, p.n_kv_heads, min(p.top_k, n_mid)))
+        idx_flat = torch.empty(max(1, sum(a * b * c for a, b, c in shapes)), dtype=torch.int32, device=dev)
+    if want_sets and vote is not None:
+        cap = max(1, vote_cap(Params(**{**p.__dict__, "n_query": 1, "max_position": 0}), vote))
+        sel_all = torch.empty(len(chunks), cap, dtype=torch.int32, device=dev)
+        n_sel_all = torch.zeros(len(chunks), dtype=torch.int32, device=dev)
+    _check(lib().reattn_prefill_sequence(
+        C.byref(cp), pv, chunk, _dev(q, "q", p.torch_dtype()), _dev(k_new, "k_new", p.torch_dtype()),
+        _dev(v_new, "v_new", p.torch_dtype()), _dev(k_cache, "k_cache", p.torch_dtype()),
+        _dev(v_cache, "v_cache", p.torch_dtype()), _dev(out, "out", torch.float32),
+        _dev(idx_flat, "idx_out", torch.int32), _dev(sel_all, "sel_out", torch.int32),
+        _dev(n_sel_all, "n_sel_out", torch.int32), _dev(ws, "ws"), ws.numel(), _stream()), "reattn_prefill_sequence")
+    res = {"out": out, "k_cache": k_cache, "v_cache": v_cache, "chunks": chunks}
+    if idx_flat is not None:
+        res["idx"], at = [], 0
+        for a, b, c in shapes:
+            res["idx"].append(idx_flat[at:at + a * b * c].view(a, b, c))
+            at += a * b * c
+    if sel_all is not None:
+        res["sel"], res["n_sel"] = sel_all, n_sel_all
+    return res

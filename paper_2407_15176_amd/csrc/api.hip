@@ -37,7 +37,9 @@ int make_plan(const reattn_params* p, Plan* out) {
   pl.n_mid = pl.N - pl.s_eff - pl.l_eff;
   pl.k_eff = (int)(p->top_k < pl.n_mid ? p->top_k : pl.n_mid);
   const int64_t S = pl.s_eff + pl.k_eff + pl.l_eff;
-  if (pl.M > pl.l_eff) return REATTN_ERR_RANGE;          // a chunk lies inside the local window
+  // a chunk lies inside the local window; with an empty middle the kept entries are simply all
+  // N tokens in order, so any M <= N is causal attention (the first prefill chunk of l_global + l_local)
+  if (pl.M > pl.l_eff && pl.n_mid > 0) return REATTN_ERR_RANGE;
   if (p->max_position > 0 && S > p->max_position) return REATTN_ERR_WINDOW;
   pl.S = (int)S;
 
@@ -143,7 +145,7 @@ inline int hip_rc(hipError_t e) { return e == hipSuccess ? REATTN_OK : REATTN_ER
 // and KV head), everything else the flash-decoding kernel with its split-S combine.
 int attend_cache(const Plan& pl, const Ws& w, char* ws, const void* q, const void* k_cache,
                  const void* v_cache, const int32_t* idx, float* out, hipStream_t st) {
-  if (attend_prefill_applies(pl))
+  if (attend_prefill_applies(pl) && pl.M <= pl.l_eff)     // its shared local operands need the chunk inside the window
     return hip_rc(launch_attend_prefill(pl, q, k_cache, v_cache, idx, (float2*)(ws + pl.off_rope16),
                                         out, st));
   return hip_rc(launch_attend(pl, true, q, 0, pl.M, k_cache, v_cache, idx, w.rope, w.part, out, st));
@@ -539,6 +541,155 @@ extern "C" int reattn_vote_layer_timed(const reattn_params* p, const reattn_vote
   }
   for (int i = 0; i < made; ++i) (void)hipEventDestroy(ev[i]);
   return rc;
+}
+
+// ---- streaming prefill of one layer ---------------------------------------------------------
+namespace {
+// Explicit strides of the cache described by p (whose n_ctx is the final length L).
+void cache_strides(const reattn_params* p, int64_t* ksh, int64_t* kst, int64_t* vsh, int64_t* vst) {
+  const bool kdef = p->k_stride_head == 0 && p->k_stride_tok == 0;
+  const bool vdef = p->v_stride_head == 0 && p->v_stride_tok == 0;
+  *kst = kdef ? p->head_dim : p->k_stride_tok;  *ksh = kdef ? p->n_ctx * p->head_dim : p->k_stride_head;
+  *vst = vdef ? p->head_dim : p->v_stride_tok;  *vsh = vdef ? p->n_ctx * p->head_dim : p->v_stride_head;
+}
+
+// Chunk c of the prefilling phase: tokens [*s, *e).  Returns false past the last chunk.
+bool sequence_chunk(const reattn_params* p, int32_t chunk, int64_t c, int64_t* s, int64_t* e) {
+  const int64_t L = p->n_ctx;
+  int64_t first = (int64_t)p->n_sink + p->n_local;
+  if (first > L) first = L;
+  if (c == 0) { *s = 0; *e = first; return true; }
+  *s = first + (c - 1) * (int64_t)chunk;
+  if (*s >= L) return false;
+  *e = *s + chunk < L ? *s + chunk : L;
+  return true;
+}
+
+// p as seen by the chunk [s, e): the cache holds e tokens, the chunk's rows are the queries.
+reattn_params chunk_params(const reattn_params* p, int64_t s, int64_t e) {
+  reattn_params pp = *p;
+  cache_strides(p, &pp.k_stride_head, &pp.k_stride_tok, &pp.v_stride_head, &pp.v_stride_tok);
+  pp.n_ctx = e;
+  pp.n_query = (int32_t)(e - s);
+  return pp;
+}
+
+int sequence_check(const reattn_params* p, int32_t chunk) {
+  if (!p) return REATTN_ERR_NULL;
+  if (chunk < 1 || chunk > 65535) return REATTN_ERR_RANGE;
+  if ((int64_t)p->n_sink + p->n_local > 65535) return REATTN_ERR_RANGE;   // the first chunk is one launch
+  return REATTN_OK;
+}
+}  // namespace
+
+extern "C" int64_t reattn_prefill_sequence_chunks(const reattn_params* p, int32_t chunk) {
+  if (sequence_check(p, chunk) || p->n_ctx < 1) return 0;
+  int64_t c = 0, s, e;
+  while (sequence_chunk(p, chunk, c, &s, &e)) ++c;
+  return c;
+}
+
+extern "C" size_t reattn_prefill_sequence_workspace_bytes(const reattn_params* p, const reattn_vote* v,
+                                                          int32_t chunk) {
+  if (sequence_check(p, chunk)) return 0;
+  size_t need = 0;
+  int64_t s, e;
+  for (int64_t c = 0; sequence_chunk(p, chunk, c, &s, &e); ++c) {
+    const reattn_params pp = chunk_params(p, s, e);
+    size_t t;
+    if (v) {
+      VotePlan vp;
+      if (make_vote_plan(&pp, v, &vp)) return 0;
+      t = vp.total;
+    } else {
+      Plan pl;
+      if (make_plan(&pp, &pl)) return 0;
+      t = pl.total;
+    }
+    if (t > need) need = t;
+  }
+  return need;
+}
+
+extern "C" int reattn_cache_append(const reattn_params* p, int64_t first_tok, int32_t n_tok, const void* k_new,
+                                   const void* v_new, void* k_cache, void* v_cache, void* stream) {
+  if (!p) return REATTN_ERR_NULL;
+  reattn_params pp = *p;
+  pp.n_query = 1;                                      // not used here
+  Plan pl;
+  const int rc = make_plan(&pp, &pl);
+  if (rc) return rc;
+  if (first_tok < 0 || n_tok < 0 || first_tok + n_tok > pl.N) return REATTN_ERR_RANGE;
+  if (n_tok == 0) return REATTN_OK;
+  if (!k_new || !v_new || !k_cache || !v_cache) return REATTN_ERR_NULL;
+  if (!aligned16(k_new) || !aligned16(v_new) || !aligned16(k_cache) || !aligned16(v_cache)) return REATTN_ERR_ALIGN;
+  return hip_rc(launch_cache_append(pl, first_tok, n_tok, k_new, v_new, k_cache, v_cache, (hipStream_t)stream));
+}
+
+extern "C" int reattn_prefill_sequence(const reattn_params* p, const reattn_vote* v, int32_t chunk, const void* q,
+                                       const void* k_new, const void* v_new, void* k_cache, void* v_cache,
+                                       float* out, int32_t* idx_out, int32_t* sel_out, int32_t* n_sel_out,
+                                       void* ws, size_t ws_bytes, void* stream) {
+  int rc = sequence_check(p, chunk);
+  if (rc) return rc;
+  {                                                    // the sequence as a whole: shapes, strides, L
+    reattn_params p1 = *p;
+    p1.n_query = 1;
+    Plan pl;
+    rc = make_plan(&p1, &pl);
+    if (rc && rc != REATTN_ERR_WINDOW) return rc;      // the window is checked chunk by chunk
+  }
+  if (!q || !k_new || !v_new || !k_cache || !v_cache || !out) return REATTN_ERR_NULL;
+  if (!aligned16(q) || !aligned16(k_new) || !aligned16(v_new) || !aligned16(k_cache) || !aligned16(v_cache) ||
+      !aligned16(out))
+    return REATTN_ERR_ALIGN;
+  const size_t need = reattn_prefill_sequence_workspace_bytes(p, v, chunk);
+  if (need == 0) {                                     // some chunk is invalid: report which rule it breaks
+    int64_t s, e;
+    for (int64_t c = 0; sequence_chunk(p, chunk, c, &s, &e); ++c) {
+      const reattn_params pp = chunk_params(p, s, e);
+      VotePlan vp; Plan pl;
+      const int r = v ? make_vote_plan(&pp, v, &vp) : make_plan(&pp, &pl);
+      if (r) return r;
+    }
+    return REATTN_ERR_RANGE;
+  }
+  if (!ws || ws_bytes < need) return REATTN_ERR_WORKSPACE;
+  if ((uintptr_t)ws % kAlign) return REATTN_ERR_ALIGN;
+  const size_t eb = p->dtype == REATTN_BF16 ? 2 : 4;
+  const size_t qrow = (size_t)p->n_q_heads * p->head_dim, krow = (size_t)p->n_kv_heads * p->head_dim;
+  // the largest selection of any chunk is the last one's: it strides sel_out
+  int64_t sel_stride = 0;
+  if (v) {
+    reattn_params pl_last = *p;
+    pl_last.n_query = 1; pl_last.max_position = 0;     // only the clamped cap is wanted here
+    VotePlan vp;
+    if (make_vote_plan(&pl_last, v, &vp)) return REATTN_ERR_RANGE;
+    sel_stride = vp.pl.k_eff > 0 ? vp.pl.k_eff : 1;
+  }
+  int64_t s, e, idx_at = 0;
+  for (int64_t c = 0; sequence_chunk(p, chunk, c, &s, &e); ++c) {
+    const reattn_params pp = chunk_params(p, s, e);
+    Plan pl;
+    rc = make_plan(&pp, &pl);
+    if (rc) return rc;
+    rc = hip_rc(launch_cache_append(pl, s, (int)(e - s), (const char*)k_new + (size_t)s * krow * eb,
+                                    (const char*)v_new + (size_t)s * krow * eb, k_cache, v_cache,
+                                    (hipStream_t)stream));
+    if (rc) return rc;
+    const char* qc = (const char*)q + (size_t)s * qrow * eb;
+    float* oc = out + (size_t)s * qrow;
+    if (v) {
+      rc = vote_layer_impl(&pp, v, qc, k_cache, v_cache, sel_out ? sel_out + c * sel_stride : nullptr,
+                           n_sel_out ? n_sel_out + c : nullptr, oc, ws, ws_bytes, stream, nullptr);
+    } else {
+      rc = run_layer(&pp, false, qc, k_cache, v_cache, idx_out ? idx_out + idx_at : nullptr, oc, ws, ws_bytes,
+                     stream);
+      idx_at += (int64_t)pl.M * pl.Hkv * pl.k_eff;
+    }
+    if (rc) return rc;
+  }
+  return REATTN_OK;
 }
 
 static int layer_timed(const reattn_params* p, bool decode_only, const void* q, const void* k_cache,

@@ -40,6 +40,8 @@ struct Plan {
 // ---- host-side launchers (one per .hip file) -------------------------------
 hipError_t launch_fill_u32(uint32_t* p, int64_t n, uint32_t v, hipStream_t st);
 hipError_t launch_prep(const Plan& pl, int rows, uint32_t* hist, float2* rope, hipStream_t st);
+hipError_t launch_cache_append(const Plan& pl, int64_t first_tok, int n_tok, const void* k_new, const void* v_new,
+                               void* k_cache, void* v_cache, hipStream_t st);
 hipError_t launch_score_scan(const Plan& pl, const void* q, int n_query, const void* k_cache,
                              float* scores, uint32_t* hist, hipStream_t st);
 void prefill_sampling(const Plan& pl, int64_t* stride, int64_t* n_s, uint32_t* rho, uint32_t* cap);

@@ -97,7 +97,35 @@ __global__ __launch_bounds__(256) void gather_rope_kernel(GatherArgs a) {
   }
 }
 
+// Appends the rows of n_tok new tokens, delivered token-major [n_tok][Hkv][D] (as the projections
+// produce them), to the head-major cache: cache[h][first_tok + t][:] = new[t][h][:].  16 bytes per thread.
+__global__ __launch_bounds__(256) void cache_append_kernel(const u32x4* __restrict__ k_new, const u32x4* __restrict__ v_new,
+                                                           char* k_cache, char* v_cache, int64_t first_tok,
+                                                           int64_t n_vec, int Hkv, int vec_per_row,
+                                                           int64_t ksh_b, int64_t kst_b, int64_t vsh_b, int64_t vst_b) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n_vec) return;
+  const int piece = (int)(i % vec_per_row);
+  const int64_t row = i / vec_per_row;                 // t * Hkv + h
+  const int h = (int)(row % Hkv);
+  const int64_t t = row / Hkv;
+  *(u32x4*)(k_cache + h * ksh_b + (first_tok + t) * kst_b + piece * 16) = k_new[i];
+  *(u32x4*)(v_cache + h * vsh_b + (first_tok + t) * vst_b + piece * 16) = v_new[i];
+}
+
 }  // namespace
+
+hipError_t launch_cache_append(const Plan& pl, int64_t first_tok, int n_tok, const void* k_new, const void* v_new,
+                               void* k_cache, void* v_cache, hipStream_t st) {
+  if (n_tok <= 0) return hipSuccess;
+  const int64_t eb = pl.dtype == 1 ? 2 : 4;
+  const int vec_per_row = (int)(pl.D * eb / 16);
+  const int64_t n_vec = (int64_t)n_tok * pl.Hkv * vec_per_row;
+  hipLaunchKernelGGL(cache_append_kernel, dim3((unsigned)((n_vec + 255) / 256)), dim3(256), 0, st,
+                     (const u32x4*)k_new, (const u32x4*)v_new, (char*)k_cache, (char*)v_cache, first_tok, n_vec,
+                     pl.Hkv, vec_per_row, pl.ksh * eb, pl.kst * eb, pl.vsh * eb, pl.vst * eb);
+  return hipGetLastError();
+}
 
 hipError_t launch_prep(const Plan& pl, int rows, uint32_t* hist, float2* rope, hipStream_t st) {
   if (!hist) rows = 0;

