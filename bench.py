@@ -41,7 +41,11 @@ def main() -> int:
                     help="run the vote-selection leg alone and print its object (for profiling runs)")
     ap.add_argument("--only-vote-prefill", action="store_true",
                     help="run the vote-selection prefill chunk alone (config 4's cache) and print its object")
-    ap.add_argument("--chunk", type=int, default=4096, help="query rows of --only-vote-prefill")
+    ap.add_argument("--chunk", type=int, default=4096, help="query rows of --only-vote-prefill / --only-sequence")
+    ap.add_argument("--only-sequence", action="store_true",
+                    help="run the streaming prefill of one layer over --seq-len tokens alone (chunk 512 by default)")
+    ap.add_argument("--seq-len", type=int, default=65536)
+    ap.add_argument("--no-sequence", action="store_true", help="skip the streaming-prefill leg")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy 3 times (a known-size kernel against "
                          "which rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings are scaled)")
@@ -61,6 +65,10 @@ def main() -> int:
     torch.cuda.set_device(0)
     if args.only_prefill:
         print(json.dumps({"prefill": prefill_leg(min(args.steps, 5))}), flush=True)
+        return 0
+    if args.only_sequence:
+        print(json.dumps({"prefill_sequence": sequence_leg(args.seq_len, args.chunk if args.chunk != 4096 else 512)}),
+              flush=True)
         return 0
     if args.only_vote_prefill:
         print(json.dumps({"vote_prefill": vote_prefill_leg(min(args.steps, 5), args.chunk)}), flush=True)
@@ -158,6 +166,9 @@ def main() -> int:
         if not args.no_vote:
             torch.cuda.empty_cache()
             result["vote_prefill"] = vote_prefill_leg(min(args.steps, 5))
+        if not args.no_sequence:
+            torch.cuda.empty_cache()
+            result["prefill_sequence"] = sequence_leg(args.seq_len, 512)
         t = None
     if not args.no_cpu_baseline:
         if t is None:
@@ -255,6 +266,44 @@ def vote_prefill_leg(steps: int, n_query: int = 4096) -> dict:
             "frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 4), "algorithmic_flops": flops, "traffic": None,
         },
     }
+
+
+def sequence_leg(seq_len: int, chunk: int, steps: int = 2) -> dict:
+    """Streaming prefill of ONE layer over a whole sequence (appendix, prefilling phase): first chunk of
+    n_sink + n_local tokens, then `chunk` tokens per step, each appended to the cache before it selects
+    and attends.  Llama-3.1-8B layer shape, config 2's channel scales; both selections are timed."""
+    import torch
+    from dataclasses import replace
+    from paper_2407_15176_amd import binding as B
+    from paper_2407_15176_amd import workloads as wl
+    w = wl.CONFIGS[2].scaled(n_ctx=seq_len, n_needles=0, top_k=4096)
+    g = torch.Generator(device="cuda").manual_seed(240715000 + 91)
+    sig = wl.channel_sigma(w).to("cuda")
+    q = torch.randn(seq_len, w.n_q_heads, w.head_dim, generator=g, device="cuda").bfloat16()
+    k_new = (torch.randn(seq_len, w.n_kv_heads, w.head_dim, generator=g, device="cuda") * sig[None]).bfloat16()
+    v_new = (torch.randn(seq_len, w.n_kv_heads, w.head_dim, generator=g, device="cuda") * sig[None]).bfloat16()
+    kc = torch.empty(w.n_kv_heads, seq_len, w.head_dim, dtype=torch.bfloat16, device="cuda")
+    vc = torch.empty_like(kc)
+    res = {"workload": f"llama3.1-8b layer, {seq_len} tokens, chunk {chunk}, sink {w.n_sink}, local {w.n_local}",
+           "seq_len": seq_len, "chunk": chunk}
+    for name, vote, top_k in (("vote_4_127_32", B.Vote(4, 127, 32), 0), ("topk_4096_per_query", None, 4096)):
+        p = B.Params.from_workload(replace(w, n_query=1, top_k=top_k, max_position=0))
+        cp = p.c()
+        need = B.lib().reattn_prefill_sequence_workspace_bytes(
+            __import__("ctypes").byref(cp), __import__("ctypes").byref(vote.c()) if vote else None, chunk)
+        ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+        B.prefill_sequence(p, chunk, q, k_new, v_new, kc, vc, vote=vote, ws=ws, want_sets=False)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            B.prefill_sequence(p, chunk, q, k_new, v_new, kc, vc, vote=vote, ws=ws, want_sets=False)
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / steps
+        res[name] = {"ms_per_layer": round(ms, 2), "tokens_per_s_per_layer": round(seq_len / (ms * 1e-3), 1),
+                     "n_chunks": len(B.sequence_chunks(p, chunk)), "workspace_MiB": round(need / 2**20, 1)}
+        del ws
+        torch.cuda.empty_cache()
+    return res
 
 
 def vote_leg(t: dict, cfg: int, steps: int, warmup: int) -> dict:
