@@ -49,14 +49,14 @@
 #include <stdlib.h>
 #include <string.h>
 
-enum { RO_F32 = 0, RO_BF16 = 1 };
+enum { RO_F32 = 0, RO_BF16 = 1, RO_F16 = 2 };
 enum { RO_AGG_SUM = 0, RO_AGG_MAX = 1 };
 
 typedef struct {
   int32_t n_q_heads;     /* Hq */
   int32_t n_kv_heads;    /* Hkv, divides Hq */
   int32_t head_dim;      /* D, even */
-  int32_t dtype;         /* RO_F32 / RO_BF16: storage of q, K, V */
+  int32_t dtype;         /* RO_F32 / RO_BF16 / RO_F16: storage of q, K, V */
   int64_t n_ctx;         /* N cached tokens (current tokens already appended) */
   int32_t n_sink;        /* l_global */
   int32_t n_local;       /* l_local */
@@ -69,8 +69,19 @@ typedef struct {
 } ro_shape;
 
 /* ---- exact widening of one stored element ------------------------------- */
+/* IEEE binary16 (1 sign, 5 exponent, 10 fraction bits) from its definition. */
+static double ro_half(uint16_t h) {
+  const int sign = h >> 15, e = (h >> 10) & 31, f = h & 1023;
+  double v;
+  if (e == 0) v = ldexp((double)f, -24);                       /* subnormal: f * 2^-10 * 2^-14 */
+  else if (e == 31) v = f ? NAN : INFINITY;
+  else v = ldexp(1.0 + (double)f / 1024.0, e - 15);
+  return sign ? -v : v;
+}
+
 static double ro_load(const void* base, int64_t i, int dtype) {
   if (dtype == RO_F32) return (double)((const float*)base)[i];
+  if (dtype == RO_F16) return ro_half(((const uint16_t*)base)[i]);
   uint32_t bits = ((uint32_t)((const uint16_t*)base)[i]) << 16; /* bf16 = top half of fp32 */
   float f;
   memcpy(&f, &bits, sizeof f);
@@ -78,6 +89,7 @@ static double ro_load(const void* base, int64_t i, int dtype) {
 }
 
 double ro_widen_bf16(uint16_t h) { return ro_load(&h, 0, RO_BF16); }
+double ro_widen_f16(uint16_t h) { return ro_load(&h, 0, RO_F16); }
 
 /* ---- Eq. 1: partition ---------------------------------------------------- */
 /* sink = [0, s), middle = [s, N - l), local = [N - l, N).  When the cache is

@@ -5,7 +5,7 @@ benchmark's CPU-baseline leg.  The product package never imports this module and
 this module never imports the product package.
 
 Arrays are numpy; q / K / V are passed as their exact stored bytes: float32
-arrays, or bfloat16 as uint16 bit patterns (dtype="bf16").
+arrays, or bfloat16 / IEEE half as uint16 bit patterns (dtype="bf16" / "f16").
 """
 from __future__ import annotations
 
@@ -20,7 +20,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "reattn_oracle.c")
 _LIB = os.path.join(_HERE, "libreattn_oracle.so")
 
-F32, BF16 = 0, 1
+F32, BF16, F16 = 0, 1, 2
+_DTYPE_CODE = {"f32": F32, "bf16": BF16, "f16": F16}
 AGG_SUM, AGG_MAX = 0, 1
 
 
@@ -50,7 +51,7 @@ class Shape:
     n_q_heads: int
     n_kv_heads: int
     head_dim: int
-    dtype: str            # "f32" | "bf16"
+    dtype: str            # "f32" | "bf16" | "f16"
     n_ctx: int
     n_sink: int
     n_local: int
@@ -61,7 +62,7 @@ class Shape:
 
     def c(self) -> _Shape:
         D, N = self.head_dim, self.n_ctx
-        return _Shape(self.n_q_heads, self.n_kv_heads, D, BF16 if self.dtype == "bf16" else F32,
+        return _Shape(self.n_q_heads, self.n_kv_heads, D, _DTYPE_CODE[self.dtype],
                       N, self.n_sink, self.n_local, self.top_k, self.agg,
                       float(self.rope_theta), float(self.softmax_scale),
                       N * D, D, N * D, D)
@@ -87,6 +88,8 @@ def _lib():
         lib.ro_partition.restype = None
         lib.ro_widen_bf16.argtypes = [C.c_uint16]
         lib.ro_widen_bf16.restype = C.c_double
+        lib.ro_widen_f16.argtypes = [C.c_uint16]
+        lib.ro_widen_f16.restype = C.c_double
         lib.ro_score.argtypes = [P, C.c_int32, P, P, P]
         lib.ro_topk_row.argtypes = [P, C.c_int64, C.c_int64, C.c_int64, P, P]
         lib.ro_topk.argtypes = [P, C.c_int64, C.c_int64, C.c_int64, C.c_int64, P, P]
@@ -106,7 +109,7 @@ def _ptr(a):
 
 
 def _check_store(a: np.ndarray, sh: Shape, name: str) -> np.ndarray:
-    want = np.uint16 if sh.dtype == "bf16" else np.float32
+    want = np.float32 if sh.dtype == "f32" else np.uint16        # bf16 / f16 travel as bit patterns
     if a.dtype != want:
         raise TypeError(f"{name}: expected {want} storage for dtype {sh.dtype}, got {a.dtype}")
     if not a.flags.c_contiguous:
@@ -121,6 +124,10 @@ def _check_rc(rc: int, what: str):
 
 def widen_bf16(bits: int) -> float:
     return _lib().ro_widen_bf16(int(bits) & 0xFFFF)
+
+
+def widen_f16(bits: int) -> float:
+    return _lib().ro_widen_f16(int(bits) & 0xFFFF)
 
 
 def score(sh: Shape, q: np.ndarray, k_cache: np.ndarray) -> np.ndarray:

@@ -34,7 +34,7 @@ class Workload:
     n_q_heads: int
     n_kv_heads: int
     head_dim: int
-    dtype: str               # "f32" | "bf16"
+    dtype: str               # "f32" | "bf16" | "f16"
     n_ctx: int               # N, current tokens included as the last n_query rows
     n_query: int             # M
     n_sink: int
@@ -73,7 +73,7 @@ class Workload:
 
     @property
     def elem_bytes(self) -> int:
-        return 2 if self.dtype == "bf16" else 4
+        return 4 if self.dtype == "f32" else 2
 
     @property
     def scan_bytes(self) -> int:
@@ -85,7 +85,7 @@ class Workload:
         return 2 * self.n_query * self.n_q_heads * self.n_mid * self.head_dim
 
     def torch_dtype(self):
-        return torch.bfloat16 if self.dtype == "bf16" else torch.float32
+        return {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}[self.dtype]
 
     def scaled(self, **kw) -> "Workload":
         """Same recipe at other sizes (parity cases the oracle finishes in seconds)."""
@@ -160,8 +160,8 @@ def generate(w: Workload, device="cpu") -> dict:
 
 
 def to_numpy_store(t: torch.Tensor):
-    """Exact stored bytes as numpy: float32 as is, bfloat16 as uint16 bit patterns."""
+    """Exact stored bytes as numpy: float32 as is, bfloat16 and float16 as uint16 bit patterns."""
     t = t.detach().contiguous().cpu()
-    if t.dtype == torch.bfloat16:
+    if t.dtype in (torch.bfloat16, torch.float16):
         return t.view(torch.int16).numpy().view("uint16")
     return t.numpy()

@@ -37,6 +37,8 @@ def rng_inputs(seed, M, Hq, Hkv, D, N, dtype="f32"):
     v = torch.randn(Hkv, N, D, generator=g)
     if dtype == "bf16":
         q, k, v = q.bfloat16(), k.bfloat16(), v.bfloat16()
+    if dtype == "f16":
+        q, k, v = q.half(), k.half(), v.half()
     return q, k, v
 
 
@@ -88,6 +90,30 @@ def test_bf16_widening_exact():
     x = torch.randn(4096, generator=torch.Generator().manual_seed(5)).bfloat16()
     got = np.array([ro.widen_bf16(int(b)) for b in store(x)])
     assert np.array_equal(got, f64(x))
+
+
+def test_f16_widening_exact():
+    assert ro.widen_f16(0x3C00) == 1.0
+    assert ro.widen_f16(0xC000) == -2.0
+    assert ro.widen_f16(0x3E00) == 1.5
+    assert ro.widen_f16(0x0001) == 2.0 ** -24            # smallest subnormal
+    assert ro.widen_f16(0x0400) == 2.0 ** -14            # smallest normal
+    assert ro.widen_f16(0x7BFF) == 65504.0               # largest finite
+    assert ro.widen_f16(0x4248) == 3.140625              # half(pi)
+    x = torch.randn(4096, generator=torch.Generator().manual_seed(6)).half()
+    x[:4] = torch.tensor([1e-6, -3e-7, 6e-5, 0.0]).half()             # subnormals and zero
+    got = np.array([ro.widen_f16(int(b)) for b in store(x)])
+    assert np.array_equal(got, f64(x))
+
+
+@pytest.mark.parametrize("M", [1, 5])
+def test_full_cover_equals_brute_force_attention_f16(M):
+    Hq, Hkv, D, N, s, l = 4, 2, 8, 96, 4, 16
+    q, k, v = rng_inputs(41 + M, M, Hq, Hkv, D, N, "f16")
+    sh = ro.Shape(Hq, Hkv, D, "f16", N, s, l, top_k=10_000, rope_theta=10000.0)
+    res = ro.forward(sh, store(q), store(k), store(v))
+    want = brute_full_attention(f64(q), f64(k), f64(v), np.arange(N - M, N), 10000.0)
+    assert np.abs(res["out"] - want).max() < 1e-12
 
 
 # ------------------------------------------------------ Eq. 1: the partition
