@@ -19,7 +19,7 @@
  * sink = [0, s_eff), middle = [s_eff, N - l_eff), local = [N - l_eff, N).
  *
  * Layouts (row-major, contiguous innermost D):
- *     q        [M][Hq][D]        storage dtype (fp32 or bf16), WITHOUT rotary encoding
+ *     q        [M][Hq][D]        storage dtype (fp32, bf16 or fp16), WITHOUT rotary encoding
  *     k_cache  [Hkv][N][D]       storage dtype, WITHOUT rotary encoding; strides in params
  *     v_cache  [Hkv][N][D]       storage dtype; strides in params
  *     scores   [M][Hkv][N_mid]   fp32
@@ -55,7 +55,12 @@ typedef enum {
   REATTN_ERR_HIP = -8        /* the HIP runtime refused a launch */
 } reattn_status;
 
-typedef enum { REATTN_F32 = 0, REATTN_BF16 = 1 } reattn_dtype;
+/* Storage of q, k_cache, v_cache, v_sel.  All arithmetic is fp32 on exactly widened inputs (the
+ * matrix-core paths split what they must round into hi + lo halves).  REATTN_F16 (IEEE half, the
+ * precision of the paper's own runs) takes the streaming kernels for every step and the matrix
+ * cores for the vote selection; the per-query top-k of a chunk (reattn_prefill_chunk with M > 1)
+ * streams once per query row for it. */
+typedef enum { REATTN_F32 = 0, REATTN_BF16 = 1, REATTN_F16 = 2 } reattn_dtype;
 
 /* How the G heads of one GQA group are combined into one score per KV head.
  * The paper votes over per-head lists; this library aggregates scores instead. */

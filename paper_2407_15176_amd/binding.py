@@ -16,7 +16,8 @@ import torch  # loads the HIP runtime the library binds to; used for memory and 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libreattn.so")
 
-F32, BF16 = 0, 1
+F32, BF16, F16 = 0, 1, 2
+_DTYPE_CODE = {"f32": F32, "bf16": BF16, "f16": F16}
 AGG_SUM = 0
 
 OK = 0
@@ -135,11 +136,11 @@ class Params:
 
     @classmethod
     def from_workload(cls, w) -> "Params":
-        return cls(w.n_q_heads, w.n_kv_heads, w.head_dim, BF16 if w.dtype == "bf16" else F32,
+        return cls(w.n_q_heads, w.n_kv_heads, w.head_dim, _DTYPE_CODE[w.dtype],
                    w.n_ctx, w.n_query, w.n_sink, w.n_local, w.top_k, w.rope_theta, w.max_position)
 
     def torch_dtype(self):
-        return torch.bfloat16 if self.dtype == BF16 else torch.float32
+        return {F32: torch.float32, BF16: torch.bfloat16, F16: torch.float16}[self.dtype]
 
 
 def version() -> int:

@@ -21,7 +21,7 @@ int make_plan(const reattn_params* p, Plan* out) {
   if (p->n_q_heads < 1 || p->n_kv_heads < 1 || p->n_q_heads % p->n_kv_heads) return REATTN_ERR_SHAPE;
   if (p->n_q_heads / p->n_kv_heads > 16) return REATTN_ERR_SHAPE;
   if (p->head_dim != 64 && p->head_dim != 128) return REATTN_ERR_SHAPE;
-  if (p->dtype != REATTN_F32 && p->dtype != REATTN_BF16) return REATTN_ERR_DTYPE;
+  if (p->dtype != REATTN_F32 && p->dtype != REATTN_BF16 && p->dtype != REATTN_F16) return REATTN_ERR_DTYPE;
   if (p->agg != REATTN_AGG_SUM) return REATTN_ERR_DTYPE;
   if (p->n_ctx < 1 || p->n_ctx > 0x7fffffffLL) return REATTN_ERR_RANGE;
   if (p->n_query < 1 || p->n_query > p->n_ctx || p->n_query > 65535) return REATTN_ERR_RANGE;
@@ -43,7 +43,7 @@ int make_plan(const reattn_params* p, Plan* out) {
   if (p->max_position > 0 && S > p->max_position) return REATTN_ERR_WINDOW;
   pl.S = (int)S;
 
-  const int64_t eb = pl.dtype == REATTN_BF16 ? 2 : 4;
+  const int64_t eb = elem_bytes(pl.dtype);
   const bool kdef = p->k_stride_head == 0 && p->k_stride_tok == 0;
   const bool vdef = p->v_stride_head == 0 && p->v_stride_tok == 0;
   pl.kst = kdef ? pl.D : p->k_stride_tok;  pl.ksh = kdef ? pl.N * pl.D : p->k_stride_head;
@@ -158,7 +158,7 @@ inline void mark(hipEvent_t* ev, int i, hipStream_t st) { if (ev) (void)hipEvent
 int select_tile(const Plan& pl, const Ws& w, const void* q, int q0, int nq, const void* k_cache,
                 int32_t* idx_all, bool rope_too, hipEvent_t* ev, hipStream_t st) {
   const int rows = nq * pl.Hkv;
-  const size_t eb = pl.dtype == REATTN_BF16 ? 2 : 4;
+  const size_t eb = (size_t)elem_bytes(pl.dtype);
   const char* qt = (const char*)q + (size_t)q0 * pl.Hq * pl.D * eb;
   int rc = hip_rc(launch_prep(pl, pl.k_eff > 0 ? rows : 0, w.hist, rope_too ? w.rope : nullptr, st));
   mark(ev, 1, st);
@@ -291,7 +291,7 @@ int reattn_score(const reattn_params* p, const void* q, const void* k_cache, flo
     return hip_rc(launch_score_gemm(pl, q, 0, pl.M, k_cache, scores, w.qsplit, st));
   }
   const int per = 65535 / pl.Hkv;
-  const size_t eb = pl.dtype == REATTN_BF16 ? 2 : 4;
+  const size_t eb = (size_t)elem_bytes(pl.dtype);
   for (int q0 = 0; q0 < pl.M && !rc; q0 += per) {
     const int nq = pl.M - q0 < per ? pl.M - q0 : per;
     rc = hip_rc(launch_score_scan(pl, (const char*)q + (size_t)q0 * pl.Hq * pl.D * eb, nq, k_cache,
@@ -428,7 +428,7 @@ int vote_topk_impl(const VotePlan& vp, const void* q, const void* k_cache, int32
   const Plan& pl = vp.pl;
   if (vp.kk == 0) return REATTN_OK;
   const int per = vote_queries_per_launch(pl, vp.kk);
-  const size_t eb = pl.dtype == REATTN_BF16 ? 2 : 4;
+  const size_t eb = (size_t)elem_bytes(pl.dtype);
   int rc = REATTN_OK;
   for (int q0 = 0; q0 < pl.M && !rc; q0 += per) {
     const int nq = pl.M - q0 < per ? pl.M - q0 : per;
@@ -656,7 +656,7 @@ extern "C" int reattn_prefill_sequence(const reattn_params* p, const reattn_vote
   }
   if (!ws || ws_bytes < need) return REATTN_ERR_WORKSPACE;
   if ((uintptr_t)ws % kAlign) return REATTN_ERR_ALIGN;
-  const size_t eb = p->dtype == REATTN_BF16 ? 2 : 4;
+  const size_t eb = (size_t)elem_bytes(p->dtype);
   const size_t qrow = (size_t)p->n_q_heads * p->head_dim, krow = (size_t)p->n_kv_heads * p->head_dim;
   // the largest selection of any chunk is the last one's: it strides sel_out
   int64_t sel_stride = 0;

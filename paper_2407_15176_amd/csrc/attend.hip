@@ -62,6 +62,19 @@ template <> struct Half<uint16_t, 2> {
   }
 };
 
+template <> struct Half<f16bits, 4> {
+  static __device__ __forceinline__ void load(const void* p, float* x) {
+    const u32x2 d = *(const u32x2*)p;
+    x[0] = f16_lo(d.x); x[1] = f16_hi(d.x); x[2] = f16_lo(d.y); x[3] = f16_hi(d.y);
+  }
+};
+template <> struct Half<f16bits, 2> {
+  static __device__ __forceinline__ void load(const void* p, float* x) {
+    const uint32_t d = *(const uint32_t*)p;
+    x[0] = f16_lo(d); x[1] = f16_hi(d);
+  }
+};
+
 // T: storage type of q / V (and of K when FUSED).  GT: query heads per workgroup.
 template <typename T, int D, int GT, bool FUSED>
 __global__ __launch_bounds__(256) void attend_kernel(AttendArgs a) {
@@ -302,9 +315,12 @@ void launch_gt(const AttendArgs& a, int gt, dim3 grid, hipStream_t st) {
 
 template <bool FUSED>
 void launch_td(const Plan& pl, const AttendArgs& a, dim3 grid, hipStream_t st) {
-  if (pl.dtype == 0) {
+  if (pl.dtype == kF32) {
     if (pl.D == 64) launch_gt<float, 64, FUSED>(a, pl.gt, grid, st);
     else            launch_gt<float, 128, FUSED>(a, pl.gt, grid, st);
+  } else if (pl.dtype == kF16) {
+    if (pl.D == 64) launch_gt<f16bits, 64, FUSED>(a, pl.gt, grid, st);
+    else            launch_gt<f16bits, 128, FUSED>(a, pl.gt, grid, st);
   } else {
     if (pl.D == 64) launch_gt<uint16_t, 64, FUSED>(a, pl.gt, grid, st);
     else            launch_gt<uint16_t, 128, FUSED>(a, pl.gt, grid, st);

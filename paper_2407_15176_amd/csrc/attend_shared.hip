@@ -4,8 +4,8 @@
 // differs only in its causal cut inside the local part.  So the concatenation is formed once
 //
 //   pack_shared   slot r -> cache row, key rotary-encoded at position r in fp32 and split into
-//                 two bf16 halves hi + lo (a rotated bf16 key is not a bf16 number; the split
-//                 keeps ~16 mantissa bits), value rows transposed per tile of 32 slots so that
+//                 two halves hi + lo of the storage format (a rotated bf16 key is not a bf16
+//                 number; the split keeps ~16 mantissa bits for bf16, ~22 for IEEE half), value rows transposed per tile of 32 slots so that
 //                 the slot index is the contiguous one (the contraction index of P.V);
 //   qprep_shared  query rows rotary-encoded at their own slot, pre-scaled by
 //                 softmax_scale * log2(e), split hi + lo;
@@ -39,12 +39,6 @@ constexpr int kVTile = 128 * kVPitch;           // 10,240
 constexpr int kBuf = kKTile + kVTile;
 constexpr float kMasked = -1.0e30f;
 
-__device__ __forceinline__ uint16_t as_bf16_rne(float x) {
-  uint32_t u = __float_as_uint(x);
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return (uint16_t)(u >> 16);
-}
-__device__ __forceinline__ float from_bf16(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
 __device__ __forceinline__ u32x4 pack8(const uint16_t* h) {
   u32x4 w;
   w.x = (uint32_t)h[0] | ((uint32_t)h[1] << 16); w.y = (uint32_t)h[2] | ((uint32_t)h[3] << 16);
@@ -76,7 +70,9 @@ __device__ __forceinline__ float2 rope_cs(const SharedArgs& a, int r, int c) {
 }
 
 // One workgroup per (tile of 32 slots, KV head).
+template <bool F16>
 __global__ __launch_bounds__(256) void pack_shared_kernel(SharedArgs a) {
+  typedef Mm<F16> F;
   __shared__ uint16_t vt[kSlots][128 + 8];
   const int tile = blockIdx.x, h = blockIdx.y, tid = threadIdx.x;
   const int n_sel = *a.n_sel;
@@ -99,10 +95,10 @@ __global__ __launch_bounds__(256) void pack_shared_kernel(SharedArgs a) {
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
     const float2 cs = rope_cs(a, r < s_total ? r : 0, c0 + e);
-    const float x = from_bf16(half_of(klo, e)), y = from_bf16(half_of(khi, e));
+    const float x = F::widen(half_of(klo, e)), y = F::widen(half_of(khi, e));
     const float ra = x * cs.x - y * cs.y, rb = y * cs.x + x * cs.y;
-    o_hi_a[e] = as_bf16_rne(ra); o_lo_a[e] = as_bf16_rne(ra - from_bf16(o_hi_a[e]));
-    o_hi_b[e] = as_bf16_rne(rb); o_lo_b[e] = as_bf16_rne(rb - from_bf16(o_hi_b[e]));
+    o_hi_a[e] = F::narrow(ra); o_lo_a[e] = F::narrow(ra - F::widen(o_hi_a[e]));
+    o_hi_b[e] = F::narrow(rb); o_lo_b[e] = F::narrow(rb - F::widen(o_hi_b[e]));
   }
   uint16_t* ko = a.kp + (((int64_t)h * a.s_pad + r) * 2) * 128;
   *(u32x4*)(ko + c0) = pack8(o_hi_a);
@@ -123,23 +119,27 @@ __global__ __launch_bounds__(256) void pack_shared_kernel(SharedArgs a) {
 }
 
 // One thread per channel pair of one (query row, head).
+template <bool F16>
 __global__ __launch_bounds__(64) void qprep_shared_kernel(SharedArgs a) {
+  typedef Mm<F16> F;
   const int i = blockIdx.x, hq = blockIdx.y, c = threadIdx.x;
   const int p = a.s_eff + *a.n_sel + (a.l_eff - a.M + i);   // the slot of the query's own key
   const uint16_t* qr = a.q + ((int64_t)i * a.Hq + hq) * 128;
   const float2 cs = rope_cs(a, p, c);
-  const float x = from_bf16(qr[c]), y = from_bf16(qr[c + 64]);
+  const float x = F::widen(qr[c]), y = F::widen(qr[c + 64]);
   const float ra = (x * cs.x - y * cs.y) * a.scale_log2e, rb = (y * cs.x + x * cs.y) * a.scale_log2e;
   uint16_t* o = a.qp + (((int64_t)i * a.Hq + hq) * 2) * 128;
-  const uint16_t ha = as_bf16_rne(ra), hb = as_bf16_rne(rb);
+  const uint16_t ha = F::narrow(ra), hb = F::narrow(rb);
   o[c] = ha; o[c + 64] = hb;
-  o[128 + c] = as_bf16_rne(ra - from_bf16(ha));
-  o[192 + c] = as_bf16_rne(rb - from_bf16(hb));
+  o[128 + c] = F::narrow(ra - F::widen(ha));
+  o[192 + c] = F::narrow(rb - F::widen(hb));
 }
 
 
 // grid: (row tiles of one KV head, Hkv); longest scopes first.
+template <bool F16>
 __global__ __launch_bounds__(256) void attend_shared_kernel(SharedArgs a, int q_per_wg, int n_row_tiles) {
+  typedef typename Mm<F16>::op8 op8;
   extern __shared__ __attribute__((aligned(16))) unsigned char as_lds[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int ln = lane & 31, lh = lane >> 5;
@@ -156,13 +156,13 @@ __global__ __launch_bounds__(256) void attend_shared_kernel(SharedArgs a, int q_
   if (q_last > a.M - 1) q_last = a.M - 1;
   const int n_tiles = (base_scope + q_last + kSlots - 1) / kSlots;       // the workgroup's longest scope
 
-  bf16x8 qh[8], ql[8];
+  op8 qh[8], ql[8];
   {
     const uint16_t* qr = a.qp + (((int64_t)(live ? qi : 0) * a.Hq + (int64_t)h * a.G + (live ? g : 0)) * 2) * 128 + lh * 8;
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) {
-      qh[ks] = *(const bf16x8*)(qr + ks * 16);
-      ql[ks] = *(const bf16x8*)(qr + 128 + ks * 16);
+      qh[ks] = *(const op8*)(qr + ks * 16);
+      ql[ks] = *(const op8*)(qr + 128 + ks * 16);
     }
   }
   f32x16 o[4];
@@ -208,11 +208,11 @@ __global__ __launch_bounds__(256) void attend_shared_kernel(SharedArgs a, int q_
     const unsigned char* arow = kb + pim * kKPitch + lh * 16;
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) {
-      const bf16x8 kh = *(const bf16x8*)(arow + ks * 32);
-      const bf16x8 kl = *(const bf16x8*)(arow + 256 + ks * 32);
-      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kh, qh[ks], s, 0, 0, 0);
-      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kl, qh[ks], s, 0, 0, 0);
-      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kh, ql[ks], s, 0, 0, 0);
+      const op8 kh = *(const op8*)(arow + ks * 32);
+      const op8 kl = *(const op8*)(arow + 256 + ks * 32);
+      s = Mm<F16>::mfma32(kh, qh[ks], s);
+      s = Mm<F16>::mfma32(kl, qh[ks], s);
+      s = Mm<F16>::mfma32(kh, ql[ks], s);
     }
     // s[i] is slot 32t + 16(i/8) + 8(lane/32) + i%8 of this lane's column
     const int slot0 = t * kSlots + lh * 8;
@@ -237,11 +237,11 @@ __global__ __launch_bounds__(256) void attend_shared_kernel(SharedArgs a, int q_
       psum += p;
       pv[i >> 3][i & 7] = p;
     }
-    bf16x8 ph[2], pl[2];
+    op8 ph[2], pl[2];
 #pragma unroll
     for (int kk = 0; kk < 2; ++kk) {
-      ph[kk] = __builtin_convertvector(pv[kk], bf16x8);
-      pl[kk] = __builtin_convertvector(pv[kk] - __builtin_convertvector(ph[kk], f32x8), bf16x8);
+      ph[kk] = __builtin_convertvector(pv[kk], op8);
+      pl[kk] = __builtin_convertvector(pv[kk] - __builtin_convertvector(ph[kk], f32x8), op8);
     }
     l_run = l_run * alpha + psum;
     if (__any(alpha != 1.0f)) {
@@ -253,12 +253,12 @@ __global__ __launch_bounds__(256) void attend_shared_kernel(SharedArgs a, int q_
     // O^T += V^T P^T: A = values [channel][slot], B = this lane's weights (two k-steps of 16 slots)
 #pragma unroll
     for (int kk = 0; kk < 2; ++kk) {
-      const bf16x8 bh = ph[kk], bl = pl[kk];
+      const op8 bh = ph[kk], bl = pl[kk];
 #pragma unroll
       for (int db = 0; db < 4; ++db) {
-        const bf16x8 va = *(const bf16x8*)(vb + (db * 32 + ln) * kVPitch + kk * 32 + lh * 16);
-        o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, bh, o[db], 0, 0, 0);
-        o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, bl, o[db], 0, 0, 0);
+        const op8 va = *(const op8*)(vb + (db * 32 + ln) * kVPitch + kk * 32 + lh * 16);
+        o[db] = Mm<F16>::mfma32(va, bh, o[db]);
+        o[db] = Mm<F16>::mfma32(va, bl, o[db]);
       }
     }
     if (t + 1 < n_tiles) stash_tile(buf ^ 1);
@@ -282,7 +282,7 @@ __global__ __launch_bounds__(256) void attend_shared_kernel(SharedArgs a, int q_
 
 }  // namespace
 
-bool attend_shared_applies(const Plan& pl) { return pl.dtype == 1 && pl.D == 128 && pl.M > 1 && pl.G <= 16; }
+bool attend_shared_applies(const Plan& pl) { return pl.dtype != kF32 && pl.D == 128 && pl.M > 1 && pl.G <= 16; }
 
 int attend_shared_spad(const Plan& pl) { return (pl.S + kSlots - 1) / kSlots * kSlots; }
 
@@ -306,19 +306,25 @@ hipError_t launch_attend_shared(const Plan& pl, const void* q, const void* k_cac
   a.Hq = pl.Hq; a.Hkv = pl.Hkv; a.G = pl.G; a.M = pl.M;
   a.s_eff = (int)pl.s_eff; a.l_eff = (int)pl.l_eff; a.s_pad = attend_shared_spad(pl);
   a.scale_log2e = pl.scale * 1.4426950408889634f;
-  hipLaunchKernelGGL(pack_shared_kernel, dim3((unsigned)(a.s_pad / kSlots), (unsigned)pl.Hkv), dim3(256), 0, st, a);
-  hipLaunchKernelGGL(qprep_shared_kernel, dim3((unsigned)pl.M, (unsigned)pl.Hq), dim3(64), 0, st, a);
+  const dim3 pgrid((unsigned)(a.s_pad / kSlots), (unsigned)pl.Hkv), qgrid((unsigned)pl.M, (unsigned)pl.Hq);
   const int q_per_wg = 128 / pl.G;
   const int n_row_tiles = (pl.M + q_per_wg - 1) / q_per_wg;
-  static bool attr_done = false;
-  if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute((const void*)attend_shared_kernel,
+  const dim3 agrid((unsigned)n_row_tiles, (unsigned)pl.Hkv);
+  if (pl.dtype == kF16) {
+    hipLaunchKernelGGL(pack_shared_kernel<true>, pgrid, dim3(256), 0, st, a);
+    hipLaunchKernelGGL(qprep_shared_kernel<true>, qgrid, dim3(64), 0, st, a);
+    hipError_t e = hipFuncSetAttribute((const void*)attend_shared_kernel<true>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, 2 * kBuf);
     if (e != hipSuccess) return e;
-    attr_done = true;
+    hipLaunchKernelGGL(attend_shared_kernel<true>, agrid, dim3(256), 2 * kBuf, st, a, q_per_wg, n_row_tiles);
+  } else {
+    hipLaunchKernelGGL(pack_shared_kernel<false>, pgrid, dim3(256), 0, st, a);
+    hipLaunchKernelGGL(qprep_shared_kernel<false>, qgrid, dim3(64), 0, st, a);
+    hipError_t e = hipFuncSetAttribute((const void*)attend_shared_kernel<false>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, 2 * kBuf);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(attend_shared_kernel<false>, agrid, dim3(256), 2 * kBuf, st, a, q_per_wg, n_row_tiles);
   }
-  hipLaunchKernelGGL(attend_shared_kernel, dim3((unsigned)n_row_tiles, (unsigned)pl.Hkv), dim3(256), 2 * kBuf, st,
-                     a, q_per_wg, n_row_tiles);
   return hipGetLastError();
 }
 

@@ -17,6 +17,10 @@ constexpr int kExactSlots = 64;               // workgroups (and score scratch r
 constexpr int kRopeLo = 128;                  // positions covered by the low rotary table
 __host__ __device__ inline int rope_rows_hi(int S) { return (S + kRopeLo - 1) / kRopeLo; }
 
+// storage dtype codes as in reattn_dtype
+constexpr int kF32 = 0, kBF16 = 1, kF16 = 2;
+inline int64_t elem_bytes(int dtype) { return dtype == kF32 ? 4 : 2; }
+
 struct Plan {
   int Hq, Hkv, D, G, dtype, M;
   int64_t N, s_eff, l_eff, n_mid;
@@ -111,6 +115,47 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+// Storage tags of the 16-bit formats: bf16 travels as uint16_t, IEEE half as f16bits.
+struct f16bits { uint16_t v; };
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ float f16_lo(uint32_t w) { return (float)__builtin_bit_cast(f16x2, w)[0]; }
+__device__ __forceinline__ float f16_hi(uint32_t w) { return (float)__builtin_bit_cast(f16x2, w)[1]; }
+__device__ __forceinline__ float f16_one(uint16_t h) { return (float)__builtin_bit_cast(_Float16, h); }
+
+// The two 16-bit matrix-core operand formats behind one interface: F16 = false is bf16, true IEEE half.
+typedef __bf16 mm_bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 mm_f16x8 __attribute__((ext_vector_type(8)));
+typedef float mm_f32x4 __attribute__((ext_vector_type(4)));
+typedef float mm_f32x8 __attribute__((ext_vector_type(8)));
+typedef float mm_f32x16 __attribute__((ext_vector_type(16)));
+template <bool F16> struct Mm;
+template <> struct Mm<false> {
+  typedef mm_bf16x8 op8;
+  static __device__ __forceinline__ mm_f32x16 mfma32(op8 a, op8 b, mm_f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+  }
+  static __device__ __forceinline__ mm_f32x4 mfma16(op8 a, op8 b, mm_f32x4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+  }
+  static __device__ __forceinline__ float widen(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
+  static __device__ __forceinline__ uint16_t narrow(float x) {           // round to nearest even
+    uint32_t u = __float_as_uint(x);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+  }
+};
+template <> struct Mm<true> {
+  typedef mm_f16x8 op8;
+  static __device__ __forceinline__ mm_f32x16 mfma32(op8 a, op8 b, mm_f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
+  }
+  static __device__ __forceinline__ mm_f32x4 mfma16(op8 a, op8 b, mm_f32x4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
+  }
+  static __device__ __forceinline__ float widen(uint16_t h) { return f16_one(h); }
+  static __device__ __forceinline__ uint16_t narrow(float x) { return __builtin_bit_cast(uint16_t, (_Float16)x); }
+};
 
 // Order-preserving image of an fp32 score: larger float <=> larger key.  -0 maps to +0's key.
 __device__ __forceinline__ uint32_t score_key(float x) {

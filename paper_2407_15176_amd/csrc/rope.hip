@@ -13,6 +13,7 @@
 //   gather_rope  materialised form of the concatenation: K rows rotated into an
 //                fp32 buffer, V rows copied.
 #include "common.hpp"
+#include <type_traits>
 
 namespace reattn {
 namespace {
@@ -66,7 +67,7 @@ __global__ __launch_bounds__(256) void gather_rope_kernel(GatherArgs a) {
 #pragma unroll
     for (int e = 0; e < E; ++e) {
       ko[c0 + e] = 0.f; ko[D / 2 + c0 + e] = 0.f;
-      vo[c0 + e] = T(0); vo[D / 2 + c0 + e] = T(0);
+      vo[c0 + e] = T{}; vo[D / 2 + c0 + e] = T{};
     }
     return;
   }
@@ -80,7 +81,10 @@ __global__ __launch_bounds__(256) void gather_rope_kernel(GatherArgs a) {
   for (int e = 0; e < E; ++e) {
     const int c = c0 + e;
     float lo, hi;
-    if (sizeof(T) == 2) {
+    if (std::is_same<T, f16bits>::value) {
+      lo = f16_one(((const uint16_t*)kr)[c]);
+      hi = f16_one(((const uint16_t*)kr)[c + D / 2]);
+    } else if (sizeof(T) == 2) {
       lo = __uint_as_float(((uint32_t)((const uint16_t*)kr)[c]) << 16);
       hi = __uint_as_float(((uint32_t)((const uint16_t*)kr)[c + D / 2]) << 16);
     } else {
@@ -118,7 +122,7 @@ __global__ __launch_bounds__(256) void cache_append_kernel(const u32x4* __restri
 hipError_t launch_cache_append(const Plan& pl, int64_t first_tok, int n_tok, const void* k_new, const void* v_new,
                                void* k_cache, void* v_cache, hipStream_t st) {
   if (n_tok <= 0) return hipSuccess;
-  const int64_t eb = pl.dtype == 1 ? 2 : 4;
+  const int64_t eb = elem_bytes(pl.dtype);
   const int vec_per_row = (int)(pl.D * eb / 16);
   const int64_t n_vec = (int64_t)n_tok * pl.Hkv * vec_per_row;
   hipLaunchKernelGGL(cache_append_kernel, dim3((unsigned)((n_vec + 255) / 256)), dim3(256), 0, st,
@@ -155,9 +159,12 @@ hipError_t launch_gather_rope(const Plan& pl, const void* k_cache, const void* v
   const int64_t total = (int64_t)pl.M * pl.Hkv * pl.S;
   if (total == 0) return hipSuccess;
   const dim3 grid((unsigned)((total + 15) / 16));
-  if (pl.dtype == 0) {
+  if (pl.dtype == kF32) {
     if (pl.D == 64) hipLaunchKernelGGL((gather_rope_kernel<float, 64>), grid, dim3(256), 0, st, a);
     else            hipLaunchKernelGGL((gather_rope_kernel<float, 128>), grid, dim3(256), 0, st, a);
+  } else if (pl.dtype == kF16) {
+    if (pl.D == 64) hipLaunchKernelGGL((gather_rope_kernel<f16bits, 64>), grid, dim3(256), 0, st, a);
+    else            hipLaunchKernelGGL((gather_rope_kernel<f16bits, 128>), grid, dim3(256), 0, st, a);
   } else {
     if (pl.D == 64) hipLaunchKernelGGL((gather_rope_kernel<uint16_t, 64>), grid, dim3(256), 0, st, a);
     else            hipLaunchKernelGGL((gather_rope_kernel<uint16_t, 128>), grid, dim3(256), 0, st, a);

@@ -54,6 +54,15 @@ template <> struct Store<uint16_t> {   // bf16 bit patterns
   }
 };
 
+template <> struct Store<f16bits> {    // IEEE half bit patterns
+  static constexpr int kPerLoad = 8;
+  static __device__ __forceinline__ void widen(const u32x4& d, float* x) {
+    x[0] = f16_lo(d.x); x[1] = f16_hi(d.x); x[2] = f16_lo(d.y); x[3] = f16_hi(d.y);
+    x[4] = f16_lo(d.z); x[5] = f16_hi(d.z); x[6] = f16_lo(d.w); x[7] = f16_hi(d.w);
+  }
+  static __device__ __forceinline__ float one(const void* p, int64_t i) { return f16_one(((const uint16_t*)p)[i]); }
+};
+
 constexpr int kScanThreads = 1024;
 constexpr int kScanMaxRows = 32768;            // rows of scores one workgroup parks in LDS (128 KiB)
 
@@ -210,8 +219,10 @@ hipError_t launch_score_scan(const Plan& pl, const void* q, int n_query, const v
   dim3 grid((unsigned)((pl.n_mid + a.rows_per_block - 1) / a.rows_per_block),
             (unsigned)(pl.Hkv * n_query));
   const bool h = hist != nullptr;
-  if (pl.dtype == 0) return pl.D == 64 ? launch_t<float, 64>(a, grid, h, st)
-                                       : launch_t<float, 128>(a, grid, h, st);
+  if (pl.dtype == kF32) return pl.D == 64 ? launch_t<float, 64>(a, grid, h, st)
+                                          : launch_t<float, 128>(a, grid, h, st);
+  if (pl.dtype == kF16) return pl.D == 64 ? launch_t<f16bits, 64>(a, grid, h, st)
+                                          : launch_t<f16bits, 128>(a, grid, h, st);
   return pl.D == 64 ? launch_t<uint16_t, 64>(a, grid, h, st)
                     : launch_t<uint16_t, 128>(a, grid, h, st);
 }

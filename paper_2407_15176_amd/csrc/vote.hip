@@ -200,8 +200,9 @@ struct MfmaScanArgs {
   int Hq, Hkv, G, n_query, q_per_pass, rows_per_block, n_wg;
 };
 
-template <int KT, int NB>
+template <int KT, int NB, bool F16>
 __global__ __launch_bounds__(kVoteThreads) void head_topk_mfma_kernel(MfmaScanArgs a) {
+  typedef typename Mm<F16>::op8 op8;
   constexpr int D = 128, T = kMfmaTiles, NC = 16 * NB;
   // staging of the key tiles [kVoteWaves][T][16 rows][16 pieces] of 16 bytes while streaming,
   // then the waves' merged lists [kVoteWaves][NC][KT]
@@ -213,7 +214,7 @@ __global__ __launch_bounds__(kVoteThreads) void head_topk_mfma_kernel(MfmaScanAr
   const int q_here = a.n_query - q0 < a.q_per_pass ? a.n_query - q0 : a.q_per_pass;
   const int n_cols = q_here * a.G;
 
-  bf16x8 bq[NB][4];
+  op8 bq[NB][4];
 #pragma unroll
   for (int nb = 0; nb < NB; ++nb) {
     const int c = nb * 16 + col;
@@ -224,7 +225,7 @@ __global__ __launch_bounds__(kVoteThreads) void head_topk_mfma_kernel(MfmaScanAr
     for (int j = 0; j < 4; ++j) {
       u32x4 w = src[4 * j + kq];
       if (!live) w = u32x4{0u, 0u, 0u, 0u};
-      bq[nb][j] = __builtin_bit_cast(bf16x8, w);
+      bq[nb][j] = __builtin_bit_cast(op8, w);
     }
   }
   float bv[NB][KT]; uint32_t bi[NB][KT];
@@ -266,7 +267,7 @@ __global__ __launch_bounds__(kVoteThreads) void head_topk_mfma_kernel(MfmaScanAr
         f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int j = 0; j < 4; ++j)
-          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ka[j]), bq[nb][j], acc, 0, 0, 0);
+          acc = Mm<F16>::mfma16(__builtin_bit_cast(op8, ka[j]), bq[nb][j], acc);
         const float m01 = acc[0] > acc[1] ? acc[0] : acc[1], m23 = acc[2] > acc[3] ? acc[2] : acc[3];
         if ((m01 > m23 ? m01 : m23) > bv[nb][KT - 1]) {
 #pragma unroll
@@ -586,7 +587,7 @@ int vote_list_len(int vote_k) { return vote_k <= 1 ? 1 : vote_k <= 2 ? 2 : vote_
 
 // The streaming path handles 16-lane key rows (bf16 D = 128, fp32 D = 64) and groups of up to 8 heads.
 bool vote_scan_applies(const Plan& pl) {
-  return pl.G <= 8 && ((pl.dtype == 1 && pl.D == 128) || (pl.dtype == 0 && pl.D == 64));
+  return pl.G <= 8 && ((pl.dtype != kF32 && pl.D == 128) || (pl.dtype == kF32 && pl.D == 64));
 }
 
 // Geometry of one scan launch over n_query query rows.
@@ -594,7 +595,7 @@ struct ScanGeom { bool mfma, gemm; int nb, q_per_pass, n_pass, rpb, n_wg; };
 
 ScanGeom scan_geom(const Plan& pl, int n_query, int kt) {
   ScanGeom g;
-  g.mfma = pl.dtype == 1 && pl.D == 128;
+  g.mfma = pl.dtype != kF32 && pl.D == 128;
   g.gemm = g.mfma && n_query * pl.G > 32;              // more columns than one streaming pass holds
   if (g.gemm) {                                        // tiled contraction: every key is read once per 256 columns
     g.nb = 0; g.q_per_pass = n_query; g.n_pass = 1; g.rpb = 0;
@@ -625,18 +626,23 @@ size_t vote_part_bytes(const Plan& pl, int n_query, int vote_k) {
   return (size_t)n_query * pl.Hq * scan_geom(pl, n_query, vote_list_len(vote_k)).n_wg * vote_list_len(vote_k) * sizeof(uint64_t);
 }
 
-template <int KT>
+template <int KT, bool F16>
 hipError_t mfma_launch_nb(const MfmaScanArgs& a, int nb, dim3 grid, hipStream_t st) {
   const size_t lds = (size_t)kVoteWaves * kMfmaTiles * 256 * 16;      // staging; the merged lists fit inside
   static_assert((size_t)kVoteWaves * 32 * 8 * sizeof(uint64_t) <= (size_t)kVoteWaves * kMfmaTiles * 256 * 16, "lists alias the staging");
-  auto k1 = head_topk_mfma_kernel<KT, 1>;
-  auto k2 = head_topk_mfma_kernel<KT, 2>;
+  auto k1 = head_topk_mfma_kernel<KT, 1, F16>;
+  auto k2 = head_topk_mfma_kernel<KT, 2, F16>;
   hipError_t e = hipFuncSetAttribute(nb == 1 ? (const void*)k1 : (const void*)k2,
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   if (e != hipSuccess) return e;
   if (nb == 1) hipLaunchKernelGGL(k1, grid, dim3(kVoteThreads), lds, st, a);
   else         hipLaunchKernelGGL(k2, grid, dim3(kVoteThreads), lds, st, a);
   return hipGetLastError();
+}
+template <bool F16>
+hipError_t mfma_launch_kt(const MfmaScanArgs& a, int kt, int nb, dim3 grid, hipStream_t st) {
+  return kt == 1 ? mfma_launch_nb<1, F16>(a, nb, grid, st) : kt == 2 ? mfma_launch_nb<2, F16>(a, nb, grid, st)
+       : kt == 4 ? mfma_launch_nb<4, F16>(a, nb, grid, st) : mfma_launch_nb<8, F16>(a, nb, grid, st);
 }
 
 // head_topk[i][hq][vote_k] for queries [0, n_query): ascending absolute indices.
@@ -655,8 +661,7 @@ hipError_t launch_head_topk_scan(const Plan& pl, const void* q, int n_query, con
     a.ksh = pl.ksh; a.kst = pl.kst; a.n_mid = pl.n_mid; a.first_tok = pl.s_eff;
     a.Hq = pl.Hq; a.Hkv = pl.Hkv; a.G = pl.G; a.n_query = n_query; a.q_per_pass = g.q_per_pass;
     a.rows_per_block = g.rpb; a.n_wg = g.n_wg;
-    e = kt == 1 ? mfma_launch_nb<1>(a, g.nb, grid, st) : kt == 2 ? mfma_launch_nb<2>(a, g.nb, grid, st)
-      : kt == 4 ? mfma_launch_nb<4>(a, g.nb, grid, st) : mfma_launch_nb<8>(a, g.nb, grid, st);
+    e = pl.dtype == kF16 ? mfma_launch_kt<true>(a, kt, g.nb, grid, st) : mfma_launch_kt<false>(a, kt, g.nb, grid, st);
   } else {
     HeadScanArgs a;
     a.k = k_cache; a.q = q; a.part = part;

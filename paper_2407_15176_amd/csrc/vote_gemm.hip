@@ -47,8 +47,9 @@ __device__ __forceinline__ uint64_t vg_composite(float score, uint32_t pos) {
   return ((uint64_t)score_key(score) << 32) | (uint64_t)(0xffffffffu - pos);
 }
 
-template <int KT>
+template <int KT, bool F16>
 __global__ __launch_bounds__(kThreads) void vote_gemm_kernel(VoteGemmArgs a) {
+  typedef typename Mm<F16>::op8 op8;
   extern __shared__ __attribute__((aligned(16))) unsigned char vg_lds[];
   unsigned char* tiles = vg_lds;                            // two staged key tiles, later the merge area
 
@@ -64,7 +65,7 @@ __global__ __launch_bounds__(kThreads) void vote_gemm_kernel(VoteGemmArgs a) {
   if (n_tiles > a.tiles_per_block) n_tiles = a.tiles_per_block;
 
   // query operands of this wave: 2 column blocks x 8 k-steps of 8 bf16 (columns past the end are zero)
-  bf16x8 bq[2][8];
+  op8 bq[2][8];
 #pragma unroll
   for (int cb = 0; cb < 2; ++cb) {
     const int c = c0 + (cw * 2 + cb) * 32 + ln;
@@ -75,7 +76,7 @@ __global__ __launch_bounds__(kThreads) void vote_gemm_kernel(VoteGemmArgs a) {
     for (int ks = 0; ks < 8; ++ks) {
       u32x4 w = *(const u32x4*)(row + ks * 16);
       if (!live) w = u32x4{0u, 0u, 0u, 0u};
-      bq[cb][ks] = __builtin_bit_cast(bf16x8, w);
+      bq[cb][ks] = __builtin_bit_cast(op8, w);
     }
   }
   // running lists: entry t of column block cb of this thread at lv/li[(cb * KT + t) * kThreads + tid]
@@ -141,9 +142,9 @@ __global__ __launch_bounds__(kThreads) void vote_gemm_kernel(VoteGemmArgs a) {
         for (int i = 0; i < 16; ++i) acc[x][i] = 0.f;
 #pragma unroll
       for (int ks = 0; ks < 8; ++ks) {
-        const bf16x8 av = *(const bf16x8*)(arow + ks * 32);
-        acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bq[0][ks], acc[0], 0, 0, 0);
-        acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bq[1][ks], acc[1], 0, 0, 0);
+        const op8 av = *(const op8*)(arow + ks * 32);
+        acc[0] = Mm<F16>::mfma32(av, bq[0][ks], acc[0]);
+        acc[1] = Mm<F16>::mfma32(av, bq[1][ks], acc[1]);
       }
       if (key_blk + 27 >= a.n_keys) {                       // only the last tile: keys past the end never enter a list
 #pragma unroll
@@ -231,11 +232,11 @@ __global__ __launch_bounds__(kThreads) void vote_gemm_kernel(VoteGemmArgs a) {
   }
 }
 
-template <int KT>
+template <int KT, bool F16>
 hipError_t vote_gemm_launch(const VoteGemmArgs& a, dim3 grid, hipStream_t st) {
   static_assert((size_t)kTileCols * 4 * KT * sizeof(uint64_t) <= 2 * (size_t)kTileBytes, "merge area inside the tiles");
   constexpr size_t lds = 2 * (size_t)kTileBytes + (size_t)2 * KT * kThreads * 8;
-  auto kern = vote_gemm_kernel<KT>;
+  auto kern = vote_gemm_kernel<KT, F16>;
   hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(kern, grid, dim3(kThreads), lds, st, a);
@@ -268,11 +269,19 @@ hipError_t launch_vote_gemm(const Plan& pl, const void* q, int n_query, const vo
   a.tiles_per_block = (int)((n_tiles + a.n_split - 1) / a.n_split);
   const dim3 grid((unsigned)pl.Hkv, (unsigned)(((int64_t)n_query * pl.G + kTileCols - 1) / kTileCols),
                   (unsigned)a.n_split);
+  if (pl.dtype == kF16) {
+    switch (list_len) {
+      case 1: return vote_gemm_launch<1, true>(a, grid, st);
+      case 2: return vote_gemm_launch<2, true>(a, grid, st);
+      case 4: return vote_gemm_launch<4, true>(a, grid, st);
+      default: return vote_gemm_launch<8, true>(a, grid, st);
+    }
+  }
   switch (list_len) {
-    case 1: return vote_gemm_launch<1>(a, grid, st);
-    case 2: return vote_gemm_launch<2>(a, grid, st);
-    case 4: return vote_gemm_launch<4>(a, grid, st);
-    default: return vote_gemm_launch<8>(a, grid, st);
+    case 1: return vote_gemm_launch<1, false>(a, grid, st);
+    case 2: return vote_gemm_launch<2, false>(a, grid, st);
+    case 4: return vote_gemm_launch<4, false>(a, grid, st);
+    default: return vote_gemm_launch<8, false>(a, grid, st);
   }
 }
 

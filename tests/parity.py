@@ -18,7 +18,9 @@ from paper_2407_15176_amd import binding as B
 from paper_2407_15176_amd import workloads as wl
 
 TIE_BAND = 1e-3
-OUT_TOL = {"bf16": 2e-2, "f32": 1e-4}
+# f16 storage: not named by the benchmark spec; the arithmetic is the bf16 path's (fp32 on exactly
+# widened inputs, hi + lo halves on the matrix cores), measured at 1e-5..5e-4, so it is held to 1e-3
+OUT_TOL = {"bf16": 2e-2, "f32": 1e-4, "f16": 1e-3}
 
 
 def oracle_shape(w: wl.Workload) -> ro.Shape:

@@ -22,6 +22,9 @@ SMALL = {
                                         n_local=64, top_k=500, max_position=0),
     "f32_d64_g5": wl.CONFIGS[1].scaled(n_ctx=5_000, n_q_heads=10, n_kv_heads=2, n_local=100,
                                        top_k=50),
+    "f16_d128_g4": wl.CONFIGS[2].scaled(dtype="f16", n_ctx=15_013, n_local=300, top_k=200),
+    "f16_d64_g3": wl.CONFIGS[5].scaled(dtype="f16", n_ctx=8_000, head_dim=64, n_q_heads=6, n_kv_heads=2,
+                                       n_local=128, top_k=64, max_position=0),
 }
 
 
@@ -292,3 +295,26 @@ def test_prefill_chunk_mfma_attention_shapes(kw):
     out, idx = P.run_layer(w, t)
     r = P.check_layer(w, t, out, idx)
     assert r["max_abs_err"] <= 2e-3          # the hi/lo-split MFMA path stays far inside the 2e-2 bar
+
+
+# ------------------------------------------------- batch > 1: sequences folded into the head axis
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+def test_batched_decode_is_head_folding(dtype):
+    """B sequences of equal length, each with its own cache, decode in ONE call when the batch is
+    folded into the head axis (cache [B*Hkv][N][D], q [1][B*Hq][D]): nothing in Eq. 1-3 couples two
+    KV heads, so sequence b's rows must equal the oracle run on sequence b alone."""
+    Bn = 3
+    base = wl.CONFIGS[2].scaled(dtype=dtype, n_ctx=6_007, n_local=200, top_k=150, n_needles=4)
+    seqs = [wl.generate(base.scaled(cfg=10 + b), "cuda") for b in range(Bn)]     # different seeds per sequence
+    fold = base.scaled(n_q_heads=Bn * base.n_q_heads, n_kv_heads=Bn * base.n_kv_heads)
+    q = torch.cat([t["q"] for t in seqs], dim=1).contiguous()                     # [1, B*Hq, D]
+    k = torch.cat([t["k"] for t in seqs], dim=0).contiguous()                     # [B*Hkv, N, D]
+    v = torch.cat([t["v"] for t in seqs], dim=0).contiguous()
+    p = B.Params.from_workload(fold)
+    ws = B.alloc_workspace(p)
+    out, idx = B.decode_step(p, q, k, v, ws)
+    torch.cuda.synchronize()
+    for b, t in enumerate(seqs):
+        ob = out[:, b * base.n_q_heads:(b + 1) * base.n_q_heads].contiguous()
+        ib = idx[:, b * base.n_kv_heads:(b + 1) * base.n_kv_heads].contiguous()
+        P.check_layer(base, t, ob, ib)

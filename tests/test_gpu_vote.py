@@ -42,6 +42,10 @@ CASES = {
                                                  top_k=0), B.Vote(4, 127, 32)),
     "bf16_g3_gemm_k8": (wl.CONFIGS[5].scaled(n_ctx=6_000, n_q_heads=6, n_kv_heads=2, n_query=90, n_local=100, top_k=0,
                                              max_position=0), B.Vote(8, 50, 6)),
+    "f16_g4_decode": (wl.CONFIGS[2].scaled(dtype="f16", n_ctx=25_003, n_local=300, top_k=0), B.Vote(4, 20, 16)),
+    "f16_g4_two_blocks": (wl.CONFIGS[2].scaled(dtype="f16", n_ctx=12_000, n_query=6, n_local=300, top_k=0), B.Vote(2, 64, 8)),
+    "f16_g4_gemm": (wl.CONFIGS[4].scaled(dtype="f16", n_ctx=9_011, n_q_heads=8, n_kv_heads=2, n_query=100, n_local=160,
+                                         top_k=0), B.Vote(4, 40, 16)),
     "f32_g5_chunk": (wl.CONFIGS[1].scaled(n_ctx=5_000, n_q_heads=10, n_kv_heads=2, n_query=6, n_local=100, top_k=0,
                                           max_position=0), B.Vote(3, 11, 64)),
 }
