@@ -46,6 +46,9 @@ def main() -> int:
                     help="run the streaming prefill of one layer over --seq-len tokens alone (chunk 512 by default)")
     ap.add_argument("--seq-len", type=int, default=65536)
     ap.add_argument("--no-sequence", action="store_true", help="skip the streaming-prefill leg")
+    ap.add_argument("--only-batched", action="store_true",
+                    help="run the fp16 batched-decode leg alone (context / batch pairs of the paper's throughput table)")
+    ap.add_argument("--no-batched", action="store_true", help="skip the fp16 batched-decode leg")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy 3 times (a known-size kernel against "
                          "which rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings are scaled)")
@@ -65,6 +68,9 @@ def main() -> int:
     torch.cuda.set_device(0)
     if args.only_prefill:
         print(json.dumps({"prefill": prefill_leg(min(args.steps, 5))}), flush=True)
+        return 0
+    if args.only_batched:
+        print(json.dumps({"batched_decode_f16": batched_decode_leg(args.steps)}), flush=True)
         return 0
     if args.only_sequence:
         print(json.dumps({"prefill_sequence": sequence_leg(args.seq_len, args.chunk if args.chunk != 4096 else 512)}),
@@ -169,6 +175,9 @@ def main() -> int:
         if not args.no_sequence:
             torch.cuda.empty_cache()
             result["prefill_sequence"] = sequence_leg(args.seq_len, 512)
+        if not args.no_batched:
+            torch.cuda.empty_cache()
+            result["batched_decode_f16"] = batched_decode_leg(args.steps)
         t = None
     if not args.no_cpu_baseline:
         if t is None:
@@ -304,6 +313,58 @@ def sequence_leg(seq_len: int, chunk: int, steps: int = 2) -> dict:
         del ws
         torch.cuda.empty_cache()
     return res
+
+
+def batched_decode_leg(steps: int) -> dict:
+    """Decode steps of one layer at the (context, batch) pairs of the paper's throughput table (Appendix,
+    efficiency analysis: LLaMA3-8B, FP16) in fp16 storage.  A batch of equal-length sequences is folded
+    into the head axis (cache [B*Hkv][N][D]): one call serves the whole batch."""
+    import torch
+    from paper_2407_15176_amd import binding as B
+    from paper_2407_15176_amd import workloads as wl
+    rows = []
+    for n_ctx, batch in ((32768, 8), (65536, 5), (98304, 4), (131072, 2), (196608, 1), (262144, 1)):
+        w = wl.CONFIGS[2].scaled(dtype="f16", n_ctx=n_ctx, n_q_heads=32 * batch, n_kv_heads=8 * batch, n_needles=0)
+        g = torch.Generator(device="cuda").manual_seed(240715000 + n_ctx % 997)
+        q = torch.randn(1, w.n_q_heads, 128, generator=g, device="cuda").half()
+        n_rot = max(2, min(8, (1 << 30) // (w.n_kv_heads * n_ctx * 128 * 2)))       # keep the caches out of the 256 MB LLC
+        ks = [torch.randn(w.n_kv_heads, n_ctx, 128, generator=g, device="cuda").half() for _ in range(n_rot)]
+        vs = [torch.randn(w.n_kv_heads, n_ctx, 128, generator=g, device="cuda").half() for _ in range(n_rot)]
+        row = {"n_ctx": n_ctx, "batch": batch}
+        for name, vote in (("topk_4096", None), ("vote_4_127_32", B.Vote(4, 127, 32))):
+            p = B.Params.from_workload(w.scaled(top_k=0) if vote else w)
+            ws = B.alloc_vote_workspace(p, vote) if vote else B.alloc_workspace(p)
+            out = torch.empty(1, w.n_q_heads, 128, dtype=torch.float32, device="cuda")
+            if vote:
+                sel = torch.empty(B.vote_cap(p, vote), dtype=torch.int32, device="cuda")
+                n_sel = torch.zeros(1, dtype=torch.int32, device="cuda")
+                # the vote is pooled over ALL heads of the call: a folded batch would share one selection,
+                # so a batch of B sequences is B calls here
+                pb = B.Params.from_workload(w.scaled(top_k=0, n_q_heads=32, n_kv_heads=8))
+                wsb = B.alloc_vote_workspace(pb, vote)
+                ob = torch.empty(1, 32, 128, dtype=torch.float32, device="cuda")
+                qs = [q[:, 32 * b:32 * (b + 1)].contiguous() for b in range(batch)]
+
+                def step(i):
+                    for b in range(batch):
+                        B.vote_layer(pb, vote, qs[b], ks[i % n_rot][8 * b:8 * (b + 1)],
+                                     vs[i % n_rot][8 * b:8 * (b + 1)], wsb, sel=sel, n_sel=n_sel, out=ob)
+            else:
+                def step(i):
+                    B.decode_step(p, q, ks[i % n_rot], vs[i % n_rot], ws, out=out, want_idx=False)
+            for i in range(2):
+                step(i)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for i in range(steps):
+                step(i)
+            torch.cuda.synchronize()
+            ms = (time.perf_counter() - t0) * 1e3 / steps
+            row[name] = {"ms_per_layer": round(ms, 4), "layer_steps_per_s": round(batch / (ms * 1e-3), 1)}
+        rows.append(row)
+        del ks, vs
+        torch.cuda.empty_cache()
+    return {"workload": "llama3-8b layer shape, fp16 storage, sink 4, local 4096", "pairs": rows}
 
 
 def vote_leg(t: dict, cfg: int, steps: int, warmup: int) -> dict:
