@@ -494,61 +494,163 @@ __global__ __launch_bounds__(kMergeThreads) void vote_count_kernel(const int32_t
   if (threadIdx.x >= n_own) my_seg[threadIdx.x] = -1;
 }
 
-// Once every vote is counted: the composite of every listed token (0 in unused slots).
+// Once every vote is counted: the composite of every listed token (0 in unused slots), and how
+// many tokens hold each vote count (counts of kCountBins - 1 and more share the last bin).
+constexpr int kCountBins = 2048;
 __global__ __launch_bounds__(kMergeThreads) void vote_composite_kernel(const int32_t* __restrict__ seg,
                                                                        const uint32_t* __restrict__ counts,
-                                                                       uint64_t* comp) {
+                                                                       uint64_t* comp, uint32_t* chist) {
+  __shared__ uint32_t lh[kCountBins];
+  for (int b = threadIdx.x; b < kCountBins; b += kMergeThreads) lh[b] = 0;
+  __syncthreads();
   const int64_t i = (int64_t)blockIdx.x * kMergeThreads + threadIdx.x;
   const int32_t v = seg[i];
-  comp[i] = v >= 0 ? vote_composite(counts[v], (uint32_t)v) : 0ull;
+  uint64_t c = 0ull;
+  if (v >= 0) {
+    const uint32_t n = counts[v];
+    c = vote_composite(n, (uint32_t)v);
+    atomicAdd(&lh[n < kCountBins - 1 ? n : kCountBins - 1], 1u);
+  }
+  comp[i] = c;
+  __syncthreads();
+  for (int b = threadIdx.x; b < kCountBins; b += kMergeThreads)
+    if (lh[b]) atomicAdd(&chist[b], lh[b]);
 }
 
-// One workgroup: radix select of the kc largest composites (11-bit digits from `top_bit`
-// down), then sort + spans.  n_slots is a multiple of 1024.
+// The histogram of vote counts names the count d of the kc-th token: everything above it wins
+// outright, and the tokens holding exactly d are tied and decided by index.  Every workgroup
+// finds d for itself (2048 bins) and sorts its 1024 composites into the winners' list and the
+// list of tied tokens (one atomic per workgroup and list).  Nothing to do when the last bin,
+// which mixes counts, holds the kc-th token: the pick then selects over all composites.
+struct SiftOut {
+  uint32_t* n_lists;     // [0] winners so far, [1] tied tokens so far (zeroed with the vote array)
+  int32_t* winners;      // [kMergeThreads] tokens relative to the middle
+  uint32_t* tied;        // low words (~index) of the tied tokens' composites
+};
+
+__device__ __forceinline__ void kth_count(const uint32_t* chist, int kc, uint32_t* sh, uint32_t& n, uint32_t& d,
+                                          uint32_t& above) {
+  const uint32_t x = chist[2 * threadIdx.x] + chist[2 * threadIdx.x + 1];
+  block_scan_incl<kMergeThreads>(x, sh, n);
+  d = 0; above = 0;
+  if (n > (uint32_t)kc) find_kth_bin<kMergeThreads, kCountBins>(chist, (uint32_t)kc, sh, d, above);
+}
+
+__global__ __launch_bounds__(kMergeThreads) void vote_sift_kernel(const uint64_t* __restrict__ comp,
+                                                                  const uint32_t* __restrict__ chist, int kc,
+                                                                  SiftOut o) {
+  __shared__ uint32_t sh[40];
+  __shared__ uint32_t n_w, n_t, base_w, base_t;
+  if (threadIdx.x == 0) { n_w = 0; n_t = 0; }
+  uint32_t n, d, above;
+  kth_count(chist, kc, sh, n, d, above);                        // includes barriers
+  const bool all_win = n <= (uint32_t)kc;
+  if (!all_win && d == kCountBins - 1) return;                  // saturated bins: left to the pick
+  const uint64_t c = comp[(int64_t)blockIdx.x * kMergeThreads + threadIdx.x];
+  const uint32_t votes = (uint32_t)(c >> 32);
+  const bool wins = c != 0ull && (all_win || votes > d);
+  const bool ties = c != 0ull && !all_win && votes == d;
+  uint32_t my = 0;
+  if (wins) my = atomicAdd(&n_w, 1u);
+  if (ties) my = atomicAdd(&n_t, 1u);
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    base_w = n_w ? atomicAdd(&o.n_lists[0], n_w) : 0u;
+    base_t = n_t ? atomicAdd(&o.n_lists[1], n_t) : 0u;
+  }
+  __syncthreads();
+  if (wins) o.winners[base_w + my] = (int32_t)(0xffffffffu - (uint32_t)c);
+  if (ties) o.tied[base_t + my] = (uint32_t)c;
+}
+
+// One workgroup: the winners, plus the lowest-indexed of the tied tokens (radix select on the
+// composites' low words, the first kPickCache of them held in LDS), then sort + spans.  With
+// saturated count bins: radix select over all composites (11-bit digits from `top_bit` down).
+// n_slots is a multiple of 1024.
 __global__ __launch_bounds__(kMergeThreads) void vote_pick_kernel(const uint64_t* __restrict__ comp,
+                                                                  const uint32_t* __restrict__ chist, SiftOut o,
                                                                   int64_t n_slots, int top_bit, SpanArgs a) {
   extern __shared__ uint64_t pick_lds[];
-  uint64_t* cached = pick_lds;                                  // [kPickCache]
   uint32_t* bins = (uint32_t*)(pick_lds + kPickCache);          // [2048]
   __shared__ int32_t win[kMergeThreads], sa[kMergeThreads], sb[kMergeThreads];
   __shared__ int32_t wsum[kMergeThreads / 64];
   __shared__ uint32_t sh[40];
   __shared__ uint32_t n_win;
-  uint32_t mine = 0;
-  for (int64_t i = threadIdx.x; i < n_slots; i += kMergeThreads) {
-    const uint64_t c = comp[i];
-    if (i < kPickCache) cached[i] = c;
-    mine += c ? 1u : 0u;
-  }
-  if (threadIdx.x == 0) n_win = 0;
-  uint32_t n;                                                   // distinct voted tokens
-  block_scan_incl<kMergeThreads>(mine, sh, n);
-  auto at = [&](int64_t i) -> uint64_t { return i < kPickCache ? cached[i] : comp[i]; };
-
-  int shift = 0;
-  uint64_t prefix = 0;                                          // winners: c != 0 and (c >> shift) >= prefix
-  if ((uint32_t)a.kc < n) {
-    shift = top_bit;
-    uint32_t remaining = (uint32_t)a.kc;
-    while (shift > 0) {
-      const int w = shift < 11 ? shift : 11;
-      shift -= w;
-      for (int b = threadIdx.x; b < 2048; b += kMergeThreads) bins[b] = 0;
-      __syncthreads();
-      for (int64_t i = threadIdx.x; i < n_slots; i += kMergeThreads) {
-        const uint64_t c = at(i);
-        if (c && (c >> (shift + w)) == prefix)
-          atomicAdd(&bins[(uint32_t)(c >> shift) & ((1u << w) - 1u)], 1u);
+  uint32_t n, d, above;
+  kth_count(chist, a.kc, sh, n, d, above);
+  const bool all_win = n <= (uint32_t)a.kc;
+  if (all_win || d < kCountBins - 1) {
+    uint32_t* cached = (uint32_t*)pick_lds;                     // [2 * kPickCache] low words
+    constexpr uint32_t kCache = 2 * kPickCache;
+    const uint32_t nw = o.n_lists[0], nt = all_win ? 0u : o.n_lists[1];
+    if (threadIdx.x == 0) n_win = nw;
+    if (threadIdx.x < nw) win[threadIdx.x] = o.winners[threadIdx.x];
+    for (uint32_t i = threadIdx.x; i < nt && i < kCache; i += kMergeThreads) cached[i] = o.tied[i];
+    __syncthreads();
+    if (nt) {
+      auto low = [&](uint32_t i) -> uint32_t { return i < kCache ? cached[i] : o.tied[i]; };
+      const uint32_t need = (uint32_t)a.kc - above;             // lowest indices = largest low words
+      int shift = 0;
+      uint32_t prefix = 0;
+      if (need < nt) {
+        shift = 32;
+        uint32_t remaining = need;
+        while (shift > 0) {
+          const int w = shift < 11 ? shift : 11;
+          shift -= w;
+          for (int b = threadIdx.x; b < 2048; b += kMergeThreads) bins[b] = 0;
+          __syncthreads();
+          for (uint32_t i = threadIdx.x; i < nt; i += kMergeThreads) {
+            const uint64_t c = low(i);
+            if ((uint32_t)(c >> (shift + w)) == prefix) atomicAdd(&bins[(uint32_t)(c >> shift) & ((1u << w) - 1u)], 1u);
+          }
+          __syncthreads();
+          uint32_t dd, ab;
+          find_kth_bin<kMergeThreads, 2048>(bins, remaining, sh, dd, ab);
+          const uint32_t in_bin = bins[dd];
+          remaining -= ab;
+          prefix = (prefix << w) | dd;
+          __syncthreads();
+          if (in_bin == remaining) break;
+        }
       }
-      __syncthreads();
-      uint32_t d, ab;
-      find_kth_bin<kMergeThreads, 2048>(bins, remaining, sh, d, ab);
-      const uint32_t in_bin = bins[d];
-      remaining -= ab;
-      prefix = (prefix << w) | d;
-      __syncthreads();
-      if (in_bin == remaining) break;                           // everything sharing this prefix wins
+      for (uint32_t i = threadIdx.x; i < nt; i += kMergeThreads) {
+        const uint32_t c = low(i);
+        if ((shift >= 32 ? 0u : c >> shift) >= prefix) win[atomicAdd(&n_win, 1u)] = (int32_t)(0xffffffffu - c);
+      }
     }
+    __syncthreads();
+    centres_to_spans(win, (int)n_win, sa, sb, wsum, a);
+    return;
+  }
+
+  // ---- saturated count bins: radix select over all composites ----
+  uint64_t* cached = pick_lds;                                  // [kPickCache]
+  if (threadIdx.x == 0) n_win = 0;
+  for (int64_t i = threadIdx.x; i < n_slots && i < kPickCache; i += kMergeThreads) cached[i] = comp[i];
+  __syncthreads();
+  auto at = [&](int64_t i) -> uint64_t { return i < kPickCache ? cached[i] : comp[i]; };
+  int shift = top_bit;
+  uint64_t prefix = 0;                                          // winners: c != 0 and (c >> shift) >= prefix
+  uint32_t remaining = (uint32_t)a.kc;
+  while (shift > 0) {
+    const int w = shift < 11 ? shift : 11;
+    shift -= w;
+    for (int b = threadIdx.x; b < 2048; b += kMergeThreads) bins[b] = 0;
+    __syncthreads();
+    for (int64_t i = threadIdx.x; i < n_slots; i += kMergeThreads) {
+      const uint64_t c = at(i);
+      if (c && (c >> (shift + w)) == prefix)
+        atomicAdd(&bins[(uint32_t)(c >> shift) & ((1u << w) - 1u)], 1u);
+    }
+    __syncthreads();
+    uint32_t dd, ab;
+    find_kth_bin<kMergeThreads, 2048>(bins, remaining, sh, dd, ab);
+    const uint32_t in_bin = bins[dd];
+    remaining -= ab;
+    prefix = (prefix << w) | dd;
+    __syncthreads();
+    if (in_bin == remaining) break;                             // everything sharing this prefix wins
   }
   for (int64_t i = threadIdx.x; i < n_slots; i += kMergeThreads) {
     const uint64_t c = at(i);
@@ -681,7 +783,8 @@ void vote_merge_layout(const Plan& pl, int64_t n_votes, size_t* counts_bytes, si
                        size_t* comp_bytes) {
   const bool dense = n_votes > kMergeThreads && pl.n_mid > 0;
   const size_t slots = dense ? (size_t)((n_votes + kMergeThreads - 1) / kMergeThreads) * kMergeThreads : 0;
-  *counts_bytes = dense ? (size_t)pl.n_mid * 4 : 0;
+  // the vote array, the histogram of counts, two list lengths, the winners' list
+  *counts_bytes = dense ? ((size_t)pl.n_mid + kCountBins + 2 + kMergeThreads) * 4 : 0;
   *seg_bytes = slots * 4;
   *comp_bytes = slots * 8;
 }
@@ -705,14 +808,19 @@ hipError_t launch_vote_merge(const Plan& pl, const int32_t* lists, int64_t n_row
     lds_ok = true;
   }
   const unsigned n_blocks = (unsigned)((n_votes + kMergeThreads - 1) / kMergeThreads);
-  hipError_t e = launch_fill_u32(counts, pl.n_mid, 0u, st);
+  uint32_t* chist = counts + pl.n_mid;
+  SiftOut so;
+  so.n_lists = chist + kCountBins; so.winners = (int32_t*)(so.n_lists + 2);
+  so.tied = (uint32_t*)seg;                            // the segments are spent once the composites exist
+  hipError_t e = launch_fill_u32(counts, pl.n_mid + kCountBins + 2, 0u, st);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(vote_count_kernel, dim3(n_blocks), dim3(kMergeThreads), 0, st, lists, n_votes,
                      (int32_t)pl.s_eff, (int32_t)pl.n_mid, counts, seg);
-  hipLaunchKernelGGL(vote_composite_kernel, dim3(n_blocks), dim3(kMergeThreads), 0, st, seg, counts, comp);
+  hipLaunchKernelGGL(vote_composite_kernel, dim3(n_blocks), dim3(kMergeThreads), 0, st, seg, counts, comp, chist);
   int top_bit = 33;                                    // 32 index bits + the bits of the largest vote count
   while (top_bit < 63 && (n_rows >> (top_bit - 32)) != 0) ++top_bit;
-  hipLaunchKernelGGL(vote_pick_kernel, dim3(1), dim3(kMergeThreads), kPickLds, st, comp,
+  hipLaunchKernelGGL(vote_sift_kernel, dim3(n_blocks), dim3(kMergeThreads), 0, st, comp, chist, kc, so);
+  hipLaunchKernelGGL(vote_pick_kernel, dim3(1), dim3(kMergeThreads), kPickLds, st, comp, chist, so,
                      (int64_t)n_blocks * kMergeThreads, top_bit, a);
   return hipGetLastError();
 }

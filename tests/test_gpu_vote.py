@@ -105,6 +105,7 @@ def test_vote_merge_on_given_lists_heavy_ties():
     (40, 3_000, B.Vote(4, 127, 32)),     # most tokens voted once or twice
     (512, 30_000, B.Vote(4, 127, 32)),   # 65,536 votes, more distinct tokens than the pick caches in LDS
     (512, 100, B.Vote(8, 1024, 1)),      # fewer voted tokens than centres: all of them are kept
+    (512, 10, B.Vote(4, 3, 5)),          # ~6,500 votes per token: the count histogram saturates
 ])
 def test_vote_merge_dense_path(n_query, pool_size, vote):
     """More than 1024 votes: atomic counts in a dense array + radix select of the centres."""
@@ -124,6 +125,21 @@ def test_vote_merge_dense_path(n_query, pool_size, vote):
         torch.cuda.synchronize()
         want = ro.vote_merge(lists.reshape(-1, kk), n_mid, s_eff, vote.n_centres, vote.span)
         assert sel.cpu().numpy()[: int(n_sel.item())].tolist() == want["sel"].tolist()
+
+
+def test_vote_merge_all_votes_distinct():
+    """32,768 votes for 32,768 different tokens: every count ties, more ties than the pick holds in LDS."""
+    w = wl.CONFIGS[2].scaled(n_ctx=50_000, n_local=600, top_k=0, n_query=256, max_position=0)
+    p = B.Params.from_workload(w)
+    v = B.Vote(4, 127, 32)
+    s_eff, l_eff, n_mid, _, _ = B.scope(p)
+    perm = np.random.default_rng(1).permutation(n_mid)[: 256 * w.n_q_heads * 4] + s_eff
+    lists = np.sort(perm.reshape(-1, 4), axis=1).astype(np.int32).reshape(256, w.n_q_heads, 4)
+    ws = B.alloc_vote_workspace(p, v)
+    sel, n_sel = B.vote_merge(p, v, torch.from_numpy(lists).cuda(), ws)
+    torch.cuda.synchronize()
+    want = ro.vote_merge(lists.reshape(-1, 4), n_mid, s_eff, v.n_centres, v.span)
+    assert sel.cpu().numpy()[: int(n_sel.item())].tolist() == want["sel"].tolist()
 
 
 @pytest.mark.parametrize("n_query", [3, 64])           # one-workgroup ranking / dense vote array
