@@ -64,7 +64,7 @@ int make_plan(const reattn_params* p, Plan* out) {
   {
     // slots per workgroup: 256 (16 per 16-lane group) unless that leaves CUs idle
     const int64_t units = (int64_t)pl.Hkv * pl.nsub * pl.M;
-    int64_t want = (256 + units - 1) / units;             // workgroups along S to fill the chip
+    int64_t want = (768 + units - 1) / units;             // workgroups along S: three per CU keep the row gathers in flight
     if (want < 1) want = 1;
     int64_t len = (S + want - 1) / want;
     len = (len + 63) / 64 * 64;
@@ -370,7 +370,7 @@ struct VotePlan {
   Plan pl;                 // base plan with k_eff = cap (largest selection)
   int kk, kc, span;        // votes per list, centres, span (all clamped)
   size_t off_rope, off_apart, off_part, off_lists, off_counts, off_seg, off_comp, off_sel, off_nsel, off_kp, off_vp,
-         off_qp, total;
+         off_qp, off_spart, total;
 };
 
 int make_vote_plan(const reattn_params* p, const reattn_vote* v, VotePlan* out) {
@@ -413,11 +413,12 @@ int make_vote_plan(const reattn_params* p, const reattn_vote* v, VotePlan* out) 
   vp.off_comp = off;    off += up(mb);
   vp.off_sel = off;     off += up((size_t)(pl.k_eff > 0 ? pl.k_eff : 1) * 4);
   vp.off_nsel = off;    off += up(4);
-  size_t kpb = 0, vpb = 0, qpb = 0;
-  if (attend_shared_applies(pl)) attend_shared_layout(pl, &kpb, &vpb, &qpb);
+  size_t kpb = 0, vpb = 0, qpb = 0, spb = 0;
+  if (attend_shared_applies(pl)) attend_shared_layout(pl, &kpb, &vpb, &qpb, &spb);
   vp.off_kp = off;      off += up(kpb);
   vp.off_vp = off;      off += up(vpb);
   vp.off_qp = off;      off += up(qpb);
+  vp.off_spart = off;   off += up(spb);
   vp.total = off;
   *out = vp;
   return REATTN_OK;
@@ -508,7 +509,7 @@ static int vote_layer_impl(const reattn_params* p, const reattn_vote* v, const v
   // one shared index row for every (query, KV head); its length is read on the device
   if (attend_shared_applies(pl))       // a chunk on bf16 / D = 128: packed once, flash attention on the matrix cores
     rc = hip_rc(launch_attend_shared(pl, q, k_cache, v_cache, sel, n_sel, rope, b + vp.off_kp, b + vp.off_vp,
-                                     b + vp.off_qp, out, st));
+                                     b + vp.off_qp, (float*)(b + vp.off_spart), out, st));
   else
     rc = hip_rc(launch_attend(pl, true, q, 0, pl.M, k_cache, v_cache, sel, rope, (float*)(b + vp.off_apart), out,
                               st, n_sel, 0));

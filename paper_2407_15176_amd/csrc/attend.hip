@@ -346,14 +346,18 @@ hipError_t launch_attend(const Plan& pl, bool fused, const void* q, int q_first,
   if (fused) launch_td<true>(pl, a, grid, st); else launch_td<false>(pl, a, grid, st);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  float* o = out + (int64_t)q_first * pl.Hq * pl.D;
-  const dim3 cgrid((unsigned)(n_query * pl.Hq));
-  if (pl.nsplit > 4) {
-    if (pl.D == 64) hipLaunchKernelGGL((attend_combine_kernel<64, 16>), cgrid, dim3(1024), 0, st, part, pl.nsplit, o);
-    else            hipLaunchKernelGGL((attend_combine_kernel<128, 8>), cgrid, dim3(1024), 0, st, part, pl.nsplit, o);
+  return launch_attend_combine(pl.D, (int64_t)n_query * pl.Hq, pl.nsplit, part,
+                               out + (int64_t)q_first * pl.Hq * pl.D, st);
+}
+
+hipError_t launch_attend_combine(int D, int64_t rows, int nsplit, const float* part, float* o, hipStream_t st) {
+  const dim3 cgrid((unsigned)rows);
+  if (nsplit > 4) {
+    if (D == 64) hipLaunchKernelGGL((attend_combine_kernel<64, 16>), cgrid, dim3(1024), 0, st, part, nsplit, o);
+    else         hipLaunchKernelGGL((attend_combine_kernel<128, 8>), cgrid, dim3(1024), 0, st, part, nsplit, o);
   } else {
-    if (pl.D == 64) hipLaunchKernelGGL((attend_combine_kernel<64, 1>), cgrid, dim3(64), 0, st, part, pl.nsplit, o);
-    else            hipLaunchKernelGGL((attend_combine_kernel<128, 1>), cgrid, dim3(128), 0, st, part, pl.nsplit, o);
+    if (D == 64) hipLaunchKernelGGL((attend_combine_kernel<64, 1>), cgrid, dim3(64), 0, st, part, nsplit, o);
+    else         hipLaunchKernelGGL((attend_combine_kernel<128, 1>), cgrid, dim3(128), 0, st, part, nsplit, o);
   }
   return hipGetLastError();
 }

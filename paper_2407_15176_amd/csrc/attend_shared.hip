@@ -37,7 +37,8 @@ constexpr int kVPitch = 80;                     // bytes per staged value channe
 constexpr int kKTile = kSlots * kKPitch;        // 16,896
 constexpr int kVTile = 128 * kVPitch;           // 10,240
 constexpr int kBuf = kKTile + kVTile;
-constexpr float kMasked = -1.0e30f;
+constexpr float kNoMax = -1.0e30f;               // running maximum before any visible slot
+constexpr float kMasked = -2.0e30f;              // score of a hidden slot: 2^(kMasked - max) is 0 even against kNoMax
 
 __device__ __forceinline__ u32x4 pack8(const uint16_t* h) {
   u32x4 w;
@@ -137,9 +138,13 @@ __global__ __launch_bounds__(64) void qprep_shared_kernel(SharedArgs a) {
 
 
 // grid: (row tiles of one KV head, Hkv); longest scopes first.
+// With few query rows the slots are also split over blockIdx.z (flash-decoding): a workgroup then
+// writes its unnormalised (max, sum, output) triple per column and attend_combine merges them.
 template <bool F16>
-__global__ __launch_bounds__(256) void attend_shared_kernel(SharedArgs a, int q_per_wg, int n_row_tiles) {
+__global__ __launch_bounds__(256) void attend_shared_kernel(SharedArgs a, int q_per_wg, int n_row_tiles, int nsplit,
+                                                            float* part) {
   typedef typename Mm<F16>::op8 op8;
+  constexpr int NT = 256, KP = 1024 / NT, VP = 512 / NT;   // threads, 16-byte pieces per thread of a key / value tile
   extern __shared__ __attribute__((aligned(16))) unsigned char as_lds[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int ln = lane & 31, lh = lane >> 5;
@@ -154,7 +159,10 @@ __global__ __launch_bounds__(256) void attend_shared_kernel(SharedArgs a, int q_
   const int scope = live ? base_scope + qi : 1;                          // slots [0, scope) are visible
   int q_last = rt * q_per_wg + q_per_wg - 1;
   if (q_last > a.M - 1) q_last = a.M - 1;
-  const int n_tiles = (base_scope + q_last + kSlots - 1) / kSlots;       // the workgroup's longest scope
+  const int n_tiles_all = (base_scope + q_last + kSlots - 1) / kSlots;   // the workgroup's longest scope
+  const int per_split = (n_tiles_all + nsplit - 1) / nsplit;
+  const int t_first = (int)blockIdx.z * per_split;
+  const int t_end = t_first + per_split < n_tiles_all ? t_first + per_split : n_tiles_all;
 
   op8 qh[8], ql[8];
   {
@@ -170,35 +178,37 @@ __global__ __launch_bounds__(256) void attend_shared_kernel(SharedArgs a, int q_
   for (int db = 0; db < 4; ++db)
 #pragma unroll
     for (int i = 0; i < 16; ++i) o[db][i] = 0.f;
-  float m_run = kMasked, l_run = 0.f;
+  float m_run = kNoMax, l_run = 0.f;
 
   // staging: a key tile is 32 x 512 contiguous bytes (1024 pieces of 16), a value tile 128 x 64 (512 pieces)
   const unsigned char* kg = (const unsigned char*)(a.kp + ((int64_t)h * a.s_pad) * 256);
   const unsigned char* vg = (const unsigned char*)(a.vp + ((int64_t)h * (a.s_pad / kSlots)) * 128 * kSlots);
-  u32x4 sk[4], sv[2];
+  u32x4 sk[KP], sv[VP];
   auto load_tile = [&](int t) {
 #pragma unroll
-    for (int j = 0; j < 4; ++j) sk[j] = *(const u32x4*)(kg + (int64_t)t * (kSlots * 512) + (tid + 256 * j) * 16);
+    for (int j = 0; j < KP; ++j) sk[j] = *(const u32x4*)(kg + (int64_t)t * (kSlots * 512) + (tid + NT * j) * 16);
 #pragma unroll
-    for (int j = 0; j < 2; ++j) sv[j] = *(const u32x4*)(vg + (int64_t)t * (128 * 64) + (tid + 256 * j) * 16);
+    for (int j = 0; j < VP; ++j) sv[j] = *(const u32x4*)(vg + (int64_t)t * (128 * 64) + (tid + NT * j) * 16);
   };
   auto stash_tile = [&](int buf) {
     unsigned char* kb = as_lds + buf * kBuf;
     unsigned char* vb = kb + kKTile;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) { const int p = tid + 256 * j; *(u32x4*)(kb + (p >> 5) * kKPitch + (p & 31) * 16) = sk[j]; }
+    for (int j = 0; j < KP; ++j) { const int p = tid + NT * j; *(u32x4*)(kb + (p >> 5) * kKPitch + (p & 31) * 16) = sk[j]; }
 #pragma unroll
-    for (int j = 0; j < 2; ++j) { const int p = tid + 256 * j; *(u32x4*)(vb + (p >> 2) * kVPitch + (p & 3) * 16) = sv[j]; }
+    for (int j = 0; j < VP; ++j) { const int p = tid + NT * j; *(u32x4*)(vb + (p >> 2) * kVPitch + (p & 3) * 16) = sv[j]; }
   };
-  load_tile(0);
-  stash_tile(0);
+  if (t_first < t_end) {
+    load_tile(t_first);
+    stash_tile(0);
+  }
   __syncthreads();
 
   // A row m of the score contraction takes slot pi(m): 4-blocks 1 and 2 of every 16 swapped
   const int pim = (ln & ~12) | ((ln & 4) << 1) | ((ln & 8) >> 1);
-  for (int t = 0; t < n_tiles; ++t) {
-    const int buf = t & 1;
-    if (t + 1 < n_tiles) load_tile(t + 1);
+  for (int t = t_first; t < t_end; ++t) {
+    const int buf = (t - t_first) & 1;
+    if (t + 1 < t_end) load_tile(t + 1);
     const unsigned char* kb = as_lds + buf * kBuf;
     const unsigned char* vb = kb + kKTile;
     // S^T = K Q^T: hi.hi + lo.hi + hi.lo
@@ -261,21 +271,28 @@ __global__ __launch_bounds__(256) void attend_shared_kernel(SharedArgs a, int q_
         o[db] = Mm<F16>::mfma32(va, bl, o[db]);
       }
     }
-    if (t + 1 < n_tiles) stash_tile(buf ^ 1);
+    if (t + 1 < t_end) stash_tile(buf ^ 1);
     __syncthreads();
   }
 
   const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
   if (live) {
-    const float inv = 1.0f / l_tot;
-    float* orow = a.out + ((int64_t)qi * a.Hq + (int64_t)h * a.G + g) * 128;
+    const int64_t row = (int64_t)qi * a.Hq + (int64_t)h * a.G + g;
+    const float inv = nsplit == 1 ? 1.0f / l_tot : 1.0f;
+    float* orow = nsplit == 1 ? a.out + row * 128 : part + (row * nsplit + blockIdx.z) * 130 + 2;
+    if (nsplit > 1 && lh == 0) { orow[-2] = m_run; orow[-1] = l_tot; }
 #pragma unroll
     for (int db = 0; db < 4; ++db)
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         // o[db][4j .. 4j+3] are channels 32 db + 8 j + 4 (lane/32) + 0..3
-        float4 w = make_float4(o[db][4 * j] * inv, o[db][4 * j + 1] * inv, o[db][4 * j + 2] * inv, o[db][4 * j + 3] * inv);
-        *(float4*)(orow + db * 32 + j * 8 + lh * 4) = w;
+        float* dst = orow + db * 32 + j * 8 + lh * 4;
+        if (nsplit == 1) {
+          *(float4*)dst = make_float4(o[db][4 * j] * inv, o[db][4 * j + 1] * inv, o[db][4 * j + 2] * inv, o[db][4 * j + 3] * inv);
+        } else {                                           // rows of 130 floats: 8-byte aligned only
+          *(float2*)dst = make_float2(o[db][4 * j], o[db][4 * j + 1]);
+          *(float2*)(dst + 2) = make_float2(o[db][4 * j + 2], o[db][4 * j + 3]);
+        }
       }
   }
 }
@@ -286,18 +303,29 @@ bool attend_shared_applies(const Plan& pl) { return pl.dtype != kF32 && pl.D == 
 
 int attend_shared_spad(const Plan& pl) { return (pl.S + kSlots - 1) / kSlots * kSlots; }
 
-// bytes of the packed keys, packed values and prepared queries
-void attend_shared_layout(const Plan& pl, size_t* kp, size_t* vp, size_t* qp) {
+// Splits of the slot axis: with few query rows the row tiles alone leave most of the chip idle.
+int attend_shared_splits(const Plan& pl) {
+  const int64_t wgs = (int64_t)((pl.M + 128 / pl.G - 1) / (128 / pl.G)) * pl.Hkv;
+  int64_t n = 512 / (wgs > 0 ? wgs : 1);
+  const int64_t tiles = (pl.S + kSlots - 1) / kSlots;
+  if (n > tiles / 8) n = tiles / 8;                     // at least 8 tiles per split
+  return (int)(n < 1 ? 1 : n > 8 ? 8 : n);
+}
+
+// bytes of the packed keys, packed values, prepared queries and split partials
+void attend_shared_layout(const Plan& pl, size_t* kp, size_t* vp, size_t* qp, size_t* part) {
   const size_t sp = (size_t)attend_shared_spad(pl);
   *kp = (size_t)pl.Hkv * sp * 512;
   *vp = (size_t)pl.Hkv * sp * 256;
   *qp = (size_t)pl.M * pl.Hq * 512;
+  const int ns = attend_shared_splits(pl);
+  *part = ns > 1 ? (size_t)pl.M * pl.Hq * ns * 130 * 4 : 0;
 }
 
 // pl.S is the largest scope (s_eff + cap + l_eff); `rope` must cover it.
 hipError_t launch_attend_shared(const Plan& pl, const void* q, const void* k_cache, const void* v_cache,
                                 const int32_t* sel, const int32_t* n_sel, const float2* rope, void* kp,
-                                void* vp, void* qp, float* out, hipStream_t st) {
+                                void* vp, void* qp, float* part, float* out, hipStream_t st) {
   SharedArgs a;
   a.q = (const uint16_t*)q; a.k = (const uint16_t*)k_cache; a.v = (const uint16_t*)v_cache;
   a.sel = sel; a.n_sel = n_sel; a.rope = rope; a.rope_n_hi = rope_rows_hi(pl.S);
@@ -309,23 +337,20 @@ hipError_t launch_attend_shared(const Plan& pl, const void* q, const void* k_cac
   const dim3 pgrid((unsigned)(a.s_pad / kSlots), (unsigned)pl.Hkv), qgrid((unsigned)pl.M, (unsigned)pl.Hq);
   const int q_per_wg = 128 / pl.G;
   const int n_row_tiles = (pl.M + q_per_wg - 1) / q_per_wg;
-  const dim3 agrid((unsigned)n_row_tiles, (unsigned)pl.Hkv);
-  if (pl.dtype == kF16) {
-    hipLaunchKernelGGL(pack_shared_kernel<true>, pgrid, dim3(256), 0, st, a);
-    hipLaunchKernelGGL(qprep_shared_kernel<true>, qgrid, dim3(64), 0, st, a);
-    hipError_t e = hipFuncSetAttribute((const void*)attend_shared_kernel<true>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, 2 * kBuf);
+  const int nsplit = attend_shared_splits(pl);
+  const dim3 agrid((unsigned)n_row_tiles, (unsigned)pl.Hkv, (unsigned)nsplit);
+  auto run = [&](auto pack, auto qprep, auto att) -> hipError_t {
+    hipLaunchKernelGGL(pack, pgrid, dim3(256), 0, st, a);
+    hipLaunchKernelGGL(qprep, qgrid, dim3(64), 0, st, a);
+    hipError_t e = hipFuncSetAttribute((const void*)att, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * kBuf);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(attend_shared_kernel<true>, agrid, dim3(256), 2 * kBuf, st, a, q_per_wg, n_row_tiles);
-  } else {
-    hipLaunchKernelGGL(pack_shared_kernel<false>, pgrid, dim3(256), 0, st, a);
-    hipLaunchKernelGGL(qprep_shared_kernel<false>, qgrid, dim3(64), 0, st, a);
-    hipError_t e = hipFuncSetAttribute((const void*)attend_shared_kernel<false>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, 2 * kBuf);
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(attend_shared_kernel<false>, agrid, dim3(256), 2 * kBuf, st, a, q_per_wg, n_row_tiles);
-  }
-  return hipGetLastError();
+    hipLaunchKernelGGL(att, agrid, dim3(256), 2 * kBuf, st, a, q_per_wg, n_row_tiles, nsplit, part);
+    return hipGetLastError();
+  };
+  hipError_t e = pl.dtype == kF16 ? run(pack_shared_kernel<true>, qprep_shared_kernel<true>, attend_shared_kernel<true>)
+                                  : run(pack_shared_kernel<false>, qprep_shared_kernel<false>, attend_shared_kernel<false>);
+  if (e != hipSuccess || nsplit == 1) return e;
+  return launch_attend_combine(128, pl.M * pl.Hq, nsplit, part, out, st);
 }
 
 }  // namespace reattn

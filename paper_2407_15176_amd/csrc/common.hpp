@@ -97,10 +97,12 @@ hipError_t launch_vote_merge(const Plan& pl, const int32_t* lists, int64_t n_row
                              hipStream_t st);
 
 bool attend_shared_applies(const Plan& pl);
-void attend_shared_layout(const Plan& pl, size_t* kp, size_t* vp, size_t* qp);
+void attend_shared_layout(const Plan& pl, size_t* kp, size_t* vp, size_t* qp, size_t* part);
 hipError_t launch_attend_shared(const Plan& pl, const void* q, const void* k_cache, const void* v_cache,
                                 const int32_t* sel, const int32_t* n_sel, const float2* rope, void* kp,
-                                void* vp, void* qp, float* out, hipStream_t st);
+                                void* vp, void* qp, float* part, float* out, hipStream_t st);
+// merges split partials [(rows)][nsplit][D + 2] = (max, sum, unnormalised output) into out [rows][D]
+hipError_t launch_attend_combine(int D, int64_t rows, int nsplit, const float* part, float* out, hipStream_t st);
 size_t attend_prefill_table_bytes(const Plan& pl);
 bool attend_prefill_applies(const Plan& pl);
 hipError_t launch_attend_prefill(const Plan& pl, const void* q, const void* k_cache,
