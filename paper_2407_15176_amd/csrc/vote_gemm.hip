@@ -33,7 +33,8 @@ constexpr int kPitch = 272;                     // bytes per staged key row (256
 constexpr int kThreads = 512;                   // 8 waves: 2 pairs of key blocks x 4 column quarters
 constexpr int kTileCols = 256;                  // columns per workgroup
 constexpr int kTileBytes = kTileKeys * kPitch;
-constexpr int kStageNS = 2048 / kThreads;       // 16-byte pieces of a key tile per thread
+constexpr int kStageNS = 2048 / kThreads;
+constexpr int kFloorEvery = 32;                 // tiles between refreshes of the columns' shared floors (power of two)       // 16-byte pieces of a key tile per thread
 
 struct VoteGemmArgs {
   const uint16_t* k;        // key cache (bf16 bits)
@@ -83,6 +84,12 @@ __global__ __launch_bounds__(kThreads) void vote_gemm_kernel(VoteGemmArgs a) {
   // (best first); only the k-th value, the bar a new score has to clear, lives in a register
   float* lv = (float*)(vg_lds + 2 * kTileBytes);
   uint32_t* li = (uint32_t*)(lv + 2 * KT * kThreads);
+  // A column has four partial lists (2 wave rows x 2 lane halves).  Every kFloorEvery tiles one thread
+  // per column merges them and publishes the column's true k-th value so far (`floor`): a score below
+  // it cannot end among the column's k best, so each list admits about a quarter of what it would on
+  // its own.  A score equal to the floor may still win on its lower key, so it passes.
+  float* xfloor = (float*)(li + 2 * KT * kThreads);         // [kTileCols]
+  if (tid < kTileCols) xfloor[tid] = -__builtin_inff();
   float bar[2];
 #pragma unroll
   for (int cb = 0; cb < 2; ++cb) {
@@ -130,6 +137,9 @@ __global__ __launch_bounds__(kThreads) void vote_gemm_kernel(VoteGemmArgs a) {
   auto step = [&](int64_t t, int buf) {
     if (t + 1 < n_tiles) stash_tile(buf ^ 1, stg);
     if (t + 2 < n_tiles) load_tile(tile0 + t + 2, stg);
+    float floor_[2];
+#pragma unroll
+    for (int cb = 0; cb < 2; ++cb) floor_[cb] = xfloor[(cw * 2 + cb) * 32 + ln];
 #pragma unroll
     for (int j = 0; j < 2; ++j) {                           // the two key blocks of this wave
       const int kb = kw * 2 + j;
@@ -161,8 +171,8 @@ __global__ __launch_bounds__(kThreads) void vote_gemm_kernel(VoteGemmArgs a) {
         // A score enters a list rarely (the list's k-th value climbs quickly), and then usually
         // one per lane: take the lane's largest remaining score, insert, strike it out, again.
         // Largest first and, among equals, lowest key first: an equal score never displaces.
-        while (__any(m > bar[cb])) {
-          if (m > bar[cb]) {
+        while (__any(m > bar[cb] && m >= floor_[cb])) {
+          if (m > bar[cb] && m >= floor_[cb]) {
             int at = 15;
 #pragma unroll
             for (int i = 14; i >= 0; --i) at = acc[cb][i] == m ? i : at;     // lowest i holding the maximum
@@ -188,6 +198,31 @@ __global__ __launch_bounds__(kThreads) void vote_gemm_kernel(VoteGemmArgs a) {
             }
           }
         }
+      }
+    }
+    if ((t & (kFloorEvery - 1)) == kFloorEvery - 1) {       // workgroup-uniform
+      __syncthreads();                                      // every list is at rest
+      if (tid < kTileCols) {
+        // thread tid owns column tid = (cw2 * 32 + ln): its lists sit with threads (cw * 2 + kw) * 64 + lh * 32 + ln
+        const int cw2 = tid >> 5, lcol = tid & 31, ccw = cw2 >> 1, ccb = cw2 & 1;
+        float best[KT];
+#pragma unroll
+        for (int y = 0; y < KT; ++y) best[y] = -__builtin_inff();
+#pragma unroll
+        for (int part = 0; part < 4; ++part) {
+          const int owner = (ccw * 2 + (part >> 1)) * 64 + (part & 1) * 32 + lcol;
+#pragma unroll
+          for (int y = 0; y < KT; ++y) {
+            float v = lv[(ccb * KT + y) * kThreads + owner];
+#pragma unroll
+            for (int z = 0; z < KT; ++z) {                  // keep the KT largest, descending
+              const float hi = fmaxf(best[z], v);
+              v = fminf(best[z], v);
+              best[z] = hi;
+            }
+          }
+        }
+        xfloor[tid] = best[KT - 1];
       }
     }
     __syncthreads();
@@ -235,7 +270,7 @@ __global__ __launch_bounds__(kThreads) void vote_gemm_kernel(VoteGemmArgs a) {
 template <int KT, bool F16>
 hipError_t vote_gemm_launch(const VoteGemmArgs& a, dim3 grid, hipStream_t st) {
   static_assert((size_t)kTileCols * 4 * KT * sizeof(uint64_t) <= 2 * (size_t)kTileBytes, "merge area inside the tiles");
-  constexpr size_t lds = 2 * (size_t)kTileBytes + (size_t)2 * KT * kThreads * 8;
+  constexpr size_t lds = 2 * (size_t)kTileBytes + (size_t)2 * KT * kThreads * 8 + kTileCols * 4;
   auto kern = vote_gemm_kernel<KT, F16>;
   hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   if (e != hipSuccess) return e;
