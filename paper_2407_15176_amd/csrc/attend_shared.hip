@@ -5,8 +5,9 @@
 //
 //   pack_shared   slot r -> cache row, key rotary-encoded at position r in fp32 and split into
 //                 two halves hi + lo of the storage format (a rotated bf16 key is not a bf16
-//                 number; the split keeps ~16 mantissa bits for bf16, ~22 for IEEE half), value rows transposed per tile of 32 slots so that
-//                 the slot index is the contiguous one (the contraction index of P.V);
+//                 number; the split keeps ~16 mantissa bits for bf16, ~22 for IEEE half), value
+//                 rows transposed per tile of 32 slots so that the slot index is the contiguous
+//                 one (the contraction index of P.V);
 //   qprep_shared  query rows rotary-encoded at their own slot, pre-scaled by
 //                 softmax_scale * log2(e), split hi + lo;
 //

@@ -241,15 +241,21 @@ __global__ __launch_bounds__(kVoteThreads) void head_topk_mfma_kernel(MfmaScanAr
   const char* kbase = (const char*)a.k + ((int64_t)h * a.ksh + (a.first_tok + blk_row0) * a.kst) * 2 + col * 16;
   u32x4* my = (u32x4*)mfma_lds + wave * (T * 256);     // this wave's T tiles of 16 rows x 16 pieces
 
-  for (int t = wave * (T * 16); t < nrows; t += kVoteWaves * (T * 16)) {
-    // global -> registers: 1 KiB of consecutive memory per load (lane l: row l/16, piece l%16)
-    u32x4 d[4 * T];
+  // global -> registers: 1 KiB of consecutive memory per load (lane l: row l/16, piece l%16); the loads
+  // of the next iteration are in flight while this one is contracted and sifted
+  auto request = [&](int t, u32x4* d) {
 #pragma unroll
     for (int u = 0; u < 4 * T; ++u) {
       int r = t + u * 4 + kq;
       r = r < nrows ? r : nrows - 1;                   // tail rows re-read the last row; result dropped
       d[u] = __builtin_nontemporal_load((const u32x4*)(kbase + (int64_t)r * row_bytes));
     }
+  };
+  u32x4 d[4 * T], dn[4 * T];
+  if (wave * (T * 16) < nrows) request(wave * (T * 16), d);
+  for (int t = wave * (T * 16); t < nrows; t += kVoteWaves * (T * 16)) {
+    const int t_next = t + kVoteWaves * (T * 16);
+    if (t_next < nrows) request(t_next, dn);
     // registers -> wave-private LDS, piece index XOR row so that both sides are conflict free
 #pragma unroll
     for (int u = 0; u < 4 * T; ++u) {
@@ -287,6 +293,8 @@ __global__ __launch_bounds__(kVoteThreads) void head_topk_mfma_kernel(MfmaScanAr
         }
       }
     }
+#pragma unroll
+    for (int u = 0; u < 4 * T; ++u) d[u] = dn[u];
   }
 
   // the four lanes of a column merge their lists: KT rounds of arg-max over lanes l, l^16, l^32, l^48

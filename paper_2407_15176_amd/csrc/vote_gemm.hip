@@ -33,8 +33,8 @@ constexpr int kPitch = 272;                     // bytes per staged key row (256
 constexpr int kThreads = 512;                   // 8 waves: 2 pairs of key blocks x 4 column quarters
 constexpr int kTileCols = 256;                  // columns per workgroup
 constexpr int kTileBytes = kTileKeys * kPitch;
-constexpr int kStageNS = 2048 / kThreads;
-constexpr int kFloorEvery = 32;                 // tiles between refreshes of the columns' shared floors (power of two)       // 16-byte pieces of a key tile per thread
+constexpr int kStageNS = 2048 / kThreads;       // 16-byte pieces of a key tile per thread
+constexpr int kFloorEvery = 32;                 // tiles between refreshes of the columns' shared floors (power of two)
 
 struct VoteGemmArgs {
   const uint16_t* k;        // key cache (bf16 bits)
