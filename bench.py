@@ -49,6 +49,8 @@ def main() -> int:
     ap.add_argument("--only-batched", action="store_true",
                     help="run the fp16 batched-decode leg alone (context / batch pairs of the paper's throughput table)")
     ap.add_argument("--no-batched", action="store_true", help="skip the fp16 batched-decode leg")
+    ap.add_argument("--only-token", action="store_true", help="run the 32-layer decode-token leg alone")
+    ap.add_argument("--no-token", action="store_true", help="skip the 32-layer decode-token leg")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy 3 times (a known-size kernel against "
                          "which rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings are scaled)")
@@ -68,6 +70,9 @@ def main() -> int:
     torch.cuda.set_device(0)
     if args.only_prefill:
         print(json.dumps({"prefill": prefill_leg(min(args.steps, 5))}), flush=True)
+        return 0
+    if args.only_token:
+        print(json.dumps({"decode_token_32_layers": decode_token_leg(min(args.steps, 10))}), flush=True)
         return 0
     if args.only_batched:
         print(json.dumps({"batched_decode_f16": batched_decode_leg(args.steps)}), flush=True)
@@ -178,6 +183,9 @@ def main() -> int:
         if not args.no_batched:
             torch.cuda.empty_cache()
             result["batched_decode_f16"] = batched_decode_leg(args.steps)
+        if not args.no_token:
+            torch.cuda.empty_cache()
+            result["decode_token_32_layers"] = decode_token_leg(min(args.steps, 10))
         t = None
     if not args.no_cpu_baseline:
         if t is None:
@@ -365,6 +373,46 @@ def batched_decode_leg(steps: int) -> dict:
         del ks, vs
         torch.cuda.empty_cache()
     return {"workload": "llama3-8b layer shape, fp16 storage, sink 4, local 4096", "pairs": rows}
+
+
+def decode_token_leg(steps: int, n_layers: int = 32) -> dict:
+    """One decode token through 32 layers (the layer loop of the appendix's decoding phase without the
+    projections and feed-forward blocks): per layer, append the token's key / value rows, then the decode
+    step.  Llama-3.1-8B shape, bf16; contexts chosen so that 32 caches fit beside each other."""
+    import torch
+    from dataclasses import replace
+    from paper_2407_15176_amd import binding as B
+    from paper_2407_15176_amd import workloads as wl
+    rows = []
+    for n_ctx in (32768, 131072, 524288):
+        w = wl.CONFIGS[2].scaled(n_ctx=n_ctx, n_needles=0, top_k=4096)
+        cap = n_ctx + 64
+        g = torch.Generator(device="cuda").manual_seed(240715000 + 77)
+        kcs = [torch.randn(8, cap, 128, generator=g, device="cuda").bfloat16() for _ in range(n_layers)]
+        vcs = [torch.randn(8, cap, 128, generator=g, device="cuda").bfloat16() for _ in range(n_layers)]
+        qs = [torch.randn(1, 32, 128, generator=g, device="cuda").bfloat16() for _ in range(n_layers)]
+        kn = [torch.randn(1, 8, 128, generator=g, device="cuda").bfloat16() for _ in range(n_layers)]
+        vn = [torch.randn(1, 8, 128, generator=g, device="cuda").bfloat16() for _ in range(n_layers)]
+        outs = [torch.empty(1, 32, 128, dtype=torch.float32, device="cuda") for _ in range(n_layers)]
+        row = {"n_ctx": n_ctx, "n_layers": n_layers}
+        for name, vote in (("topk_4096", None), ("vote_4_127_32", B.Vote(4, 127, 32))):
+            p = B.Params.from_workload(w.scaled(top_k=0, max_position=0) if vote else w)
+            p = replace(p, k_stride_head=cap * 128, k_stride_tok=128, v_stride_head=cap * 128, v_stride_tok=128)
+            ws = B.alloc_vote_workspace(p, vote) if vote else B.alloc_workspace(p)
+            for _ in range(2):
+                B.decode_token(p, qs, kn, vn, kcs, vcs, ws, outs=outs, vote=vote)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(steps):
+                B.decode_token(p, qs, kn, vn, kcs, vcs, ws, outs=outs, vote=vote)
+            torch.cuda.synchronize()
+            ms = (time.perf_counter() - t0) * 1e3 / steps
+            row[name] = {"ms_per_token": round(ms, 3), "tokens_per_s": round(1e3 / ms, 1),
+                         "kv_scan_GBps": round(n_layers * w.scan_bytes / (ms * 1e-3) / 1e9, 1)}
+        rows.append(row)
+        del kcs, vcs
+        torch.cuda.empty_cache()
+    return {"workload": "llama3.1-8b shape, 32 layers' attention path per token, bf16, sink 4, local 4096", "contexts": rows}
 
 
 def vote_leg(t: dict, cfg: int, steps: int, warmup: int) -> dict:

@@ -216,6 +216,18 @@ int reattn_prefill_sequence(const reattn_params* p, const reattn_vote* v, int32_
                             float* out, int32_t* idx_out, int32_t* sel_out, int32_t* n_sel_out,
                             void* ws, size_t ws_bytes, void* stream);
 
+/* One decode token through n_layers layers (appendix, decoding phase: the loop over the layers, without
+ * the projections and the feed-forward blocks that separate them in a model): for layer l the token's rows
+ * k_new[l], v_new[l] ([Hkv][D]) are appended at position N - 1 of that layer's cache (p->n_ctx = N counts
+ * the new token; the strides describe every layer's cache), then the layer's decode step runs with q[l]
+ * ([Hq][D]) into out[l] ([Hq][D] fp32).  q, k_new, v_new, k_cache, v_cache, out are HOST arrays of
+ * n_layers DEVICE pointers.  v == NULL: per-KV-head top-k (reattn_decode_step); else the vote selection.
+ * One workspace (reattn_workspace_bytes / reattn_vote_workspace_bytes for M = 1) serves all layers. */
+int reattn_decode_token(const reattn_params* p, const reattn_vote* v, int32_t n_layers,
+                        const void* const* q, const void* const* k_new, const void* const* v_new,
+                        void* const* k_cache, void* const* v_cache, float* const* out,
+                        void* ws, size_t ws_bytes, void* stream);
+
 /* Measurement aid: reattn_decode_step with HIP events recorded on `stream` at the
  * stage boundaries; it WAITS for the step to finish and fills the HOST array
  * stage_ms[REATTN_N_STAGES] with the elapsed milliseconds of

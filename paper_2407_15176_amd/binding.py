@@ -31,7 +31,7 @@ EXPORTS = [
     "reattn_probe_read_bandwidth", "reattn_prefill_chunk_timed",
     "reattn_vote_workspace_bytes", "reattn_vote_topk", "reattn_vote_merge", "reattn_vote_layer",
     "reattn_vote_layer_timed", "reattn_cache_append", "reattn_prefill_sequence_chunks",
-    "reattn_prefill_sequence_workspace_bytes", "reattn_prefill_sequence",
+    "reattn_prefill_sequence_workspace_bytes", "reattn_prefill_sequence", "reattn_decode_token",
 ]
 PREFILL_STAGES = ("sample_threshold", "score_gemm_filter", "candidate_topk", "attend")
 STAGES = ("prep", "scan", "topk", "attend")
@@ -102,6 +102,7 @@ def lib() -> C.CDLL:
         L.reattn_prefill_sequence_chunks.restype = C.c_int64
         L.reattn_prefill_sequence_workspace_bytes.argtypes = [PP, PV, C.c_int32]
         L.reattn_prefill_sequence_workspace_bytes.restype = C.c_size_t
+        L.reattn_decode_token.argtypes = [PP, PV, C.c_int32] + [C.POINTER(C.c_void_p)] * 6 + [P, C.c_size_t, P]
         L.reattn_prefill_sequence.argtypes = [PP, PV, C.c_int32, P, P, P, P, P, P, P, P, P, P, C.c_size_t, P]
         _lib = L
     return _lib
@@ -462,3 +463,24 @@ def prefill_sequence(p: Params, chunk: int, q, k_new, v_new, k_cache=None, v_cac
     if sel_all is not None:
         res["sel"], res["n_sel"] = sel_all, n_sel_all
     return res
+
+
+# ---- one decode token through all layers -------------------------------------------------------
+def decode_token(p: Params, qs, k_news, v_news, k_caches, v_caches, ws, outs=None, vote: Vote | None = None):
+    """qs[l] [1,Hq,D]; k_news[l], v_news[l] [1,Hkv,D] (or [Hkv,D]); caches [Hkv,cap,D] with p's strides.
+    p.n_ctx counts the new token.  Returns outs (list of [1,Hq,D] fp32)."""
+    n = len(qs)
+    if outs is None:
+        outs = [torch.empty(1, p.n_q_heads, p.head_dim, dtype=torch.float32, device=qs[0].device) for _ in range(n)]
+    dt = p.torch_dtype()
+
+    def arr(ts, name, dtype):
+        return (C.c_void_p * n)(*[_dev(t, name, dtype).value for t in ts])
+    cp = p.c()
+    cv = vote.c() if vote is not None else None
+    _check(lib().reattn_decode_token(C.byref(cp), C.byref(cv) if cv is not None else None, n,
+                                     arr(qs, "q", dt), arr(k_news, "k_new", dt), arr(v_news, "v_new", dt),
+                                     arr(k_caches, "k_cache", dt), arr(v_caches, "v_cache", dt),
+                                     arr(outs, "out", torch.float32), _dev(ws, "ws"), ws.numel(), _stream()),
+           "reattn_decode_token")
+    return outs

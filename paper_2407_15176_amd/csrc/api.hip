@@ -201,7 +201,7 @@ int fused_prefill_select(const Plan& pl, const Ws& w, char* ws, const void* q, c
 
 int run_layer(const reattn_params* p, bool decode_only, const void* q, const void* k_cache,
               const void* v_cache, int32_t* idx_out, float* out, void* ws, size_t ws_bytes,
-              void* stream, hipEvent_t* ev = nullptr) {
+              void* stream, hipEvent_t* ev = nullptr, bool rope_ready = false) {
   Plan pl;
   int rc = make_plan(p, &pl);
   if (rc) return rc;
@@ -224,7 +224,7 @@ int run_layer(const reattn_params* p, bool decode_only, const void* q, const voi
   }
   for (int q0 = 0; q0 < pl.M; q0 += pl.m_tile) {
     const int nq = pl.M - q0 < pl.m_tile ? pl.M - q0 : pl.m_tile;
-    rc = select_tile(pl, w, q, q0, nq, k_cache, idx, q0 == 0, ev, st);
+    rc = select_tile(pl, w, q, q0, nq, k_cache, idx, q0 == 0 && !rope_ready, ev, st);
     if (rc) return rc;
   }
   rc = attend_cache(pl, w, (char*)ws, q, k_cache, v_cache, idx, out, st);
@@ -483,7 +483,7 @@ extern "C" int reattn_vote_merge(const reattn_params* p, const reattn_vote* v, c
 
 static int vote_layer_impl(const reattn_params* p, const reattn_vote* v, const void* q, const void* k_cache,
                            const void* v_cache, int32_t* sel_out, int32_t* n_sel_out, float* out, void* ws,
-                           size_t ws_bytes, void* stream, hipEvent_t* ev) {
+                           size_t ws_bytes, void* stream, hipEvent_t* ev, bool rope_ready = false) {
   VotePlan vp;
   int rc = make_vote_plan(p, v, &vp);
   if (rc) return rc;
@@ -504,7 +504,7 @@ static int vote_layer_impl(const reattn_params* p, const reattn_vote* v, const v
   mark(ev, 2, st);
   if (rc) return rc;
   float2* rope = (float2*)(b + vp.off_rope);
-  rc = hip_rc(launch_prep(pl, 0, nullptr, rope, st));
+  if (!rope_ready) rc = hip_rc(launch_prep(pl, 0, nullptr, rope, st));
   if (rc) return rc;
   // one shared index row for every (query, KV head); its length is read on the device
   if (attend_shared_applies(pl))       // a chunk on bf16 / D = 128: packed once, flash attention on the matrix cores
@@ -691,6 +691,43 @@ extern "C" int reattn_prefill_sequence(const reattn_params* p, const reattn_vote
     if (rc) return rc;
   }
   return REATTN_OK;
+}
+
+// ---- one decode token through all layers ----------------------------------------------------
+extern "C" int reattn_decode_token(const reattn_params* p, const reattn_vote* v, int32_t n_layers,
+                                   const void* const* q, const void* const* k_new, const void* const* v_new,
+                                   void* const* k_cache, void* const* v_cache, float* const* out,
+                                   void* ws, size_t ws_bytes, void* stream) {
+  if (!p) return REATTN_ERR_NULL;
+  if (n_layers < 1) return REATTN_ERR_RANGE;
+  if (!q || !k_new || !v_new || !k_cache || !v_cache || !out) return REATTN_ERR_NULL;
+  reattn_params pp = *p;
+  pp.n_query = 1;
+  Plan pl;
+  int rc = make_plan(&pp, &pl);
+  if (rc) return rc;
+  if (v) {
+    VotePlan vp;
+    rc = make_vote_plan(&pp, v, &vp);
+    if (rc) return rc;
+    if (!ws || ws_bytes < vp.total) return REATTN_ERR_WORKSPACE;
+  } else if (!ws || ws_bytes < pl.total) {
+    return REATTN_ERR_WORKSPACE;
+  }
+  for (int l = 0; l < n_layers; ++l) {                  // every pointer is checked before anything is launched
+    if (!q[l] || !k_new[l] || !v_new[l] || !k_cache[l] || !v_cache[l] || !out[l]) return REATTN_ERR_NULL;
+    if (!aligned16(q[l]) || !aligned16(k_new[l]) || !aligned16(v_new[l]) || !aligned16(k_cache[l]) ||
+        !aligned16(v_cache[l]) || !aligned16(out[l]))
+      return REATTN_ERR_ALIGN;
+  }
+  for (int l = 0; l < n_layers && !rc; ++l) {
+    rc = hip_rc(launch_cache_append(pl, pl.N - 1, 1, k_new[l], v_new[l], k_cache[l], v_cache[l], (hipStream_t)stream));
+    if (rc) break;
+    // the rotary table depends on the scope's upper bound alone: the first layer's serves them all
+    rc = v ? vote_layer_impl(&pp, v, q[l], k_cache[l], v_cache[l], nullptr, nullptr, out[l], ws, ws_bytes, stream, nullptr, l > 0)
+           : run_layer(&pp, true, q[l], k_cache[l], v_cache[l], nullptr, out[l], ws, ws_bytes, stream, nullptr, l > 0);
+  }
+  return rc;
 }
 
 static int layer_timed(const reattn_params* p, bool decode_only, const void* q, const void* k_cache,

@@ -387,8 +387,8 @@ struct SpanArgs {
   int32_t* sel; int32_t* n_sel;
 };
 
-template <bool MAX>
-__device__ __forceinline__ int32_t block_scan_i32(int32_t v, int32_t* wsum) {   // inclusive, 1024 threads
+template <bool MAX, int NT>
+__device__ __forceinline__ int32_t block_scan_i32(int32_t v, int32_t* wsum) {   // inclusive, NT threads
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   int32_t x = v;
 #pragma unroll
@@ -400,7 +400,7 @@ __device__ __forceinline__ int32_t block_scan_i32(int32_t v, int32_t* wsum) {   
   __syncthreads();
   int32_t base = 0;
 #pragma unroll
-  for (int w = 0; w < kMergeThreads / 64; ++w) {
+  for (int w = 0; w < NT / 64; ++w) {
     const int32_t s = wsum[w];
     if (w < wave) base = MAX ? (base > s ? base : s) : base + s;
   }
@@ -408,9 +408,10 @@ __device__ __forceinline__ int32_t block_scan_i32(int32_t v, int32_t* wsum) {   
   return MAX ? (x > base ? x : base) : x + base;
 }
 
-// win[0 .. nc): the centres (distinct tokens relative to the middle, any order), nc <= 1024.
+// win[0 .. nc): the centres (distinct tokens relative to the middle, any order), nc <= NT.
 // Sorts them, clips each span to the middle, unions overlapping spans (a span can only
 // overlap spans of earlier centres once they ascend) and writes the ascending index list.
+template <int NT>
 __device__ __forceinline__ void centres_to_spans(int32_t* win, int nc, int32_t* sa, int32_t* sb,
                                                  int32_t* wsum, const SpanArgs& a) {
   const int i = threadIdx.x;
@@ -428,19 +429,19 @@ __device__ __forceinline__ void centres_to_spans(int32_t* win, int nc, int32_t* 
     hi = (int32_t)(h64 > a.n_mid ? a.n_mid : h64);
   }
   __syncthreads();
-  const int32_t hmax = block_scan_i32<true>(hi, wsum);           // inclusive prefix maximum of hi
+  const int32_t hmax = block_scan_i32<true, NT>(hi, wsum);           // inclusive prefix maximum of hi
   sb[i] = hmax;
   __syncthreads();
   const int32_t before = i > 0 ? sb[i - 1] : 0;
   const int32_t start = lo > before ? lo : before;
   const int32_t len = hi > start ? hi - start : 0;
   __syncthreads();
-  const int32_t end_at = block_scan_i32<false>(len, wsum);       // inclusive prefix sum of lengths
+  const int32_t end_at = block_scan_i32<false, NT>(len, wsum);       // inclusive prefix sum of lengths
   sa[i] = end_at; sb[i] = start - (end_at - len);                // output slot o of centre i holds sb[i] + o
   __syncthreads();
-  const int32_t total = sa[kMergeThreads - 1];
-  for (int32_t o = i; o < total; o += kMergeThreads) {
-    int l = 0, h = kMergeThreads - 1;                  // first centre whose inclusive end exceeds o
+  const int32_t total = sa[NT - 1];
+  for (int32_t o = i; o < total; o += NT) {
+    int l = 0, h = NT - 1;                  // first centre whose inclusive end exceeds o
     while (l < h) {
       const int mid = (l + h) >> 1;
       if (sa[mid] > o) h = mid; else l = mid + 1;
@@ -450,12 +451,13 @@ __device__ __forceinline__ void centres_to_spans(int32_t* win, int nc, int32_t* 
   if (i == 0) *a.n_sel = total;
 }
 
-// Up to 1024 votes (a decode step: Hq * vote_k): everything in one workgroup, no vote array.
-__global__ __launch_bounds__(kMergeThreads) void vote_merge_small_kernel(const int32_t* __restrict__ lists,
-                                                                         int n_votes, SpanArgs a) {
-  __shared__ int32_t tok[kMergeThreads], win[kMergeThreads], sa[kMergeThreads], sb[kMergeThreads];
-  __shared__ uint64_t comp[kMergeThreads];
-  __shared__ int32_t wsum[kMergeThreads / 64];
+// Up to NT votes and centres (a decode step: Hq * vote_k votes): everything in one workgroup, no vote array.
+template <int NT>
+__global__ __launch_bounds__(NT) void vote_merge_small_kernel(const int32_t* __restrict__ lists, int n_votes,
+                                                              SpanArgs a) {
+  __shared__ int32_t tok[NT], win[NT], sa[NT], sb[NT];
+  __shared__ uint64_t comp[NT];
+  __shared__ int32_t wsum[NT / 64];
   const int t = threadIdx.x;
   int32_t v = t < n_votes ? lists[t] - a.s_eff : -1;
   if (v < 0 || v >= a.n_mid) v = -1;                   // an entry outside the middle is no vote
@@ -479,7 +481,7 @@ __global__ __launch_bounds__(kMergeThreads) void vote_merge_small_kernel(const i
   const int n_owner = __syncthreads_count(owner);
   if (owner && rank < a.kc) win[rank] = v;             // composites are distinct: ranks are a permutation
   __syncthreads();
-  centres_to_spans(win, n_owner < a.kc ? n_owner : a.kc, sa, sb, wsum, a);
+  centres_to_spans<NT>(win, n_owner < a.kc ? n_owner : a.kc, sa, sb, wsum, a);
 }
 
 // More votes than one workgroup ranks by comparison: a dense vote array over the middle.
@@ -628,7 +630,7 @@ __global__ __launch_bounds__(kMergeThreads) void vote_pick_kernel(const uint64_t
       }
     }
     __syncthreads();
-    centres_to_spans(win, (int)n_win, sa, sb, wsum, a);
+    centres_to_spans<kMergeThreads>(win, (int)n_win, sa, sb, wsum, a);
     return;
   }
 
@@ -665,7 +667,7 @@ __global__ __launch_bounds__(kMergeThreads) void vote_pick_kernel(const uint64_t
     if (c && (c >> shift) >= prefix) win[atomicAdd(&n_win, 1u)] = (int32_t)(0xffffffffu - (uint32_t)c);
   }
   __syncthreads();
-  centres_to_spans(win, (int)n_win, sa, sb, wsum, a);
+  centres_to_spans<kMergeThreads>(win, (int)n_win, sa, sb, wsum, a);
 }
 
 template <typename T, int D, int KT>
@@ -805,7 +807,11 @@ hipError_t launch_vote_merge(const Plan& pl, const int32_t* lists, int64_t n_row
   SpanArgs a;
   a.s_eff = (int32_t)pl.s_eff; a.n_mid = pl.n_mid; a.kc = kc; a.span = span; a.sel = sel; a.n_sel = n_sel;
   if (n_votes <= kMergeThreads) {
-    hipLaunchKernelGGL(vote_merge_small_kernel, dim3(1), dim3(kMergeThreads), 0, st, lists, (int)n_votes, a);
+    if (n_votes <= 256 && kc <= 256)                   // a decode step: fewer waves, cheaper barriers
+      hipLaunchKernelGGL(vote_merge_small_kernel<256>, dim3(1), dim3(256), 0, st, lists, (int)n_votes, a);
+    else
+      hipLaunchKernelGGL(vote_merge_small_kernel<kMergeThreads>, dim3(1), dim3(kMergeThreads), 0, st, lists,
+                         (int)n_votes, a);
     return hipGetLastError();
   }
   static bool lds_ok = false;

@@ -120,6 +120,12 @@ def test_sequence_loop_is_planned_on_the_host():
                                      fake, 1 << 40, None) == B.ERR_RANGE
     assert L.reattn_prefill_sequence(C.byref(cp), None, 128, fake, fake, fake, fake, fake, fake, None, None, None,
                                      fake, 16, None) == B.ERR_WORKSPACE
+    ptrs = (C.c_void_p * 2)(0x1000, 0x2000)
+    holes = (C.c_void_p * 2)(0x1000, None)
+    need1 = B.workspace_bytes(p)
+    assert L.reattn_decode_token(C.byref(cp), None, 2, ptrs, ptrs, ptrs, ptrs, ptrs, holes, fake, need1, None) == B.ERR_NULL
+    assert L.reattn_decode_token(C.byref(cp), None, 0, ptrs, ptrs, ptrs, ptrs, ptrs, ptrs, fake, need1, None) == B.ERR_RANGE
+    assert L.reattn_decode_token(C.byref(cp), None, 2, ptrs, ptrs, ptrs, ptrs, ptrs, ptrs, fake, 16, None) == B.ERR_WORKSPACE
     assert L.reattn_cache_append(C.byref(cp), 9_990, 11, fake, fake, fake, fake, None) == B.ERR_RANGE
     assert L.reattn_cache_append(C.byref(cp), 9_990, 10, fake, None, fake, fake, None) == B.ERR_NULL
 

@@ -122,3 +122,44 @@ def test_cache_append_strided_cache():
     assert not kc[:, :700].any() and not kc[:, 1000:].any()
     with pytest.raises(B.ReattnError):
         B.cache_append(p, 701, k_new, v_new, kc, vc)          # would run past n_ctx
+
+
+# --------------------------------------------------------- decode tokens through several layers
+@pytest.mark.parametrize("mode", ["topk", "vote"])
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+def test_decode_tokens_through_layers(mode, dtype):
+    """Three layers, each with its own cache (room to grow), four decode tokens in a row: every layer's
+    step is the oracle's decode step on that layer's cache as it stands after the append."""
+    n_layers, n0, n_tok, cap = 3, 5_000, 4, 5_008
+    base = wl.CONFIGS[2].scaled(dtype=dtype, n_ctx=n0, n_local=200, top_k=0 if mode == "vote" else 120, max_position=0)
+    vote = B.Vote(4, 12, 16) if mode == "vote" else None
+    dt = base.torch_dtype()
+    g = torch.Generator(device="cuda").manual_seed(240715000 + 55)
+    Hq, Hkv, D = base.n_q_heads, base.n_kv_heads, base.head_dim
+    kcs = [torch.zeros(Hkv, cap, D, dtype=dt, device="cuda") for _ in range(n_layers)]
+    vcs = [torch.zeros(Hkv, cap, D, dtype=dt, device="cuda") for _ in range(n_layers)]
+    for l in range(n_layers):                                   # the prompt's cache
+        kcs[l][:, :n0] = torch.randn(Hkv, n0, D, generator=g, device="cuda").to(dt)
+        vcs[l][:, :n0] = torch.randn(Hkv, n0, D, generator=g, device="cuda").to(dt)
+    for step in range(n_tok):
+        n = n0 + step + 1
+        w = base.scaled(n_ctx=n)
+        p = replace(B.Params.from_workload(w), k_stride_head=cap * D, k_stride_tok=D, v_stride_head=cap * D, v_stride_tok=D)
+        ws = B.alloc_vote_workspace(p, vote) if vote else B.alloc_workspace(p)
+        qs = [torch.randn(1, Hq, D, generator=g, device="cuda").to(dt) for _ in range(n_layers)]
+        kn = [torch.randn(1, Hkv, D, generator=g, device="cuda").to(dt) for _ in range(n_layers)]
+        vn = [torch.randn(1, Hkv, D, generator=g, device="cuda").to(dt) for _ in range(n_layers)]
+        outs = B.decode_token(p, qs, kn, vn, kcs, vcs, ws, vote=vote)
+        torch.cuda.synchronize()
+        sh = P.oracle_shape(w)
+        for l in range(n_layers):
+            assert torch.equal(kcs[l][:, n - 1], kn[l][0]) and torch.equal(vcs[l][:, n - 1], vn[l][0])
+            k = wl.to_numpy_store(kcs[l][:, :n].contiguous()); v = wl.to_numpy_store(vcs[l][:, :n].contiguous())
+            q = wl.to_numpy_store(qs[l])
+            if vote:
+                ref = ro.vote_forward(sh, q, k, v, vote.vote_k, vote.n_centres, vote.span)["out"]
+            else:
+                ref = ro.forward(sh, q, k, v)["out"]
+            err = np.abs(outs[l].cpu().numpy().astype(np.float64) - ref).max()
+            # random keys leave a margin of ~1e-3 relative at the k-th score: a set flip would show as a large error
+            assert err <= P.OUT_TOL[dtype], (step, l, err)
