@@ -422,7 +422,7 @@ def vote_leg(t: dict, cfg: int, steps: int, warmup: int) -> dict:
     import torch
     from paper_2407_15176_amd import binding as B
     from paper_2407_15176_amd import workloads as wl
-    w = wl.CONFIGS[cfg].scaled(top_k=0)
+    w = wl.CONFIGS[cfg].scaled(top_k=0, max_position=0)    # the vote scope is 127 spans of 32, whatever the config's window
     v = B.Vote(4, 127, 32)
     p = B.Params.from_workload(w)
     ws = B.alloc_vote_workspace(p, v)
