@@ -326,7 +326,8 @@ def sequence_leg(seq_len: int, chunk: int, steps: int = 2) -> dict:
 def batched_decode_leg(steps: int) -> dict:
     """Decode steps of one layer at the (context, batch) pairs of the paper's throughput table (Appendix,
     efficiency analysis: LLaMA3-8B, FP16) in fp16 storage.  A batch of equal-length sequences is folded
-    into the head axis (cache [B*Hkv][N][D]): one call serves the whole batch."""
+    into the head axis (cache [B*Hkv][N][D]): one call serves the whole batch (the vote selection pools the
+    votes per sequence: reattn_vote.n_seq)."""
     import torch
     from paper_2407_15176_amd import binding as B
     from paper_2407_15176_amd import workloads as wl
@@ -341,22 +342,16 @@ def batched_decode_leg(steps: int) -> dict:
         row = {"n_ctx": n_ctx, "batch": batch}
         for name, vote in (("topk_4096", None), ("vote_4_127_32", B.Vote(4, 127, 32))):
             p = B.Params.from_workload(w.scaled(top_k=0) if vote else w)
-            ws = B.alloc_vote_workspace(p, vote) if vote else B.alloc_workspace(p)
+            ws = None if vote else B.alloc_workspace(p)
             out = torch.empty(1, w.n_q_heads, 128, dtype=torch.float32, device="cuda")
             if vote:
-                sel = torch.empty(B.vote_cap(p, vote), dtype=torch.int32, device="cuda")
-                n_sel = torch.zeros(1, dtype=torch.int32, device="cuda")
-                # the vote is pooled over ALL heads of the call: a folded batch would share one selection,
-                # so a batch of B sequences is B calls here
-                pb = B.Params.from_workload(w.scaled(top_k=0, n_q_heads=32, n_kv_heads=8))
-                wsb = B.alloc_vote_workspace(pb, vote)
-                ob = torch.empty(1, 32, 128, dtype=torch.float32, device="cuda")
-                qs = [q[:, 32 * b:32 * (b + 1)].contiguous() for b in range(batch)]
+                vb = B.Vote(vote.vote_k, vote.n_centres, vote.span, n_seq=batch)    # votes pooled per sequence
+                ws = B.alloc_vote_workspace(p, vb)
+                sel = torch.empty(batch * B.vote_cap(p, vb), dtype=torch.int32, device="cuda")
+                n_sel = torch.zeros(batch, dtype=torch.int32, device="cuda")
 
                 def step(i):
-                    for b in range(batch):
-                        B.vote_layer(pb, vote, qs[b], ks[i % n_rot][8 * b:8 * (b + 1)],
-                                     vs[i % n_rot][8 * b:8 * (b + 1)], wsb, sel=sel, n_sel=n_sel, out=ob)
+                    B.vote_layer(p, vb, q, ks[i % n_rot], vs[i % n_rot], ws, sel=sel, n_sel=n_sel, out=out)
             else:
                 def step(i):
                     B.decode_step(p, q, ks[i % n_rot], vs[i % n_rot], ws, out=out, want_idx=False)

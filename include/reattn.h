@@ -155,11 +155,17 @@ int reattn_prefill_chunk(const reattn_params* p, const void* q, const void* k_ca
  * min(n_centres * span, N_mid).  In these calls p->top_k is ignored, the scope is
  * S = s_eff + n_sel + l_eff (query i sits at slot s_eff + n_sel + l_eff - M + i) and
  * p->max_position is checked against s_eff + cap + l_eff.
- * Supported: bf16 with D = 128 or fp32 with D = 64, G <= 8, vote_k <= 8, n_centres <= 1024. */
+ * Supported: bf16 / fp16 with D = 128 or fp32 with D = 64, G <= 8, vote_k <= 8, n_centres <= 1024.
+ *
+ * Batches: with n_seq > 1 the head axis holds n_seq equal-length sequences of a decode step (M = 1),
+ * sequence b owning query heads [b * Hq/n_seq, ...) and KV heads [b * Hkv/n_seq, ...) of q / the caches;
+ * votes are pooled per sequence, sel is [n_seq][cap] and n_sel [n_seq] (cap = min(n_centres * span,
+ * N_mid)), and every sequence attends over its own selection.  Hq/n_seq * vote_k <= 1024. */
 typedef struct reattn_vote {
   int32_t vote_k;     /* k: entries per (query row, head) list, 1..8; clamped to N_mid */
   int32_t n_centres;  /* k': 1..1024 */
   int32_t span;       /* m >= 1 */
+  int32_t n_seq;      /* sequences folded into the head axis; 0 or 1 = one */
 } reattn_vote;
 
 /* Bytes of device scratch the vote calls accept for (p, v); 0 if either is invalid. */

@@ -51,7 +51,7 @@ class CParams(C.Structure):
 
 
 class CVote(C.Structure):
-    _fields_ = [("vote_k", C.c_int32), ("n_centres", C.c_int32), ("span", C.c_int32)]
+    _fields_ = [("vote_k", C.c_int32), ("n_centres", C.c_int32), ("span", C.c_int32), ("n_seq", C.c_int32)]
 
 
 class ReattnError(RuntimeError):
@@ -315,9 +315,10 @@ class Vote:
     vote_k: int = 4
     n_centres: int = 127
     span: int = 32
+    n_seq: int = 1          # equal-length sequences folded into the head axis (decode only)
 
     def c(self) -> CVote:
-        return CVote(self.vote_k, self.n_centres, self.span)
+        return CVote(self.vote_k, self.n_centres, self.span, self.n_seq)
 
 
 def vote_workspace_bytes(p: Params, v: Vote) -> int:
@@ -353,9 +354,9 @@ def vote_topk(p: Params, v: Vote, q, k_cache, ws, head_topk=None):
 
 def vote_merge(p: Params, v: Vote, head_topk, ws, sel=None, n_sel=None):
     if sel is None:
-        sel = torch.empty(max(vote_cap(p, v), 1), dtype=torch.int32, device=head_topk.device)
+        sel = torch.empty(max(v.n_seq, 1) * max(vote_cap(p, v), 1), dtype=torch.int32, device=head_topk.device)
     if n_sel is None:
-        n_sel = torch.zeros(1, dtype=torch.int32, device=head_topk.device)
+        n_sel = torch.zeros(max(v.n_seq, 1), dtype=torch.int32, device=head_topk.device)
     cp, cv = p.c(), v.c()
     _check(lib().reattn_vote_merge(C.byref(cp), C.byref(cv), _dev(head_topk, "head_topk", torch.int32),
                                    _dev(sel, "sel", torch.int32), _dev(n_sel, "n_sel", torch.int32),
@@ -367,9 +368,9 @@ def vote_layer(p: Params, v: Vote, q, k_cache, v_cache, ws, sel=None, n_sel=None
     if out is None:
         out = torch.empty(p.n_query, p.n_q_heads, p.head_dim, dtype=torch.float32, device=q.device)
     if want_sel and sel is None:
-        sel = torch.empty(max(vote_cap(p, v), 1), dtype=torch.int32, device=q.device)
+        sel = torch.empty(max(v.n_seq, 1) * max(vote_cap(p, v), 1), dtype=torch.int32, device=q.device)
     if want_sel and n_sel is None:
-        n_sel = torch.zeros(1, dtype=torch.int32, device=q.device)
+        n_sel = torch.zeros(max(v.n_seq, 1), dtype=torch.int32, device=q.device)
     cp, cv = p.c(), v.c()
     _check(lib().reattn_vote_layer(C.byref(cp), C.byref(cv), _dev(q, "q", p.torch_dtype()),
                                    _dev(k_cache, "k_cache", p.torch_dtype()),

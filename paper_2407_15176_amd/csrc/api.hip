@@ -369,6 +369,7 @@ namespace {
 struct VotePlan {
   Plan pl;                 // base plan with k_eff = cap (largest selection)
   int kk, kc, span;        // votes per list, centres, span (all clamped)
+  int n_seq;               // sequences folded into the head axis
   size_t off_rope, off_apart, off_part, off_lists, off_counts, off_seg, off_comp, off_sel, off_nsel, off_kp, off_vp,
          off_qp, off_spart, total;
 };
@@ -392,6 +393,13 @@ int make_vote_plan(const reattn_params* p, const reattn_vote* v, VotePlan* out) 
     vp.span = (int)(v->span < widest ? v->span : (widest < 0x7fffffffLL ? widest : 0x7fffffffLL));
   }
   if (pl.n_mid > 0 && !vote_scan_applies(pl)) return REATTN_ERR_SHAPE;
+  vp.n_seq = v->n_seq > 1 ? v->n_seq : 1;
+  if (v->n_seq < 0) return REATTN_ERR_RANGE;
+  if (vp.n_seq > 1) {
+    if (pl.M != 1) return REATTN_ERR_RANGE;            // a folded batch is a decode step
+    if (pl.Hq % vp.n_seq || pl.Hkv % vp.n_seq) return REATTN_ERR_SHAPE;
+    if ((int64_t)(pl.Hq / vp.n_seq) * vp.kk > 1024) return REATTN_ERR_SHAPE;
+  }
   const int per = pl.n_mid > 0 ? vote_queries_per_launch(pl, vp.kk > 0 ? vp.kk : 1) : 1;
   // own layout: of the group-sum path's scratch only the rotary table and (for the flash-decoding
   // kernel) the split-S partials are needed here
@@ -411,8 +419,8 @@ int make_vote_plan(const reattn_params* p, const reattn_vote* v, VotePlan* out) 
   vp.off_counts = off;  off += up(cb);
   vp.off_seg = off;     off += up(sb);
   vp.off_comp = off;    off += up(mb);
-  vp.off_sel = off;     off += up((size_t)(pl.k_eff > 0 ? pl.k_eff : 1) * 4);
-  vp.off_nsel = off;    off += up(4);
+  vp.off_sel = off;     off += up((size_t)vp.n_seq * (pl.k_eff > 0 ? pl.k_eff : 1) * 4);
+  vp.off_nsel = off;    off += up((size_t)vp.n_seq * 4);
   size_t kpb = 0, vpb = 0, qpb = 0, spb = 0;
   if (attend_shared_applies(pl)) attend_shared_layout(pl, &kpb, &vpb, &qpb, &spb);
   vp.off_kp = off;      off += up(kpb);
@@ -444,10 +452,11 @@ int vote_merge_impl(const VotePlan& vp, const int32_t* head_topk, int32_t* sel, 
                     char* ws, hipStream_t st) {
   const Plan& pl = vp.pl;
   if (vp.kk == 0 || vp.kc == 0)                        // empty middle: nothing can be selected
-    return hip_rc(launch_fill_u32((uint32_t*)n_sel, 1, 0u, st));
+    return hip_rc(launch_fill_u32((uint32_t*)n_sel, vp.n_seq, 0u, st));
   return hip_rc(launch_vote_merge(pl, head_topk, (int64_t)pl.M * pl.Hq, vp.kk, vp.kc, vp.span,
                                   (uint32_t*)(ws + vp.off_counts), (int32_t*)(ws + vp.off_seg),
-                                  (uint64_t*)(ws + vp.off_comp), sel, n_sel, st));
+                                  (uint64_t*)(ws + vp.off_comp), sel, n_sel, st, vp.n_seq,
+                                  pl.k_eff > 0 ? pl.k_eff : 1));
 }
 }  // namespace
 
@@ -512,7 +521,8 @@ static int vote_layer_impl(const reattn_params* p, const reattn_vote* v, const v
                                      b + vp.off_qp, (float*)(b + vp.off_spart), out, st));
   else
     rc = hip_rc(launch_attend(pl, true, q, 0, pl.M, k_cache, v_cache, sel, rope, (float*)(b + vp.off_apart), out,
-                              st, n_sel, 0));
+                              st, n_sel, vp.n_seq > 1 ? (pl.k_eff > 0 ? pl.k_eff : 1) : 0,
+                              vp.n_seq > 1 ? pl.Hkv / vp.n_seq : 0));
   mark(ev, 3, st);
   return rc;
 }

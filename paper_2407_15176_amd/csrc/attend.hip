@@ -28,6 +28,7 @@ struct AttendArgs {
   const int32_t* idx; const float2* rope;
   const int32_t* k_dyn;      // device scalar: number of selected entries, or nullptr for the static k_eff
   int64_t idx_stride;        // elements between the index rows of consecutive (query, KV head) pairs; 0 = one shared row
+  int seq_heads;             // > 0: KV heads [b * seq_heads, (b + 1) * seq_heads) share index row b and length k_dyn[b]
   float* part; float* out;
   int64_t ksh, kst, vsh, vst, N;
   int Hq, Hkv, G, M, S, s_eff, k_eff, l_eff;
@@ -92,7 +93,8 @@ __global__ __launch_bounds__(256) void attend_kernel(AttendArgs a) {
   const int qn = blockIdx.z, qi = a.q_first + qn;
   // a.S / a.k_eff are the largest scope the launch was shaped for (table layout, split geometry);
   // the scope actually attended to may be shorter when the selection length is data dependent
-  const int k_eff = (FUSED && a.k_dyn) ? *a.k_dyn : a.k_eff;
+  const int seq = a.seq_heads > 0 ? h / a.seq_heads : 0;
+  const int k_eff = (FUSED && a.k_dyn) ? a.k_dyn[seq] : a.k_eff;
   const int S = a.s_eff + k_eff + a.l_eff;
   const int visible = S - (a.M - 1 - qi);           // slots this query may see; its own key is the last
   const int c0 = sub * E;
@@ -142,7 +144,7 @@ __global__ __launch_bounds__(256) void attend_kernel(AttendArgs a) {
   const int r0 = split * a.split_len;
   const int r_end = (r0 + a.split_len < visible) ? r0 + a.split_len : visible;
   const int64_t row_kv = (int64_t)qi * a.Hkv + h;
-  const int32_t* my_idx = FUSED ? a.idx + row_kv * a.idx_stride : nullptr;
+  const int32_t* my_idx = FUSED ? a.idx + (a.seq_heads > 0 ? (int64_t)seq : row_kv) * a.idx_stride : nullptr;
 
   // slot -> cache row: lane `sub` resolves the group's slot number `sub` of every batch of
   // 16 slots up front, so the index load is off the critical path of the row loads
@@ -332,11 +334,11 @@ void launch_td(const Plan& pl, const AttendArgs& a, dim3 grid, hipStream_t st) {
 hipError_t launch_attend(const Plan& pl, bool fused, const void* q, int q_first, int n_query,
                          const void* k_src, const void* v_src, const int32_t* idx,
                          const float2* rope, float* part, float* out, hipStream_t st,
-                         const int32_t* k_dyn, int64_t idx_stride) {
+                         const int32_t* k_dyn, int64_t idx_stride, int seq_heads) {
   if (n_query <= 0) return hipSuccess;
   AttendArgs a;
   a.q = q; a.k = k_src; a.v = v_src; a.idx = idx; a.rope = rope; a.part = part; a.out = out;
-  a.k_dyn = k_dyn; a.idx_stride = idx_stride < 0 ? pl.k_eff : idx_stride;
+  a.k_dyn = k_dyn; a.idx_stride = idx_stride < 0 ? pl.k_eff : idx_stride; a.seq_heads = seq_heads;
   a.ksh = pl.ksh; a.kst = pl.kst; a.vsh = pl.vsh; a.vst = pl.vst; a.N = pl.N;
   a.Hq = pl.Hq; a.Hkv = pl.Hkv; a.G = pl.G; a.M = pl.M; a.S = pl.S;
   a.s_eff = (int)pl.s_eff; a.k_eff = pl.k_eff; a.l_eff = (int)pl.l_eff;

@@ -79,7 +79,7 @@ hipError_t launch_gather_rope(const Plan& pl, const void* k_cache, const void* v
 hipError_t launch_attend(const Plan& pl, bool fused, const void* q, int q_first, int n_query,
                          const void* k_src, const void* v_src, const int32_t* idx,
                          const float2* rope, float* part, float* out, hipStream_t st,
-                         const int32_t* k_dyn = nullptr, int64_t idx_stride = -1);
+                         const int32_t* k_dyn = nullptr, int64_t idx_stride = -1, int seq_heads = 0);
 // vote selection (vote.hip)
 int vote_list_len(int vote_k);
 bool vote_scan_applies(const Plan& pl);
@@ -94,7 +94,7 @@ void vote_merge_layout(const Plan& pl, int64_t n_votes, size_t* counts_bytes, si
                        size_t* comp_bytes);
 hipError_t launch_vote_merge(const Plan& pl, const int32_t* lists, int64_t n_rows, int kk, int kc, int span,
                              uint32_t* counts, int32_t* seg, uint64_t* comp, int32_t* sel, int32_t* n_sel,
-                             hipStream_t st);
+                             hipStream_t st, int n_seq = 1, int64_t sel_stride = 0);
 
 bool attend_shared_applies(const Plan& pl);
 void attend_shared_layout(const Plan& pl, size_t* kp, size_t* vp, size_t* qp, size_t* part);

@@ -452,9 +452,13 @@ __device__ __forceinline__ void centres_to_spans(int32_t* win, int nc, int32_t* 
 }
 
 // Up to NT votes and centres (a decode step: Hq * vote_k votes): everything in one workgroup, no vote array.
+// blockIdx.x is the sequence of a folded batch: its n_votes consecutive list entries, its own output row.
 template <int NT>
 __global__ __launch_bounds__(NT) void vote_merge_small_kernel(const int32_t* __restrict__ lists, int n_votes,
-                                                              SpanArgs a) {
+                                                              int64_t sel_stride, SpanArgs a) {
+  lists += (int64_t)blockIdx.x * n_votes;
+  a.sel += (int64_t)blockIdx.x * sel_stride;
+  a.n_sel += blockIdx.x;
   __shared__ int32_t tok[NT], win[NT], sa[NT], sb[NT];
   __shared__ uint64_t comp[NT];
   __shared__ int32_t wsum[NT / 64];
@@ -802,16 +806,19 @@ void vote_merge_layout(const Plan& pl, int64_t n_votes, size_t* counts_bytes, si
 // lists: n_rows lists of kk absolute indices.  kc centres (<= 1024), span m.
 hipError_t launch_vote_merge(const Plan& pl, const int32_t* lists, int64_t n_rows, int kk, int kc, int span,
                              uint32_t* counts, int32_t* seg, uint64_t* comp, int32_t* sel, int32_t* n_sel,
-                             hipStream_t st) {
+                             hipStream_t st, int n_seq, int64_t sel_stride) {
+  if (n_seq > 1) n_rows /= n_seq;                      // per sequence; only the one-workgroup path is batched
   const int64_t n_votes = n_rows * kk;
+  if (n_seq > 1 && n_votes > kMergeThreads) return hipErrorInvalidValue;
   SpanArgs a;
   a.s_eff = (int32_t)pl.s_eff; a.n_mid = pl.n_mid; a.kc = kc; a.span = span; a.sel = sel; a.n_sel = n_sel;
   if (n_votes <= kMergeThreads) {
     if (n_votes <= 256 && kc <= 256)                   // a decode step: fewer waves, cheaper barriers
-      hipLaunchKernelGGL(vote_merge_small_kernel<256>, dim3(1), dim3(256), 0, st, lists, (int)n_votes, a);
+      hipLaunchKernelGGL(vote_merge_small_kernel<256>, dim3((unsigned)n_seq), dim3(256), 0, st, lists, (int)n_votes,
+                         sel_stride, a);
     else
-      hipLaunchKernelGGL(vote_merge_small_kernel<kMergeThreads>, dim3(1), dim3(kMergeThreads), 0, st, lists,
-                         (int)n_votes, a);
+      hipLaunchKernelGGL(vote_merge_small_kernel<kMergeThreads>, dim3((unsigned)n_seq), dim3(kMergeThreads), 0, st,
+                         lists, (int)n_votes, sel_stride, a);
     return hipGetLastError();
   }
   static bool lds_ok = false;

@@ -182,3 +182,37 @@ def test_vote_layer_degenerate_partitions(kw):
     n = int(n_sel.item())
     assert sel.cpu().numpy()[:n].tolist() == res["sel"].tolist()
     assert np.abs(out.cpu().numpy().astype(np.float64) - res["out"]).max() <= P.OUT_TOL[w.dtype]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+def test_vote_layer_batched_sequences(dtype):
+    """Three equal-length sequences folded into the head axis (n_seq = 3): votes are pooled per sequence,
+    every sequence gets its own selection and output, equal to the oracle run on that sequence alone."""
+    Bn = 3
+    base = wl.CONFIGS[2].scaled(dtype=dtype, n_ctx=7_001, n_local=200, top_k=0, n_needles=3, max_position=0)
+    v1 = B.Vote(4, 10, 16)
+    seqs = [wl.generate(base.scaled(cfg=20 + b), "cuda") for b in range(Bn)]
+    fold = base.scaled(n_q_heads=Bn * base.n_q_heads, n_kv_heads=Bn * base.n_kv_heads)
+    q = torch.cat([t["q"] for t in seqs], dim=1).contiguous()
+    k = torch.cat([t["k"] for t in seqs], dim=0).contiguous()
+    vv = torch.cat([t["v"] for t in seqs], dim=0).contiguous()
+    p = B.Params.from_workload(fold)
+    vb = B.Vote(4, 10, 16, n_seq=Bn)
+    ws = B.alloc_vote_workspace(p, vb)
+    lists = B.vote_topk(p, vb, q, k, ws)
+    out, sel, n_sel = B.vote_layer(p, vb, q, k, vv, ws)
+    torch.cuda.synchronize()
+    cap = B.vote_cap(p, vb)
+    sel = sel.view(Bn, cap).cpu().numpy(); n_sel = n_sel.cpu().numpy()
+    sh = P.oracle_shape(base)
+    Hq = base.n_q_heads
+    for b, t in enumerate(seqs):
+        qh, kh, vh = P.host_inputs(t)
+        res = ro.vote_forward(sh, qh, kh, vh, v1.vote_k, v1.n_centres, v1.span,
+                              head_topk=lists[:, b * Hq:(b + 1) * Hq].cpu().numpy())
+        assert sel[b, : n_sel[b]].tolist() == res["sel"].tolist(), b
+        err = np.abs(out[:, b * Hq:(b + 1) * Hq].cpu().numpy().astype(np.float64) - res["out"]).max()
+        assert err <= P.OUT_TOL[dtype], (b, err)
+    # a chunk cannot be folded
+    pm = B.Params.from_workload(fold.scaled(n_query=2))
+    assert B.vote_workspace_bytes(pm, vb) == 0
