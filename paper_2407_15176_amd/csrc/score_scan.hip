@@ -132,7 +132,7 @@ __global__ __launch_bounds__(kScanThreads) void score_scan_kernel(ScanArgs a) {
 
   __syncthreads();
   float* out = a.scores + (int64_t)row_id * a.n_mid + blk_row0;
-  for (int r = threadIdx.x; r < nrows; r += kScanThreads) out[r] = stage[r];
+  for (int r = threadIdx.x; r < nrows; r += kScanThreads) __builtin_nontemporal_store(stage[r], out + r);
   if (HIST) {
     uint32_t* gh = a.hist + (int64_t)row_id * kHistBins;
     for (int b = threadIdx.x; b < kHistBins; b += kScanThreads) {

@@ -251,11 +251,16 @@ __global__ __launch_bounds__(kVoteThreads) void head_topk_mfma_kernel(MfmaScanAr
       d[u] = __builtin_nontemporal_load((const u32x4*)(kbase + (int64_t)r * row_bytes));
     }
   };
-  u32x4 d[4 * T], dn[4 * T];
-  if (wave * (T * 16) < nrows) request(wave * (T * 16), d);
+  constexpr bool kAhead = NB == 1;                     // two column blocks leave no registers for a second batch
+  u32x4 d[4 * T], dn[kAhead ? 4 * T : 1];
+  if (kAhead && wave * (T * 16) < nrows) request(wave * (T * 16), d);
   for (int t = wave * (T * 16); t < nrows; t += kVoteWaves * (T * 16)) {
-    const int t_next = t + kVoteWaves * (T * 16);
-    if (t_next < nrows) request(t_next, dn);
+    if (kAhead) {
+      const int t_next = t + kVoteWaves * (T * 16);
+      if (t_next < nrows) request(t_next, dn);
+    } else {
+      request(t, d);
+    }
     // registers -> wave-private LDS, piece index XOR row so that both sides are conflict free
 #pragma unroll
     for (int u = 0; u < 4 * T; ++u) {
@@ -293,8 +298,10 @@ __global__ __launch_bounds__(kVoteThreads) void head_topk_mfma_kernel(MfmaScanAr
         }
       }
     }
+    if (kAhead) {
 #pragma unroll
-    for (int u = 0; u < 4 * T; ++u) d[u] = dn[u];
+      for (int u = 0; u < 4 * T; ++u) d[u] = dn[kAhead ? u : 0];
+    }
   }
 
   // the four lanes of a column merge their lists: KT rounds of arg-max over lanes l, l^16, l^32, l^48
