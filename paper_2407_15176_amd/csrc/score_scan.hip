@@ -189,7 +189,8 @@ hipError_t launch_t(const ScanArgs& a, dim3 grid, bool hist, hipStream_t st) {
 // Rows per workgroup: the whole job is cut into a multiple of the CU count of equal
 // slices (each within one KV head) so that every CU streams the same amount and the
 // bursts of score writes fall together at the end of each round.
-int scan_rows_per_block(int64_t n_mid, int64_t score_rows) {
+int scan_rows_per_block(int64_t n_mid, int64_t score_rows, int max_rows) {
+  if (max_rows <= 0 || max_rows > kScanMaxRows) max_rows = kScanMaxRows;
   static int n_cu = 0;
   if (n_cu == 0) {
     int dev = 0; hipDeviceProp_t pr;
@@ -198,12 +199,12 @@ int scan_rows_per_block(int64_t n_mid, int64_t score_rows) {
     if (n_cu <= 0) n_cu = 256;
   }
   const int64_t total = n_mid * score_rows;
-  const int64_t rounds = (total + (int64_t)n_cu * kScanMaxRows - 1) / ((int64_t)n_cu * kScanMaxRows);
+  const int64_t rounds = (total + (int64_t)n_cu * max_rows - 1) / ((int64_t)n_cu * max_rows);
   const int64_t wgs = rounds * n_cu;
   const int64_t per_row = (wgs + score_rows - 1) / score_rows;      // workgroups per score row
   int64_t rpb = (n_mid + per_row - 1) / per_row;
   rpb = (rpb + 31) / 32 * 32;
-  if (rpb > kScanMaxRows) rpb = kScanMaxRows;
+  if (rpb > max_rows) rpb = max_rows;
   if (rpb < 32) rpb = 32;
   return (int)rpb;
 }
@@ -215,7 +216,7 @@ hipError_t launch_score_scan(const Plan& pl, const void* q, int n_query, const v
   a.k = k_cache; a.q = q; a.scores = scores; a.hist = hist;
   a.ksh = pl.ksh; a.kst = pl.kst; a.n_mid = pl.n_mid; a.first_tok = pl.s_eff;
   a.Hq = pl.Hq; a.Hkv = pl.Hkv; a.G = pl.G;
-  a.rows_per_block = scan_rows_per_block(pl.n_mid, (int64_t)pl.Hkv * n_query);
+  a.rows_per_block = scan_rows_per_block(pl.n_mid, (int64_t)pl.Hkv * n_query, 0);
   dim3 grid((unsigned)((pl.n_mid + a.rows_per_block - 1) / a.rows_per_block),
             (unsigned)(pl.Hkv * n_query));
   const bool h = hist != nullptr;
