@@ -63,7 +63,7 @@ typedef enum {
 typedef enum { REATTN_F32 = 0, REATTN_BF16 = 1, REATTN_F16 = 2 } reattn_dtype;
 
 /* How the G heads of one GQA group are combined into one score per KV head.
- * The paper votes over per-head lists; this library aggregates scores instead. */
+ * (The paper's own way, votes over per-head lists, is the reattn_vote_* family below.) */
 typedef enum { REATTN_AGG_SUM = 0 } reattn_agg;
 
 typedef struct reattn_params {
