@@ -21,6 +21,11 @@ import time
 HBM_PEAK_GBPS = 8000.0      # MI355X published HBM3E bandwidth
 # Measured with rocprofv3 --pmc (profiles/score_scan_cfg3_pmc.md): fetched + written bytes per launch.
 SCAN_TRAFFIC_BYTES = {"cfg3_decode_1m_bf16": 2 * 1044544.6 * 1024 + 32913.8 * 1024}
+# Same for the other dominant kernels (profiles/vote_decode_cfg3_kernel_trace_pmc.md,
+# profiles/prefill_chunk_cfg4_kernel_trace_pmc.md, profiles/vote_prefill_cfg4_kernel_trace_pmc.md): fetched bytes per launch.
+VOTE_SCAN_TRAFFIC_BYTES = {"cfg3_decode_1m_bf16": 2 * 1044560.7 * 1024 + 32.0 * 1024}
+GEMM_FILTER_TRAFFIC_BYTES = 2 * 266407.5 * 1024
+VOTE_GEMM_TRAFFIC_BYTES = 2 * 533497.3 * 1024
 
 
 def main() -> int:
@@ -238,7 +243,7 @@ def prefill_leg(steps: int) -> dict:
             "executed_mfma_flops": executed,
             "executed_TFLOPs": round(executed / (gemm_ms * 1e-3) / 1e12, 1),
             "executed_frac": round(executed / (gemm_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
-            "traffic": None,
+            "traffic": GEMM_FILTER_TRAFFIC_BYTES,
         },
     }
 
@@ -280,7 +285,8 @@ def vote_prefill_leg(steps: int, n_query: int = 4096) -> dict:
         "roofline": {
             "kernel": "vote_gemm_kernel (fused per-head running top-k) + list merge", "bound": "mfma",
             "achieved": round(tf, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-            "frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 4), "algorithmic_flops": flops, "traffic": None,
+            "frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 4), "algorithmic_flops": flops,
+            "traffic": VOTE_GEMM_TRAFFIC_BYTES if n_query == 4096 else None,
         },
     }
 
@@ -450,7 +456,7 @@ def vote_leg(t: dict, cfg: int, steps: int, warmup: int) -> dict:
             "kernel": "head_topk_mfma_kernel (+ list merge)", "bound": "hbm",
             "achieved": round(scan_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
             "frac": round(scan_gbps / HBM_PEAK_GBPS, 4), "algorithmic_bytes": w.scan_bytes,
-            "traffic": None,
+            "traffic": VOTE_SCAN_TRAFFIC_BYTES.get(wl.CONFIGS[cfg].name),
         },
     }
 
