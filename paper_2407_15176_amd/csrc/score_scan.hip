@@ -32,6 +32,8 @@ struct ScanArgs {
   int64_t n_mid, first_tok;
   int Hq, Hkv, G;
   int rows_per_block;
+  int stream_out;       // scores leave with non-temporal stores (several rounds of workgroups: a round's burst
+                        // falls into the next round's reads, and ordinary stores would cost those ~9 %)
 };
 
 template <typename T> struct Store;
@@ -132,7 +134,11 @@ __global__ __launch_bounds__(kScanThreads) void score_scan_kernel(ScanArgs a) {
 
   __syncthreads();
   float* out = a.scores + (int64_t)row_id * a.n_mid + blk_row0;
-  for (int r = threadIdx.x; r < nrows; r += kScanThreads) __builtin_nontemporal_store(stage[r], out + r);
+  if (a.stream_out) {
+    for (int r = threadIdx.x; r < nrows; r += kScanThreads) __builtin_nontemporal_store(stage[r], out + r);
+  } else {                                         // one round: the scores stay in cache for the top-k that follows
+    for (int r = threadIdx.x; r < nrows; r += kScanThreads) out[r] = stage[r];
+  }
   if (HIST) {
     uint32_t* gh = a.hist + (int64_t)row_id * kHistBins;
     for (int b = threadIdx.x; b < kHistBins; b += kScanThreads) {
@@ -219,6 +225,7 @@ hipError_t launch_score_scan(const Plan& pl, const void* q, int n_query, const v
   a.rows_per_block = scan_rows_per_block(pl.n_mid, (int64_t)pl.Hkv * n_query, 0);
   dim3 grid((unsigned)((pl.n_mid + a.rows_per_block - 1) / a.rows_per_block),
             (unsigned)(pl.Hkv * n_query));
+  a.stream_out = (int64_t)grid.x * grid.y > 320 ? 1 : 0;   // more workgroups than one round over the chip
   const bool h = hist != nullptr;
   if (pl.dtype == kF32) return pl.D == 64 ? launch_t<float, 64>(a, grid, h, st)
                                           : launch_t<float, 128>(a, grid, h, st);
