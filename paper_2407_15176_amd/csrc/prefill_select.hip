@@ -290,13 +290,10 @@ hipError_t launch_cand_topk(const Plan& pl, int n_query, const uint2* cand, cons
   a.cand = cand; a.ccount = ccount; a.cap = cap; a.M = n_query; a.Hkv = pl.Hkv; a.k_eff = pl.k_eff;
   a.n_mid = pl.n_mid; a.index_base = (int32_t)pl.s_eff; a.idx = idx; a.redo = redo;
   const size_t lds = cand_topk_lds(pl);
-  static size_t lds_set = 0;
-  if (lds > lds_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)cand_topk_kernel,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return e;
-    lds_set = lds;
-  }
+  // set on every launch: the attribute belongs to the current device, and nothing is remembered between calls
+  hipError_t e = hipFuncSetAttribute((const void*)cand_topk_kernel,
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  if (e != hipSuccess) return e;
   hipLaunchKernelGGL(cand_topk_kernel, dim3(n_query, pl.Hkv), dim3(256), lds, st, a);
   return hipGetLastError();
 }

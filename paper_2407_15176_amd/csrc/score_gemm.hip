@@ -325,15 +325,10 @@ __global__ __launch_bounds__(kGemmThreads) void score_gemm_kernel(GemmArgs a) {
 
 template <int MODE>
 hipError_t gemm_launch(const GemmArgs& a, dim3 grid, hipStream_t st) {
-  static bool attr_done = false;
   constexpr size_t lds = 2 * (size_t)kTileBytes + (MODE == kFilter ? 8 * (size_t)kStageBytes : 0);
   auto kern = score_gemm_kernel<MODE>;
-  if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       (int)lds);
-    if (e != hipSuccess) return e;
-    attr_done = true;
-  }
+  hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  if (e != hipSuccess) return e;
   hipLaunchKernelGGL(kern, grid, dim3(kGemmThreads), lds, st, a);
   return hipGetLastError();
 }

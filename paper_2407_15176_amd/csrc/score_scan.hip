@@ -197,13 +197,10 @@ hipError_t launch_t(const ScanArgs& a, dim3 grid, bool hist, hipStream_t st) {
 // bursts of score writes fall together at the end of each round.
 int scan_rows_per_block(int64_t n_mid, int64_t score_rows, int max_rows) {
   if (max_rows <= 0 || max_rows > kScanMaxRows) max_rows = kScanMaxRows;
-  static int n_cu = 0;
-  if (n_cu == 0) {
-    int dev = 0; hipDeviceProp_t pr;
-    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&pr, dev) == hipSuccess)
-      n_cu = pr.multiProcessorCount;
-    if (n_cu <= 0) n_cu = 256;
-  }
+  int n_cu = 0, dev = 0;                               // of the current device, asked every time: no state is kept
+  if (hipGetDevice(&dev) != hipSuccess ||
+      hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu <= 0)
+    n_cu = 256;
   const int64_t total = n_mid * score_rows;
   const int64_t rounds = (total + (int64_t)n_cu * max_rows - 1) / ((int64_t)n_cu * max_rows);
   const int64_t wgs = rounds * n_cu;

@@ -245,12 +245,10 @@ hipError_t launch_topk(const Plan& pl, int rows, const float* scores, bool hist_
                        uint32_t* hist, uint32_t* pfx, uint32_t* ncand, int32_t* cand,
                        uint32_t* bitmap, uint32_t* cnt, int32_t* idx, hipStream_t st) {
   if (pl.k_eff <= 0 || rows <= 0) return hipSuccess;
-  static bool lds_ok = false;
-  if (!lds_ok) {
+  {
     hipError_t e = hipFuncSetAttribute((const void*)topk_refine_kernel,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)kRefineLds);
     if (e != hipSuccess) return e;
-    lds_ok = true;
   }
   const dim3 per_chunk((unsigned)pl.nchunks, (unsigned)rows);
   const uint32_t k = (uint32_t)pl.k_eff;

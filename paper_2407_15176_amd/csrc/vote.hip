@@ -829,12 +829,10 @@ hipError_t launch_vote_merge(const Plan& pl, const int32_t* lists, int64_t n_row
                          lists, (int)n_votes, sel_stride, a);
     return hipGetLastError();
   }
-  static bool lds_ok = false;
-  if (!lds_ok) {
+  {
     hipError_t e = hipFuncSetAttribute((const void*)vote_pick_kernel,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)kPickLds);
     if (e != hipSuccess) return e;
-    lds_ok = true;
   }
   const unsigned n_blocks = (unsigned)((n_votes + kMergeThreads - 1) / kMergeThreads);
   uint32_t* chist = counts + pl.n_mid;
