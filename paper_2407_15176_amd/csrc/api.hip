@@ -106,7 +106,7 @@ int make_plan(const reattn_params* p, Plan* out) {
     int64_t stride, n_s; uint32_t rho, cap;
     prefill_sampling(pl, &stride, &n_s, &rho, &cap);
     const size_t prow = (size_t)pl.M * pl.Hkv;
-    pl.off_samp = off;   off += up(prow * (size_t)n_s * 4);
+    pl.off_samp = off;   off += up(prow * (size_t)((n_s + 3) / 4 * 4) * 4);   // rows padded to 16 bytes
     pl.off_thr = off;    off += up(prow * 4);
     pl.off_pcand = off;  off += up(prow * (size_t)cap * 8);
     pl.off_pcount = off; off += up(prow * 4);
@@ -188,8 +188,9 @@ int fused_prefill_select(const Plan& pl, const Ws& w, char* ws, const void* q, c
   int rc = hip_rc(launch_prep(pl, 0, nullptr, w.rope, st));
   if (!rc) rc = hip_rc(launch_fill_u32(redo, 1, 0u, st));
   if (!rc) rc = hip_rc(launch_qsplit(pl, q, 0, pl.M, w.qsplit, st));
-  if (!rc) rc = hip_rc(launch_score_gemm_store(pl, pl.M, k_cache, w.qsplit, stride, n_s, samp, n_s, st));
-  if (!rc) rc = hip_rc(launch_sample_threshold(pl, pl.M, samp, n_s, rho, thr, st));
+  const int64_t samp_stride = (n_s + 3) / 4 * 4;         // 16-byte rows: the sampled scores leave in float4 stores
+  if (!rc) rc = hip_rc(launch_score_gemm_store(pl, pl.M, k_cache, w.qsplit, stride, n_s, samp, samp_stride, st));
+  if (!rc) rc = hip_rc(launch_sample_threshold(pl, pl.M, samp, n_s, samp_stride, rho, thr, st));
   mark(ev, 1, st);
   if (!rc) rc = hip_rc(launch_score_gemm_filter(pl, pl.M, k_cache, w.qsplit, thr, cand, ccount, cap, st));
   mark(ev, 2, st);

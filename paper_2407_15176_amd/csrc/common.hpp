@@ -51,7 +51,7 @@ hipError_t launch_score_scan(const Plan& pl, const void* q, int n_query, const v
 void prefill_sampling(const Plan& pl, int64_t* stride, int64_t* n_s, uint32_t* rho, uint32_t* cap);
 size_t cand_topk_lds(const Plan& pl);
 hipError_t launch_sample_threshold(const Plan& pl, int n_query, const float* samp, int64_t n_s,
-                                   uint32_t rho, float* thr, hipStream_t st);
+                                   int64_t row_stride, uint32_t rho, float* thr, hipStream_t st);
 hipError_t launch_cand_topk(const Plan& pl, int n_query, const uint2* cand, const uint32_t* ccount,
                             uint32_t cap, int32_t* idx, uint32_t* redo, hipStream_t st);
 hipError_t launch_row_exact(const Plan& pl, int n_query, const void* q, const void* k_cache,

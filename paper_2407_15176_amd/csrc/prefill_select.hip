@@ -46,14 +46,21 @@ __device__ __forceinline__ uint32_t bscan_incl(uint32_t v, uint32_t* wsum, uint3
   return x + base;
 }
 
-// bins[0..2048): largest-first search for the bin holding the k-th entry (1 <= k <= total).
+// LDS layouts that keep strided owners off each other's banks (64 banks of 4 bytes): a thread that owns 8
+// consecutive histogram bins, or 32 consecutive bitmap words, would otherwise meet 7 (31) other lanes in
+// every bank it touches.  One pad word per 8 bins / per 32 words makes the owners' strides odd.
+constexpr int kBins = 2048, kBinsPad = kBins + kBins / 8;
+__device__ __forceinline__ int bslot(int b) { return b + (b >> 3); }
+__device__ __forceinline__ int wslot(int w) { return w + (w >> 5); }
+
+// bins[bslot(0..2048)): largest-first search for the bin holding the k-th entry (1 <= k <= total).
 template <int NT>
 __device__ __forceinline__ void kth_bin(const uint32_t* bins, uint32_t k, uint32_t* sh,
                                         uint32_t& bin, uint32_t& above) {
   constexpr int BPT = 2048 / NT;
   uint32_t loc[BPT], sum = 0;
 #pragma unroll
-  for (int i = 0; i < BPT; ++i) { loc[i] = bins[threadIdx.x * BPT + i]; sum += loc[i]; }
+  for (int i = 0; i < BPT; ++i) { loc[i] = bins[bslot(threadIdx.x * BPT + i)]; sum += loc[i]; }
   uint32_t total;
   const uint32_t incl = bscan_incl<NT>(sum, sh, total);
   const uint32_t higher = total - incl;
@@ -82,17 +89,17 @@ __device__ __forceinline__ void radix_kth(Get get, uint32_t n, uint32_t k, int b
   while (shift > 0) {
     const int w = shift < 11 ? shift : 11;
     shift -= w;
-    for (int b = threadIdx.x; b < 2048; b += NT) bins[b] = 0;
+    for (int b = threadIdx.x; b < kBinsPad; b += NT) bins[b] = 0;
     __syncthreads();
     for (uint32_t i = threadIdx.x; i < n; i += NT) {
       const uint64_t v = get(i);
       if ((shift + w >= 64 ? 0ull : (v >> (shift + w))) == prefix)
-        atomicAdd(&bins[(uint32_t)(v >> shift) & ((1u << w) - 1u)], 1u);
+        atomicAdd(&bins[bslot((int)((uint32_t)(v >> shift) & ((1u << w) - 1u)))], 1u);
     }
     __syncthreads();
     uint32_t d, ab;
     kth_bin<NT>(bins, remaining, sh, d, ab);
-    const uint32_t in_bin = bins[d];
+    const uint32_t in_bin = bins[bslot((int)d)];
     remaining -= ab;
     prefix = (prefix << w) | d;
     __syncthreads();
@@ -102,25 +109,70 @@ __device__ __forceinline__ void radix_kth(Get get, uint32_t n, uint32_t k, int b
 }
 
 // ---- sample_threshold -------------------------------------------------------
-// samp[(i*Hkv + h) * n_s + j]: sampled scores; thr[h*M + i] = rho-th largest (or -inf if rho > n_s).
-__global__ __launch_bounds__(256) void sample_threshold_kernel(const float* __restrict__ samp,
-                                                               int64_t n_s, uint32_t rho, int M,
+// samp[(i*Hkv + h) * row_stride + j], j < n_s: sampled scores; thr[h*M + i] = a lower bound of the rho-th
+// largest, at most 2^-22 of the row's key range below it (or -inf if rho > n_s).  The row is read once
+// into registers (n_s <= 256 * R); the radix select walks the significant bits of the offsets from the
+// row's smallest ordered key, 11 at a time, and stops after two passes: the bits left undecided only
+// lower the bound, by less than any two distinct scores of the distribution differ.
+template <int R>
+__global__ __launch_bounds__(256) void sample_threshold_kernel(const float* __restrict__ samp, int64_t n_s,
+                                                               int64_t row_stride, uint32_t rho, int M,
                                                                int Hkv, float* thr) {
-  __shared__ uint32_t bins[2048];
+  __shared__ uint32_t bins[kBinsPad];
   __shared__ uint32_t sh[40];
   const int i = blockIdx.x, h = blockIdx.y;
-  const float* row = samp + ((int64_t)i * Hkv + h) * n_s;
-  float out = -__builtin_inff();
-  if (rho <= n_s) {
-    int shift; uint64_t prefix;
-    radix_kth<256>([&](uint32_t j) -> uint64_t { return score_key(row[j]); }, (uint32_t)n_s, rho, 32,
-                   bins, sh, shift, prefix);
-    // smallest key with (key >> shift) == prefix is a lower bound of the rho-th largest
-    const uint32_t key = (uint32_t)(prefix << shift);
-    const uint32_t u = (key & 0x80000000u) ? (key & 0x7fffffffu) : ~key;
-    out = __uint_as_float(u);
+  const float* row = samp + ((int64_t)i * Hkv + h) * row_stride;
+  if (rho > n_s) {
+    if (threadIdx.x == 0) thr[(int64_t)h * M + i] = -__builtin_inff();
+    return;
   }
-  if (threadIdx.x == 0) thr[(int64_t)h * M + i] = out;
+  const uint32_t n = (uint32_t)n_s;
+  uint32_t key[R];
+  uint32_t kmin = 0xffffffffu, kmax = 0u;
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    const uint32_t j = (uint32_t)r * 256u + threadIdx.x;
+    key[r] = j < n ? score_key(row[j]) : 0u;
+    if (j < n) { kmin = min(kmin, key[r]); kmax = max(kmax, key[r]); }
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    kmin = min(kmin, (uint32_t)__shfl_xor((int)kmin, o, 64));
+    kmax = max(kmax, (uint32_t)__shfl_xor((int)kmax, o, 64));
+  }
+  if ((threadIdx.x & 63) == 0) { sh[34 + (threadIdx.x >> 6)] = kmin; sh[30 + (threadIdx.x >> 6)] = kmax; }
+  __syncthreads();
+  kmin = min(min(sh[34], sh[35]), min(sh[36], sh[37]));
+  kmax = max(max(sh[30], sh[31]), max(sh[32], sh[33]));
+  __syncthreads();
+  int dsh = 32 - __clz((int)(kmax - kmin));
+  uint32_t dpref = 0, remaining = rho;
+  for (int p = 0; p < 2 && dsh > 0; ++p) {
+    const int w = dsh < 11 ? dsh : 11;
+    dsh -= w;
+    for (int b = threadIdx.x; b < kBinsPad; b += 256) bins[b] = 0;
+    __syncthreads();
+    const int up = dsh + w;
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      if ((uint32_t)r * 256u + threadIdx.x < n) {
+        const uint32_t d = key[r] - kmin;
+        if (up >= 32 || (d >> up) == dpref) atomicAdd(&bins[bslot((int)((d >> dsh) & ((1u << w) - 1u)))], 1u);
+      }
+    }
+    __syncthreads();
+    uint32_t d, ab;
+    kth_bin<256>(bins, remaining, sh, d, ab);
+    remaining -= ab;
+    dpref = (dpref << w) | d;
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    // smallest key that shares the decided prefix: a lower bound of the rho-th largest
+    const uint32_t k = kmin + (dsh >= 32 ? 0u : (dpref << dsh));
+    const uint32_t u = (k & 0x80000000u) ? (k & 0x7fffffffu) : ~k;
+    thr[(int64_t)h * M + i] = __uint_as_float(u);
+  }
 }
 
 // ---- cand_topk ---------------------------------------------------------------
@@ -137,7 +189,7 @@ __device__ __forceinline__ uint64_t cand_composite(uint2 c) {
 
 __global__ __launch_bounds__(256) void cand_topk_kernel(CandArgs a) {
   extern __shared__ uint32_t bitmap[];            // ceil(n_mid / 32) words, rounded up to 256
-  __shared__ uint32_t bins[2048];
+  __shared__ uint32_t bins[kBinsPad];
   __shared__ uint32_t sh[40];
   const int i = blockIdx.x, h = blockIdx.y;
   const int64_t row = (int64_t)h * a.M + i;
@@ -184,6 +236,166 @@ __global__ __launch_bounds__(256) void cand_topk_kernel(CandArgs a) {
   }
 }
 
+// The same selection with the row's candidates held in registers (segments of up to 256 * R entries):
+// the segment is read once instead of once per radix pass, and its loads are issued before anything
+// waits (not even for the row's count: slots past it are read and ignored).  Every candidate passed the
+// row's threshold, so the ordered score keys span a narrow range above the smallest one; the radix
+// select runs on the 32-bit offsets d from that smallest key, whose significant bits alone are walked
+// (typically two passes of 11 bits settle the k-th entry), and only a tie on d goes on to the key
+// index (lower first, as everywhere).  Winners are marked in an LDS bitmap over the middle; every
+// thread then takes its 32 consecutive bitmap words into registers, ranks them with one block scan and
+// writes the indices, in order, into LDS (over the spent bitmap), from where they leave in 16-byte
+// rows: written straight from the ranking loop, every lane of a store would touch its own cache line.
+constexpr int kRankWords = 32;                   // bitmap words a thread can rank out of registers
+
+template <int R>
+__global__ __launch_bounds__(256, 3) void cand_topk_reg_kernel(CandArgs a) {
+  extern __shared__ uint32_t bitmap[];            // wslot(nwords_pad) words; later the ranked indices
+  __shared__ uint32_t bins[kBinsPad];
+  __shared__ uint32_t sh[40];
+  const int i = blockIdx.x, h = blockIdx.y;
+  const int64_t row = (int64_t)h * a.M + i;
+  const uint2* seg = a.cand + row * a.cap;
+  uint32_t key[R], pos[R];
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    const uint32_t j = (uint32_t)r * 256u + threadIdx.x;
+    const uint2 c = j < a.cap ? seg[j] : make_uint2(0u, 0u);
+    key[r] = c.x; pos[r] = c.y;
+  }
+  const uint32_t n = a.ccount[row];
+  const int nwords = (int)((a.n_mid + 31) / 32);
+  const int nwords_pad = (nwords + 255) / 256 * 256;
+  const int nslots = wslot(nwords_pad);
+  for (int w = threadIdx.x; w < nslots; w += 256) bitmap[w] = 0;     // while the loads are in flight
+  if (n < (uint32_t)a.k_eff || n > a.cap) {
+    if (threadIdx.x == 0) {
+      const uint32_t at = atomicAdd(&a.redo[0], 1u);
+      a.redo[1 + at] = (uint32_t)row;
+    }
+    return;
+  }
+  uint32_t kmin = 0xffffffffu, kmax = 0u;
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    key[r] = score_key(__uint_as_float(key[r]));
+    if ((uint32_t)r * 256u + threadIdx.x < n) { kmin = min(kmin, key[r]); kmax = max(kmax, key[r]); }
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    kmin = min(kmin, (uint32_t)__shfl_xor((int)kmin, o, 64));
+    kmax = max(kmax, (uint32_t)__shfl_xor((int)kmax, o, 64));
+  }
+  if ((threadIdx.x & 63) == 0) { sh[34 + (threadIdx.x >> 6)] = kmin; sh[30 + (threadIdx.x >> 6)] = kmax; }
+  __syncthreads();
+  kmin = min(min(sh[34], sh[35]), min(sh[36], sh[37]));
+  kmax = max(max(sh[30], sh[31]), max(sh[32], sh[33]));
+  __syncthreads();
+  const int nbits = 32 - __clz((int)(kmax - kmin));          // significant bits of the offsets (0 when all keys are equal)
+#pragma unroll
+  for (int r = 0; r < R; ++r) { key[r] -= kmin; pos[r] = ~pos[r]; }   // d, and the index as a descending key
+
+  // Winners: in the offset part, d >> dsh >= dpref; once a tie on d = dpref had to be broken,
+  // d > dpref, or d == dpref and ~index >> psh >= ppref.
+  bool all = (uint32_t)a.k_eff == n, tie = false;
+  uint32_t dpref = 0, ppref = 0;
+  int dsh = nbits, psh = 32;
+  if (!all) {
+    uint32_t remaining = (uint32_t)a.k_eff;
+    bool done = false;
+    auto pass = [&](bool on_index, int sft, int w) {
+      for (int b = threadIdx.x; b < kBinsPad; b += 256) bins[b] = 0;
+      __syncthreads();
+      const int up = sft + w;                                // up == 32 only on a first pass: no prefix yet
+#pragma unroll
+      for (int r = 0; r < R; ++r) {
+        if ((uint32_t)r * 256u + threadIdx.x < n) {
+          const uint32_t v = on_index ? pos[r] : key[r];
+          const bool in = (up >= 32 || (v >> up) == (on_index ? ppref : dpref)) && (!on_index || key[r] == dpref);
+          if (in) atomicAdd(&bins[bslot((int)((v >> sft) & ((1u << w) - 1u)))], 1u);
+        }
+      }
+      __syncthreads();
+      uint32_t d, ab;
+      kth_bin<256>(bins, remaining, sh, d, ab);
+      const uint32_t in_bin = bins[bslot((int)d)];
+      remaining -= ab;
+      if (on_index) ppref = (ppref << w) | d; else dpref = (dpref << w) | d;
+      __syncthreads();
+      done = in_bin == remaining;                            // everything that shares this prefix is selected
+    };
+    while (dsh > 0 && !done) {
+      const int w = dsh < 11 ? dsh : 11;
+      dsh -= w;
+      pass(false, dsh, w);
+    }
+    if (!done) {                                             // dpref is the k-th entry's d: the tie ends on the index
+      tie = true;
+      while (psh > 0 && !done) {
+        const int w = psh < 11 ? psh : 11;
+        psh -= w;
+        pass(true, psh, w);
+      }
+    }
+  }
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    if ((uint32_t)r * 256u + threadIdx.x < n) {
+      const bool win = all || (tie ? (key[r] > dpref || (key[r] == dpref && (pos[r] >> psh) >= ppref))
+                                   : (dsh >= 32 || (key[r] >> dsh) >= dpref));
+      const uint32_t p = ~pos[r];
+      if (win) atomicOr(&bitmap[wslot((int)(p >> 5))], 1u << (p & 31));
+    }
+  }
+  __syncthreads();
+  // ordered compaction: thread t owns words [t*wpt, (t+1)*wpt)
+  const int wpt = nwords_pad / 256;
+  int32_t* out = a.idx + ((int64_t)i * a.Hkv + h) * a.k_eff;
+  uint32_t total;
+  if (wpt <= kRankWords) {
+    uint32_t word[kRankWords];
+    uint32_t mine = 0;
+#pragma unroll
+    for (int w = 0; w < kRankWords; ++w) {
+      word[w] = w < wpt ? bitmap[wslot(threadIdx.x * wpt + w)] : 0u;
+      mine += __popc(word[w]);
+    }
+    uint32_t at = bscan_incl<256>(mine, sh, total) - mine;   // its barriers also end every read of the bitmap
+    int32_t* ranked = (int32_t*)bitmap;                      // [k_eff]
+#pragma unroll
+    for (int w = 0; w < kRankWords; ++w) {
+      uint32_t bits = word[w];
+      const int32_t first = a.index_base + (threadIdx.x * wpt + w) * 32;
+      while (bits) {
+        const int b = __ffs((int)bits) - 1;
+        bits &= bits - 1;
+        if (at < (uint32_t)a.k_eff) ranked[at] = first + b;
+        ++at;
+      }
+    }
+    __syncthreads();
+    if ((a.k_eff & 3) == 0 && ((uintptr_t)a.idx & 15) == 0) {
+      for (int j = threadIdx.x; j < a.k_eff / 4; j += 256) ((int4*)out)[j] = ((const int4*)ranked)[j];
+    } else {
+      for (int j = threadIdx.x; j < a.k_eff; j += 256) out[j] = ranked[j];
+    }
+  } else {                                                   // a long middle: ranked from LDS, written directly
+    uint32_t mine = 0;
+    for (int w = 0; w < wpt; ++w) mine += __popc(bitmap[wslot(threadIdx.x * wpt + w)]);
+    uint32_t at = bscan_incl<256>(mine, sh, total) - mine;
+    for (int w = 0; w < wpt; ++w) {
+      uint32_t bits = bitmap[wslot(threadIdx.x * wpt + w)];
+      const int32_t first = a.index_base + (threadIdx.x * wpt + w) * 32;
+      while (bits) {
+        const int b = __ffs((int)bits) - 1;
+        bits &= bits - 1;
+        if (at < (uint32_t)a.k_eff) out[at] = first + b;
+        ++at;
+      }
+    }
+  }
+}
+
 // ---- row_exact (redo path) ----------------------------------------------------
 struct ExactArgs {
   const uint16_t* q; const uint16_t* k;
@@ -195,7 +407,7 @@ struct ExactArgs {
 };
 
 __global__ __launch_bounds__(1024) void row_exact_kernel(ExactArgs a) {
-  __shared__ uint32_t bins[2048];
+  __shared__ uint32_t bins[kBinsPad];
   __shared__ uint32_t sh[40];
   const uint32_t n_redo = a.redo[0];
   float* sc = a.scratch + (int64_t)blockIdx.x * a.n_mid;
@@ -273,15 +485,24 @@ void prefill_sampling(const Plan& pl, int64_t* stride, int64_t* n_s, uint32_t* r
 }
 
 hipError_t launch_sample_threshold(const Plan& pl, int n_query, const float* samp, int64_t n_s,
-                                   uint32_t rho, float* thr, hipStream_t st) {
-  hipLaunchKernelGGL(sample_threshold_kernel, dim3(n_query, pl.Hkv), dim3(256), 0, st, samp, n_s, rho,
-                     n_query, pl.Hkv, thr);
+                                   int64_t row_stride, uint32_t rho, float* thr, hipStream_t st) {
+  // the sample of prefill_sampling() is shorter than 2 * 8192 keys
+  if (n_s > 256 * 64) return hipErrorInvalidValue;
+  if (n_s <= 256 * 36)
+    hipLaunchKernelGGL(sample_threshold_kernel<36>, dim3(n_query, pl.Hkv), dim3(256), 0, st, samp, n_s,
+                       row_stride, rho, n_query, pl.Hkv, thr);
+  else
+    hipLaunchKernelGGL(sample_threshold_kernel<64>, dim3(n_query, pl.Hkv), dim3(256), 0, st, samp, n_s,
+                       row_stride, rho, n_query, pl.Hkv, thr);
   return hipGetLastError();
 }
 
-size_t cand_topk_lds(const Plan& pl) {
+size_t cand_topk_lds(const Plan& pl) {                     // selection bitmap over the middle + the ranked indices
   const size_t nwords = (size_t)((pl.n_mid + 31) / 32);
-  return (nwords + 255) / 256 * 256 * 4;
+  const size_t padded = (nwords + 255) / 256 * 256;
+  const size_t bitmap = (padded + padded / 32 + 4) * 4;
+  const size_t ranked = (size_t)pl.k_eff * 4;                // written over the bitmap once it is in registers
+  return bitmap > ranked ? bitmap : ranked;
 }
 
 hipError_t launch_cand_topk(const Plan& pl, int n_query, const uint2* cand, const uint32_t* ccount,
@@ -291,10 +512,11 @@ hipError_t launch_cand_topk(const Plan& pl, int n_query, const uint2* cand, cons
   a.n_mid = pl.n_mid; a.index_base = (int32_t)pl.s_eff; a.idx = idx; a.redo = redo;
   const size_t lds = cand_topk_lds(pl);
   // set on every launch: the attribute belongs to the current device, and nothing is remembered between calls
-  hipError_t e = hipFuncSetAttribute((const void*)cand_topk_kernel,
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  constexpr int kRegs = 40;                               // segments of up to 10,240 candidates stay in registers
+  auto kern = cap <= 256u * kRegs ? cand_topk_reg_kernel<kRegs> : cand_topk_kernel;
+  hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(cand_topk_kernel, dim3(n_query, pl.Hkv), dim3(256), lds, st, a);
+  hipLaunchKernelGGL(kern, dim3(n_query, pl.Hkv), dim3(256), lds, st, a);
   return hipGetLastError();
 }
 

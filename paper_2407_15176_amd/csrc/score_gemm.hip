@@ -212,17 +212,22 @@ __global__ __launch_bounds__(kGemmThreads) void score_gemm_kernel(GemmArgs a) {
       }
     }
   };
-  auto test_stage_row = [&](int r, uint32_t& mask) {        // 4 staged scores of this lane against its threshold
+  // 4 staged scores of this lane against its threshold.  score >= thr <=> the sign bit of (score - thr) is
+  // clear (the difference of equal finite values is +0), and v_alignbit shifts that bit into the running
+  // word: two vector instructions per score and no condition registers, so the tests slot freely between
+  // the MFMAs.  After all eight rows, row-major, score n sits at bit 31 - n, inverted: see hits_of().
+  auto test_stage_row = [&](int r, uint32_t& word) {
     const float4 v = stage[r * 64 + lane];
     const float th = thr[r >> 2];
-    mask |= ((v.x >= th ? 1u : 0u) | (v.y >= th ? 2u : 0u) | (v.z >= th ? 4u : 0u) |
-             (v.w >= th ? 8u : 0u)) << (r * 4);
+    word = __builtin_amdgcn_alignbit(word, __float_as_uint(v.x - th), 31);
+    word = __builtin_amdgcn_alignbit(word, __float_as_uint(v.y - th), 31);
+    word = __builtin_amdgcn_alignbit(word, __float_as_uint(v.z - th), 31);
+    word = __builtin_amdgcn_alignbit(word, __float_as_uint(v.w - th), 31);
   };
-
-  if (MODE == kFilter) {                          // NaN passes no threshold: tile 0 has no predecessor
-    const float nan = __builtin_nanf("");
+  auto hits_of = [](uint32_t word) -> uint32_t { return __brev(~word); };   // bit qb*16 + i for acc[qb][i]
+  if (MODE == kFilter) {                          // tile 0 has no predecessor: its test result is discarded
 #pragma unroll
-    for (int j = 0; j < 8; ++j) stage[j * 64 + lane] = make_float4(nan, nan, nan, nan);
+    for (int j = 0; j < 8; ++j) stage[j * 64 + lane] = make_float4(0.f, 0.f, 0.f, 0.f);
   }
   if (n_tiles > 0) {
     load_tile(tile0, stg);
@@ -266,9 +271,10 @@ __global__ __launch_bounds__(kGemmThreads) void score_gemm_kernel(GemmArgs a) {
 #pragma unroll
         for (int m = 0; m < 4; ++m) {
           __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // one MFMA
-          __builtin_amdgcn_sched_group_barrier(0x002, 6, 0);  // six vector ALU instructions
+          __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);  // four vector ALU instructions (two scores)
         }
       }
+      mask = t > 0 ? hits_of(mask) : 0u;
       if (qw == 1) append_hits(tile0 + t - 1, mask);
     }
 #pragma unroll
@@ -288,10 +294,18 @@ __global__ __launch_bounds__(kGemmThreads) void score_gemm_kernel(GemmArgs a) {
         const int qi = q0 + (qw * 2 + qb) * 32 + ln;
         if (qi < a.M) {
           float* orow = a.scores + ((int64_t)qi * a.Hkv + h) * a.score_stride;
+          // a lane holds four consecutive keys per group: one 16-byte store where the row layout allows it
+          const bool vec = (a.score_stride & 3) == 0 && ((uintptr_t)a.scores & 15) == 0;
 #pragma unroll
-          for (int i = 0; i < 16; ++i) {
-            const int64_t key = key_blk + (i >> 2) * 8 + (i & 3);
-            if (key < a.n_keys) orow[key] = acc[qb][i];
+          for (int j = 0; j < 4; ++j) {
+            const int64_t key = key_blk + j * 8;
+            if (vec && key + 3 < a.n_keys) {
+              *(float4*)(orow + key) = make_float4(acc[qb][4 * j], acc[qb][4 * j + 1], acc[qb][4 * j + 2], acc[qb][4 * j + 3]);
+            } else {
+#pragma unroll
+              for (int c = 0; c < 4; ++c)
+                if (key + c < a.n_keys) orow[key + c] = acc[qb][4 * j + c];
+            }
           }
         }
       }
@@ -316,7 +330,7 @@ __global__ __launch_bounds__(kGemmThreads) void score_gemm_kernel(GemmArgs a) {
       uint32_t mask = 0;
 #pragma unroll
       for (int r = 0; r < 8; ++r) test_stage_row(r, mask);
-      append_hits(tile0 + n_tiles - 1, mask);
+      append_hits(tile0 + n_tiles - 1, hits_of(mask));
     }
     __syncthreads();
     if (tid < kTileQ && q0 + tid < a.M) a.ccount[(int64_t)h * a.M + q0 + tid] = lcount[tid];

@@ -277,6 +277,33 @@ def test_prefill_chunk_mixed_redo_rows():
     P.check_layer(w, t, out, idx, q_rows=[0, 3, 4, 65, 66, 69])
 
 
+def test_prefill_chunk_exact_ties_straddle_the_kth_score():
+    """Runs of identical keys in the middle: their scores tie bit for bit on the GPU and exactly in the
+    oracle, and in some rows such a run straddles the k-th score, so the candidates' radix select has
+    to end on the key index.  Within a run the chosen members must be its lowest indices."""
+    w = wl.CONFIGS[4].scaled(n_ctx=30_000, n_query=48, n_local=400, top_k=300)
+    t = gen(w)
+    g = torch.Generator().manual_seed(7)
+    runs = []
+    for r in range(24):
+        start = w.n_sink + 500 + 1_150 * r
+        src = int(torch.randint(w.n_sink, w.n_ctx - w.n_local, (1,), generator=g))
+        t["k"][:, start:start + 64] = t["k"][:, src:src + 1]
+        runs.append(start)
+    out, idx = P.run_layer(w, t)
+    P.check_layer(w, t, out, idx, q_rows=list(range(0, 48, 5)))
+    idx_h = idx.cpu().numpy()
+    partial = 0
+    for i in range(idx_h.shape[0]):
+        for h in range(idx_h.shape[1]):
+            row = idx_h[i, h]
+            for start in runs:
+                inside = row[(row >= start) & (row < start + 64)]
+                assert np.array_equal(inside, np.arange(start, start + inside.size)), (i, h, start, inside)
+                partial += 0 < inside.size < 64
+    assert partial > 0            # the case the test is for did occur
+
+
 @pytest.mark.parametrize("kw", [
     dict(n_q_heads=8, n_kv_heads=8, n_query=33, n_ctx=6_000, n_local=100, top_k=37),      # G = 1
     dict(n_q_heads=4, n_kv_heads=2, n_query=20, n_ctx=5_000, n_local=64, top_k=200),      # G = 2
