@@ -132,8 +132,12 @@ __global__ __launch_bounds__(256) void sample_threshold_kernel(const float* __re
 #pragma unroll
   for (int r = 0; r < R; ++r) {
     const uint32_t j = (uint32_t)r * 256u + threadIdx.x;
-    key[r] = j < n ? score_key(row[j]) : 0u;
-    if (j < n) { kmin = min(kmin, key[r]); kmax = max(kmax, key[r]); }
+    key[r] = __float_as_uint(row[j < n ? j : n - 1]);        // clamped, not predicated: all loads go out before the first wait
+  }
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    key[r] = score_key(__uint_as_float(key[r]));
+    if ((uint32_t)r * 256u + threadIdx.x < n) { kmin = min(kmin, key[r]); kmax = max(kmax, key[r]); }
   }
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) {
@@ -145,7 +149,23 @@ __global__ __launch_bounds__(256) void sample_threshold_kernel(const float* __re
   kmin = min(min(sh[34], sh[35]), min(sh[36], sh[37]));
   kmax = max(max(sh[30], sh[31]), max(sh[32], sh[33]));
   __syncthreads();
-  int dsh = 32 - __clz((int)(kmax - kmin));
+  // The rho-th largest of a few thousand samples lies in the top few percent, so the select is run on a
+  // window below the maximum: keys down to an eighth of the largest score (three exponent steps; the
+  // ordered key of a positive float is its bit pattern with the sign set).  Over the whole row the first
+  // digits are sign and exponent, which put thousands of samples into a handful of bins: LDS atomics on
+  // one address serialise, and that was most of this kernel's time.  A row whose window holds fewer than
+  // rho samples (outliers far above the bulk) falls back to the whole range.
+  uint32_t cut = kmin;
+  if (kmax >= 0x80000000u + (4u << 23)) {
+    const uint32_t c = kmax - (3u << 23);
+    uint32_t in = 0;
+#pragma unroll
+    for (int r = 0; r < R; ++r) in += ((uint32_t)r * 256u + threadIdx.x < n && key[r] >= c) ? 1u : 0u;
+    uint32_t total;
+    block_scan_incl<256>(in, sh, total);
+    if (total >= rho) cut = c;                                 // workgroup-uniform
+  }
+  int dsh = 32 - __clz((int)(kmax - cut));
   uint32_t dpref = 0, remaining = rho;
   for (int p = 0; p < 2 && dsh > 0; ++p) {
     const int w = dsh < 11 ? dsh : 11;
@@ -155,8 +175,8 @@ __global__ __launch_bounds__(256) void sample_threshold_kernel(const float* __re
     const int up = dsh + w;
 #pragma unroll
     for (int r = 0; r < R; ++r) {
-      if ((uint32_t)r * 256u + threadIdx.x < n) {
-        const uint32_t d = key[r] - kmin;
+      if ((uint32_t)r * 256u + threadIdx.x < n && key[r] >= cut) {
+        const uint32_t d = key[r] - cut;
         if (up >= 32 || (d >> up) == dpref) atomicAdd(&bins[bslot((int)((d >> dsh) & ((1u << w) - 1u)))], 1u);
       }
     }
@@ -169,7 +189,7 @@ __global__ __launch_bounds__(256) void sample_threshold_kernel(const float* __re
   }
   if (threadIdx.x == 0) {
     // smallest key that shares the decided prefix: a lower bound of the rho-th largest
-    const uint32_t k = kmin + (dsh >= 32 ? 0u : (dpref << dsh));
+    const uint32_t k = cut + (dsh >= 32 ? 0u : (dpref << dsh));
     const uint32_t u = (k & 0x80000000u) ? (k & 0x7fffffffu) : ~k;
     thr[(int64_t)h * M + i] = __uint_as_float(u);
   }
@@ -260,7 +280,7 @@ __global__ __launch_bounds__(256, 3) void cand_topk_reg_kernel(CandArgs a) {
 #pragma unroll
   for (int r = 0; r < R; ++r) {
     const uint32_t j = (uint32_t)r * 256u + threadIdx.x;
-    const uint2 c = j < a.cap ? seg[j] : make_uint2(0u, 0u);
+    const uint2 c = seg[j < a.cap ? j : a.cap - 1];           // clamped, not predicated: all loads go out before the first wait
     key[r] = c.x; pos[r] = c.y;
   }
   const uint32_t n = a.ccount[row];

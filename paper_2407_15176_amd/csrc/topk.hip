@@ -239,6 +239,154 @@ __global__ __launch_bounds__(256) void topk_emit_kernel(
   }
 }
 
+// ---- one workgroup per row: select + refine + emit without leaving the CU ----------------
+// For rows of up to kRowMax scores (contexts up to ~64K tokens) the three kernels above are
+// mostly launch gaps and dependent trips to memory (past that size one CU cannot pull a row
+// fast enough and the chip-wide select pass wins): a whole row's bitmap (8 KiB) and its
+// pivot-bin candidates fit one workgroup's LDS, so one workgroup reads the row once (entries
+// above the pivot bin go to the LDS bitmap through wave ballots, entries in it to an LDS list
+// of composites), resolves the pivot bin with the same 11-bit radix passes, and ranks the
+// bitmap into the ascending index list, which leaves in 16-byte rows.  Rows whose pivot bin
+// holds more than kRowCand entries (degenerate score distributions) keep what fits in LDS and
+// re-read the rest from the scores on every pass: slower, same result.
+constexpr int kRowMax = 65536;                    // scores per row the fused kernel takes
+constexpr int kRowCand = 8192;                    // pivot-bin entries cached in LDS (64 KiB)
+constexpr int kRowThreads = 1024;
+constexpr size_t kRowLds = (size_t)kRowMax / 8 + (size_t)kRowCand * 8 + 2048 * 4;
+
+__global__ __launch_bounds__(kRowThreads) void topk_row_kernel(
+    const float* __restrict__ scores, int64_t n_mid, const uint32_t* __restrict__ hist, uint32_t k,
+    int32_t index_base, int32_t* idx, int k_eff) {
+  extern __shared__ uint64_t row_lds[];
+  uint64_t* cand = row_lds;                                   // [kRowCand] composites; later the ranked indices
+  uint32_t* bitmap = (uint32_t*)(row_lds + kRowCand);         // [kRowMax / 32]
+  uint32_t* bins = bitmap + kRowMax / 32;                     // [2048]
+  __shared__ uint32_t sh[40];
+  __shared__ uint32_t s_ncand;
+  const int row = blockIdx.x;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const float* sc = scores + (int64_t)row * n_mid;
+  const int n = (int)n_mid;
+  const int nwords = (n + 31) / 32;
+  const int nwords_pad = (nwords + kRowThreads - 1) / kRowThreads * kRowThreads;
+  if (threadIdx.x == 0) s_ncand = 0;
+  uint32_t pbin, above;
+  find_kth_bin<kRowThreads, kHistBins>(hist + (int64_t)row * kHistBins, k, sh, pbin, above);
+  const uint32_t need = k - above;                            // entries of the pivot bin that are selected
+  for (int w = nwords + threadIdx.x; w < nwords_pad; w += kRowThreads) bitmap[w] = 0;   // words past the row
+
+  // one pass over the row: a wave takes 64 consecutive positions per load, 16 loads in flight
+  constexpr int U = 16;
+  for (int base = wave * 64 * U; base < n; base += (kRowThreads / 64) * 64 * U) {
+    float v[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int pos = base + u * 64 + lane;
+      v[u] = sc[pos < n ? pos : n - 1];                          // clamped, not predicated: the loads go out together
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int p0 = base + u * 64;
+      if (p0 >= n) break;                                      // wave-uniform
+      const int pos = p0 + lane;
+      const uint32_t key = score_key(v[u]);
+      const uint32_t bin = key >> kKeyShift;
+      const bool valid = pos < n;
+      const uint64_t take = __ballot(valid && bin > pbin);
+      const bool is_cand = valid && bin == pbin;
+      const uint64_t cm = __ballot(is_cand);
+      if (lane == 0) ((uint64_t*)bitmap)[p0 >> 6] = take;
+      if (cm) {
+        uint32_t at = 0;
+        if (lane == 0) at = atomicAdd(&s_ncand, (uint32_t)__popcll(cm));
+        at = __shfl((int)at, 0, 64) + (uint32_t)__popcll(cm & ((1ull << lane) - 1ull));
+        if (is_cand && at < (uint32_t)kRowCand)
+          cand[at] = ((uint64_t)(key & ((1u << kKeyShift) - 1u)) << 32) | (uint64_t)(0xffffffffu - (uint32_t)pos);
+      }
+    }
+  }
+  __syncthreads();
+  const uint32_t ncand = s_ncand;
+  const uint32_t ncached = ncand < (uint32_t)kRowCand ? ncand : (uint32_t)kRowCand;
+  const bool spill = ncand > (uint32_t)kRowCand;              // workgroup-uniform
+  // every pivot-bin entry once: the cached ones from LDS; on a spill, all of them from the scores
+  auto for_each_cand = [&](auto&& f) {
+    if (!spill) {
+      for (uint32_t i = threadIdx.x; i < ncached; i += kRowThreads) f(cand[i]);
+    } else {
+      for (int pos = threadIdx.x; pos < n; pos += kRowThreads) {
+        const uint32_t key = score_key(sc[pos]);
+        if ((key >> kKeyShift) == pbin)
+          f(((uint64_t)(key & ((1u << kKeyShift) - 1u)) << 32) | (uint64_t)(0xffffffffu - (uint32_t)pos));
+      }
+    }
+  };
+  int shift = 0;
+  uint64_t prefix = 0;                                        // winners: composite >> shift >= prefix
+  if (need < ncand) {
+    shift = kKeyShift + 32;
+    uint32_t remaining = need;
+    while (shift > 0) {
+      const int w = shift < 11 ? shift : 11;
+      shift -= w;
+      for (int b = threadIdx.x; b < 2048; b += kRowThreads) bins[b] = 0;
+      __syncthreads();
+      for_each_cand([&](uint64_t cv) {
+        if ((cv >> (shift + w)) == prefix) atomicAdd(&bins[(uint32_t)(cv >> shift) & ((1u << w) - 1u)], 1u);
+      });
+      __syncthreads();
+      uint32_t d, ab;
+      find_kth_bin<kRowThreads, 2048>(bins, remaining, sh, d, ab);
+      const uint32_t in_bin = bins[d];
+      remaining -= ab;
+      prefix = (prefix << w) | d;
+      __syncthreads();
+      if (in_bin == remaining) break;                          // every entry sharing this prefix is selected
+    }
+  }
+  if (need > 0)
+    for_each_cand([&](uint64_t cv) {
+      if ((cv >> shift) >= prefix) {
+        const uint32_t pos = 0xffffffffu - (uint32_t)cv;
+        atomicOr(&bitmap[pos >> 5], 1u << (pos & 31));
+      }
+    });
+  __syncthreads();
+  // ordered compaction: thread t owns words [t*wpt, (t+1)*wpt), wpt <= 2
+  const int wpt = nwords_pad / kRowThreads;
+  uint32_t word[kRowMax / 32 / kRowThreads];
+  uint32_t mine = 0;
+#pragma unroll
+  for (int w = 0; w < kRowMax / 32 / kRowThreads; ++w) {
+    word[w] = w < wpt ? bitmap[threadIdx.x * wpt + w] : 0u;
+    mine += __popc(word[w]);
+  }
+  uint32_t total;
+  uint32_t at = block_scan_incl<kRowThreads>(mine, sh, total) - mine;
+  int32_t* out = idx + (int64_t)row * k_eff;
+  const bool staged = (size_t)k_eff * 4 <= (size_t)kRowCand * 8;   // the candidate list is spent: it stages the indices
+  int32_t* dst = staged ? (int32_t*)cand : out;
+#pragma unroll
+  for (int w = 0; w < kRowMax / 32 / kRowThreads; ++w) {
+    uint32_t bits = word[w];
+    const int32_t first = index_base + (threadIdx.x * wpt + w) * 32;
+    while (bits) {
+      const int b = __ffs((int)bits) - 1;
+      bits &= bits - 1;
+      if (at < (uint32_t)k_eff) dst[at] = first + b;
+      ++at;
+    }
+  }
+  if (staged) {
+    __syncthreads();
+    if ((k_eff & 3) == 0 && ((uintptr_t)idx & 15) == 0) {
+      for (int j = threadIdx.x; j < k_eff / 4; j += kRowThreads) ((int4*)out)[j] = ((const int4*)dst)[j];
+    } else {
+      for (int j = threadIdx.x; j < k_eff; j += kRowThreads) out[j] = dst[j];
+    }
+  }
+}
+
 }  // namespace
 
 hipError_t launch_topk(const Plan& pl, int rows, const float* scores, bool hist_ready,
@@ -254,6 +402,14 @@ hipError_t launch_topk(const Plan& pl, int rows, const float* scores, bool hist_
   const uint32_t k = (uint32_t)pl.k_eff;
   if (!hist_ready)
     hipLaunchKernelGGL(topk_hist_kernel, per_chunk, dim3(256), 0, st, scores, pl.n_mid, hist);
+  if (pl.n_mid <= kRowMax) {                        // short rows: one workgroup does the whole row
+    hipError_t e = hipFuncSetAttribute((const void*)topk_row_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)kRowLds);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(topk_row_kernel, dim3(rows), dim3(kRowThreads), kRowLds, st, scores, pl.n_mid, hist, k,
+                       (int32_t)pl.s_eff, idx, pl.k_eff);
+    return hipGetLastError();
+  }
   hipLaunchKernelGGL(topk_select_kernel, per_chunk, dim3(256), 0, st, scores, pl.n_mid, hist, k,
                      ncand, cand, bitmap, pl.nwords, cnt, pl.nchunks);
   hipLaunchKernelGGL(topk_refine_kernel, dim3(rows), dim3(1024), kRefineLds, st, scores, pl.n_mid,

@@ -95,7 +95,10 @@ def _topk_case(scores_np: np.ndarray, k: int, n_sink=4, n_local=16):
 
 
 @pytest.mark.parametrize("n_mid,k", [(20_000, 300), (8_192, 1), (8_193, 8_193), (100, 7),
-                                     (70_001, 4_096), (300_000, 8_192)])
+                                     (70_001, 4_096), (300_000, 8_192),
+                                     # either side of the longest row one workgroup takes whole; an index
+                                     # list longer than its LDS stage; a row shorter than one wave
+                                     (65_536, 4_096), (65_537, 4_096), (60_000, 20_000), (37, 37)])
 def test_topk_random_rows_exact(n_mid, k):
     r = np.random.default_rng(n_mid + k)
     _topk_case((r.standard_normal((3, n_mid)) * 37.0).astype(np.float32), k)
