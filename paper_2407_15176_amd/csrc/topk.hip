@@ -66,7 +66,7 @@ __global__ __launch_bounds__(256) void topk_select_kernel(
 #pragma unroll
   for (int j = 0; j < 32; ++j) {
     const int64_t pos = wbase + j * 64 + lane;
-    v[j] = pos < n_mid ? sc[pos] : 0.f;
+    v[j] = sc[pos < n_mid ? pos : n_mid - 1];      // clamped, not predicated: a predicated load waits for the one before it
   }
   uint32_t pbin, above;
   find_kth_bin<256, kHistBins>(hist + (int64_t)row * kHistBins, k, sh, pbin, above);
