@@ -408,8 +408,21 @@ def decode_token_leg(steps: int, n_layers: int = 32) -> dict:
                 B.decode_token(p, qs, kn, vn, kcs, vcs, ws, outs=outs, vote=vote)
             torch.cuda.synchronize()
             ms = (time.perf_counter() - t0) * 1e3 / steps
+            # the same call captured once into a HIP graph and replayed (the library only enqueues kernels)
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                B.decode_token(p, qs, kn, vn, kcs, vcs, ws, outs=outs, vote=vote)
+            graph.replay()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(steps):
+                graph.replay()
+            torch.cuda.synchronize()
+            gms = (time.perf_counter() - t0) * 1e3 / steps
+            del graph
             row[name] = {"ms_per_token": round(ms, 3), "tokens_per_s": round(1e3 / ms, 1),
-                         "kv_scan_GBps": round(n_layers * w.scan_bytes / (ms * 1e-3) / 1e9, 1)}
+                         "kv_scan_GBps": round(n_layers * w.scan_bytes / (ms * 1e-3) / 1e9, 1),
+                         "graph_replay_ms_per_token": round(gms, 3)}
         rows.append(row)
         del kcs, vcs
         torch.cuda.empty_cache()
