@@ -156,11 +156,11 @@ int attend_cache(const Plan& pl, const Ws& w, char* ws, const void* q, const voi
 inline void mark(hipEvent_t* ev, int i, hipStream_t st) { if (ev) (void)hipEventRecord(ev[i], st); }
 
 int select_tile(const Plan& pl, const Ws& w, const void* q, int q0, int nq, const void* k_cache,
-                int32_t* idx_all, bool rope_too, hipEvent_t* ev, hipStream_t st) {
+                int32_t* idx_all, bool rope_too, hipEvent_t* ev, hipStream_t st, const AppendJob* append = nullptr) {
   const int rows = nq * pl.Hkv;
   const size_t eb = (size_t)elem_bytes(pl.dtype);
   const char* qt = (const char*)q + (size_t)q0 * pl.Hq * pl.D * eb;
-  int rc = hip_rc(launch_prep(pl, pl.k_eff > 0 ? rows : 0, w.hist, rope_too ? w.rope : nullptr, st));
+  int rc = hip_rc(launch_prep(pl, pl.k_eff > 0 ? rows : 0, w.hist, rope_too ? w.rope : nullptr, st, append));
   mark(ev, 1, st);
   if (rc || pl.k_eff == 0) { mark(ev, 2, st); mark(ev, 3, st); return rc; }
   rc = hip_rc(launch_score_scan(pl, qt, nq, k_cache, w.scores, w.hist, st));
@@ -202,7 +202,7 @@ int fused_prefill_select(const Plan& pl, const Ws& w, char* ws, const void* q, c
 
 int run_layer(const reattn_params* p, bool decode_only, const void* q, const void* k_cache,
               const void* v_cache, int32_t* idx_out, float* out, void* ws, size_t ws_bytes,
-              void* stream, hipEvent_t* ev = nullptr, bool rope_ready = false) {
+              void* stream, hipEvent_t* ev = nullptr, bool rope_ready = false, const AppendJob* append = nullptr) {
   Plan pl;
   int rc = make_plan(p, &pl);
   if (rc) return rc;
@@ -217,6 +217,11 @@ int run_layer(const reattn_params* p, bool decode_only, const void* q, const voi
   int32_t* idx = idx_out ? idx_out : w.idx;
   mark(ev, 0, st);
   if (pl.fused_prefill) {
+    if (append) {                                      // not the decode shape: the rows go in with a launch of their own
+      rc = hip_rc(launch_cache_append(pl, append->first_tok, append->n_tok, append->k_new, append->v_new,
+                                      append->k_cache, append->v_cache, st));
+      if (rc) return rc;
+    }
     rc = fused_prefill_select(pl, w, (char*)ws, q, k_cache, idx, ev, st);
     if (rc) return rc;
     rc = attend_cache(pl, w, (char*)ws, q, k_cache, v_cache, idx, out, st);
@@ -225,7 +230,7 @@ int run_layer(const reattn_params* p, bool decode_only, const void* q, const voi
   }
   for (int q0 = 0; q0 < pl.M; q0 += pl.m_tile) {
     const int nq = pl.M - q0 < pl.m_tile ? pl.M - q0 : pl.m_tile;
-    rc = select_tile(pl, w, q, q0, nq, k_cache, idx, q0 == 0 && !rope_ready, ev, st);
+    rc = select_tile(pl, w, q, q0, nq, k_cache, idx, q0 == 0 && !rope_ready, ev, st, q0 == 0 ? append : nullptr);
     if (rc) return rc;
   }
   rc = attend_cache(pl, w, (char*)ws, q, k_cache, v_cache, idx, out, st);
@@ -732,11 +737,15 @@ extern "C" int reattn_decode_token(const reattn_params* p, const reattn_vote* v,
       return REATTN_ERR_ALIGN;
   }
   for (int l = 0; l < n_layers && !rc; ++l) {
-    rc = hip_rc(launch_cache_append(pl, pl.N - 1, 1, k_new[l], v_new[l], k_cache[l], v_cache[l], (hipStream_t)stream));
-    if (rc) break;
     // the rotary table depends on the scope's upper bound alone: the first layer's serves them all
-    rc = v ? vote_layer_impl(&pp, v, q[l], k_cache[l], v_cache[l], nullptr, nullptr, out[l], ws, ws_bytes, stream, nullptr, l > 0)
-           : run_layer(&pp, true, q[l], k_cache[l], v_cache[l], nullptr, out[l], ws, ws_bytes, stream, nullptr, l > 0);
+    if (v) {
+      rc = hip_rc(launch_cache_append(pl, pl.N - 1, 1, k_new[l], v_new[l], k_cache[l], v_cache[l], (hipStream_t)stream));
+      if (rc) break;
+      rc = vote_layer_impl(&pp, v, q[l], k_cache[l], v_cache[l], nullptr, nullptr, out[l], ws, ws_bytes, stream, nullptr, l > 0);
+    } else {                                           // the token's rows ride along with the layer's first launch
+      const AppendJob job{k_new[l], v_new[l], k_cache[l], v_cache[l], pl.N - 1, 1};
+      rc = run_layer(&pp, true, q[l], k_cache[l], v_cache[l], nullptr, out[l], ws, ws_bytes, stream, nullptr, l > 0, &job);
+    }
   }
   return rc;
 }

@@ -43,7 +43,15 @@ struct Plan {
 
 // ---- host-side launchers (one per .hip file) -------------------------------
 hipError_t launch_fill_u32(uint32_t* p, int64_t n, uint32_t v, hipStream_t st);
-hipError_t launch_prep(const Plan& pl, int rows, uint32_t* hist, float2* rope, hipStream_t st);
+// rows of a token-major [n_tok][Hkv][D] block on their way into a head-major cache, in 16-byte pieces
+struct AppendJob {
+  const void* k_new; const void* v_new; void* k_cache; void* v_cache;
+  int64_t first_tok; int n_tok;
+};
+// clears `rows` first-digit histograms, fills the rotary table and copies the appended rows (each part optional):
+// the small jobs that precede a layer's scan share one launch
+hipError_t launch_prep(const Plan& pl, int rows, uint32_t* hist, float2* rope, hipStream_t st,
+                       const AppendJob* append = nullptr);
 hipError_t launch_cache_append(const Plan& pl, int64_t first_tok, int n_tok, const void* k_new, const void* v_new,
                                void* k_cache, void* v_cache, hipStream_t st);
 hipError_t launch_score_scan(const Plan& pl, const void* q, int n_query, const void* k_cache,

@@ -18,12 +18,29 @@
 namespace reattn {
 namespace {
 
-__global__ __launch_bounds__(256) void prep_kernel(uint32_t* hist, int64_t n_hist,
+struct AppendArgs {
+  const u32x4* k_new; const u32x4* v_new; char* k_cache; char* v_cache;
+  int64_t first_tok, n_vec, ksh_b, kst_b, vsh_b, vst_b;
+  int Hkv, vec_per_row;
+};
+
+// piece i of a token-major block: row i / vec_per_row = t * Hkv + h
+__device__ __forceinline__ void append_piece(const AppendArgs& a, int64_t i) {
+  const int piece = (int)(i % a.vec_per_row);
+  const int64_t row = i / a.vec_per_row;
+  const int h = (int)(row % a.Hkv);
+  const int64_t t = row / a.Hkv;
+  *(u32x4*)(a.k_cache + h * a.ksh_b + (a.first_tok + t) * a.kst_b + piece * 16) = a.k_new[i];
+  *(u32x4*)(a.v_cache + h * a.vsh_b + (a.first_tok + t) * a.vst_b + piece * 16) = a.v_new[i];
+}
+
+__global__ __launch_bounds__(256) void prep_kernel(uint32_t* hist, int64_t n_hist, AppendArgs ap,
                                                    float2* rope, int S, int half, int D,
                                                    double log2_theta) {
   const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (i < n_hist) { hist[i] = 0u; return; }
-  const int64_t j = i - n_hist;
+  if (i < n_hist + ap.n_vec) { append_piece(ap, i - n_hist); return; }
+  const int64_t j = i - n_hist - ap.n_vec;
   const int n_hi = rope_rows_hi(S);
   if (rope && j < (int64_t)(n_hi + kRopeLo) * half) {
     const int row = (int)(j / half), c = (int)(j % half);
@@ -103,42 +120,49 @@ __global__ __launch_bounds__(256) void gather_rope_kernel(GatherArgs a) {
 
 // Appends the rows of n_tok new tokens, delivered token-major [n_tok][Hkv][D] (as the projections
 // produce them), to the head-major cache: cache[h][first_tok + t][:] = new[t][h][:].  16 bytes per thread.
-__global__ __launch_bounds__(256) void cache_append_kernel(const u32x4* __restrict__ k_new, const u32x4* __restrict__ v_new,
-                                                           char* k_cache, char* v_cache, int64_t first_tok,
-                                                           int64_t n_vec, int Hkv, int vec_per_row,
-                                                           int64_t ksh_b, int64_t kst_b, int64_t vsh_b, int64_t vst_b) {
+__global__ __launch_bounds__(256) void cache_append_kernel(AppendArgs a) {
   const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (i >= n_vec) return;
-  const int piece = (int)(i % vec_per_row);
-  const int64_t row = i / vec_per_row;                 // t * Hkv + h
-  const int h = (int)(row % Hkv);
-  const int64_t t = row / Hkv;
-  *(u32x4*)(k_cache + h * ksh_b + (first_tok + t) * kst_b + piece * 16) = k_new[i];
-  *(u32x4*)(v_cache + h * vsh_b + (first_tok + t) * vst_b + piece * 16) = v_new[i];
+  if (i < a.n_vec) append_piece(a, i);
 }
 
+}  // namespace
+
+namespace {
+AppendArgs append_args(const Plan& pl, const AppendJob* j) {
+  AppendArgs a;
+  const int64_t eb = elem_bytes(pl.dtype);
+  a.k_new = nullptr; a.v_new = nullptr; a.k_cache = nullptr; a.v_cache = nullptr;
+  a.first_tok = 0; a.n_vec = 0;
+  a.Hkv = pl.Hkv; a.vec_per_row = (int)(pl.D * eb / 16);
+  a.ksh_b = pl.ksh * eb; a.kst_b = pl.kst * eb; a.vsh_b = pl.vsh * eb; a.vst_b = pl.vst * eb;
+  if (j && j->n_tok > 0) {
+    a.k_new = (const u32x4*)j->k_new; a.v_new = (const u32x4*)j->v_new;
+    a.k_cache = (char*)j->k_cache; a.v_cache = (char*)j->v_cache;
+    a.first_tok = j->first_tok; a.n_vec = (int64_t)j->n_tok * pl.Hkv * a.vec_per_row;
+  }
+  return a;
+}
 }  // namespace
 
 hipError_t launch_cache_append(const Plan& pl, int64_t first_tok, int n_tok, const void* k_new, const void* v_new,
                                void* k_cache, void* v_cache, hipStream_t st) {
   if (n_tok <= 0) return hipSuccess;
-  const int64_t eb = elem_bytes(pl.dtype);
-  const int vec_per_row = (int)(pl.D * eb / 16);
-  const int64_t n_vec = (int64_t)n_tok * pl.Hkv * vec_per_row;
-  hipLaunchKernelGGL(cache_append_kernel, dim3((unsigned)((n_vec + 255) / 256)), dim3(256), 0, st,
-                     (const u32x4*)k_new, (const u32x4*)v_new, (char*)k_cache, (char*)v_cache, first_tok, n_vec,
-                     pl.Hkv, vec_per_row, pl.ksh * eb, pl.kst * eb, pl.vsh * eb, pl.vst * eb);
+  const AppendJob j{k_new, v_new, k_cache, v_cache, first_tok, n_tok};
+  const AppendArgs a = append_args(pl, &j);
+  hipLaunchKernelGGL(cache_append_kernel, dim3((unsigned)((a.n_vec + 255) / 256)), dim3(256), 0, st, a);
   return hipGetLastError();
 }
 
-hipError_t launch_prep(const Plan& pl, int rows, uint32_t* hist, float2* rope, hipStream_t st) {
+hipError_t launch_prep(const Plan& pl, int rows, uint32_t* hist, float2* rope, hipStream_t st,
+                       const AppendJob* append) {
   if (!hist) rows = 0;
+  const AppendArgs ap = append_args(pl, append);
   const int64_t n_hist = (int64_t)rows * kHistBins;
   const int64_t n_rope = rope ? (int64_t)(rope_rows_hi(pl.S) + kRopeLo) * (pl.D / 2) : 0;
-  const int64_t n = n_hist + n_rope;
+  const int64_t n = n_hist + ap.n_vec + n_rope;
   if (n == 0) return hipSuccess;
   hipLaunchKernelGGL(prep_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st,
-                     hist, n_hist, rope, pl.S, pl.D / 2, pl.D, log2((double)pl.theta));
+                     hist, n_hist, ap, rope, pl.S, pl.D / 2, pl.D, log2((double)pl.theta));
   return hipGetLastError();
 }
 
