@@ -498,7 +498,8 @@ extern "C" int reattn_vote_merge(const reattn_params* p, const reattn_vote* v, c
 
 static int vote_layer_impl(const reattn_params* p, const reattn_vote* v, const void* q, const void* k_cache,
                            const void* v_cache, int32_t* sel_out, int32_t* n_sel_out, float* out, void* ws,
-                           size_t ws_bytes, void* stream, hipEvent_t* ev, bool rope_ready = false) {
+                           size_t ws_bytes, void* stream, hipEvent_t* ev, bool rope_ready = false,
+                           const AppendJob* append = nullptr) {
   VotePlan vp;
   int rc = make_vote_plan(p, v, &vp);
   if (rc) return rc;
@@ -513,9 +514,20 @@ static int vote_layer_impl(const reattn_params* p, const reattn_vote* v, const v
   int32_t* sel = sel_out ? sel_out : (int32_t*)(b + vp.off_sel);
   int32_t* n_sel = n_sel_out ? n_sel_out : (int32_t*)(b + vp.off_nsel);
   mark(ev, 0, st);
-  rc = vote_topk_impl(vp, q, k_cache, lists, b, st);
-  mark(ev, 1, st);
-  if (!rc) rc = vote_merge_impl(vp, lists, sel, n_sel, b, st);
+  if (vote_decode_applies(pl, vp.kk, vp.kc, vp.n_seq)) {
+    // a decode step: the scan, then one workgroup per sequence for lists + votes + spans (+ the appended rows)
+    int n_cand = 0;
+    rc = hip_rc(launch_vote_decode_scan(pl, q, k_cache, vp.kk, (uint64_t*)(b + vp.off_part), &n_cand, st));
+    mark(ev, 1, st);
+    if (!rc) rc = hip_rc(launch_vote_decode_merge(pl, (const uint64_t*)(b + vp.off_part), n_cand, vp.kk, vp.kc, vp.span,
+                                                  sel, n_sel, st, vp.n_seq, pl.k_eff > 0 ? pl.k_eff : 1, append));
+  } else {
+    if (append) rc = hip_rc(launch_cache_append(pl, append->first_tok, append->n_tok, append->k_new, append->v_new,
+                                                append->k_cache, append->v_cache, st));
+    if (!rc) rc = vote_topk_impl(vp, q, k_cache, lists, b, st);
+    mark(ev, 1, st);
+    if (!rc) rc = vote_merge_impl(vp, lists, sel, n_sel, b, st);
+  }
   mark(ev, 2, st);
   if (rc) return rc;
   float2* rope = (float2*)(b + vp.off_rope);
@@ -738,14 +750,10 @@ extern "C" int reattn_decode_token(const reattn_params* p, const reattn_vote* v,
   }
   for (int l = 0; l < n_layers && !rc; ++l) {
     // the rotary table depends on the scope's upper bound alone: the first layer's serves them all
-    if (v) {
-      rc = hip_rc(launch_cache_append(pl, pl.N - 1, 1, k_new[l], v_new[l], k_cache[l], v_cache[l], (hipStream_t)stream));
-      if (rc) break;
-      rc = vote_layer_impl(&pp, v, q[l], k_cache[l], v_cache[l], nullptr, nullptr, out[l], ws, ws_bytes, stream, nullptr, l > 0);
-    } else {                                           // the token's rows ride along with the layer's first launch
-      const AppendJob job{k_new[l], v_new[l], k_cache[l], v_cache[l], pl.N - 1, 1};
-      rc = run_layer(&pp, true, q[l], k_cache[l], v_cache[l], nullptr, out[l], ws, ws_bytes, stream, nullptr, l > 0, &job);
-    }
+    // the token's rows ride along with one of the layer's small launches
+    const AppendJob job{k_new[l], v_new[l], k_cache[l], v_cache[l], pl.N - 1, 1};
+    rc = v ? vote_layer_impl(&pp, v, q[l], k_cache[l], v_cache[l], nullptr, nullptr, out[l], ws, ws_bytes, stream, nullptr, l > 0, &job)
+           : run_layer(&pp, true, q[l], k_cache[l], v_cache[l], nullptr, out[l], ws, ws_bytes, stream, nullptr, l > 0, &job);
   }
   return rc;
 }

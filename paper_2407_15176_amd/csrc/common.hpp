@@ -103,6 +103,14 @@ void vote_merge_layout(const Plan& pl, int64_t n_votes, size_t* counts_bytes, si
 hipError_t launch_vote_merge(const Plan& pl, const int32_t* lists, int64_t n_rows, int kk, int kc, int span,
                              uint32_t* counts, int32_t* seg, uint64_t* comp, int32_t* sel, int32_t* n_sel,
                              hipStream_t st, int n_seq = 1, int64_t sel_stride = 0);
+// a decode step's selection in two launches: the fused score + per-head top-k scan, then one workgroup per
+// sequence that closes the per-head lists, counts the votes, expands the spans and copies the appended rows
+bool vote_decode_applies(const Plan& pl, int kk, int kc, int n_seq);
+hipError_t launch_vote_decode_scan(const Plan& pl, const void* q, const void* k_cache, int kk, uint64_t* part,
+                                   int* n_cand, hipStream_t st);
+hipError_t launch_vote_decode_merge(const Plan& pl, const uint64_t* part, int n_cand, int kk, int kc, int span,
+                                    int32_t* sel, int32_t* n_sel, hipStream_t st, int n_seq, int64_t sel_stride,
+                                    const AppendJob* append);
 
 bool attend_shared_applies(const Plan& pl);
 void attend_shared_layout(const Plan& pl, size_t* kp, size_t* vp, size_t* qp, size_t* part);
@@ -166,6 +174,36 @@ template <> struct Mm<true> {
   static __device__ __forceinline__ float widen(uint16_t h) { return f16_one(h); }
   static __device__ __forceinline__ uint16_t narrow(float x) { return __builtin_bit_cast(uint16_t, (_Float16)x); }
 };
+
+// Rows of a token-major [n_tok][Hkv][D] block on their way into a head-major cache, as kernels see them.
+struct AppendArgs {
+  const u32x4* k_new; const u32x4* v_new; char* k_cache; char* v_cache;
+  int64_t first_tok, n_vec, ksh_b, kst_b, vsh_b, vst_b;    // n_vec 16-byte pieces (0: nothing to append)
+  int Hkv, vec_per_row;
+};
+// piece i of the block: row i / vec_per_row = t * Hkv + h
+__device__ __forceinline__ void append_piece(const AppendArgs& a, int64_t i) {
+  const int piece = (int)(i % a.vec_per_row);
+  const int64_t row = i / a.vec_per_row;
+  const int h = (int)(row % a.Hkv);
+  const int64_t t = row / a.Hkv;
+  *(u32x4*)(a.k_cache + h * a.ksh_b + (a.first_tok + t) * a.kst_b + piece * 16) = a.k_new[i];
+  *(u32x4*)(a.v_cache + h * a.vsh_b + (a.first_tok + t) * a.vst_b + piece * 16) = a.v_new[i];
+}
+inline AppendArgs append_args(const Plan& pl, const AppendJob* j) {
+  AppendArgs a;
+  const int64_t eb = elem_bytes(pl.dtype);
+  a.k_new = nullptr; a.v_new = nullptr; a.k_cache = nullptr; a.v_cache = nullptr;
+  a.first_tok = 0; a.n_vec = 0;
+  a.Hkv = pl.Hkv; a.vec_per_row = (int)(pl.D * eb / 16);
+  a.ksh_b = pl.ksh * eb; a.kst_b = pl.kst * eb; a.vsh_b = pl.vsh * eb; a.vst_b = pl.vst * eb;
+  if (j && j->n_tok > 0) {
+    a.k_new = (const u32x4*)j->k_new; a.v_new = (const u32x4*)j->v_new;
+    a.k_cache = (char*)j->k_cache; a.v_cache = (char*)j->v_cache;
+    a.first_tok = j->first_tok; a.n_vec = (int64_t)j->n_tok * pl.Hkv * a.vec_per_row;
+  }
+  return a;
+}
 
 // Order-preserving image of an fp32 score: larger float <=> larger key.  -0 maps to +0's key.
 __device__ __forceinline__ uint32_t score_key(float x) {

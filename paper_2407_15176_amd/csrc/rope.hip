@@ -18,22 +18,6 @@
 namespace reattn {
 namespace {
 
-struct AppendArgs {
-  const u32x4* k_new; const u32x4* v_new; char* k_cache; char* v_cache;
-  int64_t first_tok, n_vec, ksh_b, kst_b, vsh_b, vst_b;
-  int Hkv, vec_per_row;
-};
-
-// piece i of a token-major block: row i / vec_per_row = t * Hkv + h
-__device__ __forceinline__ void append_piece(const AppendArgs& a, int64_t i) {
-  const int piece = (int)(i % a.vec_per_row);
-  const int64_t row = i / a.vec_per_row;
-  const int h = (int)(row % a.Hkv);
-  const int64_t t = row / a.Hkv;
-  *(u32x4*)(a.k_cache + h * a.ksh_b + (a.first_tok + t) * a.kst_b + piece * 16) = a.k_new[i];
-  *(u32x4*)(a.v_cache + h * a.vsh_b + (a.first_tok + t) * a.vst_b + piece * 16) = a.v_new[i];
-}
-
 __global__ __launch_bounds__(256) void prep_kernel(uint32_t* hist, int64_t n_hist, AppendArgs ap,
                                                    float2* rope, int S, int half, int D,
                                                    double log2_theta) {
@@ -125,23 +109,6 @@ __global__ __launch_bounds__(256) void cache_append_kernel(AppendArgs a) {
   if (i < a.n_vec) append_piece(a, i);
 }
 
-}  // namespace
-
-namespace {
-AppendArgs append_args(const Plan& pl, const AppendJob* j) {
-  AppendArgs a;
-  const int64_t eb = elem_bytes(pl.dtype);
-  a.k_new = nullptr; a.v_new = nullptr; a.k_cache = nullptr; a.v_cache = nullptr;
-  a.first_tok = 0; a.n_vec = 0;
-  a.Hkv = pl.Hkv; a.vec_per_row = (int)(pl.D * eb / 16);
-  a.ksh_b = pl.ksh * eb; a.kst_b = pl.kst * eb; a.vsh_b = pl.vsh * eb; a.vst_b = pl.vst * eb;
-  if (j && j->n_tok > 0) {
-    a.k_new = (const u32x4*)j->k_new; a.v_new = (const u32x4*)j->v_new;
-    a.k_cache = (char*)j->k_cache; a.v_cache = (char*)j->v_cache;
-    a.first_tok = j->first_tok; a.n_vec = (int64_t)j->n_tok * pl.Hkv * a.vec_per_row;
-  }
-  return a;
-}
 }  // namespace
 
 hipError_t launch_cache_append(const Plan& pl, int64_t first_tok, int n_tok, const void* k_new, const void* v_new,

@@ -459,19 +459,11 @@ __device__ __forceinline__ void centres_to_spans(int32_t* win, int nc, int32_t* 
 }
 
 // Up to NT votes and centres (a decode step: Hq * vote_k votes): everything in one workgroup, no vote array.
-// blockIdx.x is the sequence of a folded batch: its n_votes consecutive list entries, its own output row.
+// v: this thread's vote as a token of the middle, or -1.
 template <int NT>
-__global__ __launch_bounds__(NT) void vote_merge_small_kernel(const int32_t* __restrict__ lists, int n_votes,
-                                                              int64_t sel_stride, SpanArgs a) {
-  lists += (int64_t)blockIdx.x * n_votes;
-  a.sel += (int64_t)blockIdx.x * sel_stride;
-  a.n_sel += blockIdx.x;
-  __shared__ int32_t tok[NT], win[NT], sa[NT], sb[NT];
-  __shared__ uint64_t comp[NT];
-  __shared__ int32_t wsum[NT / 64];
+__device__ __forceinline__ void small_merge(int32_t v, int n_votes, const SpanArgs& a, int32_t* tok, int32_t* win,
+                                            int32_t* sa, int32_t* sb, uint64_t* comp, int32_t* wsum) {
   const int t = threadIdx.x;
-  int32_t v = t < n_votes ? lists[t] - a.s_eff : -1;
-  if (v < 0 || v >= a.n_mid) v = -1;                   // an entry outside the middle is no vote
   tok[t] = v;
   __syncthreads();
   uint32_t votes = 0;
@@ -493,6 +485,72 @@ __global__ __launch_bounds__(NT) void vote_merge_small_kernel(const int32_t* __r
   if (owner && rank < a.kc) win[rank] = v;             // composites are distinct: ranks are a permutation
   __syncthreads();
   centres_to_spans<NT>(win, n_owner < a.kc ? n_owner : a.kc, sa, sb, wsum, a);
+}
+
+// blockIdx.x is the sequence of a folded batch: its n_votes consecutive list entries, its own output row.
+template <int NT>
+__global__ __launch_bounds__(NT) void vote_merge_small_kernel(const int32_t* __restrict__ lists, int n_votes,
+                                                              int64_t sel_stride, SpanArgs a) {
+  lists += (int64_t)blockIdx.x * n_votes;
+  a.sel += (int64_t)blockIdx.x * sel_stride;
+  a.n_sel += blockIdx.x;
+  __shared__ int32_t tok[NT], win[NT], sa[NT], sb[NT];
+  __shared__ uint64_t comp[NT];
+  __shared__ int32_t wsum[NT / 64];
+  const int t = threadIdx.x;
+  int32_t v = t < n_votes ? lists[t] - a.s_eff : -1;
+  if (v < 0 || v >= a.n_mid) v = -1;                   // an entry outside the middle is no vote
+  small_merge<NT>(v, n_votes, a, tok, win, sa, sb, comp, wsum);
+}
+
+// A decode step's selection after the scan, in one workgroup per sequence: every wave closes the lists of
+// its heads (best vote_k of the n_cand composites the scan's workgroups left for the head), the votes are
+// counted and the spans expanded as above, and the rows of the token being decoded are copied into the
+// cache on the side (they are the last local entry: only the attention that follows reads them).
+constexpr int kDecodeCand = 512;        // composites per head the one-workgroup decode merge holds in registers
+
+// 1024 threads: sixteen waves close the lists side by side (a wave's reductions run one after another, and
+// with four waves the eight heads each of them got made this the longest kernel of the step after the scan).
+template <int NT>
+__global__ __launch_bounds__(NT) void vote_decode_merge_kernel(const uint64_t* __restrict__ part, int n_cand,
+                                                               int vote_k, int heads, int64_t sel_stride,
+                                                               SpanArgs a, AppendArgs ap) {
+  a.sel += (int64_t)blockIdx.x * sel_stride;
+  a.n_sel += blockIdx.x;
+  __shared__ int32_t tok[NT], win[NT], sa[NT], sb[NT];
+  __shared__ uint64_t comp[NT];
+  __shared__ int32_t wsum[NT / 64];
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  if (blockIdx.x == 0)
+    for (int64_t i = t; i < ap.n_vec; i += NT) append_piece(ap, i);
+  for (int h = wave; h < heads; h += NT / 64) {
+    const uint64_t* p = part + ((int64_t)blockIdx.x * heads + h) * n_cand;
+    uint64_t c[kDecodeCand / 64];                      // the head's composites, read once (clamped, then masked)
+#pragma unroll
+    for (int u = 0; u < kDecodeCand / 64; ++u) {
+      const int i = u * 64 + lane;
+      c[u] = p[i < n_cand ? i : n_cand - 1];
+    }
+#pragma unroll
+    for (int u = 0; u < kDecodeCand / 64; ++u) c[u] = u * 64 + lane < n_cand ? c[u] : 0ull;
+    uint64_t taken_below = ~0ull;                      // composites are distinct: walk down strictly
+    uint32_t mine = 0xffffffffu;
+    for (int round = 0; round < vote_k; ++round) {
+      uint64_t m = 0ull;
+#pragma unroll
+      for (int u = 0; u < kDecodeCand / 64; ++u)
+        if (c[u] < taken_below && c[u] > m) m = c[u];
+      const uint64_t best = wave_max_u64(m);
+      taken_below = best;
+      if (lane == round) mine = best ? 0xffffffffu - (uint32_t)best : 0xffffffffu;
+    }
+    if (lane < vote_k) sa[h * vote_k + lane] = (mine != 0xffffffffu && (int64_t)mine < a.n_mid) ? (int32_t)mine : -1;
+  }
+  __syncthreads();
+  const int n_votes = heads * vote_k;
+  const int32_t v = t < n_votes ? sa[t] : -1;
+  __syncthreads();                                     // sa is scratch of the span expansion from here on
+  small_merge<NT>(v, n_votes, a, tok, win, sa, sb, comp, wsum);
 }
 
 // More votes than one workgroup ranks by comparison: a dense vote array over the middle.
@@ -770,9 +828,10 @@ hipError_t mfma_launch_kt(const MfmaScanArgs& a, int kt, int nb, dim3 grid, hipS
 }
 
 // head_topk[i][hq][vote_k] for queries [0, n_query): ascending absolute indices.
-hipError_t launch_head_topk_scan(const Plan& pl, const void* q, int n_query, const void* k_cache,
-                                 int vote_k, uint64_t* part, int32_t* head_topk, hipStream_t st) {
-  if (pl.n_mid <= 0 || n_query <= 0 || vote_k <= 0) return hipSuccess;
+namespace {
+// The scan alone: every workgroup leaves its partial lists in `part`; *n_cand = composites per (query, head).
+hipError_t launch_head_scan(const Plan& pl, const void* q, int n_query, const void* k_cache, int vote_k,
+                            uint64_t* part, int* n_cand, hipStream_t st) {
   const int kt = vote_list_len(vote_k);
   const ScanGeom g = scan_geom(pl, n_query, kt);
   const dim3 grid((unsigned)(g.n_wg > 0 ? g.n_wg : 1), (unsigned)(pl.Hkv * g.n_pass));
@@ -794,9 +853,44 @@ hipError_t launch_head_topk_scan(const Plan& pl, const void* q, int n_query, con
     a.rows_per_block = g.rpb; a.n_wg = g.n_wg;
     e = scan_launch_kt<float, 64>(a, kt, grid, st);
   }
+  *n_cand = g.n_wg * kt;
+  return e;
+}
+}  // namespace
+
+hipError_t launch_head_topk_scan(const Plan& pl, const void* q, int n_query, const void* k_cache,
+                                 int vote_k, uint64_t* part, int32_t* head_topk, hipStream_t st) {
+  if (pl.n_mid <= 0 || n_query <= 0 || vote_k <= 0) return hipSuccess;
+  int n_cand = 0;
+  hipError_t e = launch_head_scan(pl, q, n_query, k_cache, vote_k, part, &n_cand, st);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(head_topk_merge_kernel, dim3((unsigned)(n_query * pl.Hq)), dim3(64), 0, st, part,
-                     g.n_wg * kt, vote_k, (int32_t)pl.s_eff, head_topk);
+                     n_cand, vote_k, (int32_t)pl.s_eff, head_topk);
+  return hipGetLastError();
+}
+
+bool vote_decode_applies(const Plan& pl, int kk, int kc, int n_seq) {
+  if (n_seq < 1) n_seq = 1;
+  if (!(pl.M == 1 && pl.n_mid > 0 && kk > 0 && kc > 0 && kc <= kMergeThreads && pl.Hq % n_seq == 0 &&
+        (int64_t)(pl.Hq / n_seq) * kk <= kMergeThreads))
+    return false;
+  const int kt = vote_list_len(kk);
+  return scan_geom(pl, 1, kt).n_wg * kt <= kDecodeCand;
+}
+
+hipError_t launch_vote_decode_scan(const Plan& pl, const void* q, const void* k_cache, int kk, uint64_t* part,
+                                   int* n_cand, hipStream_t st) {
+  return launch_head_scan(pl, q, 1, k_cache, kk, part, n_cand, st);
+}
+
+hipError_t launch_vote_decode_merge(const Plan& pl, const uint64_t* part, int n_cand, int kk, int kc, int span,
+                                    int32_t* sel, int32_t* n_sel, hipStream_t st, int n_seq, int64_t sel_stride,
+                                    const AppendJob* append) {
+  if (n_seq < 1) n_seq = 1;
+  SpanArgs a;
+  a.s_eff = (int32_t)pl.s_eff; a.n_mid = pl.n_mid; a.kc = kc; a.span = span; a.sel = sel; a.n_sel = n_sel;
+  hipLaunchKernelGGL(vote_decode_merge_kernel<kMergeThreads>, dim3((unsigned)n_seq), dim3(kMergeThreads), 0, st, part,
+                     n_cand, kk, pl.Hq / n_seq, sel_stride, a, append_args(pl, append));
   return hipGetLastError();
 }
 
