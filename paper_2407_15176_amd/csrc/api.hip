@@ -145,7 +145,7 @@ inline int hip_rc(hipError_t e) { return e == hipSuccess ? REATTN_OK : REATTN_ER
 // and KV head), everything else the flash-decoding kernel with its split-S combine.
 int attend_cache(const Plan& pl, const Ws& w, char* ws, const void* q, const void* k_cache,
                  const void* v_cache, const int32_t* idx, float* out, hipStream_t st) {
-  if (attend_prefill_applies(pl) && pl.M <= pl.l_eff)     // its shared local operands need the chunk inside the window
+  if (attend_prefill_applies(pl))                          // an empty middle (M > l) is the same walk: every slot is its own token
     return hip_rc(launch_attend_prefill(pl, q, k_cache, v_cache, idx, (float2*)(ws + pl.off_rope16),
                                         out, st));
   return hip_rc(launch_attend(pl, true, q, 0, pl.M, k_cache, v_cache, idx, w.rope, w.part, out, st));
