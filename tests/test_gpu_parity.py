@@ -258,6 +258,24 @@ def test_prefill_chunk_sampled_thresholds_larger_cache():
     P.check_layer(w, t, out, idx, q_rows=[0, 1, 63, 64, 127, 128, 129])
 
 
+def test_prefill_chunk_wide_candidate_segments():
+    """k large enough that a row's candidate segment (capacity > 10,240) does not fit the registers of the
+    candidate kernel: the kernel that re-reads the segment per radix pass takes over."""
+    w = wl.CONFIGS[4].scaled(n_ctx=70_000, n_query=20, n_local=512, top_k=8_000, max_position=0)
+    t = gen(w)
+    out, idx = P.run_layer(w, t)
+    P.check_layer(w, t, out, idx, q_rows=[0, 7, 19])
+
+
+def test_prefill_chunk_long_middle():
+    """A middle of more than 262,144 tokens: a thread of the candidate kernel owns more bitmap words than it
+    ranks out of registers (the indices are then ranked from LDS and written directly)."""
+    w = wl.CONFIGS[4].scaled(n_ctx=300_000, n_query=6, n_local=512, top_k=700)
+    t = gen(w)
+    out, idx = P.run_layer(w, t)
+    P.check_layer(w, t, out, idx)
+
+
 def test_prefill_chunk_redo_path_on_degenerate_scores():
     """Zero queries: every score ties, every threshold misses (segment overflow), and the exact
     redo path must return the lowest k indices for every row."""
