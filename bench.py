@@ -56,6 +56,9 @@ def main() -> int:
     ap.add_argument("--no-batched", action="store_true", help="skip the fp16 batched-decode leg")
     ap.add_argument("--only-token", action="store_true", help="run the 32-layer decode-token leg alone")
     ap.add_argument("--no-token", action="store_true", help="skip the 32-layer decode-token leg")
+    ap.add_argument("--only-unfused", action="store_true",
+                    help="run the four separate calls (score, top-k, gather + rotary, attend) alone")
+    ap.add_argument("--no-unfused", action="store_true", help="skip the leg of the four separate calls")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy 3 times (a known-size kernel against "
                          "which rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings are scaled)")
@@ -88,6 +91,10 @@ def main() -> int:
         return 0
     if args.only_vote_prefill:
         print(json.dumps({"vote_prefill": vote_prefill_leg(min(args.steps, 5), args.chunk)}), flush=True)
+        return 0
+    if args.only_unfused:
+        print(json.dumps({"unfused_calls": unfused_leg(wl.generate(wl.CONFIGS[args.config], "cuda"), args.config,
+                                                       args.steps)}), flush=True)
         return 0
     if args.only_vote:
         print(json.dumps({"vote": vote_leg(wl.generate(wl.CONFIGS[args.config], "cuda"), args.config,
@@ -175,6 +182,8 @@ def main() -> int:
 
     if not args.no_vote:
         result["vote"] = vote_leg(t, args.config, args.steps, args.warmup)
+    if not args.no_unfused:
+        result["unfused_calls"] = unfused_leg(t, args.config, args.steps)
     if not args.no_prefill:
         del ks, vs, t, ws
         torch.cuda.empty_cache()
@@ -374,6 +383,51 @@ def batched_decode_leg(steps: int) -> dict:
         del ks, vs
         torch.cuda.empty_cache()
     return {"workload": "llama3-8b layer shape, fp16 storage, sink 4, local 4096", "pairs": rows}
+
+
+def unfused_leg(t: dict, cfg: int, steps: int) -> dict:
+    """The same decode step as four separate calls (Eq. 2 scores, Eq. 2 top-k, Eq. 3 concatenation with the
+    rotary encoding materialised, Eq. 3 attention on the materialised buffers), each timed with events on the
+    launch stream.  The gather writes fp32 rotated keys: D * (4 + b) bytes per slot against 2 * D * b read."""
+    import torch
+    from paper_2407_15176_amd import binding as B
+    from paper_2407_15176_amd import workloads as wl
+    w = wl.CONFIGS[cfg]
+    p = B.Params.from_workload(w)
+    ws = B.alloc_workspace(p)
+    eb = t["k"].element_size()
+    scores = torch.empty(1, w.n_kv_heads, w.n_mid, dtype=torch.float32, device="cuda")
+    idx = torch.empty(1, w.n_kv_heads, w.k_eff, dtype=torch.int32, device="cuda")
+    k_sel = torch.empty(1, w.n_kv_heads, w.scope, w.head_dim, dtype=torch.float32, device="cuda")
+    v_sel = torch.empty(1, w.n_kv_heads, w.scope, w.head_dim, dtype=t["v"].dtype, device="cuda")
+    out = torch.empty(1, w.n_q_heads, w.head_dim, dtype=torch.float32, device="cuda")
+    calls = {
+        "score": lambda: B.score(p, t["q"], t["k"], scores=scores, ws=ws),
+        "topk": lambda: B.topk(p, scores, ws, idx=idx),
+        "gather_rope": lambda: B.gather_rope(p, t["k"], t["v"], idx, k_sel=k_sel, v_sel=v_sel),
+        "attend": lambda: B.attend(p, t["q"], k_sel, v_sel, ws, out=out),
+    }
+    ms = {}
+    for name, fn in calls.items():
+        fn(); fn()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        a.record()
+        for _ in range(steps):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        ms[name] = a.elapsed_time(b) / steps
+    rows = w.scope * w.n_kv_heads
+    gather_read = 2 * rows * w.head_dim * eb + w.k_eff * w.n_kv_heads * 4
+    gather_write = rows * w.head_dim * (4 + eb)
+    gbps = (gather_read + gather_write) / (ms["gather_rope"] * 1e-3) / 1e9
+    return {"workload": w.name, "steps": steps, "ms": {k: round(v, 5) for k, v in ms.items()},
+            "ms_total": round(sum(ms.values()), 5),
+            "score_GBps": round(w.scan_bytes / (ms["score"] * 1e-3) / 1e9, 1),
+            "gather_rope": {"kernel": "gather_rope_kernel", "bound": "hbm", "read_bytes": gather_read,
+                            "write_bytes": gather_write, "achieved": round(gbps, 1), "peak": HBM_PEAK_GBPS,
+                            "unit": "GB/s", "frac": round(gbps / HBM_PEAK_GBPS, 4)}}
 
 
 def decode_token_leg(steps: int, n_layers: int = 32) -> dict:

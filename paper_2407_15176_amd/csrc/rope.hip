@@ -45,14 +45,48 @@ struct GatherArgs {
   const void* k; const void* v; const int32_t* idx; float* k_sel; void* v_sel;
   int64_t ksh, kst, vsh, vst, N;
   int Hkv, M, S, s_eff, k_eff, l_eff;
-  double log2_theta;
+  double omega[64];                                // w_c = theta^(-2c/D), formed on the host in fp64
 };
 
-// One 16-lane group per (query, KV head, slot).  Lane `sub` owns channels
-// [sub*E, sub*E+E) and their partners D/2 higher, so a rotation never leaves the lane.
+// E consecutive stored elements -> fp32, and the raw copy of them (vector accesses of E * sizeof(T) bytes).
+template <typename T, int E> struct Piece;
+template <int E> struct Piece<float, E> {
+  typedef typename std::conditional<E == 4, u32x4, u32x2>::type raw;
+  static __device__ __forceinline__ void widen(const raw& d, float* x) {
+#pragma unroll
+    for (int e = 0; e < E; ++e) x[e] = __uint_as_float(d[e]);
+  }
+};
+template <int E> struct Piece<uint16_t, E> {
+  typedef typename std::conditional<E == 4, u32x2, uint32_t>::type raw;
+  static __device__ __forceinline__ uint32_t word(const u32x2& d, int i) { return d[i]; }
+  static __device__ __forceinline__ uint32_t word(const uint32_t& d, int) { return d; }
+  static __device__ __forceinline__ void widen(const raw& d, float* x) {
+#pragma unroll
+    for (int e = 0; e < E; e += 2) { x[e] = bf16_lo(word(d, e / 2)); x[e + 1] = bf16_hi(word(d, e / 2)); }
+  }
+};
+template <int E> struct Piece<f16bits, E> {
+  typedef typename std::conditional<E == 4, u32x2, uint32_t>::type raw;
+  static __device__ __forceinline__ void widen(const raw& d, float* x) {
+#pragma unroll
+    for (int e = 0; e < E; e += 2) {
+      x[e] = f16_lo(Piece<uint16_t, E>::word(d, e / 2)); x[e + 1] = f16_hi(Piece<uint16_t, E>::word(d, e / 2));
+    }
+  }
+};
+
+// One 16-lane group per (query, KV head, slot).  Lane `sub` owns channels [sub*E, sub*E+E) and their partners
+// D/2 higher, so a rotation never leaves the lane, and every access is one vector of the lane's E elements.
+// The kernel is a gather: 2 * D * b bytes read and D * (4 + b) written per slot.  The angle r * w_c is formed
+// and reduced to [-pi, pi] in fp64 (exact to ~1e-11 rad at any position), its sine and cosine taken in fp32:
+// a full fp64 sincos per element made the kernel compute-bound at four times its memory time.
 template <typename T, int D>
 __global__ __launch_bounds__(256) void gather_rope_kernel(GatherArgs a) {
   constexpr int E = D / 32;                       // channels per lane per half
+  typedef Piece<T, E> P;
+  typedef typename P::raw Raw;
+  typedef typename Piece<float, E>::raw FRaw;
   const int sub = threadIdx.x & 15;
   const int64_t slot_id = (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);
   const int64_t total = (int64_t)a.M * a.Hkv * a.S;
@@ -65,11 +99,10 @@ __global__ __launch_bounds__(256) void gather_rope_kernel(GatherArgs a) {
   T* vo = (T*)a.v_sel + slot_id * D;
   const int c0 = sub * E;
   if (r >= visible) {
-#pragma unroll
-    for (int e = 0; e < E; ++e) {
-      ko[c0 + e] = 0.f; ko[D / 2 + c0 + e] = 0.f;
-      vo[c0 + e] = T{}; vo[D / 2 + c0 + e] = T{};
-    }
+    FRaw zf; Raw zv;
+    memset(&zf, 0, sizeof zf); memset(&zv, 0, sizeof zv);
+    *(FRaw*)(ko + c0) = zf; *(FRaw*)(ko + D / 2 + c0) = zf;
+    *(Raw*)(vo + c0) = zv; *(Raw*)(vo + D / 2 + c0) = zv;
     return;
   }
   int64_t tok;
@@ -78,32 +111,24 @@ __global__ __launch_bounds__(256) void gather_rope_kernel(GatherArgs a) {
   else tok = a.N - a.l_eff + (r - a.s_eff - a.k_eff);
   const T* kr = (const T*)a.k + (int64_t)h * a.ksh + tok * a.kst;
   const T* vr = (const T*)a.v + (int64_t)h * a.vsh + tok * a.vst;
+  const Raw klo = *(const Raw*)(kr + c0), khi = *(const Raw*)(kr + D / 2 + c0);
+  const Raw vlo = *(const Raw*)(vr + c0), vhi = *(const Raw*)(vr + D / 2 + c0);
+  float lo[E], hi[E];
+  P::widen(klo, lo); P::widen(khi, hi);
+  FRaw olo, ohi;
 #pragma unroll
   for (int e = 0; e < E; ++e) {
-    const int c = c0 + e;
-    float lo, hi;
-    if (std::is_same<T, f16bits>::value) {
-      lo = f16_one(((const uint16_t*)kr)[c]);
-      hi = f16_one(((const uint16_t*)kr)[c + D / 2]);
-    } else if (sizeof(T) == 2) {
-      lo = __uint_as_float(((uint32_t)((const uint16_t*)kr)[c]) << 16);
-      hi = __uint_as_float(((uint32_t)((const uint16_t*)kr)[c + D / 2]) << 16);
-    } else {
-      lo = ((const float*)kr)[c];
-      hi = ((const float*)kr)[c + D / 2];
-    }
-    const double w = exp2(-2.0 * (double)c / (double)D * a.log2_theta);
-    double sn, cs;
-    sincos((double)r * w, &sn, &cs);
-    ko[c] = (float)((double)lo * cs - (double)hi * sn);
-    ko[c + D / 2] = (float)((double)hi * cs + (double)lo * sn);
-    vo[c] = vr[c];
-    vo[c + D / 2] = vr[c + D / 2];
+    const double turns = (double)r * a.omega[c0 + e] * 0.15915494309189535;     // angle / (2 pi)
+    const float ang = (float)((turns - rint(turns)) * 6.283185307179586);
+    float sn, cs;
+    sincosf(ang, &sn, &cs);
+    olo[e] = __float_as_uint(lo[e] * cs - hi[e] * sn);
+    ohi[e] = __float_as_uint(hi[e] * cs + lo[e] * sn);
   }
+  *(FRaw*)(ko + c0) = olo; *(FRaw*)(ko + D / 2 + c0) = ohi;
+  *(Raw*)(vo + c0) = vlo; *(Raw*)(vo + D / 2 + c0) = vhi;
 }
 
-// Appends the rows of n_tok new tokens, delivered token-major [n_tok][Hkv][D] (as the projections
-// produce them), to the head-major cache: cache[h][first_tok + t][:] = new[t][h][:].  16 bytes per thread.
 __global__ __launch_bounds__(256) void cache_append_kernel(AppendArgs a) {
   const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (i < a.n_vec) append_piece(a, i);
@@ -146,7 +171,7 @@ hipError_t launch_gather_rope(const Plan& pl, const void* k_cache, const void* v
   a.ksh = pl.ksh; a.kst = pl.kst; a.vsh = pl.vsh; a.vst = pl.vst; a.N = pl.N;
   a.Hkv = pl.Hkv; a.M = pl.M; a.S = pl.S;
   a.s_eff = (int)pl.s_eff; a.k_eff = pl.k_eff; a.l_eff = (int)pl.l_eff;
-  a.log2_theta = log2((double)pl.theta);
+  for (int c = 0; c < pl.D / 2; ++c) a.omega[c] = exp2(-2.0 * (double)c / (double)pl.D * log2((double)pl.theta));
   const int64_t total = (int64_t)pl.M * pl.Hkv * pl.S;
   if (total == 0) return hipSuccess;
   const dim3 grid((unsigned)((total + 15) / 16));
