@@ -103,7 +103,7 @@ size_t reattn_workspace_bytes(const reattn_params* p);
 /* Eq. 2, first line: scores[i][h][j] = sum over the G heads of group h of
  * q[i][hG+g] . k_cache[h][s_eff + j], j in [0, N_mid); no rotary encoding, no
  * scaling; fp32 accumulation.  M == 1 streams the cache once (HBM-bound) and
- * needs no workspace (ws may be NULL); M > 1 with bf16 storage and D == 128 runs
+ * needs no workspace (ws may be NULL); M > 1 with bf16 / fp16 storage and D == 128 runs
  * the MFMA contraction and uses ws; other M > 1 shapes stream once per query.
  * N_mid == 0 is a no-op. */
 int reattn_score(const reattn_params* p, const void* q, const void* k_cache,
@@ -245,7 +245,7 @@ int reattn_decode_step_timed(const reattn_params* p, const void* q, const void* 
                              const void* v_cache, int32_t* idx_out, float* out,
                              void* ws, size_t ws_bytes, void* stream, float* stage_ms);
 
-/* Measurement aid: reattn_prefill_chunk on the MFMA path (bf16, D == 128, M > 1, k_eff > 0;
+/* Measurement aid: reattn_prefill_chunk on the MFMA path (bf16 / fp16, D == 128, M > 1, k_eff > 0;
  * other shapes return REATTN_ERR_SHAPE) with HIP events at the stage boundaries; WAITS and
  * fills the HOST array stage_ms[REATTN_N_STAGES] with
  *   [0] prep + query split + sampled scores + per-row thresholds,

@@ -100,7 +100,7 @@ int make_plan(const reattn_params* p, Plan* out) {
   pl.off_part = off;   off += up((size_t)pl.M * pl.Hq * (size_t)pl.nsplit * (pl.D + 2) * 4);
   pl.off_qsplit = off; off += up(pl.M > 1 ? score_gemm_qsplit_bytes(pl) : 0);
   // fused prefill selection: MFMA scores filtered against sampled thresholds
-  pl.fused_prefill = pl.M > 1 && pl.dtype == REATTN_BF16 && pl.D == 128 && pl.k_eff > 0 &&
+  pl.fused_prefill = pl.M > 1 && (pl.dtype == REATTN_BF16 || pl.dtype == REATTN_F16) && pl.D == 128 && pl.k_eff > 0 &&
                      cand_topk_lds(pl) <= (size_t)128 * 1024;
   if (pl.fused_prefill) {
     int64_t stride, n_s; uint32_t rho, cap;
@@ -136,8 +136,8 @@ int bind_ws(const Plan& pl, void* ws, size_t ws_bytes, Ws* w) {
   return REATTN_OK;
 }
 
-// M > 1 on bf16 / D = 128 takes the MFMA kernel; everything else streams per query.
-inline bool use_mfma(const Plan& pl) { return pl.M > 1 && pl.dtype == REATTN_BF16 && pl.D == 128; }
+// M > 1 on 16-bit storage / D = 128 takes the MFMA kernel; everything else streams per query.
+inline bool use_mfma(const Plan& pl) { return pl.M > 1 && (pl.dtype == REATTN_BF16 || pl.dtype == REATTN_F16) && pl.D == 128; }
 
 inline int hip_rc(hipError_t e) { return e == hipSuccess ? REATTN_OK : REATTN_ERR_HIP; }
 

@@ -27,7 +27,6 @@
 namespace reattn {
 namespace {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -58,10 +57,32 @@ __global__ __launch_bounds__(256) void rope16_kernel(float2* rope, int nb, doubl
   rope[i] = make_float2((float)cs, (float)sn);
 }
 
-__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {     // round to nearest even
-  const f32x2 v = {a, b};
-  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
-}
+// The two 16-bit storage / operand formats: F16 = false is bf16, true IEEE half.
+typedef _Float16 f16x2v __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x4v __attribute__((ext_vector_type(4)));
+template <bool F16> struct Fmt;
+template <> struct Fmt<false> {
+  static __device__ __forceinline__ uint32_t pack(float a, float b) {   // round to nearest even
+    const f32x2 v = {a, b};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+  }
+  static __device__ __forceinline__ float lo(uint32_t w) { return bf16_lo(w); }
+  static __device__ __forceinline__ float hi(uint32_t w) { return bf16_hi(w); }
+  static __device__ __forceinline__ f32x4 mfma_pv(u32x2 a, u32x2 b, f32x4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, a), __builtin_bit_cast(s16x4, b), c, 0, 0, 0);
+  }
+};
+template <> struct Fmt<true> {
+  static __device__ __forceinline__ uint32_t pack(float a, float b) {   // round to nearest even
+    const f32x2 v = {a, b};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2v));
+  }
+  static __device__ __forceinline__ float lo(uint32_t w) { return f16_lo(w); }
+  static __device__ __forceinline__ float hi(uint32_t w) { return f16_hi(w); }
+  static __device__ __forceinline__ f32x4 mfma_pv(u32x2 a, u32x2 b, f32x4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x16f16(__builtin_bit_cast(f16x4v, a), __builtin_bit_cast(f16x4v, b), c, 0, 0, 0);
+  }
+};
 __device__ __forceinline__ float2 cmul(float2 a, float2 b) {
   return make_float2(a.x * b.x - a.y * b.y, a.x * b.y + a.y * b.x);
 }
@@ -75,6 +96,7 @@ __device__ __forceinline__ float row_max16(float v) {     // max over the 16 lan
 
 // Two fp32 rows x[0..8) (channels c..c+7) and y[0..8) (channels c+64..) rotated by cs[0..8),
 // each result split into bf16 hi + lo; out: {lo-half hi, lo-half lo, hi-half hi, hi-half lo} operands.
+template <bool F16>
 __device__ __forceinline__ void rotate_split(const u32x4& klo, const u32x4& khi, const float2* cs,
                                              float mul, u32x4& a_hi, u32x4& a_lo, u32x4& b_hi,
                                              u32x4& b_lo) {
@@ -82,20 +104,21 @@ __device__ __forceinline__ void rotate_split(const u32x4& klo, const u32x4& khi,
   uint32_t ah[4], al[4], bh[4], bl[4];
 #pragma unroll
   for (int p = 0; p < 4; ++p) {
-    const float x0 = bf16_lo(wl[p]), x1 = bf16_hi(wl[p]), y0 = bf16_lo(wh[p]), y1 = bf16_hi(wh[p]);
+    const float x0 = Fmt<F16>::lo(wl[p]), x1 = Fmt<F16>::hi(wl[p]), y0 = Fmt<F16>::lo(wh[p]), y1 = Fmt<F16>::hi(wh[p]);
     const float2 c0 = cs[2 * p], c1 = cs[2 * p + 1];
     const float r0 = (x0 * c0.x - y0 * c0.y) * mul, r1 = (x1 * c1.x - y1 * c1.y) * mul;   // channels c
     const float s0 = (y0 * c0.x + x0 * c0.y) * mul, s1 = (y1 * c1.x + x1 * c1.y) * mul;   // channels c + 64
-    ah[p] = pack_bf16(r0, r1);
-    al[p] = pack_bf16(r0 - bf16_lo(ah[p]), r1 - bf16_hi(ah[p]));
-    bh[p] = pack_bf16(s0, s1);
-    bl[p] = pack_bf16(s0 - bf16_lo(bh[p]), s1 - bf16_hi(bh[p]));
+    ah[p] = Fmt<F16>::pack(r0, r1);
+    al[p] = Fmt<F16>::pack(r0 - Fmt<F16>::lo(ah[p]), r1 - Fmt<F16>::hi(ah[p]));
+    bh[p] = Fmt<F16>::pack(s0, s1);
+    bl[p] = Fmt<F16>::pack(s0 - Fmt<F16>::lo(bh[p]), s1 - Fmt<F16>::hi(bh[p]));
   }
   a_hi = u32x4{ah[0], ah[1], ah[2], ah[3]}; a_lo = u32x4{al[0], al[1], al[2], al[3]};
   b_hi = u32x4{bh[0], bh[1], bh[2], bh[3]}; b_lo = u32x4{bl[0], bl[1], bl[2], bl[3]};
 }
 
-__device__ __forceinline__ bf16x8 as_bf16x8(const u32x4& v) { return __builtin_bit_cast(bf16x8, v); }
+template <bool F16>
+__device__ __forceinline__ typename Mm<F16>::op8 as_op8(const u32x4& v) { return __builtin_bit_cast(typename Mm<F16>::op8, v); }
 
 // (cos, sin) of position 16*b + n for the 16 frequencies of lane (n, j): per-block row times the
 // lane's own factors (tl: 8 x float4 = two factors each, as kept in LDS by the attention kernel).
@@ -112,15 +135,17 @@ __device__ __forceinline__ void block_factors(const float2* t_hi_row, LaneFactor
 
 // B operands of the logit MFMAs from a raw key row: ops[4*ks2 + {0,1,2,3}] = {hi, lo} halves of the
 // rotated channels 32*ks2 + 8j + e, then of the channels 64 higher.
+template <bool F16>
 __device__ __forceinline__ void key_operands(const u32x4* kr, const float2 (*cs)[8], u32x4* ops) {
 #pragma unroll
   for (int ks2 = 0; ks2 < 2; ++ks2)
-    rotate_split(kr[ks2], kr[ks2 + 2], cs[ks2], 1.0f, ops[4 * ks2], ops[4 * ks2 + 1], ops[4 * ks2 + 2],
-                 ops[4 * ks2 + 3]);
+    rotate_split<F16>(kr[ks2], kr[ks2 + 2], cs[ks2], 1.0f, ops[4 * ks2], ops[4 * ks2 + 1], ops[4 * ks2 + 2],
+                      ops[4 * ks2 + 3]);
 }
 
 // The local window's slots s + k + t hold the same key at the same position for every query of
 // the chunk, so their MFMA operands are formed once: pre[h][lb][x][lane], block b = b0 + lb.
+template <bool F16>
 __global__ __launch_bounds__(64) void local_keys_kernel(PfArgs a, int b0, u32x4* pre) {
   const int lane = threadIdx.x, n = lane & 15, j = lane >> 4;
   const int lb = blockIdx.x, h = blockIdx.y, b = b0 + lb;
@@ -144,7 +169,7 @@ __global__ __launch_bounds__(64) void local_keys_kernel(PfArgs a, int b0, u32x4*
     u32x4 kr[4];
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) kr[ks] = *(const u32x4*)(row + 32 * ks);
-    key_operands(kr, cs, ops);
+    key_operands<F16>(kr, cs, ops);
   } else {
 #pragma unroll
     for (int x = 0; x < 8; ++x) ops[x] = u32x4{0u, 0u, 0u, 0u};
@@ -154,7 +179,7 @@ __global__ __launch_bounds__(64) void local_keys_kernel(PfArgs a, int b0, u32x4*
   for (int x = 0; x < 8; ++x) o[x * 64] = ops[x];
 }
 
-template <int GT>
+template <int GT, bool F16>
 __global__ __launch_bounds__(256, 2) void attend_prefill_kernel(PfArgs a, int b_local0, int n_lb,
                                                                 const u32x4* __restrict__ pre) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -184,7 +209,7 @@ __global__ __launch_bounds__(256, 2) void attend_prefill_kernel(PfArgs a, int b_
 
   // A operand: row m = lane % 16 -> head m / 2, half m % 2 (hi, lo) of the query rotated at the
   // slot of its own key and scaled by softmax_scale * log2(e); rows past the group are zero.
-  bf16x8 aop[4];
+  typename Mm<F16>::op8 aop[4];
   {
     const int g = n >> 1, part = n & 1;
     const bool row_ok = g < GT && g0 + g < a.G;
@@ -200,9 +225,9 @@ __global__ __launch_bounds__(256, 2) void attend_prefill_kernel(PfArgs a, int b_
         cs[e] = cmul(t_hi[(int64_t)(pq >> 4) * 64 + 32 * ks2 + fo + e], t_lo[(pq & 15) * 64 + 32 * ks2 + fo + e]);
       const u32x4 lo = *(const u32x4*)(qr + 32 * ks2), hi = *(const u32x4*)(qr + 64 + 32 * ks2);
       u32x4 ah, al, bh, bl;
-      rotate_split(lo, hi, cs, mul, ah, al, bh, bl);
-      aop[ks2] = as_bf16x8(part ? al : ah);
-      aop[ks2 + 2] = as_bf16x8(part ? bl : bh);
+      rotate_split<F16>(lo, hi, cs, mul, ah, al, bh, bl);
+      aop[ks2] = as_op8<F16>(part ? al : ah);
+      aop[ks2 + 2] = as_op8<F16>(part ? bl : bh);
     }
   }
 
@@ -245,10 +270,10 @@ __global__ __launch_bounds__(256, 2) void attend_prefill_kernel(PfArgs a, int b_
     f32x4 c = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int ks2 = 0; ks2 < 2; ++ks2) {
-      c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aop[ks2], as_bf16x8(ops[4 * ks2]), c, 0, 0, 0);
-      c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aop[ks2], as_bf16x8(ops[4 * ks2 + 1]), c, 0, 0, 0);
-      c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aop[ks2 + 2], as_bf16x8(ops[4 * ks2 + 2]), c, 0, 0, 0);
-      c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aop[ks2 + 2], as_bf16x8(ops[4 * ks2 + 3]), c, 0, 0, 0);
+      c = Mm<F16>::mfma16(aop[ks2], as_op8<F16>(ops[4 * ks2]), c);
+      c = Mm<F16>::mfma16(aop[ks2], as_op8<F16>(ops[4 * ks2 + 1]), c);
+      c = Mm<F16>::mfma16(aop[ks2 + 2], as_op8<F16>(ops[4 * ks2 + 2]), c);
+      c = Mm<F16>::mfma16(aop[ks2 + 2], as_op8<F16>(ops[4 * ks2 + 3]), c);
     }
     return c;
   };
@@ -296,14 +321,14 @@ __global__ __launch_bounds__(256, 2) void attend_prefill_kernel(PfArgs a, int b_
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     float4 pr = make_float4(0.f, 0.f, 0.f, 0.f);
     if (pg < GT) pr = *(const float4*)&pw[pg][4 * j];
-    uint32_t pa0 = pack_bf16(pr.x, pr.y), pa1 = pack_bf16(pr.z, pr.w);
+    uint32_t pa0 = Fmt<F16>::pack(pr.x, pr.y), pa1 = Fmt<F16>::pack(pr.z, pr.w);
     if (ppart) {
-      const uint32_t l0 = pack_bf16(pr.x - bf16_lo(pa0), pr.y - bf16_hi(pa0));
-      const uint32_t l1 = pack_bf16(pr.z - bf16_lo(pa1), pr.w - bf16_hi(pa1));
+      const uint32_t l0 = Fmt<F16>::pack(pr.x - Fmt<F16>::lo(pa0), pr.y - Fmt<F16>::hi(pa0));
+      const uint32_t l1 = Fmt<F16>::pack(pr.z - Fmt<F16>::lo(pa1), pr.w - Fmt<F16>::hi(pa1));
       pa0 = l0; pa1 = l1;
     }
     __builtin_amdgcn_wave_barrier();                        // the stage is rewritten by the next block
-    const s16x4 pop = __builtin_bit_cast(s16x4, u32x2{pa0, pa1});
+    const u32x2 pop = u32x2{pa0, pa1};
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       // even channel 32u + 2n: low halves of the four slots; odd channel: high halves
@@ -311,8 +336,8 @@ __global__ __launch_bounds__(256, 2) void attend_prefill_kernel(PfArgs a, int b_
       const uint32_t e1 = __builtin_amdgcn_perm(vw[3][u], vw[2][u], 0x05040100u);
       const uint32_t o0 = __builtin_amdgcn_perm(vw[1][u], vw[0][u], 0x07060302u);
       const uint32_t o1 = __builtin_amdgcn_perm(vw[3][u], vw[2][u], 0x07060302u);
-      acc[2 * u] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pop, __builtin_bit_cast(s16x4, u32x2{e0, e1}), acc[2 * u], 0, 0, 0);
-      acc[2 * u + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pop, __builtin_bit_cast(s16x4, u32x2{o0, o1}), acc[2 * u + 1], 0, 0, 0);
+      acc[2 * u] = Fmt<F16>::mfma_pv(pop, u32x2{e0, e1}, acc[2 * u]);
+      acc[2 * u + 1] = Fmt<F16>::mfma_pv(pop, u32x2{o0, o1}, acc[2 * u + 1]);
     }
   };
 
@@ -332,7 +357,7 @@ __global__ __launch_bounds__(256, 2) void attend_prefill_kernel(PfArgs a, int b_
       float2 cs[2][8];
       block_factors(t_hi + (int64_t)b * 64 + fo, [&](int x) { return tl_lds[x][lane]; }, cs);
       u32x4 ops[8];
-      key_operands(kr, cs, ops);
+      key_operands<F16>(kr, cs, ops);
       // the key registers are free: request the next block's rows
       tok = tok_next;
       if (b + 1 < b_gen) load_key(tok, kr);
@@ -406,7 +431,7 @@ size_t attend_prefill_table_bytes(const Plan& pl) {
 }
 
 bool attend_prefill_applies(const Plan& pl) {
-  return pl.M > 1 && pl.dtype == 1 && pl.D == 128;
+  return pl.M > 1 && (pl.dtype == kBF16 || pl.dtype == kF16) && pl.D == 128;
 }
 
 // out[i][hq] for all M queries; `table` is scratch of attend_prefill_table_bytes().
@@ -430,16 +455,24 @@ hipError_t launch_attend_prefill(const Plan& pl, const void* q, const void* k_ca
   const int n_lb = a.nb - b_local0 > 0 ? a.nb - b_local0 : 0;
   const size_t table_bytes = ((size_t)n_tab * sizeof(float2) + 255) / 256 * 256;
   u32x4* pre = (u32x4*)((char*)table + table_bytes);
-  if (n_lb > 0)
-    hipLaunchKernelGGL(local_keys_kernel, dim3((unsigned)n_lb, (unsigned)pl.Hkv), dim3(64), 0, st, a,
-                       b_local0, pre);
-  const dim3 grid((unsigned)((pl.M + 3) / 4), (unsigned)(pl.Hkv * a.nsub));
-  switch (gt) {
-    case 1: hipLaunchKernelGGL((attend_prefill_kernel<1>), grid, dim3(256), 0, st, a, b_local0, n_lb, pre); break;
-    case 2: hipLaunchKernelGGL((attend_prefill_kernel<2>), grid, dim3(256), 0, st, a, b_local0, n_lb, pre); break;
-    case 3: hipLaunchKernelGGL((attend_prefill_kernel<3>), grid, dim3(256), 0, st, a, b_local0, n_lb, pre); break;
-    default: hipLaunchKernelGGL((attend_prefill_kernel<4>), grid, dim3(256), 0, st, a, b_local0, n_lb, pre); break;
+  const bool f16 = pl.dtype == kF16;
+  if (n_lb > 0) {
+    if (f16) hipLaunchKernelGGL(local_keys_kernel<true>, dim3((unsigned)n_lb, (unsigned)pl.Hkv), dim3(64), 0, st, a, b_local0, pre);
+    else     hipLaunchKernelGGL(local_keys_kernel<false>, dim3((unsigned)n_lb, (unsigned)pl.Hkv), dim3(64), 0, st, a, b_local0, pre);
   }
+  const dim3 grid((unsigned)((pl.M + 3) / 4), (unsigned)(pl.Hkv * a.nsub));
+#define REATTN_PF_LAUNCH(GT_)                                                                                       \
+  do {                                                                                                              \
+    if (f16) hipLaunchKernelGGL((attend_prefill_kernel<GT_, true>), grid, dim3(256), 0, st, a, b_local0, n_lb, pre); \
+    else     hipLaunchKernelGGL((attend_prefill_kernel<GT_, false>), grid, dim3(256), 0, st, a, b_local0, n_lb, pre); \
+  } while (0)
+  switch (gt) {
+    case 1: REATTN_PF_LAUNCH(1); break;
+    case 2: REATTN_PF_LAUNCH(2); break;
+    case 3: REATTN_PF_LAUNCH(3); break;
+    default: REATTN_PF_LAUNCH(4); break;
+  }
+#undef REATTN_PF_LAUNCH
   return hipGetLastError();
 }
 

@@ -426,6 +426,7 @@ struct ExactArgs {
   int32_t* idx;
 };
 
+template <bool F16>
 __global__ __launch_bounds__(1024) void row_exact_kernel(ExactArgs a) {
   __shared__ uint32_t bins[kBinsPad];
   __shared__ uint32_t sh[40];
@@ -443,7 +444,7 @@ __global__ __launch_bounds__(1024) void row_exact_kernel(ExactArgs a) {
     for (int g = 0; g < a.G; ++g) {
       const uint16_t* qr = a.q + ((int64_t)i * a.Hq + (int64_t)h * a.G + g) * 128 + sub * 8;
 #pragma unroll
-      for (int c = 0; c < 8; ++c) qv[c] += __uint_as_float(((uint32_t)qr[c]) << 16);
+      for (int c = 0; c < 8; ++c) qv[c] += Mm<F16>::widen(qr[c]);
     }
     const uint16_t* kb = a.k + (int64_t)h * a.ksh + a.first_tok * a.kst + sub * 8;
     for (int64_t j0 = (int64_t)wave * 4; j0 < a.n_mid; j0 += 64) {
@@ -451,10 +452,12 @@ __global__ __launch_bounds__(1024) void row_exact_kernel(ExactArgs a) {
       const int64_t jc = j < a.n_mid ? j : a.n_mid - 1;
       const u32x4 d = *(const u32x4*)(kb + jc * a.kst);
       float s = 0.f;
-      s = fmaf(bf16_lo(d.x), qv[0], s); s = fmaf(bf16_hi(d.x), qv[1], s);
-      s = fmaf(bf16_lo(d.y), qv[2], s); s = fmaf(bf16_hi(d.y), qv[3], s);
-      s = fmaf(bf16_lo(d.z), qv[4], s); s = fmaf(bf16_hi(d.z), qv[5], s);
-      s = fmaf(bf16_lo(d.w), qv[6], s); s = fmaf(bf16_hi(d.w), qv[7], s);
+      const uint32_t dw[4] = {d.x, d.y, d.z, d.w};
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        s = fmaf(F16 ? f16_lo(dw[c]) : bf16_lo(dw[c]), qv[2 * c], s);
+        s = fmaf(F16 ? f16_hi(dw[c]) : bf16_hi(dw[c]), qv[2 * c + 1], s);
+      }
       s = group_sum<16>(s);
       if (sub == 0 && j < a.n_mid) sc[j] = s;
     }
@@ -548,7 +551,8 @@ hipError_t launch_row_exact(const Plan& pl, int n_query, const void* q, const vo
   a.ksh = pl.ksh; a.kst = pl.kst; a.first_tok = pl.s_eff; a.n_mid = pl.n_mid;
   a.M = n_query; a.Hq = pl.Hq; a.Hkv = pl.Hkv; a.G = pl.G; a.k_eff = pl.k_eff;
   a.index_base = (int32_t)pl.s_eff; a.redo = redo; a.scratch = scratch; a.idx = idx;
-  hipLaunchKernelGGL(row_exact_kernel, dim3(n_slots), dim3(1024), 0, st, a);
+  if (pl.dtype == kF16) hipLaunchKernelGGL(row_exact_kernel<true>, dim3(n_slots), dim3(1024), 0, st, a);
+  else hipLaunchKernelGGL(row_exact_kernel<false>, dim3(n_slots), dim3(1024), 0, st, a);
   return hipGetLastError();
 }
 

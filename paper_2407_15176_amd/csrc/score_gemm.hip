@@ -41,35 +41,31 @@ namespace reattn {
 int gemm_m_pad(int n_query);
 namespace {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 constexpr int kTileKeys = 128;
 constexpr int kPitch = 272;                     // bytes per staged key row (256 + 16 pad)
 
-__device__ __forceinline__ uint16_t bf16_rne(float x) {
-  uint32_t u = __float_as_uint(x);
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return (uint16_t)(u >> 16);
-}
-
 // qs[h][i][0][:] = hi, qs[h][i][1][:] = lo of qbar[i][h][:] = sum_g q[i][hG+g][:]; rows i >= M are zero.
+// F16: IEEE half storage and operands (hi + lo then carry ~22 mantissa bits), else bf16.
+template <bool F16>
 __global__ __launch_bounds__(128) void qsplit_kernel(const uint16_t* __restrict__ q, int M, int m_pad,
                                                      int Hq, int Hkv, int G, uint16_t* qs) {
   const int i = blockIdx.x, h = blockIdx.y, c = threadIdx.x;          // D == 128
   float s = 0.f;
   if (i < M)
     for (int g = 0; g < G; ++g)
-      s += __uint_as_float(((uint32_t)q[((int64_t)i * Hq + (int64_t)h * G + g) * 128 + c]) << 16);
-  const uint16_t hi = bf16_rne(s);
-  const uint16_t lo = bf16_rne(s - __uint_as_float((uint32_t)hi << 16));
+      s += Mm<F16>::widen(q[((int64_t)i * Hq + (int64_t)h * G + g) * 128 + c]);
+  const uint16_t hi = Mm<F16>::narrow(s);
+  const uint16_t lo = Mm<F16>::narrow(s - Mm<F16>::widen(hi));
   uint16_t* o = qs + (((int64_t)h * m_pad + i) * 2) * 128;
   o[c] = hi;
   o[128 + c] = lo;
 }
 
 struct GemmArgs {
-  const uint16_t* k;        // key cache (bf16 bits)
+  const uint16_t* k;        // key cache (bf16 or IEEE half bits)
+  bool f16;                 // IEEE half storage
   const uint16_t* qs;       // split queries [Hkv][m_pad][2][128]
   int64_t ksh, kst;         // key strides in elements
   int64_t first_tok;        // cache row of key 0
@@ -91,8 +87,9 @@ constexpr int kTileBytes = kTileKeys * kPitch;  // one staged key tile
 constexpr int kStageBytes = 32 * 64 * 4;        // one wave's 32 x 64 scores of a tile (filter mode)
 constexpr int kStageNS = 2048 / kGemmThreads;   // 16-byte pieces of a key tile per thread
 
-template <int MODE>
+template <int MODE, bool F16>
 __global__ __launch_bounds__(kGemmThreads) void score_gemm_kernel(GemmArgs a) {
+  typedef typename Mm<F16>::op8 bf16x8;                     // the operand vector of the storage format
   extern __shared__ __attribute__((aligned(16))) unsigned char gemm_lds[];
   unsigned char* tiles = gemm_lds;                          // two staged key tiles
   __shared__ uint32_t lcount[kTileQ];
@@ -253,10 +250,10 @@ __global__ __launch_bounds__(kGemmThreads) void score_gemm_kernel(GemmArgs a) {
     const unsigned char* arow = tiles + buf * kTileBytes + (kw * 32 + ln) * kPitch + lh * 16;
     auto mfma_step = [&](int ks) {
       const bf16x8 av = *(const bf16x8*)(arow + ks * 32);
-      acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bhi[0][ks], acc[0], 0, 0, 0);
-      acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bhi[1][ks], acc[1], 0, 0, 0);
-      acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, blo[0][ks], acc[0], 0, 0, 0);
-      acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, blo[1][ks], acc[1], 0, 0, 0);
+      acc[0] = Mm<F16>::mfma32(av, bhi[0][ks], acc[0]);
+      acc[1] = Mm<F16>::mfma32(av, bhi[1][ks], acc[1]);
+      acc[0] = Mm<F16>::mfma32(av, blo[0][ks], acc[0]);
+      acc[1] = Mm<F16>::mfma32(av, blo[1][ks], acc[1]);
     };
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
@@ -337,21 +334,25 @@ __global__ __launch_bounds__(kGemmThreads) void score_gemm_kernel(GemmArgs a) {
   }
 }
 
-template <int MODE>
-hipError_t gemm_launch(const GemmArgs& a, dim3 grid, hipStream_t st) {
+template <int MODE, bool F16>
+hipError_t gemm_launch_t(const GemmArgs& a, dim3 grid, hipStream_t st) {
   constexpr size_t lds = 2 * (size_t)kTileBytes + (MODE == kFilter ? 8 * (size_t)kStageBytes : 0);
-  auto kern = score_gemm_kernel<MODE>;
+  auto kern = score_gemm_kernel<MODE, F16>;
   hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(kern, grid, dim3(kGemmThreads), lds, st, a);
   return hipGetLastError();
+}
+template <int MODE>
+hipError_t gemm_launch(const GemmArgs& a, dim3 grid, hipStream_t st) {
+  return a.f16 ? gemm_launch_t<MODE, true>(a, grid, st) : gemm_launch_t<MODE, false>(a, grid, st);
 }
 
 GemmArgs base_args(const Plan& pl, int n_query, const void* k_cache, const void* q_split) {
   GemmArgs a;
   a.k = (const uint16_t*)k_cache; a.qs = (const uint16_t*)q_split;
   a.ksh = pl.ksh; a.kst = pl.kst; a.first_tok = pl.s_eff; a.n_keys = pl.n_mid; a.key_step = 1;
-  a.M = n_query; a.m_pad = gemm_m_pad(n_query); a.Hkv = pl.Hkv;
+  a.M = n_query; a.m_pad = gemm_m_pad(n_query); a.Hkv = pl.Hkv; a.f16 = pl.dtype == kF16;
   a.tiles_per_block = 0;
   a.scores = nullptr; a.score_stride = 0;
   a.thr = nullptr; a.cand = nullptr; a.ccount = nullptr; a.cap = 0;
@@ -370,8 +371,12 @@ hipError_t launch_qsplit(const Plan& pl, const void* q, int q_first, int n_query
                          hipStream_t st) {
   const int m_pad = gemm_m_pad(n_query);
   const uint16_t* qp = (const uint16_t*)q + (int64_t)q_first * pl.Hq * pl.D;
-  hipLaunchKernelGGL(qsplit_kernel, dim3(m_pad, pl.Hkv), dim3(128), 0, st, qp, n_query, m_pad, pl.Hq,
-                     pl.Hkv, pl.G, (uint16_t*)q_split);
+  if (pl.dtype == kF16)
+    hipLaunchKernelGGL(qsplit_kernel<true>, dim3(m_pad, pl.Hkv), dim3(128), 0, st, qp, n_query, m_pad, pl.Hq,
+                       pl.Hkv, pl.G, (uint16_t*)q_split);
+  else
+    hipLaunchKernelGGL(qsplit_kernel<false>, dim3(m_pad, pl.Hkv), dim3(128), 0, st, qp, n_query, m_pad, pl.Hq,
+                       pl.Hkv, pl.G, (uint16_t*)q_split);
   return hipGetLastError();
 }
 

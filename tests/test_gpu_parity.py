@@ -48,10 +48,11 @@ def test_score_matches_oracle(name):
     assert err <= 2e-6 * np.abs(want).max() + 1e-6, err
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
 @pytest.mark.parametrize("M,n_ctx", [(5, 4_321), (64, 20_011), (130, 9_000), (257, 33_000)])
-def test_score_prefill_mfma_matches_oracle(M, n_ctx):
-    """M > 1, bf16, D = 128: the MFMA contraction (hi/lo split of the group-summed query)."""
-    w = wl.CONFIGS[4].scaled(n_ctx=n_ctx, n_query=M, n_local=max(300, M), top_k=64)
+def test_score_prefill_mfma_matches_oracle(M, n_ctx, dtype):
+    """M > 1, 16-bit storage, D = 128: the MFMA contraction (hi/lo split of the group-summed query)."""
+    w = wl.CONFIGS[4].scaled(dtype=dtype, n_ctx=n_ctx, n_query=M, n_local=max(300, M), top_k=64)
     t = gen(w)
     p = B.Params.from_workload(w)
     ws = B.alloc_workspace(p)
@@ -242,7 +243,8 @@ def test_window_error_is_reported():
 
 
 # ----------------------------------------------------------- reattn_prefill_chunk
-@pytest.mark.parametrize("name,M", [("f32_d64_g4", 5), ("bf16_d128_g4", 64), ("bf16_d128_g3", 17)])
+@pytest.mark.parametrize("name,M", [("f32_d64_g4", 5), ("bf16_d128_g4", 64), ("bf16_d128_g3", 17),
+                                    ("f16_d128_g4", 70), ("f16_d64_g3", 6)])
 def test_prefill_chunk_matches_oracle(name, M):
     w = SMALL[name].scaled(n_query=M, n_needles=0, scale_q=True)
     t = gen(w)
@@ -250,12 +252,14 @@ def test_prefill_chunk_matches_oracle(name, M):
     P.check_layer(w, t, out, idx)
 
 
-def test_prefill_chunk_sampled_thresholds_larger_cache():
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+def test_prefill_chunk_sampled_thresholds_larger_cache(dtype):
     """n_mid / 8192 > 1: the thresholds come from a strided sample of the keys."""
-    w = wl.CONFIGS[4].scaled(n_ctx=70_000, n_query=130, n_local=512, top_k=1_000)
+    w = wl.CONFIGS[4].scaled(dtype=dtype, n_ctx=70_000, n_query=130, n_local=512, top_k=1_000)
     t = gen(w)
     out, idx = P.run_layer(w, t)
-    P.check_layer(w, t, out, idx, q_rows=[0, 1, 63, 64, 127, 128, 129])
+    r = P.check_layer(w, t, out, idx, q_rows=[0, 1, 63, 64, 127, 128, 129])
+    assert r["max_abs_err"] <= 2e-3          # the hi/lo-split operands stay far inside the bar in both formats
 
 
 def test_prefill_chunk_wide_candidate_segments():
@@ -288,9 +292,10 @@ def test_prefill_chunk_redo_path_on_degenerate_scores():
     P.check_layer(w, t, out, idx)
 
 
-def test_prefill_chunk_mixed_redo_rows():
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+def test_prefill_chunk_mixed_redo_rows(dtype):
     """Some query rows are zero (redo path), the others take the filtered path."""
-    w = wl.CONFIGS[4].scaled(n_ctx=30_000, n_query=70, n_local=400, top_k=300)
+    w = wl.CONFIGS[4].scaled(dtype=dtype, n_ctx=30_000, n_query=70, n_local=400, top_k=300)
     t = gen(w)
     t["q"][3].zero_()
     t["q"][66].zero_()
