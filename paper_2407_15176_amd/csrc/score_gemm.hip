@@ -25,16 +25,20 @@
 // bound on the k-th largest score, estimated beforehand from a strided sample of the
 // keys; the few percent that pass are appended as (score, key) pairs to the row's
 // candidate segment.  A workgroup owns its query rows for ALL keys, so the per-row
-// counters live in LDS and no global atomics are needed.  The filter of tile t - 1 runs
-// inside the MFMA sequence of tile t: a wave parks its 32 x 64 scores in a private LDS
-// stage, tests them between the first 16 MFMAs of the next tile, and appends the hits
-// either between the two MFMA halves or after them, depending on its query half, so
-// that the two waves sharing a SIMD are not both away from the matrix pipe.
+// counters live in LDS and no global atomics are needed.  A finished tile's 32 x 64 scores
+// are tested in the accumulator registers (score >= bound as the sign bit of their
+// difference, shifted into a per-lane hit word: two vector instructions per score, no
+// condition registers) and parked in a wave-private LDS stage, from which the few hits are
+// fetched by index and appended during the NEXT tile's MFMAs: between its two halves or
+// after them, depending on the wave's query half, so that the two waves sharing a SIMD
+// are not both away from the matrix pipe.
 //
 // Measured on MI355X (random bf16 operands): the matrix pipe itself sustains 1790
 // TFLOP/s from registers and 1680 with one LDS operand read per four MFMAs (all-zero
 // operands reach 2480: the clock is power-limited under real data), the bare loop of
-// this kernel 1400, the fused filter 880 executed = 1760 algorithmic.
+// this kernel 1400, the fused filter about 900 executed = 1800 algorithmic (testing the scores
+// out of the stage, in the shadow of the next tile's first MFMAs, cost more in LDS
+// traffic than it hid).
 #include "common.hpp"
 
 namespace reattn {
@@ -209,23 +213,10 @@ __global__ __launch_bounds__(kGemmThreads) void score_gemm_kernel(GemmArgs a) {
       }
     }
   };
-  // 4 staged scores of this lane against its threshold.  score >= thr <=> the sign bit of (score - thr) is
-  // clear (the difference of equal finite values is +0), and v_alignbit shifts that bit into the running
-  // word: two vector instructions per score and no condition registers, so the tests slot freely between
-  // the MFMAs.  After all eight rows, row-major, score n sits at bit 31 - n, inverted: see hits_of().
-  auto test_stage_row = [&](int r, uint32_t& word) {
-    const float4 v = stage[r * 64 + lane];
-    const float th = thr[r >> 2];
-    word = __builtin_amdgcn_alignbit(word, __float_as_uint(v.x - th), 31);
-    word = __builtin_amdgcn_alignbit(word, __float_as_uint(v.y - th), 31);
-    word = __builtin_amdgcn_alignbit(word, __float_as_uint(v.z - th), 31);
-    word = __builtin_amdgcn_alignbit(word, __float_as_uint(v.w - th), 31);
-  };
+  // score >= thr <=> the sign bit of (score - thr) is clear (the difference of equal finite values is +0);
+  // v_alignbit shifts that bit into a running word, so after the 32 scores of a lane, in the order
+  // n = qb*16 + i, score n sits at bit 31 - n, inverted.
   auto hits_of = [](uint32_t word) -> uint32_t { return __brev(~word); };   // bit qb*16 + i for acc[qb][i]
-  if (MODE == kFilter) {                          // tile 0 has no predecessor: its test result is discarded
-#pragma unroll
-    for (int j = 0; j < 8; ++j) stage[j * 64 + lane] = make_float4(0.f, 0.f, 0.f, 0.f);
-  }
   if (n_tiles > 0) {
     load_tile(tile0, stg);
     stash_tile(0, stg);
@@ -238,6 +229,7 @@ __global__ __launch_bounds__(kGemmThreads) void score_gemm_kernel(GemmArgs a) {
   // by side), and its hits are appended either between the two halves (waves of query half 1)
   // or after the second (query half 0): the two waves that share a SIMD are then never both
   // away from the matrix pipe.
+  uint32_t pending = 0;                           // hit mask of the previous tile (bit qb*16 + i for acc[qb][i])
   auto step = [&](int64_t t, int buf) {
     if (t + 1 < n_tiles) stash_tile(buf ^ 1, stg);
     if (t + 2 < n_tiles) load_tile(tile0 + t + 2, stg);
@@ -246,7 +238,6 @@ __global__ __launch_bounds__(kGemmThreads) void score_gemm_kernel(GemmArgs a) {
     for (int qb = 0; qb < 2; ++qb)
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[qb][i] = 0.f;
-    uint32_t mask = 0;
     const unsigned char* arow = tiles + buf * kTileBytes + (kw * 32 + ln) * kPitch + lh * 16;
     auto mfma_step = [&](int ks) {
       const bf16x8 av = *(const bf16x8*)(arow + ks * 32);
@@ -256,29 +247,22 @@ __global__ __launch_bounds__(kGemmThreads) void score_gemm_kernel(GemmArgs a) {
       acc[1] = Mm<F16>::mfma32(av, blo[1][ks], acc[1]);
     };
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      mfma_step(ks);
-      if (MODE == kFilter) { test_stage_row(2 * ks, mask); test_stage_row(2 * ks + 1, mask); }
-    }
+    for (int ks = 0; ks < 4; ++ks) mfma_step(ks);
     if (MODE == kFilter) {
-      // scheduling pattern for the block above: tests spread between the MFMAs
-#pragma unroll
-      for (int ks = 0; ks < 4; ++ks) {
-        __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);   // LDS reads: key operand, 2 staged rows
-#pragma unroll
-        for (int m = 0; m < 4; ++m) {
-          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // one MFMA
-          __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);  // four vector ALU instructions (two scores)
-        }
-      }
-      mask = t > 0 ? hits_of(mask) : 0u;
-      if (qw == 1) append_hits(tile0 + t - 1, mask);
+      if (qw == 1) append_hits(tile0 + t - 1, pending);
     }
 #pragma unroll
     for (int ks = 4; ks < 8; ++ks) mfma_step(ks);
     const int64_t key_blk = (tile0 + t) * kTileKeys + kw * 32 + lh * 4;
     if (MODE == kFilter) {
-      if (qw == 0) append_hits(tile0 + t - 1, mask);
+      if (qw == 0) append_hits(tile0 + t - 1, pending);
+      // this tile's scores against the thresholds, out of the accumulators
+      uint32_t word = 0;
+#pragma unroll
+      for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) word = __builtin_amdgcn_alignbit(word, __float_as_uint(acc[qb][i] - thr[qb]), 31);
+      pending = hits_of(word);
 #pragma unroll
       for (int qb = 0; qb < 2; ++qb)
 #pragma unroll
@@ -323,12 +307,7 @@ __global__ __launch_bounds__(kGemmThreads) void score_gemm_kernel(GemmArgs a) {
   }
 
   if (MODE == kFilter) {
-    if (n_tiles > 0) {                              // the last tile has no successor to hide behind
-      uint32_t mask = 0;
-#pragma unroll
-      for (int r = 0; r < 8; ++r) test_stage_row(r, mask);
-      append_hits(tile0 + n_tiles - 1, hits_of(mask));
-    }
+    if (n_tiles > 0) append_hits(tile0 + n_tiles - 1, pending);   // the last tile has no successor to hide behind
     __syncthreads();
     if (tid < kTileQ && q0 + tid < a.M) a.ccount[(int64_t)h * a.M + q0 + tid] = lcount[tid];
   }
