@@ -56,6 +56,8 @@ def main() -> int:
     ap.add_argument("--no-batched", action="store_true", help="skip the fp16 batched-decode leg")
     ap.add_argument("--only-token", action="store_true", help="run the 32-layer decode-token leg alone")
     ap.add_argument("--no-token", action="store_true", help="skip the 32-layer decode-token leg")
+    ap.add_argument("--only-paged", action="store_true", help="run the paged-cache decode step alone")
+    ap.add_argument("--no-paged", action="store_true", help="skip the paged-cache decode step")
     ap.add_argument("--only-unfused", action="store_true",
                     help="run the four separate calls (score, top-k, gather + rotary, attend) alone")
     ap.add_argument("--no-unfused", action="store_true", help="skip the leg of the four separate calls")
@@ -91,6 +93,10 @@ def main() -> int:
         return 0
     if args.only_vote_prefill:
         print(json.dumps({"vote_prefill": vote_prefill_leg(min(args.steps, 5), args.chunk)}), flush=True)
+        return 0
+    if args.only_paged:
+        print(json.dumps({"paged_decode": paged_leg(wl.generate(wl.CONFIGS[args.config], "cuda"), args.config,
+                                                    args.steps, args.warmup)}), flush=True)
         return 0
     if args.only_unfused:
         print(json.dumps({"unfused_calls": unfused_leg(wl.generate(wl.CONFIGS[args.config], "cuda"), args.config,
@@ -184,6 +190,8 @@ def main() -> int:
         result["vote"] = vote_leg(t, args.config, args.steps, args.warmup)
     if not args.no_unfused:
         result["unfused_calls"] = unfused_leg(t, args.config, args.steps)
+    if not args.no_paged:
+        result["paged_decode"] = paged_leg(t, args.config, args.steps, args.warmup)
     if not args.no_prefill:
         del ks, vs, t, ws
         torch.cuda.empty_cache()
@@ -383,6 +391,50 @@ def batched_decode_leg(steps: int) -> dict:
         del ks, vs
         torch.cuda.empty_cache()
     return {"workload": "llama3-8b layer shape, fp16 storage, sink 4, local 4096", "pairs": rows}
+
+
+def paged_leg(t: dict, cfg: int, steps: int, warmup: int, page_size: int = 256) -> dict:
+    """The decode step over a paged cache: the same keys and values scattered page by page (a seeded random
+    permutation) over pools [Hkv][P * page_size][D] behind a device page table."""
+    import torch
+    from dataclasses import replace
+    from paper_2407_15176_amd import binding as B
+    from paper_2407_15176_amd import workloads as wl
+    w = wl.CONFIGS[cfg]
+    N, Hkv, D = w.n_ctx, w.n_kv_heads, w.head_dim
+    n_pages = -(-N // page_size)
+    table = torch.randperm(n_pages, generator=torch.Generator().manual_seed(240715000 + 10 * cfg + 9)).to(torch.int32)
+    k_pool = torch.empty(Hkv, n_pages * page_size, D, dtype=t["k"].dtype, device="cuda")
+    v_pool = torch.empty_like(k_pool)
+    tc = table.cuda().long()
+    pad = n_pages * page_size - N
+    for src, dst in ((t["k"], k_pool), (t["v"], v_pool)):       # page i of the sequence -> page table[i] of the pool
+        pages = torch.nn.functional.pad(src, (0, 0, 0, pad)).view(Hkv, n_pages, page_size, D)
+        dst.view(Hkv, n_pages, page_size, D)[:, tc] = pages
+        del pages
+    p = replace(B.Params.from_workload(w), k_stride_head=n_pages * page_size * D, k_stride_tok=D,
+                v_stride_head=n_pages * page_size * D, v_stride_tok=D, page_table=table.cuda(), page_size=page_size)
+    ws = B.alloc_workspace(p)
+    out = torch.empty(1, w.n_q_heads, D, dtype=torch.float32, device="cuda")
+    idx = torch.empty(1, Hkv, w.k_eff, dtype=torch.int32, device="cuda")
+    for _ in range(warmup):
+        B.decode_step(p, t["q"], k_pool, v_pool, ws, idx_out=idx, out=out)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        B.decode_step(p, t["q"], k_pool, v_pool, ws, idx_out=idx, out=out)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    stage_sum = {s: 0.0 for s in B.STAGES}
+    for _ in range(steps):
+        _, _, st = B.decode_step_timed(p, t["q"], k_pool, v_pool, ws, idx_out=idx, out=out)
+        for s in B.STAGES:
+            stage_sum[s] += st[s]
+    stages = {s: round(v / steps, 5) for s, v in stage_sum.items()}
+    gbps = w.scan_bytes / (stages["scan"] * 1e-3) / 1e9
+    del k_pool, v_pool
+    return {"workload": w.name, "page_size": page_size, "n_pages": n_pages, "ms_per_step": round(ms, 5),
+            "stages_ms": stages, "kv_scan_GBps": round(gbps, 1), "scan_frac_of_peak": round(gbps / HBM_PEAK_GBPS, 4)}
 
 
 def unfused_leg(t: dict, cfg: int, steps: int) -> dict:

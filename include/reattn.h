@@ -57,9 +57,8 @@ typedef enum {
 
 /* Storage of q, k_cache, v_cache, v_sel.  All arithmetic is fp32 on exactly widened inputs (the
  * matrix-core paths split what they must round into hi + lo halves).  REATTN_F16 (IEEE half, the
- * precision of the paper's own runs) takes the streaming kernels for every step and the matrix
- * cores for the vote selection; the per-query top-k of a chunk (reattn_prefill_chunk with M > 1)
- * streams once per query row for it. */
+ * precision of the paper's own runs) takes the same kernels as bf16: the streaming kernels of a decode
+ * step, the matrix cores (f16 MFMA instructions) for chunks and for the vote selection. */
 typedef enum { REATTN_F32 = 0, REATTN_BF16 = 1, REATTN_F16 = 2 } reattn_dtype;
 
 /* How the G heads of one GQA group are combined into one score per KV head.
@@ -82,6 +81,16 @@ typedef struct reattn_params {
   float   softmax_scale;/* 0 selects 1/sqrt(D) */
   int64_t k_stride_head, k_stride_tok; /* in elements; 0,0 means contiguous [Hkv][N][D] */
   int64_t v_stride_head, v_stride_tok;
+  /* Paged cache (NULL / 0: none).  k_cache and v_cache are then pools [Hkv][P * page_size][D] of P pages
+   * per head, and token t of the sequence sits in row page_table[t / page_size] * page_size + t % page_size
+   * of every head's slice.  page_table is a DEVICE array of ceil(N / page_size) int32 page numbers in
+   * [0, P); the library cannot read it on the host, so entries outside the pool are the caller's fault.
+   * page_size is a power of two >= 64; the four strides must be given (stride_head >= P * page_size * D).
+   * Served: a decode step by the per-KV-head top-k (reattn_score with M == 1, reattn_gather_rope,
+   * reattn_decode_step, reattn_decode_token without votes, reattn_cache_append); other calls return
+   * REATTN_ERR_SHAPE for paged params.  Indices (idx) stay token positions of the sequence. */
+  const int32_t* page_table;
+  int32_t page_size;
 } reattn_params;
 
 /* Library version (major*10000 + minor*100 + patch) and a static message for a status. */

@@ -47,6 +47,7 @@ class CParams(C.Structure):
         ("softmax_scale", C.c_float),
         ("k_stride_head", C.c_int64), ("k_stride_tok", C.c_int64),
         ("v_stride_head", C.c_int64), ("v_stride_tok", C.c_int64),
+        ("page_table", C.c_void_p), ("page_size", C.c_int32),
     ]
 
 
@@ -128,12 +129,23 @@ class Params:
     k_stride_tok: int = 0
     v_stride_head: int = 0
     v_stride_tok: int = 0
+    page_table: "torch.Tensor | None" = None     # int32 device tensor [ceil(n_ctx / page_size)], or None
+    page_size: int = 0
 
     def c(self) -> CParams:
+        pt = None
+        if self.page_table is not None:
+            t = self.page_table
+            if not (t.is_cuda and t.dtype == torch.int32 and t.is_contiguous()):
+                raise ValueError("page_table must be a contiguous int32 device tensor")
+            if t.numel() * max(self.page_size, 1) < self.n_ctx:
+                raise ValueError("page_table does not cover n_ctx tokens")
+            pt = t.data_ptr()
         return CParams(self.n_q_heads, self.n_kv_heads, self.head_dim, self.dtype, self.n_ctx,
                        self.n_query, self.n_sink, self.n_local, self.top_k, self.rope_theta,
                        self.max_position, self.agg, self.softmax_scale,
-                       self.k_stride_head, self.k_stride_tok, self.v_stride_head, self.v_stride_tok)
+                       self.k_stride_head, self.k_stride_tok, self.v_stride_head, self.v_stride_tok,
+                       pt, self.page_size)
 
     @classmethod
     def from_workload(cls, w) -> "Params":

@@ -52,6 +52,16 @@ int make_plan(const reattn_params* p, Plan* out) {
   if (pl.Hkv > 1 && (pl.ksh < pl.D || pl.vsh < pl.D)) return REATTN_ERR_SHAPE;   // heads must not alias
   if ((pl.kst * eb) % 16 || (pl.ksh * eb) % 16 || (pl.vst * eb) % 16 || (pl.vsh * eb) % 16)
     return REATTN_ERR_ALIGN;
+  pl.pt = nullptr; pl.page_lg = 0;
+  if (p->page_table || p->page_size) {                 // paged cache: pools [Hkv][P * page_size][D]
+    if (!p->page_table) return REATTN_ERR_NULL;
+    if (p->page_size < 64 || (p->page_size & (p->page_size - 1))) return REATTN_ERR_RANGE;
+    if (kdef || vdef) return REATTN_ERR_SHAPE;         // the pool's extent is not the sequence's: strides must be given
+    if (pl.M != 1) return REATTN_ERR_SHAPE;            // served: the decode step of the per-KV-head top-k
+    if (pl.ksh / pl.D > 0x7fffffffLL || pl.vsh / pl.D > 0x7fffffffLL) return REATTN_ERR_RANGE;   // pool rows are int32
+    pl.pt = p->page_table;
+    while ((1 << pl.page_lg) < p->page_size) ++pl.page_lg;
+  }
 
   pl.theta = p->rope_theta;
   pl.scale = p->softmax_scale > 0.f ? p->softmax_scale : 1.0f / std::sqrt((float)pl.D);
@@ -390,6 +400,7 @@ int make_vote_plan(const reattn_params* p, const reattn_vote* v, VotePlan* out) 
   VotePlan vp;
   int rc = make_plan(&pp, &vp.pl);
   if (rc) return rc;
+  if (vp.pl.pt) return REATTN_ERR_SHAPE;               // the vote scans read contiguous caches only
   const Plan& pl = vp.pl;
   vp.kk = (int)(v->vote_k < pl.n_mid ? v->vote_k : pl.n_mid);
   vp.kc = (int)(v->n_centres < pl.n_mid ? v->n_centres : pl.n_mid);

@@ -29,6 +29,7 @@ struct AttendArgs {
   const int32_t* k_dyn;      // device scalar: number of selected entries, or nullptr for the static k_eff
   int64_t idx_stride;        // elements between the index rows of consecutive (query, KV head) pairs; 0 = one shared row
   int seq_heads;             // > 0: KV heads [b * seq_heads, (b + 1) * seq_heads) share index row b and length k_dyn[b]
+  const int32_t* pt; int page_lg;   // paged cache (fused form): token -> row of the head's pool slice
   float* part; float* out;
   int64_t ksh, kst, vsh, vst, N;
   int Hq, Hkv, G, M, S, s_eff, k_eff, l_eff;
@@ -150,9 +151,11 @@ __global__ __launch_bounds__(256) void attend_kernel(AttendArgs a) {
   // 16 slots up front, so the index load is off the critical path of the row loads
   auto resolve = [&](int r) -> int {
     const int r2 = r < r_end ? r : r_end - 1;
-    if (r2 < a.s_eff) return r2;
-    if (r2 < a.s_eff + k_eff) return my_idx[r2 - a.s_eff];
-    return (int)(a.N - a.l_eff) + (r2 - a.s_eff - k_eff);
+    int tok;
+    if (r2 < a.s_eff) tok = r2;
+    else if (r2 < a.s_eff + k_eff) tok = my_idx[r2 - a.s_eff];
+    else tok = (int)(a.N - a.l_eff) + (r2 - a.s_eff - k_eff);
+    return (FUSED && a.pt) ? (int)paged_row(a.pt, a.page_lg, tok) : tok;
   };
 
   for (int base = r0; base < r_end; base += kGroupsPerBlock * UNR) {
@@ -339,6 +342,7 @@ hipError_t launch_attend(const Plan& pl, bool fused, const void* q, int q_first,
   AttendArgs a;
   a.q = q; a.k = k_src; a.v = v_src; a.idx = idx; a.rope = rope; a.part = part; a.out = out;
   a.k_dyn = k_dyn; a.idx_stride = idx_stride < 0 ? pl.k_eff : idx_stride; a.seq_heads = seq_heads;
+  a.pt = fused ? pl.pt : nullptr; a.page_lg = pl.page_lg;
   a.ksh = pl.ksh; a.kst = pl.kst; a.vsh = pl.vsh; a.vst = pl.vst; a.N = pl.N;
   a.Hq = pl.Hq; a.Hkv = pl.Hkv; a.G = pl.G; a.M = pl.M; a.S = pl.S;
   a.s_eff = (int)pl.s_eff; a.k_eff = pl.k_eff; a.l_eff = (int)pl.l_eff;

@@ -26,6 +26,8 @@ struct Plan {
   int64_t N, s_eff, l_eff, n_mid;
   int k_eff, S;
   int64_t ksh, kst, vsh, vst;     // strides in elements
+  const int32_t* pt;              // page table of a paged cache (device), or nullptr
+  int page_lg;                    // log2 of the page size
   float theta, scale;
   // top-k geometry for one row of n_mid scores
   int nchunks;                    // ceil(n_mid / kChunk)
@@ -175,11 +177,17 @@ template <> struct Mm<true> {
   static __device__ __forceinline__ uint16_t narrow(float x) { return __builtin_bit_cast(uint16_t, (_Float16)x); }
 };
 
+// Paged cache: token t of the sequence -> row of every head's slice of the pool.
+__device__ __forceinline__ int64_t paged_row(const int32_t* pt, int lg, int64_t tok) {
+  return ((int64_t)pt[tok >> lg] << lg) | (tok & (((int64_t)1 << lg) - 1));
+}
+
 // Rows of a token-major [n_tok][Hkv][D] block on their way into a head-major cache, as kernels see them.
 struct AppendArgs {
   const u32x4* k_new; const u32x4* v_new; char* k_cache; char* v_cache;
   int64_t first_tok, n_vec, ksh_b, kst_b, vsh_b, vst_b;    // n_vec 16-byte pieces (0: nothing to append)
   int Hkv, vec_per_row;
+  const int32_t* pt; int page_lg;                          // paged cache, or nullptr
 };
 // piece i of the block: row i / vec_per_row = t * Hkv + h
 __device__ __forceinline__ void append_piece(const AppendArgs& a, int64_t i) {
@@ -187,14 +195,15 @@ __device__ __forceinline__ void append_piece(const AppendArgs& a, int64_t i) {
   const int64_t row = i / a.vec_per_row;
   const int h = (int)(row % a.Hkv);
   const int64_t t = row / a.Hkv;
-  *(u32x4*)(a.k_cache + h * a.ksh_b + (a.first_tok + t) * a.kst_b + piece * 16) = a.k_new[i];
-  *(u32x4*)(a.v_cache + h * a.vsh_b + (a.first_tok + t) * a.vst_b + piece * 16) = a.v_new[i];
+  const int64_t r = a.pt ? paged_row(a.pt, a.page_lg, a.first_tok + t) : a.first_tok + t;
+  *(u32x4*)(a.k_cache + h * a.ksh_b + r * a.kst_b + piece * 16) = a.k_new[i];
+  *(u32x4*)(a.v_cache + h * a.vsh_b + r * a.vst_b + piece * 16) = a.v_new[i];
 }
 inline AppendArgs append_args(const Plan& pl, const AppendJob* j) {
   AppendArgs a;
   const int64_t eb = elem_bytes(pl.dtype);
   a.k_new = nullptr; a.v_new = nullptr; a.k_cache = nullptr; a.v_cache = nullptr;
-  a.first_tok = 0; a.n_vec = 0;
+  a.first_tok = 0; a.n_vec = 0; a.pt = pl.pt; a.page_lg = pl.page_lg;
   a.Hkv = pl.Hkv; a.vec_per_row = (int)(pl.D * eb / 16);
   a.ksh_b = pl.ksh * eb; a.kst_b = pl.kst * eb; a.vsh_b = pl.vsh * eb; a.vst_b = pl.vst * eb;
   if (j && j->n_tok > 0) {

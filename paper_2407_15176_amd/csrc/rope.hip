@@ -45,6 +45,7 @@ struct GatherArgs {
   const void* k; const void* v; const int32_t* idx; float* k_sel; void* v_sel;
   int64_t ksh, kst, vsh, vst, N;
   int Hkv, M, S, s_eff, k_eff, l_eff;
+  const int32_t* pt; int page_lg;                  // paged cache, or nullptr
   double omega[64];                                // w_c = theta^(-2c/D), formed on the host in fp64
 };
 
@@ -109,6 +110,7 @@ __global__ __launch_bounds__(256) void gather_rope_kernel(GatherArgs a) {
   if (r < a.s_eff) tok = r;
   else if (r < a.s_eff + a.k_eff) tok = a.idx[((int64_t)qi * a.Hkv + h) * a.k_eff + (r - a.s_eff)];
   else tok = a.N - a.l_eff + (r - a.s_eff - a.k_eff);
+  if (a.pt) tok = paged_row(a.pt, a.page_lg, tok);
   const T* kr = (const T*)a.k + (int64_t)h * a.ksh + tok * a.kst;
   const T* vr = (const T*)a.v + (int64_t)h * a.vsh + tok * a.vst;
   const Raw klo = *(const Raw*)(kr + c0), khi = *(const Raw*)(kr + D / 2 + c0);
@@ -170,7 +172,7 @@ hipError_t launch_gather_rope(const Plan& pl, const void* k_cache, const void* v
   a.k = k_cache; a.v = v_cache; a.idx = idx; a.k_sel = k_sel; a.v_sel = v_sel;
   a.ksh = pl.ksh; a.kst = pl.kst; a.vsh = pl.vsh; a.vst = pl.vst; a.N = pl.N;
   a.Hkv = pl.Hkv; a.M = pl.M; a.S = pl.S;
-  a.s_eff = (int)pl.s_eff; a.k_eff = pl.k_eff; a.l_eff = (int)pl.l_eff;
+  a.s_eff = (int)pl.s_eff; a.k_eff = pl.k_eff; a.l_eff = (int)pl.l_eff; a.pt = pl.pt; a.page_lg = pl.page_lg;
   for (int c = 0; c < pl.D / 2; ++c) a.omega[c] = exp2(-2.0 * (double)c / (double)pl.D * log2((double)pl.theta));
   const int64_t total = (int64_t)pl.M * pl.Hkv * pl.S;
   if (total == 0) return hipSuccess;

@@ -34,6 +34,8 @@ struct ScanArgs {
   int rows_per_block;
   int stream_out;       // scores leave with non-temporal stores (several rounds of workgroups: a round's burst
                         // falls into the next round's reads, and ordinary stores would cost those ~9 %)
+  const int32_t* pt;    // paged cache: the page of every 2^page_lg tokens of the sequence (PAGED kernels only)
+  int page_lg;
 };
 
 template <typename T> struct Store;
@@ -68,7 +70,9 @@ template <> struct Store<f16bits> {    // IEEE half bit patterns
 constexpr int kScanThreads = 1024;
 constexpr int kScanMaxRows = 32768;            // rows of scores one workgroup parks in LDS (128 KiB)
 
-template <typename T, int D, int U, bool HIST>
+// PAGED: the rows of a workgroup's slice are found through the page table; the few entries the slice
+// spans are copied into LDS first, so a row costs one LDS read and two integer instructions more.
+template <typename T, int D, int U, bool HIST, bool PAGED = false>
 __global__ __launch_bounds__(kScanThreads) void score_scan_kernel(ScanArgs a) {
   constexpr int EPL = Store<T>::kPerLoad;      // elements per 16-byte load
   constexpr int LPR = D / EPL;                 // lanes per key row
@@ -104,7 +108,17 @@ __global__ __launch_bounds__(kScanThreads) void score_scan_kernel(ScanArgs a) {
   const int nrows = left < a.rows_per_block ? (int)left : a.rows_per_block;
   const int64_t row_bytes = a.kst * (int64_t)sizeof(T);
   const char* kbase = (const char*)a.k +
-      ((int64_t)h * a.ksh + (a.first_tok + blk_row0) * a.kst) * (int64_t)sizeof(T) + sub * 16;
+      ((int64_t)h * a.ksh + (PAGED ? 0 : a.first_tok + blk_row0) * a.kst) * (int64_t)sizeof(T) + sub * 16;
+  // paged: pages[i] = first row of page (pg0 + i) of the sequence, pg0 the page of the slice's first token
+  int32_t* pages = (int32_t*)(lhist + (HIST ? kHistBins : 0));
+  const int64_t tok0 = a.first_tok + blk_row0;
+  const int64_t pg0 = PAGED ? tok0 >> a.page_lg : 0;
+  if (PAGED) {
+    const int n_pg = nrows > 0 ? (int)(((tok0 + nrows - 1) >> a.page_lg) - pg0) + 1 : 0;
+    for (int i = threadIdx.x; i < n_pg; i += kScanThreads) pages[i] = a.pt[pg0 + i] << a.page_lg;
+    __syncthreads();
+  }
+  const int64_t in_page = ((int64_t)1 << a.page_lg) - 1;
 
   for (int t = wave * RW; t < nrows; t += nwaves * RW) {
     u32x4 d[U];
@@ -112,7 +126,12 @@ __global__ __launch_bounds__(kScanThreads) void score_scan_kernel(ScanArgs a) {
     for (int u = 0; u < U; ++u) {
       int r = t + u * RPL + grp;
       r = r < nrows ? r : nrows - 1;           // tail rows re-read the last row; result dropped
-      d[u] = __builtin_nontemporal_load((const u32x4*)(kbase + (int64_t)r * row_bytes));
+      int64_t row = r;
+      if (PAGED) {
+        const int64_t tok = tok0 + r;
+        row = (int64_t)pages[(tok >> a.page_lg) - pg0] + (tok & in_page);
+      }
+      d[u] = __builtin_nontemporal_load((const u32x4*)(kbase + row * row_bytes));
     }
     float mine = 0.f;
 #pragma unroll
@@ -172,22 +191,22 @@ __global__ __launch_bounds__(kScanThreads) void read_probe_kernel(const u32x4* _
   if (acc == 0x9e3779b9u && sink) sink[0] = acc;   // keeps the loads alive; practically never taken
 }
 
+template <typename T, int D, bool HIST, bool PAGED>
+hipError_t launch_hp(const ScanArgs& a, dim3 grid, hipStream_t st) {
+  constexpr int U = 8;
+  const size_t lds = (size_t)a.rows_per_block * 4 + (HIST ? kHistBins * 4 : 0) +
+                     (PAGED ? ((size_t)(a.rows_per_block >> a.page_lg) + 2) * 4 : 0);
+  auto kern = score_scan_kernel<T, D, U, HIST, PAGED>;
+  hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(kern, grid, dim3(kScanThreads), lds, st, a);
+  return hipGetLastError();
+}
+
 template <typename T, int D>
 hipError_t launch_t(const ScanArgs& a, dim3 grid, bool hist, hipStream_t st) {
-  constexpr int U = 8;
-  const size_t lds = (size_t)a.rows_per_block * 4 + (hist ? kHistBins * 4 : 0);
-  if (hist) {
-    auto kern = score_scan_kernel<T, D, U, true>;
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(kern, grid, dim3(kScanThreads), lds, st, a);
-  } else {
-    auto kern = score_scan_kernel<T, D, U, false>;
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(kern, grid, dim3(kScanThreads), lds, st, a);
-  }
-  return hipGetLastError();
+  if (a.pt) return hist ? launch_hp<T, D, true, true>(a, grid, st) : launch_hp<T, D, false, true>(a, grid, st);
+  return hist ? launch_hp<T, D, true, false>(a, grid, st) : launch_hp<T, D, false, false>(a, grid, st);
 }
 
 }  // namespace
@@ -218,7 +237,7 @@ hipError_t launch_score_scan(const Plan& pl, const void* q, int n_query, const v
   ScanArgs a;
   a.k = k_cache; a.q = q; a.scores = scores; a.hist = hist;
   a.ksh = pl.ksh; a.kst = pl.kst; a.n_mid = pl.n_mid; a.first_tok = pl.s_eff;
-  a.Hq = pl.Hq; a.Hkv = pl.Hkv; a.G = pl.G;
+  a.Hq = pl.Hq; a.Hkv = pl.Hkv; a.G = pl.G; a.pt = pl.pt; a.page_lg = pl.page_lg;
   a.rows_per_block = scan_rows_per_block(pl.n_mid, (int64_t)pl.Hkv * n_query, 0);
   dim3 grid((unsigned)((pl.n_mid + a.rows_per_block - 1) / a.rows_per_block),
             (unsigned)(pl.Hkv * n_query));

@@ -92,6 +92,30 @@ def test_validate_rejects(kw, status):
     assert B.workspace_bytes(p) == 0
 
 
+def test_paged_cache_parameters_are_checked_on_the_host():
+    """Paged caches: pools [Hkv][P * page_size][D] behind a device page table (never read on the host)."""
+    L = B.lib()
+
+    def status(page_size=256, table=0x1000, **kw):
+        base = dict(n_ctx=10_000, n_local=256, top_k=64, max_position=0, k_stride_tok=128,
+                    k_stride_head=128 * 16_384, v_stride_tok=128, v_stride_head=128 * 16_384)
+        base.update(kw)
+        cp = good(**base).c()
+        cp.page_table, cp.page_size = table, page_size
+        return L.reattn_validate(C.byref(cp)), L.reattn_workspace_bytes(C.byref(cp)), cp
+
+    rc, ws, cp = status()
+    assert rc == B.OK and ws > 0
+    assert status(page_size=100)[0] == B.ERR_RANGE                 # not a power of two
+    assert status(page_size=32)[0] == B.ERR_RANGE                  # below the smallest page
+    assert status(table=None)[0] == B.ERR_NULL                     # a page size without a table
+    assert status(k_stride_tok=0, k_stride_head=0)[0] == B.ERR_SHAPE      # the pool's extent must be given
+    assert status(n_query=8)[0] == B.ERR_SHAPE                     # chunks read contiguous caches only
+    assert status(k_stride_head=128 * 2 ** 31, v_stride_head=128 * 2 ** 31)[0] == B.ERR_RANGE   # pool rows are int32
+    cv = B.Vote(4, 20, 8).c()
+    assert L.reattn_vote_workspace_bytes(C.byref(cp), C.byref(cv)) == 0    # and so do the vote scans
+
+
 def test_empty_middle_takes_any_query_count():
     # N = 3 < sink: no middle, the kept entries are simply the 3 tokens in order: plain attention
     assert B.validate(good(n_ctx=3, n_local=16, top_k=10, max_position=0)) == B.OK

@@ -1,0 +1,123 @@
+"""Paged caches: pools [Hkv][P * page_size][D] behind a device page table.
+
+A paged call reads exactly the rows a contiguous call reads, through one more indirection, and runs the
+same arithmetic in the same order: every result must equal the contiguous call's bit for bit (and the
+contiguous call is what the oracle tests pin).  Pages are scattered over a pool with spare pages that hold
+garbage, so a wrong translation shows."""
+from dataclasses import replace
+
+import pytest
+import torch
+
+from paper_2407_15176_amd import binding as B
+from paper_2407_15176_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+def _paged(w: wl.Workload, t: dict, page_size: int, seed: int, spare: int = 7):
+    """Scatters the contiguous caches of t over pools; returns (params, k_pool, v_pool, rows) with
+    rows[tok] = the pool row of token tok."""
+    N, Hkv, D = w.n_ctx, w.n_kv_heads, w.head_dim
+    n_pages = -(-N // page_size)
+    P = n_pages + spare
+    g = torch.Generator().manual_seed(seed)
+    table = torch.randperm(P, generator=g)[:n_pages].to(torch.int32)
+    tok = torch.arange(N)
+    rows = table[tok // page_size].long() * page_size + tok % page_size
+    dt = t["k"].dtype
+    gd = torch.Generator(device="cuda").manual_seed(seed)
+    k_pool = torch.randn(Hkv, P * page_size, D, generator=gd, device="cuda").to(dt)   # garbage in the unused rows
+    v_pool = torch.randn(Hkv, P * page_size, D, generator=gd, device="cuda").to(dt)
+    k_pool[:, rows.cuda()] = t["k"]
+    v_pool[:, rows.cuda()] = t["v"]
+    p = replace(B.Params.from_workload(w), k_stride_head=P * page_size * D, k_stride_tok=D,
+                v_stride_head=P * page_size * D, v_stride_tok=D, page_table=table.cuda(), page_size=page_size)
+    return p, k_pool, v_pool, rows.cuda()
+
+
+CASES = {
+    "bf16_d128_g4": (wl.CONFIGS[2].scaled(n_ctx=20_011, n_local=300, top_k=333), 64),
+    "bf16_d128_long": (wl.CONFIGS[2].scaled(n_ctx=150_001, n_local=1_000, top_k=2_000), 256),   # several workgroups per head
+    "f32_d64_g4": (wl.CONFIGS[1].scaled(n_ctx=9_973, n_local=200, top_k=100), 128),
+    "f16_d128_g3": (wl.CONFIGS[5].scaled(dtype="f16", n_ctx=17_000, n_local=257, top_k=128, max_position=0), 1024),
+    "bf16_one_page": (wl.CONFIGS[2].scaled(n_ctx=700, n_local=64, top_k=50), 1024),
+}
+
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_paged_decode_step_equals_contiguous(name):
+    w, ps = CASES[name]
+    t = wl.generate(w, "cuda")
+    p0 = B.Params.from_workload(w)
+    out0, idx0 = B.decode_step(p0, t["q"], t["k"], t["v"], B.alloc_workspace(p0), want_idx=True)
+    p, kp, vp, _ = _paged(w, t, ps, seed=11)
+    out1, idx1 = B.decode_step(p, t["q"], kp, vp, B.alloc_workspace(p), want_idx=True)
+    torch.cuda.synchronize()
+    assert torch.equal(idx0, idx1)
+    assert torch.equal(out0, out1)
+
+
+@pytest.mark.parametrize("name", ["bf16_d128_g4", "f32_d64_g4"])
+def test_paged_separate_calls_equal_contiguous(name):
+    w, ps = CASES[name]
+    t = wl.generate(w, "cuda")
+    p0 = B.Params.from_workload(w)
+    p, kp, vp, _ = _paged(w, t, ps, seed=12)
+    ws0, ws1 = B.alloc_workspace(p0), B.alloc_workspace(p)
+    s0 = B.score(p0, t["q"], t["k"], ws=ws0)
+    s1 = B.score(p, t["q"], kp, ws=ws1)
+    torch.cuda.synchronize()
+    assert torch.equal(s0, s1)
+    idx = B.topk(p0, s0, ws0)
+    k0, v0 = B.gather_rope(p0, t["k"], t["v"], idx)
+    k1, v1 = B.gather_rope(p, kp, vp, idx)
+    torch.cuda.synchronize()
+    assert torch.equal(k0, k1) and torch.equal(v0, v1)
+
+
+def test_paged_append_and_decode_token():
+    """Three layers over paged pools that share one page table: the token's rows land in the right pool rows
+    and every layer's output equals the contiguous call's."""
+    n_layers, ps = 3, 128
+    w = wl.CONFIGS[2].scaled(n_ctx=9_000, n_local=200, top_k=150, max_position=0, n_needles=0)
+    dt = w.torch_dtype()
+    Hq, Hkv, D, N = w.n_q_heads, w.n_kv_heads, w.head_dim, w.n_ctx
+    g = torch.Generator(device="cuda").manual_seed(240715000 + 91)
+    ts = [wl.generate(w, "cuda") for _ in range(n_layers)]
+    for l in range(1, n_layers):                                 # distinct caches per layer
+        ts[l]["k"] = torch.randn(Hkv, N, D, generator=g, device="cuda").to(dt)
+        ts[l]["v"] = torch.randn(Hkv, N, D, generator=g, device="cuda").to(dt)
+    qs = [torch.randn(1, Hq, D, generator=g, device="cuda").to(dt) for _ in range(n_layers)]
+    kn = [torch.randn(1, Hkv, D, generator=g, device="cuda").to(dt) for _ in range(n_layers)]
+    vn = [torch.randn(1, Hkv, D, generator=g, device="cuda").to(dt) for _ in range(n_layers)]
+    p0 = replace(B.Params.from_workload(w), n_query=1)
+    k0 = [t["k"].clone() for t in ts]; v0 = [t["v"].clone() for t in ts]
+    want = B.decode_token(p0, qs, kn, vn, k0, v0, B.alloc_workspace(p0))
+    pools = [_paged(w, t, ps, seed=13) for t in ts]              # the same seed: one page table for all layers
+    p = pools[0][0]
+    kps = [x[1] for x in pools]; vps = [x[2] for x in pools]
+    rows = pools[0][3]
+    got = B.decode_token(p, qs, kn, vn, kps, vps, B.alloc_workspace(p))
+    torch.cuda.synchronize()
+    for l in range(n_layers):
+        assert torch.equal(kps[l][:, rows[N - 1]], kn[l][0]) and torch.equal(vps[l][:, rows[N - 1]], vn[l][0])
+        assert torch.equal(kps[l][:, rows], k0[l]) and torch.equal(vps[l][:, rows], v0[l])
+        assert torch.equal(got[l], want[l]), l
+    # a block of tokens through reattn_cache_append
+    k_new = torch.randn(300, Hkv, D, generator=g, device="cuda").to(dt)
+    v_new = torch.randn(300, Hkv, D, generator=g, device="cuda").to(dt)
+    B.cache_append(p, 4_000, k_new, v_new, kps[0], vps[0])
+    torch.cuda.synchronize()
+    assert torch.equal(kps[0][:, rows[4_000:4_300]], k_new.transpose(0, 1))
+    assert torch.equal(vps[0][:, rows[4_000:4_300]], v_new.transpose(0, 1))
+
+
+def test_paged_calls_outside_the_decode_step_are_refused():
+    w, ps = CASES["bf16_d128_g4"]
+    t = wl.generate(w, "cuda")
+    p, kp, vp, _ = _paged(w, t, ps, seed=14)
+    with pytest.raises(B.ReattnError):
+        B.alloc_vote_workspace(p, B.Vote(4, 12, 16))
+    with pytest.raises(B.ReattnError):
+        B.alloc_workspace(replace(p, n_query=8))
