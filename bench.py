@@ -432,9 +432,30 @@ def paged_leg(t: dict, cfg: int, steps: int, warmup: int, page_size: int = 256) 
             stage_sum[s] += st[s]
     stages = {s: round(v / steps, 5) for s, v in stage_sum.items()}
     gbps = w.scan_bytes / (stages["scan"] * 1e-3) / 1e9
+    # the paper's vote selection (k = 4, k' = 127, m = 32) over the same pools
+    vote = B.Vote(4, 127, 32)
+    pv = replace(p, top_k=0)
+    wsv = B.alloc_vote_workspace(pv, vote)
+    sel = torch.empty(B.vote_cap(pv, vote), dtype=torch.int32, device="cuda")
+    n_sel = torch.zeros(1, dtype=torch.int32, device="cuda")
+    for _ in range(warmup):
+        B.vote_layer(pv, vote, t["q"], k_pool, v_pool, wsv, sel=sel, n_sel=n_sel, out=out)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        B.vote_layer(pv, vote, t["q"], k_pool, v_pool, wsv, sel=sel, n_sel=n_sel, out=out)
+    torch.cuda.synchronize()
+    vote_ms = (time.perf_counter() - t0) * 1e3 / steps
+    vsum = {s: 0.0 for s in B.VOTE_STAGES}
+    for _ in range(steps):
+        *_, st = B.vote_layer_timed(pv, vote, t["q"], k_pool, v_pool, wsv, sel=sel, n_sel=n_sel, out=out)
+        for s in B.VOTE_STAGES:
+            vsum[s] += st[s]
+    vstages = {s: round(v / steps, 5) for s, v in vsum.items()}
     del k_pool, v_pool
     return {"workload": w.name, "page_size": page_size, "n_pages": n_pages, "ms_per_step": round(ms, 5),
-            "stages_ms": stages, "kv_scan_GBps": round(gbps, 1), "scan_frac_of_peak": round(gbps / HBM_PEAK_GBPS, 4)}
+            "stages_ms": stages, "kv_scan_GBps": round(gbps, 1), "scan_frac_of_peak": round(gbps / HBM_PEAK_GBPS, 4),
+            "vote_4_127_32": {"ms_per_step": round(vote_ms, 5), "stages_ms": vstages}}
 
 
 def unfused_leg(t: dict, cfg: int, steps: int) -> dict:

@@ -400,7 +400,6 @@ int make_vote_plan(const reattn_params* p, const reattn_vote* v, VotePlan* out) 
   VotePlan vp;
   int rc = make_plan(&pp, &vp.pl);
   if (rc) return rc;
-  if (vp.pl.pt) return REATTN_ERR_SHAPE;               // the vote scans read contiguous caches only
   const Plan& pl = vp.pl;
   vp.kk = (int)(v->vote_k < pl.n_mid ? v->vote_k : pl.n_mid);
   vp.kc = (int)(v->n_centres < pl.n_mid ? v->n_centres : pl.n_mid);

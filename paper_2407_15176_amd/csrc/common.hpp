@@ -182,6 +182,36 @@ __device__ __forceinline__ int64_t paged_row(const int32_t* pt, int lg, int64_t 
   return ((int64_t)pt[tok >> lg] << lg) | (tok & (((int64_t)1 << lg) - 1));
 }
 
+// Paged cache, streaming kernels: a workgroup keeps the first pool rows of the pages its slice of tokens spans
+// in LDS (one spare entry behind the last), and a wave's tile of at most 64 consecutive tokens lies in at most
+// two of them (pages hold 64 tokens or more): the two bases are read once per tile into scalars and a lane
+// picks one by comparing its offset in the first page against the page size.
+__device__ __forceinline__ void slice_pages_fill(int32_t* pages, const int32_t* pt, int lg, int64_t tok0, int nrows,
+                                                 int n_threads) {
+  const int64_t pg0 = tok0 >> lg;
+  const int n_pg = nrows > 0 ? (int)(((tok0 + nrows - 1) >> lg) - pg0) + 1 : 0;
+  for (int i = threadIdx.x; i <= n_pg; i += n_threads) pages[i] = i < n_pg ? pt[pg0 + i] << lg : 0;
+  __syncthreads();
+}
+struct TilePages {
+  int32_t first, second_less_page, in0, page;
+  // pool row of token (tile's first token + c)
+  __device__ __forceinline__ int32_t row(int c) const {
+    const int32_t in = in0 + c;
+    return (in < page ? first : second_less_page) + in;
+  }
+};
+// tok = the tile's first token (wave-uniform), tok0 = the slice's first token
+__device__ __forceinline__ TilePages tile_pages(const int32_t* pages, int lg, int64_t tok0, int64_t tok) {
+  const int i = __builtin_amdgcn_readfirstlane((int)((tok >> lg) - (tok0 >> lg)));
+  TilePages t;
+  t.page = 1 << lg;
+  t.first = __builtin_amdgcn_readfirstlane(pages[i]);
+  t.second_less_page = __builtin_amdgcn_readfirstlane(pages[i + 1]) - t.page;
+  t.in0 = __builtin_amdgcn_readfirstlane((int)(tok & (t.page - 1)));
+  return t;
+}
+
 // Rows of a token-major [n_tok][Hkv][D] block on their way into a head-major cache, as kernels see them.
 struct AppendArgs {
   const u32x4* k_new; const u32x4* v_new; char* k_cache; char* v_cache;

@@ -112,25 +112,18 @@ __global__ __launch_bounds__(kScanThreads) void score_scan_kernel(ScanArgs a) {
   // paged: pages[i] = first row of page (pg0 + i) of the sequence, pg0 the page of the slice's first token
   int32_t* pages = (int32_t*)(lhist + (HIST ? kHistBins : 0));
   const int64_t tok0 = a.first_tok + blk_row0;
-  const int64_t pg0 = PAGED ? tok0 >> a.page_lg : 0;
-  if (PAGED) {
-    const int n_pg = nrows > 0 ? (int)(((tok0 + nrows - 1) >> a.page_lg) - pg0) + 1 : 0;
-    for (int i = threadIdx.x; i < n_pg; i += kScanThreads) pages[i] = a.pt[pg0 + i] << a.page_lg;
-    __syncthreads();
-  }
-  const int64_t in_page = ((int64_t)1 << a.page_lg) - 1;
+  if (PAGED) slice_pages_fill(pages, a.pt, a.page_lg, tok0, nrows, kScanThreads);
+  static_assert(RW <= 64, "a wave's tile lies in at most two pages");
 
   for (int t = wave * RW; t < nrows; t += nwaves * RW) {
     u32x4 d[U];
+    TilePages tp;
+    if (PAGED) tp = tile_pages(pages, a.page_lg, tok0, tok0 + t);
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       int r = t + u * RPL + grp;
       r = r < nrows ? r : nrows - 1;           // tail rows re-read the last row; result dropped
-      int64_t row = r;
-      if (PAGED) {
-        const int64_t tok = tok0 + r;
-        row = (int64_t)pages[(tok >> a.page_lg) - pg0] + (tok & in_page);
-      }
+      const int64_t row = PAGED ? tp.row(r - t) : r;
       d[u] = __builtin_nontemporal_load((const u32x4*)(kbase + row * row_bytes));
     }
     float mine = 0.f;
@@ -195,7 +188,7 @@ template <typename T, int D, bool HIST, bool PAGED>
 hipError_t launch_hp(const ScanArgs& a, dim3 grid, hipStream_t st) {
   constexpr int U = 8;
   const size_t lds = (size_t)a.rows_per_block * 4 + (HIST ? kHistBins * 4 : 0) +
-                     (PAGED ? ((size_t)(a.rows_per_block >> a.page_lg) + 2) * 4 : 0);
+                     (PAGED ? ((size_t)(a.rows_per_block >> a.page_lg) + 3) * 4 : 0);
   auto kern = score_scan_kernel<T, D, U, HIST, PAGED>;
   hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   if (e != hipSuccess) return e;

@@ -58,11 +58,18 @@ struct HeadScanArgs {
   uint64_t* part;          // [rows = n_query * Hq][n_wg][KT] composites, best first
   int64_t ksh, kst, n_mid, first_tok;
   int Hq, Hkv, G, rows_per_block, n_wg;
+  const int32_t* pt; int page_lg;   // paged cache (PAGED kernels): the page of every 2^page_lg tokens
 };
 
+// Paged caches: a slice of at most 16,384 rows spans at most 257 pages of 64 tokens or more (+ the spare entry);
+// a multiple of 16 bytes, so that the dynamic LDS behind it keeps its 16-byte alignment (128-bit LDS accesses).
+constexpr int kVotePages = 16384 / 64 + 4;
+static_assert(kVotePages * sizeof(int32_t) % 16 == 0, "keeps the staging tiles 16-byte aligned");
+
 // KT: list length kept per head (>= vote_k); GH: heads a lane keeps lists for (ceil(G / 2)).
-template <typename T, int D, int KT, int GH>
+template <typename T, int D, int KT, int GH, bool PAGED = false>
 __global__ __launch_bounds__(kVoteThreads) void head_topk_scan_kernel(HeadScanArgs a) {
+  __shared__ int32_t s_pages[PAGED ? kVotePages : 1];
   constexpr int EPL = Elem<T>::kPerLoad, LPR = D / EPL, RPL = 64 / LPR, U = 8, RW = U * RPL;
   static_assert(LPR == 16, "a key row spans 16 lanes (D = 128 bf16 or D = 64 fp32)");
   constexpr int GMAX = 2 * GH;
@@ -93,16 +100,22 @@ __global__ __launch_bounds__(kVoteThreads) void head_topk_scan_kernel(HeadScanAr
   const int64_t left = a.n_mid - blk_row0;
   const int nrows = left < a.rows_per_block ? (int)left : a.rows_per_block;
   const int64_t row_bytes = a.kst * (int64_t)sizeof(T);
+  const int64_t tok0 = a.first_tok + blk_row0;
   const char* kbase = (const char*)a.k +
-      ((int64_t)h * a.ksh + (a.first_tok + blk_row0) * a.kst) * (int64_t)sizeof(T) + sub * 16;
+      ((int64_t)h * a.ksh + (PAGED ? 0 : tok0) * a.kst) * (int64_t)sizeof(T) + sub * 16;
+  if (PAGED) slice_pages_fill(s_pages, a.pt, a.page_lg, tok0, nrows, kVoteThreads);
+  static_assert(RW <= 64, "a wave's tile lies in at most two pages");
 
   for (int t = wave * RW; t < nrows; t += kVoteWaves * RW) {
     u32x4 d[U];
+    TilePages tp;
+    if (PAGED) tp = tile_pages(s_pages, a.page_lg, tok0, tok0 + t);
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       int r = t + u * RPL + grp;
       r = r < nrows ? r : nrows - 1;                   // tail rows re-read the last row; result dropped
-      d[u] = __builtin_nontemporal_load((const u32x4*)(kbase + (int64_t)r * row_bytes));
+      const int64_t row = PAGED ? tp.row(r - t) : r;
+      d[u] = __builtin_nontemporal_load((const u32x4*)(kbase + row * row_bytes));
     }
     float mine[GH];
 #pragma unroll
@@ -198,15 +211,17 @@ struct MfmaScanArgs {
   uint64_t* part;          // [n_query * Hq][n_wg][KT] composites, best first
   int64_t ksh, kst, n_mid, first_tok;
   int Hq, Hkv, G, n_query, q_per_pass, rows_per_block, n_wg;
+  const int32_t* pt; int page_lg;   // paged cache (PAGED kernels)
 };
 
-template <int KT, int NB, bool F16>
+template <int KT, int NB, bool F16, bool PAGED = false>
 __global__ __launch_bounds__(kVoteThreads) void head_topk_mfma_kernel(MfmaScanArgs a) {
   typedef typename Mm<F16>::op8 op8;
+  __shared__ int32_t s_pages[PAGED ? kVotePages : 1];
   constexpr int D = 128, T = kMfmaTiles, NC = 16 * NB;
   // staging of the key tiles [kVoteWaves][T][16 rows][16 pieces] of 16 bytes while streaming,
   // then the waves' merged lists [kVoteWaves][NC][KT]
-  extern __shared__ uint64_t mfma_lds[];
+  extern __shared__ __attribute__((aligned(16))) uint64_t mfma_lds[];
   uint64_t* mfma_best = mfma_lds;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int col = lane & 15, kq = lane >> 4;
@@ -238,17 +253,23 @@ __global__ __launch_bounds__(kVoteThreads) void head_topk_mfma_kernel(MfmaScanAr
   const int64_t left = a.n_mid - blk_row0;
   const int nrows = left < a.rows_per_block ? (int)left : a.rows_per_block;
   const int64_t row_bytes = a.kst * 2;
-  const char* kbase = (const char*)a.k + ((int64_t)h * a.ksh + (a.first_tok + blk_row0) * a.kst) * 2 + col * 16;
+  const int64_t tok0 = a.first_tok + blk_row0;
+  const char* kbase = (const char*)a.k + ((int64_t)h * a.ksh + (PAGED ? 0 : tok0) * a.kst) * 2 + col * 16;
+  if (PAGED) slice_pages_fill(s_pages, a.pt, a.page_lg, tok0, nrows, kVoteThreads);
+  static_assert(16 * T <= 64, "a wave's tile lies in at most two pages");
   u32x4* my = (u32x4*)mfma_lds + wave * (T * 256);     // this wave's T tiles of 16 rows x 16 pieces
 
   // global -> registers: 1 KiB of consecutive memory per load (lane l: row l/16, piece l%16); the loads
   // of the next iteration are in flight while this one is contracted and sifted
   auto request = [&](int t, u32x4* d) {
+    TilePages tp;
+    if (PAGED) tp = tile_pages(s_pages, a.page_lg, tok0, tok0 + t);
 #pragma unroll
     for (int u = 0; u < 4 * T; ++u) {
       int r = t + u * 4 + kq;
       r = r < nrows ? r : nrows - 1;                   // tail rows re-read the last row; result dropped
-      d[u] = __builtin_nontemporal_load((const u32x4*)(kbase + (int64_t)r * row_bytes));
+      const int64_t row = PAGED ? tp.row(r - t) : r;
+      d[u] = __builtin_nontemporal_load((const u32x4*)(kbase + row * row_bytes));
     }
   };
   constexpr bool kAhead = NB == 1;                     // two column blocks leave no registers for a second batch
@@ -742,6 +763,15 @@ __global__ __launch_bounds__(kMergeThreads) void vote_pick_kernel(const uint64_t
 template <typename T, int D, int KT>
 hipError_t scan_launch_gh(const HeadScanArgs& a, dim3 grid, hipStream_t st) {
   const int gh = (a.G + 1) / 2;
+  if (a.pt) {
+    switch (gh) {
+      case 1: hipLaunchKernelGGL((head_topk_scan_kernel<T, D, KT, 1, true>), grid, dim3(kVoteThreads), 0, st, a); break;
+      case 2: hipLaunchKernelGGL((head_topk_scan_kernel<T, D, KT, 2, true>), grid, dim3(kVoteThreads), 0, st, a); break;
+      case 3: hipLaunchKernelGGL((head_topk_scan_kernel<T, D, KT, 3, true>), grid, dim3(kVoteThreads), 0, st, a); break;
+      default: hipLaunchKernelGGL((head_topk_scan_kernel<T, D, KT, 4, true>), grid, dim3(kVoteThreads), 0, st, a); break;
+    }
+    return hipGetLastError();
+  }
   switch (gh) {
     case 1: hipLaunchKernelGGL((head_topk_scan_kernel<T, D, KT, 1>), grid, dim3(kVoteThreads), 0, st, a); break;
     case 2: hipLaunchKernelGGL((head_topk_scan_kernel<T, D, KT, 2>), grid, dim3(kVoteThreads), 0, st, a); break;
@@ -814,11 +844,14 @@ hipError_t mfma_launch_nb(const MfmaScanArgs& a, int nb, dim3 grid, hipStream_t 
   static_assert((size_t)kVoteWaves * 32 * 8 * sizeof(uint64_t) <= (size_t)kVoteWaves * kMfmaTiles * 256 * 16, "lists alias the staging");
   auto k1 = head_topk_mfma_kernel<KT, 1, F16>;
   auto k2 = head_topk_mfma_kernel<KT, 2, F16>;
-  hipError_t e = hipFuncSetAttribute(nb == 1 ? (const void*)k1 : (const void*)k2,
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  auto kp = head_topk_mfma_kernel<KT, 1, F16, true>;      // a paged cache is read by decode steps: one column block
+  if (a.pt && nb != 1) return hipErrorInvalidValue;
+  const void* kern = a.pt ? (const void*)kp : nb == 1 ? (const void*)k1 : (const void*)k2;
+  hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   if (e != hipSuccess) return e;
-  if (nb == 1) hipLaunchKernelGGL(k1, grid, dim3(kVoteThreads), lds, st, a);
-  else         hipLaunchKernelGGL(k2, grid, dim3(kVoteThreads), lds, st, a);
+  if (a.pt)         hipLaunchKernelGGL(kp, grid, dim3(kVoteThreads), lds, st, a);
+  else if (nb == 1) hipLaunchKernelGGL(k1, grid, dim3(kVoteThreads), lds, st, a);
+  else              hipLaunchKernelGGL(k2, grid, dim3(kVoteThreads), lds, st, a);
   return hipGetLastError();
 }
 template <bool F16>
@@ -843,14 +876,14 @@ hipError_t launch_head_scan(const Plan& pl, const void* q, int n_query, const vo
     a.k = k_cache; a.q = q; a.part = part;
     a.ksh = pl.ksh; a.kst = pl.kst; a.n_mid = pl.n_mid; a.first_tok = pl.s_eff;
     a.Hq = pl.Hq; a.Hkv = pl.Hkv; a.G = pl.G; a.n_query = n_query; a.q_per_pass = g.q_per_pass;
-    a.rows_per_block = g.rpb; a.n_wg = g.n_wg;
+    a.rows_per_block = g.rpb; a.n_wg = g.n_wg; a.pt = pl.pt; a.page_lg = pl.page_lg;
     e = pl.dtype == kF16 ? mfma_launch_kt<true>(a, kt, g.nb, grid, st) : mfma_launch_kt<false>(a, kt, g.nb, grid, st);
   } else {
     HeadScanArgs a;
     a.k = k_cache; a.q = q; a.part = part;
     a.ksh = pl.ksh; a.kst = pl.kst; a.n_mid = pl.n_mid; a.first_tok = pl.s_eff;
     a.Hq = pl.Hq; a.Hkv = pl.Hkv; a.G = pl.G;
-    a.rows_per_block = g.rpb; a.n_wg = g.n_wg;
+    a.rows_per_block = g.rpb; a.n_wg = g.n_wg; a.pt = pl.pt; a.page_lg = pl.page_lg;
     e = scan_launch_kt<float, 64>(a, kt, grid, st);
   }
   *n_cand = g.n_wg * kt;

@@ -113,7 +113,9 @@ def test_paged_cache_parameters_are_checked_on_the_host():
     assert status(n_query=8)[0] == B.ERR_SHAPE                     # chunks read contiguous caches only
     assert status(k_stride_head=128 * 2 ** 31, v_stride_head=128 * 2 ** 31)[0] == B.ERR_RANGE   # pool rows are int32
     cv = B.Vote(4, 20, 8).c()
-    assert L.reattn_vote_workspace_bytes(C.byref(cp), C.byref(cv)) == 0    # and so do the vote scans
+    assert L.reattn_vote_workspace_bytes(C.byref(cp), C.byref(cv)) > 0     # the vote's decode step reads pages too
+    cp8 = status(n_query=8)[2]
+    assert L.reattn_vote_workspace_bytes(C.byref(cp8), C.byref(cv)) == 0   # its chunks do not
 
 
 def test_empty_middle_takes_any_query_count():

@@ -113,11 +113,65 @@ def test_paged_append_and_decode_token():
     assert torch.equal(vps[0][:, rows[4_000:4_300]], v_new.transpose(0, 1))
 
 
-def test_paged_calls_outside_the_decode_step_are_refused():
+VOTES = {
+    "bf16_d128_g4": B.Vote(4, 12, 16),
+    "bf16_d128_long": B.Vote(8, 127, 32),          # lists of 8 from many workgroups
+    "f32_d64_g4": B.Vote(2, 20, 8),                # the vector-ALU scan
+    "f16_d128_g3": B.Vote(1, 64, 4),
+    "bf16_one_page": B.Vote(4, 5, 7),
+}
+
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_paged_vote_layer_equals_contiguous(name):
+    w, ps = CASES[name]
+    v = VOTES[name]
+    t = wl.generate(w, "cuda")
+    p0 = B.Params.from_workload(w)
+    out0, sel0, n0 = B.vote_layer(p0, v, t["q"], t["k"], t["v"], B.alloc_vote_workspace(p0, v))
+    p, kp, vp, _ = _paged(w, t, ps, seed=15)
+    ws = B.alloc_vote_workspace(p, v)
+    lists1 = B.vote_topk(p, v, t["q"], kp, ws)
+    lists0 = B.vote_topk(p0, v, t["q"], t["k"], B.alloc_vote_workspace(p0, v))
+    out1, sel1, n1 = B.vote_layer(p, v, t["q"], kp, vp, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(lists0, lists1)
+    assert int(n0) == int(n1) and torch.equal(sel0[: int(n0)], sel1[: int(n1)])
+    assert torch.equal(out0, out1)
+
+
+def test_paged_vote_decode_token():
+    n_layers, ps = 2, 64
+    w = wl.CONFIGS[2].scaled(n_ctx=12_345, n_local=200, top_k=0, max_position=0, n_needles=0)
+    v = B.Vote(4, 12, 16)
+    dt = w.torch_dtype()
+    Hq, Hkv, D, N = w.n_q_heads, w.n_kv_heads, w.head_dim, w.n_ctx
+    g = torch.Generator(device="cuda").manual_seed(240715000 + 92)
+    ts = [wl.generate(w, "cuda") for _ in range(n_layers)]
+    ts[1]["k"] = torch.randn(Hkv, N, D, generator=g, device="cuda").to(dt)
+    ts[1]["v"] = torch.randn(Hkv, N, D, generator=g, device="cuda").to(dt)
+    qs = [torch.randn(1, Hq, D, generator=g, device="cuda").to(dt) for _ in range(n_layers)]
+    kn = [torch.randn(1, Hkv, D, generator=g, device="cuda").to(dt) for _ in range(n_layers)]
+    vn = [torch.randn(1, Hkv, D, generator=g, device="cuda").to(dt) for _ in range(n_layers)]
+    p0 = replace(B.Params.from_workload(w), n_query=1)
+    k0 = [t["k"].clone() for t in ts]; v0 = [t["v"].clone() for t in ts]
+    want = B.decode_token(p0, qs, kn, vn, k0, v0, B.alloc_vote_workspace(p0, v), vote=v)
+    pools = [_paged(w, t, ps, seed=16) for t in ts]
+    p = pools[0][0]
+    kps = [x[1] for x in pools]; vps = [x[2] for x in pools]
+    rows = pools[0][3]
+    got = B.decode_token(p, qs, kn, vn, kps, vps, B.alloc_vote_workspace(p, v), vote=v)
+    torch.cuda.synchronize()
+    for l in range(n_layers):
+        assert torch.equal(kps[l][:, rows], k0[l]) and torch.equal(vps[l][:, rows], v0[l])
+        assert torch.equal(got[l], want[l]), l
+
+
+def test_paged_chunks_are_refused():
     w, ps = CASES["bf16_d128_g4"]
     t = wl.generate(w, "cuda")
     p, kp, vp, _ = _paged(w, t, ps, seed=14)
     with pytest.raises(B.ReattnError):
-        B.alloc_vote_workspace(p, B.Vote(4, 12, 16))
+        B.alloc_vote_workspace(replace(p, n_query=8), B.Vote(4, 12, 16))
     with pytest.raises(B.ReattnError):
         B.alloc_workspace(replace(p, n_query=8))
