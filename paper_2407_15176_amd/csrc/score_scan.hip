@@ -115,7 +115,13 @@ __global__ __launch_bounds__(kScanThreads) void score_scan_kernel(ScanArgs a) {
   if (PAGED) slice_pages_fill(pages, a.pt, a.page_lg, tok0, nrows, kScanThreads);
   static_assert(RW <= 64, "a wave's tile lies in at most two pages");
 
-  for (int t = wave * RW; t < nrows; t += nwaves * RW) {
+  // heads start at different phases of their slices: the KV heads lie a power of two apart in a
+  // contiguous cache, and workgroups of equal index would walk the same memory channels in step
+  const int n_tile = (nrows + RW - 1) / RW;
+  const int rot = (int)((int64_t)h * n_tile / a.Hkv);
+  for (int it = wave; it < n_tile; it += nwaves) {
+    const int tile = it + rot < n_tile ? it + rot : it + rot - n_tile;
+    const int t = tile * RW;
     u32x4 d[U];
     TilePages tp;
     if (PAGED) tp = tile_pages(pages, a.page_lg, tok0, tok0 + t);
