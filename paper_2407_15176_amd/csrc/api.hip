@@ -165,15 +165,22 @@ int attend_cache(const Plan& pl, const Ws& w, char* ws, const void* q, const voi
 // `ev`, when given, holds REATTN_N_STAGES + 1 events recorded at the stage boundaries.
 inline void mark(hipEvent_t* ev, int i, hipStream_t st) { if (ev) (void)hipEventRecord(ev[i], st); }
 
+// hist_clean: the previous selection over this workspace left the histograms of these rows zeroed.
 int select_tile(const Plan& pl, const Ws& w, const void* q, int q0, int nq, const void* k_cache,
-                int32_t* idx_all, bool rope_too, hipEvent_t* ev, hipStream_t st, const AppendJob* append = nullptr) {
+                int32_t* idx_all, bool rope_too, hipEvent_t* ev, hipStream_t st, const AppendJob* append = nullptr,
+                bool hist_clean = false) {
   const int rows = nq * pl.Hkv;
   const size_t eb = (size_t)elem_bytes(pl.dtype);
   const char* qt = (const char*)q + (size_t)q0 * pl.Hq * pl.D * eb;
-  int rc = hip_rc(launch_prep(pl, pl.k_eff > 0 ? rows : 0, w.hist, rope_too ? w.rope : nullptr, st, append));
+  // new rows past the middle ride with the scan (which never reads them); otherwise with the clearing launch
+  const bool with_scan = append && pl.k_eff > 0 && append->first_tok >= pl.s_eff + pl.n_mid;
+  const int clear_rows = pl.k_eff > 0 && !hist_clean ? rows : 0;
+  int rc = REATTN_OK;
+  if (clear_rows || rope_too || (append && !with_scan))
+    rc = hip_rc(launch_prep(pl, clear_rows, w.hist, rope_too ? w.rope : nullptr, st, with_scan ? nullptr : append));
   mark(ev, 1, st);
   if (rc || pl.k_eff == 0) { mark(ev, 2, st); mark(ev, 3, st); return rc; }
-  rc = hip_rc(launch_score_scan(pl, qt, nq, k_cache, w.scores, w.hist, st));
+  rc = hip_rc(launch_score_scan(pl, qt, nq, k_cache, w.scores, w.hist, st, with_scan ? append : nullptr));
   mark(ev, 2, st);
   if (rc) return rc;
   rc = hip_rc(launch_topk(pl, rows, w.scores, true, w.hist, w.pfx, w.ncand, w.cand, w.bitmap,
@@ -212,7 +219,8 @@ int fused_prefill_select(const Plan& pl, const Ws& w, char* ws, const void* q, c
 
 int run_layer(const reattn_params* p, bool decode_only, const void* q, const void* k_cache,
               const void* v_cache, int32_t* idx_out, float* out, void* ws, size_t ws_bytes,
-              void* stream, hipEvent_t* ev = nullptr, bool rope_ready = false, const AppendJob* append = nullptr) {
+              void* stream, hipEvent_t* ev = nullptr, bool rope_ready = false, const AppendJob* append = nullptr,
+              bool hist_clean = false) {
   Plan pl;
   int rc = make_plan(p, &pl);
   if (rc) return rc;
@@ -240,7 +248,8 @@ int run_layer(const reattn_params* p, bool decode_only, const void* q, const voi
   }
   for (int q0 = 0; q0 < pl.M; q0 += pl.m_tile) {
     const int nq = pl.M - q0 < pl.m_tile ? pl.M - q0 : pl.m_tile;
-    rc = select_tile(pl, w, q, q0, nq, k_cache, idx, q0 == 0 && !rope_ready, ev, st, q0 == 0 ? append : nullptr);
+    rc = select_tile(pl, w, q, q0, nq, k_cache, idx, q0 == 0 && !rope_ready, ev, st, q0 == 0 ? append : nullptr,
+                     hist_clean && q0 == 0);
     if (rc) return rc;
   }
   rc = attend_cache(pl, w, (char*)ws, q, k_cache, v_cache, idx, out, st);
@@ -763,7 +772,8 @@ extern "C" int reattn_decode_token(const reattn_params* p, const reattn_vote* v,
     // the token's rows ride along with one of the layer's small launches
     const AppendJob job{k_new[l], v_new[l], k_cache[l], v_cache[l], pl.N - 1, 1};
     rc = v ? vote_layer_impl(&pp, v, q[l], k_cache[l], v_cache[l], nullptr, nullptr, out[l], ws, ws_bytes, stream, nullptr, l > 0, &job)
-           : run_layer(&pp, true, q[l], k_cache[l], v_cache[l], nullptr, out[l], ws, ws_bytes, stream, nullptr, l > 0, &job);
+           : run_layer(&pp, true, q[l], k_cache[l], v_cache[l], nullptr, out[l], ws, ws_bytes, stream, nullptr, l > 0, &job,
+                       l > 0);                        // layer l - 1's top-k left the histograms zeroed
   }
   return rc;
 }

@@ -56,8 +56,9 @@ hipError_t launch_prep(const Plan& pl, int rows, uint32_t* hist, float2* rope, h
                        const AppendJob* append = nullptr);
 hipError_t launch_cache_append(const Plan& pl, int64_t first_tok, int n_tok, const void* k_new, const void* v_new,
                                void* k_cache, void* v_cache, hipStream_t st);
+// append: rows of new tokens past the middle, copied into the caches by the same launch
 hipError_t launch_score_scan(const Plan& pl, const void* q, int n_query, const void* k_cache,
-                             float* scores, uint32_t* hist, hipStream_t st);
+                             float* scores, uint32_t* hist, hipStream_t st, const AppendJob* append = nullptr);
 void prefill_sampling(const Plan& pl, int64_t* stride, int64_t* n_s, uint32_t* rho, uint32_t* cap);
 size_t cand_topk_lds(const Plan& pl);
 hipError_t launch_sample_threshold(const Plan& pl, int n_query, const float* samp, int64_t n_s,
@@ -81,6 +82,8 @@ hipError_t launch_score_gemm_discard(const Plan& pl, int n_query, const void* k_
                                      const void* q_split, float* sink, hipStream_t st);
 hipError_t launch_score_gemm(const Plan& pl, const void* q, int q_first, int n_query,
                              const void* k_cache, float* scores, void* q_split, hipStream_t st);
+// The kernel that reads a row's histogram last (one workgroup per row) leaves it zeroed: the next
+// selection over the same workspace needs no clearing launch.
 hipError_t launch_topk(const Plan& pl, int rows, const float* scores, bool hist_ready,
                        uint32_t* hist, uint32_t* pfx, uint32_t* ncand, int32_t* cand,
                        uint32_t* bitmap, uint32_t* cnt, int32_t* idx, hipStream_t st);

@@ -36,6 +36,7 @@ struct ScanArgs {
                         // falls into the next round's reads, and ordinary stores would cost those ~9 %)
   const int32_t* pt;    // paged cache: the page of every 2^page_lg tokens of the sequence (PAGED kernels only)
   int page_lg;
+  AppendArgs ap;        // rows of new tokens (past the middle) to copy into the caches on the way; n_vec 0: none
 };
 
 template <typename T> struct Store;
@@ -82,6 +83,11 @@ __global__ __launch_bounds__(kScanThreads) void score_scan_kernel(ScanArgs a) {
 
   extern __shared__ float stage[];             // [rows_per_block] scores, then the histogram
   uint32_t* lhist = (uint32_t*)(stage + a.rows_per_block);
+  if (a.ap.n_vec) {                            // a decode token's own rows: a few 16-byte pieces, copied first
+    const int64_t n_thr = (int64_t)gridDim.x * gridDim.y * kScanThreads;
+    for (int64_t i = ((int64_t)blockIdx.y * gridDim.x + blockIdx.x) * kScanThreads + threadIdx.x; i < a.ap.n_vec; i += n_thr)
+      append_piece(a.ap, i);
+  }
   if (HIST) {
     for (int b = threadIdx.x; b < kHistBins; b += kScanThreads) lhist[b] = 0;
     __syncthreads();
@@ -231,9 +237,13 @@ int scan_rows_per_block(int64_t n_mid, int64_t score_rows, int max_rows) {
 }
 
 hipError_t launch_score_scan(const Plan& pl, const void* q, int n_query, const void* k_cache,
-                             float* scores, uint32_t* hist, hipStream_t st) {
-  if (pl.n_mid <= 0 || n_query <= 0) return hipSuccess;
+                             float* scores, uint32_t* hist, hipStream_t st, const AppendJob* append) {
+  if (pl.n_mid <= 0 || n_query <= 0)
+    return append ? launch_cache_append(pl, append->first_tok, append->n_tok, append->k_new, append->v_new,
+                                        append->k_cache, append->v_cache, st)
+                  : hipSuccess;
   ScanArgs a;
+  a.ap = append_args(pl, append);
   a.k = k_cache; a.q = q; a.scores = scores; a.hist = hist;
   a.ksh = pl.ksh; a.kst = pl.kst; a.n_mid = pl.n_mid; a.first_tok = pl.s_eff;
   a.Hq = pl.Hq; a.Hkv = pl.Hkv; a.G = pl.G; a.pt = pl.pt; a.page_lg = pl.page_lg;

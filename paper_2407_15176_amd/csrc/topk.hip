@@ -123,7 +123,7 @@ constexpr int kRefinePfx = 4096;      // chunks whose candidate offsets are kept
 constexpr size_t kRefineLds = 2048 * 4 + kRefinePfx * 4 + (size_t)kRefineCache * 8;
 
 __global__ __launch_bounds__(1024) void topk_refine_kernel(
-    const float* __restrict__ scores, int64_t n_mid, const uint32_t* __restrict__ hist, uint32_t k,
+    const float* __restrict__ scores, int64_t n_mid, uint32_t* __restrict__ hist, uint32_t k,
     const uint32_t* __restrict__ ncand, const int32_t* __restrict__ cand, uint32_t* gpfx,
     uint32_t* bitmap, int64_t nwords, uint32_t* cnt, int nchunks) {
   extern __shared__ uint64_t refine_lds[];
@@ -138,6 +138,9 @@ __global__ __launch_bounds__(1024) void topk_refine_kernel(
   uint32_t pbin, above;
   find_kth_bin<1024, kHistBins>(hist + (int64_t)row * kHistBins, k, sh, pbin, above);
   const uint32_t need = k - above;               // entries of the pivot bin that are selected
+  // the row's histogram has had its last reader: left zeroed for the next selection over this workspace
+  static_assert(kHistBins == 4 * 1024, "four bins per thread");
+  *(uint4*)(hist + (int64_t)row * kHistBins + 4 * threadIdx.x) = uint4{0u, 0u, 0u, 0u};
 
   // flatten the per-chunk candidate segments: exclusive prefix of their counts
   uint32_t* pfx = nchunks <= kRefinePfx ? lpfx : gpfx + (int64_t)row * nchunks;
@@ -255,7 +258,7 @@ constexpr int kRowThreads = 1024;
 constexpr size_t kRowLds = (size_t)kRowMax / 8 + (size_t)kRowCand * 8 + 2048 * 4;
 
 __global__ __launch_bounds__(kRowThreads) void topk_row_kernel(
-    const float* __restrict__ scores, int64_t n_mid, const uint32_t* __restrict__ hist, uint32_t k,
+    const float* __restrict__ scores, int64_t n_mid, uint32_t* __restrict__ hist, uint32_t k,
     int32_t index_base, int32_t* idx, int k_eff) {
   extern __shared__ uint64_t row_lds[];
   uint64_t* cand = row_lds;                                   // [kRowCand] composites; later the ranked indices
@@ -273,6 +276,9 @@ __global__ __launch_bounds__(kRowThreads) void topk_row_kernel(
   uint32_t pbin, above;
   find_kth_bin<kRowThreads, kHistBins>(hist + (int64_t)row * kHistBins, k, sh, pbin, above);
   const uint32_t need = k - above;                            // entries of the pivot bin that are selected
+  // the row's histogram has had its only reader: left zeroed for the next selection over this workspace
+  static_assert(kHistBins == 4 * kRowThreads, "four bins per thread");
+  *(uint4*)(hist + (int64_t)row * kHistBins + 4 * threadIdx.x) = uint4{0u, 0u, 0u, 0u};
   for (int w = nwords + threadIdx.x; w < nwords_pad; w += kRowThreads) bitmap[w] = 0;   // words past the row
 
   // one pass over the row: a wave takes 64 consecutive positions per load, 16 loads in flight

@@ -163,3 +163,33 @@ def test_decode_tokens_through_layers(mode, dtype):
             err = np.abs(outs[l].cpu().numpy().astype(np.float64) - ref).max()
             # random keys leave a margin of ~1e-3 relative at the k-th score: a set flip would show as a large error
             assert err <= P.OUT_TOL[dtype], (step, l, err)
+
+
+@pytest.mark.parametrize("n_ctx", [9_001, 80_001])
+def test_decode_token_layers_equal_separate_steps(n_ctx):
+    """Layers after the first skip the clearing launch (the previous layer's top-k leaves the histograms
+    zeroed) and copy the token's rows inside the scan: every layer must equal cache_append + decode_step
+    on its own workspace, bit for bit.  80,001 tokens take the chip-wide select / refine / emit kernels,
+    9,001 the one-workgroup-per-row kernel."""
+    n_layers = 4
+    w = wl.CONFIGS[2].scaled(n_ctx=n_ctx, n_local=300, top_k=500, max_position=0, n_needles=0)
+    dt = w.torch_dtype()
+    Hq, Hkv, D, N = w.n_q_heads, w.n_kv_heads, w.head_dim, w.n_ctx
+    g = torch.Generator(device="cuda").manual_seed(240715000 + 56)
+    kcs = [torch.randn(Hkv, N, D, generator=g, device="cuda").to(dt) for _ in range(n_layers)]
+    vcs = [torch.randn(Hkv, N, D, generator=g, device="cuda").to(dt) for _ in range(n_layers)]
+    qs = [torch.randn(1, Hq, D, generator=g, device="cuda").to(dt) for _ in range(n_layers)]
+    kn = [torch.randn(1, Hkv, D, generator=g, device="cuda").to(dt) for _ in range(n_layers)]
+    vn = [torch.randn(1, Hkv, D, generator=g, device="cuda").to(dt) for _ in range(n_layers)]
+    p = replace(B.Params.from_workload(w), n_query=1)
+    k2 = [x.clone() for x in kcs]; v2 = [x.clone() for x in vcs]
+    ws = B.alloc_workspace(p)
+    for rep in range(2):                                        # the second call starts on the workspace the first left
+        outs = B.decode_token(p, qs, kn, vn, kcs, vcs, ws)
+        torch.cuda.synchronize()
+        for l in range(n_layers):
+            B.cache_append(p, N - 1, kn[l], vn[l], k2[l], v2[l])
+            want, _ = B.decode_step(p, qs[l], k2[l], v2[l], B.alloc_workspace(p), want_idx=True)
+            torch.cuda.synchronize()
+            assert torch.equal(kcs[l], k2[l]) and torch.equal(vcs[l], v2[l]), (rep, l)
+            assert torch.equal(outs[l], want), (rep, l)
