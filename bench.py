@@ -20,7 +20,7 @@ import time
 
 HBM_PEAK_GBPS = 8000.0      # MI355X published HBM3E bandwidth
 # Measured with rocprofv3 --pmc (profiles/score_scan_cfg3_pmc.md): fetched + written bytes per launch.
-SCAN_TRAFFIC_BYTES = {"cfg3_decode_1m_bf16": 2 * 1044544.6 * 1024 + 32913.8 * 1024}
+SCAN_TRAFFIC_BYTES = {"cfg3_decode_1m_bf16": 2 * 1044576.9 * 1024 + 32914.1 * 1024}
 # Same for the other dominant kernels (profiles/vote_decode_cfg3_kernel_trace_pmc.md,
 # profiles/prefill_chunk_cfg4_kernel_trace_pmc.md, profiles/vote_prefill_cfg4_kernel_trace_pmc.md): fetched bytes per launch.
 VOTE_SCAN_TRAFFIC_BYTES = {"cfg3_decode_1m_bf16": 2 * 1044560.7 * 1024 + 32.0 * 1024}
