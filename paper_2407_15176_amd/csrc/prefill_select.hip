@@ -275,19 +275,8 @@ __global__ __launch_bounds__(256, 3) void cand_topk_reg_kernel(CandArgs a) {
   __shared__ uint32_t sh[40];
   const int i = blockIdx.x, h = blockIdx.y;
   const int64_t row = (int64_t)h * a.M + i;
-  const uint2* seg = a.cand + row * a.cap;
-  uint32_t key[R], pos[R];
-#pragma unroll
-  for (int r = 0; r < R; ++r) {
-    const uint32_t j = (uint32_t)r * 256u + threadIdx.x;
-    const uint2 c = seg[j < a.cap ? j : a.cap - 1];           // clamped, not predicated: all loads go out before the first wait
-    key[r] = c.x; pos[r] = c.y;
-  }
+  static_assert(R % 2 == 0, "candidates are loaded in pairs");
   const uint32_t n = a.ccount[row];
-  const int nwords = (int)((a.n_mid + 31) / 32);
-  const int nwords_pad = (nwords + 255) / 256 * 256;
-  const int nslots = wslot(nwords_pad);
-  for (int w = threadIdx.x; w < nslots; w += 256) bitmap[w] = 0;     // while the loads are in flight
   if (n < (uint32_t)a.k_eff || n > a.cap) {
     if (threadIdx.x == 0) {
       const uint32_t at = atomicAdd(&a.redo[0], 1u);
@@ -295,11 +284,28 @@ __global__ __launch_bounds__(256, 3) void cand_topk_reg_kernel(CandArgs a) {
     }
     return;
   }
+  // Two candidates per 16-byte load (segments start 16-byte aligned: the capacity is even); register slot r
+  // of thread t holds entry 2 * (256 * (r / 2) + t) + r % 2.  Only the row's own n entries are fetched: pairs
+  // past them repeat the last one (clamped, not predicated: all loads go out before the first wait).
+  const uint4* seg = (const uint4*)(a.cand + row * a.cap);
+  const uint32_t last_pair = n > 0 ? (n - 1) >> 1 : 0;
+  auto entry = [&](int r) -> uint32_t { return 2u * ((uint32_t)(r >> 1) * 256u + threadIdx.x) + (uint32_t)(r & 1); };
+  uint32_t key[R], pos[R];
+#pragma unroll
+  for (int r2 = 0; r2 < R / 2; ++r2) {
+    const uint32_t j = (uint32_t)r2 * 256u + threadIdx.x;
+    const uint4 c = seg[j < last_pair ? j : last_pair];
+    key[2 * r2] = c.x; pos[2 * r2] = c.y; key[2 * r2 + 1] = c.z; pos[2 * r2 + 1] = c.w;
+  }
+  const int nwords = (int)((a.n_mid + 31) / 32);
+  const int nwords_pad = (nwords + 255) / 256 * 256;
+  const int nslots = wslot(nwords_pad);
+  for (int w = threadIdx.x; w < nslots; w += 256) bitmap[w] = 0;     // while the loads are in flight
   uint32_t kmin = 0xffffffffu, kmax = 0u;
 #pragma unroll
   for (int r = 0; r < R; ++r) {
     key[r] = score_key(__uint_as_float(key[r]));
-    if ((uint32_t)r * 256u + threadIdx.x < n) { kmin = min(kmin, key[r]); kmax = max(kmax, key[r]); }
+    if (entry(r) < n) { kmin = min(kmin, key[r]); kmax = max(kmax, key[r]); }
   }
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) {
@@ -329,7 +335,7 @@ __global__ __launch_bounds__(256, 3) void cand_topk_reg_kernel(CandArgs a) {
       const int up = sft + w;                                // up == 32 only on a first pass: no prefix yet
 #pragma unroll
       for (int r = 0; r < R; ++r) {
-        if ((uint32_t)r * 256u + threadIdx.x < n) {
+        if (entry(r) < n) {
           const uint32_t v = on_index ? pos[r] : key[r];
           const bool in = (up >= 32 || (v >> up) == (on_index ? ppref : dpref)) && (!on_index || key[r] == dpref);
           if (in) atomicAdd(&bins[bslot((int)((v >> sft) & ((1u << w) - 1u)))], 1u);
@@ -360,7 +366,7 @@ __global__ __launch_bounds__(256, 3) void cand_topk_reg_kernel(CandArgs a) {
   }
 #pragma unroll
   for (int r = 0; r < R; ++r) {
-    if ((uint32_t)r * 256u + threadIdx.x < n) {
+    if (entry(r) < n) {
       const bool win = all || (tie ? (key[r] > dpref || (key[r] == dpref && (pos[r] >> psh) >= ppref))
                                    : (dsh >= 32 || (key[r] >> dsh) >= dpref));
       const uint32_t p = ~pos[r];
@@ -504,7 +510,7 @@ void prefill_sampling(const Plan& pl, int64_t* stride, int64_t* n_s, uint32_t* r
   double c = expect * (1.0 + 6.0 / sqrt(r)) + 64.0;
   if (c > (double)pl.n_mid) c = (double)pl.n_mid;
   if (c < (double)pl.k_eff) c = (double)pl.k_eff;
-  *stride = st; *n_s = ns; *rho = (uint32_t)r; *cap = (uint32_t)c;
+  *stride = st; *n_s = ns; *rho = (uint32_t)r; *cap = ((uint32_t)c + 1u) & ~1u;   // even: 16-byte segment starts
 }
 
 hipError_t launch_sample_threshold(const Plan& pl, int n_query, const float* samp, int64_t n_s,
