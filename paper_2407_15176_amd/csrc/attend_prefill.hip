@@ -179,6 +179,9 @@ __global__ __launch_bounds__(64) void local_keys_kernel(PfArgs a, int b0, u32x4*
   for (int x = 0; x < 8; ++x) o[x * 64] = ops[x];
 }
 
+constexpr int kFacBlocks = 4;                              // blocks per round of shared rotary factors
+constexpr size_t kFacLds = 2 * (size_t)kFacBlocks * 8 * 64 * sizeof(float4);
+
 template <int GT, bool F16>
 __global__ __launch_bounds__(256, 2) void attend_prefill_kernel(PfArgs a, int b_local0, int n_lb,
                                                                 const u32x4* __restrict__ pre) {
@@ -205,7 +208,38 @@ __global__ __launch_bounds__(256, 2) void attend_prefill_kernel(PfArgs a, int b_
     }
   }
   __syncthreads();
-  if (qi < 0) return;                                      // wave-uniform, after the only barrier
+
+  // The rotary factors of a block of slots are the same for every query, so the four waves form them for
+  // kFacBlocks blocks at a time, one block each, into LDS (two buffers: one barrier per round), and every wave
+  // reads the factors of its current block from there: a quarter of the complex products and table loads.
+  // The number of rounds is the workgroup's (wave 0 has the longest scope); a wave past the last query only
+  // produces and waits.
+  extern __shared__ __attribute__((aligned(16))) unsigned char pf_lds[];
+  float4 (*fac)[kFacBlocks][8][64] = (float4 (*)[kFacBlocks][8][64])pf_lds;      // [2][kFacBlocks][8][64]
+  const int vis0 = a.S - blockIdx.x * 4;                   // slots the workgroup's first wave sees
+  const int nblk0 = (vis0 + kBlk - 1) / kBlk;
+  const int n_round = ((nblk0 < b_local0 ? nblk0 : b_local0) + kFacBlocks - 1) / kFacBlocks;
+  auto produce = [&](int round) {
+    const int b = round * kFacBlocks + wave;
+    if (round < n_round && b < a.nb) {
+      float2 cs[2][8];
+      block_factors(t_hi + (int64_t)b * 64 + fo, [&](int x) { return tl_lds[x][lane]; }, cs);
+#pragma unroll
+      for (int x = 0; x < 8; ++x) {
+        const float2 c0 = cs[x >> 2][2 * (x & 3)], c1 = cs[x >> 2][2 * (x & 3) + 1];
+        fac[round & 1][wave][x][lane] = make_float4(c0.x, c0.y, c1.x, c1.y);
+      }
+    }
+  };
+  produce(0);
+  __syncthreads();
+  if (qi < 0) {                                            // wave-uniform: as many barriers as the other waves pass
+    for (int round = 0; round < n_round; ++round) {
+      produce(round + 1);
+      __syncthreads();
+    }
+    return;
+  }
 
   // A operand: row m = lane % 16 -> head m / 2, half m % 2 (hi, lo) of the query rotated at the
   // slot of its own key and scaled by softmax_scale * log2(e); rows past the group are zero.
@@ -343,27 +377,37 @@ __global__ __launch_bounds__(256, 2) void attend_prefill_kernel(PfArgs a, int b_
 
   // ---- phase 1: blocks with sink or selected slots: gather, rotate, split -----------------
   const int b_gen = nblk < b_local0 ? nblk : b_local0;
-  if (b_gen > 0) {
+  {
     int tok = slot_token(n);
     u32x4 kr[4];
-    load_key(tok, kr);
+    if (b_gen > 0) load_key(tok, kr);
     int tok_next = slot_token(kBlk + n);
-    for (int b = 0; b < b_gen; ++b) {
-      uint32_t vw[4][4];
-      int ts[4];
+    for (int round = 0; round < n_round; ++round) {
+      produce(round + 1);
+      const int b_end = (round + 1) * kFacBlocks < b_gen ? (round + 1) * kFacBlocks : b_gen;
+      for (int b = round * kFacBlocks; b < b_end; ++b) {
+        uint32_t vw[4][4];
+        int ts[4];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) ts[i] = __shfl(tok, 4 * j + i, 64);
-      load_values(ts, vw);
-      float2 cs[2][8];
-      block_factors(t_hi + (int64_t)b * 64 + fo, [&](int x) { return tl_lds[x][lane]; }, cs);
-      u32x4 ops[8];
-      key_operands<F16>(kr, cs, ops);
-      // the key registers are free: request the next block's rows
-      tok = tok_next;
-      if (b + 1 < b_gen) load_key(tok, kr);
-      tok_next = slot_token((b + 2) * kBlk + n);
-      const f32x4 c = logits(ops);
-      finish_block(b, c, vw);
+        for (int i = 0; i < 4; ++i) ts[i] = __shfl(tok, 4 * j + i, 64);
+        load_values(ts, vw);
+        float2 cs[2][8];
+#pragma unroll
+        for (int x = 0; x < 8; ++x) {
+          const float4 f = fac[round & 1][b - round * kFacBlocks][x][lane];
+          cs[x >> 2][2 * (x & 3)] = make_float2(f.x, f.y);
+          cs[x >> 2][2 * (x & 3) + 1] = make_float2(f.z, f.w);
+        }
+        u32x4 ops[8];
+        key_operands<F16>(kr, cs, ops);
+        // the key registers are free: request the next block's rows
+        tok = tok_next;
+        if (b + 1 < b_gen) load_key(tok, kr);
+        tok_next = slot_token((b + 2) * kBlk + n);
+        const f32x4 c = logits(ops);
+        finish_block(b, c, vw);
+      }
+      __syncthreads();                                      // the other buffer is complete; this one may be rewritten
     }
   }
   // ---- phase 2: blocks of the local window: operands formed once for the whole chunk -------
@@ -463,8 +507,11 @@ hipError_t launch_attend_prefill(const Plan& pl, const void* q, const void* k_ca
   const dim3 grid((unsigned)((pl.M + 3) / 4), (unsigned)(pl.Hkv * a.nsub));
 #define REATTN_PF_LAUNCH(GT_)                                                                                       \
   do {                                                                                                              \
-    if (f16) hipLaunchKernelGGL((attend_prefill_kernel<GT_, true>), grid, dim3(256), 0, st, a, b_local0, n_lb, pre); \
-    else     hipLaunchKernelGGL((attend_prefill_kernel<GT_, false>), grid, dim3(256), 0, st, a, b_local0, n_lb, pre); \
+    const void* kern = f16 ? (const void*)attend_prefill_kernel<GT_, true> : (const void*)attend_prefill_kernel<GT_, false>; \
+    const hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kFacLds);      \
+    if (e != hipSuccess) return e;                                                                                  \
+    if (f16) hipLaunchKernelGGL((attend_prefill_kernel<GT_, true>), grid, dim3(256), kFacLds, st, a, b_local0, n_lb, pre); \
+    else     hipLaunchKernelGGL((attend_prefill_kernel<GT_, false>), grid, dim3(256), kFacLds, st, a, b_local0, n_lb, pre); \
   } while (0)
   switch (gt) {
     case 1: REATTN_PF_LAUNCH(1); break;
