@@ -281,14 +281,18 @@ __global__ __launch_bounds__(D * NG) void attend_combine_kernel(const float* __r
   const int c = threadIdx.x % D, grp = threadIdx.x / D;
   const int64_t qh = blockIdx.x;
   const float* pp = part + qh * nsplit * (D + 2);
-  float mx = kNegBig;
-  for (int s = grp; s < nsplit; s += NG) mx = fmaxf(mx, pp[(int64_t)s * (D + 2)]);
-  float lsum = 0.f, acc = 0.f;
+  // one pass, the running maximum carried along: every load is independent of the arithmetic,
+  // so the partials arrive in one round trip
+  float mx = kNegBig, lsum = 0.f, acc = 0.f;
+#pragma unroll 4
   for (int s = grp; s < nsplit; s += NG) {
     const float* ps = pp + (int64_t)s * (D + 2);
-    const float w = exp2f(ps[0] - mx);
-    lsum = fmaf(ps[1], w, lsum);
-    acc = fmaf(ps[2 + c], w, acc);
+    const float ms = ps[0], ls = ps[1], as = ps[2 + c];
+    const float nm = fmaxf(mx, ms);
+    const float w_old = exp2f(mx - nm), w = exp2f(ms - nm);
+    lsum = fmaf(ls, w, lsum * w_old);
+    acc = fmaf(as, w, acc * w_old);
+    mx = nm;
   }
   if (c == 0) s_m[grp] = mx;
   s_l[grp][c] = lsum; s_a[grp][c] = acc;
