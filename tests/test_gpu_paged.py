@@ -175,3 +175,29 @@ def test_paged_chunks_are_refused():
         B.alloc_vote_workspace(replace(p, n_query=8), B.Vote(4, 12, 16))
     with pytest.raises(B.ReattnError):
         B.alloc_workspace(replace(p, n_query=8))
+
+
+def test_paged_batch_folded_into_heads():
+    """Two equal-length sequences folded into the head axis share one page table (the pools hold 2 * Hkv
+    head slices): the top-k step and the vote step with votes pooled per sequence equal the contiguous calls."""
+    batch = 2
+    base = wl.CONFIGS[2]
+    w = base.scaled(n_ctx=11_003, n_local=256, top_k=200, n_q_heads=base.n_q_heads * batch,
+                    n_kv_heads=base.n_kv_heads * batch, max_position=0)
+    t = wl.generate(w, "cuda")
+    p0 = B.Params.from_workload(w)
+    p, kp, vp, _ = _paged(w, t, 128, seed=17)
+    out0, idx0 = B.decode_step(p0, t["q"], t["k"], t["v"], B.alloc_workspace(p0), want_idx=True)
+    out1, idx1 = B.decode_step(p, t["q"], kp, vp, B.alloc_workspace(p), want_idx=True)
+    torch.cuda.synchronize()
+    assert torch.equal(idx0, idx1) and torch.equal(out0, out1)
+    v = B.Vote(4, 12, 16, n_seq=batch)
+    pv0, pv = replace(p0, top_k=0), replace(p, top_k=0)
+    o0, s0, n0 = B.vote_layer(pv0, v, t["q"], t["k"], t["v"], B.alloc_vote_workspace(pv0, v))
+    o1, s1, n1 = B.vote_layer(pv, v, t["q"], kp, vp, B.alloc_vote_workspace(pv, v))
+    torch.cuda.synchronize()
+    assert torch.equal(n0, n1)
+    cap = B.vote_cap(pv0, v)
+    for b in range(batch):                                       # the lists' tails past n_sel are not written
+        assert torch.equal(s0[b * cap: b * cap + int(n0[b])], s1[b * cap: b * cap + int(n1[b])]), b
+    assert torch.equal(o0, o1)
