@@ -115,11 +115,13 @@ int make_plan(const reattn_params* p, Plan* out) {
   if (pl.fused_prefill) {
     int64_t stride, n_s; uint32_t rho, cap;
     prefill_sampling(pl, &stride, &n_s, &rho, &cap);
+    int nz; uint32_t cap_z;
+    prefill_filter_splits(pl, cap, &nz, &cap_z);
     const size_t prow = (size_t)pl.M * pl.Hkv;
     pl.off_samp = off;   off += up(prow * (size_t)((n_s + 3) / 4 * 4) * 4);   // rows padded to 16 bytes
     pl.off_thr = off;    off += up(prow * 4);
-    pl.off_pcand = off;  off += up(prow * (size_t)cap * 8);
-    pl.off_pcount = off; off += up(prow * 4);
+    pl.off_pcand = off;  off += up(prow * (size_t)nz * cap_z * 8);
+    pl.off_pcount = off; off += up(prow * (size_t)nz * 4);
     pl.off_redo = off;   off += up((prow + 1) * 4);
     pl.off_exact = off;  off += up((size_t)kExactSlots * (size_t)pl.n_mid * 4);
   }
@@ -195,6 +197,8 @@ int fused_prefill_select(const Plan& pl, const Ws& w, char* ws, const void* q, c
                          int32_t* idx, hipEvent_t* ev, hipStream_t st) {
   int64_t stride, n_s; uint32_t rho, cap;
   prefill_sampling(pl, &stride, &n_s, &rho, &cap);
+  int nz; uint32_t cap_z;
+  prefill_filter_splits(pl, cap, &nz, &cap_z);
   float* samp = (float*)(ws + pl.off_samp);
   float* thr = (float*)(ws + pl.off_thr);
   uint2* cand = (uint2*)(ws + pl.off_pcand);
@@ -209,9 +213,9 @@ int fused_prefill_select(const Plan& pl, const Ws& w, char* ws, const void* q, c
   if (!rc) rc = hip_rc(launch_score_gemm_store(pl, pl.M, k_cache, w.qsplit, stride, n_s, samp, samp_stride, st));
   if (!rc) rc = hip_rc(launch_sample_threshold(pl, pl.M, samp, n_s, samp_stride, rho, thr, st));
   mark(ev, 1, st);
-  if (!rc) rc = hip_rc(launch_score_gemm_filter(pl, pl.M, k_cache, w.qsplit, thr, cand, ccount, cap, st));
+  if (!rc) rc = hip_rc(launch_score_gemm_filter(pl, pl.M, k_cache, w.qsplit, thr, cand, ccount, cap_z, nz, st));
   mark(ev, 2, st);
-  if (!rc) rc = hip_rc(launch_cand_topk(pl, pl.M, cand, ccount, cap, idx, redo, st));
+  if (!rc) rc = hip_rc(launch_cand_topk(pl, pl.M, cand, ccount, cap_z, nz, idx, redo, st));
   if (!rc) rc = hip_rc(launch_row_exact(pl, pl.M, q, k_cache, redo, exact, kExactSlots, idx, st));
   mark(ev, 3, st);
   return rc;

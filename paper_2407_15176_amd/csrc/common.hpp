@@ -60,11 +60,14 @@ hipError_t launch_cache_append(const Plan& pl, int64_t first_tok, int n_tok, con
 hipError_t launch_score_scan(const Plan& pl, const void* q, int n_query, const void* k_cache,
                              float* scores, uint32_t* hist, hipStream_t st, const AppendJob* append = nullptr);
 void prefill_sampling(const Plan& pl, int64_t* stride, int64_t* n_s, uint32_t* rho, uint32_t* cap);
+// Key splits of the fused filter (few query tiles would leave most of the chip idle) and the capacity of one
+// split's part of a row's candidate segment.
+void prefill_filter_splits(const Plan& pl, uint32_t cap, int* n_split, uint32_t* cap_split);
 size_t cand_topk_lds(const Plan& pl);
 hipError_t launch_sample_threshold(const Plan& pl, int n_query, const float* samp, int64_t n_s,
                                    int64_t row_stride, uint32_t rho, float* thr, hipStream_t st);
 hipError_t launch_cand_topk(const Plan& pl, int n_query, const uint2* cand, const uint32_t* ccount,
-                            uint32_t cap, int32_t* idx, uint32_t* redo, hipStream_t st);
+                            uint32_t cap, int n_split, int32_t* idx, uint32_t* redo, hipStream_t st);
 hipError_t launch_row_exact(const Plan& pl, int n_query, const void* q, const void* k_cache,
                             const uint32_t* redo, float* scratch, int n_slots, int32_t* idx,
                             hipStream_t st);
@@ -77,7 +80,7 @@ hipError_t launch_score_gemm_store(const Plan& pl, int n_query, const void* k_ca
                                    float* scores, int64_t score_stride, hipStream_t st);
 hipError_t launch_score_gemm_filter(const Plan& pl, int n_query, const void* k_cache,
                                     const void* q_split, const float* thr, uint2* cand,
-                                    uint32_t* ccount, uint32_t cap, hipStream_t st);
+                                    uint32_t* ccount, uint32_t cap, int n_split, hipStream_t st);
 hipError_t launch_score_gemm_discard(const Plan& pl, int n_query, const void* k_cache,
                                      const void* q_split, float* sink, hipStream_t st);
 hipError_t launch_score_gemm(const Plan& pl, const void* q, int q_first, int n_query,

@@ -197,7 +197,8 @@ __global__ __launch_bounds__(256) void sample_threshold_kernel(const float* __re
 
 // ---- cand_topk ---------------------------------------------------------------
 struct CandArgs {
-  const uint2* cand; const uint32_t* ccount; uint32_t cap;
+  const uint2* cand; const uint32_t* ccount; uint32_t cap;   // row r: n_split parts of cap entries, counts ccount[r * n_split + z]
+  int n_split;
   int M, Hkv, k_eff; int64_t n_mid; int32_t index_base;
   int32_t* idx;              // [M][Hkv][k_eff]
   uint32_t* redo;            // redo[0] = count, redo[1..] = rows (h*M + i)
@@ -276,27 +277,56 @@ __global__ __launch_bounds__(256, 3) void cand_topk_reg_kernel(CandArgs a) {
   const int i = blockIdx.x, h = blockIdx.y;
   const int64_t row = (int64_t)h * a.M + i;
   static_assert(R % 2 == 0, "candidates are loaded in pairs");
-  const uint32_t n = a.ccount[row];
-  if (n < (uint32_t)a.k_eff || n > a.cap) {
-    if (threadIdx.x == 0) {
+  // The row's candidates sit in n_split parts (one per key split of the filter), part z holding cnt[z] of
+  // them.  Two candidates per 16-byte load (parts start 16-byte aligned: the capacity is even); the parts'
+  // pairs are numbered through, pair j of the row goes to register slots 2j', 2j'+1 of thread j % 256.  Only
+  // the row's own entries are fetched: pairs past them repeat the last one (clamped, not predicated: all
+  // loads go out before the first wait).  valid: bit r set when register slot r holds a candidate.
+  __shared__ uint32_t s_first[9], s_cnt[8];                  // first pair of each part; its count
+  if (threadIdx.x == 0) {
+    const uint32_t* cnt = a.ccount + row * a.n_split;
+    uint32_t pairs = 0, total = 0, over = 0;
+    for (int z = 0; z < a.n_split; ++z) {
+      const uint32_t c = cnt[z];
+      over |= c > a.cap ? 1u : 0u;
+      s_first[z] = pairs; s_cnt[z] = c;
+      pairs += (c + 1) >> 1; total += c;
+    }
+    s_first[8] = pairs;
+    sh[0] = total; sh[1] = over;
+  }
+  __syncthreads();
+  const uint32_t n = sh[0], n_pair = s_first[8];
+  if (sh[1] || n < (uint32_t)a.k_eff || n_pair > 256u * (R / 2) || n == 0) {
+    if (threadIdx.x == 0 && (sh[1] || n < (uint32_t)a.k_eff || n_pair > 256u * (R / 2))) {
       const uint32_t at = atomicAdd(&a.redo[0], 1u);
       a.redo[1 + at] = (uint32_t)row;
     }
     return;
   }
-  // Two candidates per 16-byte load (segments start 16-byte aligned: the capacity is even); register slot r
-  // of thread t holds entry 2 * (256 * (r / 2) + t) + r % 2.  Only the row's own n entries are fetched: pairs
-  // past them repeat the last one (clamped, not predicated: all loads go out before the first wait).
-  const uint4* seg = (const uint4*)(a.cand + row * a.cap);
-  const uint32_t last_pair = n > 0 ? (n - 1) >> 1 : 0;
-  auto entry = [&](int r) -> uint32_t { return 2u * ((uint32_t)(r >> 1) * 256u + threadIdx.x) + (uint32_t)(r & 1); };
+  const uint4* seg = (const uint4*)(a.cand + row * a.n_split * a.cap);
+  const uint32_t part_pairs = a.cap >> 1;
   uint32_t key[R], pos[R];
+  uint64_t valid = 0;
 #pragma unroll
   for (int r2 = 0; r2 < R / 2; ++r2) {
     const uint32_t j = (uint32_t)r2 * 256u + threadIdx.x;
-    const uint4 c = seg[j < last_pair ? j : last_pair];
+    const uint32_t jc = j < n_pair ? j : n_pair - 1;
+    uint32_t first = 0, cnt = s_cnt[0], part = 0;
+    for (int z = 1; z < a.n_split; ++z) {                   // the last part that starts at or before pair jc
+      const uint32_t f = s_first[z];
+      if (jc >= f) { first = f; cnt = s_cnt[z]; part = (uint32_t)z; }
+    }
+    const uint32_t local = jc - first;
+    const uint4 c = seg[part * part_pairs + local];
     key[2 * r2] = c.x; pos[2 * r2] = c.y; key[2 * r2 + 1] = c.z; pos[2 * r2 + 1] = c.w;
+    if (j < n_pair) {
+      if (2 * local < cnt) valid |= 1ull << (2 * r2);
+      if (2 * local + 1 < cnt) valid |= 1ull << (2 * r2 + 1);
+    }
   }
+  auto live = [&](int r) -> bool { return (valid >> r) & 1ull; };
+  __syncthreads();                                           // sh is reused below
   const int nwords = (int)((a.n_mid + 31) / 32);
   const int nwords_pad = (nwords + 255) / 256 * 256;
   const int nslots = wslot(nwords_pad);
@@ -305,7 +335,7 @@ __global__ __launch_bounds__(256, 3) void cand_topk_reg_kernel(CandArgs a) {
 #pragma unroll
   for (int r = 0; r < R; ++r) {
     key[r] = score_key(__uint_as_float(key[r]));
-    if (entry(r) < n) { kmin = min(kmin, key[r]); kmax = max(kmax, key[r]); }
+    if (live(r)) { kmin = min(kmin, key[r]); kmax = max(kmax, key[r]); }
   }
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) {
@@ -335,7 +365,7 @@ __global__ __launch_bounds__(256, 3) void cand_topk_reg_kernel(CandArgs a) {
       const int up = sft + w;                                // up == 32 only on a first pass: no prefix yet
 #pragma unroll
       for (int r = 0; r < R; ++r) {
-        if (entry(r) < n) {
+        if (live(r)) {
           const uint32_t v = on_index ? pos[r] : key[r];
           const bool in = (up >= 32 || (v >> up) == (on_index ? ppref : dpref)) && (!on_index || key[r] == dpref);
           if (in) atomicAdd(&bins[bslot((int)((v >> sft) & ((1u << w) - 1u)))], 1u);
@@ -366,7 +396,7 @@ __global__ __launch_bounds__(256, 3) void cand_topk_reg_kernel(CandArgs a) {
   }
 #pragma unroll
   for (int r = 0; r < R; ++r) {
-    if (entry(r) < n) {
+    if (live(r)) {
       const bool win = all || (tie ? (key[r] > dpref || (key[r] == dpref && (pos[r] >> psh) >= ppref))
                                    : (dsh >= 32 || (key[r] >> dsh) >= dpref));
       const uint32_t p = ~pos[r];
@@ -513,6 +543,26 @@ void prefill_sampling(const Plan& pl, int64_t* stride, int64_t* n_s, uint32_t* r
   *stride = st; *n_s = ns; *rho = (uint32_t)r; *cap = ((uint32_t)c + 1u) & ~1u;   // even: 16-byte segment starts
 }
 
+void prefill_filter_splits(const Plan& pl, uint32_t cap, int* n_split, uint32_t* cap_split) {
+  const int64_t wgs = (int64_t)pl.Hkv * ((pl.M + 127) / 128);       // workgroups of the filter without a key split
+  const int64_t n_tiles = (pl.n_mid + 127) / 128;
+  int64_t z = 1;
+  if (wgs < 128 && cap <= 256u * 40u) {                  // the register kernel reads the parts; its limit is 8
+    z = (256 + wgs - 1) / wgs;
+    if (z > 8) z = 8;
+    if (z > n_tiles) z = n_tiles;
+    if (z < 1) z = 1;
+    const int64_t per = (n_tiles + z - 1) / z;           // tiles per split; the last split may be shorter
+    z = (n_tiles + per - 1) / per;
+  }
+  // candidates are not spread evenly over the keys: a part takes three times its even share (a row that
+  // overflows one goes to the exact redo)
+  uint64_t c = cap;
+  if (z > 3) c = ((uint64_t)3 * cap + z - 1) / z;
+  *n_split = (int)z;
+  *cap_split = ((uint32_t)c + 1u) & ~1u;
+}
+
 hipError_t launch_sample_threshold(const Plan& pl, int n_query, const float* samp, int64_t n_s,
                                    int64_t row_stride, uint32_t rho, float* thr, hipStream_t st) {
   // the sample of prefill_sampling() is shorter than 2 * 8192 keys
@@ -535,13 +585,15 @@ size_t cand_topk_lds(const Plan& pl) {                     // selection bitmap o
 }
 
 hipError_t launch_cand_topk(const Plan& pl, int n_query, const uint2* cand, const uint32_t* ccount,
-                            uint32_t cap, int32_t* idx, uint32_t* redo, hipStream_t st) {
+                            uint32_t cap, int n_split, int32_t* idx, uint32_t* redo, hipStream_t st) {
   CandArgs a;
-  a.cand = cand; a.ccount = ccount; a.cap = cap; a.M = n_query; a.Hkv = pl.Hkv; a.k_eff = pl.k_eff;
+  a.cand = cand; a.ccount = ccount; a.cap = cap; a.n_split = n_split < 1 ? 1 : n_split;
+  a.M = n_query; a.Hkv = pl.Hkv; a.k_eff = pl.k_eff;
   a.n_mid = pl.n_mid; a.index_base = (int32_t)pl.s_eff; a.idx = idx; a.redo = redo;
   const size_t lds = cand_topk_lds(pl);
   // set on every launch: the attribute belongs to the current device, and nothing is remembered between calls
   constexpr int kRegs = 40;                               // segments of up to 10,240 candidates stay in registers
+  if (a.n_split > 1 && (a.n_split > 8 || cap > 256u * kRegs)) return hipErrorInvalidValue;   // splits are read by the register kernel only
   auto kern = cap <= 256u * kRegs ? cand_topk_reg_kernel<kRegs> : cand_topk_kernel;
   hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   if (e != hipSuccess) return e;

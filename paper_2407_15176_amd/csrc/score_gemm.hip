@@ -80,7 +80,8 @@ struct GemmArgs {
   // STORE: scores[(i * Hkv + h) * score_stride + key]
   float* scores; int64_t score_stride;
   // FILTER: per-row threshold, candidate segments and counts (row = h * M + i)
-  const float* thr; uint2* cand; uint32_t* ccount; uint32_t cap;
+  const float* thr; uint2* cand; uint32_t* ccount; uint32_t cap;   // cap: of one key split's part of a row's segment
+  int n_split;              // FILTER: key splits (blockIdx.z); split z of row r owns segment part and count r * n_split + z
 };
 
 enum { kStore = 0, kFilter = 1, kDiscard = 2 };
@@ -132,7 +133,7 @@ __global__ __launch_bounds__(kGemmThreads) void score_gemm_kernel(GemmArgs a) {
     for (int qb = 0; qb < 2; ++qb) {
       const int qi = q0 + (qw * 2 + qb) * 32 + ln;
       thr[qb] = qi < a.M ? a.thr[(int64_t)h * a.M + qi] : __builtin_inff();
-      seg[qb] = a.cand + ((int64_t)h * a.M + qi) * a.cap;
+      seg[qb] = a.cand + (((int64_t)h * a.M + qi) * a.n_split + blockIdx.z) * a.cap;
     }
   }
   // filter mode: this wave's 32 x 64 scores of the previous tile, as 8 rows of 64 float4:
@@ -309,7 +310,7 @@ __global__ __launch_bounds__(kGemmThreads) void score_gemm_kernel(GemmArgs a) {
   if (MODE == kFilter) {
     if (n_tiles > 0) append_hits(tile0 + n_tiles - 1, pending);   // the last tile has no successor to hide behind
     __syncthreads();
-    if (tid < kTileQ && q0 + tid < a.M) a.ccount[(int64_t)h * a.M + q0 + tid] = lcount[tid];
+    if (tid < kTileQ && q0 + tid < a.M) a.ccount[((int64_t)h * a.M + q0 + tid) * a.n_split + blockIdx.z] = lcount[tid];
   }
 }
 
@@ -334,7 +335,7 @@ GemmArgs base_args(const Plan& pl, int n_query, const void* k_cache, const void*
   a.M = n_query; a.m_pad = gemm_m_pad(n_query); a.Hkv = pl.Hkv; a.f16 = pl.dtype == kF16;
   a.tiles_per_block = 0;
   a.scores = nullptr; a.score_stride = 0;
-  a.thr = nullptr; a.cand = nullptr; a.ccount = nullptr; a.cap = 0;
+  a.thr = nullptr; a.cand = nullptr; a.ccount = nullptr; a.cap = 0; a.n_split = 1;
   return a;
 }
 
@@ -376,17 +377,18 @@ hipError_t launch_score_gemm_store(const Plan& pl, int n_query, const void* k_ca
   return gemm_launch<kStore>(a, grid, st);
 }
 
-// Fused filter over all n_mid keys: candidates with score >= thr[h*M + i] go to cand[(h*M + i) * cap ...],
-// ccount[h*M + i] receives the number of hits (which may exceed cap: the excess is dropped).
+// Fused filter over all n_mid keys, the keys cut into n_split equal runs of tiles (blockIdx.z): candidates of
+// row r = h*M + i with score >= thr[r] found by split z go to cand[(r * n_split + z) * cap ...], and
+// ccount[r * n_split + z] receives their number (which may exceed cap: the excess is dropped).
 hipError_t launch_score_gemm_filter(const Plan& pl, int n_query, const void* k_cache,
                                     const void* q_split, const float* thr, uint2* cand,
-                                    uint32_t* ccount, uint32_t cap, hipStream_t st) {
+                                    uint32_t* ccount, uint32_t cap, int n_split, hipStream_t st) {
   if (n_query <= 0 || pl.n_mid <= 0) return hipSuccess;
   GemmArgs a = base_args(pl, n_query, k_cache, q_split);
-  a.thr = thr; a.cand = cand; a.ccount = ccount; a.cap = cap;
+  a.thr = thr; a.cand = cand; a.ccount = ccount; a.cap = cap; a.n_split = n_split < 1 ? 1 : n_split;
   const int64_t n_tiles = (pl.n_mid + kTileKeys - 1) / kTileKeys;
-  a.tiles_per_block = (int)n_tiles;
-  const dim3 grid((unsigned)pl.Hkv, (unsigned)(a.m_pad / 128), 1u);
+  a.tiles_per_block = (int)((n_tiles + a.n_split - 1) / a.n_split);
+  const dim3 grid((unsigned)pl.Hkv, (unsigned)(a.m_pad / 128), (unsigned)a.n_split);
   return gemm_launch<kFilter>(a, grid, st);
 }
 

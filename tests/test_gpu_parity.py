@@ -292,6 +292,25 @@ def test_prefill_chunk_redo_path_on_degenerate_scores():
     P.check_layer(w, t, out, idx)
 
 
+def test_prefill_chunk_key_splits_skewed_and_even():
+    """Few query tiles: the filter cuts the keys into splits, each with its own part of a row's candidate
+    segment.  With a direction shared by the queries and the keys at the start of the middle nearly every candidate of every
+    row falls into the first split, whose part overflows: those rows take the exact redo; an even cache takes
+    the split parts as they come.  Both must equal the oracle."""
+    w = wl.CONFIGS[4].scaled(n_ctx=24_000, n_query=64, n_local=512, top_k=2_048, n_needles=0, max_position=0)
+    t = gen(w)
+    out, idx = P.run_layer(w, t)
+    P.check_layer(w, t, out, idx, q_rows=[0, 1, 31, 62, 63])
+    # a direction shared by every query and by the keys of the first of the eight splits (2,944 keys)
+    u = 2 * torch.randn(w.head_dim, generator=torch.Generator(device="cuda").manual_seed(5), device="cuda")
+    t["q"] = (t["q"].float() + u).to(t["q"].dtype)
+    t["k"][:, w.n_sink: w.n_sink + 2_900] = (t["k"][:, w.n_sink: w.n_sink + 2_900].float() + u).to(t["k"].dtype)
+    out, idx = P.run_layer(w, t)
+    # nearly every selection sits in the first split, whose part holds 3/8 of a segment
+    assert int((idx < w.n_sink + 2_900).sum()) > 0.9 * idx.numel()
+    P.check_layer(w, t, out, idx, q_rows=[0, 1, 31, 62, 63])
+
+
 @pytest.mark.parametrize("dtype", ["bf16", "f16"])
 def test_prefill_chunk_mixed_redo_rows(dtype):
     """Some query rows are zero (redo path), the others take the filtered path."""
