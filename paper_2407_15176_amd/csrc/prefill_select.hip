@@ -308,14 +308,23 @@ __global__ __launch_bounds__(256, 3) void cand_topk_reg_kernel(CandArgs a) {
   const uint32_t part_pairs = a.cap >> 1;
   uint32_t key[R], pos[R];
   uint64_t valid = 0;
+  uint32_t pfirst[8], pcnt[8];                               // the parts' first pairs and counts, in registers
+#pragma unroll
+  for (int z = 0; z < 8; ++z) {
+    pfirst[z] = z < a.n_split ? s_first[z] : 0xffffffffu;    // no pair reaches a part that is not there
+    pcnt[z] = z < a.n_split ? s_cnt[z] : 0u;
+  }
 #pragma unroll
   for (int r2 = 0; r2 < R / 2; ++r2) {
     const uint32_t j = (uint32_t)r2 * 256u + threadIdx.x;
     const uint32_t jc = j < n_pair ? j : n_pair - 1;
-    uint32_t first = 0, cnt = s_cnt[0], part = 0;
-    for (int z = 1; z < a.n_split; ++z) {                   // the last part that starts at or before pair jc
-      const uint32_t f = s_first[z];
-      if (jc >= f) { first = f; cnt = s_cnt[z]; part = (uint32_t)z; }
+    uint32_t first = 0, cnt = pcnt[0], part = 0;
+    if (a.n_split > 1) {                                     // the last part that starts at or before pair jc
+#pragma unroll
+      for (int z = 1; z < 8; ++z) {
+        const bool at = jc >= pfirst[z];
+        first = at ? pfirst[z] : first; cnt = at ? pcnt[z] : cnt; part = at ? (uint32_t)z : part;
+      }
     }
     const uint32_t local = jc - first;
     const uint4 c = seg[part * part_pairs + local];
