@@ -556,7 +556,7 @@ void prefill_filter_splits(const Plan& pl, uint32_t cap, int* n_split, uint32_t*
   const int64_t wgs = (int64_t)pl.Hkv * ((pl.M + 127) / 128);       // workgroups of the filter without a key split
   const int64_t n_tiles = (pl.n_mid + 127) / 128;
   int64_t z = 1;
-  if (wgs < 128 && cap <= 256u * 40u) {                  // the register kernel reads the parts; its limit is 8
+  if (wgs < 256 && cap <= 256u * 40u) {                  // the register kernel reads the parts; its limit is 8
     z = (256 + wgs - 1) / wgs;
     if (z > 8) z = 8;
     if (z > n_tiles) z = n_tiles;

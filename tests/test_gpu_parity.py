@@ -311,6 +311,15 @@ def test_prefill_chunk_key_splits_skewed_and_even():
     P.check_layer(w, t, out, idx, q_rows=[0, 1, 31, 62, 63])
 
 
+def test_prefill_chunk_two_key_splits():
+    """144 workgroups (16 KV heads x 9 query tiles) are cut into two key splits, each with a full-size part."""
+    w = wl.CONFIGS[4].scaled(n_ctx=21_000, n_query=1_100, n_local=1_200, top_k=512, n_q_heads=32, n_kv_heads=16,
+                             n_needles=0, max_position=0)
+    t = gen(w)
+    out, idx = P.run_layer(w, t)
+    P.check_layer(w, t, out, idx, q_rows=[0, 127, 128, 555, 1_098, 1_099])
+
+
 @pytest.mark.parametrize("dtype", ["bf16", "f16"])
 def test_prefill_chunk_mixed_redo_rows(dtype):
     """Some query rows are zero (redo path), the others take the filtered path."""
