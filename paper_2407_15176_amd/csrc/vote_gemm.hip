@@ -280,11 +280,12 @@ hipError_t vote_gemm_launch(const VoteGemmArgs& a, dim3 grid, hipStream_t st) {
 
 }  // namespace
 
-// Key splits of the chunk contraction: enough workgroups for two rounds over the chip.
+// Key splits of the chunk contraction: enough workgroups for one round over the chip (one workgroup per CU: a
+// second round only repeats the insertion-heavy start of every running list).
 int vote_gemm_splits(const Plan& pl, int n_query) {
   const int64_t col_tiles = ((int64_t)n_query * pl.G + kTileCols - 1) / kTileCols;
   const int64_t n_tiles = (pl.n_mid + kTileKeys - 1) / kTileKeys;
-  int64_t split = (512 + col_tiles * pl.Hkv - 1) / (col_tiles * pl.Hkv);
+  int64_t split = (256 + col_tiles * pl.Hkv - 1) / (col_tiles * pl.Hkv);
   if (split > n_tiles) split = n_tiles;
   if (split < 1) split = 1;
   const int64_t per = (n_tiles + split - 1) / split;        // tiles per workgroup
