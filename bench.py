@@ -248,6 +248,8 @@ def prefill_leg(steps: int) -> dict:
     alg = w.score_flops                                   # 2*M*Hq*N_mid*D: every head scored (Eq. 2)
     executed = 2 * w.n_query * w.n_kv_heads * w.n_mid * w.head_dim * 2   # hi + lo of the group sum
     alg_tf = alg / (gemm_ms * 1e-3) / 1e12
+    visible = w.n_query * w.scope - w.n_query * (w.n_query - 1) // 2      # slots seen, summed over the chunk's rows
+    gather = visible * w.n_kv_heads * 2 * w.head_dim * t["k"].element_size()
     return {
         "workload": w.name, "ms_per_chunk": round(ms_chunk, 3), "steps": steps,
         "tokens_per_s": round(w.n_query / (ms_chunk * 1e-3), 1),
@@ -261,6 +263,12 @@ def prefill_leg(steps: int) -> dict:
             "executed_TFLOPs": round(executed / (gemm_ms * 1e-3) / 1e12, 1),
             "executed_frac": round(executed / (gemm_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
             "traffic": GEMM_FILTER_TRAFFIC_BYTES,
+        },
+        # Eq. 3 of the chunk: every query row gathers its own kept K and V rows (causal inside the chunk); the
+        # rows requested per second against the HBM peak (part of them is served by L2 and the memory-side cache)
+        "attend_gather": {
+            "kernel": "attend_prefill_kernel", "requested_bytes": gather,
+            "requested_GBps": round(gather / (acc["attend"] * 1e-3) / 1e9, 1), "hbm_peak_GBps": HBM_PEAK_GBPS,
         },
     }
 
