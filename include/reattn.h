@@ -86,9 +86,8 @@ typedef struct reattn_params {
    * of every head's slice.  page_table is a DEVICE array of ceil(N / page_size) int32 page numbers in
    * [0, P); the library cannot read it on the host, so entries outside the pool are the caller's fault.
    * page_size is a power of two >= 64; the four strides must be given (stride_head >= P * page_size * D).
-   * Served: decode steps (M == 1) of both selections: reattn_score, reattn_gather_rope, reattn_decode_step,
-   * reattn_vote_topk, reattn_vote_layer, reattn_decode_token with or without votes, and reattn_cache_append;
-   * calls with M > 1 return REATTN_ERR_SHAPE for paged params.  Indices (idx, sel, head_topk) stay token
+   * Every call that reads or writes a cache takes paged params (decode steps and chunks of both selections,
+   * the chunk loop, the decode token, reattn_cache_append).  Indices (idx, sel, head_topk) stay token
    * positions of the sequence. */
   const int32_t* page_table;
   int32_t page_size;

@@ -57,7 +57,6 @@ int make_plan(const reattn_params* p, Plan* out) {
     if (!p->page_table) return REATTN_ERR_NULL;
     if (p->page_size < 64 || (p->page_size & (p->page_size - 1))) return REATTN_ERR_RANGE;
     if (kdef || vdef) return REATTN_ERR_SHAPE;         // the pool's extent is not the sequence's: strides must be given
-    if (pl.M != 1) return REATTN_ERR_SHAPE;            // served: the decode step of the per-KV-head top-k
     if (pl.ksh / pl.D > 0x7fffffffLL || pl.vsh / pl.D > 0x7fffffffLL) return REATTN_ERR_RANGE;   // pool rows are int32
     pl.pt = p->page_table;
     while ((1 << pl.page_lg) < p->page_size) ++pl.page_lg;
@@ -157,9 +156,18 @@ inline int hip_rc(hipError_t e) { return e == hipSuccess ? REATTN_OK : REATTN_ER
 // and KV head), everything else the flash-decoding kernel with its split-S combine.
 int attend_cache(const Plan& pl, const Ws& w, char* ws, const void* q, const void* k_cache,
                  const void* v_cache, const int32_t* idx, float* out, hipStream_t st) {
-  if (attend_prefill_applies(pl))                          // an empty middle (M > l) is the same walk: every slot is its own token
+  if (attend_prefill_applies(pl)) {                        // an empty middle (M > l) is the same walk: every slot is its own token
+    bool rows = false;
+    if (pl.pt && pl.k_eff > 0) {
+      // paged cache: the selected tokens' pool rows are looked up once, into the workspace's index block
+      // (in place when the indices already live there: then nobody else reads them)
+      const int rc = hip_rc(launch_translate_rows(pl, idx, w.idx, (int64_t)pl.M * pl.Hkv * pl.k_eff, st));
+      if (rc) return rc;
+      idx = w.idx; rows = true;
+    }
     return hip_rc(launch_attend_prefill(pl, q, k_cache, v_cache, idx, (float2*)(ws + pl.off_rope16),
-                                        out, st));
+                                        out, st, rows));
+  }
   return hip_rc(launch_attend(pl, true, q, 0, pl.M, k_cache, v_cache, idx, w.rope, w.part, out, st));
 }
 

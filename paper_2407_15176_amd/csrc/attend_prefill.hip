@@ -39,6 +39,8 @@ struct PfArgs {
   const uint16_t* q; const uint16_t* k; const uint16_t* v;
   const int32_t* idx; const float2* rope; float* out;
   int64_t ksh, kst, vsh, vst, N;
+  const int32_t* pt; int page_lg;            // paged cache (nullptr: none): token -> row of the head's pool slice
+  int idx_is_rows;                           // idx already holds pool rows (paged: looked up once per chunk)
   int Hq, Hkv, G, M, S, s_eff, k_eff, l_eff, nsub;
   int nb;                                    // rows of the per-block table: ceil(S / 16)
   float scale_log2e;
@@ -164,7 +166,8 @@ __global__ __launch_bounds__(64) void local_keys_kernel(PfArgs a, int b0, u32x4*
     }
     float2 cs[2][8];
     block_factors(t_hi + (int64_t)b * 64 + fo, [&](int x) { return tl[x]; }, cs);
-    const int64_t tok = a.N - a.l_eff + (r - a.s_eff - a.k_eff);
+    int64_t tok = a.N - a.l_eff + (r - a.s_eff - a.k_eff);
+    if (a.pt) tok = paged_row(a.pt, a.page_lg, tok);
     const uint16_t* row = a.k + (int64_t)h * a.ksh + tok * a.kst + fo;
     u32x4 kr[4];
 #pragma unroll
@@ -182,7 +185,8 @@ __global__ __launch_bounds__(64) void local_keys_kernel(PfArgs a, int b0, u32x4*
 constexpr int kFacBlocks = 4;                              // blocks per round of shared rotary factors
 constexpr size_t kFacLds = 2 * (size_t)kFacBlocks * 8 * 64 * sizeof(float4);
 
-template <int GT, bool F16>
+// PAGED: cache rows are found through the page table (selected slots come translated in idx).
+template <int GT, bool F16, bool PAGED = false>
 __global__ __launch_bounds__(256, 2) void attend_prefill_kernel(PfArgs a, int b_local0, int n_lb,
                                                                 const u32x4* __restrict__ pre) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -278,9 +282,13 @@ __global__ __launch_bounds__(256, 2) void attend_prefill_kernel(PfArgs a, int b_
 
   auto slot_token = [&](int r) -> int {                    // cache row of slot r (clamped into the scope)
     const int rc = r < visible ? r : visible - 1;
-    if (rc < a.s_eff) return rc;
-    if (rc < a.s_eff + a.k_eff) return my_idx[rc - a.s_eff];
-    return (int)(a.N - a.l_eff) + (rc - a.s_eff - a.k_eff);
+    int tok;
+    if (rc < a.s_eff) tok = rc;
+    else if (rc < a.s_eff + a.k_eff) {
+      tok = my_idx[rc - a.s_eff];
+      if (PAGED && a.idx_is_rows) return tok;
+    } else tok = (int)(a.N - a.l_eff) + (rc - a.s_eff - a.k_eff);
+    return PAGED ? (int)paged_row(a.pt, a.page_lg, tok) : tok;   // a paged cache: the row of the head's pool slice
   };
   const uint16_t* kh = a.k + (int64_t)h * a.ksh + fo;
   const uint16_t* vh = a.v + (int64_t)h * a.vsh + 2 * n;
@@ -417,13 +425,25 @@ __global__ __launch_bounds__(256, 2) void attend_prefill_kernel(PfArgs a, int b_
     u32x4 ops[8];
 #pragma unroll
     for (int x = 0; x < 8; ++x) ops[x] = pp[x * 64];
-    for (int b = b_local0; b < nblk; ++b) {
-      uint32_t vw[4][4];
-      int ts[4];
+    auto local_rows = [&](int b, int* ts) {                 // cache rows of this lane's four slots of block b
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const int r = b * kBlk + 4 * j + i;
         ts[i] = tok0 + (r < visible ? r : visible - 1);
+        if (PAGED) ts[i] = (int)paged_row(a.pt, a.page_lg, ts[i]);
+      }
+    };
+    int ts_next[4];
+    if (PAGED) local_rows(b_local0, ts_next);
+    for (int b = b_local0; b < nblk; ++b) {
+      uint32_t vw[4][4];
+      int ts[4];
+      if (PAGED) {                                          // the next block's page entries are on their way
+#pragma unroll
+        for (int i = 0; i < 4; ++i) ts[i] = ts_next[i];
+        if (b + 1 < nblk) local_rows(b + 1, ts_next);
+      } else {
+        local_rows(b, ts);
       }
       load_values(ts, vw);
       const f32x4 c = logits(ops);
@@ -481,11 +501,12 @@ bool attend_prefill_applies(const Plan& pl) {
 // out[i][hq] for all M queries; `table` is scratch of attend_prefill_table_bytes().
 hipError_t launch_attend_prefill(const Plan& pl, const void* q, const void* k_cache,
                                  const void* v_cache, const int32_t* idx, float2* table, float* out,
-                                 hipStream_t st) {
+                                 hipStream_t st, bool idx_is_rows) {
   PfArgs a;
   a.q = (const uint16_t*)q; a.k = (const uint16_t*)k_cache; a.v = (const uint16_t*)v_cache;
   a.idx = idx; a.rope = table; a.out = out;
-  a.ksh = pl.ksh; a.kst = pl.kst; a.vsh = pl.vsh; a.vst = pl.vst; a.N = pl.N;
+  a.ksh = pl.ksh; a.kst = pl.kst; a.vsh = pl.vsh; a.vst = pl.vst; a.N = pl.N; a.pt = pl.pt; a.page_lg = pl.page_lg;
+  a.idx_is_rows = idx_is_rows ? 1 : 0;
   a.Hq = pl.Hq; a.Hkv = pl.Hkv; a.G = pl.G; a.M = pl.M; a.S = pl.S;
   a.s_eff = (int)pl.s_eff; a.k_eff = pl.k_eff; a.l_eff = (int)pl.l_eff;
   a.nb = pf_blocks(pl);
@@ -505,13 +526,17 @@ hipError_t launch_attend_prefill(const Plan& pl, const void* q, const void* k_ca
     else     hipLaunchKernelGGL(local_keys_kernel<false>, dim3((unsigned)n_lb, (unsigned)pl.Hkv), dim3(64), 0, st, a, b_local0, pre);
   }
   const dim3 grid((unsigned)((pl.M + 3) / 4), (unsigned)(pl.Hkv * a.nsub));
+#define REATTN_PF_LAUNCH_P(GT_, F16_, PAGED_)                                                                       \
+  do {                                                                                                              \
+    auto kern = attend_prefill_kernel<GT_, F16_, PAGED_>;                                                           \
+    const hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kFacLds); \
+    if (e != hipSuccess) return e;                                                                                  \
+    hipLaunchKernelGGL(kern, grid, dim3(256), kFacLds, st, a, b_local0, n_lb, pre);                                 \
+  } while (0)
 #define REATTN_PF_LAUNCH(GT_)                                                                                       \
   do {                                                                                                              \
-    const void* kern = f16 ? (const void*)attend_prefill_kernel<GT_, true> : (const void*)attend_prefill_kernel<GT_, false>; \
-    const hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kFacLds);      \
-    if (e != hipSuccess) return e;                                                                                  \
-    if (f16) hipLaunchKernelGGL((attend_prefill_kernel<GT_, true>), grid, dim3(256), kFacLds, st, a, b_local0, n_lb, pre); \
-    else     hipLaunchKernelGGL((attend_prefill_kernel<GT_, false>), grid, dim3(256), kFacLds, st, a, b_local0, n_lb, pre); \
+    if (a.pt) { if (f16) REATTN_PF_LAUNCH_P(GT_, true, true); else REATTN_PF_LAUNCH_P(GT_, false, true); }          \
+    else      { if (f16) REATTN_PF_LAUNCH_P(GT_, true, false); else REATTN_PF_LAUNCH_P(GT_, false, false); }        \
   } while (0)
   switch (gt) {
     case 1: REATTN_PF_LAUNCH(1); break;
@@ -520,6 +545,7 @@ hipError_t launch_attend_prefill(const Plan& pl, const void* q, const void* k_ca
     default: REATTN_PF_LAUNCH(4); break;
   }
 #undef REATTN_PF_LAUNCH
+#undef REATTN_PF_LAUNCH_P
   return hipGetLastError();
 }
 

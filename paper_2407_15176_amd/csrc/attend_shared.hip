@@ -61,6 +61,7 @@ struct SharedArgs {
   uint16_t* qp;       // [M][Hq][2][128]  rotated, scaled queries, hi then lo
   float* out;         // [M][Hq][128]
   int64_t ksh, kst, vsh, vst, N;
+  const int32_t* pt; int page_lg;               // paged cache (nullptr: none)
   int Hq, Hkv, G, M, s_eff, l_eff, s_pad;
   float scale_log2e;
 };
@@ -87,6 +88,7 @@ __global__ __launch_bounds__(256) void pack_shared_kernel(SharedArgs a) {
     if (r < a.s_eff) tok = r;
     else if (r < a.s_eff + n_sel) tok = a.sel[r - a.s_eff];
     else tok = a.N - a.l_eff + (r - a.s_eff - n_sel);
+    if (a.pt) tok = paged_row(a.pt, a.page_lg, tok);
     const uint16_t* kr = a.k + (int64_t)h * a.ksh + tok * a.kst;
     const uint16_t* vr = a.v + (int64_t)h * a.vsh + tok * a.vst;
     klo = *(const u32x4*)(kr + c0); khi = *(const u32x4*)(kr + 64 + c0);
@@ -331,7 +333,7 @@ hipError_t launch_attend_shared(const Plan& pl, const void* q, const void* k_cac
   a.q = (const uint16_t*)q; a.k = (const uint16_t*)k_cache; a.v = (const uint16_t*)v_cache;
   a.sel = sel; a.n_sel = n_sel; a.rope = rope; a.rope_n_hi = rope_rows_hi(pl.S);
   a.kp = (uint16_t*)kp; a.vp = (uint16_t*)vp; a.qp = (uint16_t*)qp; a.out = out;
-  a.ksh = pl.ksh; a.kst = pl.kst; a.vsh = pl.vsh; a.vst = pl.vst; a.N = pl.N;
+  a.ksh = pl.ksh; a.kst = pl.kst; a.vsh = pl.vsh; a.vst = pl.vst; a.N = pl.N; a.pt = pl.pt; a.page_lg = pl.page_lg;
   a.Hq = pl.Hq; a.Hkv = pl.Hkv; a.G = pl.G; a.M = pl.M;
   a.s_eff = (int)pl.s_eff; a.l_eff = (int)pl.l_eff; a.s_pad = attend_shared_spad(pl);
   a.scale_log2e = pl.scale * 1.4426950408889634f;

@@ -131,7 +131,9 @@ size_t attend_prefill_table_bytes(const Plan& pl);
 bool attend_prefill_applies(const Plan& pl);
 hipError_t launch_attend_prefill(const Plan& pl, const void* q, const void* k_cache,
                                  const void* v_cache, const int32_t* idx, float2* table, float* out,
-                                 hipStream_t st);
+                                 hipStream_t st, bool idx_is_rows = false);
+// rows[i] = pool row of token idx[i] (paged caches; rows may be idx itself)
+hipError_t launch_translate_rows(const Plan& pl, const int32_t* idx, int32_t* rows, int64_t n, hipStream_t st);
 
 // ---- device helpers ---------------------------------------------------------
 #ifdef __HIPCC__

@@ -465,6 +465,7 @@ __global__ __launch_bounds__(256, 3) void cand_topk_reg_kernel(CandArgs a) {
 struct ExactArgs {
   const uint16_t* q; const uint16_t* k;
   int64_t ksh, kst, first_tok, n_mid;
+  const int32_t* pt; int page_lg;   // paged cache (nullptr: none)
   int M, Hq, Hkv, G, k_eff; int32_t index_base;
   const uint32_t* redo;
   float* scratch;            // [gridDim.x][n_mid] scores
@@ -491,11 +492,12 @@ __global__ __launch_bounds__(1024) void row_exact_kernel(ExactArgs a) {
 #pragma unroll
       for (int c = 0; c < 8; ++c) qv[c] += Mm<F16>::widen(qr[c]);
     }
-    const uint16_t* kb = a.k + (int64_t)h * a.ksh + a.first_tok * a.kst + sub * 8;
+    const uint16_t* kb = a.k + (int64_t)h * a.ksh + (a.pt ? 0 : a.first_tok) * a.kst + sub * 8;
     for (int64_t j0 = (int64_t)wave * 4; j0 < a.n_mid; j0 += 64) {
       int64_t j = j0 + grp;
       const int64_t jc = j < a.n_mid ? j : a.n_mid - 1;
-      const u32x4 d = *(const u32x4*)(kb + jc * a.kst);
+      const int64_t krow = a.pt ? paged_row(a.pt, a.page_lg, a.first_tok + jc) : jc;
+      const u32x4 d = *(const u32x4*)(kb + krow * a.kst);
       float s = 0.f;
       const uint32_t dw[4] = {d.x, d.y, d.z, d.w};
 #pragma unroll
@@ -615,7 +617,7 @@ hipError_t launch_row_exact(const Plan& pl, int n_query, const void* q, const vo
                             hipStream_t st) {
   ExactArgs a;
   a.q = (const uint16_t*)q; a.k = (const uint16_t*)k_cache;
-  a.ksh = pl.ksh; a.kst = pl.kst; a.first_tok = pl.s_eff; a.n_mid = pl.n_mid;
+  a.ksh = pl.ksh; a.kst = pl.kst; a.first_tok = pl.s_eff; a.n_mid = pl.n_mid; a.pt = pl.pt; a.page_lg = pl.page_lg;
   a.M = n_query; a.Hq = pl.Hq; a.Hkv = pl.Hkv; a.G = pl.G; a.k_eff = pl.k_eff;
   a.index_base = (int32_t)pl.s_eff; a.redo = redo; a.scratch = scratch; a.idx = idx;
   if (pl.dtype == kF16) hipLaunchKernelGGL(row_exact_kernel<true>, dim3(n_slots), dim3(1024), 0, st, a);

@@ -138,6 +138,21 @@ __global__ __launch_bounds__(256) void cache_append_kernel(AppendArgs a) {
 
 }  // namespace
 
+namespace {
+__global__ __launch_bounds__(256) void translate_rows_kernel(const int32_t* idx, int32_t* rows, int64_t n,
+                                                             const int32_t* pt, int page_lg) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n) rows[i] = (int32_t)paged_row(pt, page_lg, idx[i]);
+}
+}  // namespace
+
+hipError_t launch_translate_rows(const Plan& pl, const int32_t* idx, int32_t* rows, int64_t n, hipStream_t st) {
+  if (n <= 0 || !pl.pt) return hipSuccess;
+  hipLaunchKernelGGL(translate_rows_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, idx, rows, n, pl.pt,
+                     pl.page_lg);
+  return hipGetLastError();
+}
+
 hipError_t launch_cache_append(const Plan& pl, int64_t first_tok, int n_tok, const void* k_new, const void* v_new,
                                void* k_cache, void* v_cache, hipStream_t st) {
   if (n_tok <= 0) return hipSuccess;

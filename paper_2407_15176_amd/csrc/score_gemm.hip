@@ -81,6 +81,7 @@ struct GemmArgs {
   float* scores; int64_t score_stride;
   // FILTER: per-row threshold, candidate segments and counts (row = h * M + i)
   const float* thr; uint2* cand; uint32_t* ccount; uint32_t cap;   // cap: of one key split's part of a row's segment
+  const int32_t* pt; int page_lg;   // paged cache (nullptr: none): token -> row of the head's pool slice
   int n_split;              // FILTER: key splits (blockIdx.z); split z of row r owns segment part and count r * n_split + z
 };
 
@@ -154,7 +155,15 @@ __global__ __launch_bounds__(kGemmThreads) void score_gemm_kernel(GemmArgs a) {
   const char* next = kbase + (tile0 * kTileKeys + srow) * row_bytes;   // this thread's piece of the next tile to request
   u32x4 stg[kStageNS];
   auto load_tile = [&](int64_t tile, u32x4* s) {
-    if ((tile + 1) * kTileKeys <= a.n_keys) {                // wave-uniform: every tile but a ragged last one
+    if (a.pt) {                                              // paged cache: every row through the page table
+      const char* hbase = (const char*)(a.k + (int64_t)h * a.ksh) + scol * 16;
+#pragma unroll
+      for (int j = 0; j < kStageNS; ++j) {
+        int64_t key = tile * kTileKeys + srow + RS * j;
+        if (key >= a.n_keys) key = a.n_keys - 1;
+        s[j] = *(const u32x4*)(hbase + paged_row(a.pt, a.page_lg, a.first_tok + key * a.key_step) * a.kst * 2);
+      }
+    } else if ((tile + 1) * kTileKeys <= a.n_keys) {         // wave-uniform: every tile but a ragged last one
 #pragma unroll
       for (int j = 0; j < kStageNS; ++j) s[j] = *(const u32x4*)(next + (int64_t)(RS * j) * row_bytes);
     } else {
@@ -333,6 +342,7 @@ GemmArgs base_args(const Plan& pl, int n_query, const void* k_cache, const void*
   a.k = (const uint16_t*)k_cache; a.qs = (const uint16_t*)q_split;
   a.ksh = pl.ksh; a.kst = pl.kst; a.first_tok = pl.s_eff; a.n_keys = pl.n_mid; a.key_step = 1;
   a.M = n_query; a.m_pad = gemm_m_pad(n_query); a.Hkv = pl.Hkv; a.f16 = pl.dtype == kF16;
+  a.pt = pl.pt; a.page_lg = pl.page_lg;
   a.tiles_per_block = 0;
   a.scores = nullptr; a.score_stride = 0;
   a.thr = nullptr; a.cand = nullptr; a.ccount = nullptr; a.cap = 0; a.n_split = 1;

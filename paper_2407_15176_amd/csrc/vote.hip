@@ -844,14 +844,18 @@ hipError_t mfma_launch_nb(const MfmaScanArgs& a, int nb, dim3 grid, hipStream_t 
   static_assert((size_t)kVoteWaves * 32 * 8 * sizeof(uint64_t) <= (size_t)kVoteWaves * kMfmaTiles * 256 * 16, "lists alias the staging");
   auto k1 = head_topk_mfma_kernel<KT, 1, F16>;
   auto k2 = head_topk_mfma_kernel<KT, 2, F16>;
-  auto kp = head_topk_mfma_kernel<KT, 1, F16, true>;      // a paged cache is read by decode steps: one column block
-  if (a.pt && nb != 1) return hipErrorInvalidValue;
-  const void* kern = a.pt ? (const void*)kp : nb == 1 ? (const void*)k1 : (const void*)k2;
+  auto p1 = head_topk_mfma_kernel<KT, 1, F16, true>;      // the same over a paged cache
+  auto p2 = head_topk_mfma_kernel<KT, 2, F16, true>;
+  const void* kern = a.pt ? (nb == 1 ? (const void*)p1 : (const void*)p2) : (nb == 1 ? (const void*)k1 : (const void*)k2);
   hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   if (e != hipSuccess) return e;
-  if (a.pt)         hipLaunchKernelGGL(kp, grid, dim3(kVoteThreads), lds, st, a);
-  else if (nb == 1) hipLaunchKernelGGL(k1, grid, dim3(kVoteThreads), lds, st, a);
-  else              hipLaunchKernelGGL(k2, grid, dim3(kVoteThreads), lds, st, a);
+  if (a.pt) {
+    if (nb == 1) hipLaunchKernelGGL(p1, grid, dim3(kVoteThreads), lds, st, a);
+    else         hipLaunchKernelGGL(p2, grid, dim3(kVoteThreads), lds, st, a);
+  } else {
+    if (nb == 1) hipLaunchKernelGGL(k1, grid, dim3(kVoteThreads), lds, st, a);
+    else         hipLaunchKernelGGL(k2, grid, dim3(kVoteThreads), lds, st, a);
+  }
   return hipGetLastError();
 }
 template <bool F16>

@@ -41,6 +41,7 @@ struct VoteGemmArgs {
   const uint16_t* q;        // [n_query][Hq][128] bf16 bits
   uint64_t* part;           // [n_query * Hq][n_split][KT] composites, best first
   int64_t ksh, kst, first_tok, n_keys;
+  const int32_t* pt; int page_lg;   // paged cache (nullptr: none)
   int n_query, Hq, G, n_split, tiles_per_block;
 };
 
@@ -107,7 +108,15 @@ __global__ __launch_bounds__(kThreads) void vote_gemm_kernel(VoteGemmArgs a) {
   const char* next = kbase + (tile0 * kTileKeys + srow) * row_bytes;
   u32x4 stg[kStageNS];
   auto load_tile = [&](int64_t tile, u32x4* s) {
-    if ((tile + 1) * kTileKeys <= a.n_keys) {                // every tile but a ragged last one
+    if (a.pt) {                                              // paged cache: every row through the page table
+      const char* hbase = (const char*)(a.k + (int64_t)h * a.ksh) + scol * 16;
+#pragma unroll
+      for (int j = 0; j < kStageNS; ++j) {
+        int64_t key = tile * kTileKeys + srow + RS * j;
+        if (key >= a.n_keys) key = a.n_keys - 1;
+        s[j] = *(const u32x4*)(hbase + paged_row(a.pt, a.page_lg, a.first_tok + key) * row_bytes);
+      }
+    } else if ((tile + 1) * kTileKeys <= a.n_keys) {         // every tile but a ragged last one
 #pragma unroll
       for (int j = 0; j < kStageNS; ++j) s[j] = *(const u32x4*)(next + (int64_t)(RS * j) * row_bytes);
     } else {
@@ -298,7 +307,7 @@ hipError_t launch_vote_gemm(const Plan& pl, const void* q, int n_query, const vo
   if (n_query <= 0 || pl.n_mid <= 0) return hipSuccess;
   VoteGemmArgs a;
   a.k = (const uint16_t*)k_cache; a.q = (const uint16_t*)q; a.part = part;
-  a.ksh = pl.ksh; a.kst = pl.kst; a.first_tok = pl.s_eff; a.n_keys = pl.n_mid;
+  a.ksh = pl.ksh; a.kst = pl.kst; a.first_tok = pl.s_eff; a.n_keys = pl.n_mid; a.pt = pl.pt; a.page_lg = pl.page_lg;
   a.n_query = n_query; a.Hq = pl.Hq; a.G = pl.G;
   a.n_split = vote_gemm_splits(pl, n_query);
   const int64_t n_tiles = (pl.n_mid + kTileKeys - 1) / kTileKeys;

@@ -167,14 +167,81 @@ def test_paged_vote_decode_token():
         assert torch.equal(got[l], want[l]), l
 
 
-def test_paged_chunks_are_refused():
-    w, ps = CASES["bf16_d128_g4"]
+CHUNKS = {
+    # matrix-core selection and attention, several query tiles, key splits of the filter
+    "bf16_mfma": (wl.CONFIGS[4].scaled(n_ctx=40_003, n_query=300, n_local=512, top_k=700, max_position=0), 128),
+    "f16_mfma": (wl.CONFIGS[4].scaled(dtype="f16", n_ctx=20_000, n_query=65, n_local=300, top_k=256, max_position=0), 64),
+    # the streaming scan once per query row and the flash-decoding kernel
+    "f32_scan": (wl.CONFIGS[1].scaled(n_ctx=6_001, n_query=5, n_local=64, top_k=100, max_position=0), 256),
+    # a zero query row: every score ties, the exact redo reads the pages
+    "bf16_redo": (wl.CONFIGS[4].scaled(n_ctx=15_000, n_query=9, n_local=300, top_k=200, max_position=0), 1024),
+}
+
+
+@pytest.mark.parametrize("name", list(CHUNKS))
+def test_paged_prefill_chunk_equals_contiguous(name):
+    w, ps = CHUNKS[name]
     t = wl.generate(w, "cuda")
-    p, kp, vp, _ = _paged(w, t, ps, seed=14)
-    with pytest.raises(B.ReattnError):
-        B.alloc_vote_workspace(replace(p, n_query=8), B.Vote(4, 12, 16))
-    with pytest.raises(B.ReattnError):
-        B.alloc_workspace(replace(p, n_query=8))
+    if name == "bf16_redo":
+        t["q"][4].zero_()
+    p0 = B.Params.from_workload(w)
+    out0, idx0 = B.prefill_chunk(p0, t["q"], t["k"], t["v"], B.alloc_workspace(p0), want_idx=True)
+    p, kp, vp, _ = _paged(w, t, ps, seed=21)
+    out1, idx1 = B.prefill_chunk(p, t["q"], kp, vp, B.alloc_workspace(p), want_idx=True)
+    torch.cuda.synchronize()
+    assert torch.equal(idx0, idx1)
+    assert torch.equal(out0, out1)
+
+
+@pytest.mark.parametrize("M,dtype", [(6, "bf16"), (40, "bf16"), (300, "f16"), (3, "f32")])
+def test_paged_vote_chunk_equals_contiguous(M, dtype):
+    """6 query rows take the streaming scan with two column blocks, 40 and 300 the tiled contraction and the
+    shared-set attention, fp32 the vector-ALU scan."""
+    base = wl.CONFIGS[4] if dtype != "f32" else wl.CONFIGS[1]
+    w = base.scaled(dtype=dtype, n_ctx=18_000, n_query=M, n_local=400, top_k=0, max_position=0)
+    v = B.Vote(4, 30, 16)
+    t = wl.generate(w, "cuda")
+    p0 = B.Params.from_workload(w)
+    ws0 = B.alloc_vote_workspace(p0, v)
+    lists0 = B.vote_topk(p0, v, t["q"], t["k"], ws0)
+    out0, sel0, n0 = B.vote_layer(p0, v, t["q"], t["k"], t["v"], ws0)
+    p, kp, vp, _ = _paged(w, t, 128, seed=22)
+    ws = B.alloc_vote_workspace(p, v)
+    lists1 = B.vote_topk(p, v, t["q"], kp, ws)
+    out1, sel1, n1 = B.vote_layer(p, v, t["q"], kp, vp, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(lists0, lists1)
+    assert int(n0) == int(n1) and torch.equal(sel0[: int(n0)], sel1[: int(n1)])
+    assert torch.equal(out0, out1)
+
+
+@pytest.mark.parametrize("mode", ["topk", "vote"])
+def test_paged_prefill_sequence_equals_contiguous(mode):
+    """The chunk loop of one layer writes the rows of every chunk through the page table and reads them back
+    through it: outputs and the pools' contents equal the contiguous run."""
+    L, chunk, ps = 3_000, 256, 64
+    w = wl.CONFIGS[2].scaled(n_ctx=L, n_local=300, top_k=0 if mode == "vote" else 128, max_position=0, n_needles=0)
+    vote = B.Vote(4, 12, 16) if mode == "vote" else None
+    dt = w.torch_dtype()
+    Hq, Hkv, D = w.n_q_heads, w.n_kv_heads, w.head_dim
+    g = torch.Generator(device="cuda").manual_seed(240715000 + 93)
+    q = torch.randn(L, Hq, D, generator=g, device="cuda").to(dt)
+    k_new = torch.randn(L, Hkv, D, generator=g, device="cuda").to(dt)
+    v_new = torch.randn(L, Hkv, D, generator=g, device="cuda").to(dt)
+    p0 = replace(B.Params.from_workload(w), n_query=1)
+    want = B.prefill_sequence(p0, chunk, q, k_new, v_new, vote=vote)
+    # empty pools behind a scattered page table
+    n_pages = -(-L // ps); P = n_pages + 5
+    table = torch.randperm(P, generator=torch.Generator().manual_seed(23))[:n_pages].to(torch.int32)
+    kp = torch.zeros(Hkv, P * ps, D, dtype=dt, device="cuda"); vp = torch.zeros_like(kp)
+    p = replace(p0, k_stride_head=P * ps * D, k_stride_tok=D, v_stride_head=P * ps * D, v_stride_tok=D,
+                page_table=table.cuda(), page_size=ps)
+    got = B.prefill_sequence(p, chunk, q, k_new, v_new, kp, vp, vote=vote)
+    torch.cuda.synchronize()
+    tok = torch.arange(L)
+    rows = (table[tok // ps].long() * ps + tok % ps).cuda()
+    assert torch.equal(kp[:, rows], k_new.transpose(0, 1)) and torch.equal(vp[:, rows], v_new.transpose(0, 1))
+    assert torch.equal(got["out"], want["out"])
 
 
 def test_paged_batch_folded_into_heads():
