@@ -58,6 +58,7 @@ def main() -> int:
     ap.add_argument("--no-token", action="store_true", help="skip the 32-layer decode-token leg")
     ap.add_argument("--only-paged", action="store_true", help="run the paged-cache decode step alone")
     ap.add_argument("--no-paged", action="store_true", help="skip the paged-cache decode step")
+    ap.add_argument("--only-paged-prefill", action="store_true", help="run the paged-cache prefill chunk alone")
     ap.add_argument("--only-unfused", action="store_true",
                     help="run the four separate calls (score, top-k, gather + rotary, attend) alone")
     ap.add_argument("--no-unfused", action="store_true", help="skip the leg of the four separate calls")
@@ -93,6 +94,9 @@ def main() -> int:
         return 0
     if args.only_vote_prefill:
         print(json.dumps({"vote_prefill": vote_prefill_leg(min(args.steps, 5), args.chunk)}), flush=True)
+        return 0
+    if args.only_paged_prefill:
+        print(json.dumps({"paged_prefill": paged_prefill_leg(args.steps if args.steps < 5 else 5)}))
         return 0
     if args.only_paged:
         print(json.dumps({"paged_decode": paged_leg(wl.generate(wl.CONFIGS[args.config], "cuda"), args.config,
@@ -192,6 +196,8 @@ def main() -> int:
         result["unfused_calls"] = unfused_leg(t, args.config, args.steps)
     if not args.no_paged:
         result["paged_decode"] = paged_leg(t, args.config, args.steps, args.warmup)
+        if not args.no_prefill:
+            result["paged_prefill"] = paged_prefill_leg(5)
     if not args.no_prefill:
         del ks, vs, t, ws
         torch.cuda.empty_cache()
@@ -464,6 +470,50 @@ def paged_leg(t: dict, cfg: int, steps: int, warmup: int, page_size: int = 256) 
     return {"workload": w.name, "page_size": page_size, "n_pages": n_pages, "ms_per_step": round(ms, 5),
             "stages_ms": stages, "kv_scan_GBps": round(gbps, 1), "scan_frac_of_peak": round(gbps / HBM_PEAK_GBPS, 4),
             "vote_4_127_32": {"ms_per_step": round(vote_ms, 5), "stages_ms": vstages}}
+
+
+def paged_prefill_leg(steps: int, page_size: int = 256) -> dict:
+    """Config 4's chunk (both selections) over a paged cache: the keys and values scattered page by page
+    (a seeded random permutation) over pools [Hkv][P * page_size][D] behind a device page table."""
+    import torch
+    from dataclasses import replace
+    from paper_2407_15176_amd import binding as B
+    from paper_2407_15176_amd import workloads as wl
+    w = wl.CONFIGS[4]
+    t = wl.generate(w, "cuda")
+    N, Hkv, D = w.n_ctx, w.n_kv_heads, w.head_dim
+    n_pages = -(-N // page_size)
+    table = torch.randperm(n_pages, generator=torch.Generator().manual_seed(240715000 + 49)).to(torch.int32)
+    tc = table.cuda().long()
+    k_pool = torch.empty(Hkv, n_pages * page_size, D, dtype=t["k"].dtype, device="cuda")
+    v_pool = torch.empty_like(k_pool)
+    for src, dst in ((t["k"], k_pool), (t["v"], v_pool)):
+        pages = torch.nn.functional.pad(src, (0, 0, 0, n_pages * page_size - N)).view(Hkv, n_pages, page_size, D)
+        dst.view(Hkv, n_pages, page_size, D)[:, tc] = pages
+        del pages
+    del t["k"], t["v"]
+    p = replace(B.Params.from_workload(w), k_stride_head=n_pages * page_size * D, k_stride_tok=D,
+                v_stride_head=n_pages * page_size * D, v_stride_tok=D, page_table=table.cuda(), page_size=page_size)
+    ws = B.alloc_workspace(p)
+    acc = {s: 0.0 for s in B.PREFILL_STAGES}
+    for i in range(steps + 1):
+        _, _, ms = B.prefill_chunk_timed(p, t["q"], k_pool, v_pool, ws)
+        if i:
+            for s in acc:
+                acc[s] += ms[s] / steps
+    del ws
+    vote = B.Vote(4, 127, 32)
+    pv = replace(p, top_k=0)
+    wsv = B.alloc_vote_workspace(pv, vote)
+    vacc = {s: 0.0 for s in B.VOTE_STAGES}
+    for i in range(steps + 1):
+        *_, ms = B.vote_layer_timed(pv, vote, t["q"], k_pool, v_pool, wsv)
+        if i:
+            for s in vacc:
+                vacc[s] += ms[s] / steps
+    return {"workload": w.name, "page_size": page_size, "n_pages": n_pages,
+            "topk_4096_per_query": {"ms_per_chunk": round(sum(acc.values()), 3), "stages_ms": {s: round(x, 4) for s, x in acc.items()}},
+            "vote_4_127_32": {"ms_per_chunk": round(sum(vacc.values()), 3), "stages_ms": {s: round(x, 4) for s, x in vacc.items()}}}
 
 
 def unfused_leg(t: dict, cfg: int, steps: int) -> dict:
