@@ -71,3 +71,35 @@ def test_vote_layer_random_shape(seed):
     assert sel.cpu().numpy()[:n].tolist() == res["sel"].tolist()
     err = np.abs(out.cpu().numpy().astype(np.float64) - res["out"]).max()
     assert err <= P.OUT_TOL[w.dtype], err
+
+
+def _draw_large(seed: int):
+    """Longer middles (the chip-wide top-k past 65,536 scores), chunks of several query tiles and odd query
+    counts, more heads: what the draws above do not reach."""
+    r = np.random.default_rng(5000 + seed)
+    dtype = ["bf16", "f16", "bf16", "f32"][seed % 4]
+    D = 128 if dtype != "f32" else int(r.choice([64, 128]))
+    G = int(r.choice([1, 3, 4, 7, 8]))
+    Hkv = int(r.choice([1, 2, 4]))
+    n_sink = int(r.choice([0, 4, 32]))
+    n_local = int(r.choice([64, 300, 1024]))
+    n_mid = int(r.choice([3000, 30000, 66000, 70001, 140000]))
+    M = min(int(r.choice([1, 1, 2, 5, 64, 129, 300, 511])), n_local)
+    top_k = int(r.choice([1, 100, 1024, 4096]))
+    base = wl.CONFIGS[2] if dtype != "f32" else wl.CONFIGS[1]
+    w = base.scaled(dtype=dtype, head_dim=D, n_q_heads=G * Hkv, n_kv_heads=Hkv, n_ctx=n_sink + n_local + n_mid, n_query=M,
+                    n_sink=n_sink, n_local=n_local, top_k=top_k, max_position=0, n_needles=int(r.choice([0, 3])),
+                    cfg=int(r.integers(1, 90)), scale_q=bool(r.integers(0, 2)))
+    rows = None if M <= 8 else sorted(set([0, 1, M // 2, M - 2, M - 1] + [int(x) for x in r.integers(0, M, 3)]))
+    return w, rows
+
+
+@pytest.mark.parametrize("seed", range(48))
+def test_layer_random_large_shape(seed):
+    w, rows = _draw_large(seed)
+    p = B.Params.from_workload(w)
+    if B.validate(p) != B.OK:
+        pytest.skip("shape outside the library's domain")
+    t = wl.generate(w, "cuda")
+    out, idx = P.run_layer(w, t)
+    P.check_layer(w, t, out, idx, q_rows=rows)
