@@ -268,3 +268,23 @@ def test_paged_batch_folded_into_heads():
     for b in range(batch):                                       # the lists' tails past n_sel are not written
         assert torch.equal(s0[b * cap: b * cap + int(n0[b])], s1[b * cap: b * cap + int(n1[b])]), b
     assert torch.equal(o0, o1)
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_paged_random_shape_equals_contiguous(seed):
+    """The seeded random shapes of test_gpu_random_shapes (small and large draws alternating), decode steps and
+    chunks alike, over pages of a random size: indices and outputs equal the contiguous call's bit for bit."""
+    from tests import test_gpu_random_shapes as R
+    w = R._draw(seed)[0] if seed % 2 else R._draw_large(seed)[0]
+    p0 = B.Params.from_workload(w)
+    if B.validate(p0) != B.OK:
+        pytest.skip("shape outside the library's domain")
+    ps = [64, 128, 1024][seed % 3]
+    t = wl.generate(w, "cuda")
+    fn = B.decode_step if w.n_query == 1 else B.prefill_chunk
+    out0, idx0 = fn(p0, t["q"], t["k"], t["v"], B.alloc_workspace(p0), want_idx=True)
+    p, kp, vp, _ = _paged(w, t, ps, seed=100 + seed, spare=3)
+    out1, idx1 = fn(p, t["q"], kp, vp, B.alloc_workspace(p), want_idx=True)
+    torch.cuda.synchronize()
+    assert torch.equal(idx0, idx1)
+    assert torch.equal(out0, out1)
