@@ -193,3 +193,38 @@ def test_decode_token_layers_equal_separate_steps(n_ctx):
             torch.cuda.synchronize()
             assert torch.equal(kcs[l], k2[l]) and torch.equal(vcs[l], v2[l]), (rep, l)
             assert torch.equal(outs[l], want), (rep, l)
+
+
+@pytest.mark.parametrize("seed", range(30))
+def test_decode_token_random_shapes_equal_separate_steps(seed):
+    """Seeded random shapes (small and large draws alternating), three layers, both selections: every layer of
+    decode_token equals cache_append followed by the layer's own step on a fresh workspace, bit for bit."""
+    from tests import test_gpu_random_shapes as R
+    w, vote = R._draw(seed) if seed % 2 else (R._draw_large(seed)[0], B.Vote(4, 20, 8))
+    use_vote = seed % 4 >= 2
+    w = w.scaled(n_query=1, top_k=0 if use_vote else w.top_k, n_needles=0)
+    p = replace(B.Params.from_workload(w), n_query=1)
+    if B.validate(p) != B.OK or (use_vote and B.vote_workspace_bytes(p, vote) == 0):
+        pytest.skip("shape outside the library's domain")
+    n_layers = 3
+    dt = w.torch_dtype()
+    Hq, Hkv, D, N = w.n_q_heads, w.n_kv_heads, w.head_dim, w.n_ctx
+    g = torch.Generator(device="cuda").manual_seed(240715000 + 300 + seed)
+    kcs = [torch.randn(Hkv, N, D, generator=g, device="cuda").to(dt) for _ in range(n_layers)]
+    vcs = [torch.randn(Hkv, N, D, generator=g, device="cuda").to(dt) for _ in range(n_layers)]
+    qs = [torch.randn(1, Hq, D, generator=g, device="cuda").to(dt) for _ in range(n_layers)]
+    kn = [torch.randn(1, Hkv, D, generator=g, device="cuda").to(dt) for _ in range(n_layers)]
+    vn = [torch.randn(1, Hkv, D, generator=g, device="cuda").to(dt) for _ in range(n_layers)]
+    k2 = [x.clone() for x in kcs]; v2 = [x.clone() for x in vcs]
+    alloc = (lambda: B.alloc_vote_workspace(p, vote)) if use_vote else (lambda: B.alloc_workspace(p))
+    outs = B.decode_token(p, qs, kn, vn, kcs, vcs, alloc(), vote=vote if use_vote else None)
+    torch.cuda.synchronize()
+    for l in range(n_layers):
+        B.cache_append(p, N - 1, kn[l], vn[l], k2[l], v2[l])
+        if use_vote:
+            want = B.vote_layer(p, vote, qs[l], k2[l], v2[l], alloc())[0]
+        else:
+            want = B.decode_step(p, qs[l], k2[l], v2[l], alloc(), want_idx=False)[0]
+        torch.cuda.synchronize()
+        assert torch.equal(kcs[l], k2[l]) and torch.equal(vcs[l], v2[l]), l
+        assert torch.equal(outs[l], want), l
