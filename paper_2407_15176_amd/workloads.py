@@ -9,7 +9,9 @@ needle-in-a-haystack caches of 128K..4M tokens; no real model data is used):
   * q, K, V iid N(0,1); seed = 240715000 + 10*cfg + tensor_id with
     tensor_id 0=q, 1=K, 2=V, 3=channel scales, 4=needle positions.
   * configs 2,3,5: K and V of KV head h are multiplied per channel c by
-    sigma[h,c] = exp(U(ln 0.5, ln 4)) (outlier channels); q is left unscaled.
+    sigma[h,c] = exp(U(ln 0.5, ln 4)) (outlier channels; the exponential is evaluated with
+    correctly rounded elementwise operations only, so that CPU-generated inputs are the same
+    bytes on every machine); q is left unscaled.
     config 4: q is scaled too (a query head uses its KV head's sigma).
   * needles (8/32/32/0/64): distinct seeded positions in the middle of the cache,
     shared by all KV heads; K[h,pos,:] = 3*||sigma_h||_2 * qbar_h/||qbar_h||_2
@@ -19,7 +21,6 @@ Layouts: q [M,Hq,D], K and V [Hkv,N,D], contiguous.
 """
 from __future__ import annotations
 
-import math
 from dataclasses import dataclass, replace
 
 import torch
@@ -116,9 +117,24 @@ def channel_sigma(w: Workload) -> torch.Tensor:
     """sigma [Hkv, D] float32 on the CPU (ones when the config has no scales)."""
     if not w.channel_scales:
         return torch.ones(w.n_kv_heads, w.head_dim)
-    u = torch.rand(w.n_kv_heads, w.head_dim, generator=_gen("cpu", w.cfg, 3))
-    lo, hi = math.log(0.5), math.log(4.0)
-    return torch.exp(lo + (hi - lo) * u)
+    u = torch.rand(w.n_kv_heads, w.head_dim, generator=_gen("cpu", w.cfg, 3)).double()
+    return _exp_portable(_LN_HALF + (_LN_4 - _LN_HALF) * u).float()
+
+
+_LN_HALF, _LN_4, _LN_2 = -0.6931471805599453, 1.3862943611198906, 0.6931471805599453
+
+
+def _exp_portable(x: torch.Tensor) -> torch.Tensor:
+    """exp(x) for float64 x of moderate size from correctly rounded elementwise operations only
+    (round, multiply, add, power-of-two scaling): a library exp differs in the last bit between
+    machines, and inputs that stored expected values were computed from must be the same bytes
+    everywhere.  Accurate to a few ulp, which is all a random scale needs."""
+    n = torch.round(x / _LN_2)
+    r = x - n * _LN_2                       # |r| <= 0.35
+    acc = torch.ones_like(r)
+    for i in range(20, 0, -1):              # Horner form of the Taylor series, degree 20
+        acc = acc * r / float(i) + 1.0
+    return torch.ldexp(acc, n.to(torch.int32))
 
 
 def needle_positions(w: Workload) -> torch.Tensor:
