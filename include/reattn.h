@@ -52,7 +52,8 @@ typedef enum {
   REATTN_ERR_WINDOW = -5,    /* scope S exceeds max_position */
   REATTN_ERR_WORKSPACE = -6, /* ws is NULL or smaller than reattn_workspace_bytes() */
   REATTN_ERR_ALIGN = -7,     /* a pointer or stride breaks the 16-byte row alignment */
-  REATTN_ERR_HIP = -8        /* the HIP runtime refused a launch */
+  REATTN_ERR_HIP = -8,       /* the HIP runtime refused a launch */
+  REATTN_ERR_STATIC_LIMIT = -9 /* reattn_decode_step_static: the step needs more than REATTN_STATIC_SCRATCH_BYTES */
 } reattn_status;
 
 /* Storage of q, k_cache, v_cache, v_sel.  All arithmetic is fp32 on exactly widened inputs (the
@@ -144,6 +145,20 @@ int reattn_attend(const reattn_params* p, const void* q, const float* k_sel, con
 int reattn_decode_step(const reattn_params* p, const void* q, const void* k_cache,
                        const void* v_cache, int32_t* idx_out, float* out,
                        void* ws, size_t ws_bytes, void* stream);
+
+/* reattn_decode_step for callers that cannot allocate or hand over a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments minus the workspace,
+ * same kernels, same results; the step's scratch (scores, histograms, candidate lists, selection bitmap,
+ * rotary table, split-S partials) is a fixed array of REATTN_STATIC_SCRATCH_BYTES inside the library's
+ * device image, which every GPU the library runs on holds until the process ends.  The call allocates
+ * nothing and frees nothing.  Steps whose reattn_workspace_bytes() exceeds the array (a bf16 cache of
+ * 8 KV heads past ~500K tokens) return REATTN_ERR_STATIC_LIMIT before anything is launched.  All calls
+ * on one GPU share that GPU's array: calls that overlap on one GPU (two streams, two threads) race; order
+ * them on one stream.  Nothing is kept between calls. */
+#define REATTN_STATIC_SCRATCH_BYTES (32u << 20)
+size_t reattn_static_scratch_bytes(void);
+int reattn_decode_step_static(const reattn_params* p, const void* q, const void* k_cache,
+                              const void* v_cache, int32_t* idx_out, float* out, void* stream);
 
 /* One prefill chunk of one layer (appendix, prefilling phase, same lines) for
  * M >= 1 queries: per-query scores, per-query top-k, causal attention over

@@ -21,8 +21,8 @@ _DTYPE_CODE = {"f32": F32, "bf16": BF16, "f16": F16}
 AGG_SUM = 0
 
 OK = 0
-ERR_NULL, ERR_SHAPE, ERR_DTYPE, ERR_RANGE, ERR_WINDOW, ERR_WORKSPACE, ERR_ALIGN, ERR_HIP = (
-    -1, -2, -3, -4, -5, -6, -7, -8)
+ERR_NULL, ERR_SHAPE, ERR_DTYPE, ERR_RANGE, ERR_WINDOW, ERR_WORKSPACE, ERR_ALIGN, ERR_HIP, ERR_STATIC_LIMIT = (
+    -1, -2, -3, -4, -5, -6, -7, -8, -9)
 
 EXPORTS = [
     "reattn_version", "reattn_status_string", "reattn_validate", "reattn_scope",
@@ -32,6 +32,7 @@ EXPORTS = [
     "reattn_vote_workspace_bytes", "reattn_vote_topk", "reattn_vote_merge", "reattn_vote_layer",
     "reattn_vote_layer_timed", "reattn_cache_append", "reattn_prefill_sequence_chunks",
     "reattn_prefill_sequence_workspace_bytes", "reattn_prefill_sequence", "reattn_decode_token",
+    "reattn_static_scratch_bytes", "reattn_decode_step_static",
 ]
 PREFILL_STAGES = ("sample_threshold", "score_gemm_filter", "candidate_topk", "attend")
 STAGES = ("prep", "scan", "topk", "attend")
@@ -87,6 +88,8 @@ def lib() -> C.CDLL:
         L.reattn_attend.argtypes = [PP, P, P, P, P, P, C.c_size_t, P]
         L.reattn_decode_step.argtypes = [PP, P, P, P, P, P, P, C.c_size_t, P]
         L.reattn_prefill_chunk.argtypes = [PP, P, P, P, P, P, P, C.c_size_t, P]
+        L.reattn_decode_step_static.argtypes = [PP, P, P, P, P, P, P]
+        L.reattn_static_scratch_bytes.restype = C.c_size_t
         L.reattn_decode_step_timed.argtypes = [PP, P, P, P, P, P, P, C.c_size_t, P,
                                                C.POINTER(C.c_float)]
         L.reattn_prefill_chunk_timed.argtypes = L.reattn_decode_step_timed.argtypes
@@ -280,6 +283,20 @@ def _layer(fn_name: str, p: Params, q, k_cache, v_cache, ws, idx_out, out, want_
 
 def decode_step(p: Params, q, k_cache, v_cache, ws, idx_out=None, out=None, want_idx=True):
     return _layer("reattn_decode_step", p, q, k_cache, v_cache, ws, idx_out, out, want_idx)
+
+
+def static_scratch_bytes() -> int:
+    return lib().reattn_static_scratch_bytes()
+
+
+def decode_step_static(p: Params, q, k_cache, v_cache, idx_out, out):
+    """reattn_decode_step over the library's own scratch array: the caller passes every buffer, nothing is allocated."""
+    cp = p.c()
+    _check(lib().reattn_decode_step_static(
+        C.byref(cp), _dev(q, "q", p.torch_dtype()), _dev(k_cache, "k_cache", p.torch_dtype()),
+        _dev(v_cache, "v_cache", p.torch_dtype()), _dev(idx_out, "idx_out", torch.int32),
+        _dev(out, "out", torch.float32), _stream()), "reattn_decode_step_static")
+    return out, idx_out
 
 
 def prefill_chunk(p: Params, q, k_cache, v_cache, ws, idx_out=None, out=None, want_idx=True):

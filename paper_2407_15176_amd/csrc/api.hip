@@ -5,6 +5,7 @@
 
 #include <cmath>
 #include <cstring>
+#include <mutex>
 
 using namespace reattn;
 
@@ -286,6 +287,7 @@ const char* reattn_status_string(int s) {
     case REATTN_ERR_WORKSPACE: return "workspace missing or too small";
     case REATTN_ERR_ALIGN: return "pointer or stride not 16-byte aligned (workspace: 256)";
     case REATTN_ERR_HIP: return "HIP launch failed";
+    case REATTN_ERR_STATIC_LIMIT: return "problem needs more scratch than the no-allocation entry point holds";
     default: return "unknown status";
   }
 }
@@ -393,6 +395,55 @@ int reattn_decode_step(const reattn_params* p, const void* q, const void* k_cach
                        const void* v_cache, int32_t* idx_out, float* out, void* ws,
                        size_t ws_bytes, void* stream) {
   return run_layer(p, true, q, k_cache, v_cache, idx_out, out, ws, ws_bytes, stream);
+}
+
+// ---- the decode step for callers that cannot allocate ----------------------------------------
+// The step's scratch lives in the library's own device image instead of a caller's buffer.  The
+// array's name is only a host-side stand-in: its device address is asked for once per device
+// (every GPU holds its own copy at its own address) and that pointer is what the kernels get.
+}  // extern "C"
+
+static __device__ __align__(256) unsigned char scratch[REATTN_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_lock;
+void* g_scratch_ptr[kMaxDevices];
+
+// Device address of `scratch` on the current device; nullptr (and *err) when the runtime refuses.
+void* static_scratch(hipError_t* err) {
+  int dev = 0;
+  *err = hipGetDevice(&dev);
+  if (*err != hipSuccess) return nullptr;
+  if (dev < 0 || dev >= kMaxDevices) { *err = hipErrorInvalidDevice; return nullptr; }
+  std::lock_guard<std::mutex> hold(g_scratch_lock);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    *err = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (*err != hipSuccess || !ptr) { if (*err == hipSuccess) *err = hipErrorInvalidSymbol; return nullptr; }
+    g_scratch_ptr[dev] = ptr;
+  }
+  return g_scratch_ptr[dev];
+}
+}  // namespace
+
+extern "C" {
+
+size_t reattn_static_scratch_bytes(void) { return (size_t)REATTN_STATIC_SCRATCH_BYTES; }
+
+int reattn_decode_step_static(const reattn_params* p, const void* q, const void* k_cache,
+                              const void* v_cache, int32_t* idx_out, float* out, void* stream) {
+  Plan pl;
+  const int rc = make_plan(p, &pl);
+  if (rc) return rc;
+  if (pl.M != 1) return REATTN_ERR_RANGE;
+  if (pl.total > (size_t)REATTN_STATIC_SCRATCH_BYTES) return REATTN_ERR_STATIC_LIMIT;   // decided on the host, before any launch
+  hipError_t e;
+  void* ws = static_scratch(&e);
+  if (!ws) return REATTN_ERR_HIP;
+  // every kernel of the step starts from what the step itself wrote or cleared (the first launch zeroes
+  // the histograms), so what the previous call left in the array does not matter
+  return run_layer(p, true, q, k_cache, v_cache, idx_out, out, ws, (size_t)REATTN_STATIC_SCRATCH_BYTES, stream);
 }
 
 int reattn_prefill_chunk(const reattn_params* p, const void* q, const void* k_cache,

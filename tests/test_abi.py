@@ -36,11 +36,11 @@ def test_library_exports_every_declared_symbol():
 def test_version_and_status_strings():
     assert B.version() >= 100
     seen = set()
-    for s in range(0, -9, -1):
+    for s in range(0, -10, -1):
         msg = B.status_string(s)
         assert msg and msg != "unknown status"
         seen.add(msg)
-    assert len(seen) == 9
+    assert len(seen) == 10
     assert B.status_string(-99) == "unknown status"
 
 
@@ -206,3 +206,17 @@ def test_vote_parameters_are_checked_on_the_host():
     cp, cv = p.c(), B.Vote().c()
     assert L.reattn_vote_layer(C.byref(cp), C.byref(cv), None, None, None, None, None, None, None, 0, None) == B.ERR_NULL
     assert L.reattn_vote_merge(C.byref(cp), C.byref(cv), None, None, None, None, 0, None) == B.ERR_NULL
+
+
+def test_static_entry_point_rejects_steps_past_its_scratch_on_the_host():
+    """The no-allocation decode step refuses, before any HIP call, a step whose workspace exceeds its fixed array."""
+    lib = B.lib()
+    assert B.static_scratch_bytes() == 32 << 20
+    big = good(n_ctx=1 << 20, max_position=0)
+    assert B.workspace_bytes(big) > B.static_scratch_bytes()
+    cp = big.c()
+    one = C.c_void_p(256)       # never dereferenced: the size check comes first
+    assert lib.reattn_decode_step_static(C.byref(cp), one, one, one, None, one, None) == B.ERR_STATIC_LIMIT
+    cp = good(n_query=2).c()
+    assert lib.reattn_decode_step_static(C.byref(cp), one, one, one, None, one, None) == B.ERR_RANGE
+    assert "scratch" in B.status_string(B.ERR_STATIC_LIMIT)
