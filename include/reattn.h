@@ -289,6 +289,14 @@ int reattn_vote_layer_timed(const reattn_params* p, const reattn_vote* v, const 
                             int32_t* n_sel_out, float* out, void* ws, size_t ws_bytes, void* stream,
                             float* stage_ms);
 
+/* Diagnostic: where, inside the workspace of reattn_decode_step / reattn_prefill_chunk for these params,
+ * the last call left its redo list: a uint32 count of score rows whose sampled lower bound of the k-th
+ * score (Eq. 2) did not yield an exact selection by the fast route (bound above the k-th score, or more
+ * candidates than the fast route holds) and that were therefore selected exactly over all their scores.
+ * For a chunk (M > 1) the count is followed by that many uint32 row ids h * M + i.  *offset is in bytes.
+ * REATTN_ERR_SHAPE when the params take a route without such a list (short middles, other storage). */
+int reattn_redo_list_offset(const reattn_params* p, size_t* offset);
+
 /* Measurement aid: streams `bytes` of the device buffer `buf` (16-byte aligned)
  * `iters` times with the key scan's load shape and nothing else (no arithmetic, no
  * stores) and reports the rate in GB/s into the HOST float *gb_per_s: the practical

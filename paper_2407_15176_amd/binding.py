@@ -32,7 +32,7 @@ EXPORTS = [
     "reattn_vote_workspace_bytes", "reattn_vote_topk", "reattn_vote_merge", "reattn_vote_layer",
     "reattn_vote_layer_timed", "reattn_cache_append", "reattn_prefill_sequence_chunks",
     "reattn_prefill_sequence_workspace_bytes", "reattn_prefill_sequence", "reattn_decode_token",
-    "reattn_static_scratch_bytes", "reattn_decode_step_static",
+    "reattn_static_scratch_bytes", "reattn_decode_step_static", "reattn_redo_list_offset",
 ]
 PREFILL_STAGES = ("sample_threshold", "score_gemm_filter", "candidate_topk", "attend")
 STAGES = ("prep", "scan", "topk", "attend")
@@ -90,6 +90,7 @@ def lib() -> C.CDLL:
         L.reattn_prefill_chunk.argtypes = [PP, P, P, P, P, P, P, C.c_size_t, P]
         L.reattn_decode_step_static.argtypes = [PP, P, P, P, P, P, P]
         L.reattn_static_scratch_bytes.restype = C.c_size_t
+        L.reattn_redo_list_offset.argtypes = [PP, C.POINTER(C.c_size_t)]
         L.reattn_decode_step_timed.argtypes = [PP, P, P, P, P, P, P, C.c_size_t, P,
                                                C.POINTER(C.c_float)]
         L.reattn_prefill_chunk_timed.argtypes = L.reattn_decode_step_timed.argtypes
@@ -283,6 +284,20 @@ def _layer(fn_name: str, p: Params, q, k_cache, v_cache, ws, idx_out, out, want_
 
 def decode_step(p: Params, q, k_cache, v_cache, ws, idx_out=None, out=None, want_idx=True):
     return _layer("reattn_decode_step", p, q, k_cache, v_cache, ws, idx_out, out, want_idx)
+
+
+def redo_list(p: Params, ws: torch.Tensor):
+    """(count, row ids) the last decode step / prefill chunk over `ws` left in its redo list (synchronises).
+    Row ids are listed for chunks only.  Returns None when the params take a route without such a list."""
+    cp, off = p.c(), C.c_size_t(0)
+    rc = lib().reattn_redo_list_offset(C.byref(cp), C.byref(off))
+    if rc == ERR_SHAPE:
+        return None
+    _check(rc, "reattn_redo_list_offset")
+    words = ws[off.value:].view(torch.int32)
+    n = int(words[0].item())
+    rows = words[1:1 + n].cpu().tolist() if p.n_query > 1 else []
+    return n, rows
 
 
 def static_scratch_bytes() -> int:

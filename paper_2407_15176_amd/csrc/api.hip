@@ -15,6 +15,32 @@ constexpr size_t kAlign = 256;
 inline size_t up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 inline bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
 
+// Decides whether a decode step takes the filter path (no score array) and fixes its geometry: the sampling
+// step and rank, the scan's slices.  Everything follows from the params alone (the scan is cut for the 256
+// compute units of the part this library is built for), so the workspace layout never depends on a device.
+bool filter_plan(Plan* pl) {
+  pl->filter = false;
+  if (pl->M != 1 || pl->n_mid <= kRowMax || pl->k_eff <= 0) return false;
+  const int64_t target = pl->n_mid > ((int64_t)1 << 21) ? 16384 : 8192;   // longer rows: a tighter bound, or the pairs outgrow the pick
+  int64_t step = pl->n_mid / target;
+  if (step < 1) step = 1;
+  const int64_t ns = (pl->n_mid + step - 1) / step;
+  const double p = (double)pl->k_eff / (double)pl->n_mid;
+  const double mu = (double)ns * p;                     // sampled scores expected above the row's k-th score
+  const double r = mu + 6.0 * std::sqrt(mu * (1.0 - p) + 1.0) + 2.0;
+  if (r >= (double)ns) return false;                    // nearly everything is selected: nothing to filter
+  const double expect = r * (double)step;               // pairs at or above the bound, and six deviations on top
+  const double most = expect * (1.0 + 6.0 / std::sqrt(r)) + 64.0;
+  if (most > (double)kPickMax || ns > kFilterSampMax) return false;
+  const int rpb = scan_rows_per_block_for(pl->n_mid, pl->Hkv, 0, 256);
+  const int64_t nb = (pl->n_mid + rpb - 1) / rpb;
+  if (nb > kPickSlices) return false;
+  pl->filter = true;
+  pl->f_rpb = rpb; pl->f_nb = (int)nb; pl->f_step = step;
+  pl->f_nsamp = (uint32_t)ns; pl->f_rho = (uint32_t)r; pl->f_samp_stride = (ns + 3) / 4 * 4;
+  return true;
+}
+
 int make_plan(const reattn_params* p, Plan* out) {
   if (!p) return REATTN_ERR_NULL;
   Plan pl;
@@ -104,6 +130,13 @@ int make_plan(const reattn_params* p, Plan* out) {
   pl.off_cand = off;   off += up(rows * (size_t)pl.nchunks * kChunk * 4);
   pl.off_bitmap = off; off += up(rows * (size_t)pl.nwords * 4);
   pl.off_cnt = off;    off += up(rows * (size_t)pl.nchunks * 4);
+  if (filter_plan(&pl)) {                              // the same bytes, laid out for the filter path
+    size_t f = 0;
+    pl.off_fsamp = f;  f += up((size_t)pl.Hkv * (size_t)pl.f_samp_stride * 4);
+    pl.off_fcnt = f;   f += up((size_t)pl.Hkv * (size_t)pl.f_nb * 4 + 4);          // + the count of exact redos
+    pl.off_fcand = f;  f += up((size_t)pl.Hkv * (size_t)pl.f_nb * (size_t)pl.f_rpb * 8);
+    if (f > off) off = f;
+  }
   pl.off_idx = off;    off += up((size_t)pl.M * pl.Hkv * (size_t)pl.k_eff * 4);
   pl.off_rope = off;   off += up((size_t)(rope_rows_hi(pl.S) + kRopeLo) * (pl.D / 2) * sizeof(float2));
   pl.off_rope16 = off; off += up(attend_prefill_applies(pl) ? attend_prefill_table_bytes(pl) : 0);
@@ -133,6 +166,7 @@ int make_plan(const reattn_params* p, Plan* out) {
 struct Ws {
   float* scores; uint32_t* hist; uint32_t* pfx; uint32_t* ncand; int32_t* cand;
   uint32_t* bitmap; uint32_t* cnt; int32_t* idx; float2* rope; float* part; void* qsplit;
+  float* fsamp; uint32_t* fcnt; uint32_t* fredo; uint2* fcand;     // filter path (same bytes as scores .. cnt)
 };
 
 int bind_ws(const Plan& pl, void* ws, size_t ws_bytes, Ws* w) {
@@ -145,6 +179,9 @@ int bind_ws(const Plan& pl, void* ws, size_t ws_bytes, Ws* w) {
   w->cnt = (uint32_t*)(b + pl.off_cnt);      w->idx = (int32_t*)(b + pl.off_idx);
   w->rope = (float2*)(b + pl.off_rope);      w->part = (float*)(b + pl.off_part);
   w->qsplit = b + pl.off_qsplit;
+  w->fsamp = (float*)(b + pl.off_fsamp);     w->fcnt = (uint32_t*)(b + pl.off_fcnt);
+  w->fredo = w->fcnt + (size_t)pl.Hkv * (pl.filter ? pl.f_nb : 0);
+  w->fcand = (uint2*)(b + pl.off_fcand);
   return REATTN_OK;
 }
 
@@ -183,6 +220,20 @@ int select_tile(const Plan& pl, const Ws& w, const void* q, int q0, int nq, cons
   const int rows = nq * pl.Hkv;
   const size_t eb = (size_t)elem_bytes(pl.dtype);
   const char* qt = (const char*)q + (size_t)q0 * pl.Hq * pl.D * eb;
+  if (pl.filter) {                                     // a decode step over a long middle: sample -> filtering scan -> pick
+    const bool with_scan = append && append->first_tok >= pl.s_eff + pl.n_mid;
+    int rc = REATTN_OK;
+    if (append && !with_scan)                          // rows inside the middle must be in place before anything reads it
+      rc = hip_rc(launch_cache_append(pl, append->first_tok, append->n_tok, append->k_new, append->v_new,
+                                      append->k_cache, append->v_cache, st));
+    if (!rc) rc = hip_rc(launch_decode_sample(pl, qt, k_cache, w.fsamp, rope_too ? w.rope : nullptr, w.fredo, st));
+    mark(ev, 1, st);
+    if (!rc) rc = hip_rc(launch_score_scan_filter(pl, qt, k_cache, w.fsamp, w.fcand, w.fcnt, st, with_scan ? append : nullptr));
+    mark(ev, 2, st);
+    if (!rc) rc = hip_rc(launch_decode_pick(pl, qt, k_cache, w.fcand, w.fcnt, idx_all, w.fredo, st));
+    mark(ev, 3, st);
+    return rc;
+  }
   // new rows past the middle ride with the scan (which never reads them); otherwise with the clearing launch
   const bool with_scan = append && pl.k_eff > 0 && append->first_tok >= pl.s_eff + pl.n_mid;
   const int clear_rows = pl.k_eff > 0 && !hist_clean ? rows : 0;
@@ -874,6 +925,16 @@ int reattn_prefill_chunk_timed(const reattn_params* p, const void* q, const void
   if (rc) return rc;
   if (!pl.fused_prefill) return REATTN_ERR_SHAPE;   // stage boundaries are defined for the MFMA path
   return layer_timed(p, false, q, k_cache, v_cache, idx_out, out, ws, ws_bytes, stream, stage_ms);
+}
+
+int reattn_redo_list_offset(const reattn_params* p, size_t* offset) {
+  Plan pl;
+  const int rc = make_plan(p, &pl);
+  if (rc) return rc;
+  if (!offset) return REATTN_ERR_NULL;
+  if (pl.fused_prefill) { *offset = pl.off_redo; return REATTN_OK; }
+  if (pl.filter) { *offset = pl.off_fcnt + (size_t)pl.Hkv * pl.f_nb * 4; return REATTN_OK; }
+  return REATTN_ERR_SHAPE;
 }
 
 int reattn_probe_read_bandwidth(const void* buf, size_t bytes, int iters, void* stream,

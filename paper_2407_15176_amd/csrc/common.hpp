@@ -15,6 +15,10 @@ constexpr int kChunk = 8192;                  // middle positions per select/emi
 constexpr int kChunkWords = kChunk / 32;
 constexpr int kExactSlots = 64;               // workgroups (and score scratch rows) of the prefill redo path
 constexpr int kRopeLo = 128;                  // positions covered by the low rotary table
+constexpr int kRowMax = 65536;                // scores per row the one-workgroup top-k takes
+constexpr int kPickMax = 32768;               // candidate pairs the one-workgroup pick of the filter path holds in registers
+constexpr int kPickSlices = 1024;             // scan slices per row it can number through
+constexpr int kFilterSampMax = 18 * 1024;     // sampled scores per row the scan's bound search holds in registers
 __host__ __device__ inline int rope_rows_hi(int S) { return (S + kRopeLo - 1) / kRopeLo; }
 
 // storage dtype codes as in reattn_dtype
@@ -41,6 +45,12 @@ struct Plan {
          off_idx, off_rope, off_rope16, off_part, off_qsplit,
          off_samp, off_thr, off_pcand, off_pcount, off_redo, off_exact, total;
   bool fused_prefill;             // M > 1 on the MFMA path with sampled thresholds
+  // decode step over a long middle: no score array, the scan keeps only the pairs above a sampled bound
+  bool filter;
+  int f_rpb, f_nb;                // rows per scan slice, slices per score row (fixed by the plan, not by the device)
+  int64_t f_step, f_samp_stride;  // every f_step-th key of the middle is sampled; floats between two rows' samples
+  uint32_t f_nsamp, f_rho;        // samples per row; rank of the sampled score that serves as the bound
+  size_t off_fsamp, off_fcnt, off_fcand;   // laid over the score / candidate / bitmap blocks of the other selection
 };
 
 // ---- host-side launchers (one per .hip file) -------------------------------
@@ -60,6 +70,16 @@ hipError_t launch_cache_append(const Plan& pl, int64_t first_tok, int n_tok, con
 hipError_t launch_score_scan(const Plan& pl, const void* q, int n_query, const void* k_cache,
                              float* scores, uint32_t* hist, hipStream_t st, const AppendJob* append = nullptr);
 void prefill_sampling(const Plan& pl, int64_t* stride, int64_t* n_s, uint32_t* rho, uint32_t* cap);
+// Filter path of a decode step (plan.filter): sampled scores (+ the rotary table), the scan that keeps the pairs
+// at or above the sampled bound, the exact pick out of them (one workgroup per score row; a row whose bound
+// missed or whose pairs do not fit recomputes its scores and selects exactly, slowly).
+int scan_rows_per_block_for(int64_t n_mid, int64_t score_rows, int max_rows, int n_cu);
+hipError_t launch_decode_sample(const Plan& pl, const void* q, const void* k_cache, float* samp, float2* rope,
+                                uint32_t* redo_count, hipStream_t st);
+hipError_t launch_score_scan_filter(const Plan& pl, const void* q, const void* k_cache, const float* samp,
+                                    uint2* cand, uint32_t* segcnt, hipStream_t st, const AppendJob* append = nullptr);
+hipError_t launch_decode_pick(const Plan& pl, const void* q, const void* k_cache, const uint2* cand,
+                              const uint32_t* segcnt, int32_t* idx, uint32_t* redo_count, hipStream_t st);
 // Key splits of the fused filter (few query tiles would leave most of the chip idle) and the capacity of one
 // split's part of a row's candidate segment.
 void prefill_filter_splits(const Plan& pl, uint32_t cap, int* n_split, uint32_t* cap_split);
@@ -250,6 +270,18 @@ inline AppendArgs append_args(const Plan& pl, const AppendJob* j) {
     a.first_tok = j->first_tok; a.n_vec = (int64_t)j->n_tok * pl.Hkv * a.vec_per_row;
   }
   return a;
+}
+
+// Entry j of the two-level rotary table: rows [0, n_hi) hold the angles of positions 128 a, rows
+// [n_hi, n_hi + 128) those of positions b < 128; half = D / 2 entries per row.  Angles in fp64.
+__device__ __forceinline__ float2 rope_table_entry(int64_t j, int S, int half, int D, double log2_theta) {
+  const int n_hi = rope_rows_hi(S);
+  const int row = (int)(j / half), c = (int)(j % half);
+  const int r = row < n_hi ? row * kRopeLo : row - n_hi;
+  const double w = exp2(-2.0 * (double)c / (double)D * log2_theta);
+  double sn, cs;
+  sincos((double)r * w, &sn, &cs);
+  return make_float2((float)cs, (float)sn);
 }
 
 // Order-preserving image of an fp32 score: larger float <=> larger key.  -0 maps to +0's key.

@@ -19,94 +19,10 @@
 //                     the streaming kernel's arithmetic and selects exactly, whatever
 //                     the distribution (all-equal scores, adversarial data).
 #include "common.hpp"
+#include "select.hpp"
 
 namespace reattn {
 namespace {
-
-template <int NT>
-__device__ __forceinline__ uint32_t bscan_incl(uint32_t v, uint32_t* wsum, uint32_t& total) {
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  uint32_t x = v;
-#pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
-    const uint32_t y = __shfl_up(x, o, 64);
-    if (lane >= o) x += y;
-  }
-  if (lane == 63) wsum[wave] = x;
-  __syncthreads();
-  uint32_t base = 0, tot = 0;
-#pragma unroll
-  for (int w = 0; w < NT / 64; ++w) {
-    const uint32_t s = wsum[w];
-    base += (w < wave) ? s : 0u;
-    tot += s;
-  }
-  __syncthreads();
-  total = tot;
-  return x + base;
-}
-
-// LDS layouts that keep strided owners off each other's banks (64 banks of 4 bytes): a thread that owns 8
-// consecutive histogram bins, or 32 consecutive bitmap words, would otherwise meet 7 (31) other lanes in
-// every bank it touches.  One pad word per 8 bins / per 32 words makes the owners' strides odd.
-constexpr int kBins = 2048, kBinsPad = kBins + kBins / 8;
-__device__ __forceinline__ int bslot(int b) { return b + (b >> 3); }
-__device__ __forceinline__ int wslot(int w) { return w + (w >> 5); }
-
-// bins[bslot(0..2048)): largest-first search for the bin holding the k-th entry (1 <= k <= total).
-template <int NT>
-__device__ __forceinline__ void kth_bin(const uint32_t* bins, uint32_t k, uint32_t* sh,
-                                        uint32_t& bin, uint32_t& above) {
-  constexpr int BPT = 2048 / NT;
-  uint32_t loc[BPT], sum = 0;
-#pragma unroll
-  for (int i = 0; i < BPT; ++i) { loc[i] = bins[bslot(threadIdx.x * BPT + i)]; sum += loc[i]; }
-  uint32_t total;
-  const uint32_t incl = bscan_incl<NT>(sum, sh, total);
-  const uint32_t higher = total - incl;
-  if (higher < k && k <= higher + sum) {
-    uint32_t acc = higher;
-#pragma unroll
-    for (int i = BPT - 1; i >= 0; --i) {
-      if (acc < k && k <= acc + loc[i]) { sh[32] = threadIdx.x * BPT + i; sh[33] = acc; }
-      acc += loc[i];
-    }
-  }
-  __syncthreads();
-  bin = sh[32]; above = sh[33];
-  __syncthreads();
-}
-
-// k-th largest of n 64-bit values produced by get(i), all distinct or not: returns the
-// (shift, prefix) pair such that "value >> shift >= prefix" selects exactly the k largest when
-// values are distinct (and every value tied with the k-th otherwise).  `bits` = width of the values.
-template <int NT, typename Get>
-__device__ __forceinline__ void radix_kth(Get get, uint32_t n, uint32_t k, int bits, uint32_t* bins,
-                                          uint32_t* sh, int& shift_out, uint64_t& prefix_out) {
-  int shift = bits;
-  uint64_t prefix = 0;
-  uint32_t remaining = k;
-  while (shift > 0) {
-    const int w = shift < 11 ? shift : 11;
-    shift -= w;
-    for (int b = threadIdx.x; b < kBinsPad; b += NT) bins[b] = 0;
-    __syncthreads();
-    for (uint32_t i = threadIdx.x; i < n; i += NT) {
-      const uint64_t v = get(i);
-      if ((shift + w >= 64 ? 0ull : (v >> (shift + w))) == prefix)
-        atomicAdd(&bins[bslot((int)((uint32_t)(v >> shift) & ((1u << w) - 1u)))], 1u);
-    }
-    __syncthreads();
-    uint32_t d, ab;
-    kth_bin<NT>(bins, remaining, sh, d, ab);
-    const uint32_t in_bin = bins[bslot((int)d)];
-    remaining -= ab;
-    prefix = (prefix << w) | d;
-    __syncthreads();
-    if (in_bin == remaining) break;
-  }
-  shift_out = shift; prefix_out = prefix;
-}
 
 // ---- sample_threshold -------------------------------------------------------
 // samp[(i*Hkv + h) * row_stride + j], j < n_s: sampled scores; thr[h*M + i] = a lower bound of the rho-th
@@ -243,7 +159,7 @@ __global__ __launch_bounds__(256) void cand_topk_kernel(CandArgs a) {
   uint32_t mine = 0;
   for (int w = 0; w < wpt; ++w) mine += __popc(bitmap[threadIdx.x * wpt + w]);
   uint32_t total;
-  uint32_t at = bscan_incl<256>(mine, sh, total) - mine;
+  uint32_t at = block_scan_incl<256>(mine, sh, total) - mine;
   int32_t* out = a.idx + ((int64_t)i * a.Hkv + h) * a.k_eff;
   for (int w = 0; w < wpt; ++w) {
     uint32_t bits = bitmap[threadIdx.x * wpt + w];
@@ -425,7 +341,7 @@ __global__ __launch_bounds__(256, 3) void cand_topk_reg_kernel(CandArgs a) {
       word[w] = w < wpt ? bitmap[wslot(threadIdx.x * wpt + w)] : 0u;
       mine += __popc(word[w]);
     }
-    uint32_t at = bscan_incl<256>(mine, sh, total) - mine;   // its barriers also end every read of the bitmap
+    uint32_t at = block_scan_incl<256>(mine, sh, total) - mine;   // its barriers also end every read of the bitmap
     int32_t* ranked = (int32_t*)bitmap;                      // [k_eff]
 #pragma unroll
     for (int w = 0; w < kRankWords; ++w) {
@@ -447,7 +363,7 @@ __global__ __launch_bounds__(256, 3) void cand_topk_reg_kernel(CandArgs a) {
   } else {                                                   // a long middle: ranked from LDS, written directly
     uint32_t mine = 0;
     for (int w = 0; w < wpt; ++w) mine += __popc(bitmap[wslot(threadIdx.x * wpt + w)]);
-    uint32_t at = bscan_incl<256>(mine, sh, total) - mine;
+    uint32_t at = block_scan_incl<256>(mine, sh, total) - mine;
     for (int w = 0; w < wpt; ++w) {
       uint32_t bits = bitmap[wslot(threadIdx.x * wpt + w)];
       const int32_t first = a.index_base + (threadIdx.x * wpt + w) * 32;
@@ -527,7 +443,7 @@ __global__ __launch_bounds__(1024) void row_exact_kernel(ExactArgs a) {
         take = (shift >= 64 ? 0ull : (v >> shift)) >= prefix ? 1u : 0u;
       }
       uint32_t total;
-      const uint32_t at = done + bscan_incl<1024>(take, sh, total) - take;
+      const uint32_t at = done + block_scan_incl<1024>(take, sh, total) - take;
       if (take && at < (uint32_t)a.k_eff) out[at] = a.index_base + (int32_t)j;
       done += total;
     }

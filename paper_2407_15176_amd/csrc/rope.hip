@@ -25,15 +25,7 @@ __global__ __launch_bounds__(256) void prep_kernel(uint32_t* hist, int64_t n_his
   if (i < n_hist) { hist[i] = 0u; return; }
   if (i < n_hist + ap.n_vec) { append_piece(ap, i - n_hist); return; }
   const int64_t j = i - n_hist - ap.n_vec;
-  const int n_hi = rope_rows_hi(S);
-  if (rope && j < (int64_t)(n_hi + kRopeLo) * half) {
-    const int row = (int)(j / half), c = (int)(j % half);
-    const int r = row < n_hi ? row * kRopeLo : row - n_hi;
-    const double w = exp2(-2.0 * (double)c / (double)D * log2_theta);
-    double sn, cs;
-    sincos((double)r * w, &sn, &cs);
-    rope[j] = make_float2((float)cs, (float)sn);
-  }
+  if (rope && j < (int64_t)(rope_rows_hi(S) + kRopeLo) * half) rope[j] = rope_table_entry(j, S, half, D, log2_theta);
 }
 
 __global__ void fill_u32_kernel(uint32_t* p, int64_t n, uint32_t v) {

@@ -19,6 +19,7 @@
 // 4096-bin histogram of the ordered score keys) is accumulated in LDS on the way
 // and flushed with one atomic per non-empty bin.
 #include "common.hpp"
+#include "select.hpp"
 
 namespace reattn {
 namespace {
@@ -37,52 +38,40 @@ struct ScanArgs {
   const int32_t* pt;    // paged cache: the page of every 2^page_lg tokens of the sequence (PAGED kernels only)
   int page_lg;
   AppendArgs ap;        // rows of new tokens (past the middle) to copy into the caches on the way; n_vec 0: none
-};
-
-template <typename T> struct Store;
-template <> struct Store<float> {
-  static constexpr int kPerLoad = 4;
-  static __device__ __forceinline__ void widen(const u32x4& d, float* x) {
-    x[0] = __uint_as_float(d.x); x[1] = __uint_as_float(d.y);
-    x[2] = __uint_as_float(d.z); x[3] = __uint_as_float(d.w);
-  }
-  static __device__ __forceinline__ float one(const void* p, int64_t i) { return ((const float*)p)[i]; }
-};
-template <> struct Store<uint16_t> {   // bf16 bit patterns
-  static constexpr int kPerLoad = 8;
-  static __device__ __forceinline__ void widen(const u32x4& d, float* x) {
-    x[0] = bf16_lo(d.x); x[1] = bf16_hi(d.x); x[2] = bf16_lo(d.y); x[3] = bf16_hi(d.y);
-    x[4] = bf16_lo(d.z); x[5] = bf16_hi(d.z); x[6] = bf16_lo(d.w); x[7] = bf16_hi(d.w);
-  }
-  static __device__ __forceinline__ float one(const void* p, int64_t i) {
-    return __uint_as_float(((uint32_t)((const uint16_t*)p)[i]) << 16);
-  }
-};
-
-template <> struct Store<f16bits> {    // IEEE half bit patterns
-  static constexpr int kPerLoad = 8;
-  static __device__ __forceinline__ void widen(const u32x4& d, float* x) {
-    x[0] = f16_lo(d.x); x[1] = f16_hi(d.x); x[2] = f16_lo(d.y); x[3] = f16_hi(d.y);
-    x[4] = f16_lo(d.z); x[5] = f16_hi(d.z); x[6] = f16_lo(d.w); x[7] = f16_hi(d.w);
-  }
-  static __device__ __forceinline__ float one(const void* p, int64_t i) { return f16_one(((const uint16_t*)p)[i]); }
+  // filter mode: instead of the scores, every slice leaves the (score, middle position) pairs at or above a
+  // lower bound of the row's k-th score, in position order, in its own segment of rows_per_block entries
+  const float* samp;    // [rows][samp_stride] scores of a strided sample of the row's keys
+  int64_t samp_stride;
+  uint32_t n_samp, rho; // the bound is (at most a hair below) the rho-th largest of the n_samp sampled scores
+  uint2* cand;          // [rows][gridDim.x][rows_per_block]
+  uint32_t* segcnt;     // [rows][gridDim.x]
 };
 
 constexpr int kScanThreads = 1024;
 constexpr int kScanMaxRows = 32768;            // rows of scores one workgroup parks in LDS (128 KiB)
 
+// How a slice's scores leave the workgroup.
+constexpr int kOutScores = 0;                  // written as they are
+constexpr int kOutHist = 1;                    // written, and the first radix digit of the top-k counted on the way
+constexpr int kOutFilter = 2;                  // not written: only the pairs that can still be among the k largest
+constexpr int kSampRegs = kFilterSampMax / 1024;                  // sampled scores a thread holds while the bound is found
+
 // PAGED: the rows of a workgroup's slice are found through the page table; the few entries the slice
 // spans are copied into LDS first, so a row costs one LDS read and two integer instructions more.
-template <typename T, int D, int U, bool HIST, bool PAGED = false>
+template <typename T, int D, int U, int MODE, bool PAGED = false>
 __global__ __launch_bounds__(kScanThreads) void score_scan_kernel(ScanArgs a) {
+  constexpr bool HIST = MODE == kOutHist, FILTER = MODE == kOutFilter;
   constexpr int EPL = Store<T>::kPerLoad;      // elements per 16-byte load
   constexpr int LPR = D / EPL;                 // lanes per key row
   constexpr int RPL = 64 / LPR;                // rows per wave-wide load
   constexpr int RW = U * RPL;                  // rows per wave iteration
   static_assert(U <= LPR, "one result slot per lane");
 
-  extern __shared__ float stage[];             // [rows_per_block] scores, then the histogram
-  uint32_t* lhist = (uint32_t*)(stage + a.rows_per_block);
+  extern __shared__ float stage[];             // [rows_per_block] scores (filter mode: one pad word per 32), then the histogram
+  // filter mode: a thread later walks 32 consecutive scores; the pad word keeps those walks off each other's banks
+  auto sidx = [](int r) -> int { return FILTER ? r + (r >> 5) : r; };
+  uint32_t* lhist = (uint32_t*)(stage + (FILTER ? a.rows_per_block + (a.rows_per_block >> 5) + 1 : a.rows_per_block));
+  uint32_t* fsh = lhist + kBinsPad;            // filter mode: lhist holds the select's 2048 padded bins, then 40 words
   if (a.ap.n_vec) {                            // a decode token's own rows: a few 16-byte pieces, copied first
     const int64_t n_thr = (int64_t)gridDim.x * gridDim.y * kScanThreads;
     for (int64_t i = ((int64_t)blockIdx.y * gridDim.x + blockIdx.x) * kScanThreads + threadIdx.x; i < a.ap.n_vec; i += n_thr)
@@ -101,12 +90,20 @@ __global__ __launch_bounds__(kScanThreads) void score_scan_kernel(ScanArgs a) {
 
   // The group's query rows, summed in fp32: this lane's EPL channels.
   float qv[EPL];
+  group_query<T, D>(a.q, qi, h, a.Hq, a.G, sub, qv);
+
+  // filter mode: the lower bound of the row's k-th score, from the sampled scores (every workgroup of the
+  // row finds the same value; the sample is 36 KiB out of L2)
+  uint32_t thr_key = 0;
+  if (FILTER) {
+    uint32_t skey[kSampRegs];
+    const float* srow = a.samp + (int64_t)row_id * a.samp_stride;
 #pragma unroll
-  for (int e = 0; e < EPL; ++e) qv[e] = 0.f;
-  for (int g = 0; g < a.G; ++g) {
-    const int64_t qoff = ((int64_t)qi * a.Hq + (int64_t)h * a.G + g) * D + sub * EPL;
-#pragma unroll
-    for (int e = 0; e < EPL; ++e) qv[e] += Store<T>::one(a.q, qoff + e);
+    for (int r = 0; r < kSampRegs; ++r) {
+      const uint32_t i = (uint32_t)r * kScanThreads + threadIdx.x;
+      skey[r] = score_key(srow[i < a.n_samp ? i : a.n_samp - 1]);      // clamped, not predicated: the loads go out together
+    }
+    thr_key = kth_lower_bound_key<kScanThreads, kSampRegs>(skey, a.n_samp, a.rho, lhist, fsh);
   }
 
   const int64_t blk_row0 = (int64_t)blockIdx.x * a.rows_per_block;
@@ -116,7 +113,7 @@ __global__ __launch_bounds__(kScanThreads) void score_scan_kernel(ScanArgs a) {
   const char* kbase = (const char*)a.k +
       ((int64_t)h * a.ksh + (PAGED ? 0 : a.first_tok + blk_row0) * a.kst) * (int64_t)sizeof(T) + sub * 16;
   // paged: pages[i] = first row of page (pg0 + i) of the sequence, pg0 the page of the slice's first token
-  int32_t* pages = (int32_t*)(lhist + (HIST ? kHistBins : 0));
+  int32_t* pages = (int32_t*)(lhist + (HIST ? kHistBins : FILTER ? kBinsPad + 40 : 0));
   const int64_t tok0 = a.first_tok + blk_row0;
   if (PAGED) slice_pages_fill(pages, a.pt, a.page_lg, tok0, nrows, kScanThreads);
   static_assert(RW <= 64, "a wave's tile lies in at most two pages");
@@ -151,12 +148,35 @@ __global__ __launch_bounds__(kScanThreads) void score_scan_kernel(ScanArgs a) {
     }
     const int r = t + sub * RPL + grp;
     if (sub < U && r < nrows) {
-      stage[r] = mine;
+      stage[sidx(r)] = mine;
       if (HIST) atomicAdd(&lhist[score_key(mine) >> kKeyShift], 1u);
     }
   }
 
   __syncthreads();
+  if (FILTER) {
+    // ordered compaction out of LDS: thread t owns rows [32t, 32t + 32) of the slice
+    const int r0 = (int)threadIdx.x * 32;
+    uint32_t mask = 0;
+#pragma unroll
+    for (int i = 0; i < 32; ++i) {
+      const int r = r0 + i < nrows ? r0 + i : (nrows > 0 ? nrows - 1 : 0);      // clamped: the LDS read stays inside the slice
+      const bool in = r0 + i < nrows && score_key(stage[sidx(r)]) >= thr_key;
+      mask |= in ? 1u << i : 0u;
+    }
+    const uint32_t mine = (uint32_t)__popc(mask);
+    uint32_t total;
+    uint32_t at = block_scan_incl<kScanThreads>(mine, fsh, total) - mine;
+    const int64_t seg = (int64_t)row_id * gridDim.x + blockIdx.x;
+    uint2* out = a.cand + seg * a.rows_per_block;
+    while (mask) {
+      const int i = __ffs((int)mask) - 1;
+      mask &= mask - 1;
+      out[at++] = make_uint2(__float_as_uint(stage[sidx(r0 + i)]), (uint32_t)(blk_row0 + r0 + i));
+    }
+    if (threadIdx.x == 0) a.segcnt[seg] = total;
+    return;
+  }
   float* out = a.scores + (int64_t)row_id * a.n_mid + blk_row0;
   if (a.stream_out) {
     for (int r = threadIdx.x; r < nrows; r += kScanThreads) __builtin_nontemporal_store(stage[r], out + r);
@@ -196,12 +216,13 @@ __global__ __launch_bounds__(kScanThreads) void read_probe_kernel(const u32x4* _
   if (acc == 0x9e3779b9u && sink) sink[0] = acc;   // keeps the loads alive; practically never taken
 }
 
-template <typename T, int D, bool HIST, bool PAGED>
+template <typename T, int D, int MODE, bool PAGED>
 hipError_t launch_hp(const ScanArgs& a, dim3 grid, hipStream_t st) {
   constexpr int U = 8;
-  const size_t lds = (size_t)a.rows_per_block * 4 + (HIST ? kHistBins * 4 : 0) +
+  const size_t lds = (size_t)a.rows_per_block * 4 + (MODE == kOutHist ? kHistBins * 4 : 0) +
+                     (MODE == kOutFilter ? ((size_t)(a.rows_per_block >> 5) + 1 + kBinsPad + 40) * 4 : 0) +
                      (PAGED ? ((size_t)(a.rows_per_block >> a.page_lg) + 3) * 4 : 0);
-  auto kern = score_scan_kernel<T, D, U, HIST, PAGED>;
+  auto kern = score_scan_kernel<T, D, U, MODE, PAGED>;
   hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(kern, grid, dim3(kScanThreads), lds, st, a);
@@ -209,9 +230,13 @@ hipError_t launch_hp(const ScanArgs& a, dim3 grid, hipStream_t st) {
 }
 
 template <typename T, int D>
-hipError_t launch_t(const ScanArgs& a, dim3 grid, bool hist, hipStream_t st) {
-  if (a.pt) return hist ? launch_hp<T, D, true, true>(a, grid, st) : launch_hp<T, D, false, true>(a, grid, st);
-  return hist ? launch_hp<T, D, true, false>(a, grid, st) : launch_hp<T, D, false, false>(a, grid, st);
+hipError_t launch_t(const ScanArgs& a, dim3 grid, int mode, hipStream_t st) {
+  if (a.pt) return mode == kOutFilter ? launch_hp<T, D, kOutFilter, true>(a, grid, st)
+                 : mode == kOutHist   ? launch_hp<T, D, kOutHist, true>(a, grid, st)
+                                      : launch_hp<T, D, kOutScores, true>(a, grid, st);
+  return mode == kOutFilter ? launch_hp<T, D, kOutFilter, false>(a, grid, st)
+       : mode == kOutHist   ? launch_hp<T, D, kOutHist, false>(a, grid, st)
+                            : launch_hp<T, D, kOutScores, false>(a, grid, st);
 }
 
 }  // namespace
@@ -220,11 +245,15 @@ hipError_t launch_t(const ScanArgs& a, dim3 grid, bool hist, hipStream_t st) {
 // slices (each within one KV head) so that every CU streams the same amount and the
 // bursts of score writes fall together at the end of each round.
 int scan_rows_per_block(int64_t n_mid, int64_t score_rows, int max_rows) {
-  if (max_rows <= 0 || max_rows > kScanMaxRows) max_rows = kScanMaxRows;
   int n_cu = 0, dev = 0;                               // of the current device, asked every time: no state is kept
   if (hipGetDevice(&dev) != hipSuccess ||
       hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu <= 0)
     n_cu = 256;
+  return scan_rows_per_block_for(n_mid, score_rows, max_rows, n_cu);
+}
+
+int scan_rows_per_block_for(int64_t n_mid, int64_t score_rows, int max_rows, int n_cu) {
+  if (max_rows <= 0 || max_rows > kScanMaxRows) max_rows = kScanMaxRows;
   const int64_t total = n_mid * score_rows;
   const int64_t rounds = (total + (int64_t)n_cu * max_rows - 1) / ((int64_t)n_cu * max_rows);
   const int64_t wgs = rounds * n_cu;
@@ -251,13 +280,34 @@ hipError_t launch_score_scan(const Plan& pl, const void* q, int n_query, const v
   dim3 grid((unsigned)((pl.n_mid + a.rows_per_block - 1) / a.rows_per_block),
             (unsigned)(pl.Hkv * n_query));
   a.stream_out = (int64_t)grid.x * grid.y > 320 ? 1 : 0;   // more workgroups than one round over the chip
-  const bool h = hist != nullptr;
+  a.samp = nullptr; a.samp_stride = 0; a.n_samp = 0; a.rho = 0; a.cand = nullptr; a.segcnt = nullptr;
+  const int h = hist != nullptr ? kOutHist : kOutScores;
   if (pl.dtype == kF32) return pl.D == 64 ? launch_t<float, 64>(a, grid, h, st)
                                           : launch_t<float, 128>(a, grid, h, st);
   if (pl.dtype == kF16) return pl.D == 64 ? launch_t<f16bits, 64>(a, grid, h, st)
                                           : launch_t<f16bits, 128>(a, grid, h, st);
   return pl.D == 64 ? launch_t<uint16_t, 64>(a, grid, h, st)
                     : launch_t<uint16_t, 128>(a, grid, h, st);
+}
+
+hipError_t launch_score_scan_filter(const Plan& pl, const void* q, const void* k_cache, const float* samp,
+                                    uint2* cand, uint32_t* segcnt, hipStream_t st, const AppendJob* append) {
+  if (!pl.filter || pl.f_nsamp > (uint32_t)kSampRegs * kScanThreads) return hipErrorInvalidValue;
+  ScanArgs a;
+  a.ap = append_args(pl, append);
+  a.k = k_cache; a.q = q; a.scores = nullptr; a.hist = nullptr;
+  a.ksh = pl.ksh; a.kst = pl.kst; a.n_mid = pl.n_mid; a.first_tok = pl.s_eff;
+  a.Hq = pl.Hq; a.Hkv = pl.Hkv; a.G = pl.G; a.pt = pl.pt; a.page_lg = pl.page_lg;
+  a.rows_per_block = pl.f_rpb; a.stream_out = 0;
+  a.samp = samp; a.samp_stride = pl.f_samp_stride; a.n_samp = pl.f_nsamp; a.rho = pl.f_rho;
+  a.cand = cand; a.segcnt = segcnt;
+  const dim3 grid((unsigned)pl.f_nb, (unsigned)pl.Hkv);
+  if (pl.dtype == kF32) return pl.D == 64 ? launch_t<float, 64>(a, grid, kOutFilter, st)
+                                          : launch_t<float, 128>(a, grid, kOutFilter, st);
+  if (pl.dtype == kF16) return pl.D == 64 ? launch_t<f16bits, 64>(a, grid, kOutFilter, st)
+                                          : launch_t<f16bits, 128>(a, grid, kOutFilter, st);
+  return pl.D == 64 ? launch_t<uint16_t, 64>(a, grid, kOutFilter, st)
+                    : launch_t<uint16_t, 128>(a, grid, kOutFilter, st);
 }
 
 hipError_t launch_read_probe(const void* buf, size_t bytes, hipStream_t st) {

@@ -252,7 +252,6 @@ __global__ __launch_bounds__(256) void topk_emit_kernel(
 // bitmap into the ascending index list, which leaves in 16-byte rows.  Rows whose pivot bin
 // holds more than kRowCand entries (degenerate score distributions) keep what fits in LDS and
 // re-read the rest from the scores on every pass: slower, same result.
-constexpr int kRowMax = 65536;                    // scores per row the fused kernel takes
 constexpr int kRowCand = 8192;                    // pivot-bin entries cached in LDS (64 KiB)
 constexpr int kRowThreads = 1024;
 constexpr size_t kRowLds = (size_t)kRowMax / 8 + (size_t)kRowCand * 8 + 2048 * 4;

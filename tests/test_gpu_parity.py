@@ -399,3 +399,93 @@ def test_batched_decode_is_head_folding(dtype):
         ob = out[:, b * base.n_q_heads:(b + 1) * base.n_q_heads].contiguous()
         ib = idx[:, b * base.n_kv_heads:(b + 1) * base.n_kv_heads].contiguous()
         P.check_layer(base, t, ob, ib)
+
+
+# ------------------------------------------- decode steps over long middles: the filter route
+# (sampled lower bound of the k-th score -> the scan keeps only the pairs above it -> exact pick)
+FILTER_CASES = {
+    "f32_d64_g4": wl.CONFIGS[1].scaled(n_ctx=70_001, n_local=300, top_k=512, max_position=0),
+    "bf16_d128_g4": wl.CONFIGS[2].scaled(n_ctx=300_017, n_local=1000, top_k=2048),
+    "bf16_d128_g3_k1": wl.CONFIGS[5].scaled(n_ctx=150_000, n_local=257, top_k=1, max_position=0),
+    "f16_d64_g2": wl.CONFIGS[2].scaled(dtype="f16", n_ctx=90_000, head_dim=64, n_q_heads=4, n_kv_heads=2,
+                                       n_local=128, top_k=4000),
+    "f32_d128_g8_one_head": wl.CONFIGS[1].scaled(n_ctx=66_000, head_dim=128, n_q_heads=8, n_kv_heads=1,
+                                                 n_local=64, top_k=3000, max_position=0),
+    "bf16_d128_k_large": wl.CONFIGS[2].scaled(n_ctx=200_000, n_local=512, top_k=16_000, max_position=0),
+}
+
+
+def _filter_step(w, t):
+    p = B.Params.from_workload(w)
+    ws = B.alloc_workspace(p)
+    out, idx = B.decode_step(p, t["q"], t["k"], t["v"], ws)
+    torch.cuda.synchronize()
+    redo = B.redo_list(p, ws)
+    assert redo is not None, "these params were meant to take the filter route"
+    return out, idx, redo[0]
+
+
+@pytest.mark.parametrize("name", list(FILTER_CASES))
+def test_decode_filter_route_matches_oracle(name):
+    w = FILTER_CASES[name]
+    t = gen(w)
+    out, idx, n_redo = _filter_step(w, t)
+    assert n_redo == 0
+    P.check_layer(w, t, out, idx)
+
+
+def test_decode_filter_route_all_scores_equal_takes_the_exact_redo():
+    """A zero query: every score ties, every key passes the bound, the pairs outgrow the pick's registers:
+    every row is redone exactly and the lowest indices win."""
+    w = wl.CONFIGS[1].scaled(n_ctx=80_000, n_local=128, top_k=300, n_needles=0, max_position=0)
+    t = gen(w)
+    t["q"].zero_()
+    out, idx, n_redo = _filter_step(w, t)
+    assert n_redo == w.n_kv_heads
+    want = torch.arange(w.n_sink, w.n_sink + 300, dtype=torch.int32, device="cuda")
+    assert torch.equal(idx[0], want.expand(w.n_kv_heads, 300))
+    P.check_layer(w, t, out, idx)
+
+
+def test_decode_filter_route_bound_above_the_kth_score_takes_the_exact_redo():
+    """Keys that score high exactly where the sample looks (every n_mid // 8192-th key of the middle) and low
+    everywhere else: the sampled bound lies above the true k-th score, fewer than k pairs pass, and the rows
+    are redone exactly."""
+    w = wl.CONFIGS[2].scaled(n_ctx=100_000, n_local=300, top_k=3000, n_needles=0, max_position=0)
+    t = gen(w)
+    step = w.n_mid // 8192
+    qbar = t["q"][0].float().reshape(w.n_kv_heads, w.group, w.head_dim).sum(dim=1)           # [Hkv, D]
+    pos = torch.arange(w.n_sink, w.n_sink + w.n_mid, step, device="cuda")[:1500]             # fewer than k of them
+    t["k"][:, pos, :] = (qbar / qbar.norm(dim=1, keepdim=True) * 60.0).to(t["k"].dtype).unsqueeze(1)
+    out, idx, n_redo = _filter_step(w, t)
+    assert n_redo == w.n_kv_heads
+    P.check_layer(w, t, out, idx)
+
+
+def test_decode_filter_route_exact_ties_at_the_kth_score():
+    """Runs of identical keys: the k-th score is shared by many entries on both sides of the cut, so the pick
+    must break the tie by position (lower index first), bit for bit as the oracle does."""
+    w = wl.CONFIGS[2].scaled(n_ctx=120_000, n_local=300, top_k=2500, n_needles=0, max_position=0)
+    t = gen(w)
+    period = 977
+    src = t["k"][:, w.n_sink:w.n_sink + period].clone()
+    reps = -(-w.n_mid // period)
+    t["k"][:, w.n_sink:w.n_sink + w.n_mid] = src.repeat(1, reps, 1)[:, :w.n_mid]
+    out, idx, n_redo = _filter_step(w, t)
+    assert n_redo == 0
+    p = B.Params.from_workload(w)
+    q, k, v = P.host_inputs(t)
+    want = ro.forward(P.oracle_shape(w), q, k, v)["idx"]
+    # every copy of a key scores the same in fp32 and in fp64, so ties are exact on both sides; what can
+    # differ is the order of two DISTINCT keys whose scores agree to fp32 rounding: compare through the rule
+    r = P.check_layer(w, t, out, idx)
+    if r["rows_differ"] == 0:
+        assert np.array_equal(idx.cpu().numpy(), want)
+
+
+def test_decode_filter_route_is_deterministic_and_static_entry_agrees():
+    w = FILTER_CASES["bf16_d128_g4"]
+    t = gen(w)
+    out1, idx1, _ = _filter_step(w, t)
+    out2, idx2, _ = _filter_step(w, t)
+    assert torch.equal(idx1, idx2) and torch.equal(out1, out2)
