@@ -92,7 +92,17 @@ typedef struct reattn_params {
    * positions of the sequence. */
   const int32_t* page_table;
   int32_t page_size;
+  /* Which way a decode step (M == 1) over a middle of more than 65,536 tokens finds its top-k (Eq. 2); the
+   * results are the same either way.  REATTN_ROUTE_SCORES: the scan writes one fp32 score per key, a radix
+   * select runs over them.  REATTN_ROUTE_FILTER: no score is written; a strided sample of the scores gives a
+   * lower bound of the k-th score, the scan keeps only the (score, position) pairs at or above it and one
+   * workgroup per KV head picks the k best of them exactly (rows whose bound missed are redone exactly).
+   * REATTN_ROUTE_AUTO (0) takes the filter from 2^22 scored keys per step (n_mid * Hkv) upwards.  A tuning
+   * and testing aid: shapes the filter does not take (short middles, top_k so large that the kept pairs
+   * would outgrow the pick) use the scores whatever is asked for. */
+  int32_t route;
 } reattn_params;
+typedef enum { REATTN_ROUTE_AUTO = 0, REATTN_ROUTE_FILTER = 1, REATTN_ROUTE_SCORES = 2 } reattn_route;
 
 /* Library version (major*10000 + minor*100 + patch) and a static message for a status. */
 int reattn_version(void);

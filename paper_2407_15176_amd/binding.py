@@ -19,6 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libreattn.so")
 F32, BF16, F16 = 0, 1, 2
 _DTYPE_CODE = {"f32": F32, "bf16": BF16, "f16": F16}
 AGG_SUM = 0
+ROUTE_AUTO, ROUTE_FILTER, ROUTE_SCORES = 0, 1, 2
 
 OK = 0
 ERR_NULL, ERR_SHAPE, ERR_DTYPE, ERR_RANGE, ERR_WINDOW, ERR_WORKSPACE, ERR_ALIGN, ERR_HIP, ERR_STATIC_LIMIT = (
@@ -48,7 +49,7 @@ class CParams(C.Structure):
         ("softmax_scale", C.c_float),
         ("k_stride_head", C.c_int64), ("k_stride_tok", C.c_int64),
         ("v_stride_head", C.c_int64), ("v_stride_tok", C.c_int64),
-        ("page_table", C.c_void_p), ("page_size", C.c_int32),
+        ("page_table", C.c_void_p), ("page_size", C.c_int32), ("route", C.c_int32),
     ]
 
 
@@ -135,6 +136,7 @@ class Params:
     v_stride_tok: int = 0
     page_table: "torch.Tensor | None" = None     # int32 device tensor [ceil(n_ctx / page_size)], or None
     page_size: int = 0
+    route: int = 0                               # ROUTE_AUTO / ROUTE_FILTER / ROUTE_SCORES (long decode steps)
 
     def c(self) -> CParams:
         pt = None
@@ -149,7 +151,7 @@ class Params:
                        self.n_query, self.n_sink, self.n_local, self.top_k, self.rope_theta,
                        self.max_position, self.agg, self.softmax_scale,
                        self.k_stride_head, self.k_stride_tok, self.v_stride_head, self.v_stride_tok,
-                       pt, self.page_size)
+                       pt, self.page_size, self.route)
 
     @classmethod
     def from_workload(cls, w) -> "Params":

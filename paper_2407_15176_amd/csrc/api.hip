@@ -18,9 +18,14 @@ inline bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
 // Decides whether a decode step takes the filter path (no score array) and fixes its geometry: the sampling
 // step and rank, the scan's slices.  Everything follows from the params alone (the scan is cut for the 256
 // compute units of the part this library is built for), so the workspace layout never depends on a device.
-bool filter_plan(Plan* pl) {
+bool filter_plan(Plan* pl, int route) {
   pl->filter = false;
-  if (pl->M != 1 || pl->n_mid <= kRowMax || pl->k_eff <= 0) return false;
+  if (pl->M != 1 || pl->n_mid <= kRowMax || pl->k_eff <= 0 || route == REATTN_ROUTE_SCORES) return false;
+  // Measured on MI355X: the route costs a sampling launch, ~5 us at the head of every scan workgroup and a
+  // one-workgroup pick (~37 us in all) against ~40 us for histogram + select + refine + emit over the written
+  // scores; it wins once the scores no longer fit one round of workgroups (their bursts then fall into the
+  // next round's reads) and is level at a million tokens of 8 KV heads; below that the written scores win.
+  if (route != REATTN_ROUTE_FILTER && pl->n_mid * (int64_t)pl->Hkv < ((int64_t)1 << 22)) return false;
   const int64_t target = pl->n_mid > ((int64_t)1 << 21) ? 16384 : 8192;   // longer rows: a tighter bound, or the pairs outgrow the pick
   int64_t step = pl->n_mid / target;
   if (step < 1) step = 1;
@@ -56,6 +61,7 @@ int make_plan(const reattn_params* p, Plan* out) {
   if (!(p->rope_theta > 1.0f) || !std::isfinite(p->rope_theta)) return REATTN_ERR_RANGE;
   if (!(p->softmax_scale >= 0.0f) || !std::isfinite(p->softmax_scale)) return REATTN_ERR_RANGE;
   if (p->max_position < 0) return REATTN_ERR_RANGE;
+  if (p->route != REATTN_ROUTE_AUTO && p->route != REATTN_ROUTE_FILTER && p->route != REATTN_ROUTE_SCORES) return REATTN_ERR_RANGE;
 
   pl.Hq = p->n_q_heads; pl.Hkv = p->n_kv_heads; pl.D = p->head_dim; pl.G = pl.Hq / pl.Hkv;
   pl.dtype = p->dtype; pl.M = p->n_query; pl.N = p->n_ctx;
@@ -130,10 +136,10 @@ int make_plan(const reattn_params* p, Plan* out) {
   pl.off_cand = off;   off += up(rows * (size_t)pl.nchunks * kChunk * 4);
   pl.off_bitmap = off; off += up(rows * (size_t)pl.nwords * 4);
   pl.off_cnt = off;    off += up(rows * (size_t)pl.nchunks * 4);
-  if (filter_plan(&pl)) {                              // the same bytes, laid out for the filter path
+  if (filter_plan(&pl, p->route)) {                              // the same bytes, laid out for the filter path
     size_t f = 0;
     pl.off_fsamp = f;  f += up((size_t)pl.Hkv * (size_t)pl.f_samp_stride * 4);
-    pl.off_fcnt = f;   f += up((size_t)pl.Hkv * (size_t)pl.f_nb * 4 + 4);          // + the count of exact redos
+    pl.off_fcnt = f;   f += up((size_t)pl.Hkv * (size_t)pl.f_nb * 4 + 4 + (size_t)pl.Hkv * 4);   // + the redo list
     pl.off_fcand = f;  f += up((size_t)pl.Hkv * (size_t)pl.f_nb * (size_t)pl.f_rpb * 8);
     if (f > off) off = f;
   }

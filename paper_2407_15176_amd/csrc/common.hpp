@@ -279,8 +279,11 @@ __device__ __forceinline__ float2 rope_table_entry(int64_t j, int S, int half, i
   const int row = (int)(j / half), c = (int)(j % half);
   const int r = row < n_hi ? row * kRopeLo : row - n_hi;
   const double w = exp2(-2.0 * (double)c / (double)D * log2_theta);
+  // whole turns taken off in fp64 first (exact to ~1e-11 rad at position 131,071): the library routine then
+  // stays on its small-argument path
+  const double turns = (double)r * w * 0.15915494309189535;
   double sn, cs;
-  sincos((double)r * w, &sn, &cs);
+  sincos((turns - rint(turns)) * 6.283185307179586, &sn, &cs);
   return make_float2((float)cs, (float)sn);
 }
 

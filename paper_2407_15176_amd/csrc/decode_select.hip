@@ -9,13 +9,15 @@
 //   scan     (score_scan.hip, filter mode) streams the keys once; every workgroup parks its slice's scores in
 //            LDS, finds the bound from the row's samples, and leaves only the (score, position) pairs at or
 //            above it, in position order, in its own segment: ~1.5 k pairs per row instead of n_mid scores.
-//   pick     one workgroup per row numbers the segments' pairs through (position order), holds them in
-//            registers, finds the exact k-th largest (score descending, index ascending) by radix select on the
+//   pick     one workgroup per row numbers the segments' pairs through (position order), holds their keys in
+//            LDS, finds the exact k-th largest (score descending, index ascending) by radix select on the
 //            offsets from the smallest candidate key, and writes the winners' absolute indices in ascending
 //            order (ranks from wave ballots).  A row whose bound missed (fewer than k pairs: probability
-//            ~1e-9 per row on exchangeable keys) or whose pairs exceed the registers (degenerate rows: runs of
-//            equal scores) recomputes its scores with the scan's arithmetic and selects exactly over all of
-//            them: slow (one workgroup streams the row), same result.
+//            ~1e-9 per row on exchangeable keys) or whose pairs exceed the LDS (degenerate rows: runs of
+//            equal scores) is left to
+//   redo     a launch of its own right behind the pick (as a rule it finds its list empty and returns): one
+//            workgroup per listed row recomputes the row's scores with the scan's arithmetic and selects
+//            exactly over all of them: slow (one workgroup streams the row), same result.
 #include "common.hpp"
 #include "select.hpp"
 
@@ -48,12 +50,10 @@ __global__ __launch_bounds__(256) void sample_score_kernel(SampleArgs a) {
   const int sub = lane % LPR, grp = lane / LPR;
   const int row_id = blockIdx.y;                             // query * Hkv + kv head
   const int h = row_id % a.Hkv, qi = row_id / a.Hkv;
-  float qv[EPL];
-  group_query<T, D>(a.q, qi, h, a.Hq, a.G, sub, qv);
   const char* kbase = (const char*)a.k + (int64_t)h * a.ksh * (int64_t)sizeof(T) + sub * 16;
   const int64_t row_bytes = a.kst * (int64_t)sizeof(T);
   const uint32_t j0 = (uint32_t)blockIdx.x * SPB + (uint32_t)wave * (U * RPL);
-  u32x4 d[U];
+  u32x4 d[U];                                                // the key rows first: the query's loads ride along
 #pragma unroll
   for (int u = 0; u < U; ++u) {
     const uint32_t j = j0 + u * RPL + grp;
@@ -61,6 +61,8 @@ __global__ __launch_bounds__(256) void sample_score_kernel(SampleArgs a) {
     const int64_t row = a.pt ? paged_row(a.pt, a.page_lg, tok) : tok;
     d[u] = *(const u32x4*)(kbase + row * row_bytes);
   }
+  float qv[EPL];
+  group_query<T, D>(a.q, qi, h, a.Hq, a.G, sub, qv);
   float* out = a.samp + (int64_t)row_id * a.samp_stride;
 #pragma unroll
   for (int u = 0; u < U; ++u) {
@@ -71,15 +73,13 @@ __global__ __launch_bounds__(256) void sample_score_kernel(SampleArgs a) {
 }
 
 constexpr int kPickThreads = 1024;
-constexpr int kPickRegs = kPickMax / kPickThreads;           // candidate pairs per thread
-static_assert(kPickRegs == 32, "ballot bookkeeping below assumes 32 rows of 1024 pairs");
 
 struct PickArgs {
   const uint2* cand; const uint32_t* segcnt;                 // [rows][nb][rpb], [rows][nb]
   int nb, rpb, k_eff;
   int64_t n_mid; int32_t index_base;
   int32_t* idx;                                              // [rows][k_eff]
-  uint32_t* redo_count;                                      // rows that took the exact redo (nullable)
+  uint32_t* redo;                                            // [0] rows left to the exact redo, [1..] which
   // the exact redo recomputes the row's scores: over the row's own segments, which it no longer needs
   const void* q; const void* k;
   int64_t ksh, kst, first_tok;
@@ -131,10 +131,12 @@ __device__ __forceinline__ void exact_row(const PickArgs& a, int row_id, float* 
 
 template <typename T, int D>
 __global__ __launch_bounds__(kPickThreads) void decode_pick_kernel(PickArgs a) {
-  extern __shared__ uint32_t pfx[];                          // [nb + 1] pairs in front of every segment
+  extern __shared__ uint32_t pick_lds[];
+  uint32_t* pfx = pick_lds;                                  // [nb + 1] pairs in front of every segment
+  uint32_t* keys = pick_lds + ((a.nb + 1 + 3) & ~3);         // [n] ordered score keys of the row's pairs, in position order
   __shared__ uint32_t bins[kBinsPad];
   __shared__ uint32_t sh[40];
-  __shared__ uint32_t wcount[kPickRegs * (kPickThreads / 64)];   // winners per (row of 1024 pairs, wave), then their prefix
+  __shared__ uint16_t gseg[kPickMax / 64];                   // segment of the group's first pair
   const int row_id = blockIdx.x;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int64_t seg0 = (int64_t)row_id * a.nb;
@@ -147,46 +149,64 @@ __global__ __launch_bounds__(kPickThreads) void decode_pick_kernel(PickArgs a) {
     __syncthreads();
   }
   const uint32_t k = (uint32_t)a.k_eff;
-  if (n < k || n > (uint32_t)kPickMax) {                     // workgroup-uniform
-    if (threadIdx.x == 0 && a.redo_count) atomicAdd(a.redo_count, 1u);
+  if (__builtin_expect(n < k || n > (uint32_t)kPickMax, 0)) {   // workgroup-uniform: bound missed, or too many pairs
+    if (threadIdx.x == 0) atomicAdd(a.redo, 1u);
     exact_row<T, D>(a, row_id, (float*)(a.cand + seg0 * a.rpb), bins, sh);
     return;
   }
-  // pair i of the row (position order) -> slot i / 1024 of thread i % 1024
-  uint32_t key[kPickRegs], pos[kPickRegs];
-  uint32_t valid = 0;
-#pragma unroll
-  for (int r = 0; r < kPickRegs; ++r) {
-    key[r] = 0u; pos[r] = 0u;
-    if ((uint32_t)r * kPickThreads < n) {                    // workgroup-uniform
-      const uint32_t i = (uint32_t)r * kPickThreads + threadIdx.x;
-      const uint32_t ic = i < n ? i : n - 1;                 // clamped, not predicated: the loads go out together
-      int lo = 0, hi = a.nb;                                 // largest segment with pfx[segment] <= ic
-#pragma unroll
-      for (int it = 0; it < 10; ++it) {
-        const int mid = (lo + hi) >> 1;
-        const bool go = lo + 1 < hi;
-        const bool up = pfx[mid] <= ic;
-        lo = go && up ? mid : lo;
-        hi = go && !up ? mid : hi;
-      }
-      const uint2 c = a.cand[(seg0 + lo) * a.rpb + (ic - pfx[lo])];
-      key[r] = score_key(__uint_as_float(c.x)); pos[r] = c.y;
-      if (i < n) valid |= 1u << r;
-    }
+  // The pairs are numbered through in position order and cut into one run per wave (a multiple of 64 pairs):
+  // pair w * run + 64 u + lane is slot u of that lane of wave w; its key goes into LDS, its position stays in
+  // a register.  The segment of a pair is found from a table that names, for every group of 64 consecutive
+  // pairs, the segment of the group's first pair (filled by the thread that owns that segment), plus a short
+  // walk forward.  Sixteen pairs per thread at a time, their loads issued together (indices clamped, not
+  // predicated), so a batch costs one trip to memory.
+  if ((int)threadIdx.x < a.nb) {
+    const uint32_t first = pfx[threadIdx.x], end = pfx[threadIdx.x + 1];
+    for (uint32_t g = (first + 63) >> 6; (g << 6) < end; ++g) gseg[g] = (uint16_t)threadIdx.x;
   }
-  auto live = [&](int r) -> bool { return (valid >> r) & 1u; };
+  __syncthreads();
+  constexpr int kWaves = kPickThreads / 64;
+  constexpr int kSlots = kPickMax / kPickThreads, kBatch = 16;
+  static_assert(kSlots % kBatch == 0, "whole batches");
+  const uint32_t run = ((n + kWaves - 1) / kWaves + 63) / 64 * 64;     // <= 64 * kSlots
+  const uint32_t mine0 = (uint32_t)wave * run + lane;
+  uint32_t pos[kSlots];
   uint32_t kmin = 0xffffffffu, kmax = 0u;
 #pragma unroll
-  for (int r = 0; r < kPickRegs; ++r)
-    if (live(r)) { kmin = min(kmin, key[r]); kmax = max(kmax, key[r]); }
-  block_minmax<kPickThreads>(kmin, kmax, sh);
-  const int nbits = 32 - __clz((int)(kmax - kmin));          // significant bits of the offsets (0 when all keys are equal)
+  for (int b0 = 0; b0 < kSlots; b0 += kBatch) {
+    if ((uint32_t)b0 * 64 < run) {                           // workgroup-uniform
+      const uint2* src[kBatch];
 #pragma unroll
-  for (int r = 0; r < kPickRegs; ++r) { key[r] -= kmin; pos[r] = ~pos[r]; }   // d, and the position as a descending key
+      for (int u = 0; u < kBatch; ++u) {
+        const uint32_t i = mine0 + (uint32_t)(b0 + u) * 64;
+        const uint32_t ic = i < n ? i : n - 1;
+        int sg = gseg[ic >> 6];
+        while (pfx[sg + 1] <= ic) ++sg;                      // ends: pfx[nb] = n > ic
+        src[u] = a.cand + (seg0 + sg) * a.rpb + (ic - pfx[sg]);
+      }
+      uint2 c[kBatch];
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u) c[u] = *src[u];
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u) {
+        const uint32_t i = mine0 + (uint32_t)(b0 + u) * 64;
+        pos[b0 + u] = c[u].y;
+        if (i < n && (uint32_t)(b0 + u) * 64 < run) {
+          const uint32_t key = score_key(__uint_as_float(c[u].x));
+          keys[i] = key;
+          kmin = min(kmin, key); kmax = max(kmax, key);
+        }
+      }
+    } else {
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u) pos[b0 + u] = 0u;
+    }
+  }
+  block_minmax<kPickThreads>(kmin, kmax, sh);                // its barriers also publish the keys
+  const int nbits = 32 - __clz((int)(kmax - kmin));          // significant bits of the offsets (0 when all keys are equal)
 
-  // Winners: in the offset part, d >> dsh >= dpref; once a tie on d = dpref had to be broken,
-  // d > dpref, or d == dpref and ~position >> psh >= ppref.
+  // Winners: in the offset part d = key - kmin, d >> dsh >= dpref; once a tie on d = dpref had to be broken,
+  // d > dpref, or d == dpref and the pair's number i (position order: lower first) satisfies ~i >> psh >= ppref.
   const bool all = k == n;
   bool tie = false;
   uint32_t dpref = 0, ppref = 0;
@@ -198,13 +218,11 @@ __global__ __launch_bounds__(kPickThreads) void decode_pick_kernel(PickArgs a) {
       for (int b = threadIdx.x; b < kBinsPad; b += kPickThreads) bins[b] = 0;
       __syncthreads();
       const int up = sft + w;                                // up == 32 only on a first pass: no prefix yet
-#pragma unroll
-      for (int r = 0; r < kPickRegs; ++r) {
-        if (live(r)) {
-          const uint32_t v = on_pos ? pos[r] : key[r];
-          const bool in = (up >= 32 || (v >> up) == (on_pos ? ppref : dpref)) && (!on_pos || key[r] == dpref);
-          if (in) atomicAdd(&bins[bslot((int)((v >> sft) & ((1u << w) - 1u)))], 1u);
-        }
+      for (uint32_t i = threadIdx.x; i < n; i += kPickThreads) {
+        const uint32_t d = keys[i] - kmin;
+        const uint32_t v = on_pos ? ~i : d;
+        const bool in = (up >= 32 || (v >> up) == (on_pos ? ppref : dpref)) && (!on_pos || d == dpref);
+        if (in) atomicAdd(&bins[bslot((int)((v >> sft) & ((1u << w) - 1u)))], 1u);
       }
       __syncthreads();
       uint32_t d, ab;
@@ -229,41 +247,54 @@ __global__ __launch_bounds__(kPickThreads) void decode_pick_kernel(PickArgs a) {
       }
     }
   }
-  uint32_t wins = 0;
-#pragma unroll
-  for (int r = 0; r < kPickRegs; ++r) {
-    const bool win = live(r) && (all || (tie ? (key[r] > dpref || (key[r] == dpref && (pos[r] >> psh) >= ppref))
-                                              : (dsh >= 32 || (key[r] >> dsh) >= dpref)));
-    wins |= win ? 1u << r : 0u;
-  }
+  auto wins = [&](uint32_t i) -> bool {
+    if (i >= n) return false;
+    if (all) return true;
+    const uint32_t d = keys[i] - kmin;
+    return tie ? (d > dpref || (d == dpref && (~i >> psh) >= ppref)) : (dsh >= 32 || (d >> dsh) >= dpref);
+  };
   // ranks: pairs are numbered in position order, so a winner's place in the ascending index list is the
-  // number of winners in front of it: whole (row, wave) groups from a prefix over their ballot counts,
-  // plus the lanes below it in its own ballot
-#pragma unroll
-  for (int r = 0; r < kPickRegs; ++r) {
-    const uint64_t b = __ballot((wins >> r) & 1u);
-    if (lane == 0) wcount[r * (kPickThreads / 64) + wave] = (uint32_t)__popcll(b);
+  // number of winners in front of it: the totals of the waves before its own, the ballots of its wave's
+  // earlier slots, and the lanes below it in its own slot's ballot
+  uint32_t won = 0, total = 0;
+#pragma unroll 4
+  for (int u = 0; u < kSlots; ++u) {
+    const bool live = (uint32_t)u * 64 < run;                // wave-uniform
+    const bool win = live && wins(mine0 + (uint32_t)u * 64);
+    const uint64_t b = __ballot(win);
+    won |= win ? 1u << u : 0u;
+    total += (uint32_t)__popcll(b);
   }
+  if (lane == 0) sh[wave] = total;
   __syncthreads();
-  {
-    constexpr int kGroups = kPickRegs * (kPickThreads / 64);
-    static_assert(kGroups <= kPickThreads, "one group per thread");
-    const uint32_t c = threadIdx.x < kGroups ? wcount[threadIdx.x] : 0u;
-    uint32_t total;
-    const uint32_t incl = block_scan_incl<kPickThreads>(c, sh, total);
-    if (threadIdx.x < kGroups) wcount[threadIdx.x] = incl - c;
-    __syncthreads();
-  }
+  uint32_t at0 = 0;
+#pragma unroll
+  for (int w = 0; w < kWaves; ++w) at0 += w < wave ? sh[w] : 0u;
   int32_t* out = a.idx + (int64_t)row_id * a.k_eff;
   const uint64_t below = (1ull << lane) - 1ull;
 #pragma unroll
-  for (int r = 0; r < kPickRegs; ++r) {
-    const bool win = (wins >> r) & 1u;
-    const uint64_t b = __ballot(win);
-    if (win) {
-      const uint32_t at = wcount[r * (kPickThreads / 64) + wave] + (uint32_t)__popcll(b & below);
-      if (at < k) out[at] = a.index_base + (int32_t)~pos[r];
+  for (int u = 0; u < kSlots; ++u) {
+    if ((uint32_t)u * 64 < run) {                            // wave-uniform
+      const bool win = (won >> u) & 1u;
+      const uint64_t b = __ballot(win);
+      const uint32_t at = at0 + (uint32_t)__popcll(b & below);
+      if (win && at < k) out[at] = a.index_base + (int32_t)pos[u];
+      at0 += (uint32_t)__popcll(b);
     }
+  }
+}
+
+// The rows the pick left over (as a rule none: then every workgroup returns at once).  Its own launch: inside
+// the pick its registers and call frame cost every launch a third of the pick's time.
+template <typename T, int D>
+__global__ __launch_bounds__(kPickThreads) void decode_redo_kernel(PickArgs a) {
+  __shared__ uint32_t bins[kBinsPad];
+  __shared__ uint32_t sh[40];
+  const uint32_t n_redo = a.redo[0];
+  for (uint32_t e = blockIdx.x; e < n_redo; e += gridDim.x) {
+    const int row_id = (int)a.redo[1 + e];
+    exact_row<T, D>(a, row_id, (float*)(a.cand + (int64_t)row_id * a.nb * a.rpb), bins, sh);
+    __syncthreads();
   }
 }
 
@@ -280,7 +311,11 @@ hipError_t sample_td(const SampleArgs& a0, int rows, hipStream_t st) {
 
 template <typename T, int D>
 hipError_t pick_td(const PickArgs& a, int rows, hipStream_t st) {
-  hipLaunchKernelGGL((decode_pick_kernel<T, D>), dim3(rows), dim3(kPickThreads), (size_t)(a.nb + 1) * 4, st, a);
+  const size_t lds = ((size_t)((a.nb + 1 + 3) & ~3) + kPickMax) * 4;     // segment prefix + the pairs' keys
+  auto kern = decode_pick_kernel<T, D>;
+  hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(kern, dim3(rows), dim3(kPickThreads), lds, st, a);
   return hipGetLastError();
 }
 
@@ -307,7 +342,7 @@ hipError_t launch_decode_pick(const Plan& pl, const void* q, const void* k_cache
   if (!pl.filter || pl.f_nb > kPickSlices) return hipErrorInvalidValue;
   PickArgs a;
   a.cand = cand; a.segcnt = segcnt; a.nb = pl.f_nb; a.rpb = pl.f_rpb; a.k_eff = pl.k_eff;
-  a.n_mid = pl.n_mid; a.index_base = (int32_t)pl.s_eff; a.idx = idx; a.redo_count = redo_count;
+  a.n_mid = pl.n_mid; a.index_base = (int32_t)pl.s_eff; a.idx = idx; a.redo = redo_count;
   a.q = q; a.k = k_cache; a.ksh = pl.ksh; a.kst = pl.kst; a.first_tok = pl.s_eff;
   a.pt = pl.pt; a.page_lg = pl.page_lg; a.Hq = pl.Hq; a.Hkv = pl.Hkv; a.G = pl.G;
   const int rows = pl.Hkv;

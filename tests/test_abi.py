@@ -78,6 +78,7 @@ def test_scope_clamping():
     (dict(n_sink=-1), B.ERR_RANGE),
     (dict(n_local=0), B.ERR_RANGE),
     (dict(top_k=-1), B.ERR_RANGE),
+    (dict(route=3), B.ERR_RANGE),
     (dict(rope_theta=1.0), B.ERR_RANGE),
     (dict(rope_theta=float("nan")), B.ERR_RANGE),
     (dict(softmax_scale=-0.5), B.ERR_RANGE),

@@ -288,3 +288,37 @@ def test_paged_random_shape_equals_contiguous(seed):
     torch.cuda.synchronize()
     assert torch.equal(idx0, idx1)
     assert torch.equal(out0, out1)
+
+
+# ------------------------------------------------------ the filter route of long decode steps over pools
+@pytest.mark.parametrize("name,ps", [("bf16_d128_long", 256), ("bf16_d128_long", 64)])
+def test_paged_filter_route_equals_contiguous_and_oracle(name, ps):
+    """The sampling launch, the filtering scan and (through a planted miss of the bound) the exact redo all
+    find their rows through the page table; checked bit for bit against the contiguous call and, directly,
+    against the oracle on the gathered cache."""
+    from tests import parity as P
+    w, _ = CASES[name]
+    t = wl.generate(w, "cuda")
+    p0 = replace(B.Params.from_workload(w), route=B.ROUTE_FILTER)
+    ws0 = B.alloc_workspace(p0)
+    out0, idx0 = B.decode_step(p0, t["q"], t["k"], t["v"], ws0)
+    assert B.redo_list(p0, ws0) == (0, [])
+    p, kp, vp, rows = _paged(w, t, ps, seed=21)
+    p = replace(p, route=B.ROUTE_FILTER)
+    ws = B.alloc_workspace(p)
+    out1, idx1 = B.decode_step(p, t["q"], kp, vp, ws)
+    torch.cuda.synchronize()
+    assert B.redo_list(p, ws) == (0, [])
+    assert torch.equal(idx0, idx1) and torch.equal(out0, out1)
+    P.check_layer(w, t, out1, idx1)
+    # keys that score high exactly where the sample looks: fewer than k pairs pass, every row is redone
+    step = w.n_mid // 8192
+    qbar = t["q"][0].float().reshape(w.n_kv_heads, w.group, w.head_dim).sum(dim=1)
+    pos = torch.arange(w.n_sink, w.n_sink + w.n_mid, step, device="cuda")[:1500]
+    needle = (qbar / qbar.norm(dim=1, keepdim=True) * 60.0).to(t["k"].dtype).unsqueeze(1)
+    t["k"][:, pos, :] = needle
+    kp[:, rows[pos], :] = needle
+    out2, idx2 = B.decode_step(p, t["q"], kp, vp, ws)
+    torch.cuda.synchronize()
+    assert B.redo_list(p, ws)[0] == w.n_kv_heads
+    P.check_layer(w, t, out2, idx2)

@@ -416,7 +416,8 @@ FILTER_CASES = {
 
 
 def _filter_step(w, t):
-    p = B.Params.from_workload(w)
+    from dataclasses import replace
+    p = replace(B.Params.from_workload(w), route=B.ROUTE_FILTER)
     ws = B.alloc_workspace(p)
     out, idx = B.decode_step(p, t["q"], t["k"], t["v"], ws)
     torch.cuda.synchronize()
@@ -483,9 +484,15 @@ def test_decode_filter_route_exact_ties_at_the_kth_score():
         assert np.array_equal(idx.cpu().numpy(), want)
 
 
-def test_decode_filter_route_is_deterministic_and_static_entry_agrees():
+def test_decode_filter_route_is_deterministic_and_agrees_with_the_score_route():
+    from dataclasses import replace
     w = FILTER_CASES["bf16_d128_g4"]
     t = gen(w)
     out1, idx1, _ = _filter_step(w, t)
     out2, idx2, _ = _filter_step(w, t)
     assert torch.equal(idx1, idx2) and torch.equal(out1, out2)
+    p = replace(B.Params.from_workload(w), route=B.ROUTE_SCORES)
+    assert B.redo_list(p, B.alloc_workspace(p)) is None
+    out3, idx3 = B.decode_step(p, t["q"], t["k"], t["v"], B.alloc_workspace(p))
+    torch.cuda.synchronize()
+    assert torch.equal(idx1, idx3) and torch.equal(out1, out3)        # the same scores, the same tie rule

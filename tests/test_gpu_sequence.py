@@ -165,12 +165,13 @@ def test_decode_tokens_through_layers(mode, dtype):
             assert err <= P.OUT_TOL[dtype], (step, l, err)
 
 
-@pytest.mark.parametrize("n_ctx", [9_001, 80_001])
-def test_decode_token_layers_equal_separate_steps(n_ctx):
+@pytest.mark.parametrize("n_ctx,route", [(9_001, 0), (80_001, 0), (80_001, 1)])
+def test_decode_token_layers_equal_separate_steps(n_ctx, route):
     """Layers after the first skip the clearing launch (the previous layer's top-k leaves the histograms
     zeroed) and copy the token's rows inside the scan: every layer must equal cache_append + decode_step
     on its own workspace, bit for bit.  80,001 tokens take the chip-wide select / refine / emit kernels,
-    9,001 the one-workgroup-per-row kernel."""
+    9,001 the one-workgroup-per-row kernel; route 1 asks for the filter route (sampled bound, filtering scan,
+    pick), whose sampling launch skips the rotary table after the first layer."""
     n_layers = 4
     w = wl.CONFIGS[2].scaled(n_ctx=n_ctx, n_local=300, top_k=500, max_position=0, n_needles=0)
     dt = w.torch_dtype()
@@ -181,9 +182,10 @@ def test_decode_token_layers_equal_separate_steps(n_ctx):
     qs = [torch.randn(1, Hq, D, generator=g, device="cuda").to(dt) for _ in range(n_layers)]
     kn = [torch.randn(1, Hkv, D, generator=g, device="cuda").to(dt) for _ in range(n_layers)]
     vn = [torch.randn(1, Hkv, D, generator=g, device="cuda").to(dt) for _ in range(n_layers)]
-    p = replace(B.Params.from_workload(w), n_query=1)
+    p = replace(B.Params.from_workload(w), n_query=1, route=route)
     k2 = [x.clone() for x in kcs]; v2 = [x.clone() for x in vcs]
     ws = B.alloc_workspace(p)
+    assert (B.redo_list(p, ws) is not None) == (route == 1)
     for rep in range(2):                                        # the second call starts on the workspace the first left
         outs = B.decode_token(p, qs, kn, vn, kcs, vcs, ws)
         torch.cuda.synchronize()
