@@ -19,8 +19,9 @@ import sys
 import time
 
 HBM_PEAK_GBPS = 8000.0      # MI355X published HBM3E bandwidth
-# Measured with rocprofv3 --pmc (profiles/score_scan_cfg3_pmc.md): fetched + written bytes per launch.
-SCAN_TRAFFIC_BYTES = {"cfg3_decode_1m_bf16": 2 * 1044576.9 * 1024 + 32914.1 * 1024}
+# Measured with rocprofv3 --pmc: fetched + written bytes per launch of the scan kernel, per workload.
+SCAN_TRAFFIC = {"cfg3_decode_1m_bf16": {"bytes": 2 * 1044576.9 * 1024 + 32914.1 * 1024,
+                                        "source": "profiles/score_scan_cfg3_pmc.md"}}
 # Same for the other dominant kernels (profiles/vote_decode_cfg3_kernel_trace_pmc.md,
 # profiles/prefill_chunk_cfg4_kernel_trace_pmc.md, profiles/vote_prefill_cfg4_kernel_trace_pmc.md): fetched bytes per launch.
 VOTE_SCAN_TRAFFIC_BYTES = {"cfg3_decode_1m_bf16": 2 * 1044560.7 * 1024 + 32.0 * 1024}
@@ -36,6 +37,8 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=3, choices=[1, 2, 3, 5],
                     help="decode configuration (3 = the 1M-token one the metric is quoted on)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-other-configs", action="store_true",
+                    help="skip the decode legs of the configurations other than --config")
     ap.add_argument("--no-prefill", action="store_true",
                     help="skip the config-4 prefill-chunk measurement (MFMA score contraction)")
     ap.add_argument("--only-prefill", action="store_true",
@@ -111,24 +114,7 @@ def main() -> int:
                                            args.steps, args.warmup)}), flush=True)
         return 0
     w = wl.CONFIGS[args.config]
-    p = B.Params.from_workload(w)
     t = wl.generate(w, "cuda")
-    ws = B.alloc_workspace(p)
-    out = torch.empty(1, w.n_q_heads, w.head_dim, dtype=torch.float32, device="cuda")
-    idx = torch.empty(1, w.n_kv_heads, w.k_eff, dtype=torch.int32, device="cuda")
-
-    # Caches smaller than the 256 MB last-level cache would be served from it on
-    # repeated steps; rotate over several copies so every step streams from HBM.
-    n_rot = 1
-    kv_bytes = 2 * t["k"].numel() * t["k"].element_size()
-    if kv_bytes < (2 << 30):
-        n_rot = min(8, max(2, int((2 << 30) // max(kv_bytes, 1))))
-    ks = [t["k"]] + [t["k"].clone() for _ in range(n_rot - 1)]
-    vs = [t["v"]] + [t["v"].clone() for _ in range(n_rot - 1)]
-
-    def step(i):
-        B.decode_step(p, t["q"], ks[i % n_rot], vs[i % n_rot], ws, idx_out=idx, out=out)
-
     if args.calibrate_copy:
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")     # 1 GiB read + 1 GiB written
         dst = torch.empty_like(src)
@@ -136,59 +122,45 @@ def main() -> int:
             dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
-
-    for i in range(args.warmup):
-        step(i)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(i)
-    torch.cuda.synchronize()
-    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
-
-    # Same steps again with HIP events at the stage boundaries (on the launch stream).
-    stage_sum = {s: 0.0 for s in B.STAGES}
-    for i in range(args.steps):
-        _, _, ms = B.decode_step_timed(p, t["q"], ks[i % n_rot], vs[i % n_rot], ws, idx_out=idx, out=out)
-        for s in B.STAGES:
-            stage_sum[s] += ms[s]
-    stages = {s: stage_sum[s] / args.steps for s in B.STAGES}
-    read_ceiling = B.probe_read_bandwidth(ks[0], iters=10)   # plain read of the same K cache
-    scan_ms = stages["scan"]
-    scan_gbps = w.scan_bytes / (scan_ms * 1e-3) / 1e9 if scan_ms > 0 else 0.0
-
+    leg = decode_leg(w, t, args.steps, args.warmup)
+    ms_per_step = leg["ms_per_step"]
     result = {
         "metric": "decode-step latency (one layer, 1 query token, ReAttention score+top-k+attend)",
-        "value": round(ms_per_step, 5),
+        "value": ms_per_step,
         "unit": "ms/layer",
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
-        "ms_per_step": round(ms_per_step, 5),
+        "ms_per_step": ms_per_step,
         "higher_is_better": False,
         "scaling": "weak",
         "vs_baseline": None,
         "dtype": w.dtype,
         "data": "synthetic",
-        "config": {
-            "workload": w.name, "n_ctx": w.n_ctx, "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads,
-            "head_dim": w.head_dim, "n_sink": w.n_sink, "n_local": w.n_local, "top_k": w.top_k,
-            "scope": w.scope, "cache_copies_rotated": n_rot,
-        },
-        "kv_scan_GBps": round(scan_gbps, 1),
-        "stages_ms": {s: round(v, 5) for s, v in stages.items()},
-        "roofline": {
-            "kernel": "score_scan_kernel", "bound": "hbm",
-            "achieved": round(scan_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-            "frac": round(scan_gbps / HBM_PEAK_GBPS, 4),
-            "algorithmic_bytes": w.scan_bytes,
-            # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE (KiB per dispatch,
-            # FETCH_SIZE x2.0 and WRITE_SIZE x1.0 after scaling by a 1 GiB copy): see profiles/
-            "traffic": SCAN_TRAFFIC_BYTES.get(w.name),
-            "measured_read_ceiling_GBps": round(read_ceiling, 1),
-            "frac_of_measured_ceiling": round(scan_gbps / read_ceiling, 4) if read_ceiling > 0 else None,
-        },
+        "config": leg["config"],
+        "kv_scan_GBps": leg["kv_scan_GBps"],
+        "stages_ms": leg["stages_ms"],
+        "selection_route": leg["selection_route"],
+        "step_floor": leg["step_floor"],
+        "roofline": leg["roofline"],
     }
+    if not args.no_other_configs:
+        # the other decode configurations (1: 16K fp32 toy, 2: 128K, 5: 4M tokens), each with its own roofline
+        others = {}
+        for cfg in (1, 2, 5):
+            if cfg == args.config:
+                continue
+            if cfg == 5:                          # 16 GiB of cache: the main configuration's tensors make room
+                t = None
+                torch.cuda.empty_cache()
+            wc = wl.CONFIGS[cfg]
+            tc = wl.generate(wc, "cuda")
+            others[wc.name] = decode_leg(wc, tc, args.steps, args.warmup)
+            del tc
+            torch.cuda.empty_cache()
+        result["decode_configs"] = others
+        if t is None:
+            t = wl.generate(w, "cuda")
 
     if not args.no_vote:
         result["vote"] = vote_leg(t, args.config, args.steps, args.warmup)
@@ -199,7 +171,7 @@ def main() -> int:
         if not args.no_prefill:
             result["paged_prefill"] = paged_prefill_leg(5)
     if not args.no_prefill:
-        del ks, vs, t, ws
+        t = None
         torch.cuda.empty_cache()
         result["prefill"] = prefill_leg(min(args.steps, 5))
         if not args.no_vote:
@@ -224,6 +196,81 @@ def main() -> int:
 
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X published dense bf16 matrix rate
+
+
+def decode_leg(w, t: dict, steps: int, warmup: int) -> dict:
+    """One decode configuration: wall-clock ms per step over `steps` steps (inputs resident in HBM, sync on
+    both sides), the stage times from HIP events on the launch stream (a second set of instrumented steps),
+    and the roofline of the key scan.  Caches under 1 GiB of keys are rotated over enough copies that their
+    keys sum to 1 GiB (four times the 256 MB last-level cache), so that every step streams from HBM; the
+    plain-read ceiling is probed over all the copies for the same reason."""
+    import torch
+    from paper_2407_15176_amd import binding as B
+    p = B.Params.from_workload(w)
+    ws = B.alloc_workspace(p)
+    out = torch.empty(1, w.n_q_heads, w.head_dim, dtype=torch.float32, device="cuda")
+    idx = torch.empty(1, w.n_kv_heads, w.k_eff, dtype=torch.int32, device="cuda")
+    k_bytes = t["k"].numel() * t["k"].element_size()
+    n_rot = 1 if k_bytes >= (1 << 30) else min(160, -(-(1 << 30) // k_bytes))
+    if n_rot > 1:
+        kbig = t["k"].unsqueeze(0).repeat(n_rot, 1, 1, 1)
+        vbig = t["v"].unsqueeze(0).repeat(n_rot, 1, 1, 1)
+        ks, vs = list(kbig.unbind(0)), list(vbig.unbind(0))
+    else:
+        kbig, ks, vs = t["k"], [t["k"]], [t["v"]]
+
+    def step(i):
+        B.decode_step(p, t["q"], ks[i % n_rot], vs[i % n_rot], ws, idx_out=idx, out=out)
+
+    for i in range(warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        step(warmup + i)
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / steps
+    stage_sum = {s: 0.0 for s in B.STAGES}
+    for i in range(steps):
+        _, _, ms = B.decode_step_timed(p, t["q"], ks[i % n_rot], vs[i % n_rot], ws, idx_out=idx, out=out)
+        for s in B.STAGES:
+            stage_sum[s] += ms[s]
+    stages = {s: stage_sum[s] / steps for s in B.STAGES}
+    read_ceiling = B.probe_read_bandwidth(kbig, iters=10 if n_rot == 1 else 3)   # plain read of the same keys (all copies)
+    scan_ms = stages["scan"]
+    scan_gbps = w.scan_bytes / (scan_ms * 1e-3) / 1e9 if scan_ms > 0 else 0.0
+    filter_route = B.redo_list(p, ws) is not None
+    # the step's algorithmic bytes: the key scan, one fp32 score per key written once and read twice (score
+    # route; the filter route moves ~2 % of that), the K and V rows of the attention scope
+    gather = 2 * w.scope * w.n_kv_heads * w.head_dim * w.elem_bytes
+    floor_bytes = w.scan_bytes + 3 * w.n_kv_heads * w.n_mid * 4 + gather
+    floor_ms = floor_bytes / (HBM_PEAK_GBPS * 1e9) * 1e3
+    return {
+        "workload": w.name, "ms_per_step": round(ms_per_step, 5), "steps": steps,
+        "config": {
+            "workload": w.name, "n_ctx": w.n_ctx, "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads,
+            "head_dim": w.head_dim, "n_sink": w.n_sink, "n_local": w.n_local, "top_k": w.top_k,
+            "scope": w.scope, "cache_copies_rotated": n_rot,
+        },
+        "selection_route": "filter (sampled bound, filtering scan, pick)" if filter_route else "scores (scan + radix select)",
+        "kv_scan_GBps": round(scan_gbps, 1),
+        "stages_ms": {s: round(v, 5) for s, v in stages.items()},
+        "step_floor": {"algorithmic_bytes": floor_bytes, "floor_ms_at_peak": round(floor_ms, 5),
+                       "floor_over_measured": round(floor_ms / ms_per_step, 4)},
+        "roofline": {
+            "kernel": "score_scan_kernel", "bound": "hbm",
+            "achieved": round(scan_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+            "frac": round(scan_gbps / HBM_PEAK_GBPS, 4),
+            "algorithmic_bytes": w.scan_bytes,
+            # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE (KiB per dispatch, each scaled
+            # by what the same counter reads for a 1 GiB copy): measured for the workloads listed with the
+            # profile they come from, null elsewhere
+            "traffic": SCAN_TRAFFIC.get(w.name, {}).get("bytes"),
+            "traffic_source": SCAN_TRAFFIC.get(w.name, {}).get("source"),
+            "measured_read_ceiling_GBps": round(read_ceiling, 1),
+            "frac_of_measured_ceiling": round(scan_gbps / read_ceiling, 4) if read_ceiling > 0 else None,
+        },
+    }
 
 
 def prefill_leg(steps: int) -> dict:
@@ -274,7 +321,8 @@ def prefill_leg(steps: int) -> dict:
         # rows requested per second against the HBM peak (part of them is served by L2 and the memory-side cache)
         "attend_gather": {
             "kernel": "attend_prefill_kernel", "requested_bytes": gather,
-            "requested_GBps": round(gather / (acc["attend"] * 1e-3) / 1e9, 1), "hbm_peak_GBps": HBM_PEAK_GBPS,
+            # rows asked for, not bytes fetched from HBM: most of them are served by L2 and the memory-side cache
+            "requested_not_fetched_GBps": round(gather / (acc["attend"] * 1e-3) / 1e9, 1), "hbm_peak_GBps": HBM_PEAK_GBPS,
         },
     }
 

@@ -14,10 +14,10 @@
 //            offsets from the smallest candidate key, and writes the winners' absolute indices in ascending
 //            order (ranks from wave ballots).  A row whose bound missed (fewer than k pairs: probability
 //            ~1e-9 per row on exchangeable keys) or whose pairs exceed the LDS (degenerate rows: runs of
-//            equal scores) is left to
-//   redo     a launch of its own right behind the pick (as a rule it finds its list empty and returns): one
-//            workgroup per listed row recomputes the row's scores with the scan's arithmetic and selects
-//            exactly over all of them: slow (one workgroup streams the row), same result.
+//            equal scores) recomputes its scores with the scan's arithmetic and selects exactly over all of
+//            them: slow (one workgroup streams the row), same result.  (Measured: the redo has to be inlined
+//            and hinted cold; as a called function its stack cost every launch 7 us, and as a launch of its
+//            own behind the pick 4.5 us for finding its list empty.)
 #include "common.hpp"
 #include "select.hpp"
 
@@ -79,7 +79,7 @@ struct PickArgs {
   int nb, rpb, k_eff;
   int64_t n_mid; int32_t index_base;
   int32_t* idx;                                              // [rows][k_eff]
-  uint32_t* redo;                                            // [0] rows left to the exact redo, [1..] which
+  uint32_t* redo;                                            // [0] rows that took the exact redo
   // the exact redo recomputes the row's scores: over the row's own segments, which it no longer needs
   const void* q; const void* k;
   int64_t ksh, kst, first_tok;
@@ -281,20 +281,6 @@ __global__ __launch_bounds__(kPickThreads) void decode_pick_kernel(PickArgs a) {
       if (win && at < k) out[at] = a.index_base + (int32_t)pos[u];
       at0 += (uint32_t)__popcll(b);
     }
-  }
-}
-
-// The rows the pick left over (as a rule none: then every workgroup returns at once).  Its own launch: inside
-// the pick its registers and call frame cost every launch a third of the pick's time.
-template <typename T, int D>
-__global__ __launch_bounds__(kPickThreads) void decode_redo_kernel(PickArgs a) {
-  __shared__ uint32_t bins[kBinsPad];
-  __shared__ uint32_t sh[40];
-  const uint32_t n_redo = a.redo[0];
-  for (uint32_t e = blockIdx.x; e < n_redo; e += gridDim.x) {
-    const int row_id = (int)a.redo[1 + e];
-    exact_row<T, D>(a, row_id, (float*)(a.cand + (int64_t)row_id * a.nb * a.rpb), bins, sh);
-    __syncthreads();
   }
 }
 

@@ -313,7 +313,11 @@ hipError_t launch_score_scan_filter(const Plan& pl, const void* q, const void* k
 hipError_t launch_read_probe(const void* buf, size_t bytes, hipStream_t st) {
   const size_t n_vec = bytes / 16;
   if (n_vec == 0) return hipSuccess;
-  const size_t vpb = (size_t)kScanMaxRows * 16;           // 8 MiB per workgroup, as in the scan
+  // up to 8 MiB per workgroup, as in the scan; small buffers are cut finer so that they still fill the chip
+  // (a workgroup's waves take 8192 vectors per round)
+  size_t vpb = (size_t)kScanMaxRows * 16;
+  const size_t even = ((n_vec + 1023) / 1024 + 8191) / 8192 * 8192;
+  if (even < vpb) vpb = even;
   hipLaunchKernelGGL(read_probe_kernel, dim3((unsigned)((n_vec + vpb - 1) / vpb)), dim3(kScanThreads),
                      0, st, (const u32x4*)buf, n_vec, vpb, (uint32_t*)nullptr);
   return hipGetLastError();
