@@ -240,6 +240,11 @@ int reattn_vote_layer(const reattn_params* p, const reattn_vote* v, const void* 
 int reattn_cache_append(const reattn_params* p, int64_t first_tok, int32_t n_tok, const void* k_new,
                         const void* v_new, void* k_cache, void* v_cache, void* stream);
 
+/* Chunk c of the loop: its tokens are [*first, *end) (the chunk's query rows; the cache holds *end tokens when
+ * it selects).  REATTN_ERR_RANGE past the last chunk.  Either output may be NULL.  Host only.  A caller sizes
+ * idx_out of reattn_prefill_sequence by asking reattn_scope for every chunk's (n_ctx = *end, n_query = *end - *first). */
+int reattn_prefill_sequence_chunk_bounds(const reattn_params* p, int32_t chunk, int64_t c, int64_t* first, int64_t* end);
+
 /* Number of chunks of the loop (0 if p or chunk is invalid) and the scratch bytes the whole loop
  * accepts (the largest any chunk needs; v == NULL: per-query top-k, else the vote selection). */
 int64_t reattn_prefill_sequence_chunks(const reattn_params* p, int32_t chunk);

@@ -34,6 +34,7 @@ EXPORTS = [
     "reattn_vote_layer_timed", "reattn_cache_append", "reattn_prefill_sequence_chunks",
     "reattn_prefill_sequence_workspace_bytes", "reattn_prefill_sequence", "reattn_decode_token",
     "reattn_static_scratch_bytes", "reattn_decode_step_static", "reattn_redo_list_offset",
+    "reattn_prefill_sequence_chunk_bounds",
 ]
 PREFILL_STAGES = ("sample_threshold", "score_gemm_filter", "candidate_topk", "attend")
 STAGES = ("prep", "scan", "topk", "attend")
@@ -104,6 +105,7 @@ def lib() -> C.CDLL:
         L.reattn_vote_layer.argtypes = [PP, PV, P, P, P, P, P, P, P, C.c_size_t, P]
         L.reattn_vote_layer_timed.argtypes = L.reattn_vote_layer.argtypes + [C.POINTER(C.c_float)]
         L.reattn_cache_append.argtypes = [PP, C.c_int64, C.c_int32, P, P, P, P, P]
+        L.reattn_prefill_sequence_chunk_bounds.argtypes = [PP, C.c_int32, C.c_int64, C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
         L.reattn_prefill_sequence_chunks.argtypes = [PP, C.c_int32]
         L.reattn_prefill_sequence_chunks.restype = C.c_int64
         L.reattn_prefill_sequence_workspace_bytes.argtypes = [PP, PV, C.c_int32]
@@ -456,13 +458,15 @@ def cache_append(p: Params, first_tok: int, k_new, v_new, k_cache, v_cache):
 
 
 def sequence_chunks(p: Params, chunk: int):
-    """[(start, end)] of the chunk loop: first min(L, n_sink + n_local) tokens, then `chunk` at a time."""
-    L = p.n_ctx
-    out, s, e = [], 0, min(L, p.n_sink + p.n_local)
-    while s < L:
-        out.append((s, e))
-        s, e = e, min(L, e + chunk)
-    assert len(out) == lib().reattn_prefill_sequence_chunks(C.byref(p.c()), chunk)
+    """[(first, end)] of the chunk loop, as the library cuts it (reattn_prefill_sequence_chunk_bounds)."""
+    cp = p.c()
+    n = lib().reattn_prefill_sequence_chunks(C.byref(cp), chunk)
+    out = []
+    for c in range(n):
+        s, e = C.c_int64(), C.c_int64()
+        _check(lib().reattn_prefill_sequence_chunk_bounds(C.byref(cp), chunk, c, C.byref(s), C.byref(e)),
+               "reattn_prefill_sequence_chunk_bounds")
+        out.append((s.value, e.value))
     return out
 
 
@@ -487,9 +491,9 @@ def prefill_sequence(p: Params, chunk: int, q, k_new, v_new, k_cache=None, v_cac
     idx_flat = sel_all = n_sel_all = None
     shapes = []
     if want_sets and vote is None:
-        for s, e in chunks:
-            n_mid = max(0, e - min(p.n_sink, e) - min(p.n_local, e - min(p.n_sink, e)))
-            shapes.append((e - s, p.n_kv_heads, min(p.top_k, n_mid)))
+        for s, e in chunks:                                    # every chunk's k_eff from the library's own Eq. 1
+            k_eff = scope(Params(**{**p.__dict__, "n_ctx": e, "n_query": e - s, "max_position": 0}))[3]
+            shapes.append((e - s, p.n_kv_heads, k_eff))
         idx_flat = torch.empty(max(1, sum(a * b * c for a, b, c in shapes)), dtype=torch.int32, device=dev)
     if want_sets and vote is not None:
         cap = max(1, vote_cap(Params(**{**p.__dict__, "n_query": 1, "max_position": 0}), vote))

@@ -750,6 +750,18 @@ int sequence_check(const reattn_params* p, int32_t chunk) {
 }
 }  // namespace
 
+extern "C" int reattn_prefill_sequence_chunk_bounds(const reattn_params* p, int32_t chunk, int64_t c, int64_t* first,
+                                                    int64_t* end) {
+  const int rc = sequence_check(p, chunk);
+  if (rc) return rc;
+  if (p->n_ctx < 1 || c < 0) return REATTN_ERR_RANGE;
+  int64_t s, e;
+  if (!sequence_chunk(p, chunk, c, &s, &e)) return REATTN_ERR_RANGE;
+  if (first) *first = s;
+  if (end) *end = e;
+  return REATTN_OK;
+}
+
 extern "C" int64_t reattn_prefill_sequence_chunks(const reattn_params* p, int32_t chunk) {
   if (sequence_check(p, chunk) || p->n_ctx < 1) return 0;
   int64_t c = 0, s, e;

@@ -136,6 +136,15 @@ def test_sequence_loop_is_planned_on_the_host():
     L = B.lib()
     assert L.reattn_prefill_sequence_chunks(C.byref(cp), 128) == 1 + -(-(10_000 - 260) // 128)
     assert L.reattn_prefill_sequence_chunks(C.byref(cp), 0) == 0
+    # the chunks as the appendix's prefilling loop cuts them: sink + local tokens first, then 128 at a time
+    chunks = B.sequence_chunks(p, 128)
+    assert chunks[0] == (0, 260) and chunks[1] == (260, 388) and chunks[-1] == (9_988, 10_000)
+    assert all(a[1] == b[0] for a, b in zip(chunks, chunks[1:]))
+    s, e = C.c_int64(), C.c_int64()
+    assert L.reattn_prefill_sequence_chunk_bounds(C.byref(cp), 128, len(chunks), C.byref(s), C.byref(e)) == B.ERR_RANGE
+    assert L.reattn_prefill_sequence_chunk_bounds(C.byref(cp), 128, -1, None, None) == B.ERR_RANGE
+    assert L.reattn_prefill_sequence_chunk_bounds(C.byref(cp), 0, 0, None, None) == B.ERR_RANGE
+    assert B.sequence_chunks(good(n_ctx=100, n_sink=4, n_local=256, max_position=0), 64) == [(0, 100)]
     assert L.reattn_prefill_sequence_workspace_bytes(C.byref(cp), None, 128) > 0
     assert L.reattn_prefill_sequence_workspace_bytes(C.byref(cp), None, 257) == 0     # chunk above the local window
     cv = B.Vote(4, 20, 8).c()

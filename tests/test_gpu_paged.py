@@ -322,3 +322,54 @@ def test_paged_filter_route_equals_contiguous_and_oracle(name, ps):
     torch.cuda.synchronize()
     assert B.redo_list(p, ws)[0] == w.n_kv_heads
     P.check_layer(w, t, out2, idx2)
+
+
+# ------------------------------------------------------------ paged calls against the oracle itself
+# (the oracle reads the contiguous cache the pools were scattered from: t["k"], t["v"])
+@pytest.mark.parametrize("name", ["bf16_d128_g4", "f32_d64_g4", "f16_d128_g3"])
+def test_paged_decode_step_against_oracle(name):
+    from tests import parity as P
+    w, ps = CASES[name]
+    t = wl.generate(w, "cuda")
+    p, kp, vp, _ = _paged(w, t, ps, seed=31)
+    out, idx = B.decode_step(p, t["q"], kp, vp, B.alloc_workspace(p), want_idx=True)
+    torch.cuda.synchronize()
+    P.check_layer(w, t, out, idx)
+
+
+@pytest.mark.parametrize("name", ["bf16_mfma", "f32_scan"])
+def test_paged_prefill_chunk_against_oracle(name):
+    from tests import parity as P
+    w, ps = CHUNKS[name]
+    w = w.scaled(n_needles=0, scale_q=True)
+    t = wl.generate(w, "cuda")
+    p, kp, vp, _ = _paged(w, t, ps, seed=32)
+    out, idx = B.prefill_chunk(p, t["q"], kp, vp, B.alloc_workspace(p), want_idx=True)
+    torch.cuda.synchronize()
+    P.check_layer(w, t, out, idx)
+
+
+@pytest.mark.parametrize("M", [1, 40])
+def test_paged_vote_layer_against_oracle(M):
+    import numpy as np
+    from oracle import reattn_oracle as ro
+    from tests import parity as P
+    w = wl.CONFIGS[4].scaled(n_ctx=30_011, n_query=M, n_local=300, top_k=0, max_position=0)
+    v = B.Vote(4, 40, 16)
+    t = wl.generate(w, "cuda")
+    p, kp, vp, _ = _paged(w, t, 128, seed=33)
+    ws = B.alloc_vote_workspace(p, v)
+    lists = B.vote_topk(p, v, t["q"], kp, ws)
+    out, sel, n_sel = B.vote_layer(p, v, t["q"], kp, vp, ws)
+    torch.cuda.synchronize()
+    sh = P.oracle_shape(w)
+    q, k, vv = P.host_inputs(t)
+    res = ro.vote_forward(sh, q, k, vv, v.vote_k, v.n_centres, v.span, head_topk=lists.cpu().numpy())
+    s_eff, _, n_mid, _ = sh.partition()
+    R = M * w.n_q_heads
+    P.check_index_sets(lists.cpu().numpy().reshape(R, 4), res["head_topk"].reshape(R, 4),
+                       res["head_scores"].reshape(R, n_mid), res["head_kth"].reshape(R), s_eff, n_mid)
+    n = int(n_sel.item())
+    assert sel.cpu().numpy()[:n].tolist() == res["sel"].tolist()
+    err = np.abs(out.cpu().numpy().astype(np.float64) - res["out"]).max()
+    assert err <= P.OUT_TOL[w.dtype], err
