@@ -189,7 +189,9 @@ int reattn_prefill_chunk(const reattn_params* p, const void* q, const void* k_ca
  * min(n_centres * span, N_mid).  In these calls p->top_k is ignored, the scope is
  * S = s_eff + n_sel + l_eff (query i sits at slot s_eff + n_sel + l_eff - M + i) and
  * p->max_position is checked against s_eff + cap + l_eff.
- * Supported: bf16 / fp16 with D = 128 or fp32 with D = 64, G <= 8, vote_k <= 8, n_centres <= 1024.
+ * Supported: every shape reattn_validate accepts (G <= 16), vote_k <= 8, n_centres <= 1024.  16-bit storage with
+ * D = 128 scores on the matrix cores; fp32 storage and D = 64 on the vector ALU (the keys are then streamed
+ * once per query row, and once more per 8 (D = 64, or fp32 D = 64) or 16 (fp32 D = 128) heads of a group).
  *
  * Batches: with n_seq > 1 the head axis holds n_seq equal-length sequences of a decode step (M = 1),
  * sequence b owning query heads [b * Hq/n_seq, ...) and KV heads [b * Hkv/n_seq, ...) of q / the caches;

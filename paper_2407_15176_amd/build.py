@@ -16,8 +16,8 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libreattn.so")
 SOURCES = ["api.hip", "score_scan.hip", "score_gemm.hip", "prefill_select.hip", "topk.hip", "decode_select.hip", "rope.hip",
-           "attend.hip", "attend_prefill.hip", "vote.hip", "vote_gemm.hip", "attend_shared.hip"]
-HEADERS = [os.path.join(CSRC, "common.hpp"), os.path.join(CSRC, "select.hpp"), os.path.join(HERE, "..", "include", "reattn.h")]
+           "attend.hip", "attend_prefill.hip", "vote.hip", "vote_scan.hip", "vote_gemm.hip", "attend_shared.hip"]
+HEADERS = [os.path.join(CSRC, "common.hpp"), os.path.join(CSRC, "select.hpp"), os.path.join(CSRC, "vote_scan.hpp"), os.path.join(HERE, "..", "include", "reattn.h")]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

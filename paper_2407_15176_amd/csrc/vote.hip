@@ -23,171 +23,12 @@
 //                    / prefix sum -> ascending index list and its length (a device scalar: the
 //                    scope of the following attention is data dependent).
 #include "common.hpp"
+#include "select.hpp"
+#include "vote_scan.hpp"
 
 namespace reattn {
 namespace {
 
-template <typename T> struct Elem;
-template <> struct Elem<float> {
-  static constexpr int kPerLoad = 4;
-  static __device__ __forceinline__ void widen(const u32x4& d, float* x) {
-    x[0] = __uint_as_float(d.x); x[1] = __uint_as_float(d.y);
-    x[2] = __uint_as_float(d.z); x[3] = __uint_as_float(d.w);
-  }
-  static __device__ __forceinline__ float one(const void* p, int64_t i) { return ((const float*)p)[i]; }
-};
-// (score desc, index asc) as one unsigned 64-bit maximum; 0 is "nothing".
-__device__ __forceinline__ uint64_t composite(float score, uint32_t pos) {
-  return ((uint64_t)score_key(score) << 32) | (uint64_t)(0xffffffffu - pos);
-}
-__device__ __forceinline__ uint64_t wave_max_u64(uint64_t v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) {
-    const uint32_t lo = __shfl_xor((uint32_t)v, o, 64), hi = __shfl_xor((uint32_t)(v >> 32), o, 64);
-    const uint64_t w = ((uint64_t)hi << 32) | lo;
-    v = w > v ? w : v;
-  }
-  return v;
-}
-
-constexpr int kVoteThreads = 1024;
-constexpr int kVoteWaves = kVoteThreads / 64;
-
-struct HeadScanArgs {
-  const void* k; const void* q;
-  uint64_t* part;          // [rows = n_query * Hq][n_wg][KT] composites, best first
-  int64_t ksh, kst, n_mid, first_tok;
-  int Hq, Hkv, G, rows_per_block, n_wg;
-  const int32_t* pt; int page_lg;   // paged cache (PAGED kernels): the page of every 2^page_lg tokens
-};
-
-// Paged caches: a slice of at most 16,384 rows spans at most 257 pages of 64 tokens or more (+ the spare entry);
-// a multiple of 16 bytes, so that the dynamic LDS behind it keeps its 16-byte alignment (128-bit LDS accesses).
-constexpr int kVotePages = 16384 / 64 + 4;
-static_assert(kVotePages * sizeof(int32_t) % 16 == 0, "keeps the staging tiles 16-byte aligned");
-
-// KT: list length kept per head (>= vote_k); GH: heads a lane keeps lists for (ceil(G / 2)).
-template <typename T, int D, int KT, int GH, bool PAGED = false>
-__global__ __launch_bounds__(kVoteThreads) void head_topk_scan_kernel(HeadScanArgs a) {
-  __shared__ int32_t s_pages[PAGED ? kVotePages : 1];
-  constexpr int EPL = Elem<T>::kPerLoad, LPR = D / EPL, RPL = 64 / LPR, U = 8, RW = U * RPL;
-  static_assert(LPR == 16, "a key row spans 16 lanes (D = 128 bf16 or D = 64 fp32)");
-  constexpr int GMAX = 2 * GH;
-  __shared__ uint64_t wave_best[kVoteWaves][GMAX][KT];
-
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int sub = lane % LPR, grp = lane / LPR;
-  const int row_id = blockIdx.y;                       // query * Hkv + kv head
-  const int h = row_id % a.Hkv, qi = row_id / a.Hkv;
-
-  float qv[GMAX][EPL];
-#pragma unroll
-  for (int g = 0; g < GMAX; ++g) {
-    const int gg = g < a.G ? g : a.G - 1;
-    const int64_t qoff = ((int64_t)qi * a.Hq + (int64_t)h * a.G + gg) * D + sub * EPL;
-#pragma unroll
-    for (int e = 0; e < EPL; ++e) qv[g][e] = Elem<T>::one(a.q, qoff + e);
-  }
-  // lane `sub` keeps the result of load u = sub % 8 for the heads of parity sub / 8
-  const int my_u = sub & 7, my_par = sub >> 3;
-  float bv[GH][KT]; uint32_t bi[GH][KT];
-#pragma unroll
-  for (int x = 0; x < GH; ++x)
-#pragma unroll
-    for (int t = 0; t < KT; ++t) { bv[x][t] = -__builtin_inff(); bi[x][t] = 0xffffffffu; }
-
-  const int64_t blk_row0 = (int64_t)blockIdx.x * a.rows_per_block;
-  const int64_t left = a.n_mid - blk_row0;
-  const int nrows = left < a.rows_per_block ? (int)left : a.rows_per_block;
-  const int64_t row_bytes = a.kst * (int64_t)sizeof(T);
-  const int64_t tok0 = a.first_tok + blk_row0;
-  const char* kbase = (const char*)a.k +
-      ((int64_t)h * a.ksh + (PAGED ? 0 : tok0) * a.kst) * (int64_t)sizeof(T) + sub * 16;
-  if (PAGED) slice_pages_fill(s_pages, a.pt, a.page_lg, tok0, nrows, kVoteThreads);
-  static_assert(RW <= 64, "a wave's tile lies in at most two pages");
-
-  for (int t = wave * RW; t < nrows; t += kVoteWaves * RW) {
-    u32x4 d[U];
-    TilePages tp;
-    if (PAGED) tp = tile_pages(s_pages, a.page_lg, tok0, tok0 + t);
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      int r = t + u * RPL + grp;
-      r = r < nrows ? r : nrows - 1;                   // tail rows re-read the last row; result dropped
-      const int64_t row = PAGED ? tp.row(r - t) : r;
-      d[u] = __builtin_nontemporal_load((const u32x4*)(kbase + row * row_bytes));
-    }
-    float mine[GH];
-#pragma unroll
-    for (int x = 0; x < GH; ++x) mine[x] = -__builtin_inff();
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      float xk[EPL];
-      Elem<T>::widen(d[u], xk);
-#pragma unroll
-      for (int g = 0; g < GMAX; ++g) {
-        float s = 0.f;
-#pragma unroll
-        for (int e = 0; e < EPL; ++e) s = fmaf(xk[e], qv[g][e], s);
-        s = group_sum<LPR>(s);
-        const bool keep = (my_u == u) && (my_par == (g & 1));
-        mine[g >> 1] = keep ? s : mine[g >> 1];
-      }
-    }
-    const int r = t + my_u * RPL + grp;
-    if (r < nrows) {
-      const uint32_t pos = (uint32_t)(blk_row0 + r);
-#pragma unroll
-      for (int x = 0; x < GH; ++x) {
-        // rows arrive in ascending position per lane: a later equal score never displaces
-        if (2 * x + my_par < a.G && mine[x] > bv[x][KT - 1]) {
-          bv[x][KT - 1] = mine[x]; bi[x][KT - 1] = pos;
-#pragma unroll
-          for (int tt = KT - 1; tt > 0; --tt) {
-            if (bv[x][tt] > bv[x][tt - 1]) {
-              const float fv = bv[x][tt]; bv[x][tt] = bv[x][tt - 1]; bv[x][tt - 1] = fv;
-              const uint32_t iv = bi[x][tt]; bi[x][tt] = bi[x][tt - 1]; bi[x][tt - 1] = iv;
-            }
-          }
-        }
-      }
-    }
-  }
-
-  // wave merge: for each head, KT rounds of arg-max over the lanes' list heads
-#pragma unroll
-  for (int g = 0; g < GMAX; ++g) {
-    const int x = g >> 1;
-    const bool owner = my_par == (g & 1);
-#pragma unroll
-    for (int round = 0; round < KT; ++round) {
-      const uint64_t c = (owner && bi[x][0] != 0xffffffffu) ? composite(bv[x][0], bi[x][0]) : 0ull;
-      const uint64_t best = wave_max_u64(c);
-      if (owner && c == best && best != 0ull) {          // pop: composites are unique (distinct positions)
-#pragma unroll
-        for (int tt = 0; tt + 1 < KT; ++tt) { bv[x][tt] = bv[x][tt + 1]; bi[x][tt] = bi[x][tt + 1]; }
-        bv[x][KT - 1] = -__builtin_inff(); bi[x][KT - 1] = 0xffffffffu;
-      }
-      if (lane == 0) wave_best[wave][g][round] = best;
-    }
-  }
-  __syncthreads();
-  // workgroup merge: wave g takes head g; its lanes hold the 16 waves' KT entries (two per lane at most)
-  if (wave < a.G) {
-    const int g = wave;
-    uint64_t c0 = 0ull, c1 = 0ull;
-    if (lane < kVoteWaves * KT) c0 = wave_best[lane / KT][g][lane % KT];
-    if (lane + 64 < kVoteWaves * KT) c1 = wave_best[(lane + 64) / KT][g][(lane + 64) % KT];
-    uint64_t* out = a.part + (((int64_t)qi * a.Hq + (int64_t)h * a.G + g) * a.n_wg + blockIdx.x) * KT;
-#pragma unroll
-    for (int round = 0; round < KT; ++round) {
-      const uint64_t best = wave_max_u64(c0 > c1 ? c0 : c1);
-      if (c0 == best) c0 = 0ull;
-      if (c1 == best) c1 = 0ull;
-      if (lane == 0) out[round] = best;
-    }
-  }
-}
 
 // ---- the same scan on the matrix cores (bf16, D = 128) ----------------------------------
 // A key tile of 16 rows is the A operand of v_mfma_f32_16x16x32_bf16 and up to 16 (query row,
@@ -760,46 +601,14 @@ __global__ __launch_bounds__(kMergeThreads) void vote_pick_kernel(const uint64_t
   centres_to_spans<kMergeThreads>(win, (int)n_win, sa, sb, wsum, a);
 }
 
-template <typename T, int D, int KT>
-hipError_t scan_launch_gh(const HeadScanArgs& a, dim3 grid, hipStream_t st) {
-  const int gh = (a.G + 1) / 2;
-  if (a.pt) {
-    switch (gh) {
-      case 1: hipLaunchKernelGGL((head_topk_scan_kernel<T, D, KT, 1, true>), grid, dim3(kVoteThreads), 0, st, a); break;
-      case 2: hipLaunchKernelGGL((head_topk_scan_kernel<T, D, KT, 2, true>), grid, dim3(kVoteThreads), 0, st, a); break;
-      case 3: hipLaunchKernelGGL((head_topk_scan_kernel<T, D, KT, 3, true>), grid, dim3(kVoteThreads), 0, st, a); break;
-      default: hipLaunchKernelGGL((head_topk_scan_kernel<T, D, KT, 4, true>), grid, dim3(kVoteThreads), 0, st, a); break;
-    }
-    return hipGetLastError();
-  }
-  switch (gh) {
-    case 1: hipLaunchKernelGGL((head_topk_scan_kernel<T, D, KT, 1>), grid, dim3(kVoteThreads), 0, st, a); break;
-    case 2: hipLaunchKernelGGL((head_topk_scan_kernel<T, D, KT, 2>), grid, dim3(kVoteThreads), 0, st, a); break;
-    case 3: hipLaunchKernelGGL((head_topk_scan_kernel<T, D, KT, 3>), grid, dim3(kVoteThreads), 0, st, a); break;
-    default: hipLaunchKernelGGL((head_topk_scan_kernel<T, D, KT, 4>), grid, dim3(kVoteThreads), 0, st, a); break;
-  }
-  return hipGetLastError();
-}
-template <typename T, int D>
-hipError_t scan_launch_kt(const HeadScanArgs& a, int kt, dim3 grid, hipStream_t st) {
-  switch (kt) {
-    case 1: return scan_launch_gh<T, D, 1>(a, grid, st);
-    case 2: return scan_launch_gh<T, D, 2>(a, grid, st);
-    case 4: return scan_launch_gh<T, D, 4>(a, grid, st);
-    default: return scan_launch_gh<T, D, 8>(a, grid, st);
-  }
-}
-
 }  // namespace
 
 int scan_rows_per_block(int64_t n_mid, int64_t score_rows, int max_rows);
 
 int vote_list_len(int vote_k) { return vote_k <= 1 ? 1 : vote_k <= 2 ? 2 : vote_k <= 4 ? 4 : 8; }
 
-// The streaming path handles 16-lane key rows (bf16 D = 128, fp32 D = 64) and groups of up to 8 heads.
-bool vote_scan_applies(const Plan& pl) {
-  return pl.G <= 8 && ((pl.dtype != kF32 && pl.D == 128) || (pl.dtype == kF32 && pl.D == 64));
-}
+// Every shape the library takes: 16-bit storage with D = 128 on the matrix cores, the rest on the vector ALU.
+bool vote_scan_applies(const Plan& pl) { return pl.G <= 16; }
 
 // Geometry of one scan launch over n_query query rows.
 struct ScanGeom { bool mfma, gemm; int nb, q_per_pass, n_pass, rpb, n_wg; };
@@ -888,7 +697,7 @@ hipError_t launch_head_scan(const Plan& pl, const void* q, int n_query, const vo
     a.ksh = pl.ksh; a.kst = pl.kst; a.n_mid = pl.n_mid; a.first_tok = pl.s_eff;
     a.Hq = pl.Hq; a.Hkv = pl.Hkv; a.G = pl.G;
     a.rows_per_block = g.rpb; a.n_wg = g.n_wg; a.pt = pl.pt; a.page_lg = pl.page_lg;
-    e = scan_launch_kt<float, 64>(a, kt, grid, st);
+    e = launch_head_scan_valu(pl, a, kt, grid, st);
   }
   *n_cand = g.n_wg * kt;
   return e;

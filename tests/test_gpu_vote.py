@@ -48,6 +48,25 @@ CASES = {
                                          top_k=0), B.Vote(4, 40, 16)),
     "f32_g5_chunk": (wl.CONFIGS[1].scaled(n_ctx=5_000, n_q_heads=10, n_kv_heads=2, n_query=6, n_local=100, top_k=0,
                                           max_position=0), B.Vote(3, 11, 64)),
+    # the shapes the matrix-core scan does not take: 16-bit storage with D = 64 (8 lanes per key row), fp32 with
+    # D = 128 (32 lanes per key row); groups wider than one pass over the keys holds lists for
+    "bf16_d64_g4_decode": (wl.CONFIGS[2].scaled(n_ctx=30_011, head_dim=64, n_local=300, top_k=0), B.Vote(4, 20, 16)),
+    "f16_d64_g3_chunk": (wl.CONFIGS[5].scaled(dtype="f16", n_ctx=9_000, head_dim=64, n_query=5, n_local=100, top_k=0,
+                                              max_position=0), B.Vote(8, 30, 4)),
+    "bf16_d64_g8_chunk": (wl.CONFIGS[4].scaled(n_ctx=8_000, head_dim=64, n_kv_heads=4, n_query=17, n_local=64, top_k=0),
+                          B.Vote(2, 40, 9)),
+    "f32_d128_g4_decode": (wl.CONFIGS[1].scaled(n_ctx=20_000, head_dim=128, n_local=200, top_k=0, max_position=0),
+                           B.Vote(4, 20, 16)),
+    "f32_d128_g8_chunk": (wl.CONFIGS[1].scaled(n_ctx=6_000, head_dim=128, n_q_heads=8, n_kv_heads=1, n_query=3, n_local=64,
+                                               top_k=0, max_position=0), B.Vote(8, 12, 8)),
+    "f32_d64_g10_two_passes": (wl.CONFIGS[1].scaled(n_ctx=9_973, n_q_heads=20, n_kv_heads=2, n_local=200, top_k=0,
+                                                    max_position=0), B.Vote(4, 9, 7)),
+    "bf16_d64_g16_three_passes": (wl.CONFIGS[2].scaled(n_ctx=12_000, head_dim=64, n_q_heads=32, n_kv_heads=2, n_local=128,
+                                                       top_k=0), B.Vote(1, 30, 5)),
+    "bf16_d128_g16_decode": (wl.CONFIGS[2].scaled(n_ctx=25_000, n_q_heads=32, n_kv_heads=2, n_local=300, top_k=0),
+                             B.Vote(4, 20, 16)),
+    "bf16_d128_g12_chunk": (wl.CONFIGS[4].scaled(n_ctx=9_000, n_q_heads=24, n_kv_heads=2, n_query=40, n_local=160, top_k=0),
+                            B.Vote(4, 40, 16)),
 }
 
 
