@@ -208,9 +208,12 @@ def test_vote_parameters_are_checked_on_the_host():
     p8k = good(n_sink=32, top_k=0, max_position=8192)
     assert B.vote_workspace_bytes(p8k, B.Vote(4, 127, 32)) > 0
     assert B.vote_workspace_bytes(p8k, B.Vote(4, 128, 32)) == 0          # one more span overflows the window
-    # shapes the streaming vote scan does not cover are refused, not computed some other way
-    assert B.vote_workspace_bytes(good(head_dim=64, top_k=0), B.Vote()) == 0          # bf16 with D = 64
-    assert B.vote_workspace_bytes(good(n_q_heads=72, top_k=0), B.Vote()) == 0         # G = 9
+    # every shape the library takes has a vote path: 16-bit storage with D = 64, fp32 with D = 128, groups of up to 16
+    assert B.vote_workspace_bytes(good(head_dim=64, top_k=0), B.Vote()) > 0
+    assert B.vote_workspace_bytes(good(dtype=B.F32, top_k=0), B.Vote()) > 0
+    assert B.vote_workspace_bytes(good(n_q_heads=72, top_k=0), B.Vote()) > 0          # G = 9
+    assert B.vote_workspace_bytes(good(n_q_heads=128, top_k=0), B.Vote()) > 0         # G = 16
+    assert B.vote_workspace_bytes(good(n_q_heads=136, top_k=0), B.Vote()) == 0        # G = 17: no shape of the library's
     # NULL pointers are reported before anything is launched
     L = B.lib()
     cp, cv = p.c(), B.Vote().c()
