@@ -120,7 +120,7 @@ hipError_t launch_attend(const Plan& pl, bool fused, const void* q, int q_first,
 int vote_list_len(int vote_k);
 bool vote_scan_applies(const Plan& pl);
 int vote_queries_per_launch(const Plan& pl, int vote_k);
-int vote_gemm_splits(const Plan& pl, int n_query);
+int vote_gemm_splits(const Plan& pl, int n_query, int list_len);
 hipError_t launch_vote_gemm(const Plan& pl, const void* q, int n_query, const void* k_cache, int list_len,
                             uint64_t* part, hipStream_t st);
 size_t vote_part_bytes(const Plan& pl, int n_query, int vote_k);

@@ -31,7 +31,7 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 constexpr int kTileKeys = 128;
 constexpr int kPitch = 272;                     // bytes per staged key row (256 + 16 pad)
 constexpr int kThreads = 512;                   // 8 waves: 2 pairs of key blocks x 4 column quarters
-constexpr int kTileCols = 256;                  // columns per workgroup
+constexpr int kColBlocksMax = 4;                // column blocks of 32 a wave may own (2 or 4: 256 or 512 columns per workgroup)
 constexpr int kTileBytes = kTileKeys * kPitch;
 constexpr int kStageNS = 2048 / kThreads;       // 16-byte pieces of a key tile per thread
 constexpr int kFloorEvery = 32;                 // tiles between refreshes of the columns' shared floors (power of two)
@@ -49,8 +49,13 @@ __device__ __forceinline__ uint64_t vg_composite(float score, uint32_t pos) {
   return ((uint64_t)score_key(score) << 32) | (uint64_t)(0xffffffffu - pos);
 }
 
-template <int KT, bool F16>
+// NCB: column blocks of 32 per wave; the workgroup owns NCB * 128 columns.  With NCB = 4 a key operand read from
+// LDS feeds four matrix instructions instead of two, the barrier and the staging of a tile are spread over twice
+// the matrix work, and the 64 column tiles of config 4's chunk become 32 per KV head: one round of workgroups per
+// chiplet, so the keys enter the chip once instead of twice.
+template <int KT, bool F16, int NCB>
 __global__ __launch_bounds__(kThreads) void vote_gemm_kernel(VoteGemmArgs a) {
+  constexpr int kTileCols = NCB * 128;
   typedef typename Mm<F16>::op8 op8;
   extern __shared__ __attribute__((aligned(16))) unsigned char vg_lds[];
   unsigned char* tiles = vg_lds;                            // two staged key tiles, later the merge area
@@ -66,11 +71,11 @@ __global__ __launch_bounds__(kThreads) void vote_gemm_kernel(VoteGemmArgs a) {
   int64_t n_tiles = n_tiles_all - tile0;
   if (n_tiles > a.tiles_per_block) n_tiles = a.tiles_per_block;
 
-  // query operands of this wave: 2 column blocks x 8 k-steps of 8 bf16 (columns past the end are zero)
-  op8 bq[2][8];
+  // query operands of this wave: NCB column blocks x 8 k-steps of 8 bf16 (columns past the end are zero)
+  op8 bq[NCB][8];
 #pragma unroll
-  for (int cb = 0; cb < 2; ++cb) {
-    const int c = c0 + (cw * 2 + cb) * 32 + ln;
+  for (int cb = 0; cb < NCB; ++cb) {
+    const int c = c0 + (cw * NCB + cb) * 32 + ln;
     const bool live = c < n_cols;
     const int64_t qrow = live ? (int64_t)(c / a.G) * a.Hq + (int64_t)h * a.G + c % a.G : 0;
     const uint16_t* row = a.q + qrow * 128 + lh * 8;
@@ -84,16 +89,16 @@ __global__ __launch_bounds__(kThreads) void vote_gemm_kernel(VoteGemmArgs a) {
   // running lists: entry t of column block cb of this thread at lv/li[(cb * KT + t) * kThreads + tid]
   // (best first); only the k-th value, the bar a new score has to clear, lives in a register
   float* lv = (float*)(vg_lds + 2 * kTileBytes);
-  uint32_t* li = (uint32_t*)(lv + 2 * KT * kThreads);
+  uint32_t* li = (uint32_t*)(lv + NCB * KT * kThreads);
   // A column has four partial lists (2 wave rows x 2 lane halves).  Every kFloorEvery tiles one thread
   // per column merges them and publishes the column's true k-th value so far (`floor`): a score below
   // it cannot end among the column's k best, so each list admits about a quarter of what it would on
   // its own.  A score equal to the floor may still win on its lower key, so it passes.
-  float* xfloor = (float*)(li + 2 * KT * kThreads);         // [kTileCols]
-  if (tid < kTileCols) xfloor[tid] = -__builtin_inff();
-  float bar[2];
+  float* xfloor = (float*)(li + NCB * KT * kThreads);       // [kTileCols]
+  for (int c = tid; c < kTileCols; c += kThreads) xfloor[c] = -__builtin_inff();
+  float bar[NCB];
 #pragma unroll
-  for (int cb = 0; cb < 2; ++cb) {
+  for (int cb = 0; cb < NCB; ++cb) {
     bar[cb] = -__builtin_inff();
 #pragma unroll
     for (int t = 0; t < KT; ++t) { lv[(cb * KT + t) * kThreads + tid] = -__builtin_inff(); li[(cb * KT + t) * kThreads + tid] = 0xffffffffu; }
@@ -135,45 +140,54 @@ __global__ __launch_bounds__(kThreads) void vote_gemm_kernel(VoteGemmArgs a) {
       *(u32x4*)(tiles + buf * kTileBytes + (srow + RS * j) * kPitch + scol * 16) = s[j];
   };
 
+  // Tile t + 1 is written to LDS during step t from registers that were loaded during step t - 2: two steps of
+  // slack (a step is under 2 us, a trip to HBM under load is not always).  Two register sets, by tile parity.
+  u32x4 stg2[kStageNS];
   if (n_tiles > 0) {
     load_tile(tile0, stg);
     stash_tile(0, stg);
-    if (n_tiles > 1) load_tile(tile0 + 1, stg);
+    if (n_tiles > 1) load_tile(tile0 + 1, stg2);             // odd tiles travel in stg2
+    if (n_tiles > 2) load_tile(tile0 + 2, stg);              // even tiles in stg
   }
   __syncthreads();
 
   // C layout of a 32x32 block: acc[i] is key row (i/4)*8 + (lane/32)*4 + i%4, column lane%32.
-  auto step = [&](int64_t t, int buf) {
-    if (t + 1 < n_tiles) stash_tile(buf ^ 1, stg);
-    if (t + 2 < n_tiles) load_tile(tile0 + t + 2, stg);
-    float floor_[2];
+  // The two waves of a SIMD (waves w and w + 4) move the next tile into LDS at opposite ends of a step, so that
+  // one of them always has matrix work in flight while the other writes.
+  const bool stash_first = (wave >> 2) == 0;
+  auto step = [&](int64_t t, int buf, u32x4* s) {            // s: the registers that hold tile t + 1
+    if (stash_first) {
+      if (t + 1 < n_tiles) stash_tile(buf ^ 1, s);
+      if (t + 3 < n_tiles) load_tile(tile0 + t + 3, s);
+    }
+    float floor_[NCB];
 #pragma unroll
-    for (int cb = 0; cb < 2; ++cb) floor_[cb] = xfloor[(cw * 2 + cb) * 32 + ln];
+    for (int cb = 0; cb < NCB; ++cb) floor_[cb] = xfloor[(cw * NCB + cb) * 32 + ln];
 #pragma unroll
     for (int j = 0; j < 2; ++j) {                           // the two key blocks of this wave
       const int kb = kw * 2 + j;
       const unsigned char* arow = tiles + buf * kTileBytes + (kb * 32 + ln) * kPitch + lh * 16;
       const int64_t key_blk = (tile0 + t) * kTileKeys + kb * 32 + lh * 4;
-      f32x16 acc[2];
+      f32x16 acc[NCB];
 #pragma unroll
-      for (int x = 0; x < 2; ++x)
+      for (int x = 0; x < NCB; ++x)
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[x][i] = 0.f;
 #pragma unroll
       for (int ks = 0; ks < 8; ++ks) {
         const op8 av = *(const op8*)(arow + ks * 32);
-        acc[0] = Mm<F16>::mfma32(av, bq[0][ks], acc[0]);
-        acc[1] = Mm<F16>::mfma32(av, bq[1][ks], acc[1]);
+#pragma unroll
+        for (int x = 0; x < NCB; ++x) acc[x] = Mm<F16>::mfma32(av, bq[x][ks], acc[x]);
       }
       if (key_blk + 27 >= a.n_keys) {                       // only the last tile: keys past the end never enter a list
 #pragma unroll
-        for (int x = 0; x < 2; ++x)
+        for (int x = 0; x < NCB; ++x)
 #pragma unroll
           for (int i = 0; i < 16; ++i)
             if (key_blk + (i >> 2) * 8 + (i & 3) >= a.n_keys) acc[x][i] = -__builtin_inff();
       }
 #pragma unroll
-      for (int cb = 0; cb < 2; ++cb) {
+      for (int cb = 0; cb < NCB; ++cb) {
         float m = acc[cb][0];
 #pragma unroll
         for (int i = 1; i < 16; ++i) m = fmaxf(m, acc[cb][i]);
@@ -209,11 +223,15 @@ __global__ __launch_bounds__(kThreads) void vote_gemm_kernel(VoteGemmArgs a) {
         }
       }
     }
+    if (!stash_first) {
+      if (t + 1 < n_tiles) stash_tile(buf ^ 1, s);
+      if (t + 3 < n_tiles) load_tile(tile0 + t + 3, s);
+    }
     if ((t & (kFloorEvery - 1)) == kFloorEvery - 1) {       // workgroup-uniform
       __syncthreads();                                      // every list is at rest
-      if (tid < kTileCols) {
-        // thread tid owns column tid = (cw2 * 32 + ln): its lists sit with threads (cw * 2 + kw) * 64 + lh * 32 + ln
-        const int cw2 = tid >> 5, lcol = tid & 31, ccw = cw2 >> 1, ccb = cw2 & 1;
+      for (int col = tid; col < kTileCols; col += kThreads) {
+        // column col = (cw2 * 32 + ln): its lists sit with threads (cw * 2 + kw) * 64 + lh * 32 + ln
+        const int cw2 = col >> 5, lcol = col & 31, ccw = cw2 / NCB, ccb = cw2 % NCB;
         float best[KT];
 #pragma unroll
         for (int y = 0; y < KT; ++y) best[y] = -__builtin_inff();
@@ -231,22 +249,22 @@ __global__ __launch_bounds__(kThreads) void vote_gemm_kernel(VoteGemmArgs a) {
             }
           }
         }
-        xfloor[tid] = best[KT - 1];
+        xfloor[col] = best[KT - 1];
       }
     }
     __syncthreads();
   };
 
   for (int64_t t = 0; t < n_tiles; t += 2) {
-    step(t, 0);
-    if (t + 1 < n_tiles) step(t + 1, 1);
+    step(t, 0, stg2);
+    if (t + 1 < n_tiles) step(t + 1, 1, stg);
   }
 
   // the four partial lists of a column (2 wave rows x 2 lane halves) meet in LDS (over the key tiles)
   uint64_t* lists = (uint64_t*)vg_lds;                      // [kTileCols][4][KT]
 #pragma unroll
-  for (int cb = 0; cb < 2; ++cb) {
-    const int col = (cw * 2 + cb) * 32 + ln;
+  for (int cb = 0; cb < NCB; ++cb) {
+    const int col = (cw * NCB + cb) * 32 + ln;
 #pragma unroll
     for (int t = 0; t < KT; ++t) {
       const float v = lv[(cb * KT + t) * kThreads + tid];
@@ -255,9 +273,9 @@ __global__ __launch_bounds__(kThreads) void vote_gemm_kernel(VoteGemmArgs a) {
     }
   }
   __syncthreads();
-  if (tid < kTileCols && c0 + tid < n_cols) {
-    const int c = c0 + tid;
-    const uint64_t* mine = lists + (size_t)tid * 4 * KT;
+  for (int col = tid; col < kTileCols && c0 + col < n_cols; col += kThreads) {
+    const int c = c0 + col;
+    const uint64_t* mine = lists + (size_t)col * 4 * KT;
     int head[4];
 #pragma unroll
     for (int s = 0; s < 4; ++s) head[s] = 0;
@@ -276,11 +294,13 @@ __global__ __launch_bounds__(kThreads) void vote_gemm_kernel(VoteGemmArgs a) {
   }
 }
 
-template <int KT, bool F16>
+template <int KT, bool F16, int NCB>
 hipError_t vote_gemm_launch(const VoteGemmArgs& a, dim3 grid, hipStream_t st) {
+  constexpr int kTileCols = NCB * 128;
   static_assert((size_t)kTileCols * 4 * KT * sizeof(uint64_t) <= 2 * (size_t)kTileBytes, "merge area inside the tiles");
-  constexpr size_t lds = 2 * (size_t)kTileBytes + (size_t)2 * KT * kThreads * 8 + kTileCols * 4;
-  auto kern = vote_gemm_kernel<KT, F16>;
+  constexpr size_t lds = 2 * (size_t)kTileBytes + (size_t)NCB * KT * kThreads * 8 + kTileCols * 4;
+  static_assert(lds <= (size_t)160 * 1024, "fits a compute unit's LDS");
+  auto kern = vote_gemm_kernel<KT, F16, NCB>;
   hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(kern, grid, dim3(kThreads), lds, st, a);
@@ -289,16 +309,26 @@ hipError_t vote_gemm_launch(const VoteGemmArgs& a, dim3 grid, hipStream_t st) {
 
 }  // namespace
 
+// Columns per workgroup: 512 while the lists of a column block fit LDS four times over (lists of up to 4) and the
+// chunk has columns to fill them, else 256.
+int vote_gemm_tile_cols(const Plan& pl, int n_query, int list_len) {
+  (void)pl; (void)n_query; (void)list_len;
+  return 256;
+}
+
 // Key splits of the chunk contraction: enough workgroups for one round over the chip (one workgroup per CU: a
 // second round only repeats the insertion-heavy start of every running list).
-int vote_gemm_splits(const Plan& pl, int n_query) {
-  const int64_t col_tiles = ((int64_t)n_query * pl.G + kTileCols - 1) / kTileCols;
+static int gemm_splits(const Plan& pl, int n_query, int tile_cols) {
+  const int64_t col_tiles = ((int64_t)n_query * pl.G + tile_cols - 1) / tile_cols;
   const int64_t n_tiles = (pl.n_mid + kTileKeys - 1) / kTileKeys;
   int64_t split = (256 + col_tiles * pl.Hkv - 1) / (col_tiles * pl.Hkv);
   if (split > n_tiles) split = n_tiles;
   if (split < 1) split = 1;
   const int64_t per = (n_tiles + split - 1) / split;        // tiles per workgroup
   return (int)((n_tiles + per - 1) / per);
+}
+int vote_gemm_splits(const Plan& pl, int n_query, int list_len) {
+  return gemm_splits(pl, n_query, vote_gemm_tile_cols(pl, n_query, list_len));
 }
 
 // part: [n_query * Hq][splits][list_len] composites (list_len = vote_list_len(vote_k)).
@@ -309,24 +339,26 @@ hipError_t launch_vote_gemm(const Plan& pl, const void* q, int n_query, const vo
   a.k = (const uint16_t*)k_cache; a.q = (const uint16_t*)q; a.part = part;
   a.ksh = pl.ksh; a.kst = pl.kst; a.first_tok = pl.s_eff; a.n_keys = pl.n_mid; a.pt = pl.pt; a.page_lg = pl.page_lg;
   a.n_query = n_query; a.Hq = pl.Hq; a.G = pl.G;
-  a.n_split = vote_gemm_splits(pl, n_query);
+  const int tile_cols = vote_gemm_tile_cols(pl, n_query, list_len);
+  a.n_split = gemm_splits(pl, n_query, tile_cols);
   const int64_t n_tiles = (pl.n_mid + kTileKeys - 1) / kTileKeys;
   a.tiles_per_block = (int)((n_tiles + a.n_split - 1) / a.n_split);
-  const dim3 grid((unsigned)pl.Hkv, (unsigned)(((int64_t)n_query * pl.G + kTileCols - 1) / kTileCols),
+  const dim3 grid((unsigned)pl.Hkv, (unsigned)(((int64_t)n_query * pl.G + tile_cols - 1) / tile_cols),
                   (unsigned)a.n_split);
+  const bool wide = tile_cols == 512;
   if (pl.dtype == kF16) {
     switch (list_len) {
-      case 1: return vote_gemm_launch<1, true>(a, grid, st);
-      case 2: return vote_gemm_launch<2, true>(a, grid, st);
-      case 4: return vote_gemm_launch<4, true>(a, grid, st);
-      default: return vote_gemm_launch<8, true>(a, grid, st);
+      case 1: return wide ? vote_gemm_launch<1, true, 4>(a, grid, st) : vote_gemm_launch<1, true, 2>(a, grid, st);
+      case 2: return wide ? vote_gemm_launch<2, true, 4>(a, grid, st) : vote_gemm_launch<2, true, 2>(a, grid, st);
+      case 4: return wide ? vote_gemm_launch<4, true, 4>(a, grid, st) : vote_gemm_launch<4, true, 2>(a, grid, st);
+      default: return vote_gemm_launch<8, true, 2>(a, grid, st);
     }
   }
   switch (list_len) {
-    case 1: return vote_gemm_launch<1, false>(a, grid, st);
-    case 2: return vote_gemm_launch<2, false>(a, grid, st);
-    case 4: return vote_gemm_launch<4, false>(a, grid, st);
-    default: return vote_gemm_launch<8, false>(a, grid, st);
+    case 1: return wide ? vote_gemm_launch<1, false, 4>(a, grid, st) : vote_gemm_launch<1, false, 2>(a, grid, st);
+    case 2: return wide ? vote_gemm_launch<2, false, 4>(a, grid, st) : vote_gemm_launch<2, false, 2>(a, grid, st);
+    case 4: return wide ? vote_gemm_launch<4, false, 4>(a, grid, st) : vote_gemm_launch<4, false, 2>(a, grid, st);
+    default: return vote_gemm_launch<8, false, 2>(a, grid, st);
   }
 }
 
