@@ -24,6 +24,9 @@ FLAGS = [
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-function",
 ]
+# vote_gemm.hip runs one wave per SIMD with more than 256 registers: there the compiler would put every
+# matrix result into the accumulation half of the register file and copy it out for the vector unit.
+FILE_FLAGS = {"vote_gemm.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]}
 
 
 def _stale(src: str, obj: str) -> bool:
@@ -34,7 +37,7 @@ def _stale(src: str, obj: str) -> bool:
 
 
 def _compile(src: str, obj: str, verbose: bool) -> None:
-    cmd = [HIPCC, *FLAGS, "-c", "-o", obj, src]
+    cmd = [HIPCC, *FLAGS, *FILE_FLAGS.get(os.path.basename(src), []), "-c", "-o", obj, src]
     if verbose:
         print(" ".join(cmd), flush=True)
     r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)

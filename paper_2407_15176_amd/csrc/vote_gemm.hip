@@ -7,34 +7,45 @@
 // unlike the group-sum contraction there is no hi/lo split and the executed matrix work
 // equals the algorithmic 2 * M * Hq * N_mid * D.
 //
-// Tiling: a workgroup of 8 waves owns 256 columns ((query row, head) pairs, query-major) of
-// one KV head and walks key tiles of 128 rows staged through LDS (two buffers, 272-byte row
-// pitch, the tile after next travelling through registers).  Keys are the A operand, so a
-// lane of a 32x32 block holds ONE column and 16 keys: the running top-k list of a column
-// belongs to the lane that owns it (the list in LDS, its k-th value in a register), and a
-// tile costs a maximum over 16 scores and one comparison unless a score enters the list.
-// Wave (kw, cw) takes the key blocks 2kw, 2kw + 1 of the tile and the two column blocks of
-// quarter cw (their 2 x 8 query operands, 64 VGPRs, stay in registers).  The four partial
-// lists of a column (2 wave rows x 2 lane halves) are merged through LDS
-// at the end.  With few query rows the keys are also split over blockIdx.z so that the chip
-// is filled; every workgroup writes one partial list per column and head_topk_merge (the
-// same kernel that closes the decode scan) picks the best k.
+// Tiling: a workgroup of 8 waves (two per SIMD) owns 256 columns ((query row, head) pairs,
+// query-major) of one KV head and walks key tiles of 128 rows staged in LDS (four buffers,
+// 272-byte row pitch, filled by loads that go from memory straight into LDS).  Keys are the A
+// operand, so a lane of a 32x32 block holds ONE column and 16 keys: the running top-k list of a
+// column belongs to the lane that owns it (in registers), and a block costs a maximum over 16
+// scores and one comparison unless a score enters the list.  Wave cw takes column block cw (its
+// 8 query operands stay in registers) and all four key blocks of a tile, one after the other:
+// while the matrix pipe works on block j + 1 the wave filters the scores of block j (two sets of
+// accumulators), and the key operands of block j + 2 travel from LDS into registers; the first
+// block of tile t + 1 is in the pipe before the workgroup meets at the barrier that ends step t.
+// The second wave of a SIMD covers what this leaves open: an insertion into a list (rare, long,
+// divergent) and the wait at the barrier.  The two partial lists of a column (the lane halves)
+// are merged through LDS at the end.  With few query rows the keys are also split over
+// blockIdx.z so that the chip is filled; every workgroup writes one partial list per column and
+// head_topk_merge (the same kernel that closes the decode scan) picks the best k.
 // blockIdx.x is the KV head: with 8 heads every XCD streams one head's keys through its L2.
+//
+// Measured on the 4096-row chunk of 4-head groups against 256 K keys (8.66 TFLOP, times of this
+// kernel alone): the matrix instructions with nothing around them run at 1790 TFLOP/s on random
+// operands (the chip's power limit, 0.72 of the 2.5 PFLOP/s peak: 4.8 ms); with the operand reads
+// from LDS 6.0 ms; with the tile loads and the barrier 6.5 ms; with the filter and the lists
+// 7.2 ms.  Other shapes tried, same work: one wave per SIMD with two column blocks (half the LDS
+// reads, 5.6 ms for matrix work + reads) ends at 9.3 ms because nothing covers an insertion or
+// the barrier; four column blocks per wave, or two with two waves per SIMD, do not fit the
+// register file; key tiles that travel through registers (the compiler's count of loads in
+// flight makes a step wait for the tile requested one step ago, not two) 7.9 ms.
 #include "common.hpp"
+
+#include <type_traits>
 
 namespace reattn {
 namespace {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-
 constexpr int kTileKeys = 128;
 constexpr int kPitch = 272;                     // bytes per staged key row (256 + 16 pad)
-constexpr int kThreads = 512;                   // 8 waves: 2 pairs of key blocks x 4 column quarters
-constexpr int kColBlocksMax = 4;                // column blocks of 32 a wave may own (2 or 4: 256 or 512 columns per workgroup)
+constexpr int kBufs = 4;                        // staged key tiles (a power of two)
 constexpr int kTileBytes = kTileKeys * kPitch;
-constexpr int kStageNS = 2048 / kThreads;       // 16-byte pieces of a key tile per thread
-constexpr int kFloorEvery = 32;                 // tiles between refreshes of the columns' shared floors (power of two)
+constexpr int kFloorEvery = 16;                 // tiles between refreshes of the columns' shared floors (power of two)
+constexpr int kFloorEach = 64, kFloorFourth = 512;   // ... every tile before the first, every fourth before the second
 
 struct VoteGemmArgs {
   const uint16_t* k;        // key cache (bf16 bits)
@@ -49,19 +60,20 @@ __device__ __forceinline__ uint64_t vg_composite(float score, uint32_t pos) {
   return ((uint64_t)score_key(score) << 32) | (uint64_t)(0xffffffffu - pos);
 }
 
-// NCB: column blocks of 32 per wave; the workgroup owns NCB * 128 columns.  With NCB = 4 a key operand read from
-// LDS feeds four matrix instructions instead of two, the barrier and the staging of a tile are spread over twice
-// the matrix work, and the 64 column tiles of config 4's chunk become 32 per KV head: one round of workgroups per
-// chiplet, so the keys enter the chip once instead of twice.
-template <int KT, bool F16, int NCB>
-__global__ __launch_bounds__(kThreads) void vote_gemm_kernel(VoteGemmArgs a) {
-  constexpr int kTileCols = NCB * 128;
+// NCB: column blocks of 32 per wave; NW: waves of the workgroup (8: two per SIMD with half the register file each;
+// 4: one per SIMD with all of it).  The workgroup owns NCB * 32 * NW columns; every wave walks all four key blocks
+// of a tile for its own NCB column blocks.  The library launches NCB = 1, NW = 8.
+template <int KT, bool F16, int NCB, int NW>
+__global__ __launch_bounds__(64 * NW) void vote_gemm_kernel(VoteGemmArgs a) {
+  constexpr int kTileCols = NCB * 32 * NW;
+  constexpr int kThreads = 64 * NW;
+  static_assert(NW == 4 || NW == 8, "one or two waves per SIMD");
   typedef typename Mm<F16>::op8 op8;
+  typedef mm_f32x16 f32x16;
   extern __shared__ __attribute__((aligned(16))) unsigned char vg_lds[];
-  unsigned char* tiles = vg_lds;                            // two staged key tiles, later the merge area
+  unsigned char* tiles = vg_lds;                            // kBufs staged key tiles, later the merge area
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int kw = wave & 1, cw = wave >> 1;
+  const int tid = threadIdx.x, lane = tid & 63, cw = tid >> 6;
   const int ln = lane & 31, lh = lane >> 5;
   const int h = blockIdx.x;
   const int c0 = blockIdx.y * kTileCols;
@@ -84,163 +96,201 @@ __global__ __launch_bounds__(kThreads) void vote_gemm_kernel(VoteGemmArgs a) {
       u32x4 w = *(const u32x4*)(row + ks * 16);
       if (!live) w = u32x4{0u, 0u, 0u, 0u};
       bq[cb][ks] = __builtin_bit_cast(op8, w);
+      // the query operands stay in the accumulation half of the register file (a matrix instruction reads
+      // either half), which leaves the other half to the scores and the key tiles in flight
+      if (NW == 4) asm volatile("" : "+a"(bq[cb][ks]));
     }
   }
-  // running lists: entry t of column block cb of this thread at lv/li[(cb * KT + t) * kThreads + tid]
-  // (best first); only the k-th value, the bar a new score has to clear, lives in a register
-  float* lv = (float*)(vg_lds + 2 * kTileBytes);
-  uint32_t* li = (uint32_t*)(lv + NCB * KT * kThreads);
-  // A column has four partial lists (2 wave rows x 2 lane halves).  Every kFloorEvery tiles one thread
-  // per column merges them and publishes the column's true k-th value so far (`floor`): a score below
-  // it cannot end among the column's k best, so each list admits about a quarter of what it would on
-  // its own.  A score equal to the floor may still win on its lower key, so it passes.
-  float* xfloor = (float*)(li + NCB * KT * kThreads);       // [kTileCols]
+  // running lists: KT best (score, key) pairs of each of this lane's NCB columns over the keys this lane has
+  // seen, best first, in registers; lv[cb][KT - 1] is the bar a new score has to clear
+  float lv[NCB][KT];
+  uint32_t li[NCB][KT];
+#pragma unroll
+  for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+    for (int y = 0; y < KT; ++y) { lv[cb][y] = -__builtin_inff(); li[cb][y] = 0xffffffffu; }
+  // A column has two partial lists (the lane halves).  Every kFloorEvery tiles (more often early on) the lists' scores meet in LDS
+  // (lvx), one thread per column merges them and publishes the column's true k-th value so far (`floor`):
+  // a score below it cannot end among the column's k best, so each list admits about half of what it would
+  // on its own.  A score equal to the floor may still win on its lower key, so it passes.
+  float* lvx = (float*)(vg_lds + kBufs * kTileBytes);       // [NCB * KT][kThreads]
+  float* xfloor = lvx + NCB * KT * kThreads;                // [kTileCols]
   for (int c = tid; c < kTileCols; c += kThreads) xfloor[c] = -__builtin_inff();
-  float bar[NCB];
-#pragma unroll
-  for (int cb = 0; cb < NCB; ++cb) {
-    bar[cb] = -__builtin_inff();
-#pragma unroll
-    for (int t = 0; t < KT; ++t) { lv[(cb * KT + t) * kThreads + tid] = -__builtin_inff(); li[(cb * KT + t) * kThreads + tid] = 0xffffffffu; }
-  }
 
-  // staging: thread t moves kStageNS x 16 bytes of the 128 x 256-byte key tile (rows t/16 + 32j,
-  // piece t%16); tile t + 2 is requested right after tile t + 1 went from the same registers to LDS
-  constexpr int RS = kThreads / 16;
-  const int srow = tid >> 4, scol = tid & 15;
+  // staging: key tiles travel from memory straight into LDS (global_load_lds_dwordx4: lane L of a wave puts its
+  // 16 bytes at m0 + 16 L, no register in between), three tiles ahead of the matrix work: step t requests tile
+  // t + 3 into the buffer tile t - 1 has left, and the barrier that ends step t + 1 is the first that needs it
+  // (two steps of slack: a step is under 2 us, a trip to memory under load is not always).  A tile is 128 rows
+  // of 17 slots of 16 bytes (16 pieces of the row + one pad: the 272-byte pitch keeps the operand reads of 32
+  // rows off each other's banks); the pad slot receives a copy of the last piece.  Its 2176 slots are 34 wave
+  // loads of 64; wave w of W issues loads W i + w, i < 32 / W, and, so that every wave counts the same number of loads in
+  // flight per tile, load 32 + (w & 1): the two loads issued twice write the same bytes twice.
+  constexpr int kDmaEach = 32 / NW, kDma = kDmaEach + 1;
   const int64_t row_bytes = a.kst * 2;
-  const char* kbase = (const char*)(a.k + (int64_t)h * a.ksh + a.first_tok * a.kst) + scol * 16;
-  const char* next = kbase + (tile0 * kTileKeys + srow) * row_bytes;
-  u32x4 stg[kStageNS];
-  auto load_tile = [&](int64_t tile, u32x4* s) {
-    if (a.pt) {                                              // paged cache: every row through the page table
-      const char* hbase = (const char*)(a.k + (int64_t)h * a.ksh) + scol * 16;
+  const char* khead = (const char*)(a.k + (int64_t)h * a.ksh);
+  const char* kmid = khead + a.first_tok * row_bytes;
+  uint32_t voff[kDma];                                      // row * row_bytes + piece * 16 of this lane's slot of load i
 #pragma unroll
-      for (int j = 0; j < kStageNS; ++j) {
-        int64_t key = tile * kTileKeys + srow + RS * j;
-        if (key >= a.n_keys) key = a.n_keys - 1;
-        s[j] = *(const u32x4*)(hbase + paged_row(a.pt, a.page_lg, a.first_tok + key) * row_bytes);
-      }
-    } else if ((tile + 1) * kTileKeys <= a.n_keys) {         // every tile but a ragged last one
+  for (int i = 0; i < kDma; ++i) {
+    const int slot = (i < kDmaEach ? i * NW + cw : 32 + (cw & 1)) * 64 + lane;
+    const int row = slot / 17, piece = slot % 17;
+    voff[i] = (uint32_t)(row * row_bytes) + (uint32_t)(piece < 16 ? piece : 15) * 16u;
+  }
+  const uint32_t lds_tiles = (uint32_t)(uintptr_t)tiles;
+  auto dma_dst = [&](int buf, int i) -> uint32_t {           // LDS byte address of load i of this wave (wave-uniform)
+    return (uint32_t)__builtin_amdgcn_readfirstlane((int)(lds_tiles + (uint32_t)buf * kTileBytes + (uint32_t)(i < kDmaEach ? i * NW + cw : 32 + (cw & 1)) * 1024u));
+  };
+  // plain: a tile that is whole and reached without a page table (a compile-time yes skips both questions)
+  auto dma_tile = [&](auto plain, int64_t tile, int buf) __attribute__((always_inline)) {
+    if (decltype(plain)::value || (!a.pt && (tile + 1) * kTileKeys <= a.n_keys)) {
+      const char* base = kmid + tile * kTileKeys * row_bytes;      // workgroup-uniform
 #pragma unroll
-      for (int j = 0; j < kStageNS; ++j) s[j] = *(const u32x4*)(next + (int64_t)(RS * j) * row_bytes);
-    } else {
+      for (int i = 0; i < kDma; ++i)
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                     :: "s"(dma_dst(buf, i)), "v"(voff[i]), "s"(base) : "memory");
+    } else {                                                 // through the page table, or a ragged last tile
 #pragma unroll
-      for (int j = 0; j < kStageNS; ++j) {
-        int64_t key = tile * kTileKeys + srow + RS * j;
+      for (int i = 0; i < kDma; ++i) {
+        const int slot = (i < kDmaEach ? i * NW + cw : 32 + (cw & 1)) * 64 + lane;
+        const int row = slot / 17, piece = slot % 17;
+        int64_t key = tile * kTileKeys + row;
         if (key >= a.n_keys) key = a.n_keys - 1;             // rows past the end repeat the last key; their scores are dropped
-        s[j] = *(const u32x4*)(kbase + key * row_bytes);
+        const int64_t mrow = a.pt ? paged_row(a.pt, a.page_lg, a.first_tok + key) : a.first_tok + key;
+        const char* src = khead + mrow * row_bytes + (piece < 16 ? piece : 15) * 16;
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                     :: "s"(dma_dst(buf, i)), "v"(src) : "memory");
       }
     }
-    next += (int64_t)kTileKeys * row_bytes;
   };
-  auto stash_tile = [&](int buf, const u32x4* s) {
-#pragma unroll
-    for (int j = 0; j < kStageNS; ++j)
-      *(u32x4*)(tiles + buf * kTileBytes + (srow + RS * j) * kPitch + scol * 16) = s[j];
-  };
-
-  // Tile t + 1 is written to LDS during step t from registers that were loaded during step t - 2: two steps of
-  // slack (a step is under 2 us, a trip to HBM under load is not always).  Two register sets, by tile parity.
-  u32x4 stg2[kStageNS];
-  if (n_tiles > 0) {
-    load_tile(tile0, stg);
-    stash_tile(0, stg);
-    if (n_tiles > 1) load_tile(tile0 + 1, stg2);             // odd tiles travel in stg2
-    if (n_tiles > 2) load_tile(tile0 + 2, stg);              // even tiles in stg
-  }
+  constexpr std::true_type yes{};
+  constexpr std::false_type no{};
+  for (int i = 0; i < 3 && i < n_tiles; ++i) dma_tile(no, tile0 + i, i);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
 
   // C layout of a 32x32 block: acc[i] is key row (i/4)*8 + (lane/32)*4 + i%4, column lane%32.
-  // The two waves of a SIMD (waves w and w + 4) move the next tile into LDS at opposite ends of a step, so that
-  // one of them always has matrix work in flight while the other writes.
-  const bool stash_first = (wave >> 2) == 0;
-  auto step = [&](int64_t t, int buf, u32x4* s) {            // s: the registers that hold tile t + 1
-    if (stash_first) {
-      if (t + 1 < n_tiles) stash_tile(buf ^ 1, s);
-      if (t + 3 < n_tiles) load_tile(tile0 + t + 3, s);
+  f32x16 accA[NCB], accB[NCB];
+  op8 av[8];
+  auto rows_of = [&](int buf, int j) -> const unsigned char* {
+    return tiles + buf * kTileBytes + (j * 32 + ln) * kPitch + lh * 16;
+  };
+  // acc <- keys in av x queries; av <- the rows at `refill` (refills: a compile-time yes or no)
+  auto contract = [&](f32x16 (&acc)[NCB], auto refills, const unsigned char* refill) __attribute__((always_inline)) {
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+#pragma unroll
+      for (int x = 0; x < NCB; ++x) {
+        if (ks == 0) {
+          f32x16 z;
+#pragma unroll
+          for (int i = 0; i < 16; ++i) z[i] = 0.f;
+          acc[x] = Mm<F16>::mfma32(av[0], bq[x][0], z);
+        } else {
+          acc[x] = Mm<F16>::mfma32(av[ks], bq[x][ks], acc[x]);
+        }
+      }
+      if (decltype(refills)::value) av[ks] = *(const op8*)(refill + ks * 32);
     }
-    float floor_[NCB];
+    // the matrix instructions are issued here, ahead of the filter that follows in program order, and their
+    // results live in the registers the vector unit reads
 #pragma unroll
-    for (int cb = 0; cb < NCB; ++cb) floor_[cb] = xfloor[(cw * NCB + cb) * 32 + ln];
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {                           // the two key blocks of this wave
-      const int kb = kw * 2 + j;
-      const unsigned char* arow = tiles + buf * kTileBytes + (kb * 32 + ln) * kPitch + lh * 16;
-      const int64_t key_blk = (tile0 + t) * kTileKeys + kb * 32 + lh * 4;
-      f32x16 acc[NCB];
+    for (int x = 0; x < NCB; ++x) asm volatile("" : "+v"(acc[x]));
+  };
+  float floor_[NCB];
+  // the scores of one key block against the running lists; key_blk: key of acc[0] of this lane
+  auto filter = [&](auto ragged, f32x16 (&acc)[NCB], int64_t key_blk) __attribute__((always_inline)) {
+    if (decltype(ragged)::value) {                          // only a ragged last tile: keys past the end never enter a list
 #pragma unroll
       for (int x = 0; x < NCB; ++x)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) acc[x][i] = 0.f;
+        for (int i = 0; i < 16; ++i)
+          if (key_blk + (i >> 2) * 8 + (i & 3) >= a.n_keys) acc[x][i] = -__builtin_inff();
+    }
+    float m[NCB];
+    bool enters = false;
 #pragma unroll
-      for (int ks = 0; ks < 8; ++ks) {
-        const op8 av = *(const op8*)(arow + ks * 32);
+    for (int cb = 0; cb < NCB; ++cb) {
+      m[cb] = acc[cb][0];
 #pragma unroll
-        for (int x = 0; x < NCB; ++x) acc[x] = Mm<F16>::mfma32(av, bq[x][ks], acc[x]);
-      }
-      if (key_blk + 27 >= a.n_keys) {                       // only the last tile: keys past the end never enter a list
+      for (int i = 1; i < 16; ++i) m[cb] = fmaxf(m[cb], acc[cb][i]);
+      enters |= m[cb] > lv[cb][KT - 1] && m[cb] >= floor_[cb];
+    }
+    // A score enters a list rarely (the list's k-th value climbs quickly): one question per block, and then
+    // usually one score per lane: take the lane's largest remaining score, insert, strike it out, again.
+    // Largest first and, among equals, lowest key first: an equal score never displaces.
+    if (!__any(enters)) return;
 #pragma unroll
-        for (int x = 0; x < NCB; ++x)
+    for (int cb = 0; cb < NCB; ++cb) {
+      while (__any(m[cb] > lv[cb][KT - 1] && m[cb] >= floor_[cb])) {
+        if (m[cb] > lv[cb][KT - 1] && m[cb] >= floor_[cb]) {
+          int at = 15;
 #pragma unroll
-          for (int i = 0; i < 16; ++i)
-            if (key_blk + (i >> 2) * 8 + (i & 3) >= a.n_keys) acc[x][i] = -__builtin_inff();
-      }
+          for (int i = 14; i >= 0; --i) at = acc[cb][i] == m[cb] ? i : at;   // lowest i holding the maximum
+          const uint32_t key = (uint32_t)(key_blk + (at >> 2) * 8 + (at & 3));
+          // entries at least as large stay above the new one (their keys are lower)
+          bool above[KT];
 #pragma unroll
-      for (int cb = 0; cb < NCB; ++cb) {
-        float m = acc[cb][0];
+          for (int y = 0; y < KT; ++y) above[y] = lv[cb][y] >= m[cb];
 #pragma unroll
-        for (int i = 1; i < 16; ++i) m = fmaxf(m, acc[cb][i]);
-        // A score enters a list rarely (the list's k-th value climbs quickly), and then usually
-        // one per lane: take the lane's largest remaining score, insert, strike it out, again.
-        // Largest first and, among equals, lowest key first: an equal score never displaces.
-        while (__any(m > bar[cb] && m >= floor_[cb])) {
-          if (m > bar[cb] && m >= floor_[cb]) {
-            int at = 15;
-#pragma unroll
-            for (int i = 14; i >= 0; --i) at = acc[cb][i] == m ? i : at;     // lowest i holding the maximum
-            float v[KT]; uint32_t id[KT];
-#pragma unroll
-            for (int y = 0; y < KT - 1; ++y) { v[y] = lv[(cb * KT + y) * kThreads + tid]; id[y] = li[(cb * KT + y) * kThreads + tid]; }
-            v[KT - 1] = m; id[KT - 1] = (uint32_t)(key_blk + (at >> 2) * 8 + (at & 3));
-#pragma unroll
-            for (int y = KT - 1; y > 0; --y) {
-              if (v[y] > v[y - 1]) {
-                const float fv = v[y]; v[y] = v[y - 1]; v[y - 1] = fv;
-                const uint32_t iv = id[y]; id[y] = id[y - 1]; id[y - 1] = iv;
-              }
-            }
-#pragma unroll
-            for (int y = 0; y < KT; ++y) { lv[(cb * KT + y) * kThreads + tid] = v[y]; li[(cb * KT + y) * kThreads + tid] = id[y]; }
-            bar[cb] = v[KT - 1];
-            m = -__builtin_inff();
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-              acc[cb][i] = i == at ? -__builtin_inff() : acc[cb][i];
-              m = fmaxf(m, acc[cb][i]);
-            }
+          for (int y = KT - 1; y >= 0; --y) {
+            const bool here = y == 0 || above[y - 1];         // the new entry lands at y or above
+            lv[cb][y] = above[y] ? lv[cb][y] : here ? m[cb] : lv[cb][y - 1];
+            li[cb][y] = above[y] ? li[cb][y] : here ? key : li[cb][y - 1];
           }
+          float mm = -__builtin_inff();
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            acc[cb][i] = i == at ? -__builtin_inff() : acc[cb][i];
+            mm = fmaxf(mm, acc[cb][i]);
+          }
+          m[cb] = mm;
         }
       }
     }
-    if (!stash_first) {
-      if (t + 1 < n_tiles) stash_tile(buf ^ 1, s);
-      if (t + 3 < n_tiles) load_tile(tile0 + t + 3, s);
-    }
-    if ((t & (kFloorEvery - 1)) == kFloorEvery - 1) {       // workgroup-uniform
-      __syncthreads();                                      // every list is at rest
+  };
+
+  // One tile.  On entry the first key block of tile t is in the matrix pipe (accA) and av holds its second.
+  // bc: buffer of tile t.  `full`: tiles t + 1 .. t + 3 all exist, whole, and no page table is in the way, so
+  // the step has no branch but the rare insertions and the tile requests are scheduled among the matrix
+  // instructions.
+  auto step = [&](auto ragged, auto full, int64_t t, int bc) __attribute__((always_inline)) {
+    constexpr bool kFull = decltype(full)::value;
+    const int bn = (bc + 1) & (kBufs - 1);                  // buffer of tile t + 1
+    const int bd = (bc + 3) & (kBufs - 1);                  // buffer of tile t + 3: tile t - 1 has left it
+    const bool more = kFull || t + 1 < n_tiles;
+    const int64_t key0 = (tile0 + t) * kTileKeys + lh * 4;
+    contract(accB, yes, rows_of(bc, 2));
+    if (kFull || t + 3 < n_tiles) dma_tile(full, tile0 + t + 3, bd);
+#pragma unroll
+    for (int cb = 0; cb < NCB; ++cb) floor_[cb] = xfloor[(cw * NCB + cb) * 32 + ln];
+    filter(ragged, accA, key0);
+    contract(accA, yes, rows_of(bc, 3));
+    filter(ragged, accB, key0 + 32);
+    if (more) contract(accB, yes, rows_of(bn, 0));
+    else contract(accB, no, nullptr);
+    filter(ragged, accA, key0 + 64);
+    if (more) contract(accA, yes, rows_of(bn, 1));
+    filter(ragged, accB, key0 + 96);
+    // workgroup-uniform.  Early in the walk the lists move with every block and a fresh floor keeps half of the
+    // scores that would enter one of them out: refreshes are dense there (1.7 ms of filter work became 0.7).
+    if ((t & (kFloorEvery - 1)) == kFloorEvery - 1 || t < kFloorEach || (t < kFloorFourth && (t & 3) == 3)) {
+#pragma unroll
+      for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+        for (int y = 0; y < KT; ++y) lvx[(cb * KT + y) * kThreads + tid] = lv[cb][y];
+      __syncthreads();
       for (int col = tid; col < kTileCols; col += kThreads) {
-        // column col = (cw2 * 32 + ln): its lists sit with threads (cw * 2 + kw) * 64 + lh * 32 + ln
+        // column col = cw2 * 32 + ln: its lists sit with lanes {0, 32} + ln of wave cw2 / NCB, block cw2 % NCB
         const int cw2 = col >> 5, lcol = col & 31, ccw = cw2 / NCB, ccb = cw2 % NCB;
         float best[KT];
 #pragma unroll
         for (int y = 0; y < KT; ++y) best[y] = -__builtin_inff();
 #pragma unroll
-        for (int part = 0; part < 4; ++part) {
-          const int owner = (ccw * 2 + (part >> 1)) * 64 + (part & 1) * 32 + lcol;
+        for (int part = 0; part < 2; ++part) {
+          const int owner = ccw * 64 + part * 32 + lcol;
 #pragma unroll
           for (int y = 0; y < KT; ++y) {
-            float v = lv[(ccb * KT + y) * kThreads + owner];
+            float v = lvx[(ccb * KT + y) * kThreads + owner];
 #pragma unroll
             for (int z = 0; z < KT; ++z) {                  // keep the KT largest, descending
               const float hi = fmaxf(best[z], v);
@@ -252,55 +302,72 @@ __global__ __launch_bounds__(kThreads) void vote_gemm_kernel(VoteGemmArgs a) {
         xfloor[col] = best[KT - 1];
       }
     }
+    // tile t + 2 has landed (requested during step t - 1); the loads of this step may still fly
+    if (kFull) asm volatile("s_waitcnt vmcnt(%0)" :: "n"(kDma) : "memory");
+    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
   };
 
-  for (int64_t t = 0; t < n_tiles; t += 2) {
-    step(t, 0, stg2);
-    if (t + 1 < n_tiles) step(t + 1, 1, stg);
+  if (n_tiles > 0) {
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) av[ks] = *(const op8*)(rows_of(0, 0) + ks * 32);
+    contract(accA, yes, rows_of(0, 1));
+  }
+  const bool ragged_last = tile0 + n_tiles == n_tiles_all && (a.n_keys % kTileKeys) != 0;
+  int bc = 0;
+  int64_t t = 0;
+  // the long middle of the walk: a loop of its own with a single path through it
+  if (!a.pt) {
+    for (; t + 3 < n_tiles; ++t) {
+      step(no, yes, t, bc);
+      bc = (bc + 1) & (kBufs - 1);
+    }
+  }
+  for (; t < n_tiles; ++t) {
+    if (ragged_last && t == n_tiles - 1) step(yes, no, t, bc);
+    else step(no, no, t, bc);
+    bc = (bc + 1) & (kBufs - 1);
   }
 
-  // the four partial lists of a column (2 wave rows x 2 lane halves) meet in LDS (over the key tiles)
-  uint64_t* lists = (uint64_t*)vg_lds;                      // [kTileCols][4][KT]
+  // the two partial lists of a column (the lane halves) meet in LDS (over the key tiles)
+  constexpr int P = 2;
+  uint64_t* lists = (uint64_t*)vg_lds;                      // [kTileCols][P][KT]
 #pragma unroll
   for (int cb = 0; cb < NCB; ++cb) {
     const int col = (cw * NCB + cb) * 32 + ln;
 #pragma unroll
-    for (int t = 0; t < KT; ++t) {
-      const float v = lv[(cb * KT + t) * kThreads + tid];
-      const uint32_t id = li[(cb * KT + t) * kThreads + tid];
-      lists[((size_t)col * 4 + kw * 2 + lh) * KT + t] = id != 0xffffffffu ? vg_composite(v, id) : 0ull;
-    }
+    for (int y = 0; y < KT; ++y)
+      lists[((size_t)col * P + lh) * KT + y] = li[cb][y] != 0xffffffffu ? vg_composite(lv[cb][y], li[cb][y]) : 0ull;
   }
   __syncthreads();
   for (int col = tid; col < kTileCols && c0 + col < n_cols; col += kThreads) {
     const int c = c0 + col;
-    const uint64_t* mine = lists + (size_t)col * 4 * KT;
-    int head[4];
+    const uint64_t* mine = lists + (size_t)col * P * KT;
+    int head[P];
 #pragma unroll
-    for (int s = 0; s < 4; ++s) head[s] = 0;
+    for (int x = 0; x < P; ++x) head[x] = 0;
     uint64_t* out = a.part + (((int64_t)(c / a.G) * a.Hq + (int64_t)h * a.G + c % a.G) * a.n_split + blockIdx.z) * KT;
     for (int round = 0; round < KT; ++round) {              // lists are sorted: compare their heads
       uint64_t best = 0ull; int from = 0;
 #pragma unroll
-      for (int s = 0; s < 4; ++s) {
-        const uint64_t v = head[s] < KT ? mine[s * KT + head[s]] : 0ull;
-        if (v > best) { best = v; from = s; }
+      for (int x = 0; x < P; ++x) {
+        const uint64_t v = head[x] < KT ? mine[x * KT + head[x]] : 0ull;
+        if (v > best) { best = v; from = x; }
       }
 #pragma unroll
-      for (int s = 0; s < 4; ++s) head[s] += (s == from && best != 0ull) ? 1 : 0;
+      for (int x = 0; x < P; ++x) head[x] += (x == from && best != 0ull) ? 1 : 0;
       out[round] = best;
     }
   }
 }
 
-template <int KT, bool F16, int NCB>
+template <int KT, bool F16, int NCB, int NW>
 hipError_t vote_gemm_launch(const VoteGemmArgs& a, dim3 grid, hipStream_t st) {
-  constexpr int kTileCols = NCB * 128;
-  static_assert((size_t)kTileCols * 4 * KT * sizeof(uint64_t) <= 2 * (size_t)kTileBytes, "merge area inside the tiles");
-  constexpr size_t lds = 2 * (size_t)kTileBytes + (size_t)NCB * KT * kThreads * 8 + kTileCols * 4;
+  constexpr int kTileCols = NCB * 32 * NW, kThreads = 64 * NW;
+  static_assert((size_t)kTileCols * 2 * KT * sizeof(uint64_t) <= kBufs * (size_t)kTileBytes, "merge area inside the tiles");
+  constexpr size_t lds = kBufs * (size_t)kTileBytes + (size_t)NCB * KT * kThreads * 4 + kTileCols * 4;
   static_assert(lds <= (size_t)160 * 1024, "fits a compute unit's LDS");
-  auto kern = vote_gemm_kernel<KT, F16, NCB>;
+  auto kern = vote_gemm_kernel<KT, F16, NCB, NW>;
   hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(kern, grid, dim3(kThreads), lds, st, a);
@@ -309,8 +376,7 @@ hipError_t vote_gemm_launch(const VoteGemmArgs& a, dim3 grid, hipStream_t st) {
 
 }  // namespace
 
-// Columns per workgroup: 512 while the lists of a column block fit LDS four times over (lists of up to 4) and the
-// chunk has columns to fill them, else 256.
+// Columns per workgroup.
 int vote_gemm_tile_cols(const Plan& pl, int n_query, int list_len) {
   (void)pl; (void)n_query; (void)list_len;
   return 256;
@@ -345,20 +411,19 @@ hipError_t launch_vote_gemm(const Plan& pl, const void* q, int n_query, const vo
   a.tiles_per_block = (int)((n_tiles + a.n_split - 1) / a.n_split);
   const dim3 grid((unsigned)pl.Hkv, (unsigned)(((int64_t)n_query * pl.G + tile_cols - 1) / tile_cols),
                   (unsigned)a.n_split);
-  const bool wide = tile_cols == 512;
   if (pl.dtype == kF16) {
     switch (list_len) {
-      case 1: return wide ? vote_gemm_launch<1, true, 4>(a, grid, st) : vote_gemm_launch<1, true, 2>(a, grid, st);
-      case 2: return wide ? vote_gemm_launch<2, true, 4>(a, grid, st) : vote_gemm_launch<2, true, 2>(a, grid, st);
-      case 4: return wide ? vote_gemm_launch<4, true, 4>(a, grid, st) : vote_gemm_launch<4, true, 2>(a, grid, st);
-      default: return vote_gemm_launch<8, true, 2>(a, grid, st);
+      case 1: return vote_gemm_launch<1, true, 1, 8>(a, grid, st);
+      case 2: return vote_gemm_launch<2, true, 1, 8>(a, grid, st);
+      case 4: return vote_gemm_launch<4, true, 1, 8>(a, grid, st);
+      default: return vote_gemm_launch<8, true, 1, 8>(a, grid, st);
     }
   }
   switch (list_len) {
-    case 1: return wide ? vote_gemm_launch<1, false, 4>(a, grid, st) : vote_gemm_launch<1, false, 2>(a, grid, st);
-    case 2: return wide ? vote_gemm_launch<2, false, 4>(a, grid, st) : vote_gemm_launch<2, false, 2>(a, grid, st);
-    case 4: return wide ? vote_gemm_launch<4, false, 4>(a, grid, st) : vote_gemm_launch<4, false, 2>(a, grid, st);
-    default: return vote_gemm_launch<8, false, 2>(a, grid, st);
+    case 1: return vote_gemm_launch<1, false, 1, 8>(a, grid, st);
+    case 2: return vote_gemm_launch<2, false, 1, 8>(a, grid, st);
+    case 4: return vote_gemm_launch<4, false, 1, 8>(a, grid, st);
+    default: return vote_gemm_launch<8, false, 1, 8>(a, grid, st);
   }
 }
 
