@@ -7,32 +7,38 @@
 // unlike the group-sum contraction there is no hi/lo split and the executed matrix work
 // equals the algorithmic 2 * M * Hq * N_mid * D.
 //
-// Tiling: a workgroup of 8 waves (two per SIMD) owns 256 columns ((query row, head) pairs,
-// query-major) of one KV head and walks key tiles of 128 rows staged in LDS (four buffers,
-// 272-byte row pitch, filled by loads that go from memory straight into LDS).  Keys are the A
-// operand, so a lane of a 32x32 block holds ONE column and 16 keys: the running top-k list of a
-// column belongs to the lane that owns it (in registers), and a block costs a maximum over 16
-// scores and one comparison unless a score enters the list.  Wave cw takes column block cw (its
-// 8 query operands stay in registers) and all four key blocks of a tile, one after the other:
-// while the matrix pipe works on block j + 1 the wave filters the scores of block j (two sets of
-// accumulators), and the key operands of block j + 2 travel from LDS into registers; the first
-// block of tile t + 1 is in the pipe before the workgroup meets at the barrier that ends step t.
-// The second wave of a SIMD covers what this leaves open: an insertion into a list (rare, long,
-// divergent) and the wait at the barrier.  The two partial lists of a column (the lane halves)
-// are merged through LDS at the end.  With few query rows the keys are also split over
-// blockIdx.z so that the chip is filled; every workgroup writes one partial list per column and
-// head_topk_merge (the same kernel that closes the decode scan) picks the best k.
+// Tiling: a workgroup of 8 waves (two per SIMD) owns 512 columns ((query row, head) pairs,
+// query-major; 256 for a short chunk or lists of 8) of one KV head and walks key tiles of 128
+// rows staged in LDS (four buffers, 272-byte row pitch, filled by loads that go from memory
+// straight into LDS).  Keys are the A operand, so a lane of a 32x32 block holds ONE column and 16
+// keys: the running top-k list of a column belongs to the lane that owns it (in registers), and
+// a block costs a maximum over 16 scores and one comparison unless a score enters the list.
+// Wave cw takes the two column blocks 2 cw, 2 cw + 1 (their 2 x 8 query operands stay in
+// registers) and all four key blocks of a tile.  Its work is a chain of phases (key block,
+// column block): while the matrix pipe works on phase q + 1 the wave filters the scores of
+// phase q (two accumulators), both column blocks of a key block share one read of its rows from
+// LDS, and the rows of the next key block arrive behind the matrix instructions that read the
+// current ones; the first phase of tile t + 1 is in the pipe before the workgroup meets at the
+// barrier that ends step t.  The second wave of a SIMD covers what this leaves open: an
+// insertion into a list (rare, long, divergent) and the wait at the barrier.  The two partial
+// lists of a column (the lane halves) are merged through LDS at the end.  With few query rows
+// the keys are also split over blockIdx.z so that the chip is filled; every workgroup writes one
+// partial list per column and head_topk_merge (the same kernel that closes the decode scan)
+// picks the best k.
 // blockIdx.x is the KV head: with 8 heads every XCD streams one head's keys through its L2.
 //
 // Measured on the 4096-row chunk of 4-head groups against 256 K keys (8.66 TFLOP, times of this
 // kernel alone): the matrix instructions with nothing around them run at 1790 TFLOP/s on random
-// operands (the chip's power limit, 0.72 of the 2.5 PFLOP/s peak: 4.8 ms); with the operand reads
-// from LDS 6.0 ms; with the tile loads and the barrier 6.5 ms; with the filter and the lists
-// 7.2 ms.  Other shapes tried, same work: one wave per SIMD with two column blocks (half the LDS
-// reads, 5.6 ms for matrix work + reads) ends at 9.3 ms because nothing covers an insertion or
-// the barrier; four column blocks per wave, or two with two waves per SIMD, do not fit the
-// register file; key tiles that travel through registers (the compiler's count of loads in
-// flight makes a step wait for the tile requested one step ago, not two) 7.9 ms.
+// operands (the chip's power limit, 0.72 of the 2.5 PFLOP/s peak: 4.8 ms); in this kernel's
+// phase structure without any LDS read 5.2 ms, with the operand reads 6.3 ms, with the tile
+// loads and the barrier 6.5 ms, with the filter and the lists 7.0 ms.  Other shapes tried, same
+// work: one column block per wave (twice the operand reads per matrix instruction) 7.2 ms; one
+// wave per SIMD with two column blocks 9.3 ms because nothing covers an insertion or the barrier;
+// four column blocks per wave, or a second set of key operands, do not fit the register file
+// of two waves per SIMD; key tiles that travel through registers (the compiler's count of loads
+// in flight makes a step wait for the tile requested one step ago, not two) 7.9 ms.  The LDS
+// itself is far from full: 128-bit reads with this pitch reach 205 B/clk per compute unit with 8
+// waves (131 with 4), and the kernel asks for 64.
 #include "common.hpp"
 
 #include <type_traits>
@@ -62,12 +68,14 @@ __device__ __forceinline__ uint64_t vg_composite(float score, uint32_t pos) {
 
 // NCB: column blocks of 32 per wave; NW: waves of the workgroup (8: two per SIMD with half the register file each;
 // 4: one per SIMD with all of it).  The workgroup owns NCB * 32 * NW columns; every wave walks all four key blocks
-// of a tile for its own NCB column blocks.  The library launches NCB = 1, NW = 8.
+// of a tile for its own NCB column blocks.  The library launches NW = 8 with NCB = 2 (NCB = 1 for lists of 8, whose
+// floor merge would not fit LDS, and for chunks of at most 256 columns).
 template <int KT, bool F16, int NCB, int NW>
 __global__ __launch_bounds__(64 * NW) void vote_gemm_kernel(VoteGemmArgs a) {
   constexpr int kTileCols = NCB * 32 * NW;
   constexpr int kThreads = 64 * NW;
   static_assert(NW == 4 || NW == 8, "one or two waves per SIMD");
+  static_assert((4 * NCB) % 2 == 0, "the accumulator sets alternate across tiles");
   typedef typename Mm<F16>::op8 op8;
   typedef mm_f32x16 f32x16;
   extern __shared__ __attribute__((aligned(16))) unsigned char vg_lds[];
@@ -169,87 +177,71 @@ __global__ __launch_bounds__(64 * NW) void vote_gemm_kernel(VoteGemmArgs a) {
   __syncthreads();
 
   // C layout of a 32x32 block: acc[i] is key row (i/4)*8 + (lane/32)*4 + i%4, column lane%32.
-  f32x16 accA[NCB], accB[NCB];
+  f32x16 accs[2];                                           // one in the matrix pipe, one under the filter
   op8 av[8];
   auto rows_of = [&](int buf, int j) -> const unsigned char* {
     return tiles + buf * kTileBytes + (j * 32 + ln) * kPitch + lh * 16;
   };
-  // acc <- keys in av x queries; av <- the rows at `refill` (refills: a compile-time yes or no)
-  auto contract = [&](f32x16 (&acc)[NCB], auto refills, const unsigned char* refill) __attribute__((always_inline)) {
+  // acc <- keys in av x queries of column block cb; av <- the rows at `refill` (refills: a compile-time yes or no)
+  auto contract = [&](f32x16& acc, int cb, auto refills, const unsigned char* refill) __attribute__((always_inline)) {
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) {
+      if (ks == 0) {
+        f32x16 z;
 #pragma unroll
-      for (int x = 0; x < NCB; ++x) {
-        if (ks == 0) {
-          f32x16 z;
-#pragma unroll
-          for (int i = 0; i < 16; ++i) z[i] = 0.f;
-          acc[x] = Mm<F16>::mfma32(av[0], bq[x][0], z);
-        } else {
-          acc[x] = Mm<F16>::mfma32(av[ks], bq[x][ks], acc[x]);
-        }
+        for (int i = 0; i < 16; ++i) z[i] = 0.f;
+        acc = Mm<F16>::mfma32(av[0], bq[cb][0], z);
+      } else {
+        acc = Mm<F16>::mfma32(av[ks], bq[cb][ks], acc);
       }
       if (decltype(refills)::value) av[ks] = *(const op8*)(refill + ks * 32);
     }
     // the matrix instructions are issued here, ahead of the filter that follows in program order, and their
     // results live in the registers the vector unit reads
-#pragma unroll
-    for (int x = 0; x < NCB; ++x) asm volatile("" : "+v"(acc[x]));
+    asm volatile("" : "+v"(acc));
   };
   float floor_[NCB];
-  // the scores of one key block against the running lists; key_blk: key of acc[0] of this lane
-  auto filter = [&](auto ragged, f32x16 (&acc)[NCB], int64_t key_blk) __attribute__((always_inline)) {
+  // the scores of one key block of column block cb against the running list; key_blk: key of acc[0] of this lane
+  auto filter = [&](auto ragged, f32x16& acc, int cb, int64_t key_blk) __attribute__((always_inline)) {
     if (decltype(ragged)::value) {                          // only a ragged last tile: keys past the end never enter a list
 #pragma unroll
-      for (int x = 0; x < NCB; ++x)
-#pragma unroll
-        for (int i = 0; i < 16; ++i)
-          if (key_blk + (i >> 2) * 8 + (i & 3) >= a.n_keys) acc[x][i] = -__builtin_inff();
+      for (int i = 0; i < 16; ++i)
+        if (key_blk + (i >> 2) * 8 + (i & 3) >= a.n_keys) acc[i] = -__builtin_inff();
     }
-    float m[NCB];
-    bool enters = false;
+    float m = acc[0];
 #pragma unroll
-    for (int cb = 0; cb < NCB; ++cb) {
-      m[cb] = acc[cb][0];
+    for (int i = 1; i < 16; ++i) m = fmaxf(m, acc[i]);
+    // A score enters a list rarely (the list's k-th value climbs quickly), and then usually one per lane: take
+    // the lane's largest remaining score, insert, strike it out, again.  Largest first and, among equals,
+    // lowest key first: an equal score never displaces.
+    while (__any(m > lv[cb][KT - 1] && m >= floor_[cb])) {
+      if (m > lv[cb][KT - 1] && m >= floor_[cb]) {
+        int at = 15;
 #pragma unroll
-      for (int i = 1; i < 16; ++i) m[cb] = fmaxf(m[cb], acc[cb][i]);
-      enters |= m[cb] > lv[cb][KT - 1] && m[cb] >= floor_[cb];
-    }
-    // A score enters a list rarely (the list's k-th value climbs quickly): one question per block, and then
-    // usually one score per lane: take the lane's largest remaining score, insert, strike it out, again.
-    // Largest first and, among equals, lowest key first: an equal score never displaces.
-    if (!__any(enters)) return;
+        for (int i = 14; i >= 0; --i) at = acc[i] == m ? i : at;             // lowest i holding the maximum
+        const uint32_t key = (uint32_t)(key_blk + (at >> 2) * 8 + (at & 3));
+        // entries at least as large stay above the new one (their keys are lower)
+        bool above[KT];
 #pragma unroll
-    for (int cb = 0; cb < NCB; ++cb) {
-      while (__any(m[cb] > lv[cb][KT - 1] && m[cb] >= floor_[cb])) {
-        if (m[cb] > lv[cb][KT - 1] && m[cb] >= floor_[cb]) {
-          int at = 15;
+        for (int y = 0; y < KT; ++y) above[y] = lv[cb][y] >= m;
 #pragma unroll
-          for (int i = 14; i >= 0; --i) at = acc[cb][i] == m[cb] ? i : at;   // lowest i holding the maximum
-          const uint32_t key = (uint32_t)(key_blk + (at >> 2) * 8 + (at & 3));
-          // entries at least as large stay above the new one (their keys are lower)
-          bool above[KT];
-#pragma unroll
-          for (int y = 0; y < KT; ++y) above[y] = lv[cb][y] >= m[cb];
-#pragma unroll
-          for (int y = KT - 1; y >= 0; --y) {
-            const bool here = y == 0 || above[y - 1];         // the new entry lands at y or above
-            lv[cb][y] = above[y] ? lv[cb][y] : here ? m[cb] : lv[cb][y - 1];
-            li[cb][y] = above[y] ? li[cb][y] : here ? key : li[cb][y - 1];
-          }
-          float mm = -__builtin_inff();
-#pragma unroll
-          for (int i = 0; i < 16; ++i) {
-            acc[cb][i] = i == at ? -__builtin_inff() : acc[cb][i];
-            mm = fmaxf(mm, acc[cb][i]);
-          }
-          m[cb] = mm;
+        for (int y = KT - 1; y >= 0; --y) {
+          const bool here = y == 0 || above[y - 1];           // the new entry lands at y or above
+          lv[cb][y] = above[y] ? lv[cb][y] : here ? m : lv[cb][y - 1];
+          li[cb][y] = above[y] ? li[cb][y] : here ? key : li[cb][y - 1];
         }
+        float mm = -__builtin_inff();
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          acc[i] = i == at ? -__builtin_inff() : acc[i];
+          mm = fmaxf(mm, acc[i]);
+        }
+        m = mm;
       }
     }
   };
 
-  // One tile.  On entry the first key block of tile t is in the matrix pipe (accA) and av holds its second.
+  // One tile.
   // bc: buffer of tile t.  `full`: tiles t + 1 .. t + 3 all exist, whole, and no page table is in the way, so
   // the step has no branch but the rare insertions and the tile requests are scheduled among the matrix
   // instructions.
@@ -259,18 +251,31 @@ __global__ __launch_bounds__(64 * NW) void vote_gemm_kernel(VoteGemmArgs a) {
     const int bd = (bc + 3) & (kBufs - 1);                  // buffer of tile t + 3: tile t - 1 has left it
     const bool more = kFull || t + 1 < n_tiles;
     const int64_t key0 = (tile0 + t) * kTileKeys + lh * 4;
-    contract(accB, yes, rows_of(bc, 2));
-    if (kFull || t + 3 < n_tiles) dma_tile(full, tile0 + t + 3, bd);
+    // Phase q = (key block j, column block cb) of the tile, j-major.  On entry phase 0 is in the matrix pipe
+    // and av holds the rows of block 0 (of block 1 if there is one column block: the last column block of a key
+    // block refills av behind its matrix instructions).  Each turn issues the matrix work of phase q + 1, then
+    // filters phase q.
 #pragma unroll
-    for (int cb = 0; cb < NCB; ++cb) floor_[cb] = xfloor[(cw * NCB + cb) * 32 + ln];
-    filter(ragged, accA, key0);
-    contract(accA, yes, rows_of(bc, 3));
-    filter(ragged, accB, key0 + 32);
-    if (more) contract(accB, yes, rows_of(bn, 0));
-    else contract(accB, no, nullptr);
-    filter(ragged, accA, key0 + 64);
-    if (more) contract(accA, yes, rows_of(bn, 1));
-    filter(ragged, accB, key0 + 96);
+    for (int q = 0; q < 4 * NCB; ++q) {
+      const int j = q / NCB, cb = q % NCB;
+      const int jn = (q + 1) / NCB, cbn = (q + 1) % NCB;    // jn == 4: the first block of tile t + 1
+      const bool last_cb = cbn == NCB - 1;
+      if (jn < 4) {
+        // rows after block jn: of this tile, or the first of the next
+        if (last_cb && jn < 3) contract(accs[(q + 1) & 1], cbn, yes, rows_of(bc, jn + 1));
+        else if (last_cb && more) contract(accs[(q + 1) & 1], cbn, yes, rows_of(bn, 0));
+        else contract(accs[(q + 1) & 1], cbn, no, nullptr);
+      } else if (more) {
+        if (last_cb) contract(accs[(q + 1) & 1], cbn, yes, rows_of(bn, 1));
+        else contract(accs[(q + 1) & 1], cbn, no, nullptr);
+      }
+      if (q == 0) {
+        if (kFull || t + 3 < n_tiles) dma_tile(full, tile0 + t + 3, bd);
+#pragma unroll
+        for (int x = 0; x < NCB; ++x) floor_[x] = xfloor[(cw * NCB + x) * 32 + ln];
+      }
+      filter(ragged, accs[q & 1], cb, key0 + j * 32);
+    }
     // workgroup-uniform.  Early in the walk the lists move with every block and a fresh floor keeps half of the
     // scores that would enter one of them out: refreshes are dense there (1.7 ms of filter work became 0.7).
     if ((t & (kFloorEvery - 1)) == kFloorEvery - 1 || t < kFloorEach || (t < kFloorFourth && (t & 3) == 3)) {
@@ -311,7 +316,8 @@ __global__ __launch_bounds__(64 * NW) void vote_gemm_kernel(VoteGemmArgs a) {
   if (n_tiles > 0) {
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) av[ks] = *(const op8*)(rows_of(0, 0) + ks * 32);
-    contract(accA, yes, rows_of(0, 1));
+    if (NCB == 1) contract(accs[0], 0, yes, rows_of(0, 1));
+    else contract(accs[0], 0, no, nullptr);
   }
   const bool ragged_last = tile0 + n_tiles == n_tiles_all && (a.n_keys % kTileKeys) != 0;
   int bc = 0;
@@ -376,10 +382,9 @@ hipError_t vote_gemm_launch(const VoteGemmArgs& a, dim3 grid, hipStream_t st) {
 
 }  // namespace
 
-// Columns per workgroup.
+// Columns per workgroup: 512 (two column blocks per wave) where the chunk has them and the lists are short.
 int vote_gemm_tile_cols(const Plan& pl, int n_query, int list_len) {
-  (void)pl; (void)n_query; (void)list_len;
-  return 256;
+  return list_len <= 4 && (int64_t)n_query * pl.G > 256 ? 512 : 256;
 }
 
 // Key splits of the chunk contraction: enough workgroups for one round over the chip (one workgroup per CU: a
@@ -413,16 +418,16 @@ hipError_t launch_vote_gemm(const Plan& pl, const void* q, int n_query, const vo
                   (unsigned)a.n_split);
   if (pl.dtype == kF16) {
     switch (list_len) {
-      case 1: return vote_gemm_launch<1, true, 1, 8>(a, grid, st);
-      case 2: return vote_gemm_launch<2, true, 1, 8>(a, grid, st);
-      case 4: return vote_gemm_launch<4, true, 1, 8>(a, grid, st);
+      case 1: return (tile_cols == 512 ? vote_gemm_launch<1, true, 2, 8>(a, grid, st) : vote_gemm_launch<1, true, 1, 8>(a, grid, st));
+      case 2: return (tile_cols == 512 ? vote_gemm_launch<2, true, 2, 8>(a, grid, st) : vote_gemm_launch<2, true, 1, 8>(a, grid, st));
+      case 4: return (tile_cols == 512 ? vote_gemm_launch<4, true, 2, 8>(a, grid, st) : vote_gemm_launch<4, true, 1, 8>(a, grid, st));
       default: return vote_gemm_launch<8, true, 1, 8>(a, grid, st);
     }
   }
   switch (list_len) {
-    case 1: return vote_gemm_launch<1, false, 1, 8>(a, grid, st);
-    case 2: return vote_gemm_launch<2, false, 1, 8>(a, grid, st);
-    case 4: return vote_gemm_launch<4, false, 1, 8>(a, grid, st);
+    case 1: return (tile_cols == 512 ? vote_gemm_launch<1, false, 2, 8>(a, grid, st) : vote_gemm_launch<1, false, 1, 8>(a, grid, st));
+    case 2: return (tile_cols == 512 ? vote_gemm_launch<2, false, 2, 8>(a, grid, st) : vote_gemm_launch<2, false, 1, 8>(a, grid, st));
+    case 4: return (tile_cols == 512 ? vote_gemm_launch<4, false, 2, 8>(a, grid, st) : vote_gemm_launch<4, false, 1, 8>(a, grid, st));
     default: return vote_gemm_launch<8, false, 1, 8>(a, grid, st);
   }
 }
