@@ -26,7 +26,7 @@ SCAN_TRAFFIC = {"cfg3_decode_1m_bf16": {"bytes": 2 * 1045670.6 * 1024 + 916.4 * 
 # profiles/prefill_chunk_cfg4_kernel_trace_pmc.md, profiles/vote_prefill_cfg4_kernel_trace_pmc.md): fetched bytes per launch.
 VOTE_SCAN_TRAFFIC_BYTES = {"cfg3_decode_1m_bf16": 2 * 1044560.7 * 1024 + 32.0 * 1024}
 GEMM_FILTER_TRAFFIC_BYTES = 2 * 266407.5 * 1024
-VOTE_GEMM_TRAFFIC_BYTES = 2 * 533497.3 * 1024
+VOTE_GEMM_TRAFFIC_BYTES = 2 * 277092.2 * 1024
 
 
 def main() -> int:
