@@ -8,7 +8,7 @@
 //            answer).  The same launch fills the rotary table of the attention that follows.
 //   scan     (score_scan.hip, filter mode) streams the keys once; every workgroup parks its slice's scores in
 //            LDS, finds the bound from the row's samples, and leaves only the (score, position) pairs at or
-//            above it, in position order, in its own segment: ~1.5 k pairs per row instead of n_mid scores.
+//            above it, in position order, in its own segment: about 1.6 times k pairs per row instead of n_mid scores.
 //   pick     one workgroup per row numbers the segments' pairs through (position order), holds their keys in
 //            LDS, finds the exact k-th largest (score descending, index ascending) by radix select on the
 //            offsets from the smallest candidate key, and writes the winners' absolute indices in ascending
