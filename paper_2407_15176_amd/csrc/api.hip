@@ -37,7 +37,7 @@ bool filter_plan(Plan* pl, int route) {
   const double expect = r * (double)step;               // pairs at or above the bound, and six deviations on top
   const double most = expect * (1.0 + 6.0 / std::sqrt(r)) + 64.0;
   if (most > (double)kPickMax || ns > kFilterSampMax) return false;
-  const int rpb = scan_rows_per_block_for(pl->n_mid, pl->Hkv, 0, 256);
+  const int rpb = scan_rows_per_block_for(pl->n_mid, pl->Hkv, 16384, 512);   // two workgroups of 512 threads per CU, 32 rows per thread
   const int64_t nb = (pl->n_mid + rpb - 1) / rpb;
   if (nb > kPickSlices) return false;
   pl->filter = true;

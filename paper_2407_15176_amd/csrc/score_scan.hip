@@ -18,6 +18,10 @@
 // after the stream is nearly free.  The first radix digit of the top-k (a
 // 4096-bin histogram of the ordered score keys) is accumulated in LDS on the way
 // and flushed with one atomic per non-empty bin.
+// Filter mode (no score array: only the pairs at or above a sampled bound leave the kernel) has nothing to
+// write during the stream and runs two 512-thread workgroups per CU instead: one of the pair looks for its
+// row's bound before it streams, the other behind its stream, so the CU's loads never stop for both
+// (measured: 1.3 us of 326 per launch at a million tokens; all workgroups searching first: nothing).
 #include "common.hpp"
 #include "select.hpp"
 
@@ -54,13 +58,14 @@ constexpr int kScanMaxRows = 32768;            // rows of scores one workgroup p
 constexpr int kOutScores = 0;                  // written as they are
 constexpr int kOutHist = 1;                    // written, and the first radix digit of the top-k counted on the way
 constexpr int kOutFilter = 2;                  // not written: only the pairs that can still be among the k largest
-constexpr int kSampRegs = kFilterSampMax / 1024;                  // sampled scores a thread holds while the bound is found
+constexpr int kFilterThreads = 512;            // filter mode: two workgroups per CU, so that one streams while the other looks for its bound or compacts
 
 // PAGED: the rows of a workgroup's slice are found through the page table; the few entries the slice
 // spans are copied into LDS first, so a row costs one LDS read and two integer instructions more.
-template <typename T, int D, int U, int MODE, bool PAGED = false>
-__global__ __launch_bounds__(kScanThreads) void score_scan_kernel(ScanArgs a) {
+template <typename T, int D, int U, int MODE, bool PAGED = false, int NT = kScanThreads>
+__global__ __launch_bounds__(NT) void score_scan_kernel(ScanArgs a) {
   constexpr bool HIST = MODE == kOutHist, FILTER = MODE == kOutFilter;
+  constexpr int kSampRegs = kFilterSampMax / NT;     // sampled scores a thread holds while the bound is found
   constexpr int EPL = Store<T>::kPerLoad;      // elements per 16-byte load
   constexpr int LPR = D / EPL;                 // lanes per key row
   constexpr int RPL = 64 / LPR;                // rows per wave-wide load
@@ -73,17 +78,17 @@ __global__ __launch_bounds__(kScanThreads) void score_scan_kernel(ScanArgs a) {
   uint32_t* lhist = (uint32_t*)(stage + (FILTER ? a.rows_per_block + (a.rows_per_block >> 5) + 1 : a.rows_per_block));
   uint32_t* fsh = lhist + kBinsPad;            // filter mode: lhist holds the select's 2048 padded bins, then 40 words
   if (a.ap.n_vec) {                            // a decode token's own rows: a few 16-byte pieces, copied first
-    const int64_t n_thr = (int64_t)gridDim.x * gridDim.y * kScanThreads;
-    for (int64_t i = ((int64_t)blockIdx.y * gridDim.x + blockIdx.x) * kScanThreads + threadIdx.x; i < a.ap.n_vec; i += n_thr)
+    const int64_t n_thr = (int64_t)gridDim.x * gridDim.y * NT;
+    for (int64_t i = ((int64_t)blockIdx.y * gridDim.x + blockIdx.x) * NT + threadIdx.x; i < a.ap.n_vec; i += n_thr)
       append_piece(a.ap, i);
   }
   if (HIST) {
-    for (int b = threadIdx.x; b < kHistBins; b += kScanThreads) lhist[b] = 0;
+    for (int b = threadIdx.x; b < kHistBins; b += NT) lhist[b] = 0;
     __syncthreads();
   }
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  constexpr int nwaves = kScanThreads / 64;
+  constexpr int nwaves = NT / 64;
   const int sub = lane % LPR, grp = lane / LPR;
   const int row_id = blockIdx.y;               // query * Hkv + kv head
   const int h = row_id % a.Hkv, qi = row_id / a.Hkv;
@@ -94,17 +99,21 @@ __global__ __launch_bounds__(kScanThreads) void score_scan_kernel(ScanArgs a) {
 
   // filter mode: the lower bound of the row's k-th score, from the sampled scores (every workgroup of the
   // row finds the same value; the sample is 36 KiB out of L2)
+  // Two workgroups share a CU (the second round of workgroup ids lands beside the first): one looks for the
+  // bound before its stream, the other behind it, so that the CU's loads never stop for both at once.
   uint32_t thr_key = 0;
-  if (FILTER) {
+  auto find_bound = [&]() {
     uint32_t skey[kSampRegs];
     const float* srow = a.samp + (int64_t)row_id * a.samp_stride;
 #pragma unroll
     for (int r = 0; r < kSampRegs; ++r) {
-      const uint32_t i = (uint32_t)r * kScanThreads + threadIdx.x;
+      const uint32_t i = (uint32_t)r * NT + threadIdx.x;
       skey[r] = score_key(srow[i < a.n_samp ? i : a.n_samp - 1]);      // clamped, not predicated: the loads go out together
     }
-    thr_key = kth_lower_bound_key<kScanThreads, kSampRegs>(skey, a.n_samp, a.rho, lhist, fsh);
-  }
+    thr_key = kth_lower_bound_key<NT, kSampRegs>(skey, a.n_samp, a.rho, lhist, fsh);
+  };
+  const bool bound_first = (((blockIdx.y * gridDim.x + blockIdx.x) >> 8) & 1) == 0;
+  if (FILTER && bound_first) find_bound();
 
   const int64_t blk_row0 = (int64_t)blockIdx.x * a.rows_per_block;
   const int64_t left = a.n_mid - blk_row0;
@@ -115,7 +124,7 @@ __global__ __launch_bounds__(kScanThreads) void score_scan_kernel(ScanArgs a) {
   // paged: pages[i] = first row of page (pg0 + i) of the sequence, pg0 the page of the slice's first token
   int32_t* pages = (int32_t*)(lhist + (HIST ? kHistBins : FILTER ? kBinsPad + 40 : 0));
   const int64_t tok0 = a.first_tok + blk_row0;
-  if (PAGED) slice_pages_fill(pages, a.pt, a.page_lg, tok0, nrows, kScanThreads);
+  if (PAGED) slice_pages_fill(pages, a.pt, a.page_lg, tok0, nrows, NT);
   static_assert(RW <= 64, "a wave's tile lies in at most two pages");
 
   // heads start at different phases of their slices: the KV heads lie a power of two apart in a
@@ -155,6 +164,7 @@ __global__ __launch_bounds__(kScanThreads) void score_scan_kernel(ScanArgs a) {
 
   __syncthreads();
   if (FILTER) {
+    if (!bound_first) find_bound();
     // ordered compaction out of LDS: thread t owns rows [32t, 32t + 32) of the slice
     const int r0 = (int)threadIdx.x * 32;
     uint32_t mask = 0;
@@ -166,7 +176,7 @@ __global__ __launch_bounds__(kScanThreads) void score_scan_kernel(ScanArgs a) {
     }
     const uint32_t mine = (uint32_t)__popc(mask);
     uint32_t total;
-    uint32_t at = block_scan_incl<kScanThreads>(mine, fsh, total) - mine;
+    uint32_t at = block_scan_incl<NT>(mine, fsh, total) - mine;
     const int64_t seg = (int64_t)row_id * gridDim.x + blockIdx.x;
     uint2* out = a.cand + seg * a.rows_per_block;
     while (mask) {
@@ -179,13 +189,13 @@ __global__ __launch_bounds__(kScanThreads) void score_scan_kernel(ScanArgs a) {
   }
   float* out = a.scores + (int64_t)row_id * a.n_mid + blk_row0;
   if (a.stream_out) {
-    for (int r = threadIdx.x; r < nrows; r += kScanThreads) __builtin_nontemporal_store(stage[r], out + r);
+    for (int r = threadIdx.x; r < nrows; r += NT) __builtin_nontemporal_store(stage[r], out + r);
   } else {                                         // one round: the scores stay in cache for the top-k that follows
-    for (int r = threadIdx.x; r < nrows; r += kScanThreads) out[r] = stage[r];
+    for (int r = threadIdx.x; r < nrows; r += NT) out[r] = stage[r];
   }
   if (HIST) {
     uint32_t* gh = a.hist + (int64_t)row_id * kHistBins;
-    for (int b = threadIdx.x; b < kHistBins; b += kScanThreads) {
+    for (int b = threadIdx.x; b < kHistBins; b += NT) {
       const uint32_t c = lhist[b];
       if (c) atomicAdd(&gh[b], c);
     }
@@ -222,10 +232,11 @@ hipError_t launch_hp(const ScanArgs& a, dim3 grid, hipStream_t st) {
   const size_t lds = (size_t)a.rows_per_block * 4 + (MODE == kOutHist ? kHistBins * 4 : 0) +
                      (MODE == kOutFilter ? ((size_t)(a.rows_per_block >> 5) + 1 + kBinsPad + 40) * 4 : 0) +
                      (PAGED ? ((size_t)(a.rows_per_block >> a.page_lg) + 3) * 4 : 0);
-  auto kern = score_scan_kernel<T, D, U, MODE, PAGED>;
+  constexpr int NT = MODE == kOutFilter ? kFilterThreads : kScanThreads;
+  auto kern = score_scan_kernel<T, D, U, MODE, PAGED, NT>;
   hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(kern, grid, dim3(kScanThreads), lds, st, a);
+  hipLaunchKernelGGL(kern, grid, dim3(NT), lds, st, a);
   return hipGetLastError();
 }
 
@@ -292,7 +303,7 @@ hipError_t launch_score_scan(const Plan& pl, const void* q, int n_query, const v
 
 hipError_t launch_score_scan_filter(const Plan& pl, const void* q, const void* k_cache, const float* samp,
                                     uint2* cand, uint32_t* segcnt, hipStream_t st, const AppendJob* append) {
-  if (!pl.filter || pl.f_nsamp > (uint32_t)kSampRegs * kScanThreads) return hipErrorInvalidValue;
+  if (!pl.filter || pl.f_nsamp > (uint32_t)kFilterSampMax || pl.f_rpb > 32 * kFilterThreads) return hipErrorInvalidValue;
   ScanArgs a;
   a.ap = append_args(pl, append);
   a.k = k_cache; a.q = q; a.scores = nullptr; a.hist = nullptr;
