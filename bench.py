@@ -20,7 +20,7 @@ import time
 
 HBM_PEAK_GBPS = 8000.0      # MI355X published HBM3E bandwidth
 # Measured with rocprofv3 --pmc: fetched + written bytes per launch of the scan kernel, per workload.
-SCAN_TRAFFIC = {"cfg3_decode_1m_bf16": {"bytes": 2 * 1045670.6 * 1024 + 916.4 * 1024,
+SCAN_TRAFFIC = {"cfg3_decode_1m_bf16": {"bytes": 2 * 1045784.6 * 1024 + 928.1 * 1024,
                                         "source": "profiles/score_scan_cfg3_pmc.md"}}
 # Same for the other dominant kernels (profiles/vote_decode_cfg3_kernel_trace_pmc.md,
 # profiles/prefill_chunk_cfg4_kernel_trace_pmc.md, profiles/vote_prefill_cfg4_kernel_trace_pmc.md): fetched bytes per launch.
