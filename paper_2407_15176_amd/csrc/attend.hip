@@ -81,7 +81,7 @@ template <> struct Half<f16bits, 2> {
 template <typename T, int D, int GT, bool FUSED>
 __global__ __launch_bounds__(256) void attend_kernel(AttendArgs a) {
   constexpr int E = D / 32;
-  constexpr int UNR = 4;
+  constexpr int UNR = 2;                      // slots per 16-lane group in flight.  Measured at a million tokens (attention + combine by HIP events): 2: 27.6 us, 4: 28.6, 8: 33.4, 1: 30.7; reading the rotary table only every fourth turn: no gain
   typedef typename std::conditional<FUSED, T, float>::type KT;
 
   __shared__ float s_m[kGroupsPerBlock][GT];
