@@ -148,22 +148,40 @@ __global__ __launch_bounds__(64 * NW) void vote_gemm_kernel(VoteGemmArgs a) {
   auto dma_dst = [&](int buf, int i) -> uint32_t {           // LDS byte address of load i of this wave (wave-uniform)
     return (uint32_t)__builtin_amdgcn_readfirstlane((int)(lds_tiles + (uint32_t)buf * kTileBytes + (uint32_t)(i < kDmaEach ? i * NW + cw : 32 + (cw & 1)) * 1024u));
   };
-  // plain: a tile that is whole and reached without a page table (a compile-time yes skips both questions)
-  auto dma_tile = [&](auto plain, int64_t tile, int buf) __attribute__((always_inline)) {
-    if (decltype(plain)::value || (!a.pt && (tile + 1) * kTileKeys <= a.n_keys)) {
+  // whole: every row of the tile exists (a compile-time yes skips the question).  Through a page table a tile of
+  // 128 consecutive tokens lies in at most three pages (pages hold 64 tokens or more): their first rows are read
+  // with scalar loads, which the counter of the tile loads does not see, and a lane picks one by its token's page.
+  auto dma_tile = [&](auto whole, int64_t tile, int buf) __attribute__((always_inline)) {
+    if (!a.pt && (decltype(whole)::value || (tile + 1) * kTileKeys <= a.n_keys)) {
       const char* base = kmid + tile * kTileKeys * row_bytes;      // workgroup-uniform
 #pragma unroll
       for (int i = 0; i < kDma; ++i)
         asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                      :: "s"(dma_dst(buf, i)), "v"(voff[i]), "s"(base) : "memory");
     } else {                                                 // through the page table, or a ragged last tile
+      const int64_t tok0 = a.first_tok + tile * kTileKeys, tok_last = a.first_tok + a.n_keys - 1;
+      int64_t pg[3] = {0, 0, 0};
+      int64_t pg0 = 0;
+      if (a.pt) {
+        pg0 = tok0 >> a.page_lg;
+        const int64_t pg_last = tok_last >> a.page_lg;
+        // workgroup-uniform, and read as constant memory so that the loads are scalar ones (the kernel never writes the table)
+        typedef const __attribute__((address_space(4))) int32_t* const_i32;
+        const const_i32 pt = (const_i32)(uintptr_t)a.pt;
+#pragma unroll
+        for (int i = 0; i < 3; ++i) pg[i] = (int64_t)pt[pg0 + i < pg_last ? pg0 + i : pg_last] << a.page_lg;
+      }
 #pragma unroll
       for (int i = 0; i < kDma; ++i) {
         const int slot = (i < kDmaEach ? i * NW + cw : 32 + (cw & 1)) * 64 + lane;
         const int row = slot / 17, piece = slot % 17;
-        int64_t key = tile * kTileKeys + row;
-        if (key >= a.n_keys) key = a.n_keys - 1;             // rows past the end repeat the last key; their scores are dropped
-        const int64_t mrow = a.pt ? paged_row(a.pt, a.page_lg, a.first_tok + key) : a.first_tok + key;
+        int64_t tok = tok0 + row;
+        if (tok > tok_last) tok = tok_last;                  // rows past the end repeat the last key; their scores are dropped
+        int64_t mrow = tok;
+        if (a.pt) {
+          const int64_t d = (tok >> a.page_lg) - pg0;
+          mrow = (d == 0 ? pg[0] : d == 1 ? pg[1] : pg[2]) | (tok & (((int64_t)1 << a.page_lg) - 1));
+        }
         const char* src = khead + mrow * row_bytes + (piece < 16 ? piece : 15) * 16;
         asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
                      :: "s"(dma_dst(buf, i)), "v"(src) : "memory");
@@ -242,9 +260,8 @@ __global__ __launch_bounds__(64 * NW) void vote_gemm_kernel(VoteGemmArgs a) {
   };
 
   // One tile.
-  // bc: buffer of tile t.  `full`: tiles t + 1 .. t + 3 all exist, whole, and no page table is in the way, so
-  // the step has no branch but the rare insertions and the tile requests are scheduled among the matrix
-  // instructions.
+  // bc: buffer of tile t.  `full`: tiles t + 1 .. t + 3 all exist and are whole, so the step has no branch but
+  // the rare insertions (and the one on the page table) and waits only for the tile due.
   auto step = [&](auto ragged, auto full, int64_t t, int bc) __attribute__((always_inline)) {
     constexpr bool kFull = decltype(full)::value;
     const int bn = (bc + 1) & (kBufs - 1);                  // buffer of tile t + 1
@@ -323,11 +340,9 @@ __global__ __launch_bounds__(64 * NW) void vote_gemm_kernel(VoteGemmArgs a) {
   int bc = 0;
   int64_t t = 0;
   // the long middle of the walk: a loop of its own with a single path through it
-  if (!a.pt) {
-    for (; t + 3 < n_tiles; ++t) {
-      step(no, yes, t, bc);
-      bc = (bc + 1) & (kBufs - 1);
-    }
+  for (; t + 3 < n_tiles; ++t) {
+    step(no, yes, t, bc);
+    bc = (bc + 1) & (kBufs - 1);
   }
   for (; t < n_tiles; ++t) {
     if (ragged_last && t == n_tiles - 1) step(yes, no, t, bc);
