@@ -26,7 +26,8 @@ def _draw(seed: int):
     n_mid = int(r.choice([0, 1, 5, 63, 64, 65, 1000, 4097, 8193, 20000]))
     M = int(r.choice([1, 1, 1, 2, 5, 33])) if n_mid > 0 else int(r.choice([1, 3, 40]))
     M = min(M, n_local) if n_mid > 0 else M
-    n_ctx = max(n_sink + n_local + n_mid if n_mid > 0 else int(r.integers(1, n_sink + n_local + 1)), M)
+    n_ctx = n_sink + n_local + n_mid if n_mid > 0 else int(r.integers(1, n_sink + n_local + 1))
+    M = min(M, n_ctx)                                   # an empty middle takes any M <= N (the first chunk of the prefilling phase)
     top_k = int(r.choice([0, 1, 3, 64, 500, 5000]))
     base = wl.CONFIGS[2] if dtype != "f32" else wl.CONFIGS[1]
     w = base.scaled(dtype=dtype, head_dim=D, n_q_heads=G * Hkv, n_kv_heads=Hkv, n_ctx=n_ctx, n_query=M, n_sink=n_sink,
