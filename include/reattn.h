@@ -62,9 +62,12 @@ typedef enum {
  * step, the matrix cores (f16 MFMA instructions) for chunks and for the vote selection. */
 typedef enum { REATTN_F32 = 0, REATTN_BF16 = 1, REATTN_F16 = 2 } reattn_dtype;
 
-/* How the G heads of one GQA group are combined into one score per KV head.
- * (The paper's own way, votes over per-head lists, is the reattn_vote_* family below.) */
-typedef enum { REATTN_AGG_SUM = 0 } reattn_agg;
+/* How the G heads of one GQA group are combined into one score per KV head (paper Eq. 2 scores one head;
+ * the paper's own way of combining heads, votes over per-head lists, is the reattn_vote_* family below, which
+ * ignores this field).  REATTN_AGG_SUM: sum_g q_g . k, every path.  REATTN_AGG_MAX: max_g q_g . k; the scores
+ * are then formed by the streaming scan for every M (the matrix-core contraction and the filter route score
+ * group sums and are not taken), everything behind the scores is the same. */
+typedef enum { REATTN_AGG_SUM = 0, REATTN_AGG_MAX = 1 } reattn_agg;
 
 typedef struct reattn_params {
   int32_t n_q_heads;    /* Hq, multiple of n_kv_heads, G <= 16 */

@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libreattn.so")
 
 F32, BF16, F16 = 0, 1, 2
 _DTYPE_CODE = {"f32": F32, "bf16": BF16, "f16": F16}
-AGG_SUM = 0
+AGG_SUM, AGG_MAX = 0, 1
 ROUTE_AUTO, ROUTE_FILTER, ROUTE_SCORES = 0, 1, 2
 
 OK = 0

@@ -18,9 +18,13 @@ inline bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
 // Decides whether a decode step takes the filter path (no score array) and fixes its geometry: the sampling
 // step and rank, the scan's slices.  Everything follows from the params alone (the scan is cut for the 256
 // compute units of the part this library is built for), so the workspace layout never depends on a device.
+static_assert(kAggSum == REATTN_AGG_SUM && kAggMax == REATTN_AGG_MAX && kF32 == REATTN_F32 && kBF16 == REATTN_BF16 && kF16 == REATTN_F16,
+              "the kernels' constants are the header's");
+
 bool filter_plan(Plan* pl, int route) {
   pl->filter = false;
   if (pl->M != 1 || pl->n_mid <= kRowMax || pl->k_eff <= 0 || route == REATTN_ROUTE_SCORES) return false;
+  if (pl->agg != REATTN_AGG_SUM) return false;        // the sampling and the exact redo score group sums
   // Measured on MI355X: the route costs a sampling launch, ~5 us at the head of every scan workgroup and a
   // one-workgroup pick (~37 us in all) against ~40 us for histogram + select + refine + emit over the written
   // scores; it wins once the scores no longer fit one round of workgroups (their bursts then fall into the
@@ -54,7 +58,7 @@ int make_plan(const reattn_params* p, Plan* out) {
   if (p->n_q_heads / p->n_kv_heads > 16) return REATTN_ERR_SHAPE;
   if (p->head_dim != 64 && p->head_dim != 128) return REATTN_ERR_SHAPE;
   if (p->dtype != REATTN_F32 && p->dtype != REATTN_BF16 && p->dtype != REATTN_F16) return REATTN_ERR_DTYPE;
-  if (p->agg != REATTN_AGG_SUM) return REATTN_ERR_DTYPE;
+  if (p->agg != REATTN_AGG_SUM && p->agg != REATTN_AGG_MAX) return REATTN_ERR_DTYPE;
   if (p->n_ctx < 1 || p->n_ctx > 0x7fffffffLL) return REATTN_ERR_RANGE;
   if (p->n_query < 1 || p->n_query > p->n_ctx || p->n_query > 65535) return REATTN_ERR_RANGE;
   if (p->n_sink < 0 || p->n_local < 1 || p->top_k < 0) return REATTN_ERR_RANGE;
@@ -64,7 +68,7 @@ int make_plan(const reattn_params* p, Plan* out) {
   if (p->route != REATTN_ROUTE_AUTO && p->route != REATTN_ROUTE_FILTER && p->route != REATTN_ROUTE_SCORES) return REATTN_ERR_RANGE;
 
   pl.Hq = p->n_q_heads; pl.Hkv = p->n_kv_heads; pl.D = p->head_dim; pl.G = pl.Hq / pl.Hkv;
-  pl.dtype = p->dtype; pl.M = p->n_query; pl.N = p->n_ctx;
+  pl.dtype = p->dtype; pl.M = p->n_query; pl.N = p->n_ctx; pl.agg = p->agg;
   pl.s_eff = p->n_sink < pl.N ? p->n_sink : pl.N;
   pl.l_eff = p->n_local < pl.N - pl.s_eff ? p->n_local : pl.N - pl.s_eff;
   pl.n_mid = pl.N - pl.s_eff - pl.l_eff;
@@ -150,6 +154,7 @@ int make_plan(const reattn_params* p, Plan* out) {
   pl.off_qsplit = off; off += up(pl.M > 1 ? score_gemm_qsplit_bytes(pl) : 0);
   // fused prefill selection: MFMA scores filtered against sampled thresholds
   pl.fused_prefill = pl.M > 1 && (pl.dtype == REATTN_BF16 || pl.dtype == REATTN_F16) && pl.D == 128 && pl.k_eff > 0 &&
+                     pl.agg == REATTN_AGG_SUM &&
                      cand_topk_lds(pl) <= (size_t)128 * 1024;
   if (pl.fused_prefill) {
     int64_t stride, n_s; uint32_t rho, cap;
@@ -192,7 +197,10 @@ int bind_ws(const Plan& pl, void* ws, size_t ws_bytes, Ws* w) {
 }
 
 // M > 1 on 16-bit storage / D = 128 takes the MFMA kernel; everything else streams per query.
-inline bool use_mfma(const Plan& pl) { return pl.M > 1 && (pl.dtype == REATTN_BF16 || pl.dtype == REATTN_F16) && pl.D == 128; }
+// (the matrix-core contraction scores the group SUM, (sum_g q_g) . k: max aggregation streams too)
+inline bool use_mfma(const Plan& pl) {
+  return pl.M > 1 && (pl.dtype == REATTN_BF16 || pl.dtype == REATTN_F16) && pl.D == 128 && pl.agg == REATTN_AGG_SUM;
+}
 
 inline int hip_rc(hipError_t e) { return e == hipSuccess ? REATTN_OK : REATTN_ERR_HIP; }
 

@@ -23,10 +23,12 @@ __host__ __device__ inline int rope_rows_hi(int S) { return (S + kRopeLo - 1) / 
 
 // storage dtype codes as in reattn_dtype
 constexpr int kF32 = 0, kBF16 = 1, kF16 = 2;
+constexpr int kAggSum = 0, kAggMax = 1;       // reattn_agg
 inline int64_t elem_bytes(int dtype) { return dtype == kF32 ? 4 : 2; }
 
 struct Plan {
   int Hq, Hkv, D, G, dtype, M;
+  int agg;                        // reattn_agg: how the G heads of a group become one score
   int64_t N, s_eff, l_eff, n_mid;
   int k_eff, S;
   int64_t ksh, kst, vsh, vst;     // strides in elements

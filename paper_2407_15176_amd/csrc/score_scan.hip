@@ -36,6 +36,7 @@ struct ScanArgs {
   int64_t ksh, kst;     // key strides in elements
   int64_t n_mid, first_tok;
   int Hq, Hkv, G;
+  int agg_max;          // REATTN_AGG_MAX: largest per-head dot product instead of their sum (MAXAGG kernels only)
   int rows_per_block;
   int stream_out;       // scores leave with non-temporal stores (several rounds of workgroups: a round's burst
                         // falls into the next round's reads, and ordinary stores would cost those ~9 %)
@@ -62,7 +63,7 @@ constexpr int kFilterThreads = 512;            // filter mode: two workgroups pe
 
 // PAGED: the rows of a workgroup's slice are found through the page table; the few entries the slice
 // spans are copied into LDS first, so a row costs one LDS read and two integer instructions more.
-template <typename T, int D, int U, int MODE, bool PAGED = false, int NT = kScanThreads>
+template <typename T, int D, int U, int MODE, bool PAGED = false, int NT = kScanThreads, bool MAXAGG = false>
 __global__ __launch_bounds__(NT) void score_scan_kernel(ScanArgs a) {
   constexpr bool HIST = MODE == kOutHist, FILTER = MODE == kOutFilter;
   constexpr int kSampRegs = kFilterSampMax / NT;     // sampled scores a thread holds while the bound is found
@@ -95,7 +96,7 @@ __global__ __launch_bounds__(NT) void score_scan_kernel(ScanArgs a) {
 
   // The group's query rows, summed in fp32: this lane's EPL channels.
   float qv[EPL];
-  group_query<T, D>(a.q, qi, h, a.Hq, a.G, sub, qv);
+  if (!MAXAGG) group_query<T, D>(a.q, qi, h, a.Hq, a.G, sub, qv);
 
   // filter mode: the lower bound of the row's k-th score, from the sampled scores (every workgroup of the
   // row finds the same value; the sample is 36 KiB out of L2)
@@ -125,6 +126,18 @@ __global__ __launch_bounds__(NT) void score_scan_kernel(ScanArgs a) {
   int32_t* pages = (int32_t*)(lhist + (HIST ? kHistBins : FILTER ? kBinsPad + 40 : 0));
   const int64_t tok0 = a.first_tok + blk_row0;
   if (PAGED) slice_pages_fill(pages, a.pt, a.page_lg, tok0, nrows, NT);
+  // max aggregation: the group's query rows, fp32, behind everything else in LDS
+  float* qs = (float*)(pages + (PAGED ? (a.rows_per_block >> a.page_lg) + 3 : 0));
+  float qr[MAXAGG ? 4 : 1][EPL];                        // ... or in registers when the group has at most four heads
+  const bool few = a.G <= 4;
+  if (MAXAGG) {
+    if (few) {
+      group_rows_to_regs<T, D>(a.q, qi, h, a.Hq, a.G, sub, qr);
+    } else {
+      group_rows_to_lds<T, D>(a.q, qi, h, a.Hq, a.G, qs, NT);
+      __syncthreads();
+    }
+  }
   static_assert(RW <= 64, "a wave's tile lies in at most two pages");
 
   // heads start at different phases of their slices: the KV heads lie a power of two apart in a
@@ -147,12 +160,17 @@ __global__ __launch_bounds__(NT) void score_scan_kernel(ScanArgs a) {
     float mine = 0.f;
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      float x[EPL];
-      Store<T>::widen(d[u], x);
-      float s = 0.f;
+      float s;
+      if (MAXAGG) {
+        s = few ? row_dot_max4<T, D>(d[u], qr) : row_dot_max<T, D>(d[u], qs, a.G, sub);
+      } else {
+        float x[EPL];
+        Store<T>::widen(d[u], x);
+        s = 0.f;
 #pragma unroll
-      for (int e = 0; e < EPL; ++e) s = fmaf(x[e], qv[e], s);
-      s = group_sum<LPR>(s);
+        for (int e = 0; e < EPL; ++e) s = fmaf(x[e], qv[e], s);
+        s = group_sum<LPR>(s);
+      }
       mine = (sub == u) ? s : mine;            // lane (grp, sub) keeps the result of load `sub`
     }
     const int r = t + sub * RPL + grp;
@@ -226,18 +244,26 @@ __global__ __launch_bounds__(kScanThreads) void read_probe_kernel(const u32x4* _
   if (acc == 0x9e3779b9u && sink) sink[0] = acc;   // keeps the loads alive; practically never taken
 }
 
-template <typename T, int D, int MODE, bool PAGED>
-hipError_t launch_hp(const ScanArgs& a, dim3 grid, hipStream_t st) {
+template <typename T, int D, int MODE, bool PAGED, bool MAXAGG>
+hipError_t launch_hpa(const ScanArgs& a, dim3 grid, hipStream_t st) {
   constexpr int U = 8;
   const size_t lds = (size_t)a.rows_per_block * 4 + (MODE == kOutHist ? kHistBins * 4 : 0) +
                      (MODE == kOutFilter ? ((size_t)(a.rows_per_block >> 5) + 1 + kBinsPad + 40) * 4 : 0) +
-                     (PAGED ? ((size_t)(a.rows_per_block >> a.page_lg) + 3) * 4 : 0);
+                     (PAGED ? ((size_t)(a.rows_per_block >> a.page_lg) + 3) * 4 : 0) +
+                     (MAXAGG ? (size_t)a.G * D * 4 : 0);
   constexpr int NT = MODE == kOutFilter ? kFilterThreads : kScanThreads;
-  auto kern = score_scan_kernel<T, D, U, MODE, PAGED, NT>;
+  auto kern = score_scan_kernel<T, D, U, MODE, PAGED, NT, MAXAGG>;
   hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(kern, grid, dim3(NT), lds, st, a);
   return hipGetLastError();
+}
+
+// The filter route is a sum-aggregation path only (its plan is not made for REATTN_AGG_MAX).
+template <typename T, int D, int MODE, bool PAGED>
+hipError_t launch_hp(const ScanArgs& a, dim3 grid, hipStream_t st) {
+  if (MODE != kOutFilter && a.agg_max) return launch_hpa<T, D, MODE == kOutFilter ? kOutScores : MODE, PAGED, true>(a, grid, st);
+  return launch_hpa<T, D, MODE, PAGED, false>(a, grid, st);
 }
 
 template <typename T, int D>
@@ -287,7 +313,9 @@ hipError_t launch_score_scan(const Plan& pl, const void* q, int n_query, const v
   a.k = k_cache; a.q = q; a.scores = scores; a.hist = hist;
   a.ksh = pl.ksh; a.kst = pl.kst; a.n_mid = pl.n_mid; a.first_tok = pl.s_eff;
   a.Hq = pl.Hq; a.Hkv = pl.Hkv; a.G = pl.G; a.pt = pl.pt; a.page_lg = pl.page_lg;
-  a.rows_per_block = scan_rows_per_block(pl.n_mid, (int64_t)pl.Hkv * n_query, 0);
+  a.agg_max = pl.agg == kAggMax ? 1 : 0;
+  // max aggregation keeps G * D floats of query rows in LDS behind the parked scores
+  a.rows_per_block = scan_rows_per_block(pl.n_mid, (int64_t)pl.Hkv * n_query, a.agg_max ? kScanMaxRows - 4096 : 0);
   dim3 grid((unsigned)((pl.n_mid + a.rows_per_block - 1) / a.rows_per_block),
             (unsigned)(pl.Hkv * n_query));
   a.stream_out = (int64_t)grid.x * grid.y > 320 ? 1 : 0;   // more workgroups than one round over the chip
@@ -309,7 +337,7 @@ hipError_t launch_score_scan_filter(const Plan& pl, const void* q, const void* k
   a.k = k_cache; a.q = q; a.scores = nullptr; a.hist = nullptr;
   a.ksh = pl.ksh; a.kst = pl.kst; a.n_mid = pl.n_mid; a.first_tok = pl.s_eff;
   a.Hq = pl.Hq; a.Hkv = pl.Hkv; a.G = pl.G; a.pt = pl.pt; a.page_lg = pl.page_lg;
-  a.rows_per_block = pl.f_rpb; a.stream_out = 0;
+  a.rows_per_block = pl.f_rpb; a.stream_out = 0; a.agg_max = 0;
   a.samp = samp; a.samp_stride = pl.f_samp_stride; a.n_samp = pl.f_nsamp; a.rho = pl.f_rho;
   a.cand = cand; a.segcnt = segcnt;
   const dim3 grid((unsigned)pl.f_nb, (unsigned)pl.Hkv);

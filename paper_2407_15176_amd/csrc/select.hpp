@@ -63,6 +63,59 @@ __device__ __forceinline__ float row_dot(const u32x4& d, const float* qv) {
   return group_sum<D / EPL>(s);
 }
 
+// Max aggregation (REATTN_AGG_MAX): the score of a key is the largest of its G per-head dot products, so the
+// heads cannot be summed first.  The group's query rows sit in LDS as fp32, qs[g * D + c].
+template <typename T, int D>
+__device__ __forceinline__ void group_rows_to_lds(const void* q, int qi, int h, int Hq, int G, float* qs, int n_threads) {
+  const int64_t q0 = ((int64_t)qi * Hq + (int64_t)h * G) * D;
+  for (int i = threadIdx.x; i < G * D; i += n_threads) qs[i] = Store<T>::one(q, q0 + i);
+}
+template <typename T, int D>
+__device__ __forceinline__ float row_dot_max(const u32x4& d, const float* qs, int G, int sub) {
+  constexpr int EPL = Store<T>::kPerLoad;
+  float x[EPL];
+  Store<T>::widen(d, x);
+  float best = 0.f;
+  for (int g = 0; g < G; ++g) {
+    const float* qg = qs + g * D + sub * EPL;
+    float s = 0.f;
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) s = fmaf(x[e], qg[e], s);
+    s = group_sum<D / EPL>(s);
+    best = g == 0 ? s : fmaxf(best, s);
+  }
+  return best;
+}
+
+// The same out of registers for groups of up to four heads (the usual GQA groups): qr[g][e], rows past G unused.
+template <typename T, int D>
+__device__ __forceinline__ void group_rows_to_regs(const void* q, int qi, int h, int Hq, int G, int sub, float (*qr)[Store<T>::kPerLoad]) {
+  constexpr int EPL = Store<T>::kPerLoad;
+#pragma unroll
+  for (int g = 0; g < 4; ++g) {
+    const int gg = g < G ? g : G - 1;
+    const int64_t qoff = ((int64_t)qi * Hq + (int64_t)h * G + gg) * D + sub * EPL;
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) qr[g][e] = Store<T>::one(q, qoff + e);
+  }
+}
+template <typename T, int D>
+__device__ __forceinline__ float row_dot_max4(const u32x4& d, const float (*qr)[Store<T>::kPerLoad]) {
+  constexpr int EPL = Store<T>::kPerLoad;
+  float x[EPL];
+  Store<T>::widen(d, x);
+  float best = 0.f;
+#pragma unroll
+  for (int g = 0; g < 4; ++g) {                      // rows past G repeat the last head: the maximum does not change
+    float s = 0.f;
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) s = fmaf(x[e], qr[g][e], s);
+    s = group_sum<D / EPL>(s);
+    best = g == 0 ? s : fmaxf(best, s);
+  }
+  return best;
+}
+
 // ---- LDS histograms of 2048 bins -----------------------------------------------------------------
 // A thread that owns consecutive bins (or 32 consecutive bitmap words) would meet the other owners in
 // every bank it touches (64 banks of 4 bytes): one pad word per 8 bins / per 32 words makes the owners'

@@ -23,9 +23,9 @@ TIE_BAND = 1e-3
 OUT_TOL = {"bf16": 2e-2, "f32": 1e-4, "f16": 1e-3}
 
 
-def oracle_shape(w: wl.Workload) -> ro.Shape:
+def oracle_shape(w: wl.Workload, agg: int = ro.AGG_SUM) -> ro.Shape:
     return ro.Shape(w.n_q_heads, w.n_kv_heads, w.head_dim, w.dtype, w.n_ctx, w.n_sink, w.n_local,
-                    w.top_k, w.rope_theta)
+                    w.top_k, w.rope_theta, agg=agg)
 
 
 def host_inputs(t: dict):
@@ -62,10 +62,10 @@ def check_index_sets(gpu_idx: np.ndarray, ora_idx: np.ndarray, ora_scores: np.nd
 
 
 def check_layer(w: wl.Workload, t: dict, gpu_out: torch.Tensor, gpu_idx: torch.Tensor,
-                q_rows=None):
+                q_rows=None, agg: int = ro.AGG_SUM):
     """Full comparison of one decode step / prefill chunk.  q_rows: subset of query rows the
     oracle evaluates (None = all)."""
-    sh = oracle_shape(w)
+    sh = oracle_shape(w, agg)
     q, k, v = host_inputs(t)
     M = w.n_query
     rows = np.arange(M) if q_rows is None else np.asarray(q_rows)
@@ -98,8 +98,10 @@ def check_layer(w: wl.Workload, t: dict, gpu_out: torch.Tensor, gpu_idx: torch.T
     return {"rows_differ": differ, "max_abs_err": float(err), "max_abs_err_own_set": float(err2)}
 
 
-def run_layer(w: wl.Workload, t: dict):
+def run_layer(w: wl.Workload, t: dict, agg: int = B.AGG_SUM, route: int = 0):
     p = B.Params.from_workload(w)
+    p.agg = agg
+    p.route = route
     ws = B.alloc_workspace(p)
     fn = B.decode_step if w.n_query == 1 else B.prefill_chunk
     out, idx = fn(p, t["q"], t["k"], t["v"], ws)

@@ -233,3 +233,16 @@ def test_static_entry_point_rejects_steps_past_its_scratch_on_the_host():
     cp = good(n_query=2).c()
     assert lib.reattn_decode_step_static(C.byref(cp), one, one, one, None, one, None) == B.ERR_RANGE
     assert "scratch" in B.status_string(B.ERR_STATIC_LIMIT)
+
+
+def test_both_aggregations_validate():
+    """REATTN_AGG_SUM and REATTN_AGG_MAX are the reattn_agg values; workspace sizes do not depend on the choice
+    except where max aggregation leaves the matrix-core chunk path (it then needs no split-query buffers)."""
+    from dataclasses import replace
+    from paper_2407_15176_amd import workloads as wl
+    p = B.Params.from_workload(wl.CONFIGS[2])
+    for agg in (B.AGG_SUM, B.AGG_MAX):
+        q = replace(p, agg=agg)
+        assert B.validate(q) == B.OK
+        assert B.workspace_bytes(q) > 0
+    assert B.workspace_bytes(replace(p, agg=B.AGG_MAX)) == B.workspace_bytes(p)      # a decode step: the same plan but the route

@@ -326,15 +326,17 @@ def test_paged_filter_route_equals_contiguous_and_oracle(name, ps):
 
 # ------------------------------------------------------------ paged calls against the oracle itself
 # (the oracle reads the contiguous cache the pools were scattered from: t["k"], t["v"])
+@pytest.mark.parametrize("agg", [B.AGG_SUM, B.AGG_MAX])
 @pytest.mark.parametrize("name", ["bf16_d128_g4", "f32_d64_g4", "f16_d128_g3"])
-def test_paged_decode_step_against_oracle(name):
+def test_paged_decode_step_against_oracle(name, agg):
     from tests import parity as P
     w, ps = CASES[name]
     t = wl.generate(w, "cuda")
     p, kp, vp, _ = _paged(w, t, ps, seed=31)
+    p = replace(p, agg=agg)
     out, idx = B.decode_step(p, t["q"], kp, vp, B.alloc_workspace(p), want_idx=True)
     torch.cuda.synchronize()
-    P.check_layer(w, t, out, idx)
+    P.check_layer(w, t, out, idx, agg=agg)
 
 
 @pytest.mark.parametrize("name", ["bf16_mfma", "f32_scan"])

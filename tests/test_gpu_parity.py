@@ -496,3 +496,61 @@ def test_decode_filter_route_is_deterministic_and_agrees_with_the_score_route():
     out3, idx3 = B.decode_step(p, t["q"], t["k"], t["v"], B.alloc_workspace(p))
     torch.cuda.synchronize()
     assert torch.equal(idx1, idx3) and torch.equal(out1, out3)        # the same scores, the same tie rule
+
+
+# ------------------------------------------------------------------- REATTN_AGG_MAX
+# (largest per-head dot product of a GQA group instead of their sum: the oracle's RO_AGG_MAX)
+@pytest.mark.parametrize("name", list(SMALL))
+def test_score_max_aggregation_matches_oracle(name):
+    from dataclasses import replace
+    w = SMALL[name]
+    t = gen(w)
+    p = replace(B.Params.from_workload(w), agg=B.AGG_MAX)
+    sc = B.score(p, t["q"], t["k"])
+    torch.cuda.synchronize()
+    q, k, _ = P.host_inputs(t)
+    want = ro.score(P.oracle_shape(w, ro.AGG_MAX), q, k)
+    got = sc.cpu().numpy().astype(np.float64)
+    assert got.shape == want.shape
+    assert np.abs(got - want).max() <= 2e-6 * np.abs(want).max() + 1e-6
+    if w.n_q_heads > w.n_kv_heads:                        # and it is not the sum
+        assert np.abs(want - ro.score(P.oracle_shape(w), q, k)).max() > 1e-3
+
+
+@pytest.mark.parametrize("name", list(SMALL))
+def test_decode_step_max_aggregation_matches_oracle(name):
+    w = SMALL[name]
+    t = gen(w)
+    out, idx = P.run_layer(w, t, agg=B.AGG_MAX)
+    P.check_layer(w, t, out, idx, agg=ro.AGG_MAX)
+
+
+@pytest.mark.parametrize("name,M", [("f32_d64_g4", 5), ("bf16_d128_g4", 64), ("f16_d128_g4", 33), ("f16_d64_g3", 6)])
+def test_prefill_chunk_max_aggregation_matches_oracle(name, M):
+    """Chunks stream the scan once per query row under max aggregation (the matrix-core contraction scores group sums)."""
+    w = SMALL[name].scaled(n_query=M, n_needles=0, scale_q=True)
+    t = gen(w)
+    out, idx = P.run_layer(w, t, agg=B.AGG_MAX)
+    P.check_layer(w, t, out, idx, agg=ro.AGG_MAX)
+
+
+@pytest.mark.parametrize("route", [B.ROUTE_AUTO, B.ROUTE_FILTER])
+def test_decode_step_max_aggregation_long_middle_takes_the_score_route(route):
+    """Past 65,536 middle tokens (and past the filter route's automatic threshold) max aggregation still selects over
+    written scores; a forced filter route is not an error, it is not taken."""
+    w = wl.CONFIGS[2].scaled(n_ctx=600_011, n_local=1000, top_k=2048, max_position=0)
+    t = gen(w)
+    from dataclasses import replace
+    p = replace(B.Params.from_workload(w), agg=B.AGG_MAX, route=route)
+    ws = B.alloc_workspace(p)
+    out, idx = B.decode_step(p, t["q"], t["k"], t["v"], ws)
+    torch.cuda.synchronize()
+    assert B.redo_list(p, ws) is None                     # no filter route, no redo list
+    P.check_layer(w, t, out, idx, agg=ro.AGG_MAX)
+
+
+def test_decode_step_max_aggregation_sixteen_heads_per_group():
+    w = wl.CONFIGS[1].scaled(n_ctx=7_013, head_dim=128, n_q_heads=16, n_kv_heads=1, n_local=64, top_k=300, max_position=0)
+    t = gen(w)
+    out, idx = P.run_layer(w, t, agg=B.AGG_MAX)
+    P.check_layer(w, t, out, idx, agg=ro.AGG_MAX)

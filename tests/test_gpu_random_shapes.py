@@ -48,6 +48,15 @@ def test_layer_random_shape(seed):
     P.check_layer(w, t, out, idx)
 
 
+@pytest.mark.parametrize("seed", range(0, 72, 3))
+def test_layer_random_shape_max_aggregation(seed):
+    """The same draws with the largest per-head score of a group instead of the sum (REATTN_AGG_MAX)."""
+    w, _ = _draw(seed)
+    t = wl.generate(w, "cuda")
+    out, idx = P.run_layer(w, t, agg=B.AGG_MAX)
+    P.check_layer(w, t, out, idx, agg=B.AGG_MAX)
+
+
 @pytest.mark.parametrize("seed", range(72))
 def test_vote_layer_random_shape(seed):
     w, v = _draw(seed)
