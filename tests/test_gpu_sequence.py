@@ -39,16 +39,16 @@ CASES = {
 }
 
 
-@pytest.mark.parametrize("name", list(CASES))
-def test_sequence_topk_matches_oracle_loop(name):
+@pytest.mark.parametrize("name,agg", [(n, B.AGG_SUM) for n in CASES] + [(n, B.AGG_MAX) for n in list(CASES)[:2]])
+def test_sequence_topk_matches_oracle_loop(name, agg):
     w, chunk = CASES[name]
     q, k_new, v_new = _sequence_inputs(w, 1)
-    p = B.Params.from_workload(replace(w, n_query=1))
+    p = replace(B.Params.from_workload(replace(w, n_query=1)), agg=agg)
     res = B.prefill_sequence(p, chunk, q, k_new, v_new)
     torch.cuda.synchronize()
     assert torch.equal(res["k_cache"], k_new.transpose(0, 1).contiguous())       # the append is a plain copy
     assert torch.equal(res["v_cache"], v_new.transpose(0, 1).contiguous())
-    sh = P.oracle_shape(w)
+    sh = P.oracle_shape(w, agg)
     qh, kh, vh = wl.to_numpy_store(q), wl.to_numpy_store(k_new), wl.to_numpy_store(v_new)
     want = ro.prefill_sequence(sh, qh, kh, vh, chunk)
     assert [(a, b) for a, b, _ in want["chunks"]] == res["chunks"]
