@@ -617,7 +617,7 @@ ScanGeom scan_geom(const Plan& pl, int n_query, int kt) {
   ScanGeom g;
   g.mfma = pl.dtype != kF32 && pl.D == 128;
   g.gemm = g.mfma && n_query * pl.G > 32;              // more columns than one streaming pass holds
-  if (g.gemm) {                                        // tiled contraction: every key is read once per 256 columns
+  if (g.gemm) {                                        // tiled contraction: every key is read once per workgroup of 256 or 512 columns
     g.nb = 0; g.q_per_pass = n_query; g.n_pass = 1; g.rpb = 0;
     g.n_wg = vote_gemm_splits(pl, n_query, kt);
     return g;

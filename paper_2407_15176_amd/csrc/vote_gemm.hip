@@ -69,7 +69,7 @@ __device__ __forceinline__ uint64_t vg_composite(float score, uint32_t pos) {
 // NCB: column blocks of 32 per wave; NW: waves of the workgroup (8: two per SIMD with half the register file each;
 // 4: one per SIMD with all of it).  The workgroup owns NCB * 32 * NW columns; every wave walks all four key blocks
 // of a tile for its own NCB column blocks.  The library launches NW = 8 with NCB = 2 (NCB = 1 for lists of 8, whose
-// floor merge would not fit LDS, and for chunks of at most 256 columns).
+// floor merge would not fit LDS, and for chunks of at most 2048 columns per KV head).
 template <int KT, bool F16, int NCB, int NW>
 __global__ __launch_bounds__(64 * NW) void vote_gemm_kernel(VoteGemmArgs a) {
   constexpr int kTileCols = NCB * 32 * NW;
