@@ -102,7 +102,7 @@ typedef struct reattn_params {
    * workgroup per KV head picks the k best of them exactly (rows whose bound missed are redone exactly).
    * REATTN_ROUTE_AUTO (0) takes the filter from 2^22 scored keys per step (n_mid * Hkv) upwards.  A tuning
    * and testing aid: shapes the filter does not take (short middles, top_k so large that the kept pairs
-   * would outgrow the pick) use the scores whatever is asked for. */
+   * would outgrow the pick, REATTN_AGG_MAX) use the scores whatever is asked for. */
   int32_t route;
 } reattn_params;
 typedef enum { REATTN_ROUTE_AUTO = 0, REATTN_ROUTE_FILTER = 1, REATTN_ROUTE_SCORES = 2 } reattn_route;
