@@ -193,19 +193,21 @@ def test_paged_prefill_chunk_equals_contiguous(name):
     assert torch.equal(out0, out1)
 
 
-@pytest.mark.parametrize("M,dtype", [(6, "bf16"), (40, "bf16"), (300, "f16"), (3, "f32")])
-def test_paged_vote_chunk_equals_contiguous(M, dtype):
-    """6 query rows take the streaming scan with two column blocks, 40 and 300 the tiled contraction and the
-    shared-set attention, fp32 the vector-ALU scan."""
+@pytest.mark.parametrize("M,dtype,ps", [(6, "bf16", 128), (40, "bf16", 128), (300, "f16", 128), (3, "f32", 128),
+                                        (600, "bf16", 64), (600, "f16", 256)])
+def test_paged_vote_chunk_equals_contiguous(M, dtype, ps):
+    """6 query rows take the streaming scan with two column blocks, 40 and 300 the tiled contraction (256-column
+    workgroups) and the shared-set attention, 600 the 512-column workgroups (a key tile of 128 tokens then lies in up
+    to three 64-token pages), fp32 the vector-ALU scan."""
     base = wl.CONFIGS[4] if dtype != "f32" else wl.CONFIGS[1]
-    w = base.scaled(dtype=dtype, n_ctx=18_000, n_query=M, n_local=400, top_k=0, max_position=0)
+    w = base.scaled(dtype=dtype, n_ctx=18_000, n_query=M, n_local=max(400, M + 37), top_k=0, max_position=0)
     v = B.Vote(4, 30, 16)
     t = wl.generate(w, "cuda")
     p0 = B.Params.from_workload(w)
     ws0 = B.alloc_vote_workspace(p0, v)
     lists0 = B.vote_topk(p0, v, t["q"], t["k"], ws0)
     out0, sel0, n0 = B.vote_layer(p0, v, t["q"], t["k"], t["v"], ws0)
-    p, kp, vp, _ = _paged(w, t, 128, seed=22)
+    p, kp, vp, _ = _paged(w, t, ps, seed=22)
     ws = B.alloc_vote_workspace(p, v)
     lists1 = B.vote_topk(p, v, t["q"], kp, ws)
     out1, sel1, n1 = B.vote_layer(p, v, t["q"], kp, vp, ws)

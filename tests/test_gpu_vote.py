@@ -46,6 +46,14 @@ CASES = {
     "f16_g4_two_blocks": (wl.CONFIGS[2].scaled(dtype="f16", n_ctx=12_000, n_query=6, n_local=300, top_k=0), B.Vote(2, 64, 8)),
     "f16_g4_gemm": (wl.CONFIGS[4].scaled(dtype="f16", n_ctx=9_011, n_q_heads=8, n_kv_heads=2, n_query=100, n_local=160,
                                          top_k=0), B.Vote(4, 40, 16)),
+    # more than 2048 columns per KV head: 512-column workgroups (two column blocks per wave), ragged column tail,
+    # key splits, a ragged last key tile
+    "bf16_g4_gemm_wide": (wl.CONFIGS[4].scaled(n_ctx=9_011, n_q_heads=8, n_kv_heads=2, n_query=600, n_local=640, top_k=0),
+                          B.Vote(4, 127, 32)),
+    "f16_g4_gemm_wide_k2": (wl.CONFIGS[4].scaled(dtype="f16", n_ctx=7_300, n_q_heads=8, n_kv_heads=2, n_query=530, n_local=600,
+                                                 top_k=0), B.Vote(2, 40, 16)),
+    "bf16_g8_gemm_wide_k1": (wl.CONFIGS[4].scaled(n_ctx=6_000, n_q_heads=8, n_kv_heads=1, n_query=300, n_local=320, top_k=0),
+                             B.Vote(1, 64, 8)),
     "f32_g5_chunk": (wl.CONFIGS[1].scaled(n_ctx=5_000, n_q_heads=10, n_kv_heads=2, n_query=6, n_local=100, top_k=0,
                                           max_position=0), B.Vote(3, 11, 64)),
     # the shapes the matrix-core scan does not take: 16-bit storage with D = 64 (8 lanes per key row), fp32 with
