@@ -292,14 +292,25 @@ int scan_rows_per_block(int64_t n_mid, int64_t score_rows, int max_rows) {
 int scan_rows_per_block_for(int64_t n_mid, int64_t score_rows, int max_rows, int n_cu) {
   if (max_rows <= 0 || max_rows > kScanMaxRows) max_rows = kScanMaxRows;
   const int64_t total = n_mid * score_rows;
-  const int64_t rounds = (total + (int64_t)n_cu * max_rows - 1) / ((int64_t)n_cu * max_rows);
-  const int64_t wgs = rounds * n_cu;
-  const int64_t per_row = (wgs + score_rows - 1) / score_rows;      // workgroups per score row
-  int64_t rpb = (n_mid + per_row - 1) / per_row;
-  rpb = (rpb + 31) / 32 * 32;
-  if (rpb > max_rows) rpb = max_rows;
-  if (rpb < 32) rpb = 32;
-  return (int)rpb;
+  const int64_t r_min = (total + (int64_t)n_cu * max_rows - 1) / ((int64_t)n_cu * max_rows);
+  // A row count that does not divide the chip (40 KV heads of a batch of five on 256 CUs) must not spill a few
+  // workgroups into a round of their own: every score row gets floor(workgroups / rows) slices, and of the next few
+  // round counts the one with the least (rounds x slice length) wins; a workgroup's fixed start (its query rows,
+  // its first loads in flight) is priced like kStartRows rows.
+  constexpr int64_t kStartRows = 512;
+  int64_t best = 0, best_cost = 0;
+  for (int64_t rounds = r_min; rounds < r_min + 4; ++rounds) {
+    int64_t per_row = rounds * n_cu / score_rows;                      // workgroups per score row
+    if (per_row < 1) per_row = 1;
+    int64_t rpb = (n_mid + per_row - 1) / per_row;
+    rpb = (rpb + 31) / 32 * 32;
+    if (rpb > max_rows) rpb = max_rows;
+    if (rpb < 32) rpb = 32;
+    const int64_t wgs = (n_mid + rpb - 1) / rpb * score_rows;
+    const int64_t cost = (wgs + n_cu - 1) / n_cu * (rpb + kStartRows);
+    if (best == 0 || cost < best_cost) { best = rpb; best_cost = cost; }
+  }
+  return (int)best;
 }
 
 hipError_t launch_score_scan(const Plan& pl, const void* q, int n_query, const void* k_cache,

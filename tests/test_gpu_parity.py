@@ -226,6 +226,17 @@ def test_decode_step_degenerate_partitions(kw):
     P.check_layer(w, t, out, idx)
 
 
+@pytest.mark.parametrize("n_kv,route", [(40, B.ROUTE_SCORES), (56, B.ROUTE_SCORES), (40, B.ROUTE_FILTER), (24, B.ROUTE_FILTER)])
+def test_decode_step_head_counts_that_do_not_divide_the_chip(n_kv, route):
+    """Batches of 3, 5 or 7 eight-head sequences folded into the head axis: the scan's slices per head are
+    rounded down so that no workgroup spills into a round of its own, and the grid leaves some CUs idle."""
+    w = wl.CONFIGS[2].scaled(dtype="f16", n_ctx=9_000, n_q_heads=4 * n_kv, n_kv_heads=n_kv, n_local=300, top_k=150,
+                             n_needles=0)
+    t = gen(w)
+    out, idx = P.run_layer(w, t, route=route)
+    P.check_layer(w, t, out, idx)
+
+
 def test_decode_step_zero_query_takes_lowest_indices():
     w = wl.CONFIGS[1].scaled(n_ctx=40_000, n_local=128, top_k=300, n_needles=0)
     t = gen(w)
