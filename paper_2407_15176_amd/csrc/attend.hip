@@ -77,6 +77,11 @@ template <> struct Half<f16bits, 2> {
   }
 };
 
+// 2^x for x <= 0 as the bare instruction: results below the smallest normal number come out as 0, which a
+// softmax weight may (the library call wraps the instruction in a range test and a rescale, 4 instructions more,
+// and this kernel is bound by its vector instruction count once there are enough heads to fill the chip).
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
 // T: storage type of q / V (and of K when FUSED).  GT: query heads per workgroup.
 template <typename T, int D, int GT, bool FUSED>
 __global__ __launch_bounds__(256) void attend_kernel(AttendArgs a) {
@@ -158,7 +163,18 @@ __global__ __launch_bounds__(256) void attend_kernel(AttendArgs a) {
     return (FUSED && a.pt) ? (int)paged_row(a.pt, a.page_lg, tok) : tok;
   };
 
-  for (int base = r0; base < r_end; base += kGroupsPerBlock * UNR) {
+  // Rotary factors of the group's slots: slot r + 16 * UNR follows from slot r by one complex multiplication
+  // with a fixed step, and only every kReseed-th turn reads the table again (rounding does not pile up, and the
+  // low table level, 64 KB at D = 128, does not fit the first-level cache: read per slot it doubled the bytes
+  // a slot pulls out of L2).
+  constexpr int kReseed = 8;
+  float2 cs_run[UNR][E], cs_step[E];
+  if (FUSED) {
+    const int stride = kGroupsPerBlock * UNR;
+    rope_at(stride < a.S ? stride : a.S - 1, cs_step);     // a scope shorter than one turn never steps
+  }
+
+  for (int base = r0, turn = 0; base < r_end; base += kGroupsPerBlock * UNR, ++turn) {
     float klo[UNR][E], khi[UNR][E], vlo[UNR][E], vhi[UNR][E];
     bool valid[UNR];
     int rr[UNR];
@@ -199,11 +215,18 @@ __global__ __launch_bounds__(256) void attend_kernel(AttendArgs a) {
     if (FUSED) {
 #pragma unroll
       for (int u = 0; u < UNR; ++u) {
-        float2 rp[E];
-        rope_at(rr[u], rp);
+        if (turn % kReseed == 0) {
+          rope_at(rr[u], cs_run[u]);
+        } else {
+#pragma unroll
+          for (int e = 0; e < E; ++e) {
+            const float2 x = cs_run[u][e], y = cs_step[e];
+            cs_run[u][e] = make_float2(x.x * y.x - x.y * y.y, x.y * y.x + x.x * y.y);
+          }
+        }
 #pragma unroll
         for (int e = 0; e < E; ++e) {
-          const float2 cs = rp[e];
+          const float2 cs = cs_run[u][e];
           const float lo = klo[u][e], hi = khi[u][e];
           klo[u][e] = lo * cs.x - hi * cs.y;
           khi[u][e] = hi * cs.x + lo * cs.y;
@@ -223,14 +246,17 @@ __global__ __launch_bounds__(256) void attend_kernel(AttendArgs a) {
         s[u] = valid[u] ? d : kNegBig;
         mx = fmaxf(mx, s[u]);
       }
-      const float corr = exp2f(m[g] - mx);
-      m[g] = mx;
-      float lsum = l[g] * corr;
+      float lsum = l[g];
+      if (__any(mx > m[g])) {                      // a running maximum moves O(log n) times in n slots: mostly skipped
+        const float corr = fast_exp2(m[g] - mx);
+        m[g] = mx;
+        lsum *= corr;
 #pragma unroll
-      for (int e = 0; e < E; ++e) { alo[g][e] *= corr; ahi[g][e] *= corr; }
+        for (int e = 0; e < E; ++e) { alo[g][e] *= corr; ahi[g][e] *= corr; }
+      }
 #pragma unroll
       for (int u = 0; u < UNR; ++u) {
-        const float p = valid[u] ? exp2f(s[u] - mx) : 0.f;
+        const float p = valid[u] ? fast_exp2(s[u] - mx) : 0.f;
         lsum += p;
 #pragma unroll
         for (int e = 0; e < E; ++e) {
