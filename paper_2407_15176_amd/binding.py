@@ -51,6 +51,7 @@ class CParams(C.Structure):
         ("k_stride_head", C.c_int64), ("k_stride_tok", C.c_int64),
         ("v_stride_head", C.c_int64), ("v_stride_tok", C.c_int64),
         ("page_table", C.c_void_p), ("page_size", C.c_int32), ("route", C.c_int32),
+        ("ws_warm", C.c_int32),
     ]
 
 
@@ -139,6 +140,7 @@ class Params:
     page_table: "torch.Tensor | None" = None     # int32 device tensor [ceil(n_ctx / page_size)], or None
     page_size: int = 0
     route: int = 0                               # ROUTE_AUTO / ROUTE_FILTER / ROUTE_SCORES (long decode steps)
+    ws_warm: int = 0                             # decode steps: the workspace was last written by a step of the same shape
 
     def c(self) -> CParams:
         pt = None
@@ -153,7 +155,7 @@ class Params:
                        self.n_query, self.n_sink, self.n_local, self.top_k, self.rope_theta,
                        self.max_position, self.agg, self.softmax_scale,
                        self.k_stride_head, self.k_stride_tok, self.v_stride_head, self.v_stride_tok,
-                       pt, self.page_size, self.route)
+                       pt, self.page_size, self.route, self.ws_warm)
 
     @classmethod
     def from_workload(cls, w) -> "Params":

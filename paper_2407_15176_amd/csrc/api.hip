@@ -132,23 +132,27 @@ int make_plan(const reattn_params* p, Plan* out) {
   pl.m_tile = (int)mt;
 
   const size_t rows = (size_t)pl.m_tile * pl.Hkv;
+  // What a warm workspace keeps from one decode step to the next (reattn_params.ws_warm) comes first, at
+  // offsets that do not move as the context grows: the histograms (left zeroed by their last reader) and the
+  // rotary table.
   size_t off = 0;
-  pl.off_scores = off; off += up(rows * (size_t)pl.n_mid * 4);
   pl.off_hist = off;   off += up(rows * kHistBins * 4);
+  pl.off_rope = off;   off += up((size_t)(rope_rows_hi(pl.S) + kRopeLo) * (pl.D / 2) * sizeof(float2));
+  const size_t front = off;
+  pl.off_scores = off; off += up(rows * (size_t)pl.n_mid * 4);
   pl.off_pfx = off;    off += up(rows * (size_t)pl.nchunks * 4);
   pl.off_ncand = off;  off += up(rows * (size_t)pl.nchunks * 4);
   pl.off_cand = off;   off += up(rows * (size_t)pl.nchunks * kChunk * 4);
   pl.off_bitmap = off; off += up(rows * (size_t)pl.nwords * 4);
   pl.off_cnt = off;    off += up(rows * (size_t)pl.nchunks * 4);
   if (filter_plan(&pl, p->route)) {                              // the same bytes, laid out for the filter path
-    size_t f = 0;
+    size_t f = front;
     pl.off_fsamp = f;  f += up((size_t)pl.Hkv * (size_t)pl.f_samp_stride * 4);
     pl.off_fcnt = f;   f += up((size_t)pl.Hkv * (size_t)pl.f_nb * 4 + 4 + (size_t)pl.Hkv * 4);   // + the redo list
     pl.off_fcand = f;  f += up((size_t)pl.Hkv * (size_t)pl.f_nb * (size_t)pl.f_rpb * 8);
     if (f > off) off = f;
   }
   pl.off_idx = off;    off += up((size_t)pl.M * pl.Hkv * (size_t)pl.k_eff * 4);
-  pl.off_rope = off;   off += up((size_t)(rope_rows_hi(pl.S) + kRopeLo) * (pl.D / 2) * sizeof(float2));
   pl.off_rope16 = off; off += up(attend_prefill_applies(pl) ? attend_prefill_table_bytes(pl) : 0);
   pl.off_part = off;   off += up((size_t)pl.M * pl.Hq * (size_t)pl.nsplit * (pl.D + 2) * 4);
   pl.off_qsplit = off; off += up(pl.M > 1 ? score_gemm_qsplit_bytes(pl) : 0);
@@ -459,7 +463,8 @@ int reattn_attend(const reattn_params* p, const void* q, const float* k_sel, con
 int reattn_decode_step(const reattn_params* p, const void* q, const void* k_cache,
                        const void* v_cache, int32_t* idx_out, float* out, void* ws,
                        size_t ws_bytes, void* stream) {
-  return run_layer(p, true, q, k_cache, v_cache, idx_out, out, ws, ws_bytes, stream);
+  const bool warm = p && p->ws_warm != 0;
+  return run_layer(p, true, q, k_cache, v_cache, idx_out, out, ws, ws_bytes, stream, nullptr, warm, nullptr, warm);
 }
 
 // ---- the decode step for callers that cannot allocate ----------------------------------------
@@ -507,8 +512,11 @@ int reattn_decode_step_static(const reattn_params* p, const void* q, const void*
   void* ws = static_scratch(&e);
   if (!ws) return REATTN_ERR_HIP;
   // every kernel of the step starts from what the step itself wrote or cleared (the first launch zeroes
-  // the histograms), so what the previous call left in the array does not matter
-  return run_layer(p, true, q, k_cache, v_cache, idx_out, out, ws, (size_t)REATTN_STATIC_SCRATCH_BYTES, stream);
+  // the histograms), so what the previous call left in the array does not matter -- unless the caller
+  // vouches for it (ws_warm: the previous step through this entry point on this GPU had the same shape)
+  const bool warm = p->ws_warm != 0;
+  return run_layer(p, true, q, k_cache, v_cache, idx_out, out, ws, (size_t)REATTN_STATIC_SCRATCH_BYTES, stream,
+                   nullptr, warm, nullptr, warm);
 }
 
 int reattn_prefill_chunk(const reattn_params* p, const void* q, const void* k_cache,
@@ -927,7 +935,8 @@ static int layer_timed(const reattn_params* p, bool decode_only, const void* q, 
   for (; made <= REATTN_N_STAGES; ++made)
     if (hipEventCreate(&ev[made]) != hipSuccess) break;
   int rc = made == REATTN_N_STAGES + 1 ? REATTN_OK : REATTN_ERR_HIP;
-  if (!rc) rc = run_layer(p, decode_only, q, k_cache, v_cache, idx_out, out, ws, ws_bytes, stream, ev);
+  const bool warm = decode_only && p && p->ws_warm != 0;
+  if (!rc) rc = run_layer(p, decode_only, q, k_cache, v_cache, idx_out, out, ws, ws_bytes, stream, ev, warm, nullptr, warm);
   if (!rc) {
     if (hipEventSynchronize(ev[REATTN_N_STAGES]) != hipSuccess) rc = REATTN_ERR_HIP;
     for (int i = 0; i < REATTN_N_STAGES && !rc; ++i)

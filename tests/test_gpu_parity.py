@@ -1,6 +1,8 @@
 """GPU parity: every C-ABI entry point of libreattn against the fp64 CPU oracle on the
 same seeded stored bytes.  Sizes span several tiles plus a ragged tail; the full-size
 configurations are covered in test_gpu_full_size.py."""
+from dataclasses import replace
+
 import numpy as np
 import pytest
 import torch
@@ -235,6 +237,28 @@ def test_decode_step_head_counts_that_do_not_divide_the_chip(n_kv, route):
     t = gen(w)
     out, idx = P.run_layer(w, t, route=route)
     P.check_layer(w, t, out, idx)
+
+
+@pytest.mark.parametrize("name,route", [("bf16_d128_g4", B.ROUTE_SCORES), ("f32_d64_g4", B.ROUTE_SCORES),
+                                        ("f16_d128_g4", B.ROUTE_SCORES), ("bf16_d128_g4", B.ROUTE_FILTER)])
+def test_decode_step_on_a_warm_workspace_equals_the_cold_step(name, route):
+    """reattn_params.ws_warm: steps of one shape over a growing (then a shorter) context on one workspace, every
+    one after the first without the clearing / table launch, against the same steps on fresh workspaces and
+    against the oracle."""
+    shapes = [SMALL[name], SMALL[name].scaled(n_ctx=SMALL[name].n_ctx + 1), SMALL[name].scaled(n_ctx=SMALL[name].n_ctx + 4_321),
+              SMALL[name].scaled(n_ctx=SMALL[name].n_ctx - 1_234)]
+    biggest = max(shapes, key=lambda w: w.n_ctx)
+    ws_big = B.alloc_workspace(replace(B.Params.from_workload(biggest), route=route))
+    ws_big.fill_(255)                                        # the cold step owes nothing to what the memory held
+    for i, w in enumerate(shapes):
+        t = gen(w)
+        cold = replace(B.Params.from_workload(w), route=route)
+        ref_out, ref_idx = B.decode_step(cold, t["q"], t["k"], t["v"], B.alloc_workspace(cold))
+        out, idx = B.decode_step(replace(cold, ws_warm=int(i > 0)), t["q"], t["k"], t["v"], ws_big)
+        torch.cuda.synchronize()
+        assert torch.equal(idx, ref_idx), (i, w.n_ctx)
+        assert torch.equal(out, ref_out), (i, w.n_ctx)
+        P.check_layer(w, t, out, idx)
 
 
 def test_decode_step_zero_query_takes_lowest_indices():
