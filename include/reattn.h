@@ -120,6 +120,10 @@ typedef enum { REATTN_ROUTE_AUTO = 0, REATTN_ROUTE_FILTER = 1, REATTN_ROUTE_SCOR
 /* Library version (major*10000 + minor*100 + patch) and a static message for a status. */
 int reattn_version(void);
 const char* reattn_status_string(int status);
+/* sizeof(reattn_params) / sizeof(reattn_vote) as this library was compiled: a binding that declares the
+ * structs by hand (ctypes, an FFI) compares them with its own before the first call. */
+size_t reattn_params_bytes(void);
+size_t reattn_vote_bytes(void);
 
 /* Host-only checks of `p` (no GPU needed).  REATTN_OK or the first error found. */
 int reattn_validate(const reattn_params* p);

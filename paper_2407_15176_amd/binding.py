@@ -79,6 +79,12 @@ def lib() -> C.CDLL:
         L = C.CDLL(LIB_PATH)
         P, PP = C.c_void_p, C.POINTER(CParams)
         L.reattn_version.restype = C.c_int
+        L.reattn_params_bytes.restype = C.c_size_t
+        L.reattn_vote_bytes.restype = C.c_size_t
+        if L.reattn_params_bytes() != C.sizeof(CParams) or L.reattn_vote_bytes() != C.sizeof(CVote):
+            raise RuntimeError(
+                f"{LIB_PATH}: reattn_params / reattn_vote are {L.reattn_params_bytes()} / {L.reattn_vote_bytes()} bytes "
+                f"in the library, {C.sizeof(CParams)} / {C.sizeof(CVote)} in this binding; rebuild the library")
         L.reattn_status_string.argtypes = [C.c_int]
         L.reattn_status_string.restype = C.c_char_p
         L.reattn_validate.argtypes = [PP]

@@ -344,6 +344,8 @@ int run_layer(const reattn_params* p, bool decode_only, const void* q, const voi
 extern "C" {
 
 int reattn_version(void) { return 100; }
+size_t reattn_params_bytes(void) { return sizeof(reattn_params); }
+size_t reattn_vote_bytes(void) { return sizeof(reattn_vote); }
 
 const char* reattn_status_string(int s) {
   switch (s) {

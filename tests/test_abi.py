@@ -246,3 +246,12 @@ def test_both_aggregations_validate():
         assert B.validate(q) == B.OK
         assert B.workspace_bytes(q) > 0
     assert B.workspace_bytes(replace(p, agg=B.AGG_MAX)) == B.workspace_bytes(p)      # a decode step: the same plan but the route
+
+
+def test_struct_sizes_match_the_binding():
+    """The ctypes structs are declared by hand: the library reports its own sizeof for both."""
+    import ctypes as C
+    from paper_2407_15176_amd import binding as B
+    L = B.lib()                                              # raises on a mismatch
+    assert L.reattn_params_bytes() == C.sizeof(B.CParams)
+    assert L.reattn_vote_bytes() == C.sizeof(B.CVote)
