@@ -34,7 +34,7 @@ EXPORTS = [
     "reattn_vote_layer_timed", "reattn_cache_append", "reattn_prefill_sequence_chunks",
     "reattn_prefill_sequence_workspace_bytes", "reattn_prefill_sequence", "reattn_decode_token",
     "reattn_static_scratch_bytes", "reattn_decode_step_static", "reattn_redo_list_offset",
-    "reattn_prefill_sequence_chunk_bounds",
+    "reattn_prefill_sequence_chunk_bounds", "reattn_params_bytes", "reattn_vote_bytes",
 ]
 PREFILL_STAGES = ("sample_threshold", "score_gemm_filter", "candidate_topk", "attend")
 STAGES = ("prep", "scan", "topk", "attend")
