@@ -461,6 +461,15 @@ def batched_decode_leg(steps: int) -> dict:
             torch.cuda.synchronize()
             ms = (time.perf_counter() - t0) * 1e3 / steps
             row[name] = {"ms_per_layer": round(ms, 4), "layer_steps_per_s": round(batch / (ms * 1e-3), 1)}
+            if not vote:                                    # the same steps on a workspace declared warm (reattn_params.ws_warm)
+                from dataclasses import replace
+                pw = replace(p, ws_warm=1)
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                for i in range(steps):
+                    B.decode_step(pw, q, ks[i % n_rot], vs[i % n_rot], ws, out=out, want_idx=False)
+                torch.cuda.synchronize()
+                row[name]["ms_per_layer_warm_workspace"] = round((time.perf_counter() - t0) * 1e3 / steps, 4)
         rows.append(row)
         del ks, vs
         torch.cuda.empty_cache()
