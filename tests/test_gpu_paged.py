@@ -341,6 +341,22 @@ def test_paged_decode_step_against_oracle(name, agg):
     P.check_layer(w, t, out, idx, agg=agg)
 
 
+@pytest.mark.parametrize("name", list(CASES)[:2])
+def test_paged_decode_step_on_a_warm_workspace(name):
+    """reattn_params.ws_warm over a paged cache: the second step on the same workspace skips the clearing / table
+    launch and returns what the cold step returned."""
+    from tests import parity as P
+    w, ps = CASES[name]
+    t = wl.generate(w, "cuda")
+    p, kp, vp, _ = _paged(w, t, ps, seed=34)
+    ws = B.alloc_workspace(p)
+    out0, idx0 = B.decode_step(p, t["q"], kp, vp, ws, want_idx=True)
+    out1, idx1 = B.decode_step(replace(p, ws_warm=1), t["q"], kp, vp, ws, want_idx=True)
+    torch.cuda.synchronize()
+    assert torch.equal(idx0, idx1) and torch.equal(out0, out1)
+    P.check_layer(w, t, out1, idx1)
+
+
 @pytest.mark.parametrize("name", ["bf16_mfma", "f32_scan"])
 def test_paged_prefill_chunk_against_oracle(name):
     from tests import parity as P
