@@ -104,15 +104,16 @@ typedef struct reattn_params {
    * and testing aid: shapes the filter does not take (short middles, top_k so large that the kept pairs
    * would outgrow the pick, REATTN_AGG_MAX) use the scores whatever is asked for. */
   int32_t route;
-  /* A decode step (reattn_decode_step, _static, _timed) normally starts with a launch that zeroes its
-   * histograms and builds its rotary table.  Nonzero ws_warm is the caller's promise that this launch is not
-   * needed: the last call that wrote `ws` was a decode step of this library with the same head counts,
-   * head_dim, dtype, n_sink, n_local, top_k, rope_theta and paging, over a context of at least
-   * n_sink + top_k + n_local tokens (so that the scope S, and with it the table, is the same; n_ctx itself may
-   * have grown), it was enqueued on the same stream or has completed, and nothing else has written `ws` since.
-   * Every step leaves the histograms zeroed behind it and both sit at the front of the workspace at offsets
-   * that do not depend on n_ctx.  A promise that does not hold gives wrong selections, not an error: the
-   * library cannot see it.  Other calls ignore the field. */
+  /* A decode step (reattn_decode_step, _static, _timed; reattn_vote_layer and its _timed form with n_query == 1)
+   * normally starts with a launch that zeroes its histograms and builds its rotary table (the vote layer's: the
+   * table only).  Nonzero ws_warm is the caller's promise that this launch is not needed: the last call that
+   * wrote `ws` was the same kind of decode step with the same head counts, head_dim, dtype, n_sink, n_local,
+   * top_k (vote selection: the same reattn_vote), rope_theta and paging, over a context of at least
+   * n_sink + top_k + n_local tokens (vote: n_sink + n_centres * span + n_local), so that the scope S, and with
+   * it the table, is the same (n_ctx itself may have grown); that call was enqueued on the same stream or has
+   * completed; and nothing else has written `ws` since.  Every step leaves the histograms zeroed behind it,
+   * and both sit at the front of the workspace at offsets that do not depend on n_ctx.  A promise that does not
+   * hold gives wrong results, not an error: the library cannot see it.  Other calls ignore the field. */
   int32_t ws_warm;
 } reattn_params;
 typedef enum { REATTN_ROUTE_AUTO = 0, REATTN_ROUTE_FILTER = 1, REATTN_ROUTE_SCORES = 2 } reattn_route;

@@ -705,7 +705,9 @@ static int vote_layer_impl(const reattn_params* p, const reattn_vote* v, const v
 extern "C" int reattn_vote_layer(const reattn_params* p, const reattn_vote* v, const void* q,
                                  const void* k_cache, const void* v_cache, int32_t* sel_out,
                                  int32_t* n_sel_out, float* out, void* ws, size_t ws_bytes, void* stream) {
-  return vote_layer_impl(p, v, q, k_cache, v_cache, sel_out, n_sel_out, out, ws, ws_bytes, stream, nullptr);
+  // a decode step on a warm workspace: the rotary table (first in the vote layout too) is already there
+  const bool warm = p && p->ws_warm != 0 && p->n_query == 1;
+  return vote_layer_impl(p, v, q, k_cache, v_cache, sel_out, n_sel_out, out, ws, ws_bytes, stream, nullptr, warm);
 }
 
 extern "C" int reattn_vote_layer_timed(const reattn_params* p, const reattn_vote* v, const void* q,
@@ -719,7 +721,8 @@ extern "C" int reattn_vote_layer_timed(const reattn_params* p, const reattn_vote
   for (; made <= kStages; ++made)
     if (hipEventCreate(&ev[made]) != hipSuccess) break;
   int rc = made == kStages + 1 ? REATTN_OK : REATTN_ERR_HIP;
-  if (!rc) rc = vote_layer_impl(p, v, q, k_cache, v_cache, sel_out, n_sel_out, out, ws, ws_bytes, stream, ev);
+  const bool warm = p && p->ws_warm != 0 && p->n_query == 1;
+  if (!rc) rc = vote_layer_impl(p, v, q, k_cache, v_cache, sel_out, n_sel_out, out, ws, ws_bytes, stream, ev, warm);
   if (!rc) {
     if (hipEventSynchronize(ev[kStages]) != hipSuccess) rc = REATTN_ERR_HIP;
     for (int i = 0; i < kStages && !rc; ++i)

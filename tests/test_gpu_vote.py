@@ -110,6 +110,28 @@ def test_vote_layer_matches_oracle(name):
         assert set(t["needles"].tolist()[: v.vote_k]) <= got
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_vote_layer_decode_on_a_warm_workspace(dtype):
+    """reattn_params.ws_warm for the vote layer's decode step: steps over a growing context on one workspace, all
+    but the first without the table launch, equal the same steps on fresh workspaces bit for bit."""
+    from dataclasses import replace
+    base = (wl.CONFIGS[2].scaled(n_ctx=20_011, n_local=300, top_k=0) if dtype == "bf16"
+            else wl.CONFIGS[1].scaled(n_ctx=9_973, n_local=200, top_k=0))
+    v = B.Vote(4, 20, 16)
+    ws = B.alloc_vote_workspace(B.Params.from_workload(base.scaled(n_ctx=base.n_ctx + 2_000)), v)
+    ws.fill_(255)
+    for i, extra in enumerate((0, 1, 2_000)):
+        w = base.scaled(n_ctx=base.n_ctx + extra)
+        t = wl.generate(w, "cuda")
+        p = B.Params.from_workload(w)
+        ref_out, ref_sel, ref_n = B.vote_layer(p, v, t["q"], t["k"], t["v"], B.alloc_vote_workspace(p, v))
+        out, sel, n_sel = B.vote_layer(replace(p, ws_warm=int(i > 0)), v, t["q"], t["k"], t["v"], ws)
+        torch.cuda.synchronize()
+        n = int(ref_n.item())
+        assert int(n_sel.item()) == n and torch.equal(sel[:n], ref_sel[:n]), i
+        assert torch.equal(out, ref_out), i
+
+
 def test_vote_merge_on_given_lists_heavy_ties():
     """Integer pipeline alone: few distinct tokens, so vote ties and overlapping spans abound."""
     w = wl.CONFIGS[2].scaled(n_ctx=5_000, n_local=100, top_k=0, n_query=7)
