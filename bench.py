@@ -139,7 +139,7 @@ def main() -> int:
         "data": "synthetic",
         "config": leg["config"],
         "kv_scan_GBps": leg["kv_scan_GBps"],
-        "ms_per_step_warm_workspace": leg["ms_per_step_warm_workspace"],
+        "warm_workspace": leg["warm_workspace"],
         "stages_ms": leg["stages_ms"],
         "selection_route": leg["selection_route"],
         "step_floor": leg["step_floor"],
@@ -223,6 +223,10 @@ def decode_leg(w, t: dict, steps: int, warmup: int) -> dict:
     def step(i):
         B.decode_step(p, t["q"], ks[i % n_rot], vs[i % n_rot], ws, idx_out=idx, out=out)
 
+    # An idle MI355X needs ~10 ms of load to reach its clocks (the first twenty steps after a pause run 4 % slower,
+    # measured, whatever kernel runs): plain reads of the same keys bring it there before the warm-up steps, so that
+    # a short --warmup still times the steady state.
+    B.probe_read_bandwidth(kbig, iters=30 if n_rot == 1 else 5)
     for i in range(warmup):
         step(i)
     torch.cuda.synchronize()
@@ -233,14 +237,23 @@ def decode_leg(w, t: dict, steps: int, warmup: int) -> dict:
     ms_per_step = (time.perf_counter() - t0) * 1e3 / steps
     # the same steps with reattn_params.ws_warm: a serving loop that keeps one workspace per shape promises that
     # the previous step left it behind, and the clearing / table launch at the head of a step is not enqueued
+    # (measured in alternation with the plain steps, best of two loops each: a loop that runs later in the process
+    # is a few microseconds faster whatever it runs, and the pair below is what may be compared)
     from dataclasses import replace
     pw = replace(p, ws_warm=1)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(steps):
-        B.decode_step(pw, t["q"], ks[i % n_rot], vs[i % n_rot], ws, idx_out=idx, out=out)
-    torch.cuda.synchronize()
-    ms_warm = (time.perf_counter() - t0) * 1e3 / steps
+
+    def loop(pp):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            B.decode_step(pp, t["q"], ks[i % n_rot], vs[i % n_rot], ws, idx_out=idx, out=out)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / steps
+
+    ms_warm, ms_cold_again = float("inf"), float("inf")
+    for _ in range(2):
+        ms_warm = min(ms_warm, loop(pw))
+        ms_cold_again = min(ms_cold_again, loop(p))
     stage_sum = {s: 0.0 for s in B.STAGES}
     for i in range(steps):
         _, _, ms = B.decode_step_timed(p, t["q"], ks[i % n_rot], vs[i % n_rot], ws, idx_out=idx, out=out)
@@ -257,7 +270,8 @@ def decode_leg(w, t: dict, steps: int, warmup: int) -> dict:
     floor_bytes = w.scan_bytes + 3 * w.n_kv_heads * w.n_mid * 4 + gather
     floor_ms = floor_bytes / (HBM_PEAK_GBPS * 1e9) * 1e3
     return {
-        "workload": w.name, "ms_per_step": round(ms_per_step, 5), "ms_per_step_warm_workspace": round(ms_warm, 5),
+        "workload": w.name, "ms_per_step": round(ms_per_step, 5),
+        "warm_workspace": {"ms_per_step": round(ms_warm, 5), "ms_per_step_plain_same_moment": round(ms_cold_again, 5)},
         "steps": steps,
         "config": {
             "workload": w.name, "n_ctx": w.n_ctx, "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads,
@@ -461,15 +475,23 @@ def batched_decode_leg(steps: int) -> dict:
             torch.cuda.synchronize()
             ms = (time.perf_counter() - t0) * 1e3 / steps
             row[name] = {"ms_per_layer": round(ms, 4), "layer_steps_per_s": round(batch / (ms * 1e-3), 1)}
-            if not vote:                                    # the same steps on a workspace declared warm (reattn_params.ws_warm)
-                from dataclasses import replace
+            if not vote:                                    # the same steps on a workspace declared warm (reattn_params.ws_warm),
+                from dataclasses import replace             # in alternation with the plain ones, best of two loops each
                 pw = replace(p, ws_warm=1)
-                torch.cuda.synchronize()
-                t0 = time.perf_counter()
-                for i in range(steps):
-                    B.decode_step(pw, q, ks[i % n_rot], vs[i % n_rot], ws, out=out, want_idx=False)
-                torch.cuda.synchronize()
-                row[name]["ms_per_layer_warm_workspace"] = round((time.perf_counter() - t0) * 1e3 / steps, 4)
+
+                def loop(pp):
+                    torch.cuda.synchronize()
+                    t0 = time.perf_counter()
+                    for i in range(steps):
+                        B.decode_step(pp, q, ks[i % n_rot], vs[i % n_rot], ws, out=out, want_idx=False)
+                    torch.cuda.synchronize()
+                    return (time.perf_counter() - t0) * 1e3 / steps
+
+                warm, plain = float("inf"), float("inf")
+                for _ in range(2):
+                    warm = min(warm, loop(pw))
+                    plain = min(plain, loop(p))
+                row[name]["warm_workspace"] = {"ms_per_layer": round(warm, 4), "ms_per_layer_plain_same_moment": round(plain, 4)}
         rows.append(row)
         del ks, vs
         torch.cuda.empty_cache()
@@ -711,12 +733,19 @@ def vote_leg(t: dict, cfg: int, steps: int, warmup: int) -> dict:
     ms_step = (time.perf_counter() - t0) * 1e3 / steps
     from dataclasses import replace
     pw = replace(p, ws_warm=1)                               # the same steps without the table launch
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(steps):
-        B.vote_layer(pw, v, t["q"], t["k"], t["v"], ws, sel=sel, n_sel=n_sel, out=out)
-    torch.cuda.synchronize()
-    ms_warm = (time.perf_counter() - t0) * 1e3 / steps
+
+    def loop(pp):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            B.vote_layer(pp, v, t["q"], t["k"], t["v"], ws, sel=sel, n_sel=n_sel, out=out)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / steps
+
+    ms_warm, ms_cold_again = float("inf"), float("inf")     # in alternation, best of two loops each
+    for _ in range(2):
+        ms_warm = min(ms_warm, loop(pw))
+        ms_cold_again = min(ms_cold_again, loop(p))
     acc = {s: 0.0 for s in B.VOTE_STAGES}
     for _ in range(steps):
         *_, ms = B.vote_layer_timed(p, v, t["q"], t["k"], t["v"], ws, sel=sel, n_sel=n_sel, out=out)
@@ -726,7 +755,8 @@ def vote_leg(t: dict, cfg: int, steps: int, warmup: int) -> dict:
     return {
         "workload": w.name, "vote_k": v.vote_k, "n_centres": v.n_centres, "span": v.span,
         "n_selected": int(n_sel.item()), "ms_per_step": round(ms_step, 5),
-        "ms_per_step_warm_workspace": round(ms_warm, 5), "steps": steps,
+        "warm_workspace": {"ms_per_step": round(ms_warm, 5), "ms_per_step_plain_same_moment": round(ms_cold_again, 5)},
+        "steps": steps,
         "stages_ms": {s: round(x, 5) for s, x in acc.items()},
         "roofline": {
             "kernel": "head_topk_mfma_kernel (+ list merge)", "bound": "hbm",
