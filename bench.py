@@ -199,6 +199,15 @@ def main() -> int:
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X published dense bf16 matrix rate
 
 
+def wake_device(buf) -> None:
+    """About 10 ms of plain reads of `buf` ahead of a leg's warm-up steps.  An idle MI355X needs that long under load
+    to reach its clocks (the first twenty decode steps after a pause run 4 % slower, measured, whatever kernel
+    runs), and a short warm-up would time the ramp instead of the step."""
+    from paper_2407_15176_amd import binding as B
+    n = buf.numel() * buf.element_size()
+    B.probe_read_bandwidth(buf, iters=max(3, min(2000, int(10e-3 * 6.5e12 / max(n, 1)))))
+
+
 def decode_leg(w, t: dict, steps: int, warmup: int) -> dict:
     """One decode configuration: wall-clock ms per step over `steps` steps (inputs resident in HBM, sync on
     both sides), the stage times from HIP events on the launch stream (a second set of instrumented steps),
@@ -223,10 +232,7 @@ def decode_leg(w, t: dict, steps: int, warmup: int) -> dict:
     def step(i):
         B.decode_step(p, t["q"], ks[i % n_rot], vs[i % n_rot], ws, idx_out=idx, out=out)
 
-    # An idle MI355X needs ~10 ms of load to reach its clocks (the first twenty steps after a pause run 4 % slower,
-    # measured, whatever kernel runs): plain reads of the same keys bring it there before the warm-up steps, so that
-    # a short --warmup still times the steady state.
-    B.probe_read_bandwidth(kbig, iters=30 if n_rot == 1 else 5)
+    wake_device(kbig)
     for i in range(warmup):
         step(i)
     torch.cuda.synchronize()
@@ -466,6 +472,7 @@ def batched_decode_leg(steps: int) -> dict:
             else:
                 def step(i):
                     B.decode_step(p, q, ks[i % n_rot], vs[i % n_rot], ws, out=out, want_idx=False)
+            wake_device(ks[0])
             for i in range(2):
                 step(i)
             torch.cuda.synchronize()
@@ -522,6 +529,7 @@ def paged_leg(t: dict, cfg: int, steps: int, warmup: int, page_size: int = 256) 
     ws = B.alloc_workspace(p)
     out = torch.empty(1, w.n_q_heads, D, dtype=torch.float32, device="cuda")
     idx = torch.empty(1, Hkv, w.k_eff, dtype=torch.int32, device="cuda")
+    wake_device(k_pool)
     for _ in range(warmup):
         B.decode_step(p, t["q"], k_pool, v_pool, ws, idx_out=idx, out=out)
     torch.cuda.synchronize()
@@ -543,6 +551,7 @@ def paged_leg(t: dict, cfg: int, steps: int, warmup: int, page_size: int = 256) 
     wsv = B.alloc_vote_workspace(pv, vote)
     sel = torch.empty(B.vote_cap(pv, vote), dtype=torch.int32, device="cuda")
     n_sel = torch.zeros(1, dtype=torch.int32, device="cuda")
+    wake_device(k_pool)
     for _ in range(warmup):
         B.vote_layer(pv, vote, t["q"], k_pool, v_pool, wsv, sel=sel, n_sel=n_sel, out=out)
     torch.cuda.synchronize()
@@ -630,6 +639,7 @@ def unfused_leg(t: dict, cfg: int, steps: int) -> dict:
         "attend": lambda: B.attend(p, t["q"], k_sel, v_sel, ws, out=out),
     }
     ms = {}
+    wake_device(t["k"])
     for name, fn in calls.items():
         fn(); fn()
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -676,6 +686,7 @@ def decode_token_leg(steps: int, n_layers: int = 32) -> dict:
             p = B.Params.from_workload(w.scaled(top_k=0, max_position=0) if vote else w)
             p = replace(p, k_stride_head=cap * 128, k_stride_tok=128, v_stride_head=cap * 128, v_stride_tok=128)
             ws = B.alloc_vote_workspace(p, vote) if vote else B.alloc_workspace(p)
+            wake_device(kcs[0])
             for _ in range(2):
                 B.decode_token(p, qs, kn, vn, kcs, vcs, ws, outs=outs, vote=vote)
             torch.cuda.synchronize()
@@ -723,6 +734,7 @@ def vote_leg(t: dict, cfg: int, steps: int, warmup: int) -> dict:
     def step():
         B.vote_layer(p, v, t["q"], t["k"], t["v"], ws, sel=sel, n_sel=n_sel, out=out)
 
+    wake_device(t["k"])
     for _ in range(warmup):
         step()
     torch.cuda.synchronize()
