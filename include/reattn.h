@@ -182,7 +182,9 @@ int reattn_decode_step(const reattn_params* p, const void* q, const void* k_cach
  * nothing and frees nothing.  Steps whose reattn_workspace_bytes() exceeds the array (a bf16 cache of
  * 8 KV heads past ~500K tokens) return REATTN_ERR_STATIC_LIMIT before anything is launched.  All calls
  * on one GPU share that GPU's array: calls that overlap on one GPU (two streams, two threads) race; order
- * them on one stream.  Nothing is kept between calls. */
+ * them on one stream.  Nothing the next call relies on is kept between calls, unless the caller sets
+ * reattn_params.ws_warm: the array is then the workspace the promise is about (the previous step through this
+ * entry point on this GPU). */
 #define REATTN_STATIC_SCRATCH_BYTES (32u << 20)
 size_t reattn_static_scratch_bytes(void);
 int reattn_decode_step_static(const reattn_params* p, const void* q, const void* k_cache,
